@@ -1,0 +1,232 @@
+/*
+ * ivfpq_hot — IVF-PQ similarity search over the GPU-resident (hot-cluster)
+ * partition of an inverted-file index on AMD MI355X (gfx950), with probes of
+ * non-resident clusters scanned on the host CPU and merged.
+ *
+ * The calls follow the tiered search structure of the paper: frequently hit
+ * clusters are placed on the GPU and the rest stay on the CPU (Section 3.2,
+ * Takeaway 2); a query is coarse-quantized, each probed cluster is looked up
+ * in a mapping table and routed to the GPU or the CPU scan (Section 4.3.1
+ * "Router"), partial results are merged and re-ranked (Section 4.3.2); the
+ * router's counters and the refresh of the GPU-resident set follow Section
+ * 4.3.3 "Adaptive Runtime Index Update".  Search itself is the three-stage
+ * IVF-PQ procedure of Section 2.2: coarse quantization, per-query lookup
+ * table, table scan with top-k.
+ *
+ * Conventions
+ *  - Plain C ABI.  Every pointer is documented as HOST or DEVICE memory.
+ *  - A negative return value is an error; ivf_last_error() then holds a
+ *    message (thread-local).  On error no output buffer is partially written.
+ *  - The library never frees or reallocates caller memory.  Arrays named in
+ *    ivf_index_desc_t are BORROWED for the lifetime of the index: they are the
+ *    source of the CPU scan and of host-to-device cluster copies.
+ *  - The library performs no device allocation of its own: all device state
+ *    lives in the caller-supplied arena.
+ *  - "L2" is squared Euclidean distance (smaller is better); "IP" is the inner
+ *    product (larger is better).  PQ codes encode the raw vector (no residual),
+ *    8 bits per sub-quantizer.
+ *  - Results are ordered best first; ties on distance go to the smaller id.
+ *    Missing results are id = -1, dist = +INF (L2) / -INF (IP).
+ *  - Threading: one searcher thread plus one migrator thread per index.
+ *  - Streams are raw hipStream_t values passed as void* (NULL = the index's
+ *    own stream).  All streams must have default priority.
+ */
+#ifndef IVFPQ_HOT_H
+#define IVFPQ_HOT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct ivf_index ivf_index_t; /* opaque */
+
+enum { IVF_METRIC_L2 = 0, IVF_METRIC_IP = 1 };
+
+enum {
+  IVF_OK = 0,
+  IVF_EINVAL = -1,  /* bad argument / unsupported shape */
+  IVF_ENOMEM = -2,  /* arena (or its cluster region) too small */
+  IVF_EDEVICE = -3, /* HIP error, or a device call on an index without arena */
+  IVF_EBUSY = -4,   /* a migration is already in flight */
+  IVF_ESTATE = -5   /* call not valid in the current state */
+};
+
+/*
+ * Index description.  All pointers are HOST memory, borrowed until
+ * ivf_index_destroy().  `codes` should be pinned for asynchronous copies.
+ *
+ * Supported shapes: nbits == 8; M a multiple of 16 and <= 128; d a multiple
+ * of M; nlist >= 1.  max_nq / max_nprobe / max_k size the per-batch workspace
+ * (max_k <= 128, max_nprobe <= 2048).
+ */
+typedef struct {
+  int32_t d;      /* vector dimension */
+  int32_t nlist;  /* number of IVF clusters */
+  int32_t M;      /* PQ sub-quantizers */
+  int32_t nbits;  /* bits per code: must be 8 */
+  int32_t metric; /* IVF_METRIC_L2 or IVF_METRIC_IP (also the coarse metric) */
+  int32_t max_nq;
+  int32_t max_nprobe;
+  int32_t max_k;
+  const float *centroids;      /* [nlist][d] */
+  const float *codebooks;      /* [M][256][d/M] */
+  const int64_t *list_offsets; /* [nlist+1] prefix sums, in vectors */
+  const uint8_t *codes;        /* [N][M], cluster after cluster */
+  const int64_t *ids;          /* [N] caller ids, same order as codes */
+} ivf_index_desc_t;
+
+/*
+ * Bytes of device arena needed for `desc` with room for `resident_vectors`
+ * vectors in GPU-resident clusters (each cluster is padded to a multiple of
+ * 64 vectors; pass N + 64*nlist for a fully resident index) and
+ * `staging_bytes` of copy staging (0 = default 64 MiB).  Returns 0 if desc is
+ * invalid.  No device call is made.
+ */
+size_t ivf_index_arena_bytes(const ivf_index_desc_t *desc, int64_t resident_vectors,
+                             size_t staging_bytes);
+
+/*
+ * Create an index.  dev_arena: DEVICE memory owned by the caller, 256-byte
+ * aligned, of arena_bytes bytes, valid until destroy; the library places
+ * centroids, codebooks, mapping tables, counters, batch workspace and the
+ * cluster region inside it.  No cluster is resident after creation.
+ *
+ * dev_arena == NULL creates a host-only index: every cluster is non-resident
+ * and only ivf_search_batch_probes(), ivf_hit_stats() and destroy are valid
+ * (anything that needs the device returns IVF_EDEVICE).
+ */
+int ivf_index_create(const ivf_index_desc_t *desc, void *dev_arena, size_t arena_bytes,
+                     size_t staging_bytes, ivf_index_t **out);
+
+void ivf_index_destroy(ivf_index_t *index);
+
+/*
+ * Make exactly the listed clusters GPU-resident (Section 4.2.3: the hot
+ * clusters chosen from the access profile are placed on the GPU; the mapping
+ * table records cluster id -> resident location).  Re-packs the cluster region
+ * from scratch, i.e. a full refresh.  cluster_ids: HOST, n entries, distinct,
+ * each in [0, nlist).  Copies run on `stream` (NULL = index stream); the call
+ * returns after the copies have completed and the mapping table is published.
+ * IVF_ENOMEM if the cluster region cannot hold them (nothing changes).
+ * Must not run concurrently with a search or a migration.
+ */
+int ivf_index_load_partition(ivf_index_t *index, const int32_t *cluster_ids, int32_t n,
+                             void *stream);
+
+/*
+ * Search a batch (Section 2.2 stages 1-3, routed per Section 4.3.1, merged per
+ * Section 4.3.2).  queries: HOST fp32 [nq][d].  out_ids: HOST int64 [nq][k];
+ * out_dists: HOST fp32 [nq][k].  nprobe > nlist is clamped.  nq == 0 is a
+ * no-op.  Requires 1 <= nq <= max_nq, 1 <= nprobe <= max_nprobe,
+ * 1 <= k <= max_k.  Returns after the results are written.
+ */
+int ivf_search_batch(ivf_index_t *index, const float *queries, int64_t nq, int32_t nprobe,
+                     int32_t k, int64_t *out_ids, float *out_dists);
+
+/*
+ * Same search with DEVICE buffers: queries, out_ids, out_dists are device
+ * pointers, work is enqueued on `stream`.  When every probed cluster can be
+ * served from the GPU (the index is fully resident) the call is asynchronous:
+ * it returns after enqueueing and the outputs are valid once `stream` reaches
+ * that point.  Otherwise the call synchronizes with `stream`, scans cold
+ * probes on the CPU, and returns with the outputs complete.
+ */
+int ivf_search_batch_dev(ivf_index_t *index, const float *queries, int64_t nq, int32_t nprobe,
+                         int32_t k, int64_t *out_ids, float *out_dists, void *stream);
+
+/*
+ * Stage 1 only (coarse quantizer): the nprobe best clusters per query, best
+ * first, ties to the smaller cluster id.  queries: DEVICE fp32 [nq][d];
+ * out_probe: DEVICE int32 [nq][nprobe] (entries beyond nlist are -1).
+ * Asynchronous on `stream`.  Does not touch the hit counters.
+ */
+int ivf_coarse_probe_dev(ivf_index_t *index, const float *queries, int64_t nq, int32_t nprobe,
+                         int32_t *out_probe, void *stream);
+
+/*
+ * Stages 2-3 with a caller-given probe list instead of the coarse quantizer
+ * (routing, GPU scan of resident probes, CPU scan of the rest, merge).  All
+ * pointers HOST.  probe: int32 [nq][nprobe]; negative entries are skipped;
+ * other entries must be in [0, nlist) and distinct within a query.  Valid on a
+ * host-only index (everything is scanned on the CPU).
+ */
+int ivf_search_batch_probes(ivf_index_t *index, const float *queries, int64_t nq,
+                            const int32_t *probe, int32_t nprobe, int32_t k, int64_t *out_ids,
+                            float *out_dists);
+
+/*
+ * Router counters (Section 4.3.3; per-query hit rate as defined in Section
+ * 3.3: resident probes / probes).  per_cluster_hits: HOST uint64 [nlist] or
+ * NULL, number of times each cluster was probed since the last reset.
+ * mean_hit_rate = resident probes / all probes; min_hit_rate = smallest
+ * per-query hit rate; n_queries = queries counted.  Any output may be NULL.
+ * reset != 0 clears the counters after reading.  Synchronizes with searches
+ * already enqueued.
+ */
+int ivf_hit_stats(ivf_index_t *index, uint64_t *per_cluster_hits, double *mean_hit_rate,
+                  double *min_hit_rate, uint64_t *n_queries, int reset);
+
+/*
+ * Change the resident set while searches continue (Section 4.3.3).  evict /
+ * admit: HOST cluster ids.  Evicted clusters stop being routed to the GPU at
+ * the next publish; admitted clusters are copied host->device on side_stream
+ * (pinned asynchronous copies when `codes` is pinned) and become resident when
+ * the copy has completed, observed at the start of the next search or by
+ * ivf_migrate_poll().  Until then their probes are served by the CPU scan, so
+ * results never change.  Space of evicted clusters is reused only after every
+ * search that could read it has drained.  IVF_EBUSY if a migration is in
+ * flight; IVF_ENOMEM if the admitted clusters do not fit without the space
+ * still held by evicted ones (nothing changes); IVF_EINVAL for an id out of
+ * range, evicting a non-resident or admitting a resident cluster.
+ */
+int ivf_migrate_clusters(ivf_index_t *index, const int32_t *evict, int32_t n_evict,
+                         const int32_t *admit, int32_t n_admit, void *side_stream);
+
+/*
+ * Progress of the migration in flight.  wait != 0 blocks until the copies have
+ * completed.  Publishes the new mapping table when complete.  Returns 1 if a
+ * migration is still in flight after the call, 0 if none is, negative on
+ * error.  bytes_copied (HOST, may be NULL): code + id bytes of clusters
+ * admitted by migrations completed since creation.
+ */
+int ivf_migrate_poll(ivf_index_t *index, int wait, uint64_t *bytes_copied);
+
+/* Number of currently resident clusters and vectors (either may be NULL). */
+int ivf_resident_info(ivf_index_t *index, int32_t *n_clusters, int64_t *n_vectors);
+
+/*
+ * Tuning and instrumentation.  scan_slices: blocks per query in the ADC scan
+ * (0 = automatic).  timing != 0 records HIP events around each kernel of
+ * subsequent searches on their stream.
+ */
+int ivf_set_tuning(ivf_index_t *index, int32_t scan_slices, int32_t timing);
+
+/*
+ * Kernel times accumulated since the last reset, from HIP events recorded on
+ * the search stream.  ms: HOST double [IVF_N_STAGES] total milliseconds per
+ * stage; launches: HOST uint64 [IVF_N_STAGES]; scan_bytes: HOST, sum over
+ * (query, resident probe) pairs of M * list length, the bytes the ADC scan
+ * must stream.  Synchronizes with recorded events.  reset != 0 clears.
+ */
+enum {
+  IVF_STAGE_COARSE_GEMM = 0,
+  IVF_STAGE_COARSE_SELECT = 1,
+  IVF_STAGE_ROUTE = 2,
+  IVF_STAGE_LUT = 3,
+  IVF_STAGE_SCAN = 4,
+  IVF_STAGE_MERGE = 5,
+  IVF_N_STAGES = 6
+};
+int ivf_stage_times(ivf_index_t *index, double *ms, uint64_t *launches, uint64_t *scan_bytes,
+                    int reset);
+
+/* Message for the last error returned on this thread ("" if none). */
+const char *ivf_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* IVFPQ_HOT_H */

@@ -1,0 +1,49 @@
+"""MI355X-native IVF-PQ search over the GPU-resident hot-cluster partition of an
+inverted-file index (after VectorLiteRAG, arXiv 2504.08930).
+
+`binding` wraps the C ABI declared in include/ivfpq_hot.h; the functions below
+carry the same names as the C entry points and only marshal arguments.
+"""
+from .binding import (  # noqa: F401
+    IVF_METRIC_IP, IVF_METRIC_L2, IvfError, IvfIndex, load_library, LIB_PATH, EXPORTS,
+)
+
+
+def ivf_index_create(data, max_nq, max_nprobe, max_k, **kw):
+    return IvfIndex(data, max_nq, max_nprobe, max_k, **kw)
+
+
+def ivf_index_destroy(index):
+    index.close()
+
+
+def ivf_index_load_partition(index, cluster_ids, stream=None):
+    return index.load_partition(cluster_ids, stream)
+
+
+def ivf_search_batch(index, queries, nprobe, k):
+    return index.search_batch(queries, nprobe, k)
+
+
+def ivf_search_batch_dev(index, queries, nprobe, k, out_ids=None, out_dists=None, stream=None):
+    return index.search_batch_dev(queries, nprobe, k, out_ids, out_dists, stream)
+
+
+def ivf_coarse_probe_dev(index, queries, nprobe, stream=None):
+    return index.coarse_probe_dev(queries, nprobe, stream)
+
+
+def ivf_search_batch_probes(index, queries, probe, k):
+    return index.search_batch_probes(queries, probe, k)
+
+
+def ivf_hit_stats(index, reset=False):
+    return index.hit_stats(reset)
+
+
+def ivf_migrate_clusters(index, evict, admit, side_stream=None):
+    return index.migrate_clusters(evict, admit, side_stream)
+
+
+def ivf_migrate_poll(index, wait=False):
+    return index.migrate_poll(wait)

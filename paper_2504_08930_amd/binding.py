@@ -1,0 +1,257 @@
+"""Thin ctypes binding of libivfpq_hot.so: argument marshalling only.
+
+Every step of the search runs inside the library; torch is used here for
+device memory (the arena, query and result tensors) and streams.  There is no
+fallback: if the shared library is missing, loading raises.
+"""
+import ctypes
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libivfpq_hot.so")
+
+IVF_METRIC_L2, IVF_METRIC_IP = 0, 1
+IVF_OK, IVF_EINVAL, IVF_ENOMEM, IVF_EDEVICE, IVF_EBUSY, IVF_ESTATE = 0, -1, -2, -3, -4, -5
+IVF_N_STAGES = 6
+STAGE_NAMES = ("coarse_gemm", "coarse_select", "route", "lut", "scan", "merge")
+
+EXPORTS = (
+    "ivf_index_arena_bytes", "ivf_index_create", "ivf_index_destroy",
+    "ivf_index_load_partition", "ivf_search_batch", "ivf_search_batch_dev",
+    "ivf_coarse_probe_dev", "ivf_search_batch_probes", "ivf_hit_stats",
+    "ivf_migrate_clusters", "ivf_migrate_poll", "ivf_resident_info",
+    "ivf_set_tuning", "ivf_stage_times", "ivf_last_error",
+)
+
+
+class IvfError(RuntimeError):
+    def __init__(self, code, message):
+        super().__init__(f"ivfpq_hot error {code}: {message}")
+        self.code = code
+
+
+class IvfIndexDesc(ctypes.Structure):
+    _fields_ = [
+        ("d", ctypes.c_int32), ("nlist", ctypes.c_int32), ("M", ctypes.c_int32),
+        ("nbits", ctypes.c_int32), ("metric", ctypes.c_int32), ("max_nq", ctypes.c_int32),
+        ("max_nprobe", ctypes.c_int32), ("max_k", ctypes.c_int32),
+        ("centroids", ctypes.c_void_p), ("codebooks", ctypes.c_void_p),
+        ("list_offsets", ctypes.c_void_p), ("codes", ctypes.c_void_p), ("ids", ctypes.c_void_p),
+    ]
+
+
+_lib = None
+
+
+def load_library():
+    """Load the HIP library; raises if it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is missing: run `python -m paper_2504_08930_amd.build` "
+                          "(there is no fallback path)")
+    lib = ctypes.CDLL(LIB_PATH)
+    P, I32, I64, SZ = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_size_t
+    DP = ctypes.POINTER(IvfIndexDesc)
+    lib.ivf_index_arena_bytes.argtypes = [DP, I64, SZ]
+    lib.ivf_index_arena_bytes.restype = SZ
+    lib.ivf_index_create.argtypes = [DP, P, SZ, SZ, ctypes.POINTER(P)]
+    lib.ivf_index_destroy.argtypes = [P]
+    lib.ivf_index_destroy.restype = None
+    lib.ivf_index_load_partition.argtypes = [P, P, I32, P]
+    lib.ivf_search_batch.argtypes = [P, P, I64, I32, I32, P, P]
+    lib.ivf_search_batch_dev.argtypes = [P, P, I64, I32, I32, P, P, P]
+    lib.ivf_coarse_probe_dev.argtypes = [P, P, I64, I32, P, P]
+    lib.ivf_search_batch_probes.argtypes = [P, P, I64, P, I32, I32, P, P]
+    lib.ivf_hit_stats.argtypes = [P, P, P, P, P, ctypes.c_int]
+    lib.ivf_migrate_clusters.argtypes = [P, P, I32, P, I32, P]
+    lib.ivf_migrate_poll.argtypes = [P, ctypes.c_int, P]
+    lib.ivf_resident_info.argtypes = [P, P, P]
+    lib.ivf_set_tuning.argtypes = [P, I32, I32]
+    lib.ivf_stage_times.argtypes = [P, P, P, P, ctypes.c_int]
+    lib.ivf_last_error.argtypes = []
+    lib.ivf_last_error.restype = ctypes.c_char_p
+    for name in EXPORTS:
+        if name not in ("ivf_index_arena_bytes", "ivf_index_destroy", "ivf_last_error"):
+            getattr(lib, name).restype = ctypes.c_int
+    _lib = lib
+    return lib
+
+
+def _check(rc):
+    if rc < 0:
+        raise IvfError(rc, load_library().ivf_last_error().decode())
+    return rc
+
+
+def _np_ptr(a):
+    return None if a is None else ctypes.c_void_p(a.ctypes.data)
+
+
+def _i32(a):
+    return np.ascontiguousarray(a, dtype=np.int32)
+
+
+class IvfIndex:
+    """Owner of an ivf_index_t handle plus the host arrays and arena it borrows."""
+
+    def __init__(self, data, max_nq, max_nprobe, max_k, resident_vectors=None,
+                 device="cuda:0", host_only=False, staging_bytes=0):
+        lib = load_library()
+        self._lib = lib
+        self.d, self.nlist, self.m, self.metric = data.d, data.nlist, data.m, data.metric
+        self.max_nq, self.max_nprobe, self.max_k = max_nq, max_nprobe, max_k
+        self.n = int(data.list_offsets[-1])
+        self._arena = None
+        self._torch = None
+        host = {
+            "centroids": np.ascontiguousarray(data.centroids, dtype=np.float32),
+            "codebooks": np.ascontiguousarray(data.codebooks, dtype=np.float32),
+            "list_offsets": np.ascontiguousarray(data.list_offsets, dtype=np.int64),
+            "codes": np.ascontiguousarray(data.codes, dtype=np.uint8),
+            "ids": np.ascontiguousarray(data.ids, dtype=np.int64),
+        }
+        if not host_only:
+            import torch
+            self._torch = torch
+            self.device = torch.device(device)
+            # pinned copies so cluster copies can be asynchronous
+            self._pinned = {}
+            for key in ("codes", "ids"):
+                t = torch.from_numpy(host[key]).pin_memory()
+                self._pinned[key] = t
+                host[key] = t.numpy()
+        self._host = host
+        desc = IvfIndexDesc(self.d, self.nlist, self.m, 8, self.metric, max_nq, max_nprobe, max_k,
+                            host["centroids"].ctypes.data, host["codebooks"].ctypes.data,
+                            host["list_offsets"].ctypes.data, host["codes"].ctypes.data,
+                            host["ids"].ctypes.data)
+        self._desc = desc
+        handle = ctypes.c_void_p()
+        if host_only:
+            _check(lib.ivf_index_create(ctypes.byref(desc), None, 0, 0, ctypes.byref(handle)))
+        else:
+            torch = self._torch
+            if resident_vectors is None:
+                resident_vectors = self.n + 64 * self.nlist
+            nbytes = lib.ivf_index_arena_bytes(ctypes.byref(desc), int(resident_vectors),
+                                               int(staging_bytes))
+            if nbytes == 0:
+                raise IvfError(IVF_EINVAL, "invalid index description")
+            with torch.cuda.device(self.device):
+                self._arena = torch.empty(nbytes + 256, dtype=torch.uint8, device=self.device)
+                base = (self._arena.data_ptr() + 255) & ~255
+                torch.cuda.synchronize()
+                _check(lib.ivf_index_create(ctypes.byref(desc), ctypes.c_void_p(base), nbytes,
+                                            int(staging_bytes), ctypes.byref(handle)))
+            self.arena_bytes = nbytes
+        self._h = handle
+
+    # ---- lifetime ----
+    def close(self):
+        if getattr(self, "_h", None):
+            self._lib.ivf_index_destroy(self._h)
+            self._h = None
+            self._arena = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    @staticmethod
+    def _stream_ptr(stream):
+        return None if stream is None else ctypes.c_void_p(stream.cuda_stream)
+
+    # ---- residency ----
+    def load_partition(self, cluster_ids, stream=None):
+        ids = _i32(cluster_ids)
+        _check(self._lib.ivf_index_load_partition(self._h, _np_ptr(ids), ids.size,
+                                                  self._stream_ptr(stream)))
+
+    def migrate_clusters(self, evict, admit, side_stream=None):
+        ev, ad = _i32(evict), _i32(admit)
+        _check(self._lib.ivf_migrate_clusters(self._h, _np_ptr(ev), ev.size, _np_ptr(ad), ad.size,
+                                              self._stream_ptr(side_stream)))
+
+    def migrate_poll(self, wait=False):
+        nbytes = ctypes.c_uint64(0)
+        rc = _check(self._lib.ivf_migrate_poll(self._h, int(bool(wait)), ctypes.byref(nbytes)))
+        return rc == 1, nbytes.value
+
+    def resident_info(self):
+        nc, nv = ctypes.c_int32(0), ctypes.c_int64(0)
+        _check(self._lib.ivf_resident_info(self._h, ctypes.byref(nc), ctypes.byref(nv)))
+        return nc.value, nv.value
+
+    # ---- search ----
+    def search_batch(self, queries, nprobe, k):
+        q = np.ascontiguousarray(queries, dtype=np.float32)
+        nq = q.shape[0]
+        ids = np.empty((nq, k), np.int64)
+        dists = np.empty((nq, k), np.float32)
+        _check(self._lib.ivf_search_batch(self._h, _np_ptr(q), nq, nprobe, k, _np_ptr(ids),
+                                          _np_ptr(dists)))
+        return ids, dists
+
+    def search_batch_dev(self, queries, nprobe, k, out_ids=None, out_dists=None, stream=None):
+        torch = self._torch
+        assert queries.is_cuda and queries.dtype == torch.float32 and queries.is_contiguous()
+        nq = queries.shape[0]
+        if out_ids is None:
+            out_ids = torch.empty((nq, k), dtype=torch.int64, device=queries.device)
+        if out_dists is None:
+            out_dists = torch.empty((nq, k), dtype=torch.float32, device=queries.device)
+        st = stream if stream is not None else torch.cuda.current_stream(queries.device)
+        _check(self._lib.ivf_search_batch_dev(self._h, ctypes.c_void_p(queries.data_ptr()), nq,
+                                              nprobe, k, ctypes.c_void_p(out_ids.data_ptr()),
+                                              ctypes.c_void_p(out_dists.data_ptr()),
+                                              self._stream_ptr(st)))
+        return out_ids, out_dists
+
+    def coarse_probe_dev(self, queries, nprobe, stream=None):
+        torch = self._torch
+        assert queries.is_cuda and queries.dtype == torch.float32 and queries.is_contiguous()
+        nq = queries.shape[0]
+        out = torch.empty((nq, nprobe), dtype=torch.int32, device=queries.device)
+        st = stream if stream is not None else torch.cuda.current_stream(queries.device)
+        _check(self._lib.ivf_coarse_probe_dev(self._h, ctypes.c_void_p(queries.data_ptr()), nq,
+                                              nprobe, ctypes.c_void_p(out.data_ptr()),
+                                              self._stream_ptr(st)))
+        return out
+
+    def search_batch_probes(self, queries, probe, k):
+        q = np.ascontiguousarray(queries, dtype=np.float32)
+        pr = _i32(probe)
+        nq, nprobe = pr.shape
+        ids = np.empty((nq, k), np.int64)
+        dists = np.empty((nq, k), np.float32)
+        _check(self._lib.ivf_search_batch_probes(self._h, _np_ptr(q), nq, _np_ptr(pr), nprobe, k,
+                                                 _np_ptr(ids), _np_ptr(dists)))
+        return ids, dists
+
+    # ---- counters / instrumentation ----
+    def hit_stats(self, reset=False):
+        hits = np.zeros(self.nlist, np.uint64)
+        mean, mn = ctypes.c_double(0), ctypes.c_double(0)
+        nq = ctypes.c_uint64(0)
+        _check(self._lib.ivf_hit_stats(self._h, _np_ptr(hits), ctypes.byref(mean), ctypes.byref(mn),
+                                       ctypes.byref(nq), int(bool(reset))))
+        return {"per_cluster_hits": hits, "mean_hit_rate": mean.value,
+                "min_hit_rate": mn.value, "n_queries": nq.value}
+
+    def set_tuning(self, scan_slices=0, timing=False):
+        _check(self._lib.ivf_set_tuning(self._h, int(scan_slices), int(bool(timing))))
+
+    def stage_times(self, reset=False):
+        ms = np.zeros(IVF_N_STAGES, np.float64)
+        n = np.zeros(IVF_N_STAGES, np.uint64)
+        sb = ctypes.c_uint64(0)
+        _check(self._lib.ivf_stage_times(self._h, _np_ptr(ms), _np_ptr(n), ctypes.byref(sb),
+                                         int(bool(reset))))
+        return {"ms": dict(zip(STAGE_NAMES, ms.tolist())),
+                "launches": dict(zip(STAGE_NAMES, n.tolist())), "scan_bytes": sb.value}

@@ -1,0 +1,112 @@
+#include "host_scan.h"
+
+#include <stdlib.h>
+
+#include <algorithm>
+#include <atomic>
+#include <thread>
+
+#include "lut_quant.h"
+
+namespace ivf {
+
+int cpu_threads() {
+  static int n = [] {
+    int v = 0;
+    if (const char *e = getenv("IVF_CPU_THREADS")) v = atoi(e);
+    if (v <= 0) {
+      if (const char *e = getenv("OMP_NUM_THREADS")) v = atoi(e);
+    }
+    if (v <= 0) v = (int)std::thread::hardware_concurrency();
+    if (v <= 0) v = 1;
+    return std::min(v, 256);
+  }();
+  return n;
+}
+
+void parallel_for(int64_t n, const std::function<void(int64_t)> &fn) {
+  if (n <= 0) return;
+  int nt = (int)std::min<int64_t>(cpu_threads(), n);
+  if (nt <= 1) {
+    for (int64_t i = 0; i < n; ++i) fn(i);
+    return;
+  }
+  std::atomic<int64_t> next(0);
+  auto work = [&]() {
+    for (;;) {
+      int64_t i = next.fetch_add(1, std::memory_order_relaxed);
+      if (i >= n) break;
+      fn(i);
+    }
+  };
+  std::vector<std::thread> th;
+  th.reserve(nt - 1);
+  for (int t = 1; t < nt; ++t) th.emplace_back(work);
+  work();
+  for (auto &t : th) t.join();
+}
+
+int cpu_build_lut(const HostIndexView &ix, const float *q, int32_t *lut) {
+  const int M = ix.M, dsub = ix.dsub;
+  std::vector<float> f((size_t)M * 256);
+  double B = 0.0;
+  for (int m = 0; m < M; ++m) {
+    float mx = 0.0f;
+    for (int j = 0; j < 256; ++j) {
+      float v = lut_entry(ix.metric_ip, q + (size_t)m * dsub,
+                          ix.codebooks + ((size_t)m * 256 + j) * dsub, dsub);
+      f[(size_t)m * 256 + j] = v;
+      mx = std::max(mx, fabsf(v));
+    }
+    B += (double)mx;
+  }
+  const int e = lut_exponent(B);
+  for (size_t i = 0; i < f.size(); ++i) lut[i] = lut_quantize(f[i], e);
+  return e;
+}
+
+static inline bool cand_less(const HostCand &a, const HostCand &b) {
+  return a.key < b.key || (a.key == b.key && a.id < b.id);
+}
+
+void cpu_scan_lists(const HostIndexView &ix, const int32_t *lut, const int32_t *clusters,
+                    int n_clusters, int k, HostCand *out) {
+  // bounded max-heap on (key, id): the worst kept candidate sits on top
+  std::vector<HostCand> heap;
+  heap.reserve((size_t)k);
+  const int M = ix.M;
+  for (int c = 0; c < n_clusters; ++c) {
+    const int cl = clusters[c];
+    if (cl < 0) continue;
+    for (int64_t v = ix.list_offsets[cl]; v < ix.list_offsets[cl + 1]; ++v) {
+      const uint8_t *code = ix.codes + (size_t)v * M;
+      int32_t sum = 0;
+      for (int m = 0; m < M; ++m) sum += lut[m * 256 + code[m]];
+      HostCand cand{sum, ix.ids[v]};
+      if ((int)heap.size() < k) {
+        heap.push_back(cand);
+        std::push_heap(heap.begin(), heap.end(), cand_less);
+      } else if (cand_less(cand, heap.front())) {
+        std::pop_heap(heap.begin(), heap.end(), cand_less);
+        heap.back() = cand;
+        std::push_heap(heap.begin(), heap.end(), cand_less);
+      }
+    }
+  }
+  std::sort_heap(heap.begin(), heap.end(), cand_less);
+  for (int r = 0; r < k; ++r)
+    out[r] = r < (int)heap.size() ? heap[r] : HostCand{kKeyInvalid, -1};
+}
+
+void merge_topk(const HostCand *a, const HostCand *b, int k, HostCand *out) {
+  int i = 0, j = 0;
+  for (int r = 0; r < k; ++r) {
+    const bool a_ok = i < k && a[i].key != kKeyInvalid;
+    const bool b_ok = j < k && b[j].key != kKeyInvalid;
+    if (a_ok && (!b_ok || cand_less(a[i], b[j]))) out[r] = a[i++];
+    else if (b_ok) out[r] = b[j++];
+    else out[r] = HostCand{kKeyInvalid, -1};
+  }
+}
+
+}  // namespace ivf

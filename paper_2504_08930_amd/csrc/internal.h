@@ -1,0 +1,106 @@
+// Internal declarations shared by the host API and the kernel launchers.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/ivfpq_hot.h"
+
+namespace ivf {
+
+constexpr int kTileVecs = 64;      // vectors per code tile (one wavefront)
+constexpr int kMaxSlices = 8;      // scan blocks per query, upper bound
+constexpr int kMaxK = 128;
+constexpr int kMaxNprobe = 2048;
+
+// Counters kept on the device next to the per-cluster hit counters.
+enum {
+  QS_RESIDENT_PROBES = 0,
+  QS_PROBES = 1,
+  QS_QUERIES = 2,
+  QS_MIN_RATE_BITS = 3,  // float bits of the smallest per-query hit rate
+  QS_SCAN_BYTES = 4,     // instrumentation, reset separately
+  QS_COUNT = 8
+};
+
+// One 64-vector tile to fill from staged raw codes/ids.
+struct TileDesc {
+  int32_t dst_tile;   // tile index in the cluster region
+  int32_t src_vec;    // first vector in the staging chunk
+  int32_t n_valid;    // 1..64 (0 never emitted)
+  int32_t pad;
+};
+
+// Pointers into the device arena.
+struct DevLayout {
+  float *centroids;        // [nlist][d]
+  float *cent_norm;        // [nlist] squared norms (L2 only)
+  float *cbT;              // [256][M][dsub] transposed codebooks
+  int32_t *clus_len;       // [nlist]
+  int32_t *clus_tile[3];   // mapping table ring: first tile of a resident cluster, or -1
+  unsigned long long *hits;    // [nlist]
+  unsigned long long *qstats;  // [QS_COUNT]
+  float *queries;          // [max_nq][d]
+  float *scores;           // [max_nq][nlist]
+  int32_t *probe;          // [max_nq][max_nprobe]
+  int32_t *g_base;         // [max_nq][max_nprobe] first tile of each resident probe
+  int32_t *g_len;          // [max_nq][max_nprobe] list length
+  int32_t *g_prefix;       // [max_nq][max_nprobe+1] running tile count
+  int32_t *g_n;            // [max_nq] resident probes
+  int32_t *cold;           // [max_nq][max_nprobe] non-resident cluster ids
+  int32_t *n_cold;         // [max_nq]
+  float *lut;              // [max_nq][256][M]
+  uint32_t *lutmax;        // [max_nq][M] bits of max |entry|
+  int32_t *lutexp;         // [max_nq]
+  int32_t *part_key;       // [max_nq][kMaxSlices][max_k]
+  int64_t *part_id;
+  int32_t *res_key;        // [max_nq][max_k] merged GPU partial (hybrid path)
+  int64_t *res_id;
+  int64_t *out_ids;        // [max_nq][max_k] host-API staging
+  float *out_dists;
+  uint8_t *staging;        // copy staging
+  size_t staging_bytes;
+  uint8_t *tile_codes;     // [cap_tiles][M*64]
+  int64_t *tile_ids;       // [cap_tiles][64]
+  int64_t cap_tiles;
+};
+
+struct Shape {
+  int d, nlist, M, dsub, metric_ip;
+};
+
+// ---- kernel launchers (kernels_*.hip).  All enqueue on `st` and return the
+// HIP error of the launch. ----
+hipError_t launch_fill_u32(uint32_t *p, size_t n, uint32_t v, hipStream_t st);
+
+hipError_t launch_cent_norms(const float *cent, int nlist, int d, float *out, hipStream_t st);
+
+hipError_t launch_coarse_gemm(const Shape &sh, const float *q, int nq, const float *cent,
+                              const float *cent_norm, float *scores, hipStream_t st);
+
+hipError_t launch_coarse_select(const Shape &sh, const float *scores, int nq, int nprobe,
+                                int probe_stride, int32_t *probe, hipStream_t st);
+
+hipError_t launch_route(const int32_t *probe, int nq, int nprobe, int probe_stride,
+                        const int32_t *clus_tile, const int32_t *clus_len, int M, int32_t *g_base,
+                        int32_t *g_len, int32_t *g_prefix, int32_t *g_n, int32_t *cold,
+                        int32_t *n_cold, unsigned long long *hits, unsigned long long *qstats,
+                        int count_stats, hipStream_t st);
+
+hipError_t launch_lut(const Shape &sh, const float *q, int nq, const float *cbT, float *lut,
+                      uint32_t *lutmax, int32_t *lutexp, hipStream_t st);
+
+// Returns hipErrorInvalidValue for an unsupported (M, k).
+hipError_t launch_scan(const Shape &sh, const DevLayout &L, int nq, int probe_stride, int slices,
+                       int k, hipStream_t st);
+
+// final != 0: write (id, dist) to out_ids/out_dists; else (key, id) to res_key/res_id.
+hipError_t launch_merge(const Shape &sh, const DevLayout &L, int nq, int slices, int k,
+                        int64_t *out_ids, float *out_dists, hipStream_t st);
+
+hipError_t launch_interleave(const uint8_t *stage_codes, const int64_t *stage_ids,
+                             const TileDesc *descs, int n_tiles, int M, uint8_t *tile_codes,
+                             int64_t *tile_ids, hipStream_t st);
+
+bool scan_supports(int M, int k);
+
+}  // namespace ivf

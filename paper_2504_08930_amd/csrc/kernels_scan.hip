@@ -1,0 +1,655 @@
+// Routing, lookup-table construction, ADC scan, top-k merge, and the code-tile
+// layout transform, for gfx950 (wave64, 160 KB LDS per CU).
+//
+// Stage numbering follows Section 2.2 ("Search Operation in IVF Index"):
+// stage 2 builds the per-query table of partial distances, stage 3 scans the
+// codes of the probed clusters through it and keeps the k best.  Routing of
+// probes by the mapping table follows Section 4.3.1.
+//
+// ADC scan design (what differs from the one-thread-block-per-(query, cluster)
+// scheme the paper describes for its GPU tier in Section 3.1):
+//  * one block serves one query and walks ALL of that query's resident probes
+//    (or a 1/S slice of their tiles), so the table is staged in LDS once per
+//    block instead of once per probed cluster;
+//  * codes are stored in 64-vector tiles, one lane per vector, 16-byte units
+//    interleaved across lanes, so every global load instruction is a fully
+//    coalesced 1 KB read;
+//  * the table is stored code-major ([code][column], 64 columns per row) and
+//    each lane visits the sub-quantizers of a 32-wide group in the order
+//    column = lane XOR step.  For a fixed step the 32 lanes of a half-wave hit
+//    32 different LDS banks whatever the code values are: lookups are
+//    conflict-free by construction.  The codes are stored pre-permuted to match
+//    (see src_subq), so no register shuffling is needed at scan time;
+//  * the LDS address of a lookup is assembled by one byte-permute instruction
+//    (code byte -> address bits 8..15, lane column -> bits 0..7);
+//  * table entries are int32 fixed point (lut_quant.h), so the visiting order
+//    does not change the sum.
+#include <hip/hip_runtime.h>
+
+#include "internal.h"
+#include "lut_quant.h"
+
+namespace ivf {
+
+// ---------------------------------------------------------------------------
+// small helpers
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ bool cand_less(int ka, long long ia, int kb, long long ib) {
+  return ka < kb || (ka == kb && ia < ib);
+}
+
+// Read an int at a raw LDS byte address.  The scan kernel's dynamic LDS block
+// is the kernel's only LDS and therefore starts at address 0, so table offsets
+// are LDS addresses; going through an address-space-3 pointer keeps the
+// compiler from adding a (zero) base to every lookup.
+typedef const __attribute__((address_space(3))) int *lds_int_ptr;
+__device__ __forceinline__ int lds_read_i32(uint32_t addr) {
+  return *reinterpret_cast<lds_int_ptr>(static_cast<uintptr_t>(addr));
+}
+
+__device__ __forceinline__ void wave_sync() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// In-place ascending bitonic sort of n (power of two) candidates held in LDS.
+// BLOCK = true: all threads of the block take part, separated by __syncthreads;
+// BLOCK = false: one wavefront sorts its own private range.
+template <bool BLOCK>
+__device__ void bitonic_sort_lds(int *keys, long long *ids, int n, int tid, int nthreads) {
+  for (int size = 2; size <= n; size <<= 1) {
+    for (int stride = size >> 1; stride > 0; stride >>= 1) {
+      for (int i = tid; i < n; i += nthreads) {
+        int j = i ^ stride;
+        if (j > i) {
+          bool asc = (i & size) == 0;
+          int ka = keys[i], kb = keys[j];
+          long long ia = ids[i], ib = ids[j];
+          bool b_first = cand_less(kb, ib, ka, ia);
+          if (b_first == asc) {
+            keys[i] = kb; ids[i] = ib;
+            keys[j] = ka; ids[j] = ia;
+          }
+        }
+      }
+      if (BLOCK) __syncthreads(); else wave_sync();
+    }
+  }
+}
+
+__global__ void k_fill_u32(uint32_t *p, size_t n, uint32_t v) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  size_t step = (size_t)gridDim.x * blockDim.x;
+  for (; i < n; i += step) p[i] = v;
+}
+
+hipError_t launch_fill_u32(uint32_t *p, size_t n, uint32_t v, hipStream_t st) {
+  if (n == 0) return hipSuccess;
+  size_t blocks = (n + 255) / 256;
+  if (blocks > 4096) blocks = 4096;
+  hipLaunchKernelGGL(k_fill_u32, dim3((unsigned)blocks), dim3(256), 0, st, p, n, v);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+// Routing (Section 4.3.1): each probe is looked up in the mapping table;
+// resident probes form the query's GPU work list, the others its cold list.
+// Also the router's counters (Section 4.3.3).
+// ---------------------------------------------------------------------------
+__global__ void k_route(const int32_t *__restrict__ probe, int nq, int nprobe, int stride,
+                        const int32_t *__restrict__ clus_tile,
+                        const int32_t *__restrict__ clus_len, int M, int32_t *g_base,
+                        int32_t *g_len, int32_t *g_prefix, int32_t *g_n, int32_t *cold,
+                        int32_t *n_cold, unsigned long long *hits, unsigned long long *qstats,
+                        int count_stats) {
+  int q = blockIdx.x * blockDim.x + threadIdx.x;
+  if (q >= nq) return;
+  const int32_t *pr = probe + (size_t)q * stride;
+  int32_t *gb = g_base + (size_t)q * stride;
+  int32_t *gl = g_len + (size_t)q * stride;
+  int32_t *gp = g_prefix + (size_t)q * (stride + 1);
+  int32_t *cd = cold + (size_t)q * stride;
+  int ng = 0, nc = 0, tiles = 0, valid = 0;
+  unsigned long long vecs = 0;
+  for (int p = 0; p < nprobe; ++p) {
+    int c = pr[p];
+    if (c < 0) continue;
+    ++valid;
+    if (count_stats) atomicAdd(&hits[c], 1ull);
+    int t = clus_tile[c];
+    int len = clus_len[c];
+    if (t >= 0) {
+      gb[ng] = t;
+      gl[ng] = len;
+      gp[ng] = tiles;
+      tiles += (len + kTileVecs - 1) / kTileVecs;
+      vecs += (unsigned long long)len;
+      ++ng;
+    } else {
+      cd[nc++] = c;
+    }
+  }
+  gp[ng] = tiles;
+  g_n[q] = ng;
+  n_cold[q] = nc;
+  for (int p = nc; p < nprobe; ++p) cd[p] = -1;
+  atomicAdd(&qstats[QS_SCAN_BYTES], vecs * (unsigned long long)M);
+  if (count_stats) {
+    atomicAdd(&qstats[QS_RESIDENT_PROBES], (unsigned long long)ng);
+    atomicAdd(&qstats[QS_PROBES], (unsigned long long)valid);
+    atomicAdd(&qstats[QS_QUERIES], 1ull);
+    float rate = valid ? (float)ng / (float)valid : 0.0f;
+    atomicMin(reinterpret_cast<unsigned int *>(&qstats[QS_MIN_RATE_BITS]), __float_as_uint(rate));
+  }
+}
+
+hipError_t launch_route(const int32_t *probe, int nq, int nprobe, int probe_stride,
+                        const int32_t *clus_tile, const int32_t *clus_len, int M, int32_t *g_base,
+                        int32_t *g_len, int32_t *g_prefix, int32_t *g_n, int32_t *cold,
+                        int32_t *n_cold, unsigned long long *hits, unsigned long long *qstats,
+                        int count_stats, hipStream_t st) {
+  hipLaunchKernelGGL(k_route, dim3((nq + 63) / 64), dim3(64), 0, st, probe, nq, nprobe,
+                     probe_stride, clus_tile, clus_len, M, g_base, g_len, g_prefix, g_n, cold,
+                     n_cold, hits, qstats, count_stats);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+// Stage 2: per-query lookup table, fp32, layout [query][code j][sub-quantizer m],
+// plus the largest |entry| per (query, m) for the fixed-point scale.
+// Thread (ml, jl) owns one codeword (m, j) in registers and loops over the
+// queries of its tile, so codebooks are read once per query tile, not once per
+// query.  Lanes run along m: table stores are contiguous in m.
+// ---------------------------------------------------------------------------
+constexpr int kLutQTile = 32;
+
+template <int DSUB>
+__global__ __launch_bounds__(256) void k_lut(const float *__restrict__ queries, int nq, int d,
+                                             int M, int dsub_rt, int MW,
+                                             const float *__restrict__ cbT, int metric_ip,
+                                             float *__restrict__ lut,
+                                             uint32_t *__restrict__ lutmax) {
+  const int dsub = DSUB > 0 ? DSUB : dsub_rt;
+  const int tid = threadIdx.x;
+  const int JT = 256 / MW;
+  const int ml = tid % MW, jl = tid / MW;
+  const int m = blockIdx.y * MW + ml;
+  const int j = blockIdx.x * JT + jl;
+  const int q0 = blockIdx.z * kLutQTile;
+  const int q1 = min(nq, q0 + kLutQTile);
+  __shared__ uint32_t smax[256];
+
+  const float *cw = cbT + ((size_t)j * M + m) * dsub;
+  float creg[DSUB > 0 ? DSUB : 1];
+  if (DSUB > 0) {
+#pragma unroll
+    for (int t = 0; t < DSUB; ++t) creg[t] = cw[t];
+  }
+  for (int qi = q0; qi < q1; ++qi) {
+    const float *qv = queries + (size_t)qi * d + (size_t)m * dsub;
+    float v;
+    if (DSUB > 0) {
+      float qreg[DSUB > 0 ? DSUB : 1];
+#pragma unroll
+      for (int t = 0; t < DSUB; ++t) qreg[t] = qv[t];
+      v = lut_entry(metric_ip, qreg, creg, DSUB);
+    } else {
+      v = lut_entry(metric_ip, qv, cw, dsub);
+    }
+    lut[((size_t)qi * 256 + j) * M + m] = v;
+    smax[tid] = __float_as_uint(fabsf(v));
+    __syncthreads();
+    if (tid < MW) {
+      uint32_t mx = 0;
+      for (int r = 0; r < JT; ++r) mx = max(mx, smax[r * MW + tid]);
+      atomicMax(&lutmax[(size_t)qi * M + m], mx);
+    }
+    __syncthreads();
+  }
+}
+
+__global__ void k_lut_exp(const uint32_t *__restrict__ lutmax, int nq, int M,
+                          int32_t *__restrict__ lutexp) {
+  int q = blockIdx.x * blockDim.x + threadIdx.x;
+  if (q >= nq) return;
+  double B = 0.0;
+  for (int m = 0; m < M; ++m) B += (double)__uint_as_float(lutmax[(size_t)q * M + m]);
+  lutexp[q] = lut_exponent(B);
+}
+
+hipError_t launch_lut(const Shape &sh, const float *q, int nq, const float *cbT, float *lut,
+                      uint32_t *lutmax, int32_t *lutexp, hipStream_t st) {
+  hipError_t e = launch_fill_u32(lutmax, (size_t)nq * sh.M, 0u, st);
+  if (e != hipSuccess) return e;
+  const int MW = (sh.M % 32 == 0) ? 32 : 16;
+  const int JT = 256 / MW;
+  dim3 grid(256 / JT, sh.M / MW, (nq + kLutQTile - 1) / kLutQTile);
+#define IVF_LUT_CASE(DS)                                                                       \
+  case DS:                                                                                     \
+    hipLaunchKernelGGL(k_lut<DS>, grid, dim3(256), 0, st, q, nq, sh.d, sh.M, sh.dsub, MW, cbT, \
+                       sh.metric_ip, lut, lutmax);                                             \
+    break;
+  switch (sh.dsub) {
+    IVF_LUT_CASE(2)
+    IVF_LUT_CASE(4)
+    IVF_LUT_CASE(8)
+    IVF_LUT_CASE(12)
+    IVF_LUT_CASE(16)
+    default:
+      hipLaunchKernelGGL(k_lut<0>, grid, dim3(256), 0, st, q, nq, sh.d, sh.M, sh.dsub, MW, cbT,
+                         sh.metric_ip, lut, lutmax);
+  }
+#undef IVF_LUT_CASE
+  e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(k_lut_exp, dim3((nq + 63) / 64), dim3(64), 0, st, lutmax, nq, sh.M, lutexp);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+// Code-tile layout.
+//
+// Sub-quantizers are split into groups of 32 (a trailing group of 16 when M is
+// not a multiple of 32).  Byte i of a lane's M stored bytes belongs to group
+// gi = i / 32 (position ip inside the group) and holds the code of
+// sub-quantizer  32*gi + ((lane XOR ip) & (W-1)),  W the group width.
+// A tile holds 64 vectors: 16-byte unit u of lane l sits at
+// ((u * 64) + l) * 16 bytes from the start of the tile.
+// ---------------------------------------------------------------------------
+__host__ __device__ inline int src_subq(int lane, int i, int M) {
+  const int n_full = M / 32;
+  int gi = i / 32;
+  int ip = i % 32;
+  int W = 32;
+  if (gi >= n_full) {  // trailing 16-wide group
+    gi = n_full;
+    ip = i - 32 * n_full;
+    W = 16;
+  }
+  return 32 * gi + ((lane ^ ip) & (W - 1));
+}
+
+__global__ __launch_bounds__(512) void k_interleave(const uint8_t *__restrict__ stage_codes,
+                                                    const int64_t *__restrict__ stage_ids,
+                                                    const TileDesc *__restrict__ descs, int M,
+                                                    uint8_t *__restrict__ tile_codes,
+                                                    int64_t *__restrict__ tile_ids) {
+  const TileDesc td = descs[blockIdx.x];
+  const int units = M / 16;
+  const int lane = threadIdx.x & 63;
+  const int u = threadIdx.x >> 6;
+  const bool valid = lane < td.n_valid;
+  const size_t src = (size_t)(td.src_vec + lane);
+  if (u < units) {
+    uint32_t w[4] = {0u, 0u, 0u, 0u};
+    if (valid) {
+      const uint8_t *row = stage_codes + src * M;
+#pragma unroll
+      for (int b = 0; b < 16; ++b) {
+        int m = src_subq(lane, 16 * u + b, M);
+        w[b >> 2] |= (uint32_t)row[m] << (8 * (b & 3));
+      }
+    }
+    uint4 *dst = reinterpret_cast<uint4 *>(tile_codes + (size_t)td.dst_tile * kTileVecs * M);
+    dst[(size_t)u * 64 + lane] = make_uint4(w[0], w[1], w[2], w[3]);
+  }
+  if (u == 0) {
+    tile_ids[(size_t)td.dst_tile * kTileVecs + lane] = valid ? stage_ids[src] : -1;
+  }
+}
+
+hipError_t launch_interleave(const uint8_t *stage_codes, const int64_t *stage_ids,
+                             const TileDesc *descs, int n_tiles, int M, uint8_t *tile_codes,
+                             int64_t *tile_ids, hipStream_t st) {
+  if (n_tiles <= 0) return hipSuccess;
+  hipLaunchKernelGGL(k_interleave, dim3(n_tiles), dim3(512), 0, st, stage_codes, stage_ids, descs,
+                     M, tile_codes, tile_ids);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+// Stage 3: ADC scan with in-block top-k.
+// ---------------------------------------------------------------------------
+struct ScanParams {
+  const uint8_t *tile_codes;
+  const int64_t *tile_ids;
+  const float *lut;
+  const int32_t *lutexp;
+  const int32_t *g_base;
+  const int32_t *g_len;
+  const int32_t *g_prefix;
+  const int32_t *g_n;
+  int32_t *part_key;
+  int64_t *part_id;
+  int probe_stride;
+  int slices;
+  int k;
+  int kp;  // k rounded up to a power of two (>= 16)
+};
+
+template <int M>
+struct ScanGeom {
+  static constexpr int kFull = M / 32;
+  static constexpr int kRem = M % 32;
+  static constexpr int kGroups = kFull + (kRem ? 1 : 0);
+  static constexpr int kTables = (kGroups + 1) / 2;
+  static constexpr int kTableBytes = 65536;  // 256 rows x 64 columns x 4 B
+};
+
+// A located tile: where its codes are and which vectors of it are real.
+struct TileRef {
+  int gtile;   // tile index in the cluster region
+  int first;   // position of lane 0 inside its list
+  int len;     // list length
+};
+
+template <int M, int NW, int CAP>
+__global__ __launch_bounds__(NW * 64) void k_scan(ScanParams P) {
+  using G = ScanGeom<M>;
+  extern __shared__ __align__(16) unsigned char smem[];
+  int *tab = reinterpret_cast<int *>(smem);
+  long long *buf_id_all = reinterpret_cast<long long *>(smem + G::kTables * G::kTableBytes);
+  int *buf_key_all = reinterpret_cast<int *>(smem + G::kTables * G::kTableBytes +
+                                             (size_t)NW * CAP * sizeof(long long));
+  int *s_thr = buf_key_all + NW * CAP;
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int q = blockIdx.x / P.slices;
+  const int s = blockIdx.x % P.slices;
+  const int k = P.k;
+
+  // ---- stage the query's table in LDS as fixed point, code-major ----
+  {
+    const int e = P.lutexp[q];
+    const float4 *src = reinterpret_cast<const float4 *>(P.lut + (size_t)q * 256 * M);
+    constexpr int kVec = 256 * M / 4;
+    for (int idx = tid; idx < kVec; idx += NW * 64) {
+      const float4 v = src[idx];
+      const int flat = idx * 4;
+      const int j = flat / M;
+      const int m0 = flat % M;  // 4 consecutive sub-quantizers of one code (M % 4 == 0)
+      const float vv[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+      for (int t = 0; t < 4; ++t) {
+        const int m = m0 + t;
+        const int key = lut_quantize(vv[t], e);
+        int gi = m / 32, r = m % 32;
+        int *row = tab + (gi >> 1) * (G::kTableBytes / 4) + j * 64 + (gi & 1) * 32;
+        row[r] = key;
+        if (G::kRem && gi == G::kFull) row[r + 16] = key;  // 16-wide group: second replica
+      }
+    }
+    for (int i = tid; i < NW * CAP; i += NW * 64) {
+      buf_key_all[i] = kKeyInvalid;
+      buf_id_all[i] = 0x7fffffffffffffffll;
+    }
+    if (tid == 0) *s_thr = kKeyInvalid;
+  }
+  __syncthreads();
+
+  int *bkey = buf_key_all + w * CAP;
+  long long *bid = buf_id_all + w * CAP;
+
+  // per-lane column offsets: x[ip] = ((lane ^ ip) & 31) * 4, with 1 in byte 2
+  // (selected by the permute only for lookups in the second table).
+  uint32_t x[32];
+#pragma unroll
+  for (int ip = 0; ip < 32; ++ip) x[ip] = ((uint32_t)((lane ^ ip) & 31) << 2) | 0x00010000u;
+
+  const int ng = P.g_n[q];
+  const int32_t *gpre = P.g_prefix + (size_t)q * (P.probe_stride + 1);
+  const int32_t *gbase = P.g_base + (size_t)q * P.probe_stride;
+  const int32_t *glen = P.g_len + (size_t)q * P.probe_stride;
+  const int T = gpre[ng];
+  const int t_begin = (int)((long long)T * s / P.slices);
+  const int t_end = (int)((long long)T * (s + 1) / P.slices);
+
+  // window of 64 probes held one per lane
+  int win_base = -64, win_end = 0;  // win_end: first tile index beyond the window
+  int w_pre = 0, w_tile = 0, w_len = 0;
+
+  auto locate = [&](int t) -> TileRef {
+    while (t >= win_end) {  // wave-uniform
+      win_base += 64;
+      const int p = win_base + lane;
+      const bool in = p < ng;
+      w_pre = in ? gpre[p] : 0x7fffffff;
+      w_tile = in ? gbase[p] : 0;
+      w_len = in ? glen[p] : 0;
+      const int last = min(win_base + 64, ng);
+      win_end = gpre[last];
+    }
+    const unsigned long long mask = __ballot(w_pre <= t);
+    const int pl = __popcll(mask) - 1;  // last probe of the window starting at or before t
+    const int pre = __builtin_amdgcn_readlane(w_pre, pl);
+    TileRef r;
+    r.gtile = __builtin_amdgcn_readlane(w_tile, pl) + (t - pre);
+    r.first = (t - pre) * kTileVecs;
+    r.len = __builtin_amdgcn_readlane(w_len, pl);
+    return r;
+  };
+
+  auto load_tile = [&](const TileRef &tr, uint4 (&c)[M / 16]) {
+    const uint4 *src =
+        reinterpret_cast<const uint4 *>(P.tile_codes + (size_t)tr.gtile * (kTileVecs * M));
+#pragma unroll
+    for (int u = 0; u < M / 16; ++u) c[u] = src[u * 64 + lane];
+  };
+
+  int cnt = 0;                 // candidates in this wave's buffer
+  int tk = kKeyInvalid;        // this wave's k-th best so far (key, id)
+  long long tkid = 0x7fffffffffffffffll;
+
+  auto compact = [&]() {
+    for (int i = cnt + lane; i < CAP; i += 64) {
+      bkey[i] = kKeyInvalid;
+      bid[i] = 0x7fffffffffffffffll;
+    }
+    wave_sync();
+    bitonic_sort_lds<false>(bkey, bid, CAP, lane, 64);
+    if (cnt >= k) {
+      cnt = k;
+      tk = bkey[k - 1];
+      tkid = bid[k - 1];
+      if (lane == 0) atomicMin(s_thr, tk);
+    }
+  };
+
+  auto process = [&](const TileRef &tr, const uint4 (&c)[M / 16]) {
+    int acc = 0;
+#pragma unroll
+    for (int u = 0; u < M / 16; ++u) {
+      const uint32_t dw[4] = {c[u].x, c[u].y, c[u].z, c[u].w};
+#pragma unroll
+      for (int ww = 0; ww < 4; ++ww) {
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+          const int i = 16 * u + 4 * ww + b;
+          int gi = i / 32, ip = i % 32;
+          if (G::kRem && gi >= G::kFull) { gi = G::kFull; ip = i - 32 * G::kFull; }
+          // result byte0 = x.byte0, byte1 = code byte b, byte2 = x.byte2 or 0, byte3 = 0
+          const uint32_t sel = 0x0c000000u | ((gi >> 1) ? 0x00020000u : 0x000c0000u) |
+                               ((uint32_t)(4 + b) << 8);
+          const uint32_t off = __builtin_amdgcn_perm(dw[ww], x[ip], sel);
+          acc += lds_read_i32(off + (gi & 1) * 128);
+        }
+      }
+    }
+    const int pos = tr.first + lane;
+    const bool valid = pos < tr.len;
+    const int key = valid ? acc : kKeyInvalid;
+    const int thr = min(tk, __atomic_load_n(s_thr, __ATOMIC_RELAXED));
+    const bool pre = valid && key <= thr;
+    if (__ballot(pre)) {  // rare after the first tiles
+      long long id = 0;
+      if (pre) id = P.tile_ids[(size_t)tr.gtile * kTileVecs + lane];
+      const bool pass = pre && cand_less(key, id, tk, tkid);
+      const unsigned long long mask = __ballot(pass);
+      if (mask) {
+        if (pass) {
+          const int off = cnt + __popcll(mask & ((1ull << lane) - 1ull));
+          bkey[off] = key;
+          bid[off] = id;
+        }
+        cnt += __popcll(mask);
+        if (cnt > CAP - 64) compact();
+      }
+    }
+  };
+
+  {
+    int t = t_begin + w;
+    TileRef cur{0, 0, 0};
+    uint4 ca[M / 16];
+    if (t < t_end) {
+      cur = locate(t);
+      load_tile(cur, ca);
+    }
+    while (t < t_end) {
+      const int tn = t + NW;
+      TileRef nxt{0, 0, 0};
+      uint4 cb[M / 16];
+      if (tn < t_end) {
+        nxt = locate(tn);
+        load_tile(nxt, cb);
+      } else {
+#pragma unroll
+        for (int u = 0; u < M / 16; ++u) cb[u] = make_uint4(0, 0, 0, 0);
+      }
+      process(cur, ca);
+#pragma unroll
+      for (int u = 0; u < M / 16; ++u) ca[u] = cb[u];
+      cur = nxt;
+      t = tn;
+    }
+  }
+
+  // ---- merge the waves' candidates: each wave sorts its own, then the block
+  // sorts NW * kp of them in the (now idle) table region ----
+  wave_sync();
+  compact();
+  __syncthreads();
+  const int kp = P.kp;
+  const int n2 = NW * kp;
+  int *mkey = reinterpret_cast<int *>(smem + (size_t)n2 * sizeof(long long));
+  long long *mid = reinterpret_cast<long long *>(smem);
+  for (int i = tid; i < n2; i += NW * 64) {
+    const int ww = i / kp, r = i % kp;
+    const bool ok = r < k;
+    mkey[i] = ok ? buf_key_all[ww * CAP + r] : kKeyInvalid;
+    mid[i] = ok ? buf_id_all[ww * CAP + r] : 0x7fffffffffffffffll;
+  }
+  __syncthreads();
+  bitonic_sort_lds<true>(mkey, mid, n2, tid, NW * 64);
+  for (int r = tid; r < k; r += NW * 64) {
+    const size_t o = ((size_t)q * P.slices + s) * k + r;
+    P.part_key[o] = mkey[r];
+    P.part_id[o] = mid[r];
+  }
+}
+
+template <int M, int NW, int CAP>
+static hipError_t launch_scan_t(const ScanParams &P, int nq, hipStream_t st) {
+  using G = ScanGeom<M>;
+  const size_t lds = (size_t)G::kTables * G::kTableBytes + (size_t)NW * CAP * 12 + 64;
+  static bool attr_done = false;
+  if (!attr_done) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_scan<M, NW, CAP>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    attr_done = true;
+  }
+  hipLaunchKernelGGL((k_scan<M, NW, CAP>), dim3(nq * P.slices), dim3(NW * 64), lds, st, P);
+  return hipGetLastError();
+}
+
+bool scan_supports(int M, int k) {
+  if (k < 1 || k > kMaxK) return false;
+  return M == 16 || M == 32 || M == 48 || M == 64 || M == 96 || M == 128;
+}
+
+hipError_t launch_scan(const Shape &sh, const DevLayout &L, int nq, int probe_stride, int slices,
+                       int k, hipStream_t st) {
+  if (!scan_supports(sh.M, k)) return hipErrorInvalidValue;
+  ScanParams P;
+  P.tile_codes = L.tile_codes;
+  P.tile_ids = L.tile_ids;
+  P.lut = L.lut;
+  P.lutexp = L.lutexp;
+  P.g_base = L.g_base;
+  P.g_len = L.g_len;
+  P.g_prefix = L.g_prefix;
+  P.g_n = L.g_n;
+  P.part_key = L.part_key;
+  P.part_id = L.part_id;
+  P.probe_stride = probe_stride;
+  P.slices = slices;
+  P.k = k;
+  int kp = 16;
+  while (kp < k) kp <<= 1;
+  P.kp = kp;
+#define IVF_SCAN_CASE(MM)                                             \
+  case MM:                                                            \
+    return k <= 64 ? launch_scan_t<MM, 16, 128>(P, nq, st)            \
+                   : launch_scan_t<MM, 8, 256>(P, nq, st);
+  switch (sh.M) {
+    IVF_SCAN_CASE(16)
+    IVF_SCAN_CASE(32)
+    IVF_SCAN_CASE(48)
+    IVF_SCAN_CASE(64)
+    IVF_SCAN_CASE(96)
+    IVF_SCAN_CASE(128)
+  }
+#undef IVF_SCAN_CASE
+  return hipErrorInvalidValue;
+}
+
+// ---------------------------------------------------------------------------
+// Per-query merge of the scan blocks' partial lists; emits the GPU result.
+// One wavefront per query.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(64) void k_merge(const int32_t *__restrict__ part_key,
+                                              const int64_t *__restrict__ part_id, int slices,
+                                              int k, int n2, const int32_t *__restrict__ lutexp,
+                                              int metric_ip, int32_t *res_key, int64_t *res_id,
+                                              int64_t *out_ids, float *out_dists) {
+  __shared__ int mkey[kMaxSlices * kMaxK];
+  __shared__ long long mid[kMaxSlices * kMaxK];
+  const int q = blockIdx.x;
+  const int lane = threadIdx.x;
+  const int n_in = slices * k;
+  for (int i = lane; i < n2; i += 64) {
+    const bool ok = i < n_in;
+    mkey[i] = ok ? part_key[(size_t)q * n_in + i] : kKeyInvalid;
+    mid[i] = ok ? (long long)part_id[(size_t)q * n_in + i] : 0x7fffffffffffffffll;
+  }
+  wave_sync();
+  if (slices > 1) bitonic_sort_lds<false>(mkey, mid, n2, lane, 64);
+  const int e = lutexp[q];
+  for (int r = lane; r < k; r += 64) {
+    const int key = mkey[r];
+    const bool ok = key != kKeyInvalid;
+    if (out_ids) {
+      out_ids[(size_t)q * k + r] = ok ? (int64_t)mid[r] : -1;
+      out_dists[(size_t)q * k + r] =
+          ok ? key_to_dist(key, e, metric_ip) : (metric_ip ? -INFINITY : INFINITY);
+    } else {
+      res_key[(size_t)q * k + r] = key;
+      res_id[(size_t)q * k + r] = ok ? (int64_t)mid[r] : -1;
+    }
+  }
+}
+
+hipError_t launch_merge(const Shape &sh, const DevLayout &L, int nq, int slices, int k,
+                        int64_t *out_ids, float *out_dists, hipStream_t st) {
+  int n2 = 1;
+  while (n2 < slices * k) n2 <<= 1;
+  hipLaunchKernelGGL(k_merge, dim3(nq), dim3(64), 0, st, L.part_key, L.part_id, slices, k, n2,
+                     L.lutexp, sh.metric_ip, L.res_key, L.res_id, out_ids, out_dists);
+  return hipGetLastError();
+}
+
+}  // namespace ivf

@@ -1,0 +1,147 @@
+"""CPU-only tests: the shared library loads and exports the declared C ABI, and
+its host logic (router with everything cold, CPU scan of cold probes, merge,
+counters, argument checks) agrees with the oracle.  No GPU call is made."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from synthdata import SPECS, build_index, mixture_centers, make_queries
+from tests.parity import compare_topk, scale_S
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    import paper_2504_08930_amd as pkg
+    if not os.path.exists(pkg.LIB_PATH):
+        from paper_2504_08930_amd.build import build
+        build()
+    return pkg
+
+
+def test_library_exports_every_declared_symbol(lib):
+    header = open(os.path.join(ROOT, "include", "ivfpq_hot.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(ivf_[a-z_]+)\s*\(", header))
+    assert len(declared) >= 15
+    cdll = lib.load_library()
+    for name in sorted(declared):
+        assert hasattr(cdll, name), f"{name} declared in the header but not exported"
+    assert declared == set(lib.EXPORTS)
+
+
+@pytest.fixture(scope="module", params=["T_L2", "T_IP", "T_IP96"])
+def case(request, lib, oracle):
+    spec = SPECS[request.param]
+    ix = build_index(spec)
+    q, _ = make_queries(spec, mixture_centers(spec))
+    q = q.numpy()
+    index = lib.IvfIndex(ix, spec.nq, spec.nprobe, 64, host_only=True)
+    yield spec, ix, q, index
+    index.close()
+
+
+def test_host_only_search_matches_oracle(case, oracle):
+    spec, ix, q, index = case
+    probe, _, _ = oracle.coarse(ix.metric, ix.centroids, q, spec.nprobe)
+    for k in (1, spec.k, 50):
+        ids, dist = index.search_batch_probes(q, probe, k)
+        ref_i, ref_d = oracle.scan(ix.metric, ix.codebooks, ix.list_offsets, ix.codes, ix.ids,
+                                   q, probe, k + 16)
+        amb = compare_topk(ids, dist, ref_i, ref_d, k, scale_S(ix.metric, q))
+        assert amb <= max(1, q.shape[0] // 20)
+
+
+def test_host_only_identical_codes_tie_by_id(lib, oracle):
+    rng = np.random.default_rng(3)
+
+    class D:
+        pass
+    d = D()
+    d.d, d.nlist, d.m, d.metric = 32, 2, 16, 0
+    d.centroids = rng.standard_normal((2, 32)).astype(np.float32)
+    d.codebooks = rng.standard_normal((16, 256, 2)).astype(np.float32)
+    row = rng.integers(0, 256, 16, dtype=np.uint8)
+    d.codes = np.stack([row, rng.integers(0, 256, 16, dtype=np.uint8), row, row])
+    d.ids = np.array([40, 3, 7, 21], np.int64)
+    d.list_offsets = np.array([0, 4, 4], np.int64)
+    q = rng.standard_normal((1, 32)).astype(np.float32)
+    index = lib.IvfIndex(d, 1, 2, 8, host_only=True)
+    ids, dist = index.search_batch_probes(q, np.array([[0, 1]], np.int32), 6)
+    same = [i for i in ids[0].tolist() if i in (40, 7, 21)]
+    assert same == [7, 21, 40]
+    assert ids[0, 4] == -1 and ids[0, 5] == -1 and np.isinf(dist[0, 4])
+    pos = [ids[0].tolist().index(i) for i in (7, 21, 40)]
+    assert dist[0, pos[0]] == dist[0, pos[1]] == dist[0, pos[2]]     # bit-identical sums
+    index.close()
+
+
+def test_host_only_batch_invariance_and_negative_probes(case, oracle):
+    spec, ix, q, index = case
+    probe, _, _ = oracle.coarse(ix.metric, ix.centroids, q, spec.nprobe)
+    ids_all, d_all = index.search_batch_probes(q, probe, spec.k)
+    ids_one, d_one = index.search_batch_probes(q[5:6], probe[5:6], spec.k)
+    assert np.array_equal(ids_all[5], ids_one[0]) and np.array_equal(d_all[5], d_one[0])
+    # dropping probes with -1 equals searching the shorter list
+    p2 = probe.copy()
+    p2[:, 1::2] = -1
+    a_i, a_d = index.search_batch_probes(q, p2, spec.k)
+    b_i, b_d = index.search_batch_probes(q, np.ascontiguousarray(probe[:, 0::2]), spec.k)
+    assert np.array_equal(a_i, b_i) and np.array_equal(a_d, b_d)
+
+
+def test_host_only_counters(case, oracle):
+    spec, ix, q, index = case
+    index.hit_stats(reset=True)
+    probe, _, _ = oracle.coarse(ix.metric, ix.centroids, q, spec.nprobe)
+    index.search_batch_probes(q, probe, spec.k)
+    st = index.hit_stats(reset=True)
+    ref, _ = oracle.hit_stats(ix.nlist, probe, np.zeros(ix.nlist, np.uint8))
+    assert np.array_equal(st["per_cluster_hits"], ref)
+    assert st["n_queries"] == q.shape[0] and st["mean_hit_rate"] == 0.0
+    assert index.hit_stats()["per_cluster_hits"].sum() == 0
+
+
+def test_argument_errors(case, lib):
+    spec, ix, q, index = case
+    good = np.zeros((q.shape[0], 2), np.int32)
+    good[:, 1] = 1
+    with pytest.raises(lib.IvfError) as e:
+        index.search_batch(q, spec.nprobe, spec.k)          # coarse quantizer needs the device
+    assert e.value.code == -3
+    bad = good.copy()
+    bad[0, 1] = ix.nlist
+    with pytest.raises(lib.IvfError):
+        index.search_batch_probes(q, bad, 5)
+    dup = good.copy()
+    dup[0, 1] = 0
+    with pytest.raises(lib.IvfError):
+        index.search_batch_probes(q, dup, 5)
+    with pytest.raises(lib.IvfError):
+        index.search_batch_probes(q, good, 0)
+    with pytest.raises(lib.IvfError):
+        index.load_partition([0])
+    with pytest.raises(lib.IvfError):
+        index.migrate_clusters([], [0])
+
+
+def test_desc_validation_and_arena_size(lib):
+    cdll = lib.load_library()
+    from paper_2504_08930_amd.binding import IvfIndexDesc
+
+    def desc(**kw):
+        base = dict(d=768, nlist=16384, M=96, nbits=8, metric=1, max_nq=1024, max_nprobe=64,
+                    max_k=10, centroids=0, codebooks=0, list_offsets=0, codes=0, ids=0)
+        base.update(kw)
+        return IvfIndexDesc(**base)
+    ok = desc()
+    nbytes = cdll.ivf_index_arena_bytes(ctypes.byref(ok), 10_000_000 + 64 * 16384, 0)
+    # codes (96 B) + ids (8 B) per resident vector dominate; workspace adds < 1 GiB here
+    assert 11_000_000 * 104 < nbytes < 11_100_000 * 104 + (1 << 30)
+    for bad in (desc(nbits=4), desc(M=24), desc(M=160), desc(d=770), desc(metric=7),
+                desc(max_k=1000), desc(max_nprobe=0), desc(nlist=0)):
+        assert cdll.ivf_index_arena_bytes(ctypes.byref(bad), 1000, 0) == 0
