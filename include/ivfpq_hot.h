@@ -28,8 +28,11 @@
  *  - Results are ordered best first; ties on distance go to the smaller id.
  *    Missing results are id = -1, dist = +INF (L2) / -INF (IP).
  *  - Threading: one searcher thread plus one migrator thread per index.
- *  - Streams are raw hipStream_t values passed as void* (NULL = the index's
- *    own stream).  All streams must have default priority.
+ *  - Streams are raw hipStream_t values passed as void*; NULL is HIP's null
+ *    stream.  All streams must have default priority.  The host-pointer entry
+ *    points run on a stream the index owns.  The batch workspace is shared: a
+ *    call issued on a different stream than the previous asynchronous call
+ *    first waits for that call to finish.
  */
 #ifndef IVFPQ_HOT_H
 #define IVFPQ_HOT_H
@@ -108,7 +111,7 @@ void ivf_index_destroy(ivf_index_t *index);
  * clusters chosen from the access profile are placed on the GPU; the mapping
  * table records cluster id -> resident location).  Re-packs the cluster region
  * from scratch, i.e. a full refresh.  cluster_ids: HOST, n entries, distinct,
- * each in [0, nlist).  Copies run on `stream` (NULL = index stream); the call
+ * each in [0, nlist).  Copies run on `stream`; the call
  * returns after the copies have completed and the mapping table is published.
  * IVF_ENOMEM if the cluster region cannot hold them (nothing changes).
  * Must not run concurrently with a search or a migration.

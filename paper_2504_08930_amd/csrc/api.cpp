@@ -157,6 +157,11 @@ struct ivf_index {
   int32_t *h_probe = nullptr;
   unsigned long long *h_stats = nullptr;
 
+  // stream of the last asynchronous search: the batch workspace is shared, so
+  // a call on another stream first waits for it
+  bool async_pending = false;
+  hipStream_t async_stream = nullptr;
+
   int32_t tune_slices = 0;
   int32_t timing = 0;
   std::vector<TimingRec> trecs;
@@ -530,7 +535,7 @@ extern "C" int ivf_index_load_partition(ivf_index_t *ix, const int32_t *cluster_
   std::vector<char> seen(ix->sh.nlist, 0);
   int rc = check_cluster_list(ix, cluster_ids, n, "load_partition", seen);
   if (rc != IVF_OK) return rc;
-  hipStream_t st = stream ? (hipStream_t)stream : ix->own_stream;
+  hipStream_t st = (hipStream_t)stream;
 
   std::vector<int32_t> clusters(cluster_ids, cluster_ids + n);
   std::sort(clusters.begin(), clusters.end());
@@ -647,7 +652,7 @@ extern "C" int ivf_migrate_clusters(ivf_index_t *ix, const int32_t *evict, int32
   for (int32_t i = 0; i < n_admit; ++i)
     if (ix->h_map[admit[i]] >= 0)
       return fail(IVF_EINVAL, "admit: cluster %d is already resident", admit[i]);
-  hipStream_t st = side_stream ? (hipStream_t)side_stream : ix->own_stream;
+  hipStream_t st = (hipStream_t)side_stream;
 
   reclaim(ix);
   const int target = (ix->versions.back().buf + 1) % 3;
@@ -919,6 +924,10 @@ static int search_device(ivf_index *ix, const SearchArgs &a) {
   bool timing;
   {
     std::lock_guard<std::mutex> lk(ix->mu);
+    if (ix->async_pending && ix->async_stream != st) {
+      HIP_TRY(hipStreamSynchronize(ix->async_stream));
+      ix->async_pending = false;
+    }
     int rc = publish_if_done_locked(ix, false);
     if (rc < 0) return rc;
     reclaim(ix);
@@ -935,6 +944,8 @@ static int search_device(ivf_index *ix, const SearchArgs &a) {
     for (auto &v : ix->versions) {
       if (v.id != ver_id) continue;
       if (async_tail) {
+        ix->async_pending = true;
+        ix->async_stream = st;
         hipEvent_t e = get_event(ix);
         if (e && hipEventRecord(e, st) == hipSuccess) v.events.push_back(e);
         else (void)hipStreamSynchronize(st);
@@ -1125,7 +1136,7 @@ extern "C" int ivf_search_batch_dev(ivf_index_t *ix, const float *queries, int64
   a.out_ids = out_ids;
   a.out_dists = out_dists;
   a.out_device = true;
-  a.st = stream ? (hipStream_t)stream : ix->own_stream;
+  a.st = (hipStream_t)stream;
   return search_device(ix, a);
 }
 
@@ -1138,10 +1149,22 @@ extern "C" int ivf_coarse_probe_dev(ivf_index_t *ix, const float *queries, int64
   if (!queries || !out_probe) return fail(IVF_EINVAL, "NULL buffer");
   if (nq > ix->desc.max_nq) return fail(IVF_EINVAL, "nq exceeds max_nq");
   if (nprobe > kMaxNprobe) return fail(IVF_EINVAL, "nprobe exceeds %d", kMaxNprobe);
-  hipStream_t st = stream ? (hipStream_t)stream : ix->own_stream;
+  hipStream_t st = (hipStream_t)stream;
+  {
+    std::lock_guard<std::mutex> lk(ix->mu);
+    if (ix->async_pending && ix->async_stream != st) {
+      HIP_TRY(hipStreamSynchronize(ix->async_stream));
+      ix->async_pending = false;
+    }
+  }
   HIP_TRY(launch_coarse_gemm(ix->sh, queries, (int)nq, ix->L.centroids, ix->L.cent_norm,
                              ix->L.scores, st));
   HIP_TRY(launch_coarse_select(ix->sh, ix->L.scores, (int)nq, nprobe, nprobe, out_probe, st));
+  {
+    std::lock_guard<std::mutex> lk(ix->mu);
+    ix->async_pending = true;
+    ix->async_stream = st;
+  }
   return IVF_OK;
 }
 

@@ -423,7 +423,7 @@ __global__ __launch_bounds__(NW * 64) void k_scan(ScanParams P) {
       win_end = gpre[last];
     }
     const unsigned long long mask = __ballot(w_pre <= t);
-    const int pl = __popcll(mask) - 1;  // last probe of the window starting at or before t
+    const int pl = max(__popcll(mask) - 1, 0);  // last probe of the window starting at or before t
     const int pre = __builtin_amdgcn_readlane(w_pre, pl);
     TileRef r;
     r.gtile = __builtin_amdgcn_readlane(w_tile, pl) + (t - pre);

@@ -1,0 +1,295 @@
+"""GPU parity tests: the HIP path, called through the C ABI, against the CPU
+oracle on the same seeded inputs.  Ids bit-exact except ties within tolerance;
+distances within 1e-4 * max(|d|, S) (tests/parity.py)."""
+import os
+
+import numpy as np
+import pytest
+
+from synthdata import SPECS, build_index, mixture_centers, make_queries
+from tests.parity import compare_probes, compare_topk, scale_S
+
+pytestmark = pytest.mark.gpu
+
+
+def _say(msg):
+    print(f"[gpu-test] {msg}", flush=True)
+
+
+@pytest.fixture(scope="module")
+def pkg():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    import paper_2504_08930_amd as p
+    assert os.path.exists(p.LIB_PATH), "build the library before running GPU tests"
+    p.load_library()
+    return p
+
+
+_CACHE = {}
+
+
+def _case(name, device="cuda"):
+    if name not in _CACHE:
+        spec = SPECS[name]
+        _say(f"building index {name} on {device}")
+        ix = build_index(spec, device=device)
+        import torch
+        centers = mixture_centers(spec, torch.device(device))
+        q, _ = make_queries(spec, centers)
+        calib, _ = make_queries(spec, centers, nq=max(spec.nq, 256), seed=spec.seed_calib)
+        _CACHE[name] = (spec, ix, q.cpu().numpy(), calib.cpu().numpy())
+    return _CACHE[name]
+
+
+def hottest(index, calib_q, nprobe, frac, nlist):
+    """Hottest round(frac * nlist) clusters by probe count over calibration
+    queries (ties to the smaller id)."""
+    index.hit_stats(reset=True)
+    import torch
+    for s in range(0, calib_q.shape[0], index.max_nq):
+        qd = torch.from_numpy(calib_q[s:s + index.max_nq]).cuda()
+        index.search_batch_dev(qd, nprobe, 1)
+    torch.cuda.synchronize()
+    hits = index.hit_stats(reset=True)["per_cluster_hits"].astype(np.int64)
+    order = np.lexsort((np.arange(nlist), -hits))
+    return np.sort(order[: int(round(frac * nlist))]).astype(np.int32)
+
+
+def _oracle_ref(oracle, ix, q, nprobe, k):
+    probe, pscore, gap = oracle.coarse(ix.metric, ix.centroids, q, min(nprobe + 8, ix.nlist))
+    return probe, pscore
+
+
+def _check_search(oracle, ix, q, nprobe, k, got_ids, got_d, got_probe=None):
+    """End-to-end check with the coarse near-tie rule: if the GPU's probe set
+    differs from the oracle's only by boundary ties, ids are compared against
+    the oracle run on the GPU's own probe list."""
+    S = scale_S(ix.metric, q)
+    npb = min(nprobe, ix.nlist)
+    ext = min(npb + 8, ix.nlist)
+    probe_ext, score_ext, _ = oracle.coarse(ix.metric, ix.centroids, q, ext)
+    use_probe = np.ascontiguousarray(probe_ext[:, :npb])
+    n_coarse = 0
+    if got_probe is not None:
+        n_coarse = compare_probes(got_probe[:, :npb], probe_ext, score_ext, npb, S)
+        use_probe = np.ascontiguousarray(got_probe[:, :npb])
+    ref_i, ref_d = oracle.scan(ix.metric, ix.codebooks, ix.list_offsets, ix.codes, ix.ids, q,
+                               use_probe, k + 16)
+    n_amb = compare_topk(got_ids, got_d, ref_i, ref_d, k, S)
+    return n_coarse, n_amb
+
+
+@pytest.mark.parametrize("name", ["T_L2", "T_IP", "T_IP96"])
+def test_small_end_to_end_all_resident(pkg, oracle, name):
+    import torch
+    spec, ix, q, calib = _case(name)
+    index = pkg.IvfIndex(ix, max_nq=256, max_nprobe=ix.nlist, max_k=128)
+    index.load_partition(np.arange(ix.nlist, dtype=np.int32))
+    assert index.resident_info() == (ix.nlist, ix.n)
+    qd = torch.from_numpy(q).cuda()
+    for nprobe, k in ((spec.nprobe, spec.k), (1, 1), (spec.nprobe, 64), (ix.nlist + 5, 100)):
+        _say(f"{name} nprobe={nprobe} k={k}")
+        probe = index.coarse_probe_dev(qd, min(nprobe, ix.nlist)).cpu().numpy()
+        ids_d, dist_d = index.search_batch_dev(qd, nprobe, k)
+        torch.cuda.synchronize()
+        ids_h, dist_h = index.search_batch(q, nprobe, k)
+        assert np.array_equal(ids_d.cpu().numpy(), ids_h)
+        assert np.array_equal(dist_d.cpu().numpy(), dist_h)
+        n_coarse, n_amb = _check_search(oracle, ix, q, nprobe, k, ids_h, dist_h, probe)
+        assert n_coarse <= 1 and n_amb <= max(1, q.shape[0] // 20)
+    index.close()
+
+
+@pytest.mark.parametrize("name", ["T_L2", "T_IP96"])
+def test_forced_probes_and_scan_slices(pkg, oracle, name):
+    spec, ix, q, calib = _case(name)
+    index = pkg.IvfIndex(ix, max_nq=256, max_nprobe=ix.nlist, max_k=128)
+    index.load_partition(np.arange(ix.nlist, dtype=np.int32))
+    probe, _, _ = oracle.coarse(ix.metric, ix.centroids, q, spec.nprobe)
+    ref_i, ref_d = oracle.scan(ix.metric, ix.codebooks, ix.list_offsets, ix.codes, ix.ids, q,
+                               probe, spec.k + 16)
+    base = None
+    for slices in (0, 1, 3, 8):
+        _say(f"{name} slices={slices}")
+        index.set_tuning(scan_slices=slices)
+        ids, dist = index.search_batch_probes(q, probe, spec.k)
+        compare_topk(ids, dist, ref_i, ref_d, spec.k, scale_S(ix.metric, q))
+        if base is None:
+            base = (ids, dist)
+        assert np.array_equal(ids, base[0]) and np.array_equal(dist, base[1])
+    index.close()
+
+
+@pytest.mark.parametrize("name", ["T_L2", "T_IP", "T_IP96"])
+def test_residency_invariance_and_counters(pkg, oracle, name):
+    """Results must not depend on which clusters are GPU-resident (Section 4.3.2:
+    the hybrid result is the merge of the CPU and GPU partial results); with the
+    fixed-point table both sides produce identical sums, so equality is exact."""
+    spec, ix, q, calib = _case(name)
+    index = pkg.IvfIndex(ix, max_nq=256, max_nprobe=ix.nlist, max_k=128)
+    rng = np.random.default_rng(11)
+    base = None
+    full = np.arange(ix.nlist, dtype=np.int32)
+    index.load_partition(full)
+    hot30 = hottest(index, calib, spec.nprobe, 0.3, ix.nlist)
+    sets = [full, np.zeros(0, np.int32), hot30,
+            np.sort(rng.choice(ix.nlist, ix.nlist // 2, replace=False)).astype(np.int32)]
+    probe_ref, _, _ = oracle.coarse(ix.metric, ix.centroids, q, spec.nprobe)
+    for rs in sets:
+        _say(f"{name} resident={len(rs)}/{ix.nlist}")
+        index.load_partition(rs)
+        index.hit_stats(reset=True)
+        ids, dist = index.search_batch(q, spec.nprobe, spec.k)
+        if base is None:
+            base = (ids, dist)
+            _check_search(oracle, ix, q, spec.nprobe, spec.k, ids, dist)
+        assert np.array_equal(ids, base[0]), "ids depend on residency"
+        assert np.array_equal(dist, base[1]), "distances depend on residency"
+        st = index.hit_stats(reset=True)
+        mask = np.zeros(ix.nlist, np.uint8)
+        mask[rs] = 1
+        import torch
+        got_probe = index.coarse_probe_dev(torch.from_numpy(q).cuda(), spec.nprobe).cpu().numpy()
+        ref_hits, ref_rate = oracle.hit_stats(ix.nlist, got_probe, mask)
+        assert np.array_equal(st["per_cluster_hits"], ref_hits)
+        assert st["per_cluster_hits"].sum() == q.shape[0] * spec.nprobe
+        assert st["n_queries"] == q.shape[0]
+        assert abs(st["mean_hit_rate"] - ref_rate.mean()) < 1e-9
+        assert abs(st["min_hit_rate"] - ref_rate.min()) < 1e-6
+    assert index.hit_stats()["per_cluster_hits"].sum() == 0
+    index.close()
+
+
+def test_migration_keeps_results(pkg, oracle):
+    """Evict / admit while searching (Section 4.3.3): results identical before,
+    during and after; clusters in transit are served by the CPU path."""
+    import torch
+    spec, ix, q, calib = _case("T_IP96")
+    index = pkg.IvfIndex(ix, max_nq=256, max_nprobe=ix.nlist, max_k=128)
+    rng = np.random.default_rng(5)
+    perm = rng.permutation(ix.nlist).astype(np.int32)
+    a, b = np.sort(perm[: ix.nlist // 3]), np.sort(perm[ix.nlist // 3: 2 * ix.nlist // 3])
+    index.load_partition(a)
+    ref = index.search_batch(q, spec.nprobe, spec.k)
+    side = torch.cuda.Stream()
+    lens = np.diff(ix.list_offsets)
+    total = 0
+    resident = set(a.tolist())
+    for step in range(4):
+        evict, admit = (a[: len(a) // 2], b[: len(b) // 2]) if step % 2 == 0 else \
+                       (b[: len(b) // 2], a[: len(a) // 2])
+        _say(f"migration step {step}: evict {len(evict)} admit {len(admit)}")
+        index.migrate_clusters(evict, admit, side_stream=side)
+        total += int(lens[admit].sum()) * (ix.m + 8)
+        during = index.search_batch(q, spec.nprobe, spec.k)
+        assert np.array_equal(during[0], ref[0]) and np.array_equal(during[1], ref[1])
+        if index.migrate_poll()[0]:          # still in flight: a second one must be refused
+            with pytest.raises(pkg.IvfError) as e:
+                index.migrate_clusters([], [int(perm[-1])], side_stream=side)
+            assert e.value.code == -4
+        in_flight, nbytes = index.migrate_poll(wait=True)
+        assert not in_flight and nbytes == total
+        resident = (resident - set(evict.tolist())) | set(admit.tolist())
+        after = index.search_batch(q, spec.nprobe, spec.k)
+        assert np.array_equal(after[0], ref[0]) and np.array_equal(after[1], ref[1])
+        nc, nv = index.resident_info()
+        assert nc == len(resident) and nv == int(lens[sorted(resident)].sum())
+        mask = np.zeros(ix.nlist, np.uint8)
+        mask[sorted(resident)] = 1
+        index.hit_stats(reset=True)
+        index.search_batch(q, spec.nprobe, spec.k)
+        got_probe = index.coarse_probe_dev(torch.from_numpy(q).cuda(), spec.nprobe).cpu().numpy()
+        _, ref_rate = oracle.hit_stats(ix.nlist, got_probe, mask)
+        assert abs(index.hit_stats()["mean_hit_rate"] - ref_rate.mean()) < 1e-9
+    # errors leave the state unchanged
+    with pytest.raises(pkg.IvfError):
+        index.migrate_clusters([int(b[-1])], [])          # not resident
+    with pytest.raises(pkg.IvfError):
+        index.migrate_clusters([], [int(a[-1])])          # already resident
+    index.close()
+
+
+def test_cluster_region_too_small(pkg):
+    spec, ix, q, calib = _case("T_IP")
+    index = pkg.IvfIndex(ix, max_nq=64, max_nprobe=16, max_k=16, resident_vectors=ix.n // 4)
+    with pytest.raises(pkg.IvfError) as e:
+        index.load_partition(np.arange(ix.nlist, dtype=np.int32))
+    assert e.value.code == -2
+    ids, _ = index.search_batch(q, spec.nprobe, spec.k)      # still works, all cold
+    assert (ids >= 0).all()
+    index.close()
+
+
+def test_edge_shapes(pkg, oracle):
+    import torch
+    spec, ix, q, calib = _case("T_L2")
+    index = pkg.IvfIndex(ix, max_nq=256, max_nprobe=ix.nlist, max_k=128)
+    index.load_partition(np.arange(ix.nlist, dtype=np.int32))
+    # nq = 0 is a no-op
+    ids, dist = index.search_batch(np.zeros((0, ix.d), np.float32), 4, 5)
+    assert ids.shape == (0, 5)
+    # one query; batch invariance
+    one = index.search_batch(q[3:4], spec.nprobe, spec.k)
+    allq = index.search_batch(q, spec.nprobe, spec.k)
+    assert np.array_equal(one[0][0], allq[0][3]) and np.array_equal(one[1][0], allq[1][3])
+    # k-prefix property and determinism
+    k100 = index.search_batch(q, spec.nprobe, 100)
+    assert np.array_equal(k100[0][:, :spec.k], allq[0])
+    again = index.search_batch(q, spec.nprobe, 100)
+    assert np.array_equal(again[0], k100[0]) and np.array_equal(again[1], k100[1])
+    # probing only empty lists gives padding
+    lens = np.diff(ix.list_offsets)
+    empty = np.nonzero(lens == 0)[0]
+    if len(empty):
+        pr = np.full((q.shape[0], 1), empty[0], np.int32)
+        ids, dist = index.search_batch_probes(q, pr, 3)
+        assert (ids == -1).all() and np.isinf(dist).all()
+    # argument errors
+    for bad in (dict(nprobe=0, k=5), dict(nprobe=4, k=0), dict(nprobe=4, k=129)):
+        with pytest.raises(pkg.IvfError):
+            index.search_batch(q, bad["nprobe"], bad["k"])
+    with pytest.raises(pkg.IvfError):
+        index.search_batch(np.zeros((257, ix.d), np.float32), 4, 5)
+    index.close()
+
+
+def test_c1_config(pkg, oracle):
+    """Tiny config of the benchmark list: N=100k, D=128, nlist=1024, M=16, L2,
+    nq=100, nprobe=16, k=10, everything resident."""
+    import torch
+    spec, ix, q, calib = _case("C1")
+    index = pkg.IvfIndex(ix, max_nq=128, max_nprobe=64, max_k=16)
+    index.load_partition(np.arange(ix.nlist, dtype=np.int32))
+    qd = torch.from_numpy(q).cuda()
+    probe = index.coarse_probe_dev(qd, spec.nprobe).cpu().numpy()
+    ids, dist = index.search_batch(q, spec.nprobe, spec.k)
+    n_coarse, n_amb = _check_search(oracle, ix, q, spec.nprobe, spec.k, ids, dist, probe)
+    _say(f"C1: coarse-ambiguous {n_coarse}, id-ambiguous {n_amb} of {q.shape[0]}")
+    assert n_coarse <= 1 and n_amb <= 2
+    index.close()
+
+
+def test_c2_config_hybrid(pkg, oracle):
+    """1M x 768 inner-product config: hottest 30 % of clusters resident, the rest
+    scanned on the CPU; oracle checked on a sample of the 1000 queries."""
+    import torch
+    spec, ix, q, calib = _case("C2")
+    index = pkg.IvfIndex(ix, max_nq=1024, max_nprobe=64, max_k=16)
+    index.load_partition(np.arange(ix.nlist, dtype=np.int32))
+    hot = hottest(index, calib, spec.nprobe, spec.resident_frac, ix.nlist)
+    full = index.search_batch(q, spec.nprobe, spec.k)
+    index.load_partition(hot)
+    qd = torch.from_numpy(q).cuda()
+    probe = index.coarse_probe_dev(qd, spec.nprobe).cpu().numpy()
+    hyb = index.search_batch(q, spec.nprobe, spec.k)
+    st = index.hit_stats()
+    _say(f"C2: resident {len(hot)} clusters, mean hit rate {st['mean_hit_rate']:.3f}, "
+         f"min {st['min_hit_rate']:.3f}")
+    assert np.array_equal(full[0], hyb[0]) and np.array_equal(full[1], hyb[1])
+    sel = np.arange(0, q.shape[0], 5)
+    n_coarse, n_amb = _check_search(oracle, ix, q[sel], spec.nprobe, spec.k, hyb[0][sel],
+                                    hyb[1][sel], probe[sel])
+    _say(f"C2: coarse-ambiguous {n_coarse}, id-ambiguous {n_amb} of {len(sel)}")
+    assert n_coarse <= 2 and n_amb <= 4
+    index.close()
