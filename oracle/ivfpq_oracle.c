@@ -31,6 +31,10 @@
 #include <stdlib.h>
 #include <string.h>
 
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
 #define ORACLE_L2 0
 #define ORACLE_IP 1
 
@@ -202,4 +206,13 @@ int oracle_hit_stats(int nlist, int64_t nq, int nprobe, const int32_t *probe,
         per_query_rate[qi] = total ? (double)hit / (double)total : 0.0;
     }
     return 0;
+}
+
+/* Threads the query loops run on (OpenMP over queries only). */
+int oracle_num_threads(void) {
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
 }

@@ -42,6 +42,8 @@ def _load():
         lib.oracle_scan.restype = ctypes.c_int
         lib.oracle_hit_stats.argtypes = [ctypes.c_int, ctypes.c_int64, ctypes.c_int, P, P, P, P]
         lib.oracle_hit_stats.restype = ctypes.c_int
+        lib.oracle_num_threads.argtypes = []
+        lib.oracle_num_threads.restype = ctypes.c_int
         _lib = lib
     return _lib
 
@@ -118,3 +120,7 @@ def hit_stats(nlist, probe, resident_mask):
     if rc != 0:
         raise RuntimeError(f"oracle_hit_stats failed: {rc}")
     return per_cluster, rate
+
+
+def num_threads() -> int:
+    return int(_load().oracle_num_threads())
