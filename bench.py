@@ -27,6 +27,11 @@ if ROOT not in sys.path:
 
 METRIC = "search queries/sec at fixed nprobe,k; ADC-scan HBM GB/s as % of peak"
 HBM_PEAK_GBS = 8000.0
+# HBM-side bytes per k_scan launch from the rocprofv3 --pmc runs (FETCH_SIZE + WRITE_SIZE, scaled
+# by the same counters on a plain copy kernel); valid for exactly this workload and launch shape.
+MEASURED_TRAFFIC = {
+    ("C3", 1024, 1.0): (4.057e9 + 0.164e6, "profiles/c3_nq1024_scan_hbm_traffic.md"),
+}
 
 
 def log(msg):
@@ -45,6 +50,8 @@ def main():
                     help="fraction of clusters (hottest first) kept on the GPU")
     ap.add_argument("--oracle-sample", type=int, default=256)
     ap.add_argument("--no-oracle", action="store_true")
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="also launch one 1 GiB streaming copy kernel (counter calibration)")
     ap.add_argument("--no-timing", action="store_true",
                     help="do not record per-kernel HIP events in the timed region")
     args = ap.parse_args()
@@ -118,6 +125,15 @@ def main():
     hs = index.hit_stats()
     index.set_tuning(scan_slices=args.slices, timing=False)
 
+    if args.calib_copy:
+        from paper_2504_08930_amd.binding import ivf_calib_copy
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)      # 1 GiB
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        ivf_calib_copy(src, dst, stream)
+        torch.cuda.synchronize()
+        del src, dst
+
     ms_per_step = 1e3 * elapsed / args.steps
     qps = nq * args.steps / elapsed
     roofline = None
@@ -130,6 +146,9 @@ def main():
                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
                     "traffic": None, "bytes_per_launch": int(bytes_per_launch),
                     "avg_launch_ms": round(scan_ms, 4)}
+        key = (spec.name, nq, round(resident_frac, 4))
+        if key in MEASURED_TRAFFIC and args.slices == 0:
+            roofline["traffic"], roofline["traffic_source"] = MEASURED_TRAFFIC[key]
     stage_ms = {k: round(v / max(1, st["launches"][k]), 4) for k, v in st["ms"].items()}
 
     cpu_baseline = None

@@ -226,6 +226,13 @@ enum {
 int ivf_stage_times(ivf_index_t *index, double *ms, uint64_t *launches, uint64_t *scan_bytes,
                     int reset);
 
+/*
+ * Instrumentation aid: a plain streaming copy kernel (reads `bytes`, writes
+ * `bytes`; DEVICE pointers, 16-byte aligned, bytes a multiple of 16) whose
+ * known traffic calibrates hardware byte counters.  Asynchronous on `stream`.
+ */
+int ivf_calib_copy(const void *src, void *dst, size_t bytes, void *stream);
+
 /* Message for the last error returned on this thread ("" if none). */
 const char *ivf_last_error(void);
 

@@ -22,7 +22,7 @@ EXPORTS = (
     "ivf_index_load_partition", "ivf_search_batch", "ivf_search_batch_dev",
     "ivf_coarse_probe_dev", "ivf_search_batch_probes", "ivf_hit_stats",
     "ivf_migrate_clusters", "ivf_migrate_poll", "ivf_resident_info",
-    "ivf_set_tuning", "ivf_stage_times", "ivf_last_error",
+    "ivf_set_tuning", "ivf_stage_times", "ivf_calib_copy", "ivf_last_error",
 )
 
 
@@ -72,6 +72,7 @@ def load_library():
     lib.ivf_resident_info.argtypes = [P, P, P]
     lib.ivf_set_tuning.argtypes = [P, I32, I32]
     lib.ivf_stage_times.argtypes = [P, P, P, P, ctypes.c_int]
+    lib.ivf_calib_copy.argtypes = [P, P, SZ, P]
     lib.ivf_last_error.argtypes = []
     lib.ivf_last_error.restype = ctypes.c_char_p
     for name in EXPORTS:
@@ -85,6 +86,15 @@ def _check(rc):
     if rc < 0:
         raise IvfError(rc, load_library().ivf_last_error().decode())
     return rc
+
+
+def ivf_calib_copy(src, dst, stream=None):
+    """Streaming copy of torch tensor src into dst (same byte size, multiple of 16)."""
+    nbytes = src.numel() * src.element_size()
+    assert nbytes == dst.numel() * dst.element_size()
+    st = None if stream is None else ctypes.c_void_p(stream.cuda_stream)
+    _check(load_library().ivf_calib_copy(ctypes.c_void_p(src.data_ptr()),
+                                         ctypes.c_void_p(dst.data_ptr()), nbytes, st))
 
 
 def _np_ptr(a):

@@ -1203,3 +1203,9 @@ extern "C" int ivf_search_batch_probes(ivf_index_t *ix, const float *queries, in
   a.st = ix->own_stream;
   return search_device(ix, a);
 }
+
+extern "C" int ivf_calib_copy(const void *src, void *dst, size_t bytes, void *stream) {
+  if (!src || !dst || bytes % 16 != 0) return fail(IVF_EINVAL, "calib copy: bad arguments");
+  HIP_TRY(launch_calib_copy(src, dst, bytes, (hipStream_t)stream));
+  return IVF_OK;
+}

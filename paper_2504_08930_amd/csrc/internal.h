@@ -72,6 +72,8 @@ struct Shape {
 // HIP error of the launch. ----
 hipError_t launch_fill_u32(uint32_t *p, size_t n, uint32_t v, hipStream_t st);
 
+hipError_t launch_calib_copy(const void *src, void *dst, size_t bytes, hipStream_t st);
+
 hipError_t launch_cent_norms(const float *cent, int nlist, int d, float *out, hipStream_t st);
 
 hipError_t launch_coarse_gemm(const Shape &sh, const float *q, int nq, const float *cent,

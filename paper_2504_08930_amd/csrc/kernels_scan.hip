@@ -92,6 +92,22 @@ hipError_t launch_fill_u32(uint32_t *p, size_t n, uint32_t v, hipStream_t st) {
   return hipGetLastError();
 }
 
+// Plain streaming copy of known size: the reference against which hardware
+// byte counters are calibrated.
+__global__ void k_calib_copy(const uint4 *__restrict__ src, uint4 *__restrict__ dst, size_t n) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const size_t step = (size_t)gridDim.x * blockDim.x;
+  for (; i < n; i += step) dst[i] = src[i];
+}
+
+hipError_t launch_calib_copy(const void *src, void *dst, size_t bytes, hipStream_t st) {
+  const size_t n = bytes / 16;
+  if (n == 0) return hipSuccess;
+  hipLaunchKernelGGL(k_calib_copy, dim3(256 * 8), dim3(256), 0, st, (const uint4 *)src,
+                     (uint4 *)dst, n);
+  return hipGetLastError();
+}
+
 // ---------------------------------------------------------------------------
 // Routing (Section 4.3.1): each probe is looked up in the mapping table;
 // resident probes form the query's GPU work list, the others its cold list.
