@@ -151,7 +151,7 @@ struct ivf_index {
   uint64_t hc_probes = 0, hc_queries = 0;
 
   // pinned host buffers
-  int32_t *h_ncold = nullptr, *h_cold = nullptr, *h_reskey = nullptr, *h_lutexp = nullptr;
+  int32_t *h_ncold = nullptr, *h_cold = nullptr, *h_reskey = nullptr, *h_lutmax = nullptr;
   int64_t *h_resid = nullptr, *h_outids = nullptr;
   float *h_outd = nullptr, *h_queries = nullptr;
   int32_t *h_probe = nullptr;
@@ -230,8 +230,9 @@ static size_t plan_layout(const ivf_index_desc_t &d, int64_t resident_vectors, s
   t.cold = (int32_t *)take(nq * np * 4);
   t.n_cold = (int32_t *)take(nq * 4);
   t.lut = (float *)take(nq * 256 * M * 4);
-  t.lutmax = (uint32_t *)take(nq * M * 4);
-  t.lutexp = (int32_t *)take(nq * 4);
+  t.lutpart = (uint32_t *)take(nq * kLutMaxParts * 4);
+  t.lutmax = (uint32_t *)take(nq * 4);
+  t.q_vecs = (int32_t *)take(nq * 4);
   t.part_key = (int32_t *)take(nq * kMaxSlices * k * 4);
   t.part_id = (int64_t *)take(nq * kMaxSlices * k * 8);
   t.res_key = (int32_t *)take(nq * k * 4);
@@ -263,7 +264,7 @@ static hipError_t pinned_alloc(T **p, size_t count) {
 }
 
 static void free_host_buffers(ivf_index *ix) {
-  void *ptrs[] = {ix->h_ncold, ix->h_cold,   ix->h_reskey,  ix->h_lutexp, ix->h_resid,
+  void *ptrs[] = {ix->h_ncold, ix->h_cold,   ix->h_reskey,  ix->h_lutmax, ix->h_resid,
                   ix->h_outids, ix->h_outd,  ix->h_queries, ix->h_probe,  ix->h_stats};
   for (void *p : ptrs)
     if (p) (void)hipHostFree(p);
@@ -360,7 +361,7 @@ extern "C" int ivf_index_create(const ivf_index_desc_t *desc, void *dev_arena, s
       (e = pinned_alloc(&ix->h_cold, nq * np)) != hipSuccess ||
       (e = pinned_alloc(&ix->h_reskey, nq * k)) != hipSuccess ||
       (e = pinned_alloc(&ix->h_resid, nq * k)) != hipSuccess ||
-      (e = pinned_alloc(&ix->h_lutexp, nq)) != hipSuccess ||
+      (e = pinned_alloc(&ix->h_lutmax, nq)) != hipSuccess ||
       (e = pinned_alloc(&ix->h_outids, nq * k)) != hipSuccess ||
       (e = pinned_alloc(&ix->h_outd, nq * k)) != hipSuccess ||
       (e = pinned_alloc(&ix->h_queries, nq * (size_t)desc->d)) != hipSuccess ||
@@ -864,7 +865,8 @@ static void emit_results(const ivf_index *ix, const HostCand *c, int k, int e, i
 
 static int pick_slices(const ivf_index *ix, int64_t nq) {
   if (ix->tune_slices > 0) return ix->tune_slices;
-  int s = (int)((768 + nq - 1) / nq);
+  // one block per query fills the chip from 256 queries up; below that, split
+  int s = (int)((256 + nq - 1) / nq);
   if (s < 1) s = 1;
   if (s > kMaxSlices) s = kMaxSlices;
   return s;
@@ -993,13 +995,13 @@ static int search_device(ivf_index *ix, const SearchArgs &a) {
   // ---- routing ----
   S_TRY(mark(IVF_STAGE_ROUTE));
   S_TRY(launch_route(L.probe, nq, np, np, L.clus_tile[buf], L.clus_len, sh.M, L.g_base, L.g_len,
-                     L.g_prefix, L.g_n, L.cold, L.n_cold, L.hits, L.qstats, 1, st));
+                     L.g_prefix, L.g_n, L.cold, L.n_cold, L.q_vecs, L.hits, L.qstats, 1, st));
   S_TRY(mark(IVF_STAGE_LUT));
   const int slices = pick_slices(ix, nq);
   const bool final_on_gpu = all_resident;
   if (any_resident) {
     // ---- stage 2: lookup tables; stage 3: scan + top-k ----
-    S_TRY(launch_lut(sh, dq, nq, L.cbT, L.lut, L.lutmax, L.lutexp, st));
+    S_TRY(launch_lut(sh, dq, nq, L.cbT, L.lut, L.lutpart, L.lutmax, st));
     S_TRY(mark(IVF_STAGE_SCAN));
     S_TRY(launch_scan(sh, L, nq, np, slices, k, st));
     S_TRY(mark(IVF_STAGE_MERGE));
@@ -1042,7 +1044,7 @@ static int search_device(ivf_index *ix, const SearchArgs &a) {
   if (any_resident) {
     S_TRY(hipMemcpyAsync(ix->h_reskey, L.res_key, (size_t)nq * k * 4, hipMemcpyDeviceToHost, st));
     S_TRY(hipMemcpyAsync(ix->h_resid, L.res_id, (size_t)nq * k * 8, hipMemcpyDeviceToHost, st));
-    S_TRY(hipMemcpyAsync(ix->h_lutexp, L.lutexp, (size_t)nq * 4, hipMemcpyDeviceToHost, st));
+    S_TRY(hipMemcpyAsync(ix->h_lutmax, L.lutmax, (size_t)nq * 4, hipMemcpyDeviceToHost, st));
   }
   S_TRY(hipStreamSynchronize(st));
   release(false);
@@ -1055,7 +1057,12 @@ static int search_device(ivf_index *ix, const SearchArgs &a) {
       if (any_resident) gpu[r] = HostCand{ix->h_reskey[q * k + r], ix->h_resid[q * k + r]};
       else gpu[r] = HostCand{kKeyInvalid, -1};
     }
-    int e = any_resident ? ix->h_lutexp[q] : 0;
+    int e = 0;
+    if (any_resident) {
+      float mx;
+      memcpy(&mx, &ix->h_lutmax[q], 4);
+      e = lut_exponent(mx, view.M);
+    }
     const int nc = ix->h_ncold[q];
     const HostCand *res = gpu.data();
     if (nc > 0 || !any_resident) {

@@ -49,18 +49,16 @@ void parallel_for(int64_t n, const std::function<void(int64_t)> &fn) {
 int cpu_build_lut(const HostIndexView &ix, const float *q, int32_t *lut) {
   const int M = ix.M, dsub = ix.dsub;
   std::vector<float> f((size_t)M * 256);
-  double B = 0.0;
+  float mx = 0.0f;
   for (int m = 0; m < M; ++m) {
-    float mx = 0.0f;
     for (int j = 0; j < 256; ++j) {
       float v = lut_entry(ix.metric_ip, q + (size_t)m * dsub,
                           ix.codebooks + ((size_t)m * 256 + j) * dsub, dsub);
       f[(size_t)m * 256 + j] = v;
       mx = std::max(mx, fabsf(v));
     }
-    B += (double)mx;
   }
-  const int e = lut_exponent(B);
+  const int e = lut_exponent(mx, M);
   for (size_t i = 0; i < f.size(); ++i) lut[i] = lut_quantize(f[i], e);
   return e;
 }

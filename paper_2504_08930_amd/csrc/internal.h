@@ -11,6 +11,7 @@ constexpr int kTileVecs = 64;      // vectors per code tile (one wavefront)
 constexpr int kMaxSlices = 8;      // scan blocks per query, upper bound
 constexpr int kMaxK = 128;
 constexpr int kMaxNprobe = 2048;
+constexpr int kLutMaxParts = 512;  // per-query slots for partial table maxima
 
 // Counters kept on the device next to the per-cluster hit counters.
 enum {
@@ -49,8 +50,9 @@ struct DevLayout {
   int32_t *cold;           // [max_nq][max_nprobe] non-resident cluster ids
   int32_t *n_cold;         // [max_nq]
   float *lut;              // [max_nq][256][M]
-  uint32_t *lutmax;        // [max_nq][M] bits of max |entry|
-  int32_t *lutexp;         // [max_nq]
+  uint32_t *lutpart;       // [max_nq][kLutMaxParts] partial maxima, one slot per LUT-kernel wave
+  uint32_t *lutmax;        // [max_nq] bits of the largest |entry| of the query's table
+  int32_t *q_vecs;         // [max_nq] vectors in the query's resident probes
   int32_t *part_key;       // [max_nq][kMaxSlices][max_k]
   int64_t *part_id;
   int32_t *res_key;        // [max_nq][max_k] merged GPU partial (hybrid path)
@@ -85,11 +87,11 @@ hipError_t launch_coarse_select(const Shape &sh, const float *scores, int nq, in
 hipError_t launch_route(const int32_t *probe, int nq, int nprobe, int probe_stride,
                         const int32_t *clus_tile, const int32_t *clus_len, int M, int32_t *g_base,
                         int32_t *g_len, int32_t *g_prefix, int32_t *g_n, int32_t *cold,
-                        int32_t *n_cold, unsigned long long *hits, unsigned long long *qstats,
-                        int count_stats, hipStream_t st);
+                        int32_t *n_cold, int32_t *q_vecs, unsigned long long *hits,
+                        unsigned long long *qstats, int count_stats, hipStream_t st);
 
 hipError_t launch_lut(const Shape &sh, const float *q, int nq, const float *cbT, float *lut,
-                      uint32_t *lutmax, int32_t *lutexp, hipStream_t st);
+                      uint32_t *lutpart, uint32_t *lutmax, hipStream_t st);
 
 // Returns hipErrorInvalidValue for an unsupported (M, k).
 hipError_t launch_scan(const Shape &sh, const DevLayout &L, int nq, int probe_stride, int slices,

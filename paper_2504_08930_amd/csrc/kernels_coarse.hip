@@ -164,18 +164,26 @@ __device__ __forceinline__ uint32_t score_bits(float s, int metric_ip) {
   return metric_ip ? ~u : u;                        // IP: larger score first
 }
 
-constexpr int kSelThreads = 256;
+constexpr int kSelThreads = 512;
+constexpr int kSelBins = 2048;  // 11-bit digits
+constexpr int kSelBinsPerThread = kSelBins / kSelThreads;
+
+__device__ __forceinline__ unsigned long long sel_key(float s, int metric_ip, int c) {
+  return ((unsigned long long)score_bits(s, metric_ip) << 32) | (unsigned)c;
+}
 
 __global__ __launch_bounds__(kSelThreads) void k_coarse_select(const float *__restrict__ scores,
                                                                int nlist, int metric_ip, int keep,
                                                                int nprobe, int stride, int n2,
                                                                int32_t *__restrict__ probe) {
-  __shared__ unsigned int hist[256];
+  __shared__ unsigned int hist[kSelBins];
+  __shared__ unsigned int wsum[kSelThreads / 64];
   __shared__ unsigned long long s_prefix, s_mask;
   __shared__ unsigned int s_need, s_done, s_count;
   extern __shared__ unsigned long long sel[];  // n2 entries
   const int q = blockIdx.x;
   const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
   const float *row = scores + (size_t)q * nlist;
   int32_t *out = probe + (size_t)q * stride;
 
@@ -188,29 +196,53 @@ __global__ __launch_bounds__(kSelThreads) void k_coarse_select(const float *__re
   }
   unsigned long long thr = ~0ull;
   if (keep < nlist) {
-    for (int byte = 7; byte >= 0; --byte) {
-      hist[tid] = 0u;
+    // digits of the 64-bit key, most significant first: (shift, bits)
+    const int shifts[6] = {53, 42, 32, 21, 10, 0};
+    const int widths[6] = {11, 11, 10, 11, 11, 10};
+    for (int pass = 0; pass < 6; ++pass) {
+      const int shift = shifts[pass];
+      const unsigned dmask = (1u << widths[pass]) - 1u;
+#pragma unroll
+      for (int b = 0; b < kSelBinsPerThread; ++b) hist[tid * kSelBinsPerThread + b] = 0u;
       __syncthreads();
       const unsigned long long prefix = s_prefix, mask = s_mask;
+      const unsigned need = s_need;
       if (s_done) break;
       for (int c = tid; c < nlist; c += kSelThreads) {
-        const unsigned long long key =
-            ((unsigned long long)score_bits(row[c], metric_ip) << 32) | (unsigned)c;
-        if ((key & mask) == prefix) atomicAdd(&hist[(key >> (8 * byte)) & 0xff], 1u);
+        const unsigned long long key = sel_key(row[c], metric_ip, c);
+        if ((key & mask) == prefix) atomicAdd(&hist[(unsigned)(key >> shift) & dmask], 1u);
       }
       __syncthreads();
-      if (tid == 0) {
-        unsigned need = s_need, cum = 0;
+      // block-wide exclusive scan of per-thread bin sums
+      unsigned loc[kSelBinsPerThread], tsum = 0;
+#pragma unroll
+      for (int b = 0; b < kSelBinsPerThread; ++b) {
+        loc[b] = hist[tid * kSelBinsPerThread + b];
+        tsum += loc[b];
+      }
+      unsigned incl = tsum;
+#pragma unroll
+      for (int o = 1; o < 64; o <<= 1) {
+        const unsigned v = __shfl_up(incl, o, 64);
+        if (lane >= o) incl += v;
+      }
+      if (lane == 63) wsum[wave] = incl;
+      __syncthreads();
+      unsigned before = incl - tsum;
+      for (int w2 = 0; w2 < wave; ++w2) before += wsum[w2];
+      // the thread whose bins straddle rank `need` publishes the bucket
+      if (before < need && need <= before + tsum) {
+        unsigned cum = before;
         int b = 0;
-        for (; b < 256; ++b) {
-          if (cum + hist[b] >= need) break;
-          cum += hist[b];
+        for (; b < kSelBinsPerThread - 1; ++b) {
+          if (cum + loc[b] >= need) break;
+          cum += loc[b];
         }
-        // the keep-th smallest key lies in bucket b; the `cum` keys below it are in
+        const unsigned bucket = (unsigned)(tid * kSelBinsPerThread + b);
         s_need = need - cum;
-        s_prefix = prefix | ((unsigned long long)b << (8 * byte));
-        s_mask = mask | (0xffull << (8 * byte));
-        if (hist[b] == need - cum || byte == 0) s_done = 1u;  // whole bucket is selected
+        s_prefix = prefix | ((unsigned long long)bucket << shift);
+        s_mask = mask | ((unsigned long long)dmask << shift);
+        if (loc[b] == need - cum || pass == 5) s_done = 1u;  // whole bucket is selected
       }
       __syncthreads();
     }
@@ -221,8 +253,7 @@ __global__ __launch_bounds__(kSelThreads) void k_coarse_select(const float *__re
   for (int i = tid; i < n2; i += kSelThreads) sel[i] = ~0ull;
   __syncthreads();
   for (int c = tid; c < nlist; c += kSelThreads) {
-    const unsigned long long key =
-        ((unsigned long long)score_bits(row[c], metric_ip) << 32) | (unsigned)c;
+    const unsigned long long key = sel_key(row[c], metric_ip, c);
     if (key <= thr) {
       const unsigned slot = atomicAdd(&s_count, 1u);
       if (slot < (unsigned)n2) sel[slot] = key;

@@ -113,67 +113,140 @@ hipError_t launch_calib_copy(const void *src, void *dst, size_t bytes, hipStream
 // resident probes form the query's GPU work list, the others its cold list.
 // Also the router's counters (Section 4.3.3).
 // ---------------------------------------------------------------------------
-__global__ void k_route(const int32_t *__restrict__ probe, int nq, int nprobe, int stride,
-                        const int32_t *__restrict__ clus_tile,
-                        const int32_t *__restrict__ clus_len, int M, int32_t *g_base,
-                        int32_t *g_len, int32_t *g_prefix, int32_t *g_n, int32_t *cold,
-                        int32_t *n_cold, unsigned long long *hits, unsigned long long *qstats,
-                        int count_stats) {
-  int q = blockIdx.x * blockDim.x + threadIdx.x;
+__global__ __launch_bounds__(256) void k_route(
+    const int32_t *__restrict__ probe, int nq, int nprobe, int stride,
+    const int32_t *__restrict__ clus_tile, const int32_t *__restrict__ clus_len, int M,
+    int32_t *g_base, int32_t *g_len, int32_t *g_prefix, int32_t *g_n, int32_t *cold,
+    int32_t *n_cold, int32_t *q_vecs, unsigned long long *hits, int count_stats) {
+  // one wavefront per query, one lane per probe (64 probes per step); the GPU
+  // work list keeps probe order
+  const int q = blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int lane = threadIdx.x & 63;
   if (q >= nq) return;
   const int32_t *pr = probe + (size_t)q * stride;
   int32_t *gb = g_base + (size_t)q * stride;
   int32_t *gl = g_len + (size_t)q * stride;
   int32_t *gp = g_prefix + (size_t)q * (stride + 1);
   int32_t *cd = cold + (size_t)q * stride;
-  int ng = 0, nc = 0, tiles = 0, valid = 0;
+  const unsigned long long lt = (1ull << lane) - 1ull;
+  int ng = 0, nc = 0, tiles = 0, valid_n = 0;
   unsigned long long vecs = 0;
-  for (int p = 0; p < nprobe; ++p) {
-    int c = pr[p];
-    if (c < 0) continue;
-    ++valid;
-    if (count_stats) atomicAdd(&hits[c], 1ull);
-    int t = clus_tile[c];
-    int len = clus_len[c];
-    if (t >= 0) {
-      gb[ng] = t;
-      gl[ng] = len;
-      gp[ng] = tiles;
-      tiles += (len + kTileVecs - 1) / kTileVecs;
-      vecs += (unsigned long long)len;
-      ++ng;
-    } else {
-      cd[nc++] = c;
+  for (int base = 0; base < nprobe; base += 64) {
+    const int p = base + lane;
+    const int c = p < nprobe ? pr[p] : -1;
+    const bool valid = c >= 0;
+    int t = -1, len = 0;
+    if (valid) {
+      if (count_stats) atomicAdd(&hits[c], 1ull);
+      t = clus_tile[c];
+      len = clus_len[c];
     }
+    const bool res = valid && t >= 0;
+    const bool cld = valid && t < 0;
+    const unsigned long long mres = __ballot(res), mcold = __ballot(cld);
+    const int nt = res ? (len + kTileVecs - 1) / kTileVecs : 0;
+    // inclusive scan of tile counts over lanes
+    int incl = nt;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      const int v = __shfl_up(incl, o, 64);
+      if (lane >= o) incl += v;
+    }
+    if (res) {
+      const int o = ng + __popcll(mres & lt);
+      gb[o] = t;
+      gl[o] = len;
+      gp[o] = tiles + incl - nt;
+    }
+    if (cld) cd[nc + __popcll(mcold & lt)] = c;
+    // wave totals
+    long long lv = res ? len : 0;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) lv += __shfl_xor(lv, o, 64);
+    vecs += (unsigned long long)lv;
+    tiles += __shfl(incl, 63, 64);
+    ng += __popcll(mres);
+    nc += __popcll(mcold);
+    valid_n += __popcll(__ballot(valid));
   }
-  gp[ng] = tiles;
-  g_n[q] = ng;
-  n_cold[q] = nc;
-  for (int p = nc; p < nprobe; ++p) cd[p] = -1;
-  atomicAdd(&qstats[QS_SCAN_BYTES], vecs * (unsigned long long)M);
-  if (count_stats) {
-    atomicAdd(&qstats[QS_RESIDENT_PROBES], (unsigned long long)ng);
-    atomicAdd(&qstats[QS_PROBES], (unsigned long long)valid);
-    atomicAdd(&qstats[QS_QUERIES], 1ull);
-    float rate = valid ? (float)ng / (float)valid : 0.0f;
-    atomicMin(reinterpret_cast<unsigned int *>(&qstats[QS_MIN_RATE_BITS]), __float_as_uint(rate));
+  for (int p = nc + lane; p < nprobe; p += 64) cd[p] = -1;
+  if (lane == 0) {
+    gp[ng] = tiles;
+    g_n[q] = ng;
+    n_cold[q] = nc;
+    q_vecs[q] = (int32_t)vecs;
+  }
+}
+
+// Batch totals of the router counters: one block reduces the per-query values
+// (same-address atomics from every query would serialize).
+__global__ __launch_bounds__(1024) void k_route_stats(const int32_t *__restrict__ g_n,
+                                                      const int32_t *__restrict__ n_cold,
+                                                      const int32_t *__restrict__ q_vecs, int nq,
+                                                      int M, unsigned long long *qstats,
+                                                      int count_stats) {
+  __shared__ unsigned long long s_res[16], s_all[16], s_vec[16];
+  __shared__ unsigned int s_min[16];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  unsigned long long res = 0, all = 0, vec = 0;
+  unsigned int mn = 0x3f800000u;  // 1.0f
+  for (int q = tid; q < nq; q += 1024) {
+    const int ng = g_n[q], valid = ng + n_cold[q];
+    res += (unsigned long long)ng;
+    all += (unsigned long long)valid;
+    vec += (unsigned long long)q_vecs[q];
+    const float rate = valid ? (float)ng / (float)valid : 0.0f;
+    mn = min(mn, __float_as_uint(rate));
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    res += __shfl_xor((long long)res, o, 64);
+    all += __shfl_xor((long long)all, o, 64);
+    vec += __shfl_xor((long long)vec, o, 64);
+    mn = min(mn, (unsigned int)__shfl_xor((int)mn, o, 64));
+  }
+  if (lane == 0) {
+    s_res[wave] = res;
+    s_all[wave] = all;
+    s_vec[wave] = vec;
+    s_min[wave] = mn;
+  }
+  __syncthreads();
+  if (tid == 0) {
+    for (int w2 = 1; w2 < 16; ++w2) {
+      res += s_res[w2];
+      all += s_all[w2];
+      vec += s_vec[w2];
+      mn = min(mn, s_min[w2]);
+    }
+    atomicAdd(&qstats[QS_SCAN_BYTES], vec * (unsigned long long)M);
+    if (count_stats) {
+      atomicAdd(&qstats[QS_RESIDENT_PROBES], res);
+      atomicAdd(&qstats[QS_PROBES], all);
+      atomicAdd(&qstats[QS_QUERIES], (unsigned long long)nq);
+      atomicMin(reinterpret_cast<unsigned int *>(&qstats[QS_MIN_RATE_BITS]), mn);
+    }
   }
 }
 
 hipError_t launch_route(const int32_t *probe, int nq, int nprobe, int probe_stride,
                         const int32_t *clus_tile, const int32_t *clus_len, int M, int32_t *g_base,
                         int32_t *g_len, int32_t *g_prefix, int32_t *g_n, int32_t *cold,
-                        int32_t *n_cold, unsigned long long *hits, unsigned long long *qstats,
-                        int count_stats, hipStream_t st) {
-  hipLaunchKernelGGL(k_route, dim3((nq + 63) / 64), dim3(64), 0, st, probe, nq, nprobe,
+                        int32_t *n_cold, int32_t *q_vecs, unsigned long long *hits,
+                        unsigned long long *qstats, int count_stats, hipStream_t st) {
+  hipLaunchKernelGGL(k_route, dim3((nq + 3) / 4), dim3(256), 0, st, probe, nq, nprobe,
                      probe_stride, clus_tile, clus_len, M, g_base, g_len, g_prefix, g_n, cold,
-                     n_cold, hits, qstats, count_stats);
+                     n_cold, q_vecs, hits, count_stats);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(k_route_stats, dim3(1), dim3(1024), 0, st, g_n, n_cold, q_vecs, nq, M, qstats,
+                     count_stats);
   return hipGetLastError();
 }
 
 // ---------------------------------------------------------------------------
 // Stage 2: per-query lookup table, fp32, layout [query][code j][sub-quantizer m],
-// plus the largest |entry| per (query, m) for the fixed-point scale.
+// plus the largest |entry| per query for the fixed-point scale.
 // Thread (ml, jl) owns one codeword (m, j) in registers and loops over the
 // queries of its tile, so codebooks are read once per query tile, not once per
 // query.  Lanes run along m: table stores are contiguous in m.
@@ -185,7 +258,7 @@ __global__ __launch_bounds__(256) void k_lut(const float *__restrict__ queries, 
                                              int M, int dsub_rt, int MW,
                                              const float *__restrict__ cbT, int metric_ip,
                                              float *__restrict__ lut,
-                                             uint32_t *__restrict__ lutmax) {
+                                             uint32_t *__restrict__ lutpart) {
   const int dsub = DSUB > 0 ? DSUB : dsub_rt;
   const int tid = threadIdx.x;
   const int JT = 256 / MW;
@@ -194,7 +267,6 @@ __global__ __launch_bounds__(256) void k_lut(const float *__restrict__ queries, 
   const int j = blockIdx.x * JT + jl;
   const int q0 = blockIdx.z * kLutQTile;
   const int q1 = min(nq, q0 + kLutQTile);
-  __shared__ uint32_t smax[256];
 
   const float *cw = cbT + ((size_t)j * M + m) * dsub;
   float creg[DSUB > 0 ? DSUB : 1];
@@ -214,37 +286,40 @@ __global__ __launch_bounds__(256) void k_lut(const float *__restrict__ queries, 
       v = lut_entry(metric_ip, qv, cw, dsub);
     }
     lut[((size_t)qi * 256 + j) * M + m] = v;
-    smax[tid] = __float_as_uint(fabsf(v));
-    __syncthreads();
-    if (tid < MW) {
-      uint32_t mx = 0;
-      for (int r = 0; r < JT; ++r) mx = max(mx, smax[r * MW + tid]);
-      atomicMax(&lutmax[(size_t)qi * M + m], mx);
+    // largest |entry| of this block for the query: wave max, then one atomic per wave
+    // largest |entry| seen by this wave for the query: a plain store into the
+    // wave's own slot (atomics on one word per query would serialize)
+    uint32_t mx = __float_as_uint(fabsf(v));
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) mx = max(mx, (uint32_t)__shfl_xor((int)mx, o, 64));
+    if ((tid & 63) == 0) {
+      const int part = ((blockIdx.y * gridDim.x + blockIdx.x) << 2) | (tid >> 6);
+      lutpart[(size_t)qi * kLutMaxParts + part] = mx;
     }
-    __syncthreads();
   }
 }
 
-__global__ void k_lut_exp(const uint32_t *__restrict__ lutmax, int nq, int M,
-                          int32_t *__restrict__ lutexp) {
-  int q = blockIdx.x * blockDim.x + threadIdx.x;
+__global__ __launch_bounds__(256) void k_lut_max(const uint32_t *__restrict__ lutpart, int nq,
+                                                 int nparts, uint32_t *__restrict__ lutmax) {
+  const int q = blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int lane = threadIdx.x & 63;
   if (q >= nq) return;
-  double B = 0.0;
-  for (int m = 0; m < M; ++m) B += (double)__uint_as_float(lutmax[(size_t)q * M + m]);
-  lutexp[q] = lut_exponent(B);
+  uint32_t mx = 0;
+  for (int i = lane; i < nparts; i += 64) mx = max(mx, lutpart[(size_t)q * kLutMaxParts + i]);
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) mx = max(mx, (uint32_t)__shfl_xor((int)mx, o, 64));
+  if (lane == 0) lutmax[q] = mx;
 }
 
 hipError_t launch_lut(const Shape &sh, const float *q, int nq, const float *cbT, float *lut,
-                      uint32_t *lutmax, int32_t *lutexp, hipStream_t st) {
-  hipError_t e = launch_fill_u32(lutmax, (size_t)nq * sh.M, 0u, st);
-  if (e != hipSuccess) return e;
+                      uint32_t *lutpart, uint32_t *lutmax, hipStream_t st) {
   const int MW = (sh.M % 32 == 0) ? 32 : 16;
   const int JT = 256 / MW;
   dim3 grid(256 / JT, sh.M / MW, (nq + kLutQTile - 1) / kLutQTile);
 #define IVF_LUT_CASE(DS)                                                                       \
   case DS:                                                                                     \
     hipLaunchKernelGGL(k_lut<DS>, grid, dim3(256), 0, st, q, nq, sh.d, sh.M, sh.dsub, MW, cbT, \
-                       sh.metric_ip, lut, lutmax);                                             \
+                       sh.metric_ip, lut, lutpart);                                            \
     break;
   switch (sh.dsub) {
     IVF_LUT_CASE(2)
@@ -254,12 +329,13 @@ hipError_t launch_lut(const Shape &sh, const float *q, int nq, const float *cbT,
     IVF_LUT_CASE(16)
     default:
       hipLaunchKernelGGL(k_lut<0>, grid, dim3(256), 0, st, q, nq, sh.d, sh.M, sh.dsub, MW, cbT,
-                         sh.metric_ip, lut, lutmax);
+                         sh.metric_ip, lut, lutpart);
   }
 #undef IVF_LUT_CASE
-  e = hipGetLastError();
+  hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(k_lut_exp, dim3((nq + 63) / 64), dim3(64), 0, st, lutmax, nq, sh.M, lutexp);
+  const int nparts = (int)(grid.x * grid.y * 4);
+  hipLaunchKernelGGL(k_lut_max, dim3((nq + 3) / 4), dim3(256), 0, st, lutpart, nq, nparts, lutmax);
   return hipGetLastError();
 }
 
@@ -331,7 +407,7 @@ struct ScanParams {
   const uint8_t *tile_codes;
   const int64_t *tile_ids;
   const float *lut;
-  const int32_t *lutexp;
+  const uint32_t *lutmax;
   const int32_t *g_base;
   const int32_t *g_len;
   const int32_t *g_prefix;
@@ -341,7 +417,6 @@ struct ScanParams {
   int probe_stride;
   int slices;
   int k;
-  int kp;  // k rounded up to a power of two (>= 16)
 };
 
 template <int M>
@@ -369,6 +444,7 @@ __global__ __launch_bounds__(NW * 64) void k_scan(ScanParams P) {
   int *buf_key_all = reinterpret_cast<int *>(smem + G::kTables * G::kTableBytes +
                                              (size_t)NW * CAP * sizeof(long long));
   int *s_thr = buf_key_all + NW * CAP;
+  int *s_total = s_thr + 1;
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -379,7 +455,7 @@ __global__ __launch_bounds__(NW * 64) void k_scan(ScanParams P) {
 
   // ---- stage the query's table in LDS as fixed point, code-major ----
   {
-    const int e = P.lutexp[q];
+    const int e = lut_exponent(__uint_as_float(P.lutmax[q]), M);
     const float4 *src = reinterpret_cast<const float4 *>(P.lut + (size_t)q * 256 * M);
     constexpr int kVec = 256 * M / 4;
     for (int idx = tid; idx < kVec; idx += NW * 64) {
@@ -398,11 +474,10 @@ __global__ __launch_bounds__(NW * 64) void k_scan(ScanParams P) {
         if (G::kRem && gi == G::kFull) row[r + 16] = key;  // 16-wide group: second replica
       }
     }
-    for (int i = tid; i < NW * CAP; i += NW * 64) {
-      buf_key_all[i] = kKeyInvalid;
-      buf_id_all[i] = 0x7fffffffffffffffll;
+    if (tid == 0) {
+      *s_thr = kKeyInvalid;
+      *s_total = 0;
     }
-    if (tid == 0) *s_thr = kKeyInvalid;
   }
   __syncthreads();
 
@@ -455,22 +530,62 @@ __global__ __launch_bounds__(NW * 64) void k_scan(ScanParams P) {
     for (int u = 0; u < M / 16; ++u) c[u] = src[u * 64 + lane];
   };
 
-  int cnt = 0;                 // candidates in this wave's buffer
-  int tk = kKeyInvalid;        // this wave's k-th best so far (key, id)
-  long long tkid = 0x7fffffffffffffffll;
+  int cnt = 0;            // candidates in this wave's (unsorted) buffer
+  int tk = kKeyInvalid;   // a key above this can no longer reach the block's top k
+  const unsigned long long lt_mask = (1ull << lane) - 1ull;
+  constexpr int E = CAP / 64;
 
+  // Shrink the buffer to the candidates whose key is not above its k-th smallest
+  // key.  The k-th smallest key is found by a bitwise search with ballots (no
+  // sorting, no ids); ties on that key all stay - the exact (key, id) order is
+  // settled once, in the block merge.
   auto compact = [&]() {
-    for (int i = cnt + lane; i < CAP; i += 64) {
-      bkey[i] = kKeyInvalid;
-      bid[i] = 0x7fffffffffffffffll;
-    }
     wave_sync();
-    bitonic_sort_lds<false>(bkey, bid, CAP, lane, 64);
-    if (cnt >= k) {
+    int kk[E];
+    long long ii[E];
+    uint32_t uk[E];
+    bool vv[E];
+#pragma unroll
+    for (int e = 0; e < E; ++e) {
+      const int idx = lane + 64 * e;
+      vv[e] = idx < cnt;
+      kk[e] = vv[e] ? bkey[idx] : kKeyInvalid;
+      ii[e] = vv[e] ? bid[idx] : 0;
+      uk[e] = (uint32_t)kk[e] ^ 0x80000000u;  // order-preserving unsigned form
+    }
+    uint32_t prefix = 0;
+    for (int bit = 31; bit >= 0; --bit) {
+      const uint32_t cand = prefix | (1u << bit);
+      int c = 0;
+#pragma unroll
+      for (int e = 0; e < E; ++e) c += __popcll(__ballot(vv[e] && uk[e] < cand));
+      if (c < k) prefix = cand;  // fewer than k keys below cand: the k-th smallest is >= cand
+    }
+    const int T = (int)(prefix ^ 0x80000000u);
+    wave_sync();
+    int base = 0;
+#pragma unroll
+    for (int e = 0; e < E; ++e) {
+      const bool keep = vv[e] && kk[e] <= T;
+      const unsigned long long mask = __ballot(keep);
+      if (keep) {
+        const int o = base + __popcll(mask & lt_mask);
+        bkey[o] = kk[e];
+        bid[o] = ii[e];
+      }
+      base += __popcll(mask);
+    }
+    cnt = base;
+    tk = min(tk, T);
+    if (lane == 0) atomicMin(s_thr, T);
+    if (cnt > CAP - 64) {  // only with a mass of equal keys: trim exactly by (key, id)
+      for (int i = cnt + lane; i < CAP; i += 64) {
+        bkey[i] = kKeyInvalid;
+        bid[i] = 0x7fffffffffffffffll;
+      }
+      wave_sync();
+      bitonic_sort_lds<false>(bkey, bid, CAP, lane, 64);
       cnt = k;
-      tk = bkey[k - 1];
-      tkid = bid[k - 1];
-      if (lane == 0) atomicMin(s_thr, tk);
     }
   };
 
@@ -498,21 +613,17 @@ __global__ __launch_bounds__(NW * 64) void k_scan(ScanParams P) {
     const bool valid = pos < tr.len;
     const int key = valid ? acc : kKeyInvalid;
     const int thr = min(tk, __atomic_load_n(s_thr, __ATOMIC_RELAXED));
-    const bool pre = valid && key <= thr;
-    if (__ballot(pre)) {  // rare after the first tiles
-      long long id = 0;
-      if (pre) id = P.tile_ids[(size_t)tr.gtile * kTileVecs + lane];
-      const bool pass = pre && cand_less(key, id, tk, tkid);
-      const unsigned long long mask = __ballot(pass);
-      if (mask) {
-        if (pass) {
-          const int off = cnt + __popcll(mask & ((1ull << lane) - 1ull));
-          bkey[off] = key;
-          bid[off] = id;
-        }
-        cnt += __popcll(mask);
-        if (cnt > CAP - 64) compact();
+    const bool pass = valid && key <= thr;
+    const unsigned long long mask = __ballot(pass);
+    if (mask) {  // rare after the first tiles
+      if (pass) {
+        const long long id = P.tile_ids[(size_t)tr.gtile * kTileVecs + lane];
+        const int off = cnt + __popcll(mask & lt_mask);
+        bkey[off] = key;
+        bid[off] = id;
       }
+      cnt += __popcll(mask);
+      if (cnt > CAP - 64) compact();
     }
   };
 
@@ -543,27 +654,89 @@ __global__ __launch_bounds__(NW * 64) void k_scan(ScanParams P) {
     }
   }
 
-  // ---- merge the waves' candidates: each wave sorts its own, then the block
-  // sorts NW * kp of them in the (now idle) table region ----
+  // ---- block merge.  Each wave trims its buffer to about k candidates, all of
+  // them are gathered in the (now idle) table region, and one wave selects the
+  // k best by (key, id): bitwise search for the k-th smallest key, then a rank
+  // sort of the few candidates at or below it. ----
+  if (cnt > k) compact();
   wave_sync();
-  compact();
   __syncthreads();
-  const int kp = P.kp;
-  const int n2 = NW * kp;
-  int *mkey = reinterpret_cast<int *>(smem + (size_t)n2 * sizeof(long long));
+  constexpr int kMaxCand = NW * (CAP - 64);        // every wave holds at most CAP - 64
+  constexpr int kFin = kMaxCand <= 1024 ? 1024 : 2048;  // power of two >= kMaxCand
+  static_assert(kMaxCand <= kFin && kMaxCand * 12 + kFin * 12 <= 65536, "merge arrays fit");
   long long *mid = reinterpret_cast<long long *>(smem);
-  for (int i = tid; i < n2; i += NW * 64) {
-    const int ww = i / kp, r = i % kp;
-    const bool ok = r < k;
-    mkey[i] = ok ? buf_key_all[ww * CAP + r] : kKeyInvalid;
-    mid[i] = ok ? buf_id_all[ww * CAP + r] : 0x7fffffffffffffffll;
+  int *mkey = reinterpret_cast<int *>(smem + (size_t)kMaxCand * 8);
+  long long *fid = reinterpret_cast<long long *>(smem + (size_t)kMaxCand * 12);
+  int *fkey = reinterpret_cast<int *>(smem + (size_t)kMaxCand * 12 + (size_t)kFin * 8);
+  {
+    int base = 0;
+    if (lane == 0) base = atomicAdd(s_total, cnt);
+    base = __builtin_amdgcn_readfirstlane(base);
+    for (int i = lane; i < cnt; i += 64) {
+      mkey[base + i] = bkey[i];
+      mid[base + i] = bid[i];
+    }
   }
   __syncthreads();
-  bitonic_sort_lds<true>(mkey, mid, n2, tid, NW * 64);
-  for (int r = tid; r < k; r += NW * 64) {
-    const size_t o = ((size_t)q * P.slices + s) * k + r;
-    P.part_key[o] = mkey[r];
-    P.part_id[o] = mid[r];
+  if (w != 0) return;
+  const int n = *s_total;
+  int kth_key = kKeyInvalid;
+  if (n > k) {
+    uint32_t prefix = 0;
+    for (int bit = 31; bit >= 0; --bit) {
+      const uint32_t cand = prefix | (1u << bit);
+      int c = 0;
+      for (int i0 = 0; i0 < n; i0 += 64) {
+        const int i = i0 + lane;
+        const bool below = i < n && ((uint32_t)mkey[i] ^ 0x80000000u) < cand;
+        c += __popcll(__ballot(below));
+      }
+      if (c < k) prefix = cand;
+    }
+    kth_key = (int)(prefix ^ 0x80000000u);
+  }
+  int nf = 0;
+  for (int i0 = 0; i0 < n; i0 += 64) {
+    const int i = i0 + lane;
+    const bool keep = i < n && mkey[i] <= kth_key;
+    const unsigned long long mask = __ballot(keep);
+    if (keep) {
+      const int o = nf + __popcll(mask & lt_mask);
+      fkey[o] = mkey[i];
+      fid[o] = mid[i];
+    }
+    nf += __popcll(mask);
+  }
+  wave_sync();
+  const size_t obase = ((size_t)q * P.slices + s) * k;
+  if (nf <= 192) {
+    for (int i = lane; i < nf; i += 64) {
+      const int ki = fkey[i];
+      const long long idi = fid[i];
+      int rank = 0;
+      for (int j = 0; j < nf; ++j) rank += cand_less(fkey[j], fid[j], ki, idi) ? 1 : 0;
+      if (rank < k) {
+        P.part_key[obase + rank] = ki;
+        P.part_id[obase + rank] = idi;
+      }
+    }
+    for (int r = nf + lane; r < k; r += 64) {
+      P.part_key[obase + r] = kKeyInvalid;
+      P.part_id[obase + r] = 0x7fffffffffffffffll;
+    }
+  } else {  // a mass of equal keys: sort them all
+    int n2 = 256;
+    while (n2 < nf) n2 <<= 1;
+    for (int i = nf + lane; i < n2; i += 64) {
+      fkey[i] = kKeyInvalid;
+      fid[i] = 0x7fffffffffffffffll;
+    }
+    wave_sync();
+    bitonic_sort_lds<false>(fkey, fid, n2, lane, 64);
+    for (int r = lane; r < k; r += 64) {
+      P.part_key[obase + r] = fkey[r];
+      P.part_id[obase + r] = fid[r];
+    }
   }
 }
 
@@ -594,7 +767,7 @@ hipError_t launch_scan(const Shape &sh, const DevLayout &L, int nq, int probe_st
   P.tile_codes = L.tile_codes;
   P.tile_ids = L.tile_ids;
   P.lut = L.lut;
-  P.lutexp = L.lutexp;
+  P.lutmax = L.lutmax;
   P.g_base = L.g_base;
   P.g_len = L.g_len;
   P.g_prefix = L.g_prefix;
@@ -604,9 +777,6 @@ hipError_t launch_scan(const Shape &sh, const DevLayout &L, int nq, int probe_st
   P.probe_stride = probe_stride;
   P.slices = slices;
   P.k = k;
-  int kp = 16;
-  while (kp < k) kp <<= 1;
-  P.kp = kp;
 #define IVF_SCAN_CASE(MM)                                             \
   case MM:                                                            \
     return k <= 64 ? launch_scan_t<MM, 16, 128>(P, nq, st)            \
@@ -629,8 +799,8 @@ hipError_t launch_scan(const Shape &sh, const DevLayout &L, int nq, int probe_st
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(64) void k_merge(const int32_t *__restrict__ part_key,
                                               const int64_t *__restrict__ part_id, int slices,
-                                              int k, int n2, const int32_t *__restrict__ lutexp,
-                                              int metric_ip, int32_t *res_key, int64_t *res_id,
+                                              int k, int n2, const uint32_t *__restrict__ lutmax,
+                                              int M, int metric_ip, int32_t *res_key, int64_t *res_id,
                                               int64_t *out_ids, float *out_dists) {
   __shared__ int mkey[kMaxSlices * kMaxK];
   __shared__ long long mid[kMaxSlices * kMaxK];
@@ -644,7 +814,7 @@ __global__ __launch_bounds__(64) void k_merge(const int32_t *__restrict__ part_k
   }
   wave_sync();
   if (slices > 1) bitonic_sort_lds<false>(mkey, mid, n2, lane, 64);
-  const int e = lutexp[q];
+  const int e = lut_exponent(__uint_as_float(lutmax[q]), M);
   for (int r = lane; r < k; r += 64) {
     const int key = mkey[r];
     const bool ok = key != kKeyInvalid;
@@ -664,7 +834,7 @@ hipError_t launch_merge(const Shape &sh, const DevLayout &L, int nq, int slices,
   int n2 = 1;
   while (n2 < slices * k) n2 <<= 1;
   hipLaunchKernelGGL(k_merge, dim3(nq), dim3(64), 0, st, L.part_key, L.part_id, slices, k, n2,
-                     L.lutexp, sh.metric_ip, L.res_key, L.res_id, out_ids, out_dists);
+                     L.lutmax, sh.M, sh.metric_ip, L.res_key, L.res_id, out_ids, out_dists);
   return hipGetLastError();
 }
 

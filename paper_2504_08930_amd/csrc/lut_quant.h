@@ -11,9 +11,10 @@
 // and both return bit-identical distances.  For the inner product the table
 // holds the negated partial products, so "smaller is better" everywhere.
 //
-// Error bound: with B = sum_m max_j |T[m][j]| and e chosen so that
-// B * 2^e <= 2^30, every entry is off by at most 2^-(e+1), the sum by at most
-// M * 2^-(e+1) <= M * B / 2^30 (~ 9e-8 * B at M = 96).
+// Error bound: with B = M * max_{m,j} |T[m][j]| (no code sum can exceed it)
+// and e chosen so that B * 2^e <= 2^30, every entry is off by at most
+// 2^-(e+1), the sum by at most M * 2^-(e+1) <= M * B / 2^30
+// (~ 9e-8 * B at M = 96).
 #pragma once
 #include <math.h>
 #include <stdint.h>
@@ -44,9 +45,10 @@ IVF_HD inline float lut_entry(int metric_ip, const float *q, const float *c, int
   return acc;
 }
 
-// Scale exponent from B = sum over sub-quantizers of the largest |entry|:
-// B = f * 2^x with f in [0.5, 1)  =>  B * 2^(30 - x) <= 2^30.
-IVF_HD inline int lut_exponent(double B) {
+// Scale exponent from the largest |entry| of the query's table:
+// B = M * maxabs = f * 2^x with f in [0.5, 1)  =>  B * 2^(30 - x) <= 2^30.
+IVF_HD inline int lut_exponent(float maxabs, int M) {
+  const double B = (double)M * (double)maxabs;
   if (!(B > 0.0)) return 0;
   const uint64_t bits = __builtin_bit_cast(uint64_t, B);
   int x = (int)((bits >> 52) & 0x7ff) - 1022;
