@@ -53,6 +53,9 @@ SPECS = {
     # 100M x 768 IP
     "C4": WorkloadSpec("C4", 100_000_000, 768, 65536, 65536, 96, METRIC_IP, True,
                        4096, 128, 100, 1.0, 1.0),
+    # scaled-down stand-in for the 100M config's search parameters (nprobe=128, k=100)
+    "C4S": WorkloadSpec("C4S", 4_000_000, 768, 4096, 4096, 96, METRIC_IP, True,
+                        512, 128, 100, 1.0, 1.0),
     # small shapes for CPU-only tests and smoke runs
     "T_L2": WorkloadSpec("T_L2", 6_000, 32, 48, 48, 16, METRIC_L2, False,
                          24, 6, 10, None, 1.0, kmeans_iters=4),

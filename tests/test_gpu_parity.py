@@ -293,3 +293,60 @@ def test_c2_config_hybrid(pkg, oracle):
     _say(f"C2: coarse-ambiguous {n_coarse}, id-ambiguous {n_amb} of {len(sel)}")
     assert n_coarse <= 2 and n_amb <= 4
     index.close()
+
+
+def test_c3_config_full_size(pkg, oracle):
+    """The 10M x 768 configuration the benchmark times (nq=1024, nprobe=64, k=10, one scan
+    block per query): oracle parity on a sample of queries, and equality of the
+    all-resident and 30 %-resident (hybrid) results on every query."""
+    import torch
+    spec, ix, q, calib = _case("C3")
+    index = pkg.IvfIndex(ix, max_nq=1024, max_nprobe=64, max_k=16)
+    index.load_partition(np.arange(ix.nlist, dtype=np.int32))
+    qd = torch.from_numpy(q).cuda()
+    ids_d, dist_d = index.search_batch_dev(qd, spec.nprobe, spec.k)
+    torch.cuda.synchronize()
+    ids, dist = ids_d.cpu().numpy(), dist_d.cpu().numpy()
+    probe = index.coarse_probe_dev(qd, spec.nprobe).cpu().numpy()
+    sel = np.arange(0, q.shape[0], 16)
+    n_coarse, n_amb = _check_search(oracle, ix, q[sel], spec.nprobe, spec.k, ids[sel], dist[sel],
+                                    probe[sel])
+    _say(f"C3: coarse-ambiguous {n_coarse}, id-ambiguous {n_amb} of {len(sel)}")
+    assert n_coarse <= 1 and n_amb <= 2
+    # properties that hold at any size
+    assert (ids >= 0).all() and np.all(np.diff(dist, axis=1) <= 0)          # IP: best first
+    assert all(len(set(r.tolist())) == spec.k for r in ids)
+    hot = hottest(index, calib, spec.nprobe, 0.3, ix.nlist)
+    index.load_partition(hot)
+    hyb = index.search_batch(q, spec.nprobe, spec.k)
+    st = index.hit_stats()
+    _say(f"C3: 30 % resident, mean hit rate {st['mean_hit_rate']:.3f}")
+    assert np.array_equal(hyb[0], ids) and np.array_equal(hyb[1], dist)
+    index.close()
+    _CACHE.pop("C3", None)
+
+
+def test_k100_nprobe128(pkg, oracle):
+    """Search parameters of the 100M config (nprobe=128, k=100) on a 4M-vector
+    index: exercises the k > 64 scan variant and lists of ~1000 vectors."""
+    import torch
+    spec, ix, q, calib = _case("C4S")
+    index = pkg.IvfIndex(ix, max_nq=512, max_nprobe=128, max_k=100)
+    index.load_partition(np.arange(ix.nlist, dtype=np.int32))
+    qd = torch.from_numpy(q).cuda()
+    ids_d, dist_d = index.search_batch_dev(qd, spec.nprobe, spec.k)
+    torch.cuda.synchronize()
+    ids, dist = ids_d.cpu().numpy(), dist_d.cpu().numpy()
+    probe = index.coarse_probe_dev(qd, spec.nprobe).cpu().numpy()
+    sel = np.arange(0, q.shape[0], 16)
+    n_coarse, n_amb = _check_search(oracle, ix, q[sel], spec.nprobe, spec.k, ids[sel], dist[sel],
+                                    probe[sel])
+    _say(f"C4S: coarse-ambiguous {n_coarse}, id-ambiguous {n_amb} of {len(sel)}")
+    assert n_coarse <= 1 and n_amb <= 2
+    # k-prefix property against the k <= 64 kernel variant
+    ids10, dist10 = index.search_batch_dev(qd, spec.nprobe, 10)
+    torch.cuda.synchronize()
+    assert np.array_equal(ids10.cpu().numpy(), ids[:, :10])
+    assert np.array_equal(dist10.cpu().numpy(), dist[:, :10])
+    index.close()
+    _CACHE.pop("C4S", None)
