@@ -1,19 +1,25 @@
 #!/usr/bin/env python3
 """Benchmark of the IVF-PQ hot path on one MI355X.
 
-A step is one pass of the whole hot path over one query batch that is already
-resident in HBM: coarse quantizer (MFMA contraction + per-query top-nprobe),
-routing through the mapping table, per-query lookup tables, ADC scan of the
-resident inverted lists with in-block top-k, per-query merge.  The workload is
-the 10M-vector configuration (N = 10M, D = 768, nlist = 16384, PQ 96 x 8 bit,
-inner product, nq = 1024, nprobe = 64, k = 10, Zipf(1.0) query-to-cluster
-choice), seeded and synthetic, with every cluster GPU-resident.
+Default mode ("hotpath"): a step is one pass of the whole hot path over one
+query batch that is already resident in HBM: coarse quantizer (split-bf16 MFMA
+contraction + per-query top-nprobe), routing through the mapping table,
+per-query lookup tables, ADC scan of the resident inverted lists with in-block
+top-k, per-query merge.  The workload is the 10M-vector configuration (N = 10M,
+D = 768, nlist = 16384, PQ 96 x 8 bit, inner product, nq = 1024, nprobe = 64,
+k = 10, Zipf(1.0) query-to-cluster choice), seeded and synthetic, with every
+cluster GPU-resident.  Prints ONE JSON line.  `roofline` is for the ADC-scan
+kernel: algorithmic bytes (sum over (query, resident probe) pairs of M * list
+length) per launch over that kernel's average duration, taken from HIP events
+recorded on the search stream inside the timed region.  `cpu_baseline` is the
+oracle (oracle/) timed on this machine's host cores on a bounded sample of the same
+queries.
 
-Prints ONE JSON line.  `roofline` is for the ADC-scan kernel: algorithmic bytes
-(sum over (query, resident probe) pairs of M * list length) per launch over
-that kernel's average duration, taken from HIP events recorded on the search
-stream inside the timed region.  `cpu_baseline` is the oracle (oracle/) timed on
-this machine's host cores on a bounded sample of the same queries.
+Other modes (each prints one JSON line of its own):
+  --mode sweep   nq in {256, 1024, 4096} x resident fraction in {0.1, 0.3, 0.5, 1.0}
+  --mode drift   20 epochs x 10 000 queries, Zipf permutation re-drawn every 5
+                 epochs, hot set recomputed from ivf_hit_stats after every epoch
+                 and migrated with ivf_migrate_clusters while searches continue
 """
 import argparse
 import json
@@ -38,11 +44,62 @@ def log(msg):
     print(f"[bench] {msg}", file=sys.stderr, flush=True)
 
 
+def hottest_clusters(index, calib, nprobe, frac, nlist):
+    """Hottest round(frac * nlist) clusters by probe count over calibration queries."""
+    import numpy as np
+    import torch
+    index.hit_stats(reset=True)
+    for s in range(0, calib.shape[0], index.max_nq):
+        index.search_batch_dev(calib[s:s + index.max_nq].contiguous(), nprobe, 1)
+    torch.cuda.synchronize()
+    hits = index.hit_stats(reset=True)["per_cluster_hits"].astype(np.int64)
+    order = np.lexsort((np.arange(nlist), -hits))
+    return np.sort(order[: int(round(frac * nlist))]).astype(np.int32)
+
+
+def timed_steps(index, q, nprobe, k, steps, warmup, slices, timing=True):
+    """Warm up, then time `steps` searches of the device-resident batch q."""
+    import torch
+    dev = q.device
+    nq = q.shape[0]
+    out_ids = torch.empty((nq, k), dtype=torch.int64, device=dev)
+    out_d = torch.empty((nq, k), dtype=torch.float32, device=dev)
+    stream = torch.cuda.current_stream(dev)
+    index.set_tuning(scan_slices=slices, timing=False)
+    for _ in range(warmup):
+        index.search_batch_dev(q, nprobe, k, out_ids, out_d, stream)
+    torch.cuda.synchronize()
+    index.hit_stats(reset=True)
+    index.set_tuning(scan_slices=slices, timing=timing)
+    index.stage_times(reset=True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        index.search_batch_dev(q, nprobe, k, out_ids, out_d, stream)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    st = index.stage_times(reset=True)
+    hs = index.hit_stats()
+    index.set_tuning(scan_slices=slices, timing=False)
+    res = {"elapsed": elapsed, "ms_per_step": 1e3 * elapsed / steps,
+           "qps": nq * steps / elapsed, "hit_rate": hs["mean_hit_rate"],
+           "min_hit_rate": hs["min_hit_rate"], "stage": st, "out_ids": out_ids, "out_d": out_d}
+    n_scan = st["launches"]["scan"]
+    if timing and n_scan > 0:
+        scan_ms = st["ms"]["scan"] / n_scan
+        res["scan_ms"] = scan_ms
+        res["scan_bytes_per_launch"] = st["scan_bytes"] / n_scan
+        res["scan_gbs"] = res["scan_bytes_per_launch"] / (scan_ms * 1e-3) / 1e9
+    res["stage_ms"] = {s: round(v / max(1, st["launches"][s]), 4) for s, v in st["ms"].items()}
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--mode", default="hotpath", choices=["hotpath", "sweep", "drift"])
     ap.add_argument("--workload", default="C3", help="spec name in synthdata.SPECS")
     ap.add_argument("--nq", type=int, default=None)
     ap.add_argument("--slices", type=int, default=0, help="scan blocks per query (0 = auto)")
@@ -51,9 +108,12 @@ def main():
     ap.add_argument("--oracle-sample", type=int, default=256)
     ap.add_argument("--no-oracle", action="store_true")
     ap.add_argument("--calib-copy", action="store_true",
-                    help="also launch one 1 GiB streaming copy kernel (counter calibration)")
+                    help="also launch one 1 GiB streaming copy and a few 1 GiB streaming read "
+                         "kernels (counter calibration / read ceiling)")
     ap.add_argument("--no-timing", action="store_true",
                     help="do not record per-kernel HIP events in the timed region")
+    ap.add_argument("--epochs", type=int, default=20, help="drift mode: epochs")
+    ap.add_argument("--epoch-queries", type=int, default=10000, help="drift mode: queries/epoch")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (no sharding, no collectives); "
@@ -78,78 +138,160 @@ def main():
     t0 = time.time()
     ix = build_index(spec, device="cuda:0", progress=log)
     centers = mixture_centers(spec, dev)
-    q, _ = make_queries(spec, centers, nq=nq)
-    calib, _ = make_queries(spec, centers, nq=max(nq, 1024), seed=spec.seed_calib)
-    q = q.contiguous()
     torch.cuda.synchronize()
-    log(f"index built in {time.time() - t0:.1f}s: N={ix.n} nlist={ix.nlist} M={ix.m}")
-
-    index = pkg.IvfIndex(ix, max_nq=max(nq, 1024), max_nprobe=spec.nprobe, max_k=spec.k)
+    build_s = time.time() - t0
+    log(f"index built in {build_s:.1f}s: N={ix.n} nlist={ix.nlist} M={ix.m}")
+    max_nq = max(nq, 4096 if args.mode == "sweep" else 1024)
+    index = pkg.IvfIndex(ix, max_nq=max_nq, max_nprobe=spec.nprobe, max_k=spec.k)
     t0 = time.time()
-    index.load_partition(np.arange(ix.nlist, dtype=np.int32))
+    all_clusters = np.arange(ix.nlist, dtype=np.int32)
+    index.load_partition(all_clusters)
     load_s = time.time() - t0
     log(f"loaded all clusters in {load_s:.2f}s ({index.arena_bytes / 2**30:.2f} GiB arena)")
+    calib, _ = make_queries(spec, centers, nq=4096, seed=spec.seed_calib)
+
+    workload = (f"{spec.name}: N={spec.n} D={spec.d} nlist={spec.nlist} PQ{spec.m}x8 "
+                f"{'IP' if spec.metric == 1 else 'L2'} nprobe={spec.nprobe} k={spec.k} "
+                f"zipf_s={spec.zipf_s}")
+
+    if args.mode == "sweep":
+        rows = []
+        for frac in (1.0, 0.5, 0.3, 0.1):
+            if frac < 1.0:
+                index.load_partition(all_clusters)
+                index.load_partition(hottest_clusters(index, calib, spec.nprobe, frac, ix.nlist))
+            for n in (256, 1024, 4096):
+                q, _ = make_queries(spec, centers, nq=n)
+                steps = args.steps if frac == 1.0 else max(2, args.steps // 10)
+                r = timed_steps(index, q.contiguous(), spec.nprobe, spec.k, steps,
+                                args.warmup if frac == 1.0 else 1, args.slices)
+                row = {"nq": n, "resident_fraction": frac, "queries_per_s": round(r["qps"], 1),
+                       "ms_per_step": round(r["ms_per_step"], 3),
+                       "mean_hit_rate": round(r["hit_rate"], 4),
+                       "min_hit_rate": round(r["min_hit_rate"], 4),
+                       "scan_ms": round(r.get("scan_ms", 0.0), 4),
+                       "scan_GBs": round(r.get("scan_gbs", 0.0), 1), "stage_ms": r["stage_ms"]}
+                log(json.dumps(row))
+                rows.append(row)
+        index.close()
+        print(json.dumps({"mode": "sweep", "workload": workload, "unit": "queries/s",
+                          "rows": rows}), flush=True)
+        return
+
+    if args.mode == "drift":
+        frac = args.resident if args.resident < 1.0 else 0.30
+        batch = 1024
+        side = torch.cuda.Stream(device=dev)
+        hot = hottest_clusters(index, calib, spec.nprobe, frac, ix.nlist)
+        index.load_partition(hot)
+        resident = set(hot.tolist())
+        per_epoch = []
+        mig_time = 0.0
+        total_q = 0
+        t_all = time.perf_counter()
+        perm_seed = spec.seed_perm
+        pending_t0 = None
+        for ep in range(args.epochs):
+            if ep % 5 == 0:
+                perm_seed = spec.seed_perm + ep
+            q_ep, _ = make_queries(spec, centers, nq=args.epoch_queries,
+                                   seed=spec.seed_queries + 1000 + ep, perm_seed=perm_seed)
+            q_host = q_ep.cpu().numpy()
+            index.hit_stats(reset=True)
+            t_ep = time.perf_counter()
+            for s in range(0, args.epoch_queries, batch):
+                index.search_batch(q_host[s:s + batch], spec.nprobe, spec.k)
+                if pending_t0 is not None and not index.migrate_poll()[0]:
+                    mig_time += time.perf_counter() - pending_t0
+                    pending_t0 = None
+            ep_s = time.perf_counter() - t_ep
+            total_q += args.epoch_queries
+            st = index.hit_stats(reset=True)
+            # recompute the hot set from this epoch's counters and migrate the difference
+            hits = st["per_cluster_hits"].astype(np.int64)
+            order = np.lexsort((np.arange(ix.nlist), -hits))
+            want = set(order[: len(hot)].tolist())
+            if pending_t0 is not None:
+                index.migrate_poll(wait=True)
+                mig_time += time.perf_counter() - pending_t0
+                pending_t0 = None
+            evict = sorted(resident - want)
+            admit = sorted(want - resident)
+            if evict or admit:
+                pending_t0 = time.perf_counter()
+                index.migrate_clusters(evict, admit, side_stream=side)
+                resident = want
+            row = {"epoch": ep, "queries_per_s": round(args.epoch_queries / ep_s, 1),
+                   "mean_hit_rate": round(st["mean_hit_rate"], 4),
+                   "min_hit_rate": round(st["min_hit_rate"], 4),
+                   "migrated_clusters": len(admit)}
+            log(json.dumps(row))
+            per_epoch.append(row)
+        if pending_t0 is not None:
+            index.migrate_poll(wait=True)
+            mig_time += time.perf_counter() - pending_t0
+        total_s = time.perf_counter() - t_all
+        _, mig_bytes = index.migrate_poll()
+        ms = index.migrate_stats()
+        index.close()
+        print(json.dumps({
+            "mode": "drift", "workload": workload, "resident_fraction": frac,
+            "batch": batch, "epochs": args.epochs, "queries": total_q,
+            "sustained_queries_per_s": round(total_q / total_s, 1),
+            "migration_bytes": int(mig_bytes),
+            "migration_bytes_per_s": round(ms["bytes"] / (ms["copy_ms"] * 1e-3), 1)
+            if ms["copy_ms"] > 0 else None,
+            "migration_copy_ms": round(ms["copy_ms"], 3), "migrations": ms["migrations"],
+            "migration_seconds_until_published": round(mig_time, 4),
+            "per_epoch": per_epoch}), flush=True)
+        return
+
+    # ---------------- default mode: the hot path ----------------
+    q, _ = make_queries(spec, centers, nq=nq)
+    q = q.contiguous()
     resident_frac = 1.0
     if args.resident < 1.0:
-        index.hit_stats(reset=True)
-        for s in range(0, calib.shape[0], index.max_nq):
-            index.search_batch_dev(calib[s:s + index.max_nq].contiguous(), spec.nprobe, 1)
-        torch.cuda.synchronize()
-        hits = index.hit_stats(reset=True)["per_cluster_hits"].astype(np.int64)
-        order = np.lexsort((np.arange(ix.nlist), -hits))
-        hot = np.sort(order[: int(round(args.resident * ix.nlist))]).astype(np.int32)
+        hot = hottest_clusters(index, calib, spec.nprobe, args.resident, ix.nlist)
         index.load_partition(hot)
         resident_frac = len(hot) / ix.nlist
 
-    index.set_tuning(scan_slices=args.slices, timing=False)
-    out_ids = torch.empty((nq, spec.k), dtype=torch.int64, device=dev)
-    out_d = torch.empty((nq, spec.k), dtype=torch.float32, device=dev)
-    stream = torch.cuda.current_stream(dev)
+    r = timed_steps(index, q, spec.nprobe, spec.k, args.steps, args.warmup, args.slices,
+                    timing=not args.no_timing)
+    out_ids, out_d = r["out_ids"], r["out_d"]
 
-    def step():
-        index.search_batch_dev(q, spec.nprobe, spec.k, out_ids, out_d, stream)
-
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    index.hit_stats(reset=True)
-    index.set_tuning(scan_slices=args.slices, timing=not args.no_timing)
-    index.stage_times(reset=True)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
-    st = index.stage_times(reset=True)
-    hs = index.hit_stats()
-    index.set_tuning(scan_slices=args.slices, timing=False)
-
+    read_ceiling = None
     if args.calib_copy:
-        from paper_2504_08930_amd.binding import ivf_calib_copy
+        from paper_2504_08930_amd.binding import ivf_calib_copy, ivf_calib_read
         src = torch.ones(1 << 28, dtype=torch.float32, device=dev)      # 1 GiB
         dst = torch.empty_like(src)
+        sink = torch.empty(1 << 20, dtype=torch.int32, device=dev)
+        stream = torch.cuda.current_stream(dev)
         torch.cuda.synchronize()
         ivf_calib_copy(src, dst, stream)
         torch.cuda.synchronize()
-        del src, dst
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        ivf_calib_read(src, sink, stream)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(5):
+            ivf_calib_read(src, sink, stream)
+        e1.record()
+        torch.cuda.synchronize()
+        read_ceiling = round(5 * (1 << 30) / (e0.elapsed_time(e1) * 1e-3) / 1e9, 1)
+        del src, dst, sink
 
-    ms_per_step = 1e3 * elapsed / args.steps
-    qps = nq * args.steps / elapsed
     roofline = None
-    if not args.no_timing and st["launches"]["scan"] > 0:
-        n_scan = st["launches"]["scan"]
-        scan_ms = st["ms"]["scan"] / n_scan
-        bytes_per_launch = st["scan_bytes"] / n_scan
-        achieved = bytes_per_launch / (scan_ms * 1e-3) / 1e9
-        roofline = {"bound": "hbm", "kernel": "k_scan", "achieved": round(achieved, 1),
-                    "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                    "traffic": None, "bytes_per_launch": int(bytes_per_launch),
-                    "avg_launch_ms": round(scan_ms, 4)}
+    if "scan_gbs" in r:
+        roofline = {"bound": "hbm", "kernel": "k_scan", "achieved": round(r["scan_gbs"], 1),
+                    "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                    "frac": round(r["scan_gbs"] / HBM_PEAK_GBS, 4), "traffic": None,
+                    "bytes_per_launch": int(r["scan_bytes_per_launch"]),
+                    "avg_launch_ms": round(r["scan_ms"], 4)}
         key = (spec.name, nq, round(resident_frac, 4))
         if key in MEASURED_TRAFFIC and args.slices == 0:
             roofline["traffic"], roofline["traffic_source"] = MEASURED_TRAFFIC[key]
-    stage_ms = {k: round(v / max(1, st["launches"][k]), 4) for k, v in st["ms"].items()}
+        if read_ceiling is not None:
+            roofline["streaming_read_GBs"] = read_ceiling
 
     cpu_baseline = None
     parity = None
@@ -185,28 +327,26 @@ def main():
 
     out = {
         "metric": METRIC,
-        "value": round(qps, 1),
+        "value": round(r["qps"], 1),
         "unit": "queries/s",
         "n_gpus": 1,
         "steps": args.steps,
         "warmup": args.warmup,
-        "ms_per_step": round(ms_per_step, 4),
+        "ms_per_step": round(r["ms_per_step"], 4),
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "f32 table, i32 accumulate",
+        "dtype": "bf16x3 coarse contraction, f32 table, i32 accumulate",
         "data": "synthetic",
-        "config": {"workload": f"{spec.name}: N={spec.n} D={spec.d} nlist={spec.nlist} "
-                               f"PQ{spec.m}x8 IP nq={nq} nprobe={spec.nprobe} k={spec.k} "
-                               f"zipf_s={spec.zipf_s}",
+        "config": {"workload": f"{workload} nq={nq}",
                    "resident_fraction": round(resident_frac, 4),
-                   "mean_hit_rate": round(hs["mean_hit_rate"], 4),
+                   "mean_hit_rate": round(r["hit_rate"], 4),
                    "scan_slices": args.slices, "inputs": "device-resident queries"},
         "roofline": roofline,
         "cpu_baseline": cpu_baseline,
-        "stage_ms": stage_ms,
+        "stage_ms": r["stage_ms"],
         "parity": parity,
-        "index_build_s": None,
+        "index_build_s": round(build_s, 2),
         "load_partition_s": round(load_s, 3),
     }
     index.close()

@@ -197,6 +197,15 @@ int ivf_migrate_clusters(ivf_index_t *index, const int32_t *evict, int32_t n_evi
  */
 int ivf_migrate_poll(ivf_index_t *index, int wait, uint64_t *bytes_copied);
 
+/*
+ * Totals over migrations completed since creation (any output may be NULL):
+ * bytes_copied as in ivf_migrate_poll; copy_ms = time between the first copy
+ * and the last kernel of each migration on its side stream, from HIP events;
+ * n_migrations = completed migrations.  All HOST pointers.
+ */
+int ivf_migrate_stats(ivf_index_t *index, uint64_t *bytes_copied, double *copy_ms,
+                      uint64_t *n_migrations);
+
 /* Number of currently resident clusters and vectors (either may be NULL). */
 int ivf_resident_info(ivf_index_t *index, int32_t *n_clusters, int64_t *n_vectors);
 
@@ -232,6 +241,14 @@ int ivf_stage_times(ivf_index_t *index, double *ms, uint64_t *launches, uint64_t
  * known traffic calibrates hardware byte counters.  Asynchronous on `stream`.
  */
 int ivf_calib_copy(const void *src, void *dst, size_t bytes, void *stream);
+
+/*
+ * Instrumentation aid: a plain streaming read of `bytes` from src (DEVICE,
+ * 16-byte aligned, bytes a multiple of 16); sink is DEVICE scratch of at least
+ * 2 MiB that receives one word per thread.  Its rate is the achievable read
+ * bandwidth, the practical ceiling of the ADC scan.  Asynchronous on `stream`.
+ */
+int ivf_calib_read(const void *src, void *sink, size_t bytes, void *stream);
 
 /* Message for the last error returned on this thread ("" if none). */
 const char *ivf_last_error(void);

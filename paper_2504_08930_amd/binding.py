@@ -21,8 +21,8 @@ EXPORTS = (
     "ivf_index_arena_bytes", "ivf_index_create", "ivf_index_destroy",
     "ivf_index_load_partition", "ivf_search_batch", "ivf_search_batch_dev",
     "ivf_coarse_probe_dev", "ivf_search_batch_probes", "ivf_hit_stats",
-    "ivf_migrate_clusters", "ivf_migrate_poll", "ivf_resident_info",
-    "ivf_set_tuning", "ivf_stage_times", "ivf_calib_copy", "ivf_last_error",
+    "ivf_migrate_clusters", "ivf_migrate_poll", "ivf_migrate_stats", "ivf_resident_info",
+    "ivf_set_tuning", "ivf_stage_times", "ivf_calib_copy", "ivf_calib_read", "ivf_last_error",
 )
 
 
@@ -69,10 +69,12 @@ def load_library():
     lib.ivf_hit_stats.argtypes = [P, P, P, P, P, ctypes.c_int]
     lib.ivf_migrate_clusters.argtypes = [P, P, I32, P, I32, P]
     lib.ivf_migrate_poll.argtypes = [P, ctypes.c_int, P]
+    lib.ivf_migrate_stats.argtypes = [P, P, P, P]
     lib.ivf_resident_info.argtypes = [P, P, P]
     lib.ivf_set_tuning.argtypes = [P, I32, I32]
     lib.ivf_stage_times.argtypes = [P, P, P, P, ctypes.c_int]
     lib.ivf_calib_copy.argtypes = [P, P, SZ, P]
+    lib.ivf_calib_read.argtypes = [P, P, SZ, P]
     lib.ivf_last_error.argtypes = []
     lib.ivf_last_error.restype = ctypes.c_char_p
     for name in EXPORTS:
@@ -95,6 +97,15 @@ def ivf_calib_copy(src, dst, stream=None):
     st = None if stream is None else ctypes.c_void_p(stream.cuda_stream)
     _check(load_library().ivf_calib_copy(ctypes.c_void_p(src.data_ptr()),
                                          ctypes.c_void_p(dst.data_ptr()), nbytes, st))
+
+
+def ivf_calib_read(src, sink, stream=None):
+    """Streaming read of torch tensor src; sink: device tensor of >= 2 MiB."""
+    nbytes = src.numel() * src.element_size()
+    assert sink.numel() * sink.element_size() >= (2 << 20)
+    st = None if stream is None else ctypes.c_void_p(stream.cuda_stream)
+    _check(load_library().ivf_calib_read(ctypes.c_void_p(src.data_ptr()),
+                                         ctypes.c_void_p(sink.data_ptr()), nbytes, st))
 
 
 def _np_ptr(a):
@@ -192,6 +203,12 @@ class IvfIndex:
         nbytes = ctypes.c_uint64(0)
         rc = _check(self._lib.ivf_migrate_poll(self._h, int(bool(wait)), ctypes.byref(nbytes)))
         return rc == 1, nbytes.value
+
+    def migrate_stats(self):
+        nbytes, ms, n = ctypes.c_uint64(0), ctypes.c_double(0), ctypes.c_uint64(0)
+        _check(self._lib.ivf_migrate_stats(self._h, ctypes.byref(nbytes), ctypes.byref(ms),
+                                           ctypes.byref(n)))
+        return {"bytes": nbytes.value, "copy_ms": ms.value, "migrations": n.value}
 
     def resident_info(self):
         nc, nv = ctypes.c_int32(0), ctypes.c_int64(0)

@@ -111,6 +111,7 @@ struct Version {
 struct Migration {
   bool active = false;
   hipStream_t stream = nullptr;
+  hipEvent_t begin = nullptr;   // timing pair around the copies on the side stream
   hipEvent_t done = nullptr;
   std::vector<int32_t> new_map;
   std::vector<Extent> evicted;
@@ -144,6 +145,8 @@ struct ivf_index {
   int64_t resident_vectors = 0;
   Migration mig;
   uint64_t bytes_migrated = 0;
+  double migrate_ms = 0.0;      // device time of completed migrations' copies
+  uint64_t n_migrations = 0;
   std::vector<hipEvent_t> event_pool;
 
   // host-only counters (device-less index)
@@ -215,6 +218,8 @@ static size_t plan_layout(const ivf_index_desc_t &d, int64_t resident_vectors, s
   DevLayout t;
   t.centroids = (float *)take(nl * D * 4);
   t.cent_norm = (float *)take(nl * 4);
+  t.cent_parts = take(nl * D * 6);
+  t.q_parts = take(nq * D * 6);
   t.cbT = (float *)take(256 * D * 4);
   t.clus_len = (int32_t *)take(nl * 4);
   for (int i = 0; i < 3; ++i) t.clus_tile[i] = (int32_t *)take(nl * 4);
@@ -275,6 +280,7 @@ extern "C" void ivf_index_destroy(ivf_index_t *ix) {
   if (ix->has_dev) {
     (void)hipDeviceSynchronize();
     if (ix->mig.active) {
+      if (ix->mig.begin) (void)hipEventDestroy(ix->mig.begin);
       if (ix->mig.done) (void)hipEventDestroy(ix->mig.done);
       if (ix->mig.pinned_map) (void)hipHostFree(ix->mig.pinned_map);
       if (ix->mig.pinned_descs) (void)hipHostFree(ix->mig.pinned_descs);
@@ -392,7 +398,9 @@ extern "C" int ivf_index_create(const ivf_index_desc_t *desc, void *dev_arena, s
       (e = launch_fill_u32((uint32_t *)L.qstats, QS_COUNT * 2, 0u, st)) != hipSuccess ||
       (e = launch_fill_u32((uint32_t *)&L.qstats[QS_MIN_RATE_BITS], 1, 0x3f800000u, st)) !=
           hipSuccess ||
-      (e = launch_cent_norms(L.centroids, desc->nlist, desc->d, L.cent_norm, st)) != hipSuccess)
+      (e = launch_cent_norms(L.centroids, desc->nlist, desc->d, L.cent_norm, st)) != hipSuccess ||
+      (e = launch_split_bf16(L.centroids, (size_t)desc->nlist, desc->d, L.cent_parts, st)) !=
+          hipSuccess)
     return bail(e, "init kernels");
   if ((e = hipStreamSynchronize(st)) != hipSuccess) return bail(e, "hipStreamSynchronize");
   *out = ix;
@@ -628,6 +636,12 @@ static int publish_if_done_locked(ivf_index *ix, bool wait) {
   ix->resident_clusters += m.d_clusters;
   ix->resident_vectors += m.d_vectors;
   ix->bytes_migrated += m.bytes;
+  {
+    float ms = 0.f;
+    if (hipEventElapsedTime(&ms, m.begin, m.done) == hipSuccess) ix->migrate_ms += ms;
+    ix->n_migrations += 1;
+  }
+  (void)hipEventDestroy(m.begin);
   (void)hipEventDestroy(m.done);
   (void)hipHostFree(m.pinned_map);
   if (m.pinned_descs) (void)hipHostFree(m.pinned_descs);
@@ -707,15 +721,20 @@ extern "C" int ivf_migrate_clusters(ivf_index_t *ix, const int32_t *evict, int32
   }
   hipError_t e = pinned_alloc(&m.pinned_map, (size_t)ix->sh.nlist);
   if (e == hipSuccess && need_tiles > 0) e = pinned_alloc(&m.pinned_descs, (size_t)need_tiles);
-  if (e == hipSuccess) e = hipEventCreateWithFlags(&m.done, hipEventDisableTiming);
+  if (e == hipSuccess) e = hipEventCreate(&m.begin);
+  if (e == hipSuccess) e = hipEventCreate(&m.done);
   if (e != hipSuccess) {
     undo();
+    if (m.begin) (void)hipEventDestroy(m.begin);
+    if (m.done) (void)hipEventDestroy(m.done);
     if (m.pinned_map) (void)hipHostFree(m.pinned_map);
     if (m.pinned_descs) (void)hipHostFree(m.pinned_descs);
     return fail(IVF_EDEVICE, "migration setup: %s", hipGetErrorString(e));
   }
   memcpy(m.pinned_map, m.new_map.data(), (size_t)ix->sh.nlist * 4);
-  rc = enqueue_cluster_copies(ix, clusters, bases, m.pinned_descs, st);
+  e = hipEventRecord(m.begin, st);
+  rc = e == hipSuccess ? enqueue_cluster_copies(ix, clusters, bases, m.pinned_descs, st)
+                       : fail(IVF_EDEVICE, "migration enqueue: %s", hipGetErrorString(e));
   if (rc == IVF_OK) {
     e = hipMemcpyAsync(ix->L.clus_tile[target], m.pinned_map, (size_t)ix->sh.nlist * 4,
                        hipMemcpyHostToDevice, st);
@@ -726,6 +745,7 @@ extern "C" int ivf_migrate_clusters(ivf_index_t *ix, const int32_t *evict, int32
     // admitted clusters stay cold; whatever was enqueued only touches free tiles
     (void)hipStreamSynchronize(st);
     undo();
+    (void)hipEventDestroy(m.begin);
     (void)hipEventDestroy(m.done);
     (void)hipHostFree(m.pinned_map);
     if (m.pinned_descs) (void)hipHostFree(m.pinned_descs);
@@ -733,6 +753,16 @@ extern "C" int ivf_migrate_clusters(ivf_index_t *ix, const int32_t *evict, int32
   }
   m.active = true;
   ix->mig = std::move(m);
+  return IVF_OK;
+}
+
+extern "C" int ivf_migrate_stats(ivf_index_t *ix, uint64_t *bytes_copied, double *copy_ms,
+                                 uint64_t *n_migrations) {
+  if (!ix) return fail(IVF_EINVAL, "index is NULL");
+  std::lock_guard<std::mutex> lk(ix->mu);
+  if (bytes_copied) *bytes_copied = ix->bytes_migrated;
+  if (copy_ms) *copy_ms = ix->migrate_ms;
+  if (n_migrations) *n_migrations = ix->n_migrations;
   return IVF_OK;
 }
 
@@ -988,7 +1018,8 @@ static int search_device(ivf_index *ix, const SearchArgs &a) {
     S_TRY(hipMemcpyAsync(L.probe, ix->h_probe, (size_t)nq * np * 4, hipMemcpyHostToDevice, st));
   } else {
     S_TRY(mark(IVF_STAGE_COARSE_GEMM));
-    S_TRY(launch_coarse_gemm(sh, dq, nq, L.centroids, L.cent_norm, L.scores, st));
+    S_TRY(launch_split_bf16(dq, (size_t)nq, sh.d, L.q_parts, st));
+    S_TRY(launch_coarse_gemm(sh, L.q_parts, nq, L.cent_parts, L.cent_norm, L.scores, st));
     S_TRY(mark(IVF_STAGE_COARSE_SELECT));
     S_TRY(launch_coarse_select(sh, L.scores, nq, np, np, L.probe, st));
   }
@@ -1164,7 +1195,8 @@ extern "C" int ivf_coarse_probe_dev(ivf_index_t *ix, const float *queries, int64
       ix->async_pending = false;
     }
   }
-  HIP_TRY(launch_coarse_gemm(ix->sh, queries, (int)nq, ix->L.centroids, ix->L.cent_norm,
+  HIP_TRY(launch_split_bf16(queries, (size_t)nq, ix->sh.d, ix->L.q_parts, st));
+  HIP_TRY(launch_coarse_gemm(ix->sh, ix->L.q_parts, (int)nq, ix->L.cent_parts, ix->L.cent_norm,
                              ix->L.scores, st));
   HIP_TRY(launch_coarse_select(ix->sh, ix->L.scores, (int)nq, nprobe, nprobe, out_probe, st));
   {
@@ -1214,5 +1246,11 @@ extern "C" int ivf_search_batch_probes(ivf_index_t *ix, const float *queries, in
 extern "C" int ivf_calib_copy(const void *src, void *dst, size_t bytes, void *stream) {
   if (!src || !dst || bytes % 16 != 0) return fail(IVF_EINVAL, "calib copy: bad arguments");
   HIP_TRY(launch_calib_copy(src, dst, bytes, (hipStream_t)stream));
+  return IVF_OK;
+}
+
+extern "C" int ivf_calib_read(const void *src, void *sink, size_t bytes, void *stream) {
+  if (!src || !sink || bytes % 16 != 0) return fail(IVF_EINVAL, "calib read: bad arguments");
+  HIP_TRY(launch_calib_read(src, sink, bytes, (hipStream_t)stream));
   return IVF_OK;
 }

@@ -35,6 +35,8 @@ struct TileDesc {
 struct DevLayout {
   float *centroids;        // [nlist][d]
   float *cent_norm;        // [nlist] squared norms (L2 only)
+  void *cent_parts;        // centroids as a three-way bf16 split, 6 B per element
+  void *q_parts;           // [max_nq][d] queries, same split
   float *cbT;              // [256][M][dsub] transposed codebooks
   int32_t *clus_len;       // [nlist]
   int32_t *clus_tile[3];   // mapping table ring: first tile of a resident cluster, or -1
@@ -75,10 +77,15 @@ struct Shape {
 hipError_t launch_fill_u32(uint32_t *p, size_t n, uint32_t v, hipStream_t st);
 
 hipError_t launch_calib_copy(const void *src, void *dst, size_t bytes, hipStream_t st);
+// sink: at least 2 MiB (one word per launched thread)
+hipError_t launch_calib_read(const void *src, void *sink, size_t bytes, hipStream_t st);
 
 hipError_t launch_cent_norms(const float *cent, int nlist, int d, float *out, hipStream_t st);
 
-hipError_t launch_coarse_gemm(const Shape &sh, const float *q, int nq, const float *cent,
+// fp32 [rows][d] -> three-way bf16 split, 6 bytes per element
+hipError_t launch_split_bf16(const float *src, size_t rows, int d, void *dst, hipStream_t st);
+
+hipError_t launch_coarse_gemm(const Shape &sh, const void *q_parts, int nq, const void *cent_parts,
                               const float *cent_norm, float *scores, hipStream_t st);
 
 hipError_t launch_coarse_select(const Shape &sh, const float *scores, int nq, int nprobe,

@@ -1,7 +1,7 @@
 // Stage 1 of IVF search (Section 2.2): coarse quantization.  Every query is
-// scored against every centroid as a dense contraction on the fp32 matrix
-// cores (v_mfma_f32_32x32x2f32), then the nprobe best clusters per query are
-// selected exactly by a radix select over (score, cluster id).
+// scored against every centroid as a dense contraction on the matrix cores
+// (split-bf16 MFMA at fp32 accuracy), then the nprobe best clusters per query
+// are selected exactly by a radix select over (score, cluster id).
 //
 // The paper keeps this stage on the CPU to avoid ping-pong between devices
 // when several GPU shards are used (Section 4.2.1); with one GPU that concern
@@ -38,47 +38,111 @@ hipError_t launch_cent_norms(const float *cent, int nlist, int d, float *out, hi
 }
 
 // ---------------------------------------------------------------------------
+// Three-way bf16 split of an fp32 matrix: x = h1 + h2 + h3 exactly (each part
+// is the bf16 rounding of what the previous parts left over; 3 x 8 significand
+// bits cover fp32's 24).  Output layout, chunk-major so that the K = 16 chunk
+// of a 128-row tile is one contiguous 12 KB block: for row r and group g of 8
+// consecutive k, three 16-byte units (parts 1, 2, 3) at unit index
+// ((g / 2) * rows + r) * 6 + (g % 2) * 3 + part.
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ uint32_t bf16_rne_bits(float x) {
+  const uint32_t u = __float_as_uint(x);
+  return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+}
+
+__global__ void k_split_bf16(const float *__restrict__ src, size_t rows, int groups_per_row,
+                             uint4 *__restrict__ dst) {
+  const size_t g = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (g >= rows * (size_t)groups_per_row) return;
+  const size_t row = g / groups_per_row;
+  const int gr = (int)(g % groups_per_row);
+  const size_t out = ((size_t)(gr >> 1) * rows + row) * 6 + (size_t)(gr & 1) * 3;
+  const float4 lo = reinterpret_cast<const float4 *>(src)[g * 2];
+  const float4 hi = reinterpret_cast<const float4 *>(src)[g * 2 + 1];
+  const float x[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+  uint32_t part[3][8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    float r = x[i];
+#pragma unroll
+    for (int p = 0; p < 3; ++p) {
+      const uint32_t h = bf16_rne_bits(r);
+      part[p][i] = h;
+      r -= __uint_as_float(h << 16);  // exact in fp32
+    }
+  }
+#pragma unroll
+  for (int p = 0; p < 3; ++p)
+    dst[out + p] = make_uint4(part[p][0] | (part[p][1] << 16), part[p][2] | (part[p][3] << 16),
+                                part[p][4] | (part[p][5] << 16), part[p][6] | (part[p][7] << 16));
+}
+
+hipError_t launch_split_bf16(const float *src, size_t rows, int d, void *dst, hipStream_t st) {
+  const size_t n_groups = rows * (size_t)(d / 8);
+  if (n_groups == 0) return hipSuccess;
+  hipLaunchKernelGGL(k_split_bf16, dim3((unsigned)((n_groups + 255) / 256)), dim3(256), 0, st, src,
+                     rows, d / 8, (uint4 *)dst);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
 // scores[q][c] = q . c            (IP, larger is better)
 //              = |c|^2 - 2 q . c  (L2, smaller is better)
+//
+// The contraction runs on the bf16 matrix cores at fp32 accuracy: with
+// q = q1+q2+q3 and c = c1+c2+c3 (three-way bf16 splits), q.c is accumulated in
+// fp32 from the six products q1c1, q1c2, q2c1, q1c3, q2c2, q3c1; the three
+// dropped products are below 2^-23 relative.  Six v_mfma_f32_32x32x16_bf16
+// cost 6/16 of the fp32 MFMA work for the same K.
+//
 // 128 x 128 block tile, 4 waves in a 2 x 2 arrangement, each wave 64 x 64 as
-// 2 x 2 MFMA tiles of 32 x 32; K is consumed 16 at a time through LDS.
+// 2 x 2 MFMA tiles of 32 x 32; K is consumed 16 at a time through LDS (per
+// row: 2 groups x 3 parts x 16 B).  Blocks are numbered so that the row tiles
+// sharing a centroid tile run next to each other on one XCD (block id mod 8
+// picks the XCD), which keeps each centroid tile in that XCD's L2.
 // ---------------------------------------------------------------------------
-constexpr int kBM = 128, kBN = 128, kBK = 16, kLdk = kBK + 4;
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+constexpr int kBM = 128, kBN = 128;
+constexpr int kRowBytes = 112;  // 96 B of data per row and chunk, padded: conflict-free b128 reads
 
-__global__ __launch_bounds__(256) void k_coarse_gemm(const float *__restrict__ Q, int nq,
-                                                     const float *__restrict__ C, int nlist, int d,
+__global__ __launch_bounds__(256) void k_coarse_gemm(const uint4 *__restrict__ Qp, int nq,
+                                                     const uint4 *__restrict__ Cp, int nlist, int d,
                                                      const float *__restrict__ cnorm, int metric_ip,
+                                                     int row_tiles, int col_tiles,
                                                      float *__restrict__ scores) {
-  __shared__ __align__(16) float As[2][kBM * kLdk];
-  __shared__ __align__(16) float Bs[2][kBN * kLdk];
+  __shared__ __align__(16) unsigned char As[2][kBM * kRowBytes];
+  __shared__ __align__(16) unsigned char Bs[2][kBN * kRowBytes];
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = tid >> 6;
   const int wm = wave >> 1, wn = wave & 1;
-  const int row0 = blockIdx.y * kBM;   // queries
-  const int col0 = blockIdx.x * kBN;   // centroids
+  // XCD-aware tile assignment
+  const int xcd = blockIdx.x & 7, j = blockIdx.x >> 3;
+  const int ct = (j / row_tiles) * 8 + xcd, rt = j % row_tiles;
+  if (ct >= col_tiles) return;
+  const int row0 = rt * kBM;   // queries
+  const int col0 = ct * kBN;   // centroids
 
-  // global -> LDS assignment: float4 f = tid + 256 * i, row = f / 4, c4 = f % 4
-  float4 ga[2], gb[2];
-  auto gload = [&](int k0) {
+  // global -> LDS: unit f = tid + 256 * i (i < 3), row = f / 6, u = f % 6.  Loads run
+  // two chunks ahead of the MFMAs (register stage), stores one chunk ahead (LDS stage).
+  uint4 ga[2][3], gb[2][3];
+  auto gload = [&](int kc, int slot) {
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
+    for (int i = 0; i < 3; ++i) {
       const int f = tid + 256 * i;
-      const int r = f >> 2, c4 = f & 3;
+      const int r = f / 6, u = f % 6;
       const int qa = row0 + r, cb = col0 + r;
-      ga[i] = qa < nq ? *reinterpret_cast<const float4 *>(Q + (size_t)qa * d + k0 + c4 * 4)
-                      : make_float4(0.f, 0.f, 0.f, 0.f);
-      gb[i] = cb < nlist ? *reinterpret_cast<const float4 *>(C + (size_t)cb * d + k0 + c4 * 4)
-                         : make_float4(0.f, 0.f, 0.f, 0.f);
+      ga[slot][i] = qa < nq ? Qp[((size_t)kc * nq + qa) * 6 + u] : make_uint4(0, 0, 0, 0);
+      gb[slot][i] = cb < nlist ? Cp[((size_t)kc * nlist + cb) * 6 + u] : make_uint4(0, 0, 0, 0);
     }
   };
-  auto sstore = [&](int buf) {
+  auto sstore = [&](int buf, int slot) {
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
+    for (int i = 0; i < 3; ++i) {
       const int f = tid + 256 * i;
-      const int r = f >> 2, c4 = f & 3;
-      *reinterpret_cast<float4 *>(&As[buf][r * kLdk + c4 * 4]) = ga[i];
-      *reinterpret_cast<float4 *>(&Bs[buf][r * kLdk + c4 * 4]) = gb[i];
+      const int r = f / 6, u = f % 6;
+      *reinterpret_cast<uint4 *>(&As[buf][r * kRowBytes + u * 16]) = ga[slot][i];
+      *reinterpret_cast<uint4 *>(&Bs[buf][r * kRowBytes + u * 16]) = gb[slot][i];
     }
   };
 
@@ -90,40 +154,49 @@ __global__ __launch_bounds__(256) void k_coarse_gemm(const float *__restrict__ Q
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.0f;
 
-  const int nk = d / kBK;  // d is a multiple of 16
-  gload(0);
-  sstore(0);
+  const int nk = d / 16;  // d is a multiple of 16
+  gload(0, 0);
+  sstore(0, 0);
+  if (nk > 1) gload(1, 1);
   __syncthreads();
   const int li = lane & 31, kk = lane >> 5;
-  for (int kc = 0; kc < nk; ++kc) {
+  // unrolled by two so the register stage index is a compile-time constant
+  auto step = [&](int kc, int slot_next, int slot_far) {
     const int buf = kc & 1;
-    if (kc + 1 < nk) gload((kc + 1) * kBK);
-    // lane (li, kk) feeds k = kk*8 + s at MFMA step s: A and B use the same
-    // permutation of k, so the contraction is unchanged.
-    float a[2][8], b[2][8];
+    if (kc + 2 < nk) gload(kc + 2, slot_far);
+    // lane (li, kk) holds k = 8*kk .. 8*kk+7 of the chunk for row li of a tile
+    bf16x8 a[2][3], b[2][3];
 #pragma unroll
     for (int t = 0; t < 2; ++t) {
-      const float *pa = &As[buf][(wm * 64 + t * 32 + li) * kLdk + kk * 8];
-      const float *pb = &Bs[buf][(wn * 64 + t * 32 + li) * kLdk + kk * 8];
-      const float4 a0 = *reinterpret_cast<const float4 *>(pa);
-      const float4 a1 = *reinterpret_cast<const float4 *>(pa + 4);
-      const float4 b0 = *reinterpret_cast<const float4 *>(pb);
-      const float4 b1 = *reinterpret_cast<const float4 *>(pb + 4);
-      a[t][0] = a0.x; a[t][1] = a0.y; a[t][2] = a0.z; a[t][3] = a0.w;
-      a[t][4] = a1.x; a[t][5] = a1.y; a[t][6] = a1.z; a[t][7] = a1.w;
-      b[t][0] = b0.x; b[t][1] = b0.y; b[t][2] = b0.z; b[t][3] = b0.w;
-      b[t][4] = b1.x; b[t][5] = b1.y; b[t][6] = b1.z; b[t][7] = b1.w;
+#pragma unroll
+      for (int p = 0; p < 3; ++p) {
+        a[t][p] = __builtin_bit_cast(
+            bf16x8, *reinterpret_cast<const uint4 *>(
+                        &As[buf][(wm * 64 + t * 32 + li) * kRowBytes + (kk * 3 + p) * 16]));
+        b[t][p] = __builtin_bit_cast(
+            bf16x8, *reinterpret_cast<const uint4 *>(
+                        &Bs[buf][(wn * 64 + t * 32 + li) * kRowBytes + (kk * 3 + p) * 16]));
+      }
     }
 #pragma unroll
-    for (int s = 0; s < 8; ++s)
+    for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
-      for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-        for (int nt = 0; nt < 2; ++nt)
-          acc[mt][nt] =
-              __builtin_amdgcn_mfma_f32_32x32x2f32(a[mt][s], b[nt][s], acc[mt][nt], 0, 0, 0);
-    if (kc + 1 < nk) sstore(buf ^ 1);
+      for (int nt = 0; nt < 2; ++nt) {
+        floatx16 c = acc[mt][nt];
+        c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[mt][2], b[nt][0], c, 0, 0, 0);
+        c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[mt][1], b[nt][1], c, 0, 0, 0);
+        c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[mt][0], b[nt][2], c, 0, 0, 0);
+        c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[mt][1], b[nt][0], c, 0, 0, 0);
+        c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[mt][0], b[nt][1], c, 0, 0, 0);
+        c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[mt][0], b[nt][0], c, 0, 0, 0);
+        acc[mt][nt] = c;
+      }
+    if (kc + 1 < nk) sstore(buf ^ 1, slot_next);
     __syncthreads();
+  };
+  for (int kc = 0; kc < nk; kc += 2) {
+    step(kc, 1, 0);          // chunk kc+1 sits in slot 1; chunk kc+2 goes to slot 0
+    if (kc + 1 < nk) step(kc + 1, 0, 1);
   }
 
   // D[i][j]: register r of lane l holds i = 8*(r/4) + 4*(l/32) + r%4, j = l%32
@@ -144,11 +217,14 @@ __global__ __launch_bounds__(256) void k_coarse_gemm(const float *__restrict__ Q
     }
 }
 
-hipError_t launch_coarse_gemm(const Shape &sh, const float *q, int nq, const float *cent,
+hipError_t launch_coarse_gemm(const Shape &sh, const void *q_parts, int nq, const void *cent_parts,
                               const float *cent_norm, float *scores, hipStream_t st) {
-  dim3 grid((sh.nlist + kBN - 1) / kBN, (nq + kBM - 1) / kBM);
-  hipLaunchKernelGGL(k_coarse_gemm, grid, dim3(256), 0, st, q, nq, cent, sh.nlist, sh.d,
-                     cent_norm, sh.metric_ip, scores);
+  const int row_tiles = (nq + kBM - 1) / kBM;
+  const int col_tiles = (sh.nlist + kBN - 1) / kBN;
+  const int grid = 8 * ((col_tiles + 7) / 8) * row_tiles;
+  hipLaunchKernelGGL(k_coarse_gemm, dim3(grid), dim3(256), 0, st, (const uint4 *)q_parts, nq,
+                     (const uint4 *)cent_parts, sh.nlist, sh.d, cent_norm, sh.metric_ip, row_tiles,
+                     col_tiles, scores);
   return hipGetLastError();
 }
 

@@ -100,11 +100,41 @@ __global__ void k_calib_copy(const uint4 *__restrict__ src, uint4 *__restrict__ 
   for (; i < n; i += step) dst[i] = src[i];
 }
 
+// Plain streaming read (each thread folds what it reads into one word and
+// stores it once): the achievable read bandwidth of the machine, the practical
+// ceiling for the scan.
+__global__ void k_calib_read(const uint4 *__restrict__ src, size_t n, uint32_t *__restrict__ sink) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const size_t step = (size_t)gridDim.x * blockDim.x;
+  uint32_t acc = 0;
+  for (; i + 3 * step < n; i += 4 * step) {
+    const uint4 a = src[i], b = src[i + step], c = src[i + 2 * step], d = src[i + 3 * step];
+    acc ^= a.x ^ a.y ^ a.z ^ a.w ^ b.x ^ b.y ^ b.z ^ b.w ^ c.x ^ c.y ^ c.z ^ c.w ^ d.x ^ d.y ^
+           d.z ^ d.w;
+  }
+  for (; i < n; i += step) {
+    const uint4 a = src[i];
+    acc ^= a.x ^ a.y ^ a.z ^ a.w;
+  }
+  sink[(size_t)blockIdx.x * blockDim.x + threadIdx.x] = acc;
+}
+
+constexpr int kCalibBlocks = 256 * 8, kCalibThreads = 256;
+
 hipError_t launch_calib_copy(const void *src, void *dst, size_t bytes, hipStream_t st) {
   const size_t n = bytes / 16;
   if (n == 0) return hipSuccess;
-  hipLaunchKernelGGL(k_calib_copy, dim3(256 * 8), dim3(256), 0, st, (const uint4 *)src,
-                     (uint4 *)dst, n);
+  if (src == dst || bytes < (size_t)kCalibBlocks * kCalibThreads * 4) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(k_calib_copy, dim3(kCalibBlocks), dim3(kCalibThreads), 0, st,
+                     (const uint4 *)src, (uint4 *)dst, n);
+  return hipGetLastError();
+}
+
+hipError_t launch_calib_read(const void *src, void *sink, size_t bytes, hipStream_t st) {
+  const size_t n = bytes / 16;
+  if (n == 0) return hipSuccess;
+  hipLaunchKernelGGL(k_calib_read, dim3(kCalibBlocks), dim3(kCalibThreads), 0, st,
+                     (const uint4 *)src, n, (uint32_t *)sink);
   return hipGetLastError();
 }
 

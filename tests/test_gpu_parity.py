@@ -202,6 +202,8 @@ def test_migration_keeps_results(pkg, oracle):
         got_probe = index.coarse_probe_dev(torch.from_numpy(q).cuda(), spec.nprobe).cpu().numpy()
         _, ref_rate = oracle.hit_stats(ix.nlist, got_probe, mask)
         assert abs(index.hit_stats()["mean_hit_rate"] - ref_rate.mean()) < 1e-9
+    ms = index.migrate_stats()
+    assert ms["bytes"] == total and ms["migrations"] == 4 and ms["copy_ms"] > 0.0
     # errors leave the state unchanged
     with pytest.raises(pkg.IvfError):
         index.migrate_clusters([int(b[-1])], [])          # not resident
