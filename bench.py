@@ -57,25 +57,35 @@ def hottest_clusters(index, calib, nprobe, frac, nlist):
     return np.sort(order[: int(round(frac * nlist))]).astype(np.int32)
 
 
-def timed_steps(index, q, nprobe, k, steps, warmup, slices, timing=True):
-    """Warm up, then time `steps` searches of the device-resident batch q."""
+def timed_steps(index, q, nprobe, k, steps, warmup, slices, timing=True, n_streams=1):
+    """Warm up, then time `steps` searches of the device-resident batch q.  With
+    n_streams = 2 consecutive steps go to alternating streams (the library keeps
+    one workspace per stream), so one batch's coarse stage can overlap the
+    previous batch's scan; every step still does the whole path."""
     import torch
     dev = q.device
     nq = q.shape[0]
-    out_ids = torch.empty((nq, k), dtype=torch.int64, device=dev)
-    out_d = torch.empty((nq, k), dtype=torch.float32, device=dev)
-    stream = torch.cuda.current_stream(dev)
+    if n_streams <= 1:
+        streams = [torch.cuda.current_stream(dev)]
+    else:
+        streams = [torch.cuda.Stream(device=dev) for _ in range(n_streams)]
+    outs = [(torch.empty((nq, k), dtype=torch.int64, device=dev),
+             torch.empty((nq, k), dtype=torch.float32, device=dev)) for _ in streams]
+    out_ids, out_d = outs[0]
     index.set_tuning(scan_slices=slices, timing=False)
-    for _ in range(warmup):
-        index.search_batch_dev(q, nprobe, k, out_ids, out_d, stream)
+    torch.cuda.synchronize()
+    for i in range(warmup):
+        j = i % len(streams)
+        index.search_batch_dev(q, nprobe, k, outs[j][0], outs[j][1], streams[j])
     torch.cuda.synchronize()
     index.hit_stats(reset=True)
     index.set_tuning(scan_slices=slices, timing=timing)
     index.stage_times(reset=True)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(steps):
-        index.search_batch_dev(q, nprobe, k, out_ids, out_d, stream)
+    for i in range(steps):
+        j = i % len(streams)
+        index.search_batch_dev(q, nprobe, k, outs[j][0], outs[j][1], streams[j])
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     st = index.stage_times(reset=True)
@@ -103,6 +113,8 @@ def main():
     ap.add_argument("--workload", default="C3", help="spec name in synthdata.SPECS")
     ap.add_argument("--nq", type=int, default=None)
     ap.add_argument("--slices", type=int, default=0, help="scan blocks per query (0 = auto)")
+    ap.add_argument("--streams", type=int, default=1,
+                    help="issue consecutive steps on this many alternating streams (1 or 2)")
     ap.add_argument("--resident", type=float, default=1.0,
                     help="fraction of clusters (hottest first) kept on the GPU")
     ap.add_argument("--oracle-sample", type=int, default=256)
@@ -256,7 +268,7 @@ def main():
         resident_frac = len(hot) / ix.nlist
 
     r = timed_steps(index, q, spec.nprobe, spec.k, args.steps, args.warmup, args.slices,
-                    timing=not args.no_timing)
+                    timing=not args.no_timing, n_streams=args.streams)
     out_ids, out_d = r["out_ids"], r["out_d"]
 
     read_ceiling = None
@@ -341,7 +353,8 @@ def main():
         "config": {"workload": f"{workload} nq={nq}",
                    "resident_fraction": round(resident_frac, 4),
                    "mean_hit_rate": round(r["hit_rate"], 4),
-                   "scan_slices": args.slices, "inputs": "device-resident queries"},
+                   "scan_slices": args.slices, "streams": args.streams,
+                   "inputs": "device-resident queries"},
         "roofline": roofline,
         "cpu_baseline": cpu_baseline,
         "stage_ms": r["stage_ms"],

@@ -30,9 +30,10 @@
  *  - Threading: one searcher thread plus one migrator thread per index.
  *  - Streams are raw hipStream_t values passed as void*; NULL is HIP's null
  *    stream.  All streams must have default priority.  The host-pointer entry
- *    points run on a stream the index owns.  The batch workspace is shared: a
- *    call issued on a different stream than the previous asynchronous call
- *    first waits for that call to finish.
+ *    points run on a stream the index owns.  The index holds two per-batch
+ *    workspaces, each tied to the stream that used it last, so batches issued
+ *    on two different streams may be in flight together; a call on a third
+ *    stream first waits for the least recently used of them to drain.
  */
 #ifndef IVFPQ_HOT_H
 #define IVFPQ_HOT_H

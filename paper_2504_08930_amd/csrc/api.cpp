@@ -160,10 +160,13 @@ struct ivf_index {
   int32_t *h_probe = nullptr;
   unsigned long long *h_stats = nullptr;
 
-  // stream of the last asynchronous search: the batch workspace is shared, so
-  // a call on another stream first waits for it
-  bool async_pending = false;
-  hipStream_t async_stream = nullptr;
+  // workspace slots: a slot belongs to the stream that used it last; a call on
+  // a new stream takes the least recently used slot after that slot's stream
+  // has drained
+  hipStream_t slot_stream[kWsSlots] = {nullptr, nullptr};
+  bool slot_used[kWsSlots] = {false, false};
+  uint64_t slot_tick[kWsSlots] = {0, 0};
+  uint64_t tick = 0;
 
   int32_t tune_slices = 0;
   int32_t timing = 0;
@@ -219,31 +222,35 @@ static size_t plan_layout(const ivf_index_desc_t &d, int64_t resident_vectors, s
   t.centroids = (float *)take(nl * D * 4);
   t.cent_norm = (float *)take(nl * 4);
   t.cent_parts = take(nl * D * 6);
-  t.q_parts = take(nq * D * 6);
   t.cbT = (float *)take(256 * D * 4);
   t.clus_len = (int32_t *)take(nl * 4);
   for (int i = 0; i < 3; ++i) t.clus_tile[i] = (int32_t *)take(nl * 4);
   t.hits = (unsigned long long *)take(nl * 8);
   t.qstats = (unsigned long long *)take(QS_COUNT * 8);
-  t.queries = (float *)take(nq * D * 4);
-  t.scores = (float *)take(nq * nl * 4);
-  t.probe = (int32_t *)take(nq * np * 4);
-  t.g_base = (int32_t *)take(nq * np * 4);
-  t.g_len = (int32_t *)take(nq * np * 4);
-  t.g_prefix = (int32_t *)take(nq * (np + 1) * 4);
-  t.g_n = (int32_t *)take(nq * 4);
-  t.cold = (int32_t *)take(nq * np * 4);
-  t.n_cold = (int32_t *)take(nq * 4);
-  t.lut = (float *)take(nq * 256 * M * 4);
-  t.lutpart = (uint32_t *)take(nq * kLutMaxParts * 4);
-  t.lutmax = (uint32_t *)take(nq * 4);
-  t.q_vecs = (int32_t *)take(nq * 4);
-  t.part_key = (int32_t *)take(nq * kMaxSlices * k * 4);
-  t.part_id = (int64_t *)take(nq * kMaxSlices * k * 8);
-  t.res_key = (int32_t *)take(nq * k * 4);
-  t.res_id = (int64_t *)take(nq * k * 8);
-  t.out_ids = (int64_t *)take(nq * k * 8);
-  t.out_dists = (float *)take(nq * k * 4);
+  for (int sl = 0; sl < kWsSlots; ++sl) {
+    BatchWs &w = t.ws[sl];
+    w.q_parts = take(nq * D * 6);
+    w.queries = (float *)take(nq * D * 4);
+    w.scores = (float *)take(nq * nl * 4);
+    w.probe = (int32_t *)take(nq * np * 4);
+    w.g_base = (int32_t *)take(nq * np * 4);
+    w.g_len = (int32_t *)take(nq * np * 4);
+    w.g_prefix = (int32_t *)take(nq * (np + 1) * 4);
+    w.g_n = (int32_t *)take(nq * 4);
+    w.cold = (int32_t *)take(nq * np * 4);
+    w.n_cold = (int32_t *)take(nq * 4);
+    w.lut = (float *)take(nq * 256 * M * 4);
+    w.lutpart = (uint32_t *)take(nq * kLutMaxParts * 4);
+    w.lutmax = (uint32_t *)take(nq * 4);
+    w.q_vecs = (int32_t *)take(nq * 4);
+    w.order = (int32_t *)take(nq * 4);
+    w.part_key = (int32_t *)take(nq * kMaxSlices * k * 4);
+    w.part_id = (int64_t *)take(nq * kMaxSlices * k * 8);
+    w.res_key = (int32_t *)take(nq * k * 4);
+    w.res_id = (int64_t *)take(nq * k * 8);
+    w.out_ids = (int64_t *)take(nq * k * 8);
+    w.out_dists = (float *)take(nq * k * 4);
+  }
   t.staging = (unsigned char *)take(staging);
   t.staging_bytes = staging;
   int64_t cap_tiles = (resident_vectors + kTileVecs - 1) / kTileVecs;
@@ -929,6 +936,30 @@ static int search_host_only(ivf_index *ix, const float *queries, int64_t nq, con
   return IVF_OK;
 }
 
+// Workspace slot for a batch on stream st (caller holds ix->mu).
+static int acquire_slot_locked(ivf_index *ix, hipStream_t st, int *slot) {
+  int pick = -1;
+  for (int i = 0; i < kWsSlots; ++i)
+    if (ix->slot_used[i] && ix->slot_stream[i] == st) pick = i;
+  if (pick < 0)
+    for (int i = 0; i < kWsSlots; ++i)
+      if (!ix->slot_used[i]) {
+        pick = i;
+        break;
+      }
+  if (pick < 0) {
+    pick = 0;
+    for (int i = 1; i < kWsSlots; ++i)
+      if (ix->slot_tick[i] < ix->slot_tick[pick]) pick = i;
+    HIP_TRY(hipStreamSynchronize(ix->slot_stream[pick]));
+  }
+  ix->slot_used[pick] = true;
+  ix->slot_stream[pick] = st;
+  ix->slot_tick[pick] = ++ix->tick;
+  *slot = pick;
+  return IVF_OK;
+}
+
 struct SearchArgs {
   const float *q_dev = nullptr;    // device queries (may be NULL if q_host given)
   const float *q_host = nullptr;   // host queries (may be NULL if q_dev given)
@@ -949,18 +980,17 @@ static int search_device(ivf_index *ix, const SearchArgs &a) {
   const int np = a.nprobe;
   hipStream_t st = a.st;
 
-  // ---- pin the mapping-table version ----
+  // ---- workspace slot; pin the mapping-table version ----
+  int slot = 0;
   int buf;
   bool all_resident, any_resident;
   Version *ver;
   bool timing;
   {
     std::lock_guard<std::mutex> lk(ix->mu);
-    if (ix->async_pending && ix->async_stream != st) {
-      HIP_TRY(hipStreamSynchronize(ix->async_stream));
-      ix->async_pending = false;
-    }
-    int rc = publish_if_done_locked(ix, false);
+    int rc = acquire_slot_locked(ix, st, &slot);
+    if (rc < 0) return rc;
+    rc = publish_if_done_locked(ix, false);
     if (rc < 0) return rc;
     reclaim(ix);
     ver = &ix->versions.back();
@@ -970,14 +1000,13 @@ static int search_device(ivf_index *ix, const SearchArgs &a) {
     any_resident = ix->resident_clusters > 0;
     timing = ix->timing != 0;
   }
+  const BatchWs &W = L.ws[slot];
   const uint64_t ver_id = ver->id;
   auto release = [&](bool async_tail) {
     std::lock_guard<std::mutex> lk(ix->mu);
     for (auto &v : ix->versions) {
       if (v.id != ver_id) continue;
       if (async_tail) {
-        ix->async_pending = true;
-        ix->async_stream = st;
         hipEvent_t e = get_event(ix);
         if (e && hipEventRecord(e, st) == hipSuccess) v.events.push_back(e);
         else (void)hipStreamSynchronize(st);
@@ -1009,40 +1038,41 @@ static int search_device(ivf_index *ix, const SearchArgs &a) {
 
   const float *dq = a.q_dev;
   if (!dq) {
-    S_TRY(hipMemcpyAsync(L.queries, a.q_host, (size_t)nq * sh.d * 4, hipMemcpyHostToDevice, st));
-    dq = L.queries;
+    S_TRY(hipMemcpyAsync(W.queries, a.q_host, (size_t)nq * sh.d * 4, hipMemcpyHostToDevice, st));
+    dq = W.queries;
   }
   // ---- stage 1: coarse quantizer (or the caller's probe list) ----
   if (a.probe_host) {
     memcpy(ix->h_probe, a.probe_host, (size_t)nq * np * 4);
-    S_TRY(hipMemcpyAsync(L.probe, ix->h_probe, (size_t)nq * np * 4, hipMemcpyHostToDevice, st));
+    S_TRY(hipMemcpyAsync(W.probe, ix->h_probe, (size_t)nq * np * 4, hipMemcpyHostToDevice, st));
   } else {
     S_TRY(mark(IVF_STAGE_COARSE_GEMM));
-    S_TRY(launch_split_bf16(dq, (size_t)nq, sh.d, L.q_parts, st));
-    S_TRY(launch_coarse_gemm(sh, L.q_parts, nq, L.cent_parts, L.cent_norm, L.scores, st));
+    S_TRY(launch_split_bf16(dq, (size_t)nq, sh.d, W.q_parts, st));
+    S_TRY(launch_coarse_gemm(sh, W.q_parts, nq, L.cent_parts, L.cent_norm, W.scores, st));
     S_TRY(mark(IVF_STAGE_COARSE_SELECT));
-    S_TRY(launch_coarse_select(sh, L.scores, nq, np, np, L.probe, st));
+    S_TRY(launch_coarse_select(sh, W.scores, nq, np, np, W.probe, st));
   }
   // ---- routing ----
   S_TRY(mark(IVF_STAGE_ROUTE));
-  S_TRY(launch_route(L.probe, nq, np, np, L.clus_tile[buf], L.clus_len, sh.M, L.g_base, L.g_len,
-                     L.g_prefix, L.g_n, L.cold, L.n_cold, L.q_vecs, L.hits, L.qstats, 1, st));
+  S_TRY(launch_route(W.probe, nq, np, np, L.clus_tile[buf], L.clus_len, sh.M, W.g_base, W.g_len,
+                     W.g_prefix, W.g_n, W.cold, W.n_cold, W.q_vecs, L.hits, L.qstats, 1, st));
   S_TRY(mark(IVF_STAGE_LUT));
   const int slices = pick_slices(ix, nq);
   const bool final_on_gpu = all_resident;
   if (any_resident) {
     // ---- stage 2: lookup tables; stage 3: scan + top-k ----
-    S_TRY(launch_lut(sh, dq, nq, L.cbT, L.lut, L.lutpart, L.lutmax, st));
+    S_TRY(launch_order(W.probe, nq, np, W.order, st));
+    S_TRY(launch_lut(sh, dq, nq, L.cbT, W.lut, W.lutpart, W.lutmax, st));
     S_TRY(mark(IVF_STAGE_SCAN));
-    S_TRY(launch_scan(sh, L, nq, np, slices, k, st));
+    S_TRY(launch_scan(sh, L, W, nq, np, slices, k, st));
     S_TRY(mark(IVF_STAGE_MERGE));
     int64_t *oid = nullptr;
     float *od = nullptr;
     if (final_on_gpu) {
-      oid = a.out_device ? a.out_ids : L.out_ids;
-      od = a.out_device ? a.out_dists : L.out_dists;
+      oid = a.out_device ? a.out_ids : W.out_ids;
+      od = a.out_device ? a.out_dists : W.out_dists;
     }
-    S_TRY(launch_merge(sh, L, nq, slices, k, oid, od, st));
+    S_TRY(launch_merge(sh, W, nq, slices, k, oid, od, st));
     S_TRY(mark(IVF_N_STAGES));
   }
   if (timing) {
@@ -1055,8 +1085,8 @@ static int search_device(ivf_index *ix, const SearchArgs &a) {
       release(true);  // asynchronous: outputs valid when the stream gets here
       return IVF_OK;
     }
-    S_TRY(hipMemcpyAsync(ix->h_outids, L.out_ids, (size_t)nq * k * 8, hipMemcpyDeviceToHost, st));
-    S_TRY(hipMemcpyAsync(ix->h_outd, L.out_dists, (size_t)nq * k * 4, hipMemcpyDeviceToHost, st));
+    S_TRY(hipMemcpyAsync(ix->h_outids, W.out_ids, (size_t)nq * k * 8, hipMemcpyDeviceToHost, st));
+    S_TRY(hipMemcpyAsync(ix->h_outd, W.out_dists, (size_t)nq * k * 4, hipMemcpyDeviceToHost, st));
     S_TRY(hipStreamSynchronize(st));
     release(false);
     memcpy(a.out_ids, ix->h_outids, (size_t)nq * k * 8);
@@ -1065,17 +1095,17 @@ static int search_device(ivf_index *ix, const SearchArgs &a) {
   }
 
   // ---- hybrid: cold probes on the CPU, then merge (Sections 4.3.1, 4.3.2) ----
-  S_TRY(hipMemcpyAsync(ix->h_ncold, L.n_cold, (size_t)nq * 4, hipMemcpyDeviceToHost, st));
-  S_TRY(hipMemcpyAsync(ix->h_cold, L.cold, (size_t)nq * np * 4, hipMemcpyDeviceToHost, st));
+  S_TRY(hipMemcpyAsync(ix->h_ncold, W.n_cold, (size_t)nq * 4, hipMemcpyDeviceToHost, st));
+  S_TRY(hipMemcpyAsync(ix->h_cold, W.cold, (size_t)nq * np * 4, hipMemcpyDeviceToHost, st));
   const float *hq = a.q_host;
   if (!hq) {
     S_TRY(hipMemcpyAsync(ix->h_queries, dq, (size_t)nq * sh.d * 4, hipMemcpyDeviceToHost, st));
     hq = ix->h_queries;
   }
   if (any_resident) {
-    S_TRY(hipMemcpyAsync(ix->h_reskey, L.res_key, (size_t)nq * k * 4, hipMemcpyDeviceToHost, st));
-    S_TRY(hipMemcpyAsync(ix->h_resid, L.res_id, (size_t)nq * k * 8, hipMemcpyDeviceToHost, st));
-    S_TRY(hipMemcpyAsync(ix->h_lutmax, L.lutmax, (size_t)nq * 4, hipMemcpyDeviceToHost, st));
+    S_TRY(hipMemcpyAsync(ix->h_reskey, W.res_key, (size_t)nq * k * 4, hipMemcpyDeviceToHost, st));
+    S_TRY(hipMemcpyAsync(ix->h_resid, W.res_id, (size_t)nq * k * 8, hipMemcpyDeviceToHost, st));
+    S_TRY(hipMemcpyAsync(ix->h_lutmax, W.lutmax, (size_t)nq * 4, hipMemcpyDeviceToHost, st));
   }
   S_TRY(hipStreamSynchronize(st));
   release(false);
@@ -1188,22 +1218,17 @@ extern "C" int ivf_coarse_probe_dev(ivf_index_t *ix, const float *queries, int64
   if (nq > ix->desc.max_nq) return fail(IVF_EINVAL, "nq exceeds max_nq");
   if (nprobe > kMaxNprobe) return fail(IVF_EINVAL, "nprobe exceeds %d", kMaxNprobe);
   hipStream_t st = (hipStream_t)stream;
+  int slot = 0;
   {
     std::lock_guard<std::mutex> lk(ix->mu);
-    if (ix->async_pending && ix->async_stream != st) {
-      HIP_TRY(hipStreamSynchronize(ix->async_stream));
-      ix->async_pending = false;
-    }
+    int rc = acquire_slot_locked(ix, st, &slot);
+    if (rc < 0) return rc;
   }
-  HIP_TRY(launch_split_bf16(queries, (size_t)nq, ix->sh.d, ix->L.q_parts, st));
-  HIP_TRY(launch_coarse_gemm(ix->sh, ix->L.q_parts, (int)nq, ix->L.cent_parts, ix->L.cent_norm,
-                             ix->L.scores, st));
-  HIP_TRY(launch_coarse_select(ix->sh, ix->L.scores, (int)nq, nprobe, nprobe, out_probe, st));
-  {
-    std::lock_guard<std::mutex> lk(ix->mu);
-    ix->async_pending = true;
-    ix->async_stream = st;
-  }
+  const BatchWs &W = ix->L.ws[slot];
+  HIP_TRY(launch_split_bf16(queries, (size_t)nq, ix->sh.d, W.q_parts, st));
+  HIP_TRY(launch_coarse_gemm(ix->sh, W.q_parts, (int)nq, ix->L.cent_parts, ix->L.cent_norm,
+                             W.scores, st));
+  HIP_TRY(launch_coarse_select(ix->sh, W.scores, (int)nq, nprobe, nprobe, out_probe, st));
   return IVF_OK;
 }
 

@@ -11,7 +11,8 @@ constexpr int kTileVecs = 64;      // vectors per code tile (one wavefront)
 constexpr int kMaxSlices = 8;      // scan blocks per query, upper bound
 constexpr int kMaxK = 128;
 constexpr int kMaxNprobe = 2048;
-constexpr int kLutMaxParts = 512;  // per-query slots for partial table maxima
+constexpr int kLutMaxParts = 512;
+constexpr int kWsSlots = 2;        // batches that may be in flight on different streams  // per-query slots for partial table maxima
 
 // Counters kept on the device next to the per-cluster hit counters.
 enum {
@@ -31,17 +32,11 @@ struct TileDesc {
   int32_t pad;
 };
 
-// Pointers into the device arena.
-struct DevLayout {
-  float *centroids;        // [nlist][d]
-  float *cent_norm;        // [nlist] squared norms (L2 only)
-  void *cent_parts;        // centroids as a three-way bf16 split, 6 B per element
-  void *q_parts;           // [max_nq][d] queries, same split
-  float *cbT;              // [256][M][dsub] transposed codebooks
-  int32_t *clus_len;       // [nlist]
-  int32_t *clus_tile[3];   // mapping table ring: first tile of a resident cluster, or -1
-  unsigned long long *hits;    // [nlist]
-  unsigned long long *qstats;  // [QS_COUNT]
+// Per-batch workspace.  There are kWsSlots of them so that batches issued on
+// different streams can be in flight together (one batch's coarse stage then
+// overlaps another's scan).
+struct BatchWs {
+  void *q_parts;           // [max_nq][d] queries as a three-way bf16 split
   float *queries;          // [max_nq][d]
   float *scores;           // [max_nq][nlist]
   int32_t *probe;          // [max_nq][max_nprobe]
@@ -55,12 +50,26 @@ struct DevLayout {
   uint32_t *lutpart;       // [max_nq][kLutMaxParts] partial maxima, one slot per LUT-kernel wave
   uint32_t *lutmax;        // [max_nq] bits of the largest |entry| of the query's table
   int32_t *q_vecs;         // [max_nq] vectors in the query's resident probes
+  int32_t *order;          // [max_nq] scan visiting order of the queries
   int32_t *part_key;       // [max_nq][kMaxSlices][max_k]
   int64_t *part_id;
   int32_t *res_key;        // [max_nq][max_k] merged GPU partial (hybrid path)
   int64_t *res_id;
   int64_t *out_ids;        // [max_nq][max_k] host-API staging
   float *out_dists;
+};
+
+// Pointers into the device arena.
+struct DevLayout {
+  float *centroids;        // [nlist][d]
+  float *cent_norm;        // [nlist] squared norms (L2 only)
+  void *cent_parts;        // centroids as a three-way bf16 split, 6 B per element
+  float *cbT;              // [256][M][dsub] transposed codebooks
+  int32_t *clus_len;       // [nlist]
+  int32_t *clus_tile[3];   // mapping table ring: first tile of a resident cluster, or -1
+  unsigned long long *hits;    // [nlist]
+  unsigned long long *qstats;  // [QS_COUNT]
+  struct BatchWs ws[kWsSlots];  // per-batch workspaces: batches on different streams overlap
   uint8_t *staging;        // copy staging
   size_t staging_bytes;
   uint8_t *tile_codes;     // [cap_tiles][M*64]
@@ -97,15 +106,18 @@ hipError_t launch_route(const int32_t *probe, int nq, int nprobe, int probe_stri
                         int32_t *n_cold, int32_t *q_vecs, unsigned long long *hits,
                         unsigned long long *qstats, int count_stats, hipStream_t st);
 
+hipError_t launch_order(const int32_t *probe, int nq, int probe_stride, int32_t *order,
+                        hipStream_t st);
+
 hipError_t launch_lut(const Shape &sh, const float *q, int nq, const float *cbT, float *lut,
                       uint32_t *lutpart, uint32_t *lutmax, hipStream_t st);
 
 // Returns hipErrorInvalidValue for an unsupported (M, k).
-hipError_t launch_scan(const Shape &sh, const DevLayout &L, int nq, int probe_stride, int slices,
-                       int k, hipStream_t st);
+hipError_t launch_scan(const Shape &sh, const DevLayout &L, const BatchWs &W, int nq,
+                       int probe_stride, int slices, int k, hipStream_t st);
 
 // final != 0: write (id, dist) to out_ids/out_dists; else (key, id) to res_key/res_id.
-hipError_t launch_merge(const Shape &sh, const DevLayout &L, int nq, int slices, int k,
+hipError_t launch_merge(const Shape &sh, const BatchWs &W, int nq, int slices, int k,
                         int64_t *out_ids, float *out_dists, hipStream_t st);
 
 hipError_t launch_interleave(const uint8_t *stage_codes, const int64_t *stage_ids,

@@ -259,6 +259,56 @@ __global__ __launch_bounds__(1024) void k_route_stats(const int32_t *__restrict_
   }
 }
 
+// Visiting order of the scan: queries grouped by their best cluster (a counting
+// sort on the cluster id folded into kOrderBins bins; the order inside a group
+// does not matter).  One block, histogram and offsets in LDS.
+constexpr int kOrderBins = 4096;
+
+__global__ __launch_bounds__(1024) void k_order(const int32_t *__restrict__ probe, int nq,
+                                                int stride, int32_t *__restrict__ order) {
+  __shared__ unsigned int bins[kOrderBins];
+  __shared__ unsigned int wsum[16];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  for (int i = tid; i < kOrderBins; i += 1024) bins[i] = 0u;
+  __syncthreads();
+  for (int q = tid; q < nq; q += 1024)
+    atomicAdd(&bins[(unsigned)probe[(size_t)q * stride] % kOrderBins], 1u);
+  __syncthreads();
+  // exclusive scan: thread t owns bins [4t, 4t+4)
+  unsigned loc[4], tsum = 0;
+#pragma unroll
+  for (int b = 0; b < 4; ++b) {
+    loc[b] = bins[tid * 4 + b];
+    tsum += loc[b];
+  }
+  unsigned incl = tsum;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const unsigned v = __shfl_up(incl, o, 64);
+    if (lane >= o) incl += v;
+  }
+  if (lane == 63) wsum[wave] = incl;
+  __syncthreads();
+  unsigned run = incl - tsum;
+  for (int w2 = 0; w2 < wave; ++w2) run += wsum[w2];
+#pragma unroll
+  for (int b = 0; b < 4; ++b) {
+    bins[tid * 4 + b] = run;
+    run += loc[b];
+  }
+  __syncthreads();
+  for (int q = tid; q < nq; q += 1024) {
+    const unsigned pos = atomicAdd(&bins[(unsigned)probe[(size_t)q * stride] % kOrderBins], 1u);
+    order[pos] = q;
+  }
+}
+
+hipError_t launch_order(const int32_t *probe, int nq, int probe_stride, int32_t *order,
+                        hipStream_t st) {
+  hipLaunchKernelGGL(k_order, dim3(1), dim3(1024), 0, st, probe, nq, probe_stride, order);
+  return hipGetLastError();
+}
+
 hipError_t launch_route(const int32_t *probe, int nq, int nprobe, int probe_stride,
                         const int32_t *clus_tile, const int32_t *clus_len, int M, int32_t *g_base,
                         int32_t *g_len, int32_t *g_prefix, int32_t *g_n, int32_t *cold,
@@ -433,6 +483,8 @@ hipError_t launch_interleave(const uint8_t *stage_codes, const int64_t *stage_id
 // ---------------------------------------------------------------------------
 // Stage 3: ADC scan with in-block top-k.
 // ---------------------------------------------------------------------------
+constexpr int kScanChunk = 32;  // consecutive scan units kept on one XCD
+
 struct ScanParams {
   const uint8_t *tile_codes;
   const int64_t *tile_ids;
@@ -442,8 +494,10 @@ struct ScanParams {
   const int32_t *g_len;
   const int32_t *g_prefix;
   const int32_t *g_n;
+  const int32_t *order;
   int32_t *part_key;
   int64_t *part_id;
+  int nq;
   int probe_stride;
   int slices;
   int k;
@@ -479,8 +533,21 @@ __global__ __launch_bounds__(NW * 64) void k_scan(ScanParams P) {
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int q = blockIdx.x / P.slices;
-  const int s = blockIdx.x % P.slices;
+  // Block -> (query, slice).  Queries are visited in `order` (sorted by their
+  // best cluster, so queries drawn around the same hot centre, which probe
+  // nearly the same lists, run at the same time and share those lists through
+  // L2 / Infinity Cache).  Consecutive block ids go to different XCDs, so runs
+  // of kScanChunk consecutive units are mapped to one XCD.
+  int u;
+  {
+    const int b = blockIdx.x;
+    const int x = b & 7, jj = b >> 3;
+    const int within = jj % kScanChunk, cc = jj / kScanChunk;
+    u = (cc * 8 + x) * kScanChunk + within;
+  }
+  if (u >= P.nq * P.slices) return;
+  const int q = P.order[u / P.slices];
+  const int s = u % P.slices;
   const int k = P.k;
 
   // ---- stage the query's table in LDS as fixed point, code-major ----
@@ -781,7 +848,9 @@ static hipError_t launch_scan_t(const ScanParams &P, int nq, hipStream_t st) {
     if (e != hipSuccess) return e;
     attr_done = true;
   }
-  hipLaunchKernelGGL((k_scan<M, NW, CAP>), dim3(nq * P.slices), dim3(NW * 64), lds, st, P);
+  const int total = nq * P.slices;
+  const int grid = (total + 8 * kScanChunk - 1) / (8 * kScanChunk) * (8 * kScanChunk);
+  hipLaunchKernelGGL((k_scan<M, NW, CAP>), dim3(grid), dim3(NW * 64), lds, st, P);
   return hipGetLastError();
 }
 
@@ -790,20 +859,22 @@ bool scan_supports(int M, int k) {
   return M == 16 || M == 32 || M == 48 || M == 64 || M == 96 || M == 128;
 }
 
-hipError_t launch_scan(const Shape &sh, const DevLayout &L, int nq, int probe_stride, int slices,
-                       int k, hipStream_t st) {
+hipError_t launch_scan(const Shape &sh, const DevLayout &L, const BatchWs &W, int nq,
+                       int probe_stride, int slices, int k, hipStream_t st) {
   if (!scan_supports(sh.M, k)) return hipErrorInvalidValue;
   ScanParams P;
   P.tile_codes = L.tile_codes;
   P.tile_ids = L.tile_ids;
-  P.lut = L.lut;
-  P.lutmax = L.lutmax;
-  P.g_base = L.g_base;
-  P.g_len = L.g_len;
-  P.g_prefix = L.g_prefix;
-  P.g_n = L.g_n;
-  P.part_key = L.part_key;
-  P.part_id = L.part_id;
+  P.lut = W.lut;
+  P.lutmax = W.lutmax;
+  P.g_base = W.g_base;
+  P.g_len = W.g_len;
+  P.g_prefix = W.g_prefix;
+  P.g_n = W.g_n;
+  P.order = W.order;
+  P.nq = nq;
+  P.part_key = W.part_key;
+  P.part_id = W.part_id;
   P.probe_stride = probe_stride;
   P.slices = slices;
   P.k = k;
@@ -859,12 +930,12 @@ __global__ __launch_bounds__(64) void k_merge(const int32_t *__restrict__ part_k
   }
 }
 
-hipError_t launch_merge(const Shape &sh, const DevLayout &L, int nq, int slices, int k,
+hipError_t launch_merge(const Shape &sh, const BatchWs &W, int nq, int slices, int k,
                         int64_t *out_ids, float *out_dists, hipStream_t st) {
   int n2 = 1;
   while (n2 < slices * k) n2 <<= 1;
-  hipLaunchKernelGGL(k_merge, dim3(nq), dim3(64), 0, st, L.part_key, L.part_id, slices, k, n2,
-                     L.lutmax, sh.M, sh.metric_ip, L.res_key, L.res_id, out_ids, out_dists);
+  hipLaunchKernelGGL(k_merge, dim3(nq), dim3(64), 0, st, W.part_key, W.part_id, slices, k, n2,
+                     W.lutmax, sh.M, sh.metric_ip, W.res_key, W.res_id, out_ids, out_dists);
   return hipGetLastError();
 }
 
