@@ -36,7 +36,7 @@ HBM_PEAK_GBS = 8000.0
 # HBM-side bytes per k_scan launch from the rocprofv3 --pmc runs (FETCH_SIZE + WRITE_SIZE, scaled
 # by the same counters on a plain copy kernel); valid for exactly this workload and launch shape.
 MEASURED_TRAFFIC = {
-    ("C3", 1024, 1.0): (4.057e9 + 0.164e6, "profiles/c3_nq1024_scan_hbm_traffic.md"),
+    ("C3", 1024, 1.0): (3.525e9 + 0.164e6, "profiles/c3_nq1024_scan_hbm_traffic.md"),
 }
 
 
@@ -107,8 +107,8 @@ def timed_steps(index, q, nprobe, k, steps, warmup, slices, timing=True, n_strea
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--mode", default="hotpath", choices=["hotpath", "sweep", "drift"])
     ap.add_argument("--workload", default="C3", help="spec name in synthdata.SPECS")
     ap.add_argument("--nq", type=int, default=None)
@@ -174,9 +174,9 @@ def main():
                 index.load_partition(hottest_clusters(index, calib, spec.nprobe, frac, ix.nlist))
             for n in (256, 1024, 4096):
                 q, _ = make_queries(spec, centers, nq=n)
-                steps = args.steps if frac == 1.0 else max(2, args.steps // 10)
+                steps = min(args.steps, 50) if frac == 1.0 else 3
                 r = timed_steps(index, q.contiguous(), spec.nprobe, spec.k, steps,
-                                args.warmup if frac == 1.0 else 1, args.slices)
+                                min(args.warmup, 20) if frac == 1.0 else 1, args.slices)
                 row = {"nq": n, "resident_fraction": frac, "queries_per_s": round(r["qps"], 1),
                        "ms_per_step": round(r["ms_per_step"], 3),
                        "mean_hit_rate": round(r["hit_rate"], 4),

@@ -102,55 +102,71 @@ hipError_t launch_split_bf16(const float *src, size_t rows, int d, void *dst, hi
 // picks the XCD), which keeps each centroid tile in that XCD's L2.
 // ---------------------------------------------------------------------------
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-constexpr int kBM = 128, kBN = 128;
 constexpr int kRowBytes = 112;  // 96 B of data per row and chunk, padded: conflict-free b128 reads
 
-__global__ __launch_bounds__(256) void k_coarse_gemm(const uint4 *__restrict__ Qp, int nq,
-                                                     const uint4 *__restrict__ Cp, int nlist, int d,
-                                                     const float *__restrict__ cnorm, int metric_ip,
-                                                     int row_tiles, int col_tiles,
-                                                     float *__restrict__ scores) {
-  __shared__ __align__(16) unsigned char As[2][kBM * kRowBytes];
-  __shared__ __align__(16) unsigned char Bs[2][kBN * kRowBytes];
+// WM x WN waves per block, each wave TM x TN MFMA tiles of 32 x 32.
+// <2,2,2,2>: 128 x 128 block, 4 waves (small batches: more blocks);
+// <4,2,2,4>: 256 x 256 block, 8 waves, 64 x 128 per wave (half the L2 traffic
+// and 25 % fewer LDS reads per MFMA, twice the MFMA work between barriers).
+template <int WM, int WN, int TM, int TN>
+__global__ __launch_bounds__(WM *WN * 64) void k_coarse_gemm(
+    const uint4 *__restrict__ Qp, int nq, const uint4 *__restrict__ Cp, int nlist, int d,
+    const float *__restrict__ cnorm, int metric_ip, int row_tiles, int col_tiles,
+    float *__restrict__ scores) {
+  constexpr int BM = WM * TM * 32, BN = WN * TN * 32, NT = WM * WN * 64;
+  constexpr int LA = BM * 6 / NT, LB = BN * 6 / NT;  // 16-byte units per thread and chunk
+  static_assert(BM * 6 % NT == 0 && BN * 6 % NT == 0, "tile loads divide evenly");
+  extern __shared__ __align__(16) unsigned char gsm[];
+  auto a_tile = [&](int buf) { return gsm + buf * ((BM + BN) * kRowBytes); };
+  auto b_tile = [&](int buf) { return gsm + buf * ((BM + BN) * kRowBytes) + BM * kRowBytes; };
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = tid >> 6;
-  const int wm = wave >> 1, wn = wave & 1;
+  const int wm = wave / WN, wn = wave % WN;
   // XCD-aware tile assignment
   const int xcd = blockIdx.x & 7, j = blockIdx.x >> 3;
   const int ct = (j / row_tiles) * 8 + xcd, rt = j % row_tiles;
   if (ct >= col_tiles) return;
-  const int row0 = rt * kBM;   // queries
-  const int col0 = ct * kBN;   // centroids
+  const int row0 = rt * BM;   // queries
+  const int col0 = ct * BN;   // centroids
 
-  // global -> LDS: unit f = tid + 256 * i (i < 3), row = f / 6, u = f % 6.  Loads run
-  // two chunks ahead of the MFMAs (register stage), stores one chunk ahead (LDS stage).
-  uint4 ga[2][3], gb[2][3];
+  // global -> LDS: unit f = tid + NT * i, row = f / 6, u = f % 6; loads run one
+  // chunk ahead of the MFMAs in registers, LDS is double buffered.
+  uint4 ga[2][LA], gb[2][LB];  // two register stages: loads run two chunks ahead
   auto gload = [&](int kc, int slot) {
 #pragma unroll
-    for (int i = 0; i < 3; ++i) {
-      const int f = tid + 256 * i;
+    for (int i = 0; i < LA; ++i) {
+      const int f = tid + NT * i;
       const int r = f / 6, u = f % 6;
-      const int qa = row0 + r, cb = col0 + r;
+      const int qa = row0 + r;
       ga[slot][i] = qa < nq ? Qp[((size_t)kc * nq + qa) * 6 + u] : make_uint4(0, 0, 0, 0);
+    }
+#pragma unroll
+    for (int i = 0; i < LB; ++i) {
+      const int f = tid + NT * i;
+      const int r = f / 6, u = f % 6;
+      const int cb = col0 + r;
       gb[slot][i] = cb < nlist ? Cp[((size_t)kc * nlist + cb) * 6 + u] : make_uint4(0, 0, 0, 0);
     }
   };
   auto sstore = [&](int buf, int slot) {
 #pragma unroll
-    for (int i = 0; i < 3; ++i) {
-      const int f = tid + 256 * i;
-      const int r = f / 6, u = f % 6;
-      *reinterpret_cast<uint4 *>(&As[buf][r * kRowBytes + u * 16]) = ga[slot][i];
-      *reinterpret_cast<uint4 *>(&Bs[buf][r * kRowBytes + u * 16]) = gb[slot][i];
+    for (int i = 0; i < LA; ++i) {
+      const int f = tid + NT * i;
+      *reinterpret_cast<uint4 *>(a_tile(buf) + (f / 6) * kRowBytes + (f % 6) * 16) = ga[slot][i];
+    }
+#pragma unroll
+    for (int i = 0; i < LB; ++i) {
+      const int f = tid + NT * i;
+      *reinterpret_cast<uint4 *>(b_tile(buf) + (f / 6) * kRowBytes + (f % 6) * 16) = gb[slot][i];
     }
   };
 
-  floatx16 acc[2][2];
+  floatx16 acc[TM][TN];
 #pragma unroll
-  for (int a = 0; a < 2; ++a)
+  for (int a = 0; a < TM; ++a)
 #pragma unroll
-    for (int b = 0; b < 2; ++b)
+    for (int b = 0; b < TN; ++b)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.0f;
 
@@ -160,55 +176,59 @@ __global__ __launch_bounds__(256) void k_coarse_gemm(const uint4 *__restrict__ Q
   if (nk > 1) gload(1, 1);
   __syncthreads();
   const int li = lane & 31, kk = lane >> 5;
-  // unrolled by two so the register stage index is a compile-time constant
+  // one K chunk; slot_next holds chunk kc+1 (already loaded), slot_far receives chunk kc+2
   auto step = [&](int kc, int slot_next, int slot_far) {
     const int buf = kc & 1;
     if (kc + 2 < nk) gload(kc + 2, slot_far);
     // lane (li, kk) holds k = 8*kk .. 8*kk+7 of the chunk for row li of a tile
-    bf16x8 a[2][3], b[2][3];
+    bf16x8 a[TM][3];
 #pragma unroll
-    for (int t = 0; t < 2; ++t) {
+    for (int t = 0; t < TM; ++t)
 #pragma unroll
-      for (int p = 0; p < 3; ++p) {
+      for (int p = 0; p < 3; ++p)
         a[t][p] = __builtin_bit_cast(
-            bf16x8, *reinterpret_cast<const uint4 *>(
-                        &As[buf][(wm * 64 + t * 32 + li) * kRowBytes + (kk * 3 + p) * 16]));
-        b[t][p] = __builtin_bit_cast(
-            bf16x8, *reinterpret_cast<const uint4 *>(
-                        &Bs[buf][(wn * 64 + t * 32 + li) * kRowBytes + (kk * 3 + p) * 16]));
-      }
-    }
+            bf16x8,
+            *reinterpret_cast<const uint4 *>(
+                a_tile(buf) + (wm * TM * 32 + t * 32 + li) * kRowBytes + (kk * 3 + p) * 16));
 #pragma unroll
-    for (int mt = 0; mt < 2; ++mt)
+    for (int nt = 0; nt < TN; ++nt) {
+      bf16x8 b[3];
 #pragma unroll
-      for (int nt = 0; nt < 2; ++nt) {
+      for (int p = 0; p < 3; ++p)
+        b[p] = __builtin_bit_cast(
+            bf16x8,
+            *reinterpret_cast<const uint4 *>(
+                b_tile(buf) + (wn * TN * 32 + nt * 32 + li) * kRowBytes + (kk * 3 + p) * 16));
+#pragma unroll
+      for (int mt = 0; mt < TM; ++mt) {
         floatx16 c = acc[mt][nt];
-        c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[mt][2], b[nt][0], c, 0, 0, 0);
-        c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[mt][1], b[nt][1], c, 0, 0, 0);
-        c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[mt][0], b[nt][2], c, 0, 0, 0);
-        c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[mt][1], b[nt][0], c, 0, 0, 0);
-        c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[mt][0], b[nt][1], c, 0, 0, 0);
-        c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[mt][0], b[nt][0], c, 0, 0, 0);
+        c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[mt][2], b[0], c, 0, 0, 0);
+        c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[mt][1], b[1], c, 0, 0, 0);
+        c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[mt][0], b[2], c, 0, 0, 0);
+        c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[mt][1], b[0], c, 0, 0, 0);
+        c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[mt][0], b[1], c, 0, 0, 0);
+        c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[mt][0], b[0], c, 0, 0, 0);
         acc[mt][nt] = c;
       }
+    }
     if (kc + 1 < nk) sstore(buf ^ 1, slot_next);
     __syncthreads();
   };
-  for (int kc = 0; kc < nk; kc += 2) {
-    step(kc, 1, 0);          // chunk kc+1 sits in slot 1; chunk kc+2 goes to slot 0
+  for (int kc = 0; kc < nk; kc += 2) {  // unrolled by two: register stage indices are constants
+    step(kc, 1, 0);
     if (kc + 1 < nk) step(kc + 1, 0, 1);
   }
 
   // D[i][j]: register r of lane l holds i = 8*(r/4) + 4*(l/32) + r%4, j = l%32
 #pragma unroll
-  for (int mt = 0; mt < 2; ++mt)
+  for (int mt = 0; mt < TM; ++mt)
 #pragma unroll
-    for (int nt = 0; nt < 2; ++nt) {
-      const int c = col0 + wn * 64 + nt * 32 + li;
+    for (int nt = 0; nt < TN; ++nt) {
+      const int c = col0 + wn * TN * 32 + nt * 32 + li;
       const float cn = (!metric_ip && c < nlist) ? cnorm[c] : 0.0f;
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        const int qi = row0 + wm * 64 + mt * 32 + 8 * (r >> 2) + 4 * kk + (r & 3);
+        const int qi = row0 + wm * TM * 32 + mt * 32 + 8 * (r >> 2) + 4 * kk + (r & 3);
         if (qi < nq && c < nlist) {
           const float dot = acc[mt][nt][r];
           scores[(size_t)qi * nlist + c] = metric_ip ? dot : __builtin_fmaf(-2.0f, dot, cn);
@@ -217,15 +237,36 @@ __global__ __launch_bounds__(256) void k_coarse_gemm(const uint4 *__restrict__ Q
     }
 }
 
+template <int WM, int WN, int TM, int TN>
+static hipError_t launch_gemm_t(const Shape &sh, const void *q_parts, int nq,
+                                const void *cent_parts, const float *cent_norm, float *scores,
+                                hipStream_t st) {
+  constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
+  const size_t lds = (size_t)2 * (BM + BN) * kRowBytes;
+  static bool attr_done = false;
+  if (!attr_done) {
+    hipError_t e =
+        hipFuncSetAttribute(reinterpret_cast<const void *>(&k_coarse_gemm<WM, WN, TM, TN>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    attr_done = true;
+  }
+  const int row_tiles = (nq + BM - 1) / BM;
+  const int col_tiles = (sh.nlist + BN - 1) / BN;
+  const int grid = 8 * ((col_tiles + 7) / 8) * row_tiles;
+  hipLaunchKernelGGL((k_coarse_gemm<WM, WN, TM, TN>), dim3(grid), dim3(WM * WN * 64), lds, st,
+                     (const uint4 *)q_parts, nq, (const uint4 *)cent_parts, sh.nlist, sh.d,
+                     cent_norm, sh.metric_ip, row_tiles, col_tiles, scores);
+  return hipGetLastError();
+}
+
 hipError_t launch_coarse_gemm(const Shape &sh, const void *q_parts, int nq, const void *cent_parts,
                               const float *cent_norm, float *scores, hipStream_t st) {
-  const int row_tiles = (nq + kBM - 1) / kBM;
-  const int col_tiles = (sh.nlist + kBN - 1) / kBN;
-  const int grid = 8 * ((col_tiles + 7) / 8) * row_tiles;
-  hipLaunchKernelGGL(k_coarse_gemm, dim3(grid), dim3(256), 0, st, (const uint4 *)q_parts, nq,
-                     (const uint4 *)cent_parts, sh.nlist, sh.d, cent_norm, sh.metric_ip, row_tiles,
-                     col_tiles, scores);
-  return hipGetLastError();
+  // big tiles once they still give every CU a block
+  const long long big_blocks = (long long)((nq + 255) / 256) * ((sh.nlist + 255) / 256);
+  if (big_blocks >= 192)
+    return launch_gemm_t<4, 2, 2, 4>(sh, q_parts, nq, cent_parts, cent_norm, scores, st);
+  return launch_gemm_t<2, 2, 2, 2>(sh, q_parts, nq, cent_parts, cent_norm, scores, st);
 }
 
 // ---------------------------------------------------------------------------
