@@ -117,7 +117,7 @@ def main():
                     help="issue consecutive steps on this many alternating streams (1 or 2)")
     ap.add_argument("--resident", type=float, default=1.0,
                     help="fraction of clusters (hottest first) kept on the GPU")
-    ap.add_argument("--oracle-sample", type=int, default=256)
+    ap.add_argument("--oracle-sample", type=int, default=512)
     ap.add_argument("--no-oracle", action="store_true")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also launch one 1 GiB streaming copy and a few 1 GiB streaming read "
