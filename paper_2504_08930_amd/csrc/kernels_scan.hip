@@ -327,11 +327,13 @@ hipError_t launch_route(const int32_t *probe, int nq, int nprobe, int probe_stri
 // ---------------------------------------------------------------------------
 // Stage 2: per-query lookup table, fp32, layout [query][code j][sub-quantizer m],
 // plus the largest |entry| per query for the fixed-point scale.
-// Thread (ml, jl) owns one codeword (m, j) in registers and loops over the
-// queries of its tile, so codebooks are read once per query tile, not once per
-// query.  Lanes run along m: table stores are contiguous in m.
+// Thread (ml, jl) owns eight codewords of sub-quantizer m in registers and
+// loops over the queries of its tile, so codebooks are read once per query
+// tile and each query sub-vector once per eight entries.  Lanes run along m:
+// table stores are contiguous in m.
 // ---------------------------------------------------------------------------
-constexpr int kLutQTile = 32;
+constexpr int kLutQTile = 8;   // queries per block
+constexpr int kLutJPT = 8;     // codewords (of one sub-quantizer) per thread
 
 template <int DSUB>
 __global__ __launch_bounds__(256) void k_lut(const float *__restrict__ queries, int nq, int d,
@@ -341,35 +343,41 @@ __global__ __launch_bounds__(256) void k_lut(const float *__restrict__ queries, 
                                              uint32_t *__restrict__ lutpart) {
   const int dsub = DSUB > 0 ? DSUB : dsub_rt;
   const int tid = threadIdx.x;
-  const int JT = 256 / MW;
+  const int JL = 256 / MW;  // j lanes per block
   const int ml = tid % MW, jl = tid / MW;
   const int m = blockIdx.y * MW + ml;
-  const int j = blockIdx.x * JT + jl;
+  const int j0 = blockIdx.x * (JL * kLutJPT) + jl;  // this thread's codes: j0 + t * JL
   const int q0 = blockIdx.z * kLutQTile;
   const int q1 = min(nq, q0 + kLutQTile);
 
-  const float *cw = cbT + ((size_t)j * M + m) * dsub;
-  float creg[DSUB > 0 ? DSUB : 1];
+  float creg[kLutJPT][DSUB > 0 ? DSUB : 1];
   if (DSUB > 0) {
 #pragma unroll
-    for (int t = 0; t < DSUB; ++t) creg[t] = cw[t];
+    for (int t = 0; t < kLutJPT; ++t) {
+      const float *cw = cbT + ((size_t)(j0 + t * JL) * M + m) * DSUB;
+#pragma unroll
+      for (int i = 0; i < DSUB; ++i) creg[t][i] = cw[i];
+    }
   }
   for (int qi = q0; qi < q1; ++qi) {
     const float *qv = queries + (size_t)qi * d + (size_t)m * dsub;
-    float v;
+    float qreg[DSUB > 0 ? DSUB : 1];
     if (DSUB > 0) {
-      float qreg[DSUB > 0 ? DSUB : 1];
 #pragma unroll
-      for (int t = 0; t < DSUB; ++t) qreg[t] = qv[t];
-      v = lut_entry(metric_ip, qreg, creg, DSUB);
-    } else {
-      v = lut_entry(metric_ip, qv, cw, dsub);
+      for (int i = 0; i < DSUB; ++i) qreg[i] = qv[i];
     }
-    lut[((size_t)qi * 256 + j) * M + m] = v;
-    // largest |entry| of this block for the query: wave max, then one atomic per wave
+    float mxf = 0.0f;
+#pragma unroll
+    for (int t = 0; t < kLutJPT; ++t) {
+      const int j = j0 + t * JL;
+      const float v = DSUB > 0 ? lut_entry(metric_ip, qreg, creg[t], DSUB)
+                               : lut_entry(metric_ip, qv, cbT + ((size_t)j * M + m) * dsub, dsub);
+      lut[((size_t)qi * 256 + j) * M + m] = v;
+      mxf = fmaxf(mxf, fabsf(v));
+    }
     // largest |entry| seen by this wave for the query: a plain store into the
     // wave's own slot (atomics on one word per query would serialize)
-    uint32_t mx = __float_as_uint(fabsf(v));
+    uint32_t mx = __float_as_uint(mxf);
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) mx = max(mx, (uint32_t)__shfl_xor((int)mx, o, 64));
     if ((tid & 63) == 0) {
@@ -394,8 +402,8 @@ __global__ __launch_bounds__(256) void k_lut_max(const uint32_t *__restrict__ lu
 hipError_t launch_lut(const Shape &sh, const float *q, int nq, const float *cbT, float *lut,
                       uint32_t *lutpart, uint32_t *lutmax, hipStream_t st) {
   const int MW = (sh.M % 32 == 0) ? 32 : 16;
-  const int JT = 256 / MW;
-  dim3 grid(256 / JT, sh.M / MW, (nq + kLutQTile - 1) / kLutQTile);
+  const int JL = 256 / MW;
+  dim3 grid(256 / (JL * kLutJPT), sh.M / MW, (nq + kLutQTile - 1) / kLutQTile);
 #define IVF_LUT_CASE(DS)                                                                       \
   case DS:                                                                                     \
     hipLaunchKernelGGL(k_lut<DS>, grid, dim3(256), 0, st, q, nq, sh.d, sh.M, sh.dsub, MW, cbT, \
