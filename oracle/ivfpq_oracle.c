@@ -18,8 +18,9 @@
  * Arithmetic is double precision on the fp32 inputs.  Selection is a full
  * sort.  No table, no blocking, no partial selection.
  *
- * Readings where the paper is silent: PQ encodes the raw vector (no residual);
- * L2 means squared L2; ties go to the smaller cluster id / vector id; missing
+ * Readings where the paper is silent: PQ encodes the raw vector, or (by_residual)
+ * the residual of the vector to its cluster centroid, in which case a stored
+ * code decodes to centroid + representative values; L2 means squared L2; ties go to the smaller cluster id / vector id; missing
  * results are (-1, +inf for L2 | -inf for IP).
  *
  * Parity pins (tests/test_oracle_pins.py): exact brute-force kNN in flat mode,
@@ -73,6 +74,20 @@ static double pair_score(int metric, int d, const float *q, const float *x) {
     return s;
 }
 
+/* Same, against the vector a + b (the sum is formed in double, i.e. exactly). */
+static double pair_score_sum(int metric, int d, const float *q, const float *a, const float *b) {
+    double s = 0.0;
+    if (metric == ORACLE_L2) {
+        for (int i = 0; i < d; ++i) {
+            double t = (double)q[i] - ((double)a[i] + (double)b[i]);
+            s += t * t;
+        }
+    } else {
+        for (int i = 0; i < d; ++i) s += (double)q[i] * ((double)a[i] + (double)b[i]);
+    }
+    return s;
+}
+
 /*
  * Stage (1).  For each query: score all nlist centroids, full sort, keep the
  * first min(nprobe, nlist).  out_probe: [nq][nprobe] (padded with -1),
@@ -115,6 +130,8 @@ int oracle_coarse(int metric, int d, int nlist, const float *centroids,
  * Stages (2)+(3) over a given probe list (negative entries are skipped).
  * use_pq != 0: each stored code is decoded to its representative values,
  *   x_hat = concat_m codebooks[m][code[m]], and scored against the query.
+ *   With residual_centroids != NULL ([nlist][d]) the codes encode residuals and
+ *   x_hat = centroid of the list + concat_m codebooks[m][code[m]].
  * use_pq == 0 ("flat"): the raw fp32 vector (flat_vectors, same order as
  *   codes) is scored instead.
  * All candidates of the query are fully sorted; the first k are returned.
@@ -122,6 +139,7 @@ int oracle_coarse(int metric, int d, int nlist, const float *centroids,
 int oracle_scan(int metric, int d, int M, const float *codebooks,
                 const int64_t *list_offsets, const uint8_t *codes,
                 const int64_t *ids, const float *flat_vectors, int use_pq,
+                const float *residual_centroids,
                 int64_t nq, const float *queries, int nprobe,
                 const int32_t *probe, int k, int64_t *out_ids, double *out_dist) {
     if (d <= 0 || k <= 0 || nprobe <= 0 || nq < 0) return -1;
@@ -162,7 +180,11 @@ int oracle_scan(int metric, int d, int M, const float *codebooks,
                 } else {
                     x = flat_vectors + (size_t)v * d;
                 }
-                cand[n].score = pair_score(metric, d, q, x);
+                if (use_pq && residual_centroids)
+                    cand[n].score = pair_score_sum(metric, d, q,
+                                                   residual_centroids + (size_t)c * d, x);
+                else
+                    cand[n].score = pair_score(metric, d, q, x);
                 cand[n].id = ids[v];
                 ++n;
             }

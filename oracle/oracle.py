@@ -37,7 +37,7 @@ def _load():
                                       ctypes.c_int64, P, ctypes.c_int, P, P, P]
         lib.oracle_coarse.restype = ctypes.c_int
         lib.oracle_scan.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, P, P, P, P, P,
-                                    ctypes.c_int, ctypes.c_int64, P, ctypes.c_int, P,
+                                    ctypes.c_int, P, ctypes.c_int64, P, ctypes.c_int, P,
                                     ctypes.c_int, P, P]
         lib.oracle_scan.restype = ctypes.c_int
         lib.oracle_hit_stats.argtypes = [ctypes.c_int, ctypes.c_int64, ctypes.c_int, P, P, P, P]
@@ -72,9 +72,11 @@ def coarse(metric, centroids, queries, nprobe):
 
 
 def scan(metric, codebooks, list_offsets, codes, ids, queries, probe, k,
-         flat_vectors=None):
+         flat_vectors=None, residual_centroids=None):
     """Search the given probe lists.  flat_vectors (fp32 [n, d] in stored order)
-    switches PQ decoding off.  -> (ids int64 [nq, k], dists f64 [nq, k])."""
+    switches PQ decoding off.  residual_centroids (fp32 [nlist, d]) says the codes
+    encode residuals to the list's centroid.
+    -> (ids int64 [nq, k], dists f64 [nq, k])."""
     queries = _f32(queries)
     nq, d = queries.shape
     probe = np.ascontiguousarray(probe, dtype=np.int32)
@@ -87,13 +89,14 @@ def scan(metric, codebooks, list_offsets, codes, ids, queries, probe, k,
         codebooks = _f32(codebooks)
         codes = np.ascontiguousarray(codes, dtype=np.uint8)
         m = codebooks.shape[0]
+        cen = None if residual_centroids is None else _f32(residual_centroids)
         rc = _load().oracle_scan(metric, d, m, _p(codebooks), _p(list_offsets), _p(codes),
-                                 _p(ids), None, 1, nq, _p(queries), nprobe, _p(probe), k,
+                                 _p(ids), None, 1, _p(cen), nq, _p(queries), nprobe, _p(probe), k,
                                  _p(out_ids), _p(out_d))
     else:
         flat_vectors = _f32(flat_vectors)
         rc = _load().oracle_scan(metric, d, 0, None, _p(list_offsets), None, _p(ids),
-                                 _p(flat_vectors), 0, nq, _p(queries), nprobe, _p(probe), k,
+                                 _p(flat_vectors), 0, None, nq, _p(queries), nprobe, _p(probe), k,
                                  _p(out_ids), _p(out_d))
     if rc != 0:
         raise RuntimeError(f"oracle_scan failed: {rc}")
@@ -105,8 +108,13 @@ def search(index, queries, nprobe, k):
     list_offsets, codes, ids.  -> (ids, dists, probe, probe_scores, gap)."""
     probe, pscore, gap = coarse(index.metric, index.centroids, queries, nprobe)
     ids, dist = scan(index.metric, index.codebooks, index.list_offsets, index.codes,
-                     index.ids, queries, probe, k)
+                     index.ids, queries, probe, k, residual_centroids=residual_centroids_of(index))
     return ids, dist, probe, pscore, gap
+
+
+def residual_centroids_of(index):
+    """The centroids if the index encodes residuals, else None."""
+    return index.centroids if getattr(index, "by_residual", False) else None
 
 
 def hit_stats(nlist, probe, resident_mask):

@@ -28,6 +28,7 @@ class IvfPqIndexData:
     codes: np.ndarray          # uint8 [n, m], list-contiguous
     ids: np.ndarray            # int64 [n], database id of each stored code
     n: int
+    by_residual: bool = False  # codes encode x - centroid of its list
 
     @property
     def dsub(self) -> int:
@@ -102,7 +103,8 @@ def _encode(x, cb):
     return dist.argmin(2).t().contiguous().to(torch.uint8)
 
 
-def build_index(spec: WorkloadSpec, device="cpu", progress=None) -> IvfPqIndexData:
+def build_index(spec: WorkloadSpec, device="cpu", progress=None,
+                by_residual: bool = False) -> IvfPqIndexData:
     """Generate the database chunk by chunk, train, assign, encode, and lay the
     codes out list by list.  Returns host (numpy) arrays."""
     dev = torch.device(device)
@@ -121,8 +123,11 @@ def build_index(spec: WorkloadSpec, device="cpu", progress=None) -> IvfPqIndexDa
                         spec.seed_kmeans, mm_chunk)
     n_pq = min(n_train, 65536)
     say(f"pq train m={spec.m} on {n_pq} vectors")
-    codebooks = _train_pq(train[:n_pq].contiguous(), spec.m, spec.kmeans_iters,
-                          spec.seed_pq)
+    pq_train = train[:n_pq].contiguous()
+    if by_residual:
+        pq_train = pq_train - centroids[_best_centroid(pq_train, centroids, spherical, mm_chunk)]
+    codebooks = _train_pq(pq_train, spec.m, spec.kmeans_iters, spec.seed_pq)
+    del pq_train
     del train
 
     assign = torch.empty(spec.n, dtype=torch.int32, device=dev)
@@ -132,7 +137,10 @@ def build_index(spec: WorkloadSpec, device="cpu", progress=None) -> IvfPqIndexDa
     for s in range(0, spec.n, step):
         cnt = min(step, spec.n - s)
         x = database_chunk(spec, centers, s, cnt)
-        assign[s:s + cnt] = _best_centroid(x, centroids, spherical, mm_chunk).to(torch.int32)
+        a = _best_centroid(x, centroids, spherical, mm_chunk)
+        assign[s:s + cnt] = a.to(torch.int32)
+        if by_residual:
+            x = x - centroids[a]
         for e in range(0, cnt, enc_chunk):
             codes[s + e:s + e + enc_chunk] = _encode(x[e:e + enc_chunk], codebooks)
         if (s // step) % 8 == 0:
@@ -150,4 +158,5 @@ def build_index(spec: WorkloadSpec, device="cpu", progress=None) -> IvfPqIndexDa
         codes=codes.cpu().numpy(),
         ids=order.cpu().numpy().astype(np.int64),
         n=spec.n,
+        by_residual=by_residual,
     )

@@ -240,3 +240,48 @@ def test_fixture_builder_spot_checks(tiny):
             dd = ((xs - ix.codebooks.astype(np.float64)) ** 2).sum(-1)       # [m, 256]
             chosen = dd[np.arange(ix.m), ix.codes[pos].astype(np.int64)]
             assert np.all(chosen - dd.min(1) <= 1e-5 * np.maximum(1.0, dd.min(1)))
+
+
+@pytest.fixture(scope="module")
+def tiny_residual():
+    out = {}
+    for name in ("T_L2", "T_IP"):
+        spec = SPECS[name]
+        ix = build_index(spec, by_residual=True)
+        q, _ = make_queries(spec, mixture_centers(spec))
+        out[name] = (spec, ix, q.numpy())
+    return out
+
+
+@pytest.mark.parametrize("name", ["T_L2", "T_IP"])
+def test_residual_pq_all_lists_equals_exhaustive_decoded_scan(oracle, tiny_residual, name):
+    """Codes that encode residuals decode to centroid + representative values."""
+    spec, ix, q = tiny_residual[name]
+    owner = np.repeat(np.arange(ix.nlist), np.diff(ix.list_offsets))
+    dec = ix.codebooks[np.arange(ix.m)[None, :], ix.codes.astype(np.int64)].reshape(ix.n, ix.d)
+    dec = dec.astype(np.float64) + ix.centroids[owner].astype(np.float64)
+    ids, dist, probe, _, _ = oracle.search(ix, q, ix.nlist, spec.k)
+    qq = q.astype(np.float64)
+    s = ((qq[:, None, :] - dec[None]) ** 2).sum(-1) if ix.metric == L2 else qq @ dec.T
+    ref_i, ref_d = _topk_by(ix.metric, s, ix.ids, spec.k)
+    assert np.array_equal(ids, ref_i)
+    assert np.allclose(dist, ref_d, rtol=1e-12, atol=1e-12)
+    # and it is a different (better) approximation than ignoring the centroid
+    ids_raw, _ = oracle.scan(ix.metric, ix.codebooks, ix.list_offsets, ix.codes, ix.ids, q,
+                             probe, spec.k)
+    assert not np.array_equal(ids_raw, ids)
+
+
+@pytest.mark.parametrize("metric,key", [(L2, "residual_l2"), (IP, "residual_ip")])
+def test_hand_computed_residual_example(oracle, metric, key):
+    g = _read_golden()
+    cb = np.zeros((2, 256, 2), np.float32)
+    cb[0, :, 0] = np.arange(256)
+    cb[1, :, 1] = np.arange(256)
+    q = np.array([g["query"]], np.float32)
+    codes = np.array([[int(c) for c in g["code"]]], np.uint8)
+    cen = np.array([[0, 0, 0, 0], g["residual_centroid"]], np.float32)
+    offs = np.array([0, 0, 1], np.int64)                       # the code lives in list 1
+    ids, dist = oracle.scan(metric, cb, offs, codes, np.array([5], np.int64), q,
+                            np.array([[1]], np.int32), 1, residual_centroids=cen)
+    assert ids[0, 0] == 5 and dist[0, 0] == g[key][0]
