@@ -115,6 +115,8 @@ def main():
     ap.add_argument("--slices", type=int, default=0, help="scan blocks per query (0 = auto)")
     ap.add_argument("--streams", type=int, default=1,
                     help="issue consecutive steps on this many alternating streams (1 or 2)")
+    ap.add_argument("--residual", action="store_true",
+                    help="index whose PQ codes encode x - centroid (residual encoding)")
     ap.add_argument("--resident", type=float, default=1.0,
                     help="fraction of clusters (hottest first) kept on the GPU")
     ap.add_argument("--oracle-sample", type=int, default=512)
@@ -148,7 +150,7 @@ def main():
     nq = args.nq or spec.nq
 
     t0 = time.time()
-    ix = build_index(spec, device="cuda:0", progress=log)
+    ix = build_index(spec, device="cuda:0", progress=log, by_residual=args.residual)
     centers = mixture_centers(spec, dev)
     torch.cuda.synchronize()
     build_s = time.time() - t0
@@ -162,7 +164,8 @@ def main():
     log(f"loaded all clusters in {load_s:.2f}s ({index.arena_bytes / 2**30:.2f} GiB arena)")
     calib, _ = make_queries(spec, centers, nq=4096, seed=spec.seed_calib)
 
-    workload = (f"{spec.name}: N={spec.n} D={spec.d} nlist={spec.nlist} PQ{spec.m}x8 "
+    workload = (f"{spec.name}{' (residual-encoded)' if args.residual else ''}: "
+                f"N={spec.n} D={spec.d} nlist={spec.nlist} PQ{spec.m}x8 "
                 f"{'IP' if spec.metric == 1 else 'L2'} nprobe={spec.nprobe} k={spec.k} "
                 f"zipf_s={spec.zipf_s}")
 
@@ -300,7 +303,7 @@ def main():
                     "bytes_per_launch": int(r["scan_bytes_per_launch"]),
                     "avg_launch_ms": round(r["scan_ms"], 4)}
         key = (spec.name, nq, round(resident_frac, 4))
-        if key in MEASURED_TRAFFIC and args.slices == 0:
+        if key in MEASURED_TRAFFIC and args.slices == 0 and not args.residual:
             roofline["traffic"], roofline["traffic_source"] = MEASURED_TRAFFIC[key]
         if read_ceiling is not None:
             roofline["streaming_read_GBs"] = read_ceiling
@@ -317,8 +320,9 @@ def main():
         t0 = time.perf_counter()
         probe_ext, score_ext, _ = orc.coarse(ix.metric, ix.centroids, qs, spec.nprobe + 8)
         probe = np.ascontiguousarray(probe_ext[:, :spec.nprobe])
+        res_cen = orc.residual_centroids_of(ix)
         ref_i, ref_d = orc.scan(ix.metric, ix.codebooks, ix.list_offsets, ix.codes, ix.ids, qs,
-                                probe, spec.k + 16)
+                                probe, spec.k + 16, residual_centroids=res_cen)
         cpu_s = time.perf_counter() - t0
         cpu_baseline = {"value": round(ns / cpu_s, 2), "unit": "queries/s",
                         "cores": orc.num_threads(), "kind": "oracle",
@@ -332,7 +336,7 @@ def main():
         n_coarse = compare_probes(got_probe, probe_ext, score_ext, spec.nprobe, S)
         if n_coarse:
             ref_i, ref_d = orc.scan(ix.metric, ix.codebooks, ix.list_offsets, ix.codes, ix.ids,
-                                    qs, got_probe, spec.k + 16)
+                                    qs, got_probe, spec.k + 16, residual_centroids=res_cen)
         n_amb = compare_topk(got_i, got_d, ref_i, ref_d, spec.k, S)
         parity = {"queries_checked": int(ns), "coarse_ambiguous": int(n_coarse),
                   "id_ambiguous": int(n_amb), "pass": True}

@@ -23,8 +23,10 @@
  *  - The library performs no device allocation of its own: all device state
  *    lives in the caller-supplied arena.
  *  - "L2" is squared Euclidean distance (smaller is better); "IP" is the inner
- *    product (larger is better).  PQ codes encode the raw vector (no residual),
- *    8 bits per sub-quantizer.
+ *    product (larger is better).  PQ codes are 8 bits per sub-quantizer and
+ *    encode either the raw vector or (by_residual) its residual to the centroid
+ *    of its list; a stored code then stands for centroid + representative
+ *    values.  Either way one lookup table per query serves every probed list.
  *  - Results are ordered best first; ties on distance go to the smaller id.
  *    Missing results are id = -1, dist = +INF (L2) / -INF (IP).
  *  - Threading: one searcher thread plus one migrator thread per index.
@@ -75,6 +77,7 @@ typedef struct {
   int32_t max_nq;
   int32_t max_nprobe;
   int32_t max_k;
+  int32_t by_residual; /* 0: codes encode the vector; 1: the vector minus its list's centroid */
   const float *centroids;      /* [nlist][d] */
   const float *codebooks;      /* [M][256][d/M] */
   const int64_t *list_offsets; /* [nlist+1] prefix sums, in vectors */

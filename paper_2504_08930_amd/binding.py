@@ -37,6 +37,7 @@ class IvfIndexDesc(ctypes.Structure):
         ("d", ctypes.c_int32), ("nlist", ctypes.c_int32), ("M", ctypes.c_int32),
         ("nbits", ctypes.c_int32), ("metric", ctypes.c_int32), ("max_nq", ctypes.c_int32),
         ("max_nprobe", ctypes.c_int32), ("max_k", ctypes.c_int32),
+        ("by_residual", ctypes.c_int32),
         ("centroids", ctypes.c_void_p), ("codebooks", ctypes.c_void_p),
         ("list_offsets", ctypes.c_void_p), ("codes", ctypes.c_void_p), ("ids", ctypes.c_void_p),
     ]
@@ -146,8 +147,9 @@ class IvfIndex:
                 self._pinned[key] = t
                 host[key] = t.numpy()
         self._host = host
+        self.by_residual = bool(getattr(data, "by_residual", False))
         desc = IvfIndexDesc(self.d, self.nlist, self.m, 8, self.metric, max_nq, max_nprobe, max_k,
-                            host["centroids"].ctypes.data, host["codebooks"].ctypes.data,
+                            int(self.by_residual), host["centroids"].ctypes.data, host["codebooks"].ctypes.data,
                             host["list_offsets"].ctypes.data, host["codes"].ctypes.data,
                             host["ids"].ctypes.data)
         self._desc = desc

@@ -149,6 +149,10 @@ struct ivf_index {
   uint64_t n_migrations = 0;
   std::vector<hipEvent_t> event_pool;
 
+  // residual encoding: per-vector term of L2 (host copy; also uploaded with the tiles)
+  std::vector<float> pv;
+  float pv_max = 0.0f;
+
   // host-only counters (device-less index)
   std::vector<uint64_t> hc_hits;
   uint64_t hc_probes = 0, hc_queries = 0;
@@ -156,7 +160,7 @@ struct ivf_index {
   // pinned host buffers
   int32_t *h_ncold = nullptr, *h_cold = nullptr, *h_reskey = nullptr, *h_lutmax = nullptr;
   int64_t *h_resid = nullptr, *h_outids = nullptr;
-  float *h_outd = nullptr, *h_queries = nullptr;
+  float *h_outd = nullptr, *h_queries = nullptr, *h_qbmax = nullptr;
   int32_t *h_probe = nullptr;
   unsigned long long *h_stats = nullptr;
 
@@ -182,6 +186,10 @@ static HostIndexView host_view(const ivf_index *ix) {
   v.M = ix->sh.M;
   v.dsub = ix->sh.dsub;
   v.metric_ip = ix->sh.metric_ip;
+  v.by_residual = ix->desc.by_residual;
+  v.centroids = ix->desc.centroids;
+  v.pv = ix->pv.empty() ? nullptr : ix->pv.data();
+  v.pv_max = ix->pv_max;
   v.codebooks = ix->desc.codebooks;
   v.list_offsets = ix->desc.list_offsets;
   v.codes = ix->desc.codes;
@@ -198,6 +206,8 @@ static int validate_desc(const ivf_index_desc_t *d) {
   if (d->M < 16 || d->M > 128 || d->M % 16 != 0)
     return fail(IVF_EINVAL, "M must be a multiple of 16 in [16, 128] (got %d)", d->M);
   if (d->d % d->M != 0) return fail(IVF_EINVAL, "d (%d) must be a multiple of M (%d)", d->d, d->M);
+  if (d->by_residual != 0 && d->by_residual != 1)
+    return fail(IVF_EINVAL, "by_residual must be 0 or 1");
   if (d->max_nq < 1) return fail(IVF_EINVAL, "max_nq must be >= 1");
   if (d->max_nprobe < 1 || d->max_nprobe > kMaxNprobe)
     return fail(IVF_EINVAL, "max_nprobe must be in [1, %d]", kMaxNprobe);
@@ -244,6 +254,9 @@ static size_t plan_layout(const ivf_index_desc_t &d, int64_t resident_vectors, s
     w.lutmax = (uint32_t *)take(nq * 4);
     w.q_vecs = (int32_t *)take(nq * 4);
     w.order = (int32_t *)take(nq * 4);
+    w.bias = (float *)take(nq * np * 4);
+    w.g_bias = (float *)take(nq * np * 4);
+    w.qbmax = (float *)take(nq * 4);
     w.part_key = (int32_t *)take(nq * kMaxSlices * k * 4);
     w.part_id = (int64_t *)take(nq * kMaxSlices * k * 8);
     w.res_key = (int32_t *)take(nq * k * 4);
@@ -258,6 +271,9 @@ static size_t plan_layout(const ivf_index_desc_t &d, int64_t resident_vectors, s
   t.cap_tiles = cap_tiles;
   t.tile_codes = (uint8_t *)take((size_t)cap_tiles * kTileVecs * M);
   t.tile_ids = (int64_t *)take((size_t)cap_tiles * kTileVecs * 8);
+  t.tile_pv = nullptr;
+  if (d.by_residual && d.metric == IVF_METRIC_L2)
+    t.tile_pv = (float *)take((size_t)cap_tiles * kTileVecs * 4);
   off = (off + 255) & ~(size_t)255;
   if (L) *L = t;
   return off;
@@ -277,7 +293,8 @@ static hipError_t pinned_alloc(T **p, size_t count) {
 
 static void free_host_buffers(ivf_index *ix) {
   void *ptrs[] = {ix->h_ncold, ix->h_cold,   ix->h_reskey,  ix->h_lutmax, ix->h_resid,
-                  ix->h_outids, ix->h_outd,  ix->h_queries, ix->h_probe,  ix->h_stats};
+                  ix->h_outids, ix->h_outd,  ix->h_queries, ix->h_probe,  ix->h_stats,
+                  ix->h_qbmax};
   for (void *p : ptrs)
     if (p) (void)hipHostFree(p);
 }
@@ -324,7 +341,8 @@ extern "C" int ivf_index_create(const ivf_index_desc_t *desc, void *dev_arena, s
 
   ivf_index *ix = new ivf_index();
   ix->desc = *desc;
-  ix->sh = Shape{desc->d, desc->nlist, desc->M, desc->d / desc->M, desc->metric == IVF_METRIC_IP};
+  ix->sh = Shape{desc->d, desc->nlist, desc->M, desc->d / desc->M, desc->metric == IVF_METRIC_IP,
+                 desc->by_residual, 0.0f};
   ix->n_total = n_total;
   ix->h_map.assign(desc->nlist, -1);
   ix->h_len.resize(desc->nlist);
@@ -332,6 +350,13 @@ extern "C" int ivf_index_create(const ivf_index_desc_t *desc, void *dev_arena, s
     ix->h_len[c] = (int32_t)(desc->list_offsets[c + 1] - desc->list_offsets[c]);
   ix->hc_hits.assign(desc->nlist, 0);
   ix->versions.emplace_back();
+  if (desc->by_residual && desc->metric == IVF_METRIC_L2 && n_total > 0) {
+    ix->pv.resize((size_t)n_total);
+    HostIndexView v = host_view(ix);
+    v.pv = nullptr;
+    ix->pv_max = cpu_residual_pv(v, n_total, ix->pv.data());
+    ix->sh.pv_max = ix->pv_max;
+  }
 
   if (!dev_arena) {
     *out = ix;
@@ -352,7 +377,8 @@ extern "C" int ivf_index_create(const ivf_index_desc_t *desc, void *dev_arena, s
     return fail(IVF_ENOMEM, "arena of %zu bytes is smaller than the %zu bytes of fixed state",
                 arena_bytes, fixed);
   }
-  const size_t per_tile = (size_t)kTileVecs * (desc->M + 8);
+  const size_t per_tile =
+      (size_t)kTileVecs * (desc->M + 8 + ((desc->by_residual && desc->metric == IVF_METRIC_L2) ? 4 : 0));
   int64_t tiles = (int64_t)((arena_bytes - fixed) / per_tile);
   while (tiles > 0 &&
          plan_layout(*desc, tiles * kTileVecs, staging_bytes, nullptr, nullptr) > arena_bytes)
@@ -375,6 +401,7 @@ extern "C" int ivf_index_create(const ivf_index_desc_t *desc, void *dev_arena, s
       (e = pinned_alloc(&ix->h_reskey, nq * k)) != hipSuccess ||
       (e = pinned_alloc(&ix->h_resid, nq * k)) != hipSuccess ||
       (e = pinned_alloc(&ix->h_lutmax, nq)) != hipSuccess ||
+      (e = pinned_alloc(&ix->h_qbmax, nq)) != hipSuccess ||
       (e = pinned_alloc(&ix->h_outids, nq * k)) != hipSuccess ||
       (e = pinned_alloc(&ix->h_outd, nq * k)) != hipSuccess ||
       (e = pinned_alloc(&ix->h_queries, nq * (size_t)desc->d)) != hipSuccess ||
@@ -459,12 +486,15 @@ static int enqueue_cluster_copies(ivf_index *ix, const std::vector<int32_t> &clu
                                   hipStream_t st) {
   const DevLayout &L = ix->L;
   const size_t M = ix->sh.M;
-  const size_t per_tile = kTileVecs * (M + 8) + sizeof(TileDesc);
-  if (L.staging_bytes < per_tile + 1024) return fail(IVF_ENOMEM, "staging area too small");
-  const int64_t tile_cap = (int64_t)((L.staging_bytes - 768) / per_tile);
+  const bool with_pv = L.tile_pv != nullptr;
+  const size_t per_tile = kTileVecs * (M + 8 + (with_pv ? 4 : 0)) + sizeof(TileDesc);
+  if (L.staging_bytes < per_tile + 2048) return fail(IVF_ENOMEM, "staging area too small");
+  const int64_t tile_cap = (int64_t)((L.staging_bytes - 1024) / per_tile);
   unsigned char *st_codes = L.staging;
   unsigned char *st_ids = L.staging + (((size_t)tile_cap * kTileVecs * M + 255) & ~(size_t)255);
-  unsigned char *st_desc = st_ids + (((size_t)tile_cap * kTileVecs * 8 + 255) & ~(size_t)255);
+  unsigned char *st_pv = st_ids + (((size_t)tile_cap * kTileVecs * 8 + 255) & ~(size_t)255);
+  unsigned char *st_desc =
+      st_pv + (with_pv ? (((size_t)tile_cap * kTileVecs * 4 + 255) & ~(size_t)255) : 0);
 
   size_t ci = 0;          // current cluster
   int64_t tile_in = 0;    // tiles of it already copied
@@ -481,6 +511,9 @@ static int enqueue_cluster_copies(ivf_index *ix, const std::vector<int32_t> &clu
                              (size_t)run_len * M, hipMemcpyHostToDevice, st));
       HIP_TRY(hipMemcpyAsync(st_ids + (size_t)run_dst * 8, ix->desc.ids + run_src,
                              (size_t)run_len * 8, hipMemcpyHostToDevice, st));
+      if (with_pv)
+        HIP_TRY(hipMemcpyAsync(st_pv + (size_t)run_dst * 4, ix->pv.data() + run_src,
+                               (size_t)run_len * 4, hipMemcpyHostToDevice, st));
       run_len = 0;
       return IVF_OK;
     };
@@ -522,8 +555,10 @@ static int enqueue_cluster_copies(ivf_index *ix, const std::vector<int32_t> &clu
     if (chunk_tiles > 0) {
       HIP_TRY(hipMemcpyAsync(st_desc, cd, (size_t)chunk_tiles * sizeof(TileDesc),
                              hipMemcpyHostToDevice, st));
-      HIP_TRY(launch_interleave(st_codes, (const int64_t *)st_ids, (const TileDesc *)st_desc,
-                                (int)chunk_tiles, (int)M, L.tile_codes, L.tile_ids, st));
+      HIP_TRY(launch_interleave(st_codes, (const int64_t *)st_ids,
+                                with_pv ? (const float *)st_pv : nullptr,
+                                (const TileDesc *)st_desc, (int)chunk_tiles, (int)M, L.tile_codes,
+                                L.tile_ids, L.tile_pv, st));
       desc_used += (size_t)chunk_tiles;
     }
   }
@@ -724,7 +759,8 @@ extern "C" int ivf_migrate_clusters(ivf_index_t *ix, const int32_t *evict, int32
     m.new_map[clusters[i]] = (int32_t)bases[i];
     m.d_clusters += 1;
     m.d_vectors += ix->h_len[clusters[i]];
-    m.bytes += (uint64_t)ix->h_len[clusters[i]] * (uint64_t)(ix->sh.M + 8);
+    m.bytes += (uint64_t)ix->h_len[clusters[i]] *
+               (uint64_t)(ix->sh.M + 8 + (ix->L.tile_pv ? 4 : 0));
   }
   hipError_t e = pinned_alloc(&m.pinned_map, (size_t)ix->sh.nlist);
   if (e == hipSuccess && need_tiles > 0) e = pinned_alloc(&m.pinned_descs, (size_t)need_tiles);
@@ -918,8 +954,10 @@ static int search_host_only(ivf_index *ix, const float *queries, int64_t nq, con
   parallel_for(nq, [&](int64_t q) {
     std::vector<int32_t> lut((size_t)view.M * 256);
     std::vector<HostCand> cand(k);
-    const int e = cpu_build_lut(view, queries + (size_t)q * view.d, lut.data());
-    cpu_scan_lists(view, lut.data(), probe + (size_t)q * nprobe, nprobe, k, cand.data());
+    const float *qv = queries + (size_t)q * view.d;
+    const int32_t *pr = probe + (size_t)q * nprobe;
+    const int e = cpu_build_lut(view, qv, cpu_max_bias(view, qv, pr, nprobe), lut.data());
+    cpu_scan_lists(view, lut.data(), e, qv, pr, nprobe, k, cand.data());
     emit_results(ix, cand.data(), k, e, &ids[(size_t)q * k], &dists[(size_t)q * k]);
   });
   {
@@ -1054,8 +1092,12 @@ static int search_device(ivf_index *ix, const SearchArgs &a) {
   }
   // ---- routing ----
   S_TRY(mark(IVF_STAGE_ROUTE));
+  if (sh.by_residual)
+    S_TRY(launch_bias(sh, dq, nq, W.probe, np, np, L.centroids, W.bias, st));
   S_TRY(launch_route(W.probe, nq, np, np, L.clus_tile[buf], L.clus_len, sh.M, W.g_base, W.g_len,
-                     W.g_prefix, W.g_n, W.cold, W.n_cold, W.q_vecs, L.hits, L.qstats, 1, st));
+                     W.g_prefix, W.g_n, W.cold, W.n_cold, W.q_vecs,
+                     sh.by_residual ? W.bias : nullptr, W.g_bias, W.qbmax, L.hits, L.qstats, 1,
+                     st));
   S_TRY(mark(IVF_STAGE_LUT));
   const int slices = pick_slices(ix, nq);
   const bool final_on_gpu = all_resident;
@@ -1097,6 +1139,7 @@ static int search_device(ivf_index *ix, const SearchArgs &a) {
   // ---- hybrid: cold probes on the CPU, then merge (Sections 4.3.1, 4.3.2) ----
   S_TRY(hipMemcpyAsync(ix->h_ncold, W.n_cold, (size_t)nq * 4, hipMemcpyDeviceToHost, st));
   S_TRY(hipMemcpyAsync(ix->h_cold, W.cold, (size_t)nq * np * 4, hipMemcpyDeviceToHost, st));
+  S_TRY(hipMemcpyAsync(ix->h_qbmax, W.qbmax, (size_t)nq * 4, hipMemcpyDeviceToHost, st));
   const float *hq = a.q_host;
   if (!hq) {
     S_TRY(hipMemcpyAsync(ix->h_queries, dq, (size_t)nq * sh.d * 4, hipMemcpyDeviceToHost, st));
@@ -1122,16 +1165,17 @@ static int search_device(ivf_index *ix, const SearchArgs &a) {
     if (any_resident) {
       float mx;
       memcpy(&mx, &ix->h_lutmax[q], 4);
-      e = lut_exponent(mx, view.M);
+      e = lut_exponent(mx, view.M, ix->h_qbmax[q], view.pv ? view.pv_max : 0.0f);
     }
     const int nc = ix->h_ncold[q];
     const HostCand *res = gpu.data();
     if (nc > 0 || !any_resident) {
       std::vector<int32_t> lut((size_t)view.M * 256);
-      const int e_cpu = cpu_build_lut(view, hq + (size_t)q * view.d, lut.data());
+      const float *qv = hq + (size_t)q * view.d;
+      const int e_cpu = cpu_build_lut(view, qv, ix->h_qbmax[q], lut.data());
       if (any_resident && e_cpu != e) __atomic_store_n(&bad[0], 1, __ATOMIC_RELAXED);
       e = e_cpu;
-      cpu_scan_lists(view, lut.data(), ix->h_cold + (size_t)q * np, nc, k, cpu.data());
+      cpu_scan_lists(view, lut.data(), e, qv, ix->h_cold + (size_t)q * np, nc, k, cpu.data());
       merge_topk(gpu.data(), cpu.data(), k, fin.data());
       res = fin.data();
     }

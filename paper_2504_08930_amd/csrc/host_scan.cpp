@@ -46,19 +46,53 @@ void parallel_for(int64_t n, const std::function<void(int64_t)> &fn) {
   for (auto &t : th) t.join();
 }
 
-int cpu_build_lut(const HostIndexView &ix, const float *q, int32_t *lut) {
+float cpu_residual_pv(const HostIndexView &ix, int64_t n_total, float *pv) {
+  (void)n_total;
+  std::vector<float> list_max((size_t)ix.nlist, 0.0f);
+  parallel_for(ix.nlist, [&](int64_t c) {
+    const float *cen = ix.centroids + (size_t)c * ix.d;
+    float mx = 0.0f;
+    for (int64_t v = ix.list_offsets[c]; v < ix.list_offsets[c + 1]; ++v) {
+      const uint8_t *code = ix.codes + (size_t)v * ix.M;
+      float acc = 0.0f;
+      for (int m = 0; m < ix.M; ++m)
+        acc = residual_pv_accumulate(acc, ix.codebooks + ((size_t)m * 256 + code[m]) * ix.dsub,
+                                     cen + (size_t)m * ix.dsub, ix.dsub);
+      pv[v] = acc;
+      mx = std::max(mx, fabsf(acc));
+    }
+    list_max[(size_t)c] = mx;
+  });
+  float mx = 0.0f;
+  for (float v : list_max) mx = std::max(mx, v);
+  return mx;
+}
+
+float cpu_max_bias(const HostIndexView &ix, const float *q, const int32_t *clusters, int n) {
+  if (!ix.by_residual) return 0.0f;
+  float mx = 0.0f;
+  for (int i = 0; i < n; ++i) {
+    if (clusters[i] < 0) continue;
+    mx = std::max(mx, fabsf(residual_bias_host(ix.metric_ip, q,
+                                               ix.centroids + (size_t)clusters[i] * ix.d, ix.d)));
+  }
+  return mx;
+}
+
+int cpu_build_lut(const HostIndexView &ix, const float *q, float max_bias, int32_t *lut) {
   const int M = ix.M, dsub = ix.dsub;
+  const int kind = ix.metric_ip ? kLutIP : (ix.by_residual ? kLutL2Res : kLutL2);
   std::vector<float> f((size_t)M * 256);
   float mx = 0.0f;
   for (int m = 0; m < M; ++m) {
     for (int j = 0; j < 256; ++j) {
-      float v = lut_entry(ix.metric_ip, q + (size_t)m * dsub,
+      float v = lut_entry(kind, q + (size_t)m * dsub,
                           ix.codebooks + ((size_t)m * 256 + j) * dsub, dsub);
       f[(size_t)m * 256 + j] = v;
       mx = std::max(mx, fabsf(v));
     }
   }
-  const int e = lut_exponent(mx, M);
+  const int e = lut_exponent(mx, M, max_bias, ix.pv ? ix.pv_max : 0.0f);
   for (size_t i = 0; i < f.size(); ++i) lut[i] = lut_quantize(f[i], e);
   return e;
 }
@@ -67,8 +101,8 @@ static inline bool cand_less(const HostCand &a, const HostCand &b) {
   return a.key < b.key || (a.key == b.key && a.id < b.id);
 }
 
-void cpu_scan_lists(const HostIndexView &ix, const int32_t *lut, const int32_t *clusters,
-                    int n_clusters, int k, HostCand *out) {
+void cpu_scan_lists(const HostIndexView &ix, const int32_t *lut, int e, const float *q,
+                    const int32_t *clusters, int n_clusters, int k, HostCand *out) {
   // bounded max-heap on (key, id): the worst kept candidate sits on top
   std::vector<HostCand> heap;
   heap.reserve((size_t)k);
@@ -76,9 +110,14 @@ void cpu_scan_lists(const HostIndexView &ix, const int32_t *lut, const int32_t *
   for (int c = 0; c < n_clusters; ++c) {
     const int cl = clusters[c];
     if (cl < 0) continue;
+    int32_t bias_key = 0;
+    if (ix.by_residual)
+      bias_key = lut_quantize(
+          residual_bias_host(ix.metric_ip, q, ix.centroids + (size_t)cl * ix.d, ix.d), e);
     for (int64_t v = ix.list_offsets[cl]; v < ix.list_offsets[cl + 1]; ++v) {
       const uint8_t *code = ix.codes + (size_t)v * M;
-      int32_t sum = 0;
+      int32_t sum = bias_key;
+      if (ix.pv) sum += lut_quantize(ix.pv[v], e);
       for (int m = 0; m < M; ++m) sum += lut[m * 256 + code[m]];
       HostCand cand{sum, ix.ids[v]};
       if ((int)heap.size() < k) {

@@ -18,6 +18,10 @@ struct HostCand {
 
 struct HostIndexView {
   int d, nlist, M, dsub, metric_ip;
+  int by_residual;              // codes encode x - centroid of the list
+  const float *centroids;       // [nlist][d] (residual encoding only)
+  const float *pv;              // [N] per-vector term (residual-encoded L2 only), else NULL
+  float pv_max;                 // largest |pv|
   const float *codebooks;       // [M][256][dsub]
   const int64_t *list_offsets;  // [nlist+1]
   const uint8_t *codes;         // [N][M]
@@ -29,13 +33,22 @@ int cpu_threads();
 // Run fn(i) for i in [0, n) on up to cpu_threads() threads.
 void parallel_for(int64_t n, const std::function<void(int64_t)> &fn);
 
-// Fixed-point table of one query: lut[m*256 + j]; returns the scale exponent.
-int cpu_build_lut(const HostIndexView &ix, const float *q, int32_t *lut);
+// Per-vector term |r|^2 + 2 c.r of residual-encoded L2 for every stored vector
+// (r = decoded residual, c = centroid of its list); returns the largest |pv|.
+float cpu_residual_pv(const HostIndexView &ix, int64_t n_total, float *pv);
 
-// Scan the listed clusters for one query; writes k candidates, best first,
-// padded with (kKeyInvalid, -1).
-void cpu_scan_lists(const HostIndexView &ix, const int32_t *lut, const int32_t *clusters,
-                    int n_clusters, int k, HostCand *out);
+// Largest |bias(q, list)| over the listed clusters (negative ids skipped);
+// 0 without residual encoding.
+float cpu_max_bias(const HostIndexView &ix, const float *q, const int32_t *clusters, int n);
+
+// Fixed-point table of one query: lut[m*256 + j]; max_bias: largest |bias| among
+// ALL of the query's probes (resident or not).  Returns the scale exponent.
+int cpu_build_lut(const HostIndexView &ix, const float *q, float max_bias, int32_t *lut);
+
+// Scan the listed clusters for one query with the table and exponent from
+// cpu_build_lut; writes k candidates, best first, padded with (kKeyInvalid, -1).
+void cpu_scan_lists(const HostIndexView &ix, const int32_t *lut, int e, const float *q,
+                    const int32_t *clusters, int n_clusters, int k, HostCand *out);
 
 // Merge two best-first lists of k candidates into the k best.
 void merge_topk(const HostCand *a, const HostCand *b, int k, HostCand *out);

@@ -51,6 +51,9 @@ struct BatchWs {
   uint32_t *lutmax;        // [max_nq] bits of the largest |entry| of the query's table
   int32_t *q_vecs;         // [max_nq] vectors in the query's resident probes
   int32_t *order;          // [max_nq] scan visiting order of the queries
+  float *bias;             // [max_nq][max_nprobe] residual encoding: bias(q, probe), probe order
+  float *g_bias;           // [max_nq][max_nprobe] the same for resident probes, work-list order
+  float *qbmax;            // [max_nq] largest |bias| among the query's probes (0 if unused)
   int32_t *part_key;       // [max_nq][kMaxSlices][max_k]
   int64_t *part_id;
   int32_t *res_key;        // [max_nq][max_k] merged GPU partial (hybrid path)
@@ -74,11 +77,16 @@ struct DevLayout {
   size_t staging_bytes;
   uint8_t *tile_codes;     // [cap_tiles][M*64]
   int64_t *tile_ids;       // [cap_tiles][64]
+  float *tile_pv;          // [cap_tiles][64] per-vector term (residual-encoded L2), else NULL
   int64_t cap_tiles;
 };
 
 struct Shape {
   int d, nlist, M, dsub, metric_ip;
+  int by_residual;   // codes encode x - centroid
+  float pv_max;      // largest |per-vector term| (residual-encoded L2), else 0
+  int lut_kind() const { return metric_ip ? 1 : (by_residual ? 2 : 0); }
+  int scan_res() const { return by_residual ? (metric_ip ? 1 : 2) : 0; }
 };
 
 // ---- kernel launchers (kernels_*.hip).  All enqueue on `st` and return the
@@ -100,11 +108,17 @@ hipError_t launch_coarse_gemm(const Shape &sh, const void *q_parts, int nq, cons
 hipError_t launch_coarse_select(const Shape &sh, const float *scores, int nq, int nprobe,
                                 int probe_stride, int32_t *probe, hipStream_t st);
 
+// bias(q, probe) for every probe of every query (residual encoding)
+hipError_t launch_bias(const Shape &sh, const float *q, int nq, const int32_t *probe, int nprobe,
+                       int probe_stride, const float *centroids, float *bias, hipStream_t st);
+
+// bias may be NULL (no residual encoding): g_bias is then untouched and qbmax set to 0.
 hipError_t launch_route(const int32_t *probe, int nq, int nprobe, int probe_stride,
                         const int32_t *clus_tile, const int32_t *clus_len, int M, int32_t *g_base,
                         int32_t *g_len, int32_t *g_prefix, int32_t *g_n, int32_t *cold,
-                        int32_t *n_cold, int32_t *q_vecs, unsigned long long *hits,
-                        unsigned long long *qstats, int count_stats, hipStream_t st);
+                        int32_t *n_cold, int32_t *q_vecs, const float *bias, float *g_bias,
+                        float *qbmax, unsigned long long *hits, unsigned long long *qstats,
+                        int count_stats, hipStream_t st);
 
 hipError_t launch_order(const int32_t *probe, int nq, int probe_stride, int32_t *order,
                         hipStream_t st);
@@ -120,9 +134,11 @@ hipError_t launch_scan(const Shape &sh, const DevLayout &L, const BatchWs &W, in
 hipError_t launch_merge(const Shape &sh, const BatchWs &W, int nq, int slices, int k,
                         int64_t *out_ids, float *out_dists, hipStream_t st);
 
+// stage_pv / tile_pv may be NULL
 hipError_t launch_interleave(const uint8_t *stage_codes, const int64_t *stage_ids,
-                             const TileDesc *descs, int n_tiles, int M, uint8_t *tile_codes,
-                             int64_t *tile_ids, hipStream_t st);
+                             const float *stage_pv, const TileDesc *descs, int n_tiles, int M,
+                             uint8_t *tile_codes, int64_t *tile_ids, float *tile_pv,
+                             hipStream_t st);
 
 bool scan_supports(int M, int k);
 

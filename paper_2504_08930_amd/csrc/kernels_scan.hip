@@ -139,6 +139,38 @@ hipError_t launch_calib_read(const void *src, void *sink, size_t bytes, hipStrea
 }
 
 // ---------------------------------------------------------------------------
+// Residual encoding: bias(q, probe) = -(q.c) (IP) or |q - c|^2 (L2) for every
+// probe, one wavefront per (query, probe); partial sums and butterfly order
+// as in lut_quant.h so the CPU scan gets the same bits.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_bias(const float *__restrict__ q, int nq, int d,
+                                              const int32_t *__restrict__ probe, int nprobe,
+                                              int stride, const float *__restrict__ cent,
+                                              int metric_ip, float *__restrict__ bias) {
+  const long long w = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int lane = threadIdx.x & 63;
+  if (w >= (long long)nq * nprobe) return;
+  const int qi = (int)(w / nprobe), p = (int)(w % nprobe);
+  const int c = probe[(size_t)qi * stride + p];
+  float t = 0.0f;
+  if (c >= 0) {
+    t = residual_bias_part(metric_ip, q + (size_t)qi * d, cent + (size_t)c * d, d, lane);
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) t += __shfl_xor(t, o, 64);
+    if (metric_ip) t = -t;
+  }
+  if (lane == 0) bias[(size_t)qi * stride + p] = t;
+}
+
+hipError_t launch_bias(const Shape &sh, const float *q, int nq, const int32_t *probe, int nprobe,
+                       int probe_stride, const float *centroids, float *bias, hipStream_t st) {
+  const long long waves = (long long)nq * nprobe;
+  hipLaunchKernelGGL(k_bias, dim3((unsigned)((waves + 3) / 4)), dim3(256), 0, st, q, nq, sh.d,
+                     probe, nprobe, probe_stride, centroids, sh.metric_ip, bias);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
 // Routing (Section 4.3.1): each probe is looked up in the mapping table;
 // resident probes form the query's GPU work list, the others its cold list.
 // Also the router's counters (Section 4.3.3).
@@ -147,7 +179,8 @@ __global__ __launch_bounds__(256) void k_route(
     const int32_t *__restrict__ probe, int nq, int nprobe, int stride,
     const int32_t *__restrict__ clus_tile, const int32_t *__restrict__ clus_len, int M,
     int32_t *g_base, int32_t *g_len, int32_t *g_prefix, int32_t *g_n, int32_t *cold,
-    int32_t *n_cold, int32_t *q_vecs, unsigned long long *hits, int count_stats) {
+    int32_t *n_cold, int32_t *q_vecs, const float *__restrict__ bias, float *g_bias, float *qbmax,
+    unsigned long long *hits, int count_stats) {
   // one wavefront per query, one lane per probe (64 probes per step); the GPU
   // work list keeps probe order
   const int q = blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -161,15 +194,21 @@ __global__ __launch_bounds__(256) void k_route(
   const unsigned long long lt = (1ull << lane) - 1ull;
   int ng = 0, nc = 0, tiles = 0, valid_n = 0;
   unsigned long long vecs = 0;
+  float bmax = 0.0f;
   for (int base = 0; base < nprobe; base += 64) {
     const int p = base + lane;
     const int c = p < nprobe ? pr[p] : -1;
     const bool valid = c >= 0;
     int t = -1, len = 0;
+    float b = 0.0f;
     if (valid) {
       if (count_stats) atomicAdd(&hits[c], 1ull);
       t = clus_tile[c];
       len = clus_len[c];
+      if (bias) {
+        b = bias[(size_t)q * stride + p];
+        bmax = fmaxf(bmax, fabsf(b));
+      }
     }
     const bool res = valid && t >= 0;
     const bool cld = valid && t < 0;
@@ -187,6 +226,7 @@ __global__ __launch_bounds__(256) void k_route(
       gb[o] = t;
       gl[o] = len;
       gp[o] = tiles + incl - nt;
+      if (bias) g_bias[(size_t)q * stride + o] = b;
     }
     if (cld) cd[nc + __popcll(mcold & lt)] = c;
     // wave totals
@@ -200,7 +240,10 @@ __global__ __launch_bounds__(256) void k_route(
     valid_n += __popcll(__ballot(valid));
   }
   for (int p = nc + lane; p < nprobe; p += 64) cd[p] = -1;
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) bmax = fmaxf(bmax, __shfl_xor(bmax, o, 64));
   if (lane == 0) {
+    qbmax[q] = bmax;
     gp[ng] = tiles;
     g_n[q] = ng;
     n_cold[q] = nc;
@@ -312,11 +355,12 @@ hipError_t launch_order(const int32_t *probe, int nq, int probe_stride, int32_t 
 hipError_t launch_route(const int32_t *probe, int nq, int nprobe, int probe_stride,
                         const int32_t *clus_tile, const int32_t *clus_len, int M, int32_t *g_base,
                         int32_t *g_len, int32_t *g_prefix, int32_t *g_n, int32_t *cold,
-                        int32_t *n_cold, int32_t *q_vecs, unsigned long long *hits,
-                        unsigned long long *qstats, int count_stats, hipStream_t st) {
+                        int32_t *n_cold, int32_t *q_vecs, const float *bias, float *g_bias,
+                        float *qbmax, unsigned long long *hits, unsigned long long *qstats,
+                        int count_stats, hipStream_t st) {
   hipLaunchKernelGGL(k_route, dim3((nq + 3) / 4), dim3(256), 0, st, probe, nq, nprobe,
                      probe_stride, clus_tile, clus_len, M, g_base, g_len, g_prefix, g_n, cold,
-                     n_cold, q_vecs, hits, count_stats);
+                     n_cold, q_vecs, bias, g_bias, qbmax, hits, count_stats);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(k_route_stats, dim3(1), dim3(1024), 0, st, g_n, n_cold, q_vecs, nq, M, qstats,
@@ -338,7 +382,7 @@ constexpr int kLutJPT = 8;     // codewords (of one sub-quantizer) per thread
 template <int DSUB>
 __global__ __launch_bounds__(256) void k_lut(const float *__restrict__ queries, int nq, int d,
                                              int M, int dsub_rt, int MW,
-                                             const float *__restrict__ cbT, int metric_ip,
+                                             const float *__restrict__ cbT, int kind,
                                              float *__restrict__ lut,
                                              uint32_t *__restrict__ lutpart) {
   const int dsub = DSUB > 0 ? DSUB : dsub_rt;
@@ -370,8 +414,8 @@ __global__ __launch_bounds__(256) void k_lut(const float *__restrict__ queries, 
 #pragma unroll
     for (int t = 0; t < kLutJPT; ++t) {
       const int j = j0 + t * JL;
-      const float v = DSUB > 0 ? lut_entry(metric_ip, qreg, creg[t], DSUB)
-                               : lut_entry(metric_ip, qv, cbT + ((size_t)j * M + m) * dsub, dsub);
+      const float v = DSUB > 0 ? lut_entry(kind, qreg, creg[t], DSUB)
+                               : lut_entry(kind, qv, cbT + ((size_t)j * M + m) * dsub, dsub);
       lut[((size_t)qi * 256 + j) * M + m] = v;
       mxf = fmaxf(mxf, fabsf(v));
     }
@@ -407,7 +451,7 @@ hipError_t launch_lut(const Shape &sh, const float *q, int nq, const float *cbT,
 #define IVF_LUT_CASE(DS)                                                                       \
   case DS:                                                                                     \
     hipLaunchKernelGGL(k_lut<DS>, grid, dim3(256), 0, st, q, nq, sh.d, sh.M, sh.dsub, MW, cbT, \
-                       sh.metric_ip, lut, lutpart);                                            \
+                       sh.lut_kind(), lut, lutpart);                                           \
     break;
   switch (sh.dsub) {
     IVF_LUT_CASE(2)
@@ -417,7 +461,7 @@ hipError_t launch_lut(const Shape &sh, const float *q, int nq, const float *cbT,
     IVF_LUT_CASE(16)
     default:
       hipLaunchKernelGGL(k_lut<0>, grid, dim3(256), 0, st, q, nq, sh.d, sh.M, sh.dsub, MW, cbT,
-                         sh.metric_ip, lut, lutpart);
+                         sh.lut_kind(), lut, lutpart);
   }
 #undef IVF_LUT_CASE
   hipError_t e = hipGetLastError();
@@ -452,9 +496,11 @@ __host__ __device__ inline int src_subq(int lane, int i, int M) {
 
 __global__ __launch_bounds__(512) void k_interleave(const uint8_t *__restrict__ stage_codes,
                                                     const int64_t *__restrict__ stage_ids,
+                                                    const float *__restrict__ stage_pv,
                                                     const TileDesc *__restrict__ descs, int M,
                                                     uint8_t *__restrict__ tile_codes,
-                                                    int64_t *__restrict__ tile_ids) {
+                                                    int64_t *__restrict__ tile_ids,
+                                                    float *__restrict__ tile_pv) {
   const TileDesc td = descs[blockIdx.x];
   const int units = M / 16;
   const int lane = threadIdx.x & 63;
@@ -476,15 +522,17 @@ __global__ __launch_bounds__(512) void k_interleave(const uint8_t *__restrict__ 
   }
   if (u == 0) {
     tile_ids[(size_t)td.dst_tile * kTileVecs + lane] = valid ? stage_ids[src] : -1;
+    if (tile_pv) tile_pv[(size_t)td.dst_tile * kTileVecs + lane] = valid ? stage_pv[src] : 0.0f;
   }
 }
 
 hipError_t launch_interleave(const uint8_t *stage_codes, const int64_t *stage_ids,
-                             const TileDesc *descs, int n_tiles, int M, uint8_t *tile_codes,
-                             int64_t *tile_ids, hipStream_t st) {
+                             const float *stage_pv, const TileDesc *descs, int n_tiles, int M,
+                             uint8_t *tile_codes, int64_t *tile_ids, float *tile_pv,
+                             hipStream_t st) {
   if (n_tiles <= 0) return hipSuccess;
-  hipLaunchKernelGGL(k_interleave, dim3(n_tiles), dim3(512), 0, st, stage_codes, stage_ids, descs,
-                     M, tile_codes, tile_ids);
+  hipLaunchKernelGGL(k_interleave, dim3(n_tiles), dim3(512), 0, st, stage_codes, stage_ids,
+                     stage_pv, descs, M, tile_codes, tile_ids, tile_pv);
   return hipGetLastError();
 }
 
@@ -498,6 +546,10 @@ struct ScanParams {
   const int64_t *tile_ids;
   const float *lut;
   const uint32_t *lutmax;
+  const float *qbmax;
+  const float *g_bias;
+  const float *tile_pv;
+  float pv_max;
   const int32_t *g_base;
   const int32_t *g_len;
   const int32_t *g_prefix;
@@ -525,9 +577,12 @@ struct TileRef {
   int gtile;   // tile index in the cluster region
   int first;   // position of lane 0 inside its list
   int len;     // list length
+  int bias;    // quantized bias(q, list) (residual encoding), else 0
 };
 
-template <int M, int NW, int CAP>
+// RES: 0 = codes encode the vector; 1 = residual, inner product (bias per
+// list); 2 = residual, L2 (bias per list + one float per vector).
+template <int M, int NW, int CAP, int RES>
 __global__ __launch_bounds__(NW * 64) void k_scan(ScanParams P) {
   using G = ScanGeom<M>;
   extern __shared__ __align__(16) unsigned char smem[];
@@ -559,8 +614,9 @@ __global__ __launch_bounds__(NW * 64) void k_scan(ScanParams P) {
   const int k = P.k;
 
   // ---- stage the query's table in LDS as fixed point, code-major ----
+  const int e = lut_exponent(__uint_as_float(P.lutmax[q]), M, RES ? P.qbmax[q] : 0.0f,
+                             RES == 2 ? P.pv_max : 0.0f);
   {
-    const int e = lut_exponent(__uint_as_float(P.lutmax[q]), M);
     const float4 *src = reinterpret_cast<const float4 *>(P.lut + (size_t)q * 256 * M);
     constexpr int kVec = 256 * M / 4;
     for (int idx = tid; idx < kVec; idx += NW * 64) {
@@ -605,7 +661,8 @@ __global__ __launch_bounds__(NW * 64) void k_scan(ScanParams P) {
 
   // window of 64 probes held one per lane
   int win_base = -64, win_end = 0;  // win_end: first tile index beyond the window
-  int w_pre = 0, w_tile = 0, w_len = 0;
+  int w_pre = 0, w_tile = 0, w_len = 0, w_bias = 0;
+  const float *gbias = P.g_bias + (size_t)q * P.probe_stride;
 
   auto locate = [&](int t) -> TileRef {
     while (t >= win_end) {  // wave-uniform
@@ -615,6 +672,7 @@ __global__ __launch_bounds__(NW * 64) void k_scan(ScanParams P) {
       w_pre = in ? gpre[p] : 0x7fffffff;
       w_tile = in ? gbase[p] : 0;
       w_len = in ? glen[p] : 0;
+      if (RES) w_bias = in ? lut_quantize(gbias[p], e) : 0;
       const int last = min(win_base + 64, ng);
       win_end = gpre[last];
     }
@@ -625,14 +683,16 @@ __global__ __launch_bounds__(NW * 64) void k_scan(ScanParams P) {
     r.gtile = __builtin_amdgcn_readlane(w_tile, pl) + (t - pre);
     r.first = (t - pre) * kTileVecs;
     r.len = __builtin_amdgcn_readlane(w_len, pl);
+    r.bias = RES ? __builtin_amdgcn_readlane(w_bias, pl) : 0;
     return r;
   };
 
-  auto load_tile = [&](const TileRef &tr, uint4 (&c)[M / 16]) {
+  auto load_tile = [&](const TileRef &tr, uint4 (&c)[M / 16], float &pv) {
     const uint4 *src =
         reinterpret_cast<const uint4 *>(P.tile_codes + (size_t)tr.gtile * (kTileVecs * M));
 #pragma unroll
     for (int u = 0; u < M / 16; ++u) c[u] = src[u * 64 + lane];
+    if (RES == 2) pv = P.tile_pv[(size_t)tr.gtile * kTileVecs + lane];
   };
 
   int cnt = 0;            // candidates in this wave's (unsorted) buffer
@@ -694,8 +754,9 @@ __global__ __launch_bounds__(NW * 64) void k_scan(ScanParams P) {
     }
   };
 
-  auto process = [&](const TileRef &tr, const uint4 (&c)[M / 16]) {
-    int acc = 0;
+  auto process = [&](const TileRef &tr, const uint4 (&c)[M / 16], float pv) {
+    int acc = tr.bias;
+    if (RES == 2) acc += lut_quantize(pv, e);
 #pragma unroll
     for (int u = 0; u < M / 16; ++u) {
       const uint32_t dw[4] = {c[u].x, c[u].y, c[u].z, c[u].w};
@@ -734,26 +795,29 @@ __global__ __launch_bounds__(NW * 64) void k_scan(ScanParams P) {
 
   {
     int t = t_begin + w;
-    TileRef cur{0, 0, 0};
+    TileRef cur{0, 0, 0, 0};
     uint4 ca[M / 16];
+    float pa = 0.0f;
     if (t < t_end) {
       cur = locate(t);
-      load_tile(cur, ca);
+      load_tile(cur, ca, pa);
     }
     while (t < t_end) {
       const int tn = t + NW;
-      TileRef nxt{0, 0, 0};
+      TileRef nxt{0, 0, 0, 0};
       uint4 cb[M / 16];
+      float pb = 0.0f;
       if (tn < t_end) {
         nxt = locate(tn);
-        load_tile(nxt, cb);
+        load_tile(nxt, cb, pb);
       } else {
 #pragma unroll
         for (int u = 0; u < M / 16; ++u) cb[u] = make_uint4(0, 0, 0, 0);
       }
-      process(cur, ca);
+      process(cur, ca, pa);
 #pragma unroll
       for (int u = 0; u < M / 16; ++u) ca[u] = cb[u];
+      pa = pb;
       cur = nxt;
       t = tn;
     }
@@ -845,20 +909,20 @@ __global__ __launch_bounds__(NW * 64) void k_scan(ScanParams P) {
   }
 }
 
-template <int M, int NW, int CAP>
+template <int M, int NW, int CAP, int RES>
 static hipError_t launch_scan_t(const ScanParams &P, int nq, hipStream_t st) {
   using G = ScanGeom<M>;
   const size_t lds = (size_t)G::kTables * G::kTableBytes + (size_t)NW * CAP * 12 + 64;
   static bool attr_done = false;
   if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_scan<M, NW, CAP>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_scan<M, NW, CAP, RES>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
     attr_done = true;
   }
   const int total = nq * P.slices;
   const int grid = (total + 8 * kScanChunk - 1) / (8 * kScanChunk) * (8 * kScanChunk);
-  hipLaunchKernelGGL((k_scan<M, NW, CAP>), dim3(grid), dim3(NW * 64), lds, st, P);
+  hipLaunchKernelGGL((k_scan<M, NW, CAP, RES>), dim3(grid), dim3(NW * 64), lds, st, P);
   return hipGetLastError();
 }
 
@@ -886,10 +950,18 @@ hipError_t launch_scan(const Shape &sh, const DevLayout &L, const BatchWs &W, in
   P.probe_stride = probe_stride;
   P.slices = slices;
   P.k = k;
-#define IVF_SCAN_CASE(MM)                                             \
-  case MM:                                                            \
-    return k <= 64 ? launch_scan_t<MM, 16, 128>(P, nq, st)            \
-                   : launch_scan_t<MM, 8, 256>(P, nq, st);
+  P.qbmax = W.qbmax;
+  P.g_bias = W.g_bias;
+  P.tile_pv = L.tile_pv;
+  P.pv_max = sh.pv_max;
+  const int res = sh.scan_res();
+#define IVF_SCAN_RES(MM, NW_, CAP_)                                               \
+  (res == 0 ? launch_scan_t<MM, NW_, CAP_, 0>(P, nq, st)                          \
+            : res == 1 ? launch_scan_t<MM, NW_, CAP_, 1>(P, nq, st)               \
+                       : launch_scan_t<MM, NW_, CAP_, 2>(P, nq, st))
+#define IVF_SCAN_CASE(MM) \
+  case MM:                \
+    return k <= 64 ? IVF_SCAN_RES(MM, 16, 128) : IVF_SCAN_RES(MM, 8, 256);
   switch (sh.M) {
     IVF_SCAN_CASE(16)
     IVF_SCAN_CASE(32)
@@ -899,6 +971,7 @@ hipError_t launch_scan(const Shape &sh, const DevLayout &L, const BatchWs &W, in
     IVF_SCAN_CASE(128)
   }
 #undef IVF_SCAN_CASE
+#undef IVF_SCAN_RES
   return hipErrorInvalidValue;
 }
 
@@ -909,6 +982,7 @@ hipError_t launch_scan(const Shape &sh, const DevLayout &L, const BatchWs &W, in
 __global__ __launch_bounds__(64) void k_merge(const int32_t *__restrict__ part_key,
                                               const int64_t *__restrict__ part_id, int slices,
                                               int k, int n2, const uint32_t *__restrict__ lutmax,
+                                              const float *__restrict__ qbmax, float pv_max,
                                               int M, int metric_ip, int32_t *res_key, int64_t *res_id,
                                               int64_t *out_ids, float *out_dists) {
   __shared__ int mkey[kMaxSlices * kMaxK];
@@ -923,7 +997,7 @@ __global__ __launch_bounds__(64) void k_merge(const int32_t *__restrict__ part_k
   }
   wave_sync();
   if (slices > 1) bitonic_sort_lds<false>(mkey, mid, n2, lane, 64);
-  const int e = lut_exponent(__uint_as_float(lutmax[q]), M);
+  const int e = lut_exponent(__uint_as_float(lutmax[q]), M, qbmax[q], pv_max);
   for (int r = lane; r < k; r += 64) {
     const int key = mkey[r];
     const bool ok = key != kKeyInvalid;
@@ -943,7 +1017,7 @@ hipError_t launch_merge(const Shape &sh, const BatchWs &W, int nq, int slices, i
   int n2 = 1;
   while (n2 < slices * k) n2 <<= 1;
   hipLaunchKernelGGL(k_merge, dim3(nq), dim3(64), 0, st, W.part_key, W.part_id, slices, k, n2,
-                     W.lutmax, sh.M, sh.metric_ip, W.res_key, W.res_id, out_ids, out_dists);
+                     W.lutmax, W.qbmax, sh.scan_res() == 2 ? sh.pv_max : 0.0f, sh.M, sh.metric_ip, W.res_key, W.res_id, out_ids, out_dists);
   return hipGetLastError();
 }
 

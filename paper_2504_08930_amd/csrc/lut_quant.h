@@ -15,6 +15,15 @@
 // and e chosen so that B * 2^e <= 2^30, every entry is off by at most
 // 2^-(e+1), the sum by at most M * 2^-(e+1) <= M * B / 2^30
 // (~ 9e-8 * B at M = 96).
+//
+// Residual encoding (codes hold x - centroid of the list): the distance to the
+// decoded vector centroid + r splits into
+//   IP:  q.c + q.r                      = bias(q, list) + table sum
+//   L2:  |q-c|^2 + (|r|^2 + 2 c.r) - 2 q.r = bias(q, list) + pv(vector) + table sum
+// with ONE table per query (entries -q_m.cb, resp. -2 q_m.cb); bias and the
+// per-vector term pv are quantized with the same scale and added as integers,
+// so the sum stays exact and order-independent.  B then also covers the largest
+// |bias| among the query's probes and the largest |pv| of the index.
 #pragma once
 #include <math.h>
 #include <stdint.h>
@@ -30,13 +39,18 @@ namespace ivf {
 
 constexpr int kKeyInvalid = 0x7fffffff;  // larger than any valid code sum
 
-// One table entry: L2 -> sum_t (q_t - c_t)^2, IP -> -(sum_t q_t * c_t).
-// Sequential fused multiply-adds in index order (bit-identical on host and device).
-IVF_HD inline float lut_entry(int metric_ip, const float *q, const float *c, int dsub) {
+// Table kinds
+constexpr int kLutL2 = 0;      // entry = sum_t (q_t - c_t)^2
+constexpr int kLutIP = 1;      // entry = -(sum_t q_t * c_t)
+constexpr int kLutL2Res = 2;   // entry = -2 * (sum_t q_t * c_t)   (residual-encoded L2)
+
+// One table entry.  Sequential fused multiply-adds in index order
+// (bit-identical on host and device).
+IVF_HD inline float lut_entry(int kind, const float *q, const float *c, int dsub) {
   float acc = 0.0f;
-  if (metric_ip) {
+  if (kind != kLutL2) {
     for (int t = 0; t < dsub; ++t) acc = __builtin_fmaf(q[t], c[t], acc);
-    return -acc;
+    return kind == kLutIP ? -acc : -2.0f * acc;
   }
   for (int t = 0; t < dsub; ++t) {
     float diff = q[t] - c[t];
@@ -45,10 +59,12 @@ IVF_HD inline float lut_entry(int metric_ip, const float *q, const float *c, int
   return acc;
 }
 
-// Scale exponent from the largest |entry| of the query's table:
-// B = M * maxabs = f * 2^x with f in [0.5, 1)  =>  B * 2^(30 - x) <= 2^30.
-IVF_HD inline int lut_exponent(float maxabs, int M) {
-  const double B = (double)M * (double)maxabs;
+// Scale exponent from the largest |entry| of the query's table (plus, with
+// residual encoding, the largest |bias| of the query and |pv| of the index):
+// B = M * maxabs + max_bias + max_pv = f * 2^x with f in [0.5, 1)
+//   =>  B * 2^(30 - x) <= 2^30.
+IVF_HD inline int lut_exponent(float maxabs, int M, float max_bias = 0.0f, float max_pv = 0.0f) {
+  const double B = (double)M * (double)maxabs + (double)max_bias + (double)max_pv;
   if (!(B > 0.0)) return 0;
   const uint64_t bits = __builtin_bit_cast(uint64_t, B);
   int x = (int)((bits >> 52) & 0x7ff) - 1022;
@@ -60,6 +76,50 @@ IVF_HD inline int lut_exponent(float maxabs, int M) {
 
 IVF_HD inline int lut_quantize(float v, int e) {
   return (int)__builtin_rintf(__builtin_ldexpf(v, e));
+}
+
+// Residual encoding: partial sum over elements i = lane, lane + 64, ... of the
+// (query, centroid) term; the 64 partial sums are then combined by a fixed
+// xor-butterfly (residual_bias_combine), the same on host and device.
+IVF_HD inline float residual_bias_part(int metric_ip, const float *q, const float *c, int d,
+                                       int lane) {
+  float acc = 0.0f;
+  for (int i = lane; i < d; i += 64) {
+    if (metric_ip) {
+      acc = __builtin_fmaf(q[i], c[i], acc);
+    } else {
+      const float diff = q[i] - c[i];
+      acc = __builtin_fmaf(diff, diff, acc);
+    }
+  }
+  return acc;
+}
+
+// Host form of the butterfly: part[64] -> total (every slot ends up equal).
+inline float residual_bias_combine(float *part) {
+  for (int o = 32; o > 0; o >>= 1) {
+    float nxt[64];
+    for (int l = 0; l < 64; ++l) nxt[l] = part[l] + part[l ^ o];
+    for (int l = 0; l < 64; ++l) part[l] = nxt[l];
+  }
+  return part[0];
+}
+
+// bias(q, list): IP -> -(q.c), L2 -> |q - c|^2.
+inline float residual_bias_host(int metric_ip, const float *q, const float *c, int d) {
+  float part[64];
+  for (int l = 0; l < 64; ++l) part[l] = residual_bias_part(metric_ip, q, c, d, l);
+  const float t = residual_bias_combine(part);
+  return metric_ip ? -t : t;
+}
+
+// Per-vector term of residual-encoded L2: |r|^2 + 2 c.r for the decoded residual r.
+IVF_HD inline float residual_pv_accumulate(float acc, const float *r, const float *c, int n) {
+  for (int t = 0; t < n; ++t) {
+    acc = __builtin_fmaf(r[t], r[t], acc);
+    acc = __builtin_fmaf(2.0f * c[t], r[t], acc);
+  }
+  return acc;
 }
 
 // Integer code sum -> reported distance.

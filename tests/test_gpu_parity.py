@@ -29,17 +29,18 @@ def pkg():
 _CACHE = {}
 
 
-def _case(name, device="cuda"):
-    if name not in _CACHE:
+def _case(name, device="cuda", by_residual=False):
+    key = name + ("/res" if by_residual else "")
+    if key not in _CACHE:
         spec = SPECS[name]
-        _say(f"building index {name} on {device}")
-        ix = build_index(spec, device=device)
+        _say(f"building index {key} on {device}")
+        ix = build_index(spec, device=device, by_residual=by_residual)
         import torch
         centers = mixture_centers(spec, torch.device(device))
         q, _ = make_queries(spec, centers)
         calib, _ = make_queries(spec, centers, nq=max(spec.nq, 256), seed=spec.seed_calib)
-        _CACHE[name] = (spec, ix, q.cpu().numpy(), calib.cpu().numpy())
-    return _CACHE[name]
+        _CACHE[key] = (spec, ix, q.cpu().numpy(), calib.cpu().numpy())
+    return _CACHE[key]
 
 
 def hottest(index, calib_q, nprobe, frac, nlist):
@@ -75,7 +76,8 @@ def _check_search(oracle, ix, q, nprobe, k, got_ids, got_d, got_probe=None):
         n_coarse = compare_probes(got_probe[:, :npb], probe_ext, score_ext, npb, S)
         use_probe = np.ascontiguousarray(got_probe[:, :npb])
     ref_i, ref_d = oracle.scan(ix.metric, ix.codebooks, ix.list_offsets, ix.codes, ix.ids, q,
-                               use_probe, k + 16)
+                               use_probe, k + 16,
+                               residual_centroids=oracle.residual_centroids_of(ix))
     n_amb = compare_topk(got_ids, got_d, ref_i, ref_d, k, S)
     return n_coarse, n_amb
 
@@ -352,3 +354,40 @@ def test_k100_nprobe128(pkg, oracle):
     assert np.array_equal(dist10.cpu().numpy(), dist[:, :10])
     index.close()
     _CACHE.pop("C4S", None)
+
+
+@pytest.mark.parametrize("name", ["T_L2", "T_IP", "T_IP96"])
+def test_residual_encoding(pkg, oracle, name):
+    """Residual-encoded codes (x - centroid): bias per (query, list) and, for L2, a
+    per-vector term, all added in the integer domain.  Oracle parity and exact
+    independence of the resident set."""
+    import torch
+    spec, ix, q, calib = _case(name, by_residual=True)
+    assert ix.by_residual
+    index = pkg.IvfIndex(ix, max_nq=256, max_nprobe=ix.nlist, max_k=128)
+    full = np.arange(ix.nlist, dtype=np.int32)
+    index.load_partition(full)
+    qd = torch.from_numpy(q).cuda()
+    base = None
+    for nprobe, k in ((spec.nprobe, spec.k), (ix.nlist, 100)):
+        _say(f"{name}/res nprobe={nprobe} k={k}")
+        probe = index.coarse_probe_dev(qd, nprobe).cpu().numpy()
+        ids, dist = index.search_batch(q, nprobe, k)
+        n_coarse, n_amb = _check_search(oracle, ix, q, nprobe, k, ids, dist, probe)
+        assert n_coarse <= 1 and n_amb <= max(1, q.shape[0] // 20)
+        if base is None:
+            base = (ids, dist)
+    rng = np.random.default_rng(7)
+    for rs in (np.zeros(0, np.int32), full[::2].copy(),
+               np.sort(rng.choice(ix.nlist, ix.nlist // 3, replace=False)).astype(np.int32)):
+        index.load_partition(rs)
+        ids, dist = index.search_batch(q, spec.nprobe, spec.k)
+        assert np.array_equal(ids, base[0]) and np.array_equal(dist, base[1])
+    # migration carries the per-vector term along
+    side = torch.cuda.Stream()
+    index.migrate_clusters(rs[: len(rs) // 2], np.setdiff1d(full, rs)[: ix.nlist // 4],
+                           side_stream=side)
+    index.migrate_poll(wait=True)
+    ids, dist = index.search_batch(q, spec.nprobe, spec.k)
+    assert np.array_equal(ids, base[0]) and np.array_equal(dist, base[1])
+    index.close()

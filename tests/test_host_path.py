@@ -56,6 +56,24 @@ def test_host_only_search_matches_oracle(case, oracle):
         assert amb <= max(1, q.shape[0] // 20)
 
 
+@pytest.mark.parametrize("name", ["T_L2", "T_IP", "T_IP96"])
+def test_host_only_residual_encoding_matches_oracle(lib, oracle, name):
+    """Codes that encode x - centroid: bias per list, per-vector term for L2."""
+    spec = SPECS[name]
+    ix = build_index(spec, by_residual=True)
+    q, _ = make_queries(spec, mixture_centers(spec))
+    q = q.numpy()
+    index = lib.IvfIndex(ix, spec.nq, spec.nprobe, 64, host_only=True)
+    probe, _, _ = oracle.coarse(ix.metric, ix.centroids, q, spec.nprobe)
+    for k in (1, spec.k, 50):
+        ids, dist = index.search_batch_probes(q, probe, k)
+        ref_i, ref_d = oracle.scan(ix.metric, ix.codebooks, ix.list_offsets, ix.codes, ix.ids,
+                                   q, probe, k + 16, residual_centroids=ix.centroids)
+        amb = compare_topk(ids, dist, ref_i, ref_d, k, scale_S(ix.metric, q))
+        assert amb <= max(1, q.shape[0] // 20)
+    index.close()
+
+
 def test_host_only_identical_codes_tie_by_id(lib, oracle):
     rng = np.random.default_rng(3)
 
@@ -135,7 +153,7 @@ def test_desc_validation_and_arena_size(lib):
 
     def desc(**kw):
         base = dict(d=768, nlist=16384, M=96, nbits=8, metric=1, max_nq=1024, max_nprobe=64,
-                    max_k=10, centroids=0, codebooks=0, list_offsets=0, codes=0, ids=0)
+                    max_k=10, by_residual=0, centroids=0, codebooks=0, list_offsets=0, codes=0, ids=0)
         base.update(kw)
         return IvfIndexDesc(**base)
     ok = desc()
