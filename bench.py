@@ -17,6 +17,9 @@ queries.
 
 Other modes (each prints one JSON line of its own):
   --mode sweep   nq in {256, 1024, 4096} x resident fraction in {0.1, 0.3, 0.5, 1.0}
+  --mode partition  profile the access skew and the CPU tier, pick the partitioning point
+                 rho with the latency-bounded model (Eq. 1, Eq. 2, Algorithm 1; synthetic LLM
+                 inputs), load it and compare predicted with measured batch latency
   --mode drift   20 epochs x 10 000 queries, Zipf permutation re-drawn every 5
                  epochs, hot set recomputed from ivf_hit_stats after every epoch
                  and migrated with ivf_migrate_clusters while searches continue
@@ -109,7 +112,8 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=50)
-    ap.add_argument("--mode", default="hotpath", choices=["hotpath", "sweep", "drift"])
+    ap.add_argument("--mode", default="hotpath",
+                    choices=["hotpath", "sweep", "drift", "partition"])
     ap.add_argument("--workload", default="C3", help="spec name in synthdata.SPECS")
     ap.add_argument("--nq", type=int, default=None)
     ap.add_argument("--slices", type=int, default=0, help="scan blocks per query (0 = auto)")
@@ -126,6 +130,8 @@ def main():
                          "kernels (counter calibration / read ceiling)")
     ap.add_argument("--no-timing", action="store_true",
                     help="do not record per-kernel HIP events in the timed region")
+    ap.add_argument("--slo-ms", type=float, default=60.0,
+                    help="partition mode: search latency target SLO_search in ms")
     ap.add_argument("--epochs", type=int, default=20, help="drift mode: epochs")
     ap.add_argument("--epoch-queries", type=int, default=10000, help="drift mode: queries/epoch")
     args = ap.parse_args()
@@ -191,6 +197,92 @@ def main():
         index.close()
         print(json.dumps({"mode": "sweep", "workload": workload, "unit": "queries/s",
                           "rows": rows}), flush=True)
+        return
+
+    if args.mode == "partition":
+        from paper_2504_08930_amd import binding as B
+        nlist = ix.nlist
+        lens = np.diff(ix.list_offsets).astype(np.float64)
+        # --- access profile from calibration queries (Section 4.2.1) ---
+        index.hit_stats(reset=True)
+        probes = []
+        for s0 in range(0, calib.shape[0], index.max_nq):
+            cq = calib[s0:s0 + index.max_nq].contiguous()
+            index.search_batch_dev(cq, spec.nprobe, 1)
+            probes.append(index.coarse_probe_dev(cq, spec.nprobe).cpu().numpy())
+        torch.cuda.synchronize()
+        probes = np.concatenate(probes)
+        hits = index.hit_stats(reset=True)["per_cluster_hits"].astype(np.int64)
+        order = np.lexsort((np.arange(nlist), -hits))                 # hottest first
+        hit_cdf = np.concatenate([[0.0], np.cumsum(hits[order]) / hits.sum()])
+        hit_cdf[-1] = 1.0
+        per_vec = ix.m + 8 + (4 if (ix.by_residual and ix.metric == 0) else 0)
+        mem_index = np.concatenate([[0.0], np.cumsum(lens[order] * per_vec)])
+        # sigma_max^2: variance of the per-query hit rate at the coverage where the mean is 0.5
+        i_half = int(np.searchsorted(hit_cdf, 0.5))
+        hot_mask = np.zeros(nlist, bool)
+        hot_mask[order[:i_half]] = True
+        per_q = hot_mask[probes].mean(1)
+        sigma_max2 = float(per_q.var())
+        # --- CPU-tier latency model: knots measured with nothing resident ---
+        index.load_partition(np.zeros(0, np.int32))
+        knots_b, t_cq, t_lut = [], [], []
+        for b in (64, 256, 1024):
+            qb, _ = make_queries(spec, centers, nq=b, seed=spec.seed_calib + 17)
+            qh = qb.cpu().numpy()
+            index.search_batch(qh, spec.nprobe, spec.k)
+            index.set_tuning(scan_slices=0, timing=True)
+            index.stage_times(reset=True)
+            t0 = time.perf_counter()
+            reps = 3
+            for _ in range(reps):
+                index.search_batch(qh, spec.nprobe, spec.k)
+            total = (time.perf_counter() - t0) / reps
+            st = index.stage_times(reset=True)
+            index.set_tuning(scan_slices=0, timing=False)
+            cq_s = sum(st["ms"][x] for x in ("coarse_gemm", "coarse_select", "route")) / reps * 1e-3
+            knots_b.append(float(b))
+            t_cq.append(cq_s)
+            t_lut.append(max(total - cq_s, 1e-6))
+        model = B.LatencyModel(knots_b, t_cq, t_lut)
+        # --- Algorithm 1 with synthetic LLM-side inputs ---
+        slo = args.slo_ms * 1e-3
+        eps = 1.0
+        tau_s = slo / (1 + eps)
+        mu0 = 1024.0 / tau_s                     # bare LLM throughput that fills batches of 1024
+        kv = 8.0 * mem_index[-1]                 # KV-cache bytes with no index loaded
+        rho = B.ivf_model_partition_point(model, hit_cdf, mem_index, sigma_max2, slo, eps, kv, mu0,
+                                          1.0 / 512)
+        n_hot = int(round(rho * nlist))
+        mu = (kv - mem_index[n_hot]) / kv * mu0
+        batch = max(1, int(np.floor(tau_s * mu)))
+        eta_pred = B.ivf_model_min_hit_rate(float(hit_cdf[n_hot]), sigma_max2, batch)
+        lat_pred = B.ivf_model_hybrid_latency(model, batch, eta_pred)
+        index.load_partition(np.sort(order[:n_hot]).astype(np.int32))
+        lat, min_rates = [], []
+        for rep in range(8):
+            qb, _ = make_queries(spec, centers, nq=min(batch, index.max_nq),
+                                 seed=spec.seed_queries + 50 + rep)
+            qh = qb.cpu().numpy()
+            index.hit_stats(reset=True)
+            t0 = time.perf_counter()
+            index.search_batch(qh, spec.nprobe, spec.k)
+            lat.append(time.perf_counter() - t0)
+            min_rates.append(index.hit_stats(reset=True)["min_hit_rate"])
+        index.close()
+        print(json.dumps({
+            "mode": "partition", "workload": workload, "slo_search_ms": args.slo_ms, "eps": eps,
+            "tau_s_ms": round(tau_s * 1e3, 3), "sigma_max2": round(sigma_max2, 5),
+            "latency_model_knots": {"batch": knots_b, "t_cq_ms": [round(x * 1e3, 3) for x in t_cq],
+                                    "t_lut_ms": [round(x * 1e3, 3) for x in t_lut]},
+            "synthetic_llm": {"mu_llm0_per_s": round(mu0, 1), "mem_kvcache_bytes": kv},
+            "rho": round(rho, 4), "resident_clusters": n_hot,
+            "resident_bytes": float(mem_index[n_hot]), "mean_hit_rate_profile": round(float(hit_cdf[n_hot]), 4),
+            "batch": batch, "predicted_min_hit_rate": round(eta_pred, 4),
+            "measured_min_hit_rate_mean": round(float(np.mean(min_rates)), 4),
+            "predicted_latency_ms": round(lat_pred * 1e3, 3),
+            "measured_latency_ms_mean": round(float(np.mean(lat)) * 1e3, 3),
+            "measured_latency_ms_max": round(float(np.max(lat)) * 1e3, 3)}), flush=True)
         return
 
     if args.mode == "drift":

@@ -240,6 +240,49 @@ int ivf_stage_times(ivf_index_t *index, double *ms, uint64_t *launches, uint64_t
                     int reset);
 
 /*
+ * ---- Partitioning point (Section 4.2): pure host functions ----
+ *
+ * ivf_latency_model_t: piecewise-linear CPU latency models of the two search
+ * stages as functions of the batch size (Section 4.2.1), given by n_knots >= 1
+ * profiled points with strictly increasing batch sizes; linear between knots
+ * and beyond the outer ones.  All pointers HOST.
+ */
+typedef struct {
+  int32_t n_knots;
+  const double *batch; /* [n_knots] */
+  const double *t_cq;  /* [n_knots] coarse-quantization latency */
+  const double *t_lut; /* [n_knots] table build + scan latency */
+} ivf_latency_model_t;
+
+/* Eq. (1): latency of the hybrid index at batch size `batch` when the smallest
+ * hit rate in the batch is eta.  NaN on a malformed model. */
+double ivf_model_hybrid_latency(const ivf_latency_model_t *model, double batch, double eta);
+
+/* Eq. (2): expected smallest per-query hit rate in a batch of `batch` queries,
+ * hit rates ~ Beta with the given mean and variance 4 sigma_max2 mean (1 - mean)
+ * (Section 4.2.2).  0 < sigma_max2 < 0.25, else NaN. */
+double ivf_model_min_hit_rate(double mean_hit_rate, double sigma_max2, int32_t batch);
+
+/* Inverse of Eq. (2) over a measured profile ("HitRate2Coverage"): the smallest
+ * fraction of clusters (hottest first, whole clusters) whose expected smallest
+ * hit rate in a batch reaches eta_min.  hit_cdf: HOST double [nlist+1],
+ * hit_cdf[i] = share of all probes that fall into the i hottest clusters. */
+double ivf_model_hitrate_to_coverage(const double *hit_cdf, int32_t nlist, double sigma_max2,
+                                     int32_t batch, double eta_min);
+
+/* Algorithm 1 (latency-bounded partitioning): binary search for the coverage rho
+ * at which the coverage needed to hold tau_s = slo_search / (1 + eps), at the
+ * batch size the remaining LLM throughput implies, equals the coverage spent.
+ * mem_index: HOST double [nlist+1], bytes of the i hottest clusters; mem_kvcache:
+ * KV-cache bytes with no index loaded; mu_llm0: LLM throughput then (requests per
+ * unit of the latency model's time); delta: width at which the search stops.
+ * Writes rho to *rho_out.  IVF_EINVAL on bad arguments. */
+int ivf_model_partition_point(const ivf_latency_model_t *model, const double *hit_cdf,
+                              const double *mem_index, int32_t nlist, double sigma_max2,
+                              double slo_search, double eps, double mem_kvcache, double mu_llm0,
+                              double delta, double *rho_out);
+
+/*
  * Instrumentation aid: a plain streaming copy kernel (reads `bytes`, writes
  * `bytes`; DEVICE pointers, 16-byte aligned, bytes a multiple of 16) whose
  * known traffic calibrates hardware byte counters.  Asynchronous on `stream`.

@@ -23,6 +23,8 @@ EXPORTS = (
     "ivf_coarse_probe_dev", "ivf_search_batch_probes", "ivf_hit_stats",
     "ivf_migrate_clusters", "ivf_migrate_poll", "ivf_migrate_stats", "ivf_resident_info",
     "ivf_set_tuning", "ivf_stage_times", "ivf_calib_copy", "ivf_calib_read", "ivf_last_error",
+    "ivf_model_hybrid_latency", "ivf_model_min_hit_rate", "ivf_model_hitrate_to_coverage",
+    "ivf_model_partition_point",
 )
 
 
@@ -41,6 +43,11 @@ class IvfIndexDesc(ctypes.Structure):
         ("centroids", ctypes.c_void_p), ("codebooks", ctypes.c_void_p),
         ("list_offsets", ctypes.c_void_p), ("codes", ctypes.c_void_p), ("ids", ctypes.c_void_p),
     ]
+
+
+class IvfLatencyModel(ctypes.Structure):
+    _fields_ = [("n_knots", ctypes.c_int32), ("batch", ctypes.c_void_p),
+                ("t_cq", ctypes.c_void_p), ("t_lut", ctypes.c_void_p)]
 
 
 _lib = None
@@ -78,8 +85,18 @@ def load_library():
     lib.ivf_calib_read.argtypes = [P, P, SZ, P]
     lib.ivf_last_error.argtypes = []
     lib.ivf_last_error.restype = ctypes.c_char_p
+    D = ctypes.c_double
+    MP = ctypes.POINTER(IvfLatencyModel)
+    lib.ivf_model_hybrid_latency.argtypes = [MP, D, D]
+    lib.ivf_model_min_hit_rate.argtypes = [D, D, I32]
+    lib.ivf_model_hitrate_to_coverage.argtypes = [P, I32, D, I32, D]
+    lib.ivf_model_partition_point.argtypes = [MP, P, P, I32, D, D, D, D, D, D, P]
+    doubles = ("ivf_model_hybrid_latency", "ivf_model_min_hit_rate",
+               "ivf_model_hitrate_to_coverage")
+    for name in doubles:
+        getattr(lib, name).restype = D
     for name in EXPORTS:
-        if name not in ("ivf_index_arena_bytes", "ivf_index_destroy", "ivf_last_error"):
+        if name not in ("ivf_index_arena_bytes", "ivf_index_destroy", "ivf_last_error") + doubles:
             getattr(lib, name).restype = ctypes.c_int
     _lib = lib
     return lib
@@ -284,3 +301,43 @@ class IvfIndex:
                                          int(bool(reset))))
         return {"ms": dict(zip(STAGE_NAMES, ms.tolist())),
                 "launches": dict(zip(STAGE_NAMES, n.tolist())), "scan_bytes": sb.value}
+
+
+class LatencyModel:
+    """Piecewise-linear CPU latency models (knots: batch size -> seconds)."""
+
+    def __init__(self, batch, t_cq, t_lut):
+        self._b = np.ascontiguousarray(batch, np.float64)
+        self._cq = np.ascontiguousarray(t_cq, np.float64)
+        self._lut = np.ascontiguousarray(t_lut, np.float64)
+        assert self._b.shape == self._cq.shape == self._lut.shape and self._b.ndim == 1
+        self.c = IvfLatencyModel(len(self._b), self._b.ctypes.data, self._cq.ctypes.data,
+                                 self._lut.ctypes.data)
+
+
+def ivf_model_hybrid_latency(model, batch, eta):
+    return load_library().ivf_model_hybrid_latency(ctypes.byref(model.c), float(batch), float(eta))
+
+
+def ivf_model_min_hit_rate(mean_hit_rate, sigma_max2, batch):
+    return load_library().ivf_model_min_hit_rate(float(mean_hit_rate), float(sigma_max2), int(batch))
+
+
+def ivf_model_hitrate_to_coverage(hit_cdf, sigma_max2, batch, eta_min):
+    cdf = np.ascontiguousarray(hit_cdf, np.float64)
+    return load_library().ivf_model_hitrate_to_coverage(_np_ptr(cdf), len(cdf) - 1,
+                                                        float(sigma_max2), int(batch),
+                                                        float(eta_min))
+
+
+def ivf_model_partition_point(model, hit_cdf, mem_index, sigma_max2, slo_search, eps, mem_kvcache,
+                              mu_llm0, delta):
+    cdf = np.ascontiguousarray(hit_cdf, np.float64)
+    mem = np.ascontiguousarray(mem_index, np.float64)
+    assert cdf.shape == mem.shape
+    rho = ctypes.c_double(0.0)
+    _check(load_library().ivf_model_partition_point(
+        ctypes.byref(model.c), _np_ptr(cdf), _np_ptr(mem), len(cdf) - 1, float(sigma_max2),
+        float(slo_search), float(eps), float(mem_kvcache), float(mu_llm0), float(delta),
+        ctypes.byref(rho)))
+    return rho.value

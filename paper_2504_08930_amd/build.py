@@ -5,7 +5,8 @@ import subprocess
 _HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(_HERE, "csrc")
 LIB_PATH = os.path.join(_HERE, "libivfpq_hot.so")
-SOURCES = ["api.cpp", "host_scan.cpp", "kernels_scan.hip", "kernels_coarse.hip"]
+SOURCES = ["api.cpp", "host_scan.cpp", "partition_model.cpp", "kernels_scan.hip",
+           "kernels_coarse.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "-O3", "-std=c++17", "--offload-arch=gfx950",
