@@ -20,6 +20,9 @@ Other modes (each prints one JSON line of its own):
   --mode partition  profile the access skew and the CPU tier, pick the partitioning point
                  rho with the latency-bounded model (Eq. 1, Eq. 2, Algorithm 1; synthetic LLM
                  inputs), load it and compare predicted with measured batch latency
+  --mode dispatch  dynamic dispatcher on/off (Section 4.3.2): hybrid batches from host memory at
+                 several resident fractions; batch latency and mean / p90 per-query hand-off
+                 latency of ivf_search_batch_async against the bulk ivf_search_batch
   --mode drift   20 epochs x 10 000 queries, Zipf permutation re-drawn every 5
                  epochs, hot set recomputed from ivf_hit_stats after every epoch
                  and migrated with ivf_migrate_clusters while searches continue
@@ -113,7 +116,7 @@ def main():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--mode", default="hotpath",
-                    choices=["hotpath", "sweep", "drift", "partition"])
+                    choices=["hotpath", "sweep", "drift", "partition", "dispatch"])
     ap.add_argument("--workload", default="C3", help="spec name in synthdata.SPECS")
     ap.add_argument("--nq", type=int, default=None)
     ap.add_argument("--slices", type=int, default=0, help="scan blocks per query (0 = auto)")
@@ -196,6 +199,50 @@ def main():
                 rows.append(row)
         index.close()
         print(json.dumps({"mode": "sweep", "workload": workload, "unit": "queries/s",
+                          "rows": rows}), flush=True)
+        return
+
+    if args.mode == "dispatch":
+        rows = []
+        reps = 5
+        for frac in (0.9, 0.5, 0.3):
+            index.load_partition(all_clusters)
+            index.load_partition(hottest_clusters(index, calib, spec.nprobe, frac, ix.nlist))
+            for n in (256, 1024):
+                off_ms, on_ms, on_mean, on_p90, min_rate = [], [], [], [], []
+                for rep in range(reps + 1):
+                    qh = make_queries(spec, centers, nq=n,
+                                      seed=spec.seed_queries + 100 + rep)[0].cpu().numpy()
+                    index.hit_stats(reset=True)
+                    t0 = time.perf_counter()
+                    ref_i, ref_d = index.search_batch(qh, spec.nprobe, spec.k)
+                    t_off = (time.perf_counter() - t0) * 1e3
+                    mr = index.hit_stats(reset=True)["min_hit_rate"]
+                    t0 = time.perf_counter()
+                    ids, dists, done_ms = index.search_batch_async(qh, spec.nprobe, spec.k).wait()
+                    t_on = (time.perf_counter() - t0) * 1e3
+                    assert np.array_equal(ids, ref_i) and np.array_equal(dists, ref_d)
+                    if rep == 0:
+                        continue                      # warm-up pair
+                    off_ms.append(t_off)
+                    on_ms.append(t_on)
+                    on_mean.append(float(done_ms.mean()))
+                    on_p90.append(float(np.percentile(done_ms, 90)))
+                    min_rate.append(mr)
+                row = {"resident_fraction": frac, "nq": n,
+                       "min_hit_rate": round(float(np.mean(min_rate)), 4),
+                       "bulk_batch_ms": round(float(np.mean(off_ms)), 3),
+                       "dispatcher_batch_ms": round(float(np.mean(on_ms)), 3),
+                       "dispatcher_mean_query_ms": round(float(np.mean(on_mean)), 3),
+                       "dispatcher_p90_query_ms": round(float(np.mean(on_p90)), 3)}
+                row["mean_latency_change"] = round(row["dispatcher_mean_query_ms"] /
+                                                   row["bulk_batch_ms"] - 1.0, 4)
+                log(json.dumps(row))
+                rows.append(row)
+        index.close()
+        print(json.dumps({"mode": "dispatch", "workload": workload, "reps": reps,
+                          "note": "bulk: every query of a batch is available at bulk_batch_ms; "
+                                  "dispatcher: query i at done_ms[i]; identical results asserted",
                           "rows": rows}), flush=True)
         return
 

@@ -165,6 +165,51 @@ int ivf_search_batch_probes(ivf_index_t *index, const float *queries, int64_t nq
                             float *out_dists);
 
 /*
+ * Dynamic dispatcher (Section 4.3.2 "Dynamic Dispatcher"): the same search as
+ * ivf_search_batch() (probe == NULL) or ivf_search_batch_probes() (probe given),
+ * but every query is merged, re-ranked and handed on as soon as its own probes
+ * are done instead of when the whole batch is.  The call enqueues the device
+ * side, starts a dispatcher thread and returns.  The CPU search loop takes the
+ * queries' cold clusters one by one and keeps a scan count per query; when it
+ * equals the number of cold probes routed to the CPU, the query enters a
+ * thread-safe completed queue.  Once the device has signalled completion of
+ * the resident probes, the dispatcher takes queries off that queue, merges the
+ * CPU and GPU partial results, writes row q of out_ids / out_dists and calls
+ * on_done(user, q, row of ids, row of dists, k) on the dispatcher thread
+ * (on_done may be NULL).  Results are bit-identical to the synchronous calls.
+ *
+ * queries, probe (optional), out_ids, out_dists: HOST; queries and the outputs
+ * must stay valid until ivf_search_wait() returns.  A device-less index needs
+ * a probe list.  One asynchronous batch per index at a time: until
+ * ivf_search_wait() has returned, other searches on the index return
+ * IVF_EBUSY.  on_done must not call into this index.
+ */
+typedef struct ivf_ticket ivf_ticket_t; /* opaque */
+typedef void (*ivf_query_done_fn)(void *user, int64_t query, const int64_t *ids,
+                                  const float *dists, int32_t k);
+int ivf_search_batch_async(ivf_index_t *index, const float *queries, int64_t nq,
+                           const int32_t *probe, int32_t nprobe, int32_t k, int64_t *out_ids,
+                           float *out_dists, ivf_query_done_fn on_done, void *user,
+                           ivf_ticket_t **ticket);
+
+/*
+ * Take up to cap finished queries off the ticket, in the order they were
+ * handed on (each is reported once).  queries_done: HOST [cap].  *finished is
+ * set to 1 once every query of the batch has been reported through this call.
+ * Returns the batch's error, if it has failed.
+ */
+int ivf_search_poll(ivf_ticket_t *ticket, int64_t *queries_done, int64_t cap, int64_t *n_done,
+                    int32_t *finished);
+
+/*
+ * Wait for the batch, release the ticket (it is invalid afterwards, also on
+ * error) and return the batch's status.  done_ms: HOST double [nq] or NULL, the
+ * time in milliseconds from the ivf_search_batch_async() call to each query's
+ * hand-off.
+ */
+int ivf_search_wait(ivf_ticket_t *ticket, double *done_ms);
+
+/*
  * Router counters (Section 4.3.3; per-query hit rate as defined in Section
  * 3.3: resident probes / probes).  per_cluster_hits: HOST uint64 [nlist] or
  * NULL, number of times each cluster was probed since the last reset.

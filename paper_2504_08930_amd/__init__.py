@@ -37,6 +37,18 @@ def ivf_search_batch_probes(index, queries, probe, k):
     return index.search_batch_probes(queries, probe, k)
 
 
+def ivf_search_batch_async(index, queries, nprobe, k, probe=None, on_done=None):
+    return index.search_batch_async(queries, nprobe, k, probe, on_done)
+
+
+def ivf_search_poll(ticket, cap=None):
+    return ticket.poll(cap)
+
+
+def ivf_search_wait(ticket):
+    return ticket.wait()
+
+
 def ivf_hit_stats(index, reset=False):
     return index.hit_stats(reset)
 

@@ -25,7 +25,11 @@ EXPORTS = (
     "ivf_set_tuning", "ivf_stage_times", "ivf_calib_copy", "ivf_calib_read", "ivf_last_error",
     "ivf_model_hybrid_latency", "ivf_model_min_hit_rate", "ivf_model_hitrate_to_coverage",
     "ivf_model_partition_point",
+    "ivf_search_batch_async", "ivf_search_poll", "ivf_search_wait",
 )
+
+QUERY_DONE_FN = ctypes.CFUNCTYPE(None, ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p,
+                                 ctypes.c_void_p, ctypes.c_int32)
 
 
 class IvfError(RuntimeError):
@@ -74,6 +78,10 @@ def load_library():
     lib.ivf_search_batch_dev.argtypes = [P, P, I64, I32, I32, P, P, P]
     lib.ivf_coarse_probe_dev.argtypes = [P, P, I64, I32, P, P]
     lib.ivf_search_batch_probes.argtypes = [P, P, I64, P, I32, I32, P, P]
+    lib.ivf_search_batch_async.argtypes = [P, P, I64, P, I32, I32, P, P, QUERY_DONE_FN, P,
+                                           ctypes.POINTER(P)]
+    lib.ivf_search_poll.argtypes = [P, P, I64, P, P]
+    lib.ivf_search_wait.argtypes = [P, P]
     lib.ivf_hit_stats.argtypes = [P, P, P, P, P, ctypes.c_int]
     lib.ivf_migrate_clusters.argtypes = [P, P, I32, P, I32, P]
     lib.ivf_migrate_poll.argtypes = [P, ctypes.c_int, P]
@@ -280,6 +288,11 @@ class IvfIndex:
                                                  _np_ptr(ids), _np_ptr(dists)))
         return ids, dists
 
+    def search_batch_async(self, queries, nprobe, k, probe=None, on_done=None):
+        """Start a batch under the dynamic dispatcher; returns an AsyncSearch ticket.
+        on_done(query, ids_row, dists_row), if given, runs on the dispatcher thread."""
+        return AsyncSearch(self, queries, nprobe, k, probe, on_done)
+
     # ---- counters / instrumentation ----
     def hit_stats(self, reset=False):
         hits = np.zeros(self.nlist, np.uint64)
@@ -301,6 +314,59 @@ class IvfIndex:
                                          int(bool(reset))))
         return {"ms": dict(zip(STAGE_NAMES, ms.tolist())),
                 "launches": dict(zip(STAGE_NAMES, n.tolist())), "scan_bytes": sb.value}
+
+
+class AsyncSearch:
+    """Ticket of ivf_search_batch_async: poll() for finished queries, wait() for all."""
+
+    def __init__(self, index, queries, nprobe, k, probe, on_done):
+        self._lib = index._lib
+        self.queries = np.ascontiguousarray(queries, dtype=np.float32)
+        nq = self.queries.shape[0]
+        self.probe = None
+        if probe is not None:
+            self.probe = _i32(probe)
+            nprobe = self.probe.shape[1]
+        self.nq, self.k = nq, int(k)
+        self.ids = np.full((nq, k), -2, np.int64)
+        self.dists = np.full((nq, k), np.nan, np.float32)
+        if on_done is not None:
+            ids, dists = self.ids, self.dists
+
+            def tramp(_user, q, _ids, _dists, _k):
+                on_done(int(q), ids[q], dists[q])
+            self._cb = QUERY_DONE_FN(tramp)
+        else:
+            self._cb = ctypes.cast(None, QUERY_DONE_FN)
+        h = ctypes.c_void_p()
+        _check(self._lib.ivf_search_batch_async(
+            index._h, _np_ptr(self.queries), nq,
+            _np_ptr(self.probe) if self.probe is not None else None, int(nprobe), int(k),
+            _np_ptr(self.ids), _np_ptr(self.dists), self._cb, None, ctypes.byref(h)))
+        self._t = h
+
+    def poll(self, cap=None):
+        """Queries handed on since the last poll (each once), and whether the batch is over."""
+        cap = self.nq if cap is None else int(cap)
+        buf = np.empty(max(cap, 1), np.int64)
+        n, fin = ctypes.c_int64(0), ctypes.c_int32(0)
+        _check(self._lib.ivf_search_poll(self._t, _np_ptr(buf), cap, ctypes.byref(n),
+                                         ctypes.byref(fin)))
+        return buf[:n.value].copy(), bool(fin.value)
+
+    def wait(self):
+        """Blocks until the batch is done; returns (ids, dists, done_ms per query)."""
+        done_ms = np.zeros(max(self.nq, 1), np.float64)
+        t, self._t = self._t, None
+        if t is None:
+            raise IvfError(IVF_ESTATE, "ticket already waited on")
+        _check(self._lib.ivf_search_wait(t, _np_ptr(done_ms)))
+        return self.ids, self.dists, done_ms[:self.nq]
+
+    def __del__(self):
+        if getattr(self, "_t", None) is not None:
+            self._lib.ivf_search_wait(self._t, None)
+            self._t = None
 
 
 class LatencyModel:

@@ -8,10 +8,14 @@
 #include <string.h>
 
 #include <algorithm>
+#include <atomic>
+#include <chrono>
+#include <condition_variable>
 #include <deque>
 #include <map>
 #include <mutex>
 #include <string>
+#include <thread>
 #include <vector>
 
 #include "host_scan.h"
@@ -133,6 +137,8 @@ struct ivf_index {
   Shape sh;
   int64_t n_total = 0;
   bool has_dev = false;
+  int device = 0;               // HIP device the arena lives on
+  bool dispatch_active = false; // an asynchronous batch owns the pinned host buffers
   DevLayout L;
   hipStream_t own_stream = nullptr;
   std::mutex mu;
@@ -386,6 +392,7 @@ extern "C" int ivf_index_create(const ivf_index_desc_t *desc, void *dev_arena, s
   plan_layout(*desc, tiles * kTileVecs, staging_bytes, (unsigned char *)dev_arena, &ix->L);
   ix->alloc.reset(ix->L.cap_tiles);
   ix->has_dev = true;
+  (void)hipGetDevice(&ix->device);
 
   auto bail = [&](hipError_t e, const char *what) {
     std::string msg = std::string(what) + ": " + hipGetErrorString(e);
@@ -1011,175 +1018,245 @@ struct SearchArgs {
   hipStream_t st = nullptr;
 };
 
-static int search_device(ivf_index *ix, const SearchArgs &a) {
+// One batch's hold on a workspace slot and on a mapping-table version.
+struct BatchCtx {
+  int slot = 0;
+  int buf = 0;
+  bool all_resident = false, any_resident = false, timing = false;
+  uint64_t ver_id = 0;
+};
+
+static int begin_batch(ivf_index *ix, hipStream_t st, BatchCtx *c) {
+  std::lock_guard<std::mutex> lk(ix->mu);
+  int rc = acquire_slot_locked(ix, st, &c->slot);
+  if (rc < 0) return rc;
+  rc = publish_if_done_locked(ix, false);
+  if (rc < 0) return rc;
+  reclaim(ix);
+  Version &ver = ix->versions.back();
+  ver.refs += 1;
+  c->ver_id = ver.id;
+  c->buf = ver.buf;
+  c->all_resident = ix->resident_clusters == ix->sh.nlist;
+  c->any_resident = ix->resident_clusters > 0;
+  c->timing = ix->timing != 0;
+  return IVF_OK;
+}
+
+// Drop the hold on the mapping-table version.  async_tail: device work that
+// reads the table may still be queued on st, so leave an event behind.
+static void end_batch(ivf_index *ix, const BatchCtx &c, hipStream_t st, bool async_tail) {
+  std::lock_guard<std::mutex> lk(ix->mu);
+  for (auto &v : ix->versions) {
+    if (v.id != c.ver_id) continue;
+    if (async_tail) {
+      hipEvent_t e = get_event(ix);
+      if (e && hipEventRecord(e, st) == hipSuccess) v.events.push_back(e);
+      else (void)hipStreamSynchronize(st);
+    }
+    v.refs -= 1;
+    break;
+  }
+}
+
+// Enqueue the device side of one batch on a.st: coarse quantizer (or the
+// caller's probes), routing, lookup tables, scan of the resident probes and
+// merge of the slices.  final_on_gpu: every probe is resident and the merge
+// writes ids and distances; otherwise the per-query partial results, the cold
+// probe lists and the scale inputs are copied to the index's pinned buffers.
+// ev_route (optional) is recorded once the cold lists are on their way, so a
+// host thread can start on them while the device scans.
+static int enqueue_gpu(ivf_index *ix, const SearchArgs &a, const BatchCtx &c, bool final_on_gpu,
+                       hipEvent_t ev_route) {
   const DevLayout &L = ix->L;
   const Shape &sh = ix->sh;
-  const int nq = (int)a.nq, k = a.k;
-  const int np = a.nprobe;
+  const int nq = (int)a.nq, k = a.k, np = a.nprobe;
   hipStream_t st = a.st;
-
-  // ---- workspace slot; pin the mapping-table version ----
-  int slot = 0;
-  int buf;
-  bool all_resident, any_resident;
-  Version *ver;
-  bool timing;
-  {
-    std::lock_guard<std::mutex> lk(ix->mu);
-    int rc = acquire_slot_locked(ix, st, &slot);
-    if (rc < 0) return rc;
-    rc = publish_if_done_locked(ix, false);
-    if (rc < 0) return rc;
-    reclaim(ix);
-    ver = &ix->versions.back();
-    ver->refs += 1;
-    buf = ver->buf;
-    all_resident = ix->resident_clusters == sh.nlist;
-    any_resident = ix->resident_clusters > 0;
-    timing = ix->timing != 0;
-  }
-  const BatchWs &W = L.ws[slot];
-  const uint64_t ver_id = ver->id;
-  auto release = [&](bool async_tail) {
-    std::lock_guard<std::mutex> lk(ix->mu);
-    for (auto &v : ix->versions) {
-      if (v.id != ver_id) continue;
-      if (async_tail) {
-        hipEvent_t e = get_event(ix);
-        if (e && hipEventRecord(e, st) == hipSuccess) v.events.push_back(e);
-        else (void)hipStreamSynchronize(st);
-      }
-      v.refs -= 1;
-      break;
-    }
-  };
-#define S_TRY(expr)                                                                        \
-  do {                                                                                     \
-    hipError_t _e = (expr);                                                                \
-    if (_e != hipSuccess) {                                                                \
-      (void)hipStreamSynchronize(st);                                                      \
-      release(false);                                                                      \
-      return fail(IVF_EDEVICE, "%s failed: %s (%s:%d)", #expr, hipGetErrorString(_e),      \
-                  __FILE__, __LINE__);                                                     \
-    }                                                                                      \
-  } while (0)
+  const BatchWs &W = L.ws[c.slot];
 
   TimingRec trec;
   memset(&trec, 0, sizeof(trec));
   auto mark = [&](int i) -> hipError_t {
-    if (!timing) return hipSuccess;
+    if (!c.timing) return hipSuccess;
     hipError_t e = hipEventCreate(&trec.ev[i]);
     if (e != hipSuccess) return e;
     trec.valid[i] = true;
     return hipEventRecord(trec.ev[i], st);
   };
+  auto keep_timing = [&]() {
+    if (!c.timing) return;
+    std::lock_guard<std::mutex> lk(ix->mu);
+    ix->trecs.push_back(trec);
+  };
+#define G_TRY(expr)                                                                        \
+  do {                                                                                     \
+    hipError_t _e = (expr);                                                                \
+    if (_e != hipSuccess) {                                                                \
+      keep_timing();                                                                       \
+      return fail(IVF_EDEVICE, "%s failed: %s (%s:%d)", #expr, hipGetErrorString(_e),      \
+                  __FILE__, __LINE__);                                                     \
+    }                                                                                      \
+  } while (0)
 
   const float *dq = a.q_dev;
   if (!dq) {
-    S_TRY(hipMemcpyAsync(W.queries, a.q_host, (size_t)nq * sh.d * 4, hipMemcpyHostToDevice, st));
+    G_TRY(hipMemcpyAsync(W.queries, a.q_host, (size_t)nq * sh.d * 4, hipMemcpyHostToDevice, st));
     dq = W.queries;
   }
   // ---- stage 1: coarse quantizer (or the caller's probe list) ----
   if (a.probe_host) {
     memcpy(ix->h_probe, a.probe_host, (size_t)nq * np * 4);
-    S_TRY(hipMemcpyAsync(W.probe, ix->h_probe, (size_t)nq * np * 4, hipMemcpyHostToDevice, st));
+    G_TRY(hipMemcpyAsync(W.probe, ix->h_probe, (size_t)nq * np * 4, hipMemcpyHostToDevice, st));
   } else {
-    S_TRY(mark(IVF_STAGE_COARSE_GEMM));
-    S_TRY(launch_split_bf16(dq, (size_t)nq, sh.d, W.q_parts, st));
-    S_TRY(launch_coarse_gemm(sh, W.q_parts, nq, L.cent_parts, L.cent_norm, W.scores, st));
-    S_TRY(mark(IVF_STAGE_COARSE_SELECT));
-    S_TRY(launch_coarse_select(sh, W.scores, nq, np, np, W.probe, st));
+    G_TRY(mark(IVF_STAGE_COARSE_GEMM));
+    G_TRY(launch_split_bf16(dq, (size_t)nq, sh.d, W.q_parts, st));
+    G_TRY(launch_coarse_gemm(sh, W.q_parts, nq, L.cent_parts, L.cent_norm, W.scores, st));
+    G_TRY(mark(IVF_STAGE_COARSE_SELECT));
+    G_TRY(launch_coarse_select(sh, W.scores, nq, np, np, W.probe, st));
   }
   // ---- routing ----
-  S_TRY(mark(IVF_STAGE_ROUTE));
+  G_TRY(mark(IVF_STAGE_ROUTE));
   if (sh.by_residual)
-    S_TRY(launch_bias(sh, dq, nq, W.probe, np, np, L.centroids, W.bias, st));
-  S_TRY(launch_route(W.probe, nq, np, np, L.clus_tile[buf], L.clus_len, sh.M, W.g_base, W.g_len,
+    G_TRY(launch_bias(sh, dq, nq, W.probe, np, np, L.centroids, W.bias, st));
+  G_TRY(launch_route(W.probe, nq, np, np, L.clus_tile[c.buf], L.clus_len, sh.M, W.g_base, W.g_len,
                      W.g_prefix, W.g_n, W.cold, W.n_cold, W.q_vecs,
                      sh.by_residual ? W.bias : nullptr, W.g_bias, W.qbmax, L.hits, L.qstats, 1,
                      st));
-  S_TRY(mark(IVF_STAGE_LUT));
-  const int slices = pick_slices(ix, nq);
-  const bool final_on_gpu = all_resident;
-  if (any_resident) {
+  if (!final_on_gpu) {
+    // cold probes go to the CPU (Section 4.3.1)
+    G_TRY(hipMemcpyAsync(ix->h_ncold, W.n_cold, (size_t)nq * 4, hipMemcpyDeviceToHost, st));
+    G_TRY(hipMemcpyAsync(ix->h_cold, W.cold, (size_t)nq * np * 4, hipMemcpyDeviceToHost, st));
+    G_TRY(hipMemcpyAsync(ix->h_qbmax, W.qbmax, (size_t)nq * 4, hipMemcpyDeviceToHost, st));
+    if (!a.q_host)
+      G_TRY(hipMemcpyAsync(ix->h_queries, dq, (size_t)nq * sh.d * 4, hipMemcpyDeviceToHost, st));
+    if (ev_route) G_TRY(hipEventRecord(ev_route, st));
+  }
+  G_TRY(mark(IVF_STAGE_LUT));
+  if (c.any_resident) {
     // ---- stage 2: lookup tables; stage 3: scan + top-k ----
-    S_TRY(launch_order(W.probe, nq, np, W.order, st));
-    S_TRY(launch_lut(sh, dq, nq, L.cbT, W.lut, W.lutpart, W.lutmax, st));
-    S_TRY(mark(IVF_STAGE_SCAN));
-    S_TRY(launch_scan(sh, L, W, nq, np, slices, k, st));
-    S_TRY(mark(IVF_STAGE_MERGE));
+    const int slices = pick_slices(ix, nq);
+    G_TRY(launch_order(W.probe, nq, np, W.order, st));
+    G_TRY(launch_lut(sh, dq, nq, L.cbT, W.lut, W.lutpart, W.lutmax, st));
+    G_TRY(mark(IVF_STAGE_SCAN));
+    G_TRY(launch_scan(sh, L, W, nq, np, slices, k, st));
+    G_TRY(mark(IVF_STAGE_MERGE));
     int64_t *oid = nullptr;
     float *od = nullptr;
     if (final_on_gpu) {
       oid = a.out_device ? a.out_ids : W.out_ids;
       od = a.out_device ? a.out_dists : W.out_dists;
     }
-    S_TRY(launch_merge(sh, W, nq, slices, k, oid, od, st));
-    S_TRY(mark(IVF_N_STAGES));
+    G_TRY(launch_merge(sh, W, nq, slices, k, oid, od, st));
+    G_TRY(mark(IVF_N_STAGES));
+    if (!final_on_gpu) {
+      G_TRY(hipMemcpyAsync(ix->h_reskey, W.res_key, (size_t)nq * k * 4, hipMemcpyDeviceToHost, st));
+      G_TRY(hipMemcpyAsync(ix->h_resid, W.res_id, (size_t)nq * k * 8, hipMemcpyDeviceToHost, st));
+      G_TRY(hipMemcpyAsync(ix->h_lutmax, W.lutmax, (size_t)nq * 4, hipMemcpyDeviceToHost, st));
+    }
   }
-  if (timing) {
+  keep_timing();
+  return IVF_OK;
+#undef G_TRY
+}
+
+// Final result of query q of a hybrid batch: the device's partial top-k (if any
+// cluster is resident) merged with the CPU scan of its cold probes.  cpu_e is the
+// table exponent the CPU scan used (only read when cpu is non-NULL).  Returns
+// false if the CPU and the device disagree on the exponent.
+static bool finish_query(const ivf_index *ix, const HostIndexView &view, bool any_resident,
+                         int64_t q, int k, const HostCand *cpu, int cpu_e, int64_t *ids,
+                         float *dists) {
+  std::vector<HostCand> gpu((size_t)k), fin((size_t)k);
+  for (int r = 0; r < k; ++r) {
+    if (any_resident) gpu[r] = HostCand{ix->h_reskey[q * k + r], ix->h_resid[q * k + r]};
+    else gpu[r] = HostCand{kKeyInvalid, -1};
+  }
+  int e = 0;
+  if (any_resident) {
+    float mx;
+    memcpy(&mx, &ix->h_lutmax[q], 4);
+    e = lut_exponent(mx, view.M, ix->h_qbmax[q], view.pv ? view.pv_max : 0.0f);
+  }
+  const HostCand *res = gpu.data();
+  bool ok = true;
+  if (cpu) {
+    if (any_resident && cpu_e != e) ok = false;
+    e = cpu_e;
+    merge_topk(gpu.data(), cpu, k, fin.data());
+    res = fin.data();
+  }
+  emit_results(ix, res, k, e, ids, dists);
+  return ok;
+}
+
+static int search_device(ivf_index *ix, const SearchArgs &a) {
+  const int nq = (int)a.nq, k = a.k;
+  const int np = a.nprobe;
+  hipStream_t st = a.st;
+
+  {
     std::lock_guard<std::mutex> lk(ix->mu);
-    ix->trecs.push_back(trec);
+    if (ix->dispatch_active)
+      return fail(IVF_EBUSY, "an asynchronous batch is still in flight on this index");
   }
+  BatchCtx ctx;
+  int rc = begin_batch(ix, st, &ctx);
+  if (rc < 0) return rc;
+  const BatchWs &W = ix->L.ws[ctx.slot];
+  const bool final_on_gpu = ctx.all_resident;
+  const bool any_resident = ctx.any_resident;
+  rc = enqueue_gpu(ix, a, ctx, final_on_gpu, nullptr);
+  if (rc < 0) {
+    (void)hipStreamSynchronize(st);
+    end_batch(ix, ctx, st, false);
+    return rc;
+  }
+#define S_TRY(expr)                                                                        \
+  do {                                                                                     \
+    hipError_t _e = (expr);                                                                \
+    if (_e != hipSuccess) {                                                                \
+      (void)hipStreamSynchronize(st);                                                      \
+      end_batch(ix, ctx, st, false);                                                       \
+      return fail(IVF_EDEVICE, "%s failed: %s (%s:%d)", #expr, hipGetErrorString(_e),      \
+                  __FILE__, __LINE__);                                                     \
+    }                                                                                      \
+  } while (0)
 
   if (final_on_gpu) {
     if (a.out_device) {
-      release(true);  // asynchronous: outputs valid when the stream gets here
+      end_batch(ix, ctx, st, true);  // asynchronous: outputs valid when the stream gets here
       return IVF_OK;
     }
     S_TRY(hipMemcpyAsync(ix->h_outids, W.out_ids, (size_t)nq * k * 8, hipMemcpyDeviceToHost, st));
     S_TRY(hipMemcpyAsync(ix->h_outd, W.out_dists, (size_t)nq * k * 4, hipMemcpyDeviceToHost, st));
     S_TRY(hipStreamSynchronize(st));
-    release(false);
+    end_batch(ix, ctx, st, false);
     memcpy(a.out_ids, ix->h_outids, (size_t)nq * k * 8);
     memcpy(a.out_dists, ix->h_outd, (size_t)nq * k * 4);
     return IVF_OK;
   }
 
   // ---- hybrid: cold probes on the CPU, then merge (Sections 4.3.1, 4.3.2) ----
-  S_TRY(hipMemcpyAsync(ix->h_ncold, W.n_cold, (size_t)nq * 4, hipMemcpyDeviceToHost, st));
-  S_TRY(hipMemcpyAsync(ix->h_cold, W.cold, (size_t)nq * np * 4, hipMemcpyDeviceToHost, st));
-  S_TRY(hipMemcpyAsync(ix->h_qbmax, W.qbmax, (size_t)nq * 4, hipMemcpyDeviceToHost, st));
-  const float *hq = a.q_host;
-  if (!hq) {
-    S_TRY(hipMemcpyAsync(ix->h_queries, dq, (size_t)nq * sh.d * 4, hipMemcpyDeviceToHost, st));
-    hq = ix->h_queries;
-  }
-  if (any_resident) {
-    S_TRY(hipMemcpyAsync(ix->h_reskey, W.res_key, (size_t)nq * k * 4, hipMemcpyDeviceToHost, st));
-    S_TRY(hipMemcpyAsync(ix->h_resid, W.res_id, (size_t)nq * k * 8, hipMemcpyDeviceToHost, st));
-    S_TRY(hipMemcpyAsync(ix->h_lutmax, W.lutmax, (size_t)nq * 4, hipMemcpyDeviceToHost, st));
-  }
   S_TRY(hipStreamSynchronize(st));
-  release(false);
+  end_batch(ix, ctx, st, false);
+  const float *hq = a.q_host ? a.q_host : ix->h_queries;
 
   const HostIndexView view = host_view(ix);
   std::vector<int> bad(1, 0);
   parallel_for(nq, [&](int64_t q) {
-    std::vector<HostCand> gpu(k), cpu(k), fin(k);
-    for (int r = 0; r < k; ++r) {
-      if (any_resident) gpu[r] = HostCand{ix->h_reskey[q * k + r], ix->h_resid[q * k + r]};
-      else gpu[r] = HostCand{kKeyInvalid, -1};
-    }
-    int e = 0;
-    if (any_resident) {
-      float mx;
-      memcpy(&mx, &ix->h_lutmax[q], 4);
-      e = lut_exponent(mx, view.M, ix->h_qbmax[q], view.pv ? view.pv_max : 0.0f);
-    }
     const int nc = ix->h_ncold[q];
-    const HostCand *res = gpu.data();
+    std::vector<HostCand> cpu;
+    int e_cpu = 0;
     if (nc > 0 || !any_resident) {
       std::vector<int32_t> lut((size_t)view.M * 256);
+      cpu.resize((size_t)k);
       const float *qv = hq + (size_t)q * view.d;
-      const int e_cpu = cpu_build_lut(view, qv, ix->h_qbmax[q], lut.data());
-      if (any_resident && e_cpu != e) __atomic_store_n(&bad[0], 1, __ATOMIC_RELAXED);
-      e = e_cpu;
-      cpu_scan_lists(view, lut.data(), e, qv, ix->h_cold + (size_t)q * np, nc, k, cpu.data());
-      merge_topk(gpu.data(), cpu.data(), k, fin.data());
-      res = fin.data();
+      e_cpu = cpu_build_lut(view, qv, ix->h_qbmax[q], lut.data());
+      cpu_scan_lists(view, lut.data(), e_cpu, qv, ix->h_cold + (size_t)q * np, nc, k, cpu.data());
     }
-    emit_results(ix, res, k, e, &ix->h_outids[(size_t)q * k], &ix->h_outd[(size_t)q * k]);
+    if (!finish_query(ix, view, any_resident, q, k, cpu.empty() ? nullptr : cpu.data(), e_cpu,
+                      &ix->h_outids[(size_t)q * k], &ix->h_outd[(size_t)q * k]))
+      __atomic_store_n(&bad[0], 1, __ATOMIC_RELAXED);
   });
   if (bad[0])
     return fail(IVF_EDEVICE, "internal: CPU and GPU lookup-table scales disagree");
@@ -1208,6 +1285,23 @@ static int check_search_args(const ivf_index *ix, const void *queries, int64_t n
     if (k > ix->desc.max_k) return fail(IVF_EINVAL, "k %d exceeds max_k %d", k, ix->desc.max_k);
   } else if (k > kMaxK) {
     return fail(IVF_EINVAL, "k %d exceeds %d", k, kMaxK);
+  }
+  return IVF_OK;
+}
+
+// A caller's probe list: ids below nlist (negative = no probe), distinct within a query.
+static int check_probe_list(const ivf_index *ix, const int32_t *probe, int64_t nq, int nprobe) {
+  std::vector<int32_t> row((size_t)nprobe);
+  for (int64_t q = 0; q < nq; ++q) {
+    int n = 0;
+    for (int p = 0; p < nprobe; ++p) {
+      const int32_t c = probe[q * nprobe + p];
+      if (c >= ix->sh.nlist) return fail(IVF_EINVAL, "probe id %d out of range", c);
+      if (c >= 0) row[n++] = c;
+    }
+    std::sort(row.begin(), row.begin() + n);
+    if (std::adjacent_find(row.begin(), row.begin() + n) != row.begin() + n)
+      return fail(IVF_EINVAL, "query %lld lists a cluster twice", (long long)q);
   }
   return IVF_OK;
 }
@@ -1284,21 +1378,8 @@ extern "C" int ivf_search_batch_probes(ivf_index_t *ix, const float *queries, in
   if (!probe) return fail(IVF_EINVAL, "probe is NULL");
   if (ix->has_dev && nprobe > ix->desc.max_nprobe)
     return fail(IVF_EINVAL, "nprobe %d exceeds max_nprobe %d", nprobe, ix->desc.max_nprobe);
-  // validate the caller's list: ids in range, distinct within a query
-  {
-    std::vector<int32_t> row(nprobe);
-    for (int64_t q = 0; q < nq; ++q) {
-      int n = 0;
-      for (int p = 0; p < nprobe; ++p) {
-        const int32_t c = probe[q * nprobe + p];
-        if (c >= ix->sh.nlist) return fail(IVF_EINVAL, "probe id %d out of range", c);
-        if (c >= 0) row[n++] = c;
-      }
-      std::sort(row.begin(), row.begin() + n);
-      if (std::adjacent_find(row.begin(), row.begin() + n) != row.begin() + n)
-        return fail(IVF_EINVAL, "query %lld lists a cluster twice", (long long)q);
-    }
-  }
+  rc = check_probe_list(ix, probe, nq, nprobe);
+  if (rc != IVF_OK) return rc;
   if (!ix->has_dev) return search_host_only(ix, queries, nq, probe, nprobe, k, out_ids, out_dists);
   SearchArgs a;
   a.q_host = queries;
@@ -1310,6 +1391,277 @@ extern "C" int ivf_search_batch_probes(ivf_index_t *ix, const float *queries, in
   a.out_dists = out_dists;
   a.st = ix->own_stream;
   return search_device(ix, a);
+}
+
+// ---------------------------------------------------------------------------
+// dynamic dispatcher (Section 4.3.2): per-query completion of a hybrid batch
+// ---------------------------------------------------------------------------
+struct ivf_ticket {
+  ivf_index *ix = nullptr;
+  int nq = 0, np = 0, k = 0;
+  bool device = false;        // the batch has a device side
+  bool any_resident = false;
+  BatchCtx ctx;
+  hipStream_t st = nullptr;
+  hipEvent_t ev_route = nullptr, ev_gpu = nullptr;
+  const float *hq = nullptr;        // caller's queries (borrowed until wait)
+  std::vector<int32_t> own_probe;   // device-less index: the caller's probe list
+  int64_t *out_ids = nullptr;
+  float *out_dists = nullptr;
+  ivf_query_done_fn on_done = nullptr;
+  void *user = nullptr;
+
+  std::thread dispatcher;
+  std::mutex mu;
+  std::condition_variable cv;
+  std::deque<int32_t> ready;        // queries whose CPU scan count reached its expected value
+  std::vector<int32_t> forwarded;   // queries handed downstream, in completion order
+  size_t polled = 0;
+  bool finished = false;
+  int rc = IVF_OK;
+  std::string err;
+
+  std::vector<HostCand> cpu_res;    // [nq][k] CPU partial results
+  std::vector<int> cpu_e;           // table exponent of each query's CPU scan
+  std::vector<int32_t> scanned;     // clusters scanned so far, per query
+  std::vector<double> done_ms;      // time from the call to the hand-off, per query
+  std::chrono::steady_clock::time_point t0;
+};
+
+static void ticket_fail(ivf_ticket *t, int code, const std::string &msg) {
+  std::lock_guard<std::mutex> lk(t->mu);
+  if (t->rc == IVF_OK) {
+    t->rc = code;
+    t->err = msg;
+  }
+}
+
+static void dispatcher_main(ivf_ticket *t) {
+  ivf_index *ix = t->ix;
+  const int nq = t->nq, np = t->np, k = t->k;
+  const HostIndexView view = host_view(ix);
+  bool gpu_ok = true;
+  if (t->device) {
+    hipError_t e = hipSetDevice(ix->device);
+    // the cold probe lists and scale inputs are on the host once routing is done
+    if (e == hipSuccess) e = hipEventSynchronize(t->ev_route);
+    if (e != hipSuccess) {
+      ticket_fail(t, IVF_EDEVICE, std::string("routing failed: ") + hipGetErrorString(e));
+      gpu_ok = false;
+    }
+  }
+  const int32_t *cold = t->device ? ix->h_cold : t->own_probe.data();
+  auto expected = [&](int q) { return t->device ? ix->h_ncold[q] : np; };
+
+  std::vector<std::thread> workers;
+  std::atomic<int64_t> next(0);
+  std::vector<int32_t> order((size_t)nq);
+  if (gpu_ok) {
+    // CPU search loop.  Queries are taken fewest cold probes first, so that the
+    // ones the GPU served almost entirely are handed on earliest.
+    for (int q = 0; q < nq; ++q) order[q] = q;
+    std::stable_sort(order.begin(), order.end(),
+                     [&](int32_t a, int32_t b) { return expected(a) < expected(b); });
+    auto work = [&]() {
+      std::vector<int32_t> lut((size_t)view.M * 256);
+      for (;;) {
+        const int64_t i = next.fetch_add(1, std::memory_order_relaxed);
+        if (i >= nq) break;
+        const int q = order[(size_t)i];
+        const int nc = expected(q);
+        if (nc > 0) {
+          const float *qv = t->hq + (size_t)q * view.d;
+          const int32_t *pr = cold + (size_t)q * np;
+          const float mb = t->device ? ix->h_qbmax[q] : cpu_max_bias(view, qv, pr, nc);
+          const int e = cpu_build_lut(view, qv, mb, lut.data());
+          t->cpu_e[q] = e;
+          cpu_scan_lists(view, lut.data(), e, qv, pr, nc, k, &t->cpu_res[(size_t)q * k],
+                         &t->scanned[q]);
+        }
+        // scan count == expected count: the query goes to the completed queue
+        if (__atomic_load_n(&t->scanned[q], __ATOMIC_ACQUIRE) == nc) {
+          {
+            std::lock_guard<std::mutex> lk(t->mu);
+            t->ready.push_back(q);
+          }
+          t->cv.notify_one();
+        }
+      }
+    };
+    const int nt = (int)std::min<int64_t>(cpu_threads(), nq);
+    for (int i = 0; i < nt; ++i) workers.emplace_back(work);
+  }
+
+  // the GPU's completion flag: its partial results are on the host
+  if (t->device && gpu_ok) {
+    hipError_t e = hipEventSynchronize(t->ev_gpu);
+    if (e != hipSuccess) {
+      ticket_fail(t, IVF_EDEVICE, std::string("device scan failed: ") + hipGetErrorString(e));
+      gpu_ok = false;
+    }
+  }
+  if (t->device) end_batch(ix, t->ctx, t->st, false);
+
+  // poll the completed queue: merge, re-rank, hand on
+  int n_done = 0;
+  std::vector<int32_t> batch;
+  while (gpu_ok && n_done < nq) {
+    {
+      std::unique_lock<std::mutex> lk(t->mu);
+      t->cv.wait_for(lk, std::chrono::microseconds(200), [&] { return !t->ready.empty(); });
+      batch.assign(t->ready.begin(), t->ready.end());
+      t->ready.clear();
+    }
+    for (int32_t q : batch) {
+      int64_t *ids = t->out_ids + (size_t)q * k;
+      float *dists = t->out_dists + (size_t)q * k;
+      const bool has_cpu = expected(q) > 0;
+      if (!finish_query(ix, view, t->any_resident, q, k,
+                        has_cpu ? &t->cpu_res[(size_t)q * k] : nullptr, t->cpu_e[q], ids, dists))
+        ticket_fail(t, IVF_EDEVICE, "internal: CPU and GPU lookup-table scales disagree");
+      t->done_ms[q] =
+          std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t->t0)
+              .count();
+      {
+        std::lock_guard<std::mutex> lk(t->mu);
+        t->forwarded.push_back(q);
+      }
+      if (t->on_done) t->on_done(t->user, q, ids, dists, k);
+      ++n_done;
+    }
+  }
+  for (auto &w : workers) w.join();
+  {
+    std::lock_guard<std::mutex> lk(t->mu);
+    t->finished = true;
+  }
+}
+
+extern "C" int ivf_search_batch_async(ivf_index_t *ix, const float *queries, int64_t nq,
+                                      const int32_t *probe, int32_t nprobe, int32_t k,
+                                      int64_t *out_ids, float *out_dists,
+                                      ivf_query_done_fn on_done, void *user,
+                                      ivf_ticket_t **ticket) {
+  if (!ticket) return fail(IVF_EINVAL, "ticket is NULL");
+  *ticket = nullptr;
+  int rc = check_search_args(ix, queries, nq, nprobe, k, out_ids, out_dists);
+  if (rc != IVF_OK) return rc;
+  if (nq > 0x7fffffff) return fail(IVF_EINVAL, "nq too large");
+  if (!ix->has_dev && !probe)
+    return fail(IVF_EDEVICE, "host-only index: the coarse quantizer needs the device "
+                             "(pass a probe list)");
+  int np = nprobe;
+  if (!probe) np = std::min<int32_t>(nprobe, ix->sh.nlist);
+  if (ix->has_dev && np > ix->desc.max_nprobe)
+    return fail(IVF_EINVAL, "nprobe %d exceeds max_nprobe %d", np, ix->desc.max_nprobe);
+  if (!ix->has_dev && np > kMaxNprobe) return fail(IVF_EINVAL, "nprobe %d exceeds %d", np, kMaxNprobe);
+  if (probe && nq > 0) {
+    rc = check_probe_list(ix, probe, nq, np);
+    if (rc != IVF_OK) return rc;
+  }
+  {
+    std::lock_guard<std::mutex> lk(ix->mu);
+    if (ix->dispatch_active)
+      return fail(IVF_EBUSY, "an asynchronous batch is still in flight on this index");
+    ix->dispatch_active = true;
+  }
+  ivf_ticket *t = new ivf_ticket();
+  auto abandon = [&](int code) {
+    if (t->ev_route) (void)hipEventDestroy(t->ev_route);
+    if (t->ev_gpu) (void)hipEventDestroy(t->ev_gpu);
+    delete t;
+    std::lock_guard<std::mutex> lk(ix->mu);
+    ix->dispatch_active = false;
+    return code;
+  };
+  t->ix = ix;
+  t->nq = (int)nq;
+  t->np = np;
+  t->k = k;
+  t->hq = queries;
+  t->out_ids = out_ids;
+  t->out_dists = out_dists;
+  t->on_done = on_done;
+  t->user = user;
+  t->device = ix->has_dev;
+  t->cpu_res.resize((size_t)nq * k);
+  t->cpu_e.assign((size_t)nq, 0);
+  t->scanned.assign((size_t)nq, 0);
+  t->done_ms.assign((size_t)nq, 0.0);
+  t->t0 = std::chrono::steady_clock::now();
+  if (nq == 0) {
+    t->finished = true;
+    *ticket = t;
+    return IVF_OK;
+  }
+  if (t->device) {
+    hipError_t e;
+    if ((e = hipEventCreateWithFlags(&t->ev_route, hipEventDisableTiming)) != hipSuccess ||
+        (e = hipEventCreateWithFlags(&t->ev_gpu, hipEventDisableTiming)) != hipSuccess)
+      return abandon(fail(IVF_EDEVICE, "hipEventCreate failed: %s", hipGetErrorString(e)));
+    t->st = ix->own_stream;
+    rc = begin_batch(ix, t->st, &t->ctx);
+    if (rc < 0) return abandon(rc);
+    t->any_resident = t->ctx.any_resident;
+    SearchArgs a;
+    a.q_host = queries;
+    a.probe_host = probe;
+    a.nq = nq;
+    a.nprobe = np;
+    a.k = k;
+    a.st = t->st;
+    rc = enqueue_gpu(ix, a, t->ctx, /*final_on_gpu=*/false, t->ev_route);
+    if (rc == IVF_OK && hipEventRecord(t->ev_gpu, t->st) != hipSuccess)
+      rc = fail(IVF_EDEVICE, "hipEventRecord failed");
+    if (rc < 0) {
+      (void)hipStreamSynchronize(t->st);
+      end_batch(ix, t->ctx, t->st, false);
+      return abandon(rc);
+    }
+  } else {
+    t->own_probe.assign(probe, probe + (size_t)nq * np);
+    std::lock_guard<std::mutex> lk(ix->mu);
+    for (int64_t i = 0; i < nq * np; ++i)
+      if (probe[i] >= 0) {
+        ix->hc_hits[probe[i]] += 1;
+        ix->hc_probes += 1;
+      }
+    ix->hc_queries += (uint64_t)nq;
+  }
+  t->dispatcher = std::thread(dispatcher_main, t);
+  *ticket = t;
+  return IVF_OK;
+}
+
+extern "C" int ivf_search_poll(ivf_ticket_t *t, int64_t *queries_done, int64_t cap,
+                               int64_t *n_done, int32_t *finished) {
+  if (!t || !n_done || !finished || cap < 0 || (cap > 0 && !queries_done))
+    return fail(IVF_EINVAL, "bad argument");
+  std::lock_guard<std::mutex> lk(t->mu);
+  int64_t n = 0;
+  while (n < cap && t->polled < t->forwarded.size()) queries_done[n++] = t->forwarded[t->polled++];
+  *n_done = n;
+  *finished = (t->finished && t->polled == t->forwarded.size()) ? 1 : 0;
+  if (t->rc != IVF_OK) return fail(t->rc, "%s", t->err.c_str());
+  return IVF_OK;
+}
+
+extern "C" int ivf_search_wait(ivf_ticket_t *t, double *done_ms) {
+  if (!t) return fail(IVF_EINVAL, "ticket is NULL");
+  if (t->dispatcher.joinable()) t->dispatcher.join();
+  if (done_ms && t->rc == IVF_OK)
+    for (int q = 0; q < t->nq; ++q) done_ms[q] = t->done_ms[q];
+  const int rc = t->rc;
+  const std::string err = t->err;
+  if (t->ev_route) (void)hipEventDestroy(t->ev_route);
+  if (t->ev_gpu) (void)hipEventDestroy(t->ev_gpu);
+  {
+    std::lock_guard<std::mutex> lk(t->ix->mu);
+    t->ix->dispatch_active = false;
+  }
+  delete t;
+  if (rc != IVF_OK) return fail(rc, "%s", err.c_str());
+  return IVF_OK;
 }
 
 extern "C" int ivf_calib_copy(const void *src, void *dst, size_t bytes, void *stream) {

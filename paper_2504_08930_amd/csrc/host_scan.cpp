@@ -102,13 +102,15 @@ static inline bool cand_less(const HostCand &a, const HostCand &b) {
 }
 
 void cpu_scan_lists(const HostIndexView &ix, const int32_t *lut, int e, const float *q,
-                    const int32_t *clusters, int n_clusters, int k, HostCand *out) {
+                    const int32_t *clusters, int n_clusters, int k, HostCand *out,
+                    int32_t *scanned) {
   // bounded max-heap on (key, id): the worst kept candidate sits on top
   std::vector<HostCand> heap;
   heap.reserve((size_t)k);
   const int M = ix.M;
   for (int c = 0; c < n_clusters; ++c) {
     const int cl = clusters[c];
+    if (scanned) __atomic_store_n(scanned, c, __ATOMIC_RELAXED);
     if (cl < 0) continue;
     int32_t bias_key = 0;
     if (ix.by_residual)
@@ -133,6 +135,7 @@ void cpu_scan_lists(const HostIndexView &ix, const int32_t *lut, int e, const fl
   std::sort_heap(heap.begin(), heap.end(), cand_less);
   for (int r = 0; r < k; ++r)
     out[r] = r < (int)heap.size() ? heap[r] : HostCand{kKeyInvalid, -1};
+  if (scanned) __atomic_store_n(scanned, n_clusters, __ATOMIC_RELEASE);
 }
 
 void merge_topk(const HostCand *a, const HostCand *b, int k, HostCand *out) {

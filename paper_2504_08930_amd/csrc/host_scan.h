@@ -47,8 +47,12 @@ int cpu_build_lut(const HostIndexView &ix, const float *q, float max_bias, int32
 
 // Scan the listed clusters for one query with the table and exponent from
 // cpu_build_lut; writes k candidates, best first, padded with (kKeyInvalid, -1).
+// Clusters are taken one by one; `scanned` (optional) holds the number of list
+// entries finished so far and reaches n_clusters once `out` is written, which is
+// what the dispatcher compares with the query's expected count (Section 4.3.2).
 void cpu_scan_lists(const HostIndexView &ix, const int32_t *lut, int e, const float *q,
-                    const int32_t *clusters, int n_clusters, int k, HostCand *out);
+                    const int32_t *clusters, int n_clusters, int k, HostCand *out,
+                    int32_t *scanned = nullptr);
 
 // Merge two best-first lists of k candidates into the k best.
 void merge_topk(const HostCand *a, const HostCand *b, int k, HostCand *out);

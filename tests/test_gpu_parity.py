@@ -391,3 +391,46 @@ def test_residual_encoding(pkg, oracle, name):
     ids, dist = index.search_batch(q, spec.nprobe, spec.k)
     assert np.array_equal(ids, base[0]) and np.array_equal(dist, base[1])
     index.close()
+
+
+@pytest.mark.parametrize("name,residual", [("T_L2", False), ("T_IP96", False), ("T_L2", True)])
+def test_dispatcher_hybrid(pkg, oracle, name, residual):
+    """Dynamic dispatcher (Section 4.3.2): per-query hand-off of a hybrid batch.  What is
+    unique (each query's ids and distances) must equal the bulk path bit for bit and the
+    oracle within tolerance; the order of hand-off is not unique and is checked for
+    validity (each query once, its row final at that moment, times non-decreasing)."""
+    spec, ix, q, calib = _case(name, by_residual=residual)
+    index = pkg.IvfIndex(ix, max_nq=256, max_nprobe=ix.nlist, max_k=128)
+    full = np.arange(ix.nlist, dtype=np.int32)
+    index.load_partition(full)
+    hot30 = hottest(index, calib, spec.nprobe, 0.3, ix.nlist)
+    for rs in (hot30, full, np.zeros(0, np.int32)):
+        _say(f"dispatcher {name} residual={residual} resident={len(rs)}/{ix.nlist}")
+        index.load_partition(rs)
+        ref_i, ref_d = index.search_batch(q, spec.nprobe, spec.k)
+        index.hit_stats(reset=True)
+        seen = []
+        t = index.search_batch_async(q, spec.nprobe, spec.k,
+                                     on_done=lambda qi, a, b: seen.append((qi, a.copy(), b.copy())))
+        polled, fin = [], False
+        while not fin:
+            got, fin = t.poll()
+            polled.extend(got.tolist())
+        ids, dists, done_ms = t.wait()
+        assert np.array_equal(ids, ref_i) and np.array_equal(dists, ref_d)
+        assert sorted(polled) == list(range(q.shape[0]))
+        assert [s[0] for s in seen] == polled
+        for qi, a, b in seen:
+            assert np.array_equal(a, ref_i[qi]) and np.array_equal(b, ref_d[qi])
+        assert np.all(np.diff(done_ms[polled]) >= 0)
+        st = index.hit_stats(reset=True)
+        assert st["n_queries"] == q.shape[0]
+        # the index is usable again, also with a caller's probe list
+        import torch
+        gp = index.coarse_probe_dev(torch.from_numpy(q).cuda(), spec.nprobe).cpu().numpy()
+        t2 = index.search_batch_async(q, spec.nprobe, spec.k, probe=gp)
+        ids2, dists2, _ = t2.wait()
+        assert np.array_equal(ids2, ref_i) and np.array_equal(dists2, ref_d)
+    n_coarse, n_amb = _check_search(oracle, ix, q, spec.nprobe, spec.k, ids, dists)
+    assert n_amb <= max(1, q.shape[0] // 20)
+    index.close()

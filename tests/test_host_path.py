@@ -163,3 +163,53 @@ def test_desc_validation_and_arena_size(lib):
     for bad in (desc(nbits=4), desc(M=24), desc(M=160), desc(d=770), desc(metric=7),
                 desc(max_k=1000), desc(max_nprobe=0), desc(nlist=0)):
         assert cdll.ivf_index_arena_bytes(ctypes.byref(bad), 1000, 0) == 0
+
+
+def test_dispatcher_host_only_matches_synchronous_search(case, oracle):
+    """Per-query completion (Section 4.3.2): every query is handed on exactly once, its
+    row is final when the callback runs, and the results are those of the bulk path."""
+    spec, ix, q, index = case
+    probe, _, _ = oracle.coarse(ix.metric, ix.centroids, q, spec.nprobe)
+    probe = probe.astype(np.int32)
+    probe[3, 2:] = -1                      # a query with almost nothing to scan
+    ref_i, ref_d = index.search_batch_probes(q, probe, spec.k)
+    seen = []
+
+    def on_done(qi, ids_row, dists_row):
+        seen.append((qi, ids_row.copy(), dists_row.copy()))
+
+    t = index.search_batch_async(q, spec.nprobe, spec.k, probe=probe, on_done=on_done)
+    polled = []
+    fin = False
+    while not fin:
+        got, fin = t.poll(cap=7)
+        polled.extend(got.tolist())
+    ids, dists, done_ms = t.wait()
+    assert np.array_equal(ids, ref_i) and np.array_equal(dists, ref_d)
+    assert sorted(polled) == list(range(q.shape[0]))
+    assert [s[0] for s in seen] == polled                     # one order, each query once
+    for qi, ids_row, dists_row in seen:
+        assert np.array_equal(ids_row, ref_i[qi]) and np.array_equal(dists_row, ref_d[qi])
+    assert np.all(done_ms > 0) and np.all(np.diff(done_ms[polled]) >= 0)
+
+
+def test_dispatcher_blocks_other_searches_until_waited(case, lib, oracle):
+    import threading
+    spec, ix, q, index = case
+    probe, _, _ = oracle.coarse(ix.metric, ix.centroids, q, spec.nprobe)
+    gate = threading.Event()
+    t = index.search_batch_async(q, spec.nprobe, spec.k, probe=probe,
+                                 on_done=lambda *_: gate.wait(10))
+    with pytest.raises(lib.IvfError) as e:
+        index.search_batch_async(q, spec.nprobe, spec.k, probe=probe)
+    assert e.value.code == -4
+    gate.set()
+    ids, dists, _ = t.wait()
+    ref_i, ref_d = index.search_batch_probes(q, probe, spec.k)
+    assert np.array_equal(ids, ref_i) and np.array_equal(dists, ref_d)
+    with pytest.raises(lib.IvfError):
+        index.search_batch_async(q, spec.nprobe, spec.k)          # no probe list, no device
+    empty = index.search_batch_async(q[:0], spec.nprobe, spec.k, probe=probe[:0])
+    got, fin = empty.poll()
+    assert got.size == 0 and fin
+    empty.wait()
