@@ -613,35 +613,9 @@ __global__ __launch_bounds__(NW * 64) void k_scan(ScanParams P) {
   const int s = u % P.slices;
   const int k = P.k;
 
-  // ---- stage the query's table in LDS as fixed point, code-major ----
+  // scale of the query's fixed-point table
   const int e = lut_exponent(__uint_as_float(P.lutmax[q]), M, RES ? P.qbmax[q] : 0.0f,
                              RES == 2 ? P.pv_max : 0.0f);
-  {
-    const float4 *src = reinterpret_cast<const float4 *>(P.lut + (size_t)q * 256 * M);
-    constexpr int kVec = 256 * M / 4;
-    for (int idx = tid; idx < kVec; idx += NW * 64) {
-      const float4 v = src[idx];
-      const int flat = idx * 4;
-      const int j = flat / M;
-      const int m0 = flat % M;  // 4 consecutive sub-quantizers of one code (M % 4 == 0)
-      const float vv[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-      for (int t = 0; t < 4; ++t) {
-        const int m = m0 + t;
-        const int key = lut_quantize(vv[t], e);
-        int gi = m / 32, r = m % 32;
-        int *row = tab + (gi >> 1) * (G::kTableBytes / 4) + j * 64 + (gi & 1) * 32;
-        row[r] = key;
-        if (G::kRem && gi == G::kFull) row[r + 16] = key;  // 16-wide group: second replica
-      }
-    }
-    if (tid == 0) {
-      *s_thr = kKeyInvalid;
-      *s_total = 0;
-    }
-  }
-  __syncthreads();
-
   int *bkey = buf_key_all + w * CAP;
   long long *bid = buf_id_all + w * CAP;
 
@@ -802,6 +776,30 @@ __global__ __launch_bounds__(NW * 64) void k_scan(ScanParams P) {
       cur = locate(t);
       load_tile(cur, ca, pa);
     }
+    // ---- stage the query's table in LDS as fixed point, code-major (the first
+    // tile's loads are already in flight) ----
+    {
+      const float4 *src = reinterpret_cast<const float4 *>(P.lut + (size_t)q * 256 * M);
+      constexpr int kVec = 256 * M / 4;
+      for (int idx = tid; idx < kVec; idx += NW * 64) {
+        const float4 v = src[idx];
+        const int flat = idx * 4;
+        const int j = flat / M;
+        const int m0 = flat % M;  // 4 consecutive sub-quantizers of one code (M % 4 == 0)
+        const int4 keys = make_int4(lut_quantize(v.x, e), lut_quantize(v.y, e),
+                                    lut_quantize(v.z, e), lut_quantize(v.w, e));
+        const int gi = m0 / 32, r = m0 % 32;  // the four share a 32-wide group
+        int *row = tab + (gi >> 1) * (G::kTableBytes / 4) + j * 64 + (gi & 1) * 32;
+        *reinterpret_cast<int4 *>(row + r) = keys;
+        if (G::kRem && gi == G::kFull)  // 16-wide group: second replica
+          *reinterpret_cast<int4 *>(row + r + 16) = keys;
+      }
+      if (tid == 0) {
+        *s_thr = kKeyInvalid;
+        *s_total = 0;
+      }
+    }
+    __syncthreads();
     while (t < t_end) {
       const int tn = t + NW;
       TileRef nxt{0, 0, 0, 0};
@@ -849,32 +847,42 @@ __global__ __launch_bounds__(NW * 64) void k_scan(ScanParams P) {
   __syncthreads();
   if (w != 0) return;
   const int n = *s_total;
-  int kth_key = kKeyInvalid;
+  // keys of all gathered candidates in registers, order-preserving unsigned form
+  constexpr int R = kMaxCand / 64;
+  const int ne = (n + 63) >> 6;
+  uint32_t rk[R];
+#pragma unroll
+  for (int e2 = 0; e2 < R; ++e2) {
+    const int i = e2 * 64 + lane;
+    rk[e2] = (e2 < ne && i < n) ? ((uint32_t)mkey[i] ^ 0x80000000u) : 0xffffffffu;
+  }
+  uint32_t kth_u = 0xffffffffu;
   if (n > k) {
     uint32_t prefix = 0;
     for (int bit = 31; bit >= 0; --bit) {
       const uint32_t cand = prefix | (1u << bit);
       int c = 0;
-      for (int i0 = 0; i0 < n; i0 += 64) {
-        const int i = i0 + lane;
-        const bool below = i < n && ((uint32_t)mkey[i] ^ 0x80000000u) < cand;
-        c += __popcll(__ballot(below));
-      }
+#pragma unroll
+      for (int e2 = 0; e2 < R; ++e2)
+        if (e2 < ne) c += __popcll(__ballot(rk[e2] < cand));
       if (c < k) prefix = cand;
     }
-    kth_key = (int)(prefix ^ 0x80000000u);
+    kth_u = prefix;
   }
   int nf = 0;
-  for (int i0 = 0; i0 < n; i0 += 64) {
-    const int i = i0 + lane;
-    const bool keep = i < n && mkey[i] <= kth_key;
-    const unsigned long long mask = __ballot(keep);
-    if (keep) {
-      const int o = nf + __popcll(mask & lt_mask);
-      fkey[o] = mkey[i];
-      fid[o] = mid[i];
+#pragma unroll
+  for (int e2 = 0; e2 < R; ++e2) {
+    if (e2 < ne) {
+      const int i = e2 * 64 + lane;
+      const bool keep = i < n && rk[e2] <= kth_u;
+      const unsigned long long mask = __ballot(keep);
+      if (keep) {
+        const int o = nf + __popcll(mask & lt_mask);
+        fkey[o] = (int)(rk[e2] ^ 0x80000000u);
+        fid[o] = mid[i];
+      }
+      nf += __popcll(mask);
     }
-    nf += __popcll(mask);
   }
   wave_sync();
   const size_t obase = ((size_t)q * P.slices + s) * k;
