@@ -130,13 +130,16 @@ int oracle_coarse(int metric, int d, int nlist, const float *centroids,
  * Stages (2)+(3) over a given probe list (negative entries are skipped).
  * use_pq != 0: each stored code is decoded to its representative values,
  *   x_hat = concat_m codebooks[m][code[m]], and scored against the query.
+ *   nbits = 8: one byte per sub-quantizer, 256 codewords each; nbits = 4: 16
+ *   codewords each, two codes per byte (Section 2.2 describes fast-scan indexes
+ *   with such short codes), codebooks [M][16][d/M].
  *   With residual_centroids != NULL ([nlist][d]) the codes encode residuals and
  *   x_hat = centroid of the list + concat_m codebooks[m][code[m]].
  * use_pq == 0 ("flat"): the raw fp32 vector (flat_vectors, same order as
  *   codes) is scored instead.
  * All candidates of the query are fully sorted; the first k are returned.
  */
-int oracle_scan(int metric, int d, int M, const float *codebooks,
+int oracle_scan(int metric, int d, int M, int nbits, const float *codebooks,
                 const int64_t *list_offsets, const uint8_t *codes,
                 const int64_t *ids, const float *flat_vectors, int use_pq,
                 const float *residual_centroids,
@@ -144,8 +147,11 @@ int oracle_scan(int metric, int d, int M, const float *codebooks,
                 const int32_t *probe, int k, int64_t *out_ids, double *out_dist) {
     if (d <= 0 || k <= 0 || nprobe <= 0 || nq < 0) return -1;
     if (use_pq && (M <= 0 || d % M != 0)) return -1;
+    if (use_pq && nbits != 8 && !(nbits == 4 && M % 2 == 0)) return -1;
     if (!use_pq && !flat_vectors) return -1;
     int dsub = use_pq ? d / M : 0;
+    int ksub = 1 << nbits;                           /* codewords per sub-quantizer */
+    size_t code_bytes = ((size_t)M * (size_t)nbits) / 8;
     int failed = 0;
 #pragma omp parallel for schedule(dynamic, 1)
     for (int64_t qi = 0; qi < nq; ++qi) {
@@ -171,11 +177,14 @@ int oracle_scan(int metric, int d, int M, const float *codebooks,
             for (int64_t v = list_offsets[c]; v < list_offsets[c + 1]; ++v) {
                 const float *x;
                 if (use_pq) {
-                    const uint8_t *code = codes + (size_t)v * M;
-                    for (int m = 0; m < M; ++m)
+                    const uint8_t *code = codes + (size_t)v * code_bytes;
+                    for (int m = 0; m < M; ++m) {
+                        /* 4-bit codes: two per byte, the even sub-quantizer in the low half */
+                        int j = nbits == 8 ? code[m] : (code[m >> 1] >> (4 * (m & 1))) & 15;
                         memcpy(xhat + (size_t)m * dsub,
-                               codebooks + ((size_t)m * 256 + code[m]) * dsub,
+                               codebooks + ((size_t)m * ksub + j) * dsub,
                                sizeof(float) * (size_t)dsub);
+                    }
                     x = xhat;
                 } else {
                     x = flat_vectors + (size_t)v * d;

@@ -36,7 +36,7 @@ def _load():
         lib.oracle_coarse.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, P,
                                       ctypes.c_int64, P, ctypes.c_int, P, P, P]
         lib.oracle_coarse.restype = ctypes.c_int
-        lib.oracle_scan.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, P, P, P, P, P,
+        lib.oracle_scan.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, P, P, P, P, P,
                                     ctypes.c_int, P, ctypes.c_int64, P, ctypes.c_int, P,
                                     ctypes.c_int, P, P]
         lib.oracle_scan.restype = ctypes.c_int
@@ -88,14 +88,16 @@ def scan(metric, codebooks, list_offsets, codes, ids, queries, probe, k,
     if flat_vectors is None:
         codebooks = _f32(codebooks)
         codes = np.ascontiguousarray(codes, dtype=np.uint8)
-        m = codebooks.shape[0]
+        m, ksub = codebooks.shape[0], codebooks.shape[1]
+        nbits = {256: 8, 16: 4}[ksub]
+        assert codes.shape[1] == m * nbits // 8
         cen = None if residual_centroids is None else _f32(residual_centroids)
-        rc = _load().oracle_scan(metric, d, m, _p(codebooks), _p(list_offsets), _p(codes),
+        rc = _load().oracle_scan(metric, d, m, nbits, _p(codebooks), _p(list_offsets), _p(codes),
                                  _p(ids), None, 1, _p(cen), nq, _p(queries), nprobe, _p(probe), k,
                                  _p(out_ids), _p(out_d))
     else:
         flat_vectors = _f32(flat_vectors)
-        rc = _load().oracle_scan(metric, d, 0, None, _p(list_offsets), None, _p(ids),
+        rc = _load().oracle_scan(metric, d, 0, 8, None, _p(list_offsets), None, _p(ids),
                                  _p(flat_vectors), 0, None, nq, _p(queries), nprobe, _p(probe), k,
                                  _p(out_ids), _p(out_d))
     if rc != 0:

@@ -23,12 +23,13 @@ class IvfPqIndexData:
     m: int
     metric: int
     centroids: np.ndarray      # fp32 [nlist, d]
-    codebooks: np.ndarray      # fp32 [m, 256, d/m]
+    codebooks: np.ndarray      # fp32 [m, 2**nbits, d/m]
     list_offsets: np.ndarray   # int64 [nlist+1]
-    codes: np.ndarray          # uint8 [n, m], list-contiguous
+    codes: np.ndarray          # uint8 [n, m * nbits / 8], list-contiguous
     ids: np.ndarray            # int64 [n], database id of each stored code
     n: int
     by_residual: bool = False  # codes encode x - centroid of its list
+    nbits: int = 8             # bits per code; 4: two codes per byte, even sub-quantizer low
 
     @property
     def dsub(self) -> int:
@@ -71,42 +72,50 @@ def _kmeans(x, k, iters, spherical, seed, chunk):
     return cent.contiguous()
 
 
-def _train_pq(x, m, iters, seed):
-    """Per-sub-space k-means, 256 centroids each.  x: [n, d] -> [m, 256, dsub]."""
+def _train_pq(x, m, iters, seed, ksub=256):
+    """Per-sub-space k-means, ksub centroids each.  x: [n, d] -> [m, ksub, dsub]."""
     n, d = x.shape
     dsub = d // m
     xs = x.view(n, m, dsub).permute(1, 0, 2).contiguous()      # [m, n, dsub]
     g = torch.Generator(device="cpu")
     g.manual_seed(seed)
-    perm = torch.randperm(n, generator=g)[:256].to(x.device)
-    cb = xs[:, perm, :].clone()                                 # [m, 256, dsub]
-    base = (torch.arange(m, device=x.device) * 256)[:, None]
+    perm = torch.randperm(n, generator=g)[:ksub].to(x.device)
+    cb = xs[:, perm, :].clone()                                 # [m, ksub, dsub]
+    base = (torch.arange(m, device=x.device) * ksub)[:, None]
     for _ in range(iters):
         dist = (cb * cb).sum(2)[:, None, :] - 2.0 * torch.bmm(xs, cb.transpose(1, 2))
         a = dist.argmin(2)                                      # [m, n]
         flat = (a + base).reshape(-1)
-        sums = torch.zeros(m * 256, dsub, device=x.device, dtype=x.dtype)
+        sums = torch.zeros(m * ksub, dsub, device=x.device, dtype=x.dtype)
         sums.index_add_(0, flat, xs.reshape(-1, dsub))
-        cnt = torch.bincount(flat, minlength=m * 256).to(x.dtype)
-        new = (sums / cnt.clamp_min(1.0)[:, None]).view(m, 256, dsub)
-        keep = (cnt == 0).view(m, 256)
+        cnt = torch.bincount(flat, minlength=m * ksub).to(x.dtype)
+        new = (sums / cnt.clamp_min(1.0)[:, None]).view(m, ksub, dsub)
+        keep = (cnt == 0).view(m, ksub)
         new[keep] = cb[keep]
         cb = new
     return cb.contiguous()
 
 
 def _encode(x, cb):
-    """Arg-min code per sub-space.  x [b, d], cb [m, 256, dsub] -> uint8 [b, m]."""
-    m, _, dsub = cb.shape
+    """Arg-min code per sub-space.  x [b, d], cb [m, ksub, dsub] -> uint8 [b, m], or
+    [b, m / 2] when ksub is 16 (two codes per byte, the even sub-quantizer in the low half)."""
+    m, ksub, dsub = cb.shape
     xs = x.view(x.shape[0], m, dsub).permute(1, 0, 2)            # [m, b, dsub]
     dist = (cb * cb).sum(2)[:, None, :] - 2.0 * torch.bmm(xs, cb.transpose(1, 2))
-    return dist.argmin(2).t().contiguous().to(torch.uint8)
+    codes = dist.argmin(2).t().contiguous().to(torch.uint8)
+    if ksub == 16:
+        codes = (codes[:, 0::2] | (codes[:, 1::2] << 4)).contiguous()
+    return codes
 
 
 def build_index(spec: WorkloadSpec, device="cpu", progress=None,
-                by_residual: bool = False) -> IvfPqIndexData:
+                by_residual: bool = False, nbits: int = 8, m: int = None) -> IvfPqIndexData:
     """Generate the database chunk by chunk, train, assign, encode, and lay the
-    codes out list by list.  Returns host (numpy) arrays."""
+    codes out list by list.  Returns host (numpy) arrays.  nbits = 4 trains 16
+    codewords per sub-quantizer and packs two codes per byte; m overrides the
+    spec's number of sub-quantizers."""
+    m = spec.m if m is None else m
+    assert nbits in (4, 8) and spec.d % m == 0 and (nbits == 8 or m % 2 == 0)
     dev = torch.device(device)
     on_gpu = dev.type == "cuda"
     say = progress if progress is not None else (lambda *_: None)
@@ -122,16 +131,16 @@ def build_index(spec: WorkloadSpec, device="cpu", progress=None,
     centroids = _kmeans(train, spec.nlist, spec.kmeans_iters, spherical,
                         spec.seed_kmeans, mm_chunk)
     n_pq = min(n_train, 65536)
-    say(f"pq train m={spec.m} on {n_pq} vectors")
+    say(f"pq train m={m} x {nbits} bits on {n_pq} vectors")
     pq_train = train[:n_pq].contiguous()
     if by_residual:
         pq_train = pq_train - centroids[_best_centroid(pq_train, centroids, spherical, mm_chunk)]
-    codebooks = _train_pq(pq_train, spec.m, spec.kmeans_iters, spec.seed_pq)
+    codebooks = _train_pq(pq_train, m, spec.kmeans_iters, spec.seed_pq, 1 << nbits)
     del pq_train
     del train
 
     assign = torch.empty(spec.n, dtype=torch.int32, device=dev)
-    codes = torch.empty(spec.n, spec.m, dtype=torch.uint8, device=dev)
+    codes = torch.empty(spec.n, m * nbits // 8, dtype=torch.uint8, device=dev)
     step = GEN_CHUNK * (4 if on_gpu else 1)
     enc_chunk = 32768 if on_gpu else 2048
     for s in range(0, spec.n, step):
@@ -151,7 +160,7 @@ def build_index(spec: WorkloadSpec, device="cpu", progress=None,
     offsets[1:] = torch.cumsum(counts, 0)
     codes = codes[order].contiguous()
     return IvfPqIndexData(
-        d=spec.d, nlist=spec.nlist, m=spec.m, metric=spec.metric,
+        d=spec.d, nlist=spec.nlist, m=m, metric=spec.metric,
         centroids=centroids.cpu().numpy(),
         codebooks=codebooks.cpu().numpy(),
         list_offsets=offsets.cpu().numpy(),
@@ -159,4 +168,5 @@ def build_index(spec: WorkloadSpec, device="cpu", progress=None,
         ids=order.cpu().numpy().astype(np.int64),
         n=spec.n,
         by_residual=by_residual,
+        nbits=nbits,
     )

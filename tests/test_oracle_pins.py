@@ -285,3 +285,68 @@ def test_hand_computed_residual_example(oracle, metric, key):
     ids, dist = oracle.scan(metric, cb, offs, codes, np.array([5], np.int64), q,
                             np.array([[1]], np.int32), 1, residual_centroids=cen)
     assert ids[0, 0] == 5 and dist[0, 0] == g[key][0]
+
+
+# ---- 4-bit codes -------------------------------------------------------------------------
+@pytest.fixture(scope="module")
+def tiny_nibble():
+    out = {}
+    for name, m, res in (("T_L2", 32, False), ("T_IP", 32, False), ("T_L2", 16, True)):
+        spec = SPECS[name]
+        ix = build_index(spec, by_residual=res, nbits=4, m=m)
+        q, _ = make_queries(spec, mixture_centers(spec))
+        out[(name, res)] = (spec, ix, q.numpy())
+    return out
+
+
+def _unpack_nibbles(codes):
+    """[n, m/2] bytes -> [n, m] codes, even sub-quantizer from the low half."""
+    out = np.empty((codes.shape[0], codes.shape[1] * 2), np.int64)
+    out[:, 0::2] = codes & 15
+    out[:, 1::2] = codes >> 4
+    return out
+
+
+@pytest.mark.parametrize("key", [("T_L2", False), ("T_IP", False), ("T_L2", True)])
+def test_nibble_pq_all_lists_equals_exhaustive_decoded_scan(oracle, tiny_nibble, key):
+    spec, ix, q = tiny_nibble[key]
+    assert ix.codebooks.shape == (ix.m, 16, ix.d // ix.m) and ix.codes.shape == (ix.n, ix.m // 2)
+    dec = ix.codebooks[np.arange(ix.m)[None, :], _unpack_nibbles(ix.codes)].reshape(ix.n, ix.d)
+    dec = dec.astype(np.float64)
+    if ix.by_residual:
+        owner = np.repeat(np.arange(ix.nlist), np.diff(ix.list_offsets))
+        dec = dec + ix.centroids[owner].astype(np.float64)
+    ids, dist, _, _, _ = oracle.search(ix, q, ix.nlist, spec.k)
+    qq = q.astype(np.float64)
+    s = ((qq[:, None, :] - dec[None]) ** 2).sum(-1) if ix.metric == L2 else qq @ dec.T
+    ref_i, ref_d = _topk_by(ix.metric, s, ix.ids, spec.k)
+    assert np.array_equal(ids, ref_i)
+    assert np.allclose(dist, ref_d, rtol=1e-12, atol=1e-12)
+
+
+@pytest.mark.parametrize("metric,key", [(L2, "nibble_l2"), (IP, "nibble_ip")])
+def test_hand_computed_nibble_example(oracle, metric, key):
+    g = _read_golden()
+    cb = np.zeros((2, 16, 1), np.float32)
+    cb[0, :, 0] = np.arange(16)
+    cb[1, :, 0] = np.arange(16) / 2.0
+    q = np.array([g["nibble_query"]], np.float32)
+    codes = np.array([[int(b)] for b in g["nibble_bytes"]], np.uint8)
+    offs = np.array([0, 2], np.int64)
+    ids, dist = oracle.scan(metric, cb, offs, codes, np.array([8, 9], np.int64), q,
+                            np.array([[0]], np.int32), 2)
+    got = {int(i): float(d) for i, d in zip(ids[0], dist[0])}
+    assert got == {8: g[key][0], 9: g[key][1]}
+
+
+def test_nibble_encoder_picks_nearest_codeword(tiny_nibble):
+    """The fixture builder's 4-bit codes are the arg-min codewords of each sub-vector."""
+    spec, ix, _ = tiny_nibble[("T_L2", False)]
+    x = database_chunk(spec, mixture_centers(spec), 0, 512).numpy()
+    pos = {int(i): p for p, i in enumerate(ix.ids)}
+    codes = _unpack_nibbles(ix.codes)
+    dsub = ix.d // ix.m
+    for i in range(0, 512, 37):
+        xs = x[i].reshape(ix.m, 1, dsub)
+        best = ((xs - ix.codebooks) ** 2).sum(-1).argmin(1)
+        assert np.array_equal(best, codes[pos[i]])
