@@ -122,6 +122,11 @@ def main():
     ap.add_argument("--slices", type=int, default=0, help="scan blocks per query (0 = auto)")
     ap.add_argument("--streams", type=int, default=1,
                     help="issue consecutive steps on this many alternating streams (1 or 2)")
+    ap.add_argument("--nbits", type=int, default=8, choices=[4, 8],
+                    help="bits per PQ code (4: two codes per byte)")
+    ap.add_argument("--m", type=int, default=0,
+                    help="PQ sub-quantizers (default: the workload's; e.g. 192 with --nbits 4 keeps "
+                         "C3's 96 bytes per vector)")
     ap.add_argument("--residual", action="store_true",
                     help="index whose PQ codes encode x - centroid (residual encoding)")
     ap.add_argument("--resident", type=float, default=1.0,
@@ -159,7 +164,8 @@ def main():
     nq = args.nq or spec.nq
 
     t0 = time.time()
-    ix = build_index(spec, device="cuda:0", progress=log, by_residual=args.residual)
+    ix = build_index(spec, device="cuda:0", progress=log, by_residual=args.residual,
+                     nbits=args.nbits, m=args.m or None)
     centers = mixture_centers(spec, dev)
     torch.cuda.synchronize()
     build_s = time.time() - t0
@@ -174,7 +180,7 @@ def main():
     calib, _ = make_queries(spec, centers, nq=4096, seed=spec.seed_calib)
 
     workload = (f"{spec.name}{' (residual-encoded)' if args.residual else ''}: "
-                f"N={spec.n} D={spec.d} nlist={spec.nlist} PQ{spec.m}x8 "
+                f"N={spec.n} D={spec.d} nlist={spec.nlist} PQ{ix.m}x{ix.nbits} "
                 f"{'IP' if spec.metric == 1 else 'L2'} nprobe={spec.nprobe} k={spec.k} "
                 f"zipf_s={spec.zipf_s}")
 
@@ -263,7 +269,7 @@ def main():
         order = np.lexsort((np.arange(nlist), -hits))                 # hottest first
         hit_cdf = np.concatenate([[0.0], np.cumsum(hits[order]) / hits.sum()])
         hit_cdf[-1] = 1.0
-        per_vec = ix.m + 8 + (4 if (ix.by_residual and ix.metric == 0) else 0)
+        per_vec = ix.m * ix.nbits // 8 + 8 + (4 if (ix.by_residual and ix.metric == 0) else 0)
         mem_index = np.concatenate([[0.0], np.cumsum(lens[order] * per_vec)])
         # sigma_max^2: variance of the per-query hit rate at the coverage where the mean is 0.5
         i_half = int(np.searchsorted(hit_cdf, 0.5))
@@ -442,7 +448,8 @@ def main():
                     "bytes_per_launch": int(r["scan_bytes_per_launch"]),
                     "avg_launch_ms": round(r["scan_ms"], 4)}
         key = (spec.name, nq, round(resident_frac, 4))
-        if key in MEASURED_TRAFFIC and args.slices == 0 and not args.residual:
+        if (key in MEASURED_TRAFFIC and args.slices == 0 and not args.residual
+                and args.nbits == 8 and not args.m):
             roofline["traffic"], roofline["traffic_source"] = MEASURED_TRAFFIC[key]
         if read_ceiling is not None:
             roofline["streaming_read_GBs"] = read_ceiling

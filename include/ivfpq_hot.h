@@ -64,7 +64,8 @@ enum {
  * Index description.  All pointers are HOST memory, borrowed until
  * ivf_index_destroy().  `codes` should be pinned for asynchronous copies.
  *
- * Supported shapes: nbits == 8; M a multiple of 16 and <= 128; d a multiple
+ * Supported shapes: nbits == 8 or 4; M * nbits / 8 (bytes per code) a multiple
+ * of 16 and <= 128, i.e. M <= 128 for 8-bit and M <= 256 for 4-bit codes; d a multiple
  * of M; nlist >= 1.  max_nq / max_nprobe / max_k size the per-batch workspace
  * (max_k <= 128, max_nprobe <= 2048).
  */
@@ -72,16 +73,18 @@ typedef struct {
   int32_t d;      /* vector dimension */
   int32_t nlist;  /* number of IVF clusters */
   int32_t M;      /* PQ sub-quantizers */
-  int32_t nbits;  /* bits per code: must be 8 */
+  int32_t nbits;  /* bits per code: 8, or 4 (short codes as used by fast-scan indexes, Section
+                     2.2): 16 codewords per sub-quantizer, two codes per byte, sub-quantizer
+                     2i in the low half of byte i */
   int32_t metric; /* IVF_METRIC_L2 or IVF_METRIC_IP (also the coarse metric) */
   int32_t max_nq;
   int32_t max_nprobe;
   int32_t max_k;
   int32_t by_residual; /* 0: codes encode the vector; 1: the vector minus its list's centroid */
   const float *centroids;      /* [nlist][d] */
-  const float *codebooks;      /* [M][256][d/M] */
+  const float *codebooks;      /* [M][2^nbits][d/M] */
   const int64_t *list_offsets; /* [nlist+1] prefix sums, in vectors */
-  const uint8_t *codes;        /* [N][M], cluster after cluster */
+  const uint8_t *codes;        /* [N][M * nbits / 8], cluster after cluster */
   const int64_t *ids;          /* [N] caller ids, same order as codes */
 } ivf_index_desc_t;
 

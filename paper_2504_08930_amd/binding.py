@@ -173,7 +173,8 @@ class IvfIndex:
                 host[key] = t.numpy()
         self._host = host
         self.by_residual = bool(getattr(data, "by_residual", False))
-        desc = IvfIndexDesc(self.d, self.nlist, self.m, 8, self.metric, max_nq, max_nprobe, max_k,
+        self.nbits = int(getattr(data, "nbits", 8))
+        desc = IvfIndexDesc(self.d, self.nlist, self.m, self.nbits, self.metric, max_nq, max_nprobe, max_k,
                             int(self.by_residual), host["centroids"].ctypes.data, host["codebooks"].ctypes.data,
                             host["list_offsets"].ctypes.data, host["codes"].ctypes.data,
                             host["ids"].ctypes.data)

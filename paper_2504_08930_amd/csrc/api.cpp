@@ -190,6 +190,8 @@ static HostIndexView host_view(const ivf_index *ix) {
   v.d = ix->sh.d;
   v.nlist = ix->sh.nlist;
   v.M = ix->sh.M;
+  v.nbits = ix->sh.nbits;
+  v.msub = ix->sh.msub;
   v.dsub = ix->sh.dsub;
   v.metric_ip = ix->sh.metric_ip;
   v.by_residual = ix->desc.by_residual;
@@ -203,14 +205,21 @@ static HostIndexView host_view(const ivf_index *ix) {
   return v;
 }
 
+// Bytes of one stored code = columns of the scan's lookup table.
+static int code_bytes(const ivf_index_desc_t &d) { return d.M * d.nbits / 8; }
+
 static int validate_desc(const ivf_index_desc_t *d) {
   if (!d) return fail(IVF_EINVAL, "desc is NULL");
-  if (d->nbits != 8) return fail(IVF_EINVAL, "nbits must be 8 (got %d)", d->nbits);
+  if (d->nbits != 8 && d->nbits != 4)
+    return fail(IVF_EINVAL, "nbits must be 8 or 4 (got %d)", d->nbits);
   if (d->metric != IVF_METRIC_L2 && d->metric != IVF_METRIC_IP)
     return fail(IVF_EINVAL, "unknown metric %d", d->metric);
   if (d->nlist < 1 || d->d < 1) return fail(IVF_EINVAL, "nlist and d must be positive");
-  if (d->M < 16 || d->M > 128 || d->M % 16 != 0)
-    return fail(IVF_EINVAL, "M must be a multiple of 16 in [16, 128] (got %d)", d->M);
+  if (d->M < 1 || d->M > 1024) return fail(IVF_EINVAL, "M out of range (got %d)", d->M);
+  const int cb = code_bytes(*d);
+  if (cb < 16 || cb > 128 || cb % 16 != 0 || cb * 8 != d->M * d->nbits)
+    return fail(IVF_EINVAL, "M * nbits / 8 must be a multiple of 16 in [16, 128] (M = %d, nbits = %d)",
+                d->M, d->nbits);
   if (d->d % d->M != 0) return fail(IVF_EINVAL, "d (%d) must be a multiple of M (%d)", d->d, d->M);
   if (d->by_residual != 0 && d->by_residual != 1)
     return fail(IVF_EINVAL, "by_residual must be 0 or 1");
@@ -231,7 +240,7 @@ static size_t plan_layout(const ivf_index_desc_t &d, int64_t resident_vectors, s
     off += bytes;
     return p;
   };
-  const size_t nl = (size_t)d.nlist, D = (size_t)d.d, M = (size_t)d.M;
+  const size_t nl = (size_t)d.nlist, D = (size_t)d.d, M = (size_t)code_bytes(d);
   const size_t nq = (size_t)d.max_nq, np = (size_t)d.max_nprobe, k = (size_t)d.max_k;
   if (staging == 0) staging = (size_t)64 << 20;
   DevLayout t;
@@ -347,8 +356,8 @@ extern "C" int ivf_index_create(const ivf_index_desc_t *desc, void *dev_arena, s
 
   ivf_index *ix = new ivf_index();
   ix->desc = *desc;
-  ix->sh = Shape{desc->d, desc->nlist, desc->M, desc->d / desc->M, desc->metric == IVF_METRIC_IP,
-                 desc->by_residual, 0.0f};
+  ix->sh = Shape{desc->d, desc->nlist, code_bytes(*desc), desc->d / desc->M,
+                 desc->metric == IVF_METRIC_IP, desc->by_residual, 0.0f, desc->nbits, desc->M};
   ix->n_total = n_total;
   ix->h_map.assign(desc->nlist, -1);
   ix->h_len.resize(desc->nlist);
@@ -372,9 +381,10 @@ extern "C" int ivf_index_create(const ivf_index_desc_t *desc, void *dev_arena, s
     delete ix;
     return fail(IVF_EINVAL, "dev_arena must be 256-byte aligned");
   }
-  if (!scan_supports(desc->M, desc->max_k)) {
+  if (!scan_supports(code_bytes(*desc), desc->max_k)) {
     delete ix;
-    return fail(IVF_EINVAL, "no scan kernel for M=%d (supported: 16, 32, 48, 64, 96, 128)", desc->M);
+    return fail(IVF_EINVAL, "no scan kernel for %d code bytes (supported: 16, 32, 48, 64, 96, 128)",
+                code_bytes(*desc));
   }
   // how many resident vectors does the arena leave room for?
   const size_t fixed = plan_layout(*desc, 0, staging_bytes, nullptr, nullptr);
@@ -384,7 +394,8 @@ extern "C" int ivf_index_create(const ivf_index_desc_t *desc, void *dev_arena, s
                 arena_bytes, fixed);
   }
   const size_t per_tile =
-      (size_t)kTileVecs * (desc->M + 8 + ((desc->by_residual && desc->metric == IVF_METRIC_L2) ? 4 : 0));
+      (size_t)kTileVecs *
+      (code_bytes(*desc) + 8 + ((desc->by_residual && desc->metric == IVF_METRIC_L2) ? 4 : 0));
   int64_t tiles = (int64_t)((arena_bytes - fixed) / per_tile);
   while (tiles > 0 &&
          plan_layout(*desc, tiles * kTileVecs, staging_bytes, nullptr, nullptr) > arena_bytes)
@@ -418,12 +429,12 @@ extern "C" int ivf_index_create(const ivf_index_desc_t *desc, void *dev_arena, s
 
   hipStream_t st = ix->own_stream;
   const DevLayout &L = ix->L;
-  const size_t D = desc->d, M = desc->M, dsub = D / M;
-  // transposed codebooks [256][M][dsub]
-  std::vector<float> cbT(256 * D);
+  const size_t D = desc->d, M = desc->M, dsub = D / M, ksub = (size_t)1 << desc->nbits;
+  // transposed codebooks [ksub][M][dsub]
+  std::vector<float> cbT(ksub * D);
   for (size_t m = 0; m < M; ++m)
-    for (size_t j = 0; j < 256; ++j)
-      memcpy(&cbT[(j * M + m) * dsub], desc->codebooks + (m * 256 + j) * dsub, dsub * 4);
+    for (size_t j = 0; j < ksub; ++j)
+      memcpy(&cbT[(j * M + m) * dsub], desc->codebooks + (m * ksub + j) * dsub, dsub * 4);
   if ((e = hipMemcpyAsync(L.centroids, desc->centroids, (size_t)desc->nlist * D * 4,
                           hipMemcpyHostToDevice, st)) != hipSuccess ||
       (e = hipMemcpyAsync(L.cbT, cbT.data(), cbT.size() * 4, hipMemcpyHostToDevice, st)) !=

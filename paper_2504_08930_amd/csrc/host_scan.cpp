@@ -54,10 +54,13 @@ float cpu_residual_pv(const HostIndexView &ix, int64_t n_total, float *pv) {
     float mx = 0.0f;
     for (int64_t v = ix.list_offsets[c]; v < ix.list_offsets[c + 1]; ++v) {
       const uint8_t *code = ix.codes + (size_t)v * ix.M;
+      const int ksub = 1 << ix.nbits;
       float acc = 0.0f;
-      for (int m = 0; m < ix.M; ++m)
-        acc = residual_pv_accumulate(acc, ix.codebooks + ((size_t)m * 256 + code[m]) * ix.dsub,
+      for (int m = 0; m < ix.msub; ++m) {
+        const int j = ix.nbits == 8 ? code[m] : (code[m >> 1] >> (4 * (m & 1))) & 15;
+        acc = residual_pv_accumulate(acc, ix.codebooks + ((size_t)m * ksub + j) * ix.dsub,
                                      cen + (size_t)m * ix.dsub, ix.dsub);
+      }
       pv[v] = acc;
       mx = std::max(mx, fabsf(acc));
     }
@@ -84,12 +87,29 @@ int cpu_build_lut(const HostIndexView &ix, const float *q, float max_bias, int32
   const int kind = ix.metric_ip ? kLutIP : (ix.by_residual ? kLutL2Res : kLutL2);
   std::vector<float> f((size_t)M * 256);
   float mx = 0.0f;
-  for (int m = 0; m < M; ++m) {
-    for (int j = 0; j < 256; ++j) {
-      float v = lut_entry(kind, q + (size_t)m * dsub,
-                          ix.codebooks + ((size_t)m * 256 + j) * dsub, dsub);
-      f[(size_t)m * 256 + j] = v;
-      mx = std::max(mx, fabsf(v));
+  if (ix.nbits == 8) {
+    for (int m = 0; m < M; ++m) {
+      for (int j = 0; j < 256; ++j) {
+        float v = lut_entry(kind, q + (size_t)m * dsub,
+                            ix.codebooks + ((size_t)m * 256 + j) * dsub, dsub);
+        f[(size_t)m * 256 + j] = v;
+        mx = std::max(mx, fabsf(v));
+      }
+    }
+  } else {
+    // 16 entries per sub-quantizer, then one 256-entry column per code byte
+    std::vector<float> t((size_t)ix.msub * 16);
+    for (int s = 0; s < ix.msub; ++s)
+      for (int j = 0; j < 16; ++j)
+        t[(size_t)s * 16 + j] = lut_entry(kind, q + (size_t)s * dsub,
+                                          ix.codebooks + ((size_t)s * 16 + j) * dsub, dsub);
+    for (int m = 0; m < M; ++m) {
+      for (int j = 0; j < 256; ++j) {
+        float v = lut_pair_entry(t[(size_t)(2 * m) * 16 + (j & 15)],
+                                 t[(size_t)(2 * m + 1) * 16 + (j >> 4)]);
+        f[(size_t)m * 256 + j] = v;
+        mx = std::max(mx, fabsf(v));
+      }
     }
   }
   const int e = lut_exponent(mx, M, max_bias, ix.pv ? ix.pv_max : 0.0f);

@@ -17,12 +17,16 @@ struct HostCand {
 };
 
 struct HostIndexView {
-  int d, nlist, M, dsub, metric_ip;
+  int d, nlist;
+  int M;                        // bytes per stored code = columns of the lookup table
+  int dsub, metric_ip;
+  int nbits = 8;                // bits per code (8, or 4: two codes per byte)
+  int msub = 0;                 // sub-quantizers (= M for 8-bit codes, 2 M for 4-bit)
   int by_residual;              // codes encode x - centroid of the list
   const float *centroids;       // [nlist][d] (residual encoding only)
   const float *pv;              // [N] per-vector term (residual-encoded L2 only), else NULL
   float pv_max;                 // largest |pv|
-  const float *codebooks;       // [M][256][dsub]
+  const float *codebooks;       // [msub][2^nbits][dsub]
   const int64_t *list_offsets;  // [nlist+1]
   const uint8_t *codes;         // [N][M]
   const int64_t *ids;           // [N]
@@ -41,7 +45,9 @@ float cpu_residual_pv(const HostIndexView &ix, int64_t n_total, float *pv);
 // 0 without residual encoding.
 float cpu_max_bias(const HostIndexView &ix, const float *q, const int32_t *clusters, int n);
 
-// Fixed-point table of one query: lut[m*256 + j]; max_bias: largest |bias| among
+// Fixed-point table of one query: lut[m*256 + j], one column per code byte (for
+// 4-bit codes entry j of column m is the float sum of the entries of the two
+// sub-quantizers packed in that byte, formed before quantization); max_bias: largest |bias| among
 // ALL of the query's probes (resident or not).  Returns the scale exponent.
 int cpu_build_lut(const HostIndexView &ix, const float *q, float max_bias, int32_t *lut);
 

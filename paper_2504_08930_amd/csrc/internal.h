@@ -46,7 +46,7 @@ struct BatchWs {
   int32_t *g_n;            // [max_nq] resident probes
   int32_t *cold;           // [max_nq][max_nprobe] non-resident cluster ids
   int32_t *n_cold;         // [max_nq]
-  float *lut;              // [max_nq][256][M]
+  float *lut;              // [max_nq][256][M], one column per code byte
   uint32_t *lutpart;       // [max_nq][kLutMaxParts] partial maxima, one slot per LUT-kernel wave
   uint32_t *lutmax;        // [max_nq] bits of the largest |entry| of the query's table
   int32_t *q_vecs;         // [max_nq] vectors in the query's resident probes
@@ -67,7 +67,7 @@ struct DevLayout {
   float *centroids;        // [nlist][d]
   float *cent_norm;        // [nlist] squared norms (L2 only)
   void *cent_parts;        // centroids as a three-way bf16 split, 6 B per element
-  float *cbT;              // [256][M][dsub] transposed codebooks
+  float *cbT;              // [2^nbits][msub][dsub] transposed codebooks
   int32_t *clus_len;       // [nlist]
   int32_t *clus_tile[3];   // mapping table ring: first tile of a resident cluster, or -1
   unsigned long long *hits;    // [nlist]
@@ -82,9 +82,13 @@ struct DevLayout {
 };
 
 struct Shape {
-  int d, nlist, M, dsub, metric_ip;
+  int d, nlist;
+  int M;             // bytes per stored code = columns of the scan's lookup table
+  int dsub, metric_ip;
   int by_residual;   // codes encode x - centroid
   float pv_max;      // largest |per-vector term| (residual-encoded L2), else 0
+  int nbits;         // bits per code: 8, or 4 (two codes per byte)
+  int msub;          // sub-quantizers: M for 8-bit codes, 2 M for 4-bit codes
   int lut_kind() const { return metric_ip ? 1 : (by_residual ? 2 : 0); }
   int scan_res() const { return by_residual ? (metric_ip ? 1 : 2) : 0; }
 };

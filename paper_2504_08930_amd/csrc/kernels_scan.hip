@@ -443,8 +443,88 @@ __global__ __launch_bounds__(256) void k_lut_max(const uint32_t *__restrict__ lu
   if (lane == 0) lutmax[q] = mx;
 }
 
+// 4-bit codes: the table the scan reads has one column per code BYTE; entry j of
+// column m is the sum of the entries of the two sub-quantizers packed in the
+// byte (sub-quantizer 2m from the low half of j, 2m+1 from the high half).  A
+// block first builds the query's msub x 16 entries in LDS (even and odd
+// sub-quantizers apart, so the second phase reads consecutive words), then its
+// waves write rows of the 256 x M sums, lanes along m.
+template <int DSUB>
+__global__ __launch_bounds__(256) void k_lut4(const float *__restrict__ queries, int d, int M,
+                                              int dsub_rt, const float *__restrict__ cbT, int kind,
+                                              int rows_per_block, float *__restrict__ lut,
+                                              uint32_t *__restrict__ lutpart) {
+  __shared__ float t_even[16 * 128];  // [j][m]: sub-quantizer 2m
+  __shared__ float t_odd[16 * 128];   //         sub-quantizer 2m + 1
+  __shared__ float qs[2048];          // the query (d <= 2048 is checked by the launcher)
+  const int dsub = DSUB > 0 ? DSUB : dsub_rt;
+  const int msub = 2 * M;
+  const int tid = threadIdx.x;
+  const int qi = blockIdx.x;
+  for (int i = tid; i < d; i += 256) qs[i] = queries[(size_t)qi * d + i];
+  __syncthreads();
+  for (int idx = tid; idx < 16 * msub; idx += 256) {
+    const int j = idx / msub, s = idx - j * msub;
+    const float *cw = cbT + ((size_t)j * msub + s) * dsub;
+    float v;
+    if (DSUB > 0) {
+      float c[DSUB > 0 ? DSUB : 1];
+#pragma unroll
+      for (int i = 0; i < DSUB; ++i) c[i] = cw[i];
+      v = lut_entry(kind, qs + s * DSUB, c, DSUB);
+    } else {
+      v = lut_entry(kind, qs + s * dsub, cw, dsub);
+    }
+    ((s & 1) ? t_odd : t_even)[j * M + (s >> 1)] = v;
+  }
+  __syncthreads();
+  const int lane = tid & 63, w = tid >> 6;
+  const int j_begin = blockIdx.y * rows_per_block;
+  float mxf = 0.0f;
+  for (int j = j_begin + w; j < j_begin + rows_per_block; j += 4) {
+    const float *lo = t_even + (j & 15) * M;
+    const float *hi = t_odd + (j >> 4) * M;
+    float *row = lut + ((size_t)qi * 256 + j) * M;
+    for (int m = lane; m < M; m += 64) {
+      const float v = lut_pair_entry(lo[m], hi[m]);
+      row[m] = v;
+      mxf = fmaxf(mxf, fabsf(v));
+    }
+  }
+  uint32_t mx = __float_as_uint(mxf);
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) mx = max(mx, (uint32_t)__shfl_xor((int)mx, o, 64));
+  if (lane == 0) lutpart[(size_t)qi * kLutMaxParts + ((blockIdx.y << 2) | w)] = mx;
+}
+
 hipError_t launch_lut(const Shape &sh, const float *q, int nq, const float *cbT, float *lut,
                       uint32_t *lutpart, uint32_t *lutmax, hipStream_t st) {
+  if (sh.nbits == 4) {
+    if (sh.d > 2048 || sh.M > 128) return hipErrorInvalidValue;
+    const int split = nq >= 512 ? 1 : (nq >= 128 ? 4 : 16);  // blocks per query
+    const dim3 grid(nq, split);
+    const int rows = 256 / split;
+#define IVF_LUT4_CASE(DS)                                                                  \
+  case DS:                                                                                 \
+    hipLaunchKernelGGL(k_lut4<DS>, grid, dim3(256), 0, st, q, sh.d, sh.M, sh.dsub, cbT,    \
+                       sh.lut_kind(), rows, lut, lutpart);                                 \
+    break;
+    switch (sh.dsub) {
+      IVF_LUT4_CASE(1)
+      IVF_LUT4_CASE(2)
+      IVF_LUT4_CASE(4)
+      IVF_LUT4_CASE(8)
+      default:
+        hipLaunchKernelGGL(k_lut4<0>, grid, dim3(256), 0, st, q, sh.d, sh.M, sh.dsub, cbT,
+                           sh.lut_kind(), rows, lut, lutpart);
+    }
+#undef IVF_LUT4_CASE
+    hipError_t e4 = hipGetLastError();
+    if (e4 != hipSuccess) return e4;
+    hipLaunchKernelGGL(k_lut_max, dim3((nq + 3) / 4), dim3(256), 0, st, lutpart, nq, split * 4,
+                       lutmax);
+    return hipGetLastError();
+  }
   const int MW = (sh.M % 32 == 0) ? 32 : 16;
   const int JL = 256 / MW;
   dim3 grid(256 / (JL * kLutJPT), sh.M / MW, (nq + kLutQTile - 1) / kLutQTile);

@@ -59,6 +59,14 @@ IVF_HD inline float lut_entry(int kind, const float *q, const float *c, int dsub
   return acc;
 }
 
+// 4-bit codes: entry of a code byte's column = sum of the entries of the two
+// sub-quantizers packed in the byte (low half first).  A plain float addition,
+// never fused with the producers of a or b, so host and device agree bit for bit.
+IVF_HD inline float lut_pair_entry(float a, float b) {
+#pragma clang fp contract(off)
+  return a + b;
+}
+
 // Scale exponent from the largest |entry| of the query's table (plus, with
 // residual encoding, the largest |bias| of the query and |pv| of the index):
 // B = M * maxabs + max_bias + max_pv = f * 2^x with f in [0.5, 1)

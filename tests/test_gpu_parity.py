@@ -29,12 +29,12 @@ def pkg():
 _CACHE = {}
 
 
-def _case(name, device="cuda", by_residual=False):
-    key = name + ("/res" if by_residual else "")
+def _case(name, device="cuda", by_residual=False, nbits=8, m=None):
+    key = name + ("/res" if by_residual else "") + (f"/{m}x{nbits}" if nbits != 8 else "")
     if key not in _CACHE:
         spec = SPECS[name]
         _say(f"building index {key} on {device}")
-        ix = build_index(spec, device=device, by_residual=by_residual)
+        ix = build_index(spec, device=device, by_residual=by_residual, nbits=nbits, m=m)
         import torch
         centers = mixture_centers(spec, torch.device(device))
         q, _ = make_queries(spec, centers)
@@ -433,4 +433,37 @@ def test_dispatcher_hybrid(pkg, oracle, name, residual):
         assert np.array_equal(ids2, ref_i) and np.array_equal(dists2, ref_d)
     n_coarse, n_amb = _check_search(oracle, ix, q, spec.nprobe, spec.k, ids, dists)
     assert n_amb <= max(1, q.shape[0] // 20)
+    index.close()
+
+
+@pytest.mark.parametrize("name,m,residual", [("T_L2", 32, False), ("T_IP", 64, False),
+                                             ("T_IP96", 192, False), ("T_IP96", 96, True),
+                                             ("T_L2", 32, True)])
+def test_four_bit_codes(pkg, oracle, name, m, residual):
+    """4-bit codes (16 codewords per sub-quantizer, two codes per byte): oracle parity,
+    exact independence of the resident set, dispatcher equality."""
+    import torch
+    spec, ix, q, calib = _case(name, by_residual=residual, nbits=4, m=m)
+    assert ix.nbits == 4 and ix.codes.shape[1] == m // 2
+    index = pkg.IvfIndex(ix, max_nq=256, max_nprobe=ix.nlist, max_k=128)
+    full = np.arange(ix.nlist, dtype=np.int32)
+    index.load_partition(full)
+    qd = torch.from_numpy(q).cuda()
+    base = None
+    for nprobe, k in ((spec.nprobe, spec.k), (ix.nlist, 100)):
+        _say(f"{name} PQ{m}x4 residual={residual} nprobe={nprobe} k={k}")
+        probe = index.coarse_probe_dev(qd, nprobe).cpu().numpy()
+        ids, dist = index.search_batch(q, nprobe, k)
+        n_coarse, n_amb = _check_search(oracle, ix, q, nprobe, k, ids, dist, probe)
+        assert n_coarse <= 1 and n_amb <= max(1, q.shape[0] // 20)
+        if base is None:
+            base = (ids, dist)
+    rng = np.random.default_rng(5)
+    for rs in (np.zeros(0, np.int32), full[1::2].copy(),
+               np.sort(rng.choice(ix.nlist, ix.nlist // 3, replace=False)).astype(np.int32)):
+        index.load_partition(rs)
+        ids, dist = index.search_batch(q, spec.nprobe, spec.k)
+        assert np.array_equal(ids, base[0]) and np.array_equal(dist, base[1])
+    ids, dist, _ = index.search_batch_async(q, spec.nprobe, spec.k).wait()
+    assert np.array_equal(ids, base[0]) and np.array_equal(dist, base[1])
     index.close()

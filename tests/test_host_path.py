@@ -74,6 +74,27 @@ def test_host_only_residual_encoding_matches_oracle(lib, oracle, name):
     index.close()
 
 
+@pytest.mark.parametrize("name,m,residual", [("T_L2", 32, False), ("T_IP", 64, False),
+                                             ("T_IP96", 96, True), ("T_L2", 32, True)])
+def test_host_only_four_bit_codes_match_oracle(lib, oracle, name, m, residual):
+    """4-bit codes: one table column per code byte, holding the sum of the two packed
+    sub-quantizers' entries."""
+    spec = SPECS[name]
+    ix = build_index(spec, by_residual=residual, nbits=4, m=m)
+    q, _ = make_queries(spec, mixture_centers(spec))
+    q = q.numpy()
+    index = lib.IvfIndex(ix, spec.nq, spec.nprobe, 64, host_only=True)
+    probe, _, _ = oracle.coarse(ix.metric, ix.centroids, q, spec.nprobe)
+    for k in (1, spec.k, 50):
+        ids, dist = index.search_batch_probes(q, probe, k)
+        ref_i, ref_d = oracle.scan(ix.metric, ix.codebooks, ix.list_offsets, ix.codes, ix.ids,
+                                   q, probe, k + 16,
+                                   residual_centroids=oracle.residual_centroids_of(ix))
+        amb = compare_topk(ids, dist, ref_i, ref_d, k, scale_S(ix.metric, q))
+        assert amb <= max(1, q.shape[0] // 20)
+    index.close()
+
+
 def test_host_only_identical_codes_tie_by_id(lib, oracle):
     rng = np.random.default_rng(3)
 
@@ -160,7 +181,8 @@ def test_desc_validation_and_arena_size(lib):
     nbytes = cdll.ivf_index_arena_bytes(ctypes.byref(ok), 10_000_000 + 64 * 16384, 0)
     # codes (96 B) + ids (8 B) per resident vector dominate; workspace adds < 1 GiB here
     assert 11_000_000 * 104 < nbytes < 11_100_000 * 104 + (1 << 30)
-    for bad in (desc(nbits=4), desc(M=24), desc(M=160), desc(d=770), desc(metric=7),
+    assert cdll.ivf_index_arena_bytes(ctypes.byref(desc(nbits=4, M=192)), 1000, 0) > 0
+    for bad in (desc(nbits=4, M=24), desc(nbits=4, M=512), desc(nbits=2), desc(M=24), desc(M=160), desc(d=770), desc(metric=7),
                 desc(max_k=1000), desc(max_nprobe=0), desc(nlist=0)):
         assert cdll.ivf_index_arena_bytes(ctypes.byref(bad), 1000, 0) == 0
 
