@@ -246,7 +246,8 @@ static size_t plan_layout(const ivf_index_desc_t &d, int64_t resident_vectors, s
   DevLayout t;
   t.centroids = (float *)take(nl * D * 4);
   t.cent_norm = (float *)take(nl * 4);
-  t.cent_parts = take(nl * D * 6);
+  t.cent_parts = take(nl * D * 4);
+  t.cent_exp = (int32_t *)take(nl * 4);
   t.cbT = (float *)take(256 * D * 4);
   t.clus_len = (int32_t *)take(nl * 4);
   for (int i = 0; i < 3; ++i) t.clus_tile[i] = (int32_t *)take(nl * 4);
@@ -254,7 +255,8 @@ static size_t plan_layout(const ivf_index_desc_t &d, int64_t resident_vectors, s
   t.qstats = (unsigned long long *)take(QS_COUNT * 8);
   for (int sl = 0; sl < kWsSlots; ++sl) {
     BatchWs &w = t.ws[sl];
-    w.q_parts = take(nq * D * 6);
+    w.q_parts = take(nq * D * 4);
+    w.q_exp = (int32_t *)take(nq * 4);
     w.queries = (float *)take(nq * D * 4);
     w.scores = (float *)take(nq * nl * 4);
     w.probe = (int32_t *)take(nq * np * 4);
@@ -451,7 +453,8 @@ extern "C" int ivf_index_create(const ivf_index_desc_t *desc, void *dev_arena, s
       (e = launch_fill_u32((uint32_t *)&L.qstats[QS_MIN_RATE_BITS], 1, 0x3f800000u, st)) !=
           hipSuccess ||
       (e = launch_cent_norms(L.centroids, desc->nlist, desc->d, L.cent_norm, st)) != hipSuccess ||
-      (e = launch_split_bf16(L.centroids, (size_t)desc->nlist, desc->d, L.cent_parts, st)) !=
+      (e = launch_split_f16(L.centroids, (size_t)desc->nlist, desc->d, L.cent_parts, L.cent_exp,
+                            st)) !=
           hipSuccess)
     return bail(e, "init kernels");
   if ((e = hipStreamSynchronize(st)) != hipSuccess) return bail(e, "hipStreamSynchronize");
@@ -1120,8 +1123,9 @@ static int enqueue_gpu(ivf_index *ix, const SearchArgs &a, const BatchCtx &c, bo
     G_TRY(hipMemcpyAsync(W.probe, ix->h_probe, (size_t)nq * np * 4, hipMemcpyHostToDevice, st));
   } else {
     G_TRY(mark(IVF_STAGE_COARSE_GEMM));
-    G_TRY(launch_split_bf16(dq, (size_t)nq, sh.d, W.q_parts, st));
-    G_TRY(launch_coarse_gemm(sh, W.q_parts, nq, L.cent_parts, L.cent_norm, W.scores, st));
+    G_TRY(launch_split_f16(dq, (size_t)nq, sh.d, W.q_parts, W.q_exp, st));
+    G_TRY(launch_coarse_gemm(sh, W.q_parts, W.q_exp, nq, L.cent_parts, L.cent_exp, L.cent_norm,
+                             W.scores, st));
     G_TRY(mark(IVF_STAGE_COARSE_SELECT));
     G_TRY(launch_coarse_select(sh, W.scores, nq, np, np, W.probe, st));
   }
@@ -1374,8 +1378,9 @@ extern "C" int ivf_coarse_probe_dev(ivf_index_t *ix, const float *queries, int64
     if (rc < 0) return rc;
   }
   const BatchWs &W = ix->L.ws[slot];
-  HIP_TRY(launch_split_bf16(queries, (size_t)nq, ix->sh.d, W.q_parts, st));
-  HIP_TRY(launch_coarse_gemm(ix->sh, W.q_parts, (int)nq, ix->L.cent_parts, ix->L.cent_norm,
+  HIP_TRY(launch_split_f16(queries, (size_t)nq, ix->sh.d, W.q_parts, W.q_exp, st));
+  HIP_TRY(launch_coarse_gemm(ix->sh, W.q_parts, W.q_exp, (int)nq, ix->L.cent_parts, ix->L.cent_exp,
+                             ix->L.cent_norm,
                              W.scores, st));
   HIP_TRY(launch_coarse_select(ix->sh, W.scores, (int)nq, nprobe, nprobe, out_probe, st));
   return IVF_OK;

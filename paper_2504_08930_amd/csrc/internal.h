@@ -36,7 +36,8 @@ struct TileDesc {
 // different streams can be in flight together (one batch's coarse stage then
 // overlaps another's scan).
 struct BatchWs {
-  void *q_parts;           // [max_nq][d] queries as a three-way bf16 split
+  void *q_parts;           // [max_nq][d] queries as a two-way fp16 split, 4 B per element
+  int32_t *q_exp;          // [max_nq] power-of-two scale of each split row
   float *queries;          // [max_nq][d]
   float *scores;           // [max_nq][nlist]
   int32_t *probe;          // [max_nq][max_nprobe]
@@ -66,7 +67,8 @@ struct BatchWs {
 struct DevLayout {
   float *centroids;        // [nlist][d]
   float *cent_norm;        // [nlist] squared norms (L2 only)
-  void *cent_parts;        // centroids as a three-way bf16 split, 6 B per element
+  void *cent_parts;        // centroids as a two-way fp16 split, 4 B per element
+  int32_t *cent_exp;       // [nlist] power-of-two scale of each split row
   float *cbT;              // [2^nbits][msub][dsub] transposed codebooks
   int32_t *clus_len;       // [nlist]
   int32_t *clus_tile[3];   // mapping table ring: first tile of a resident cluster, or -1
@@ -103,10 +105,12 @@ hipError_t launch_calib_read(const void *src, void *sink, size_t bytes, hipStrea
 
 hipError_t launch_cent_norms(const float *cent, int nlist, int d, float *out, hipStream_t st);
 
-// fp32 [rows][d] -> three-way bf16 split, 6 bytes per element
-hipError_t launch_split_bf16(const float *src, size_t rows, int d, void *dst, hipStream_t st);
+// fp32 [rows][d] -> two-way fp16 split of the rows scaled by 2^row_exp, 4 bytes per element
+hipError_t launch_split_f16(const float *src, size_t rows, int d, void *dst, int32_t *row_exp,
+                            hipStream_t st);
 
-hipError_t launch_coarse_gemm(const Shape &sh, const void *q_parts, int nq, const void *cent_parts,
+hipError_t launch_coarse_gemm(const Shape &sh, const void *q_parts, const int32_t *q_exp, int nq,
+                              const void *cent_parts, const int32_t *cent_exp,
                               const float *cent_norm, float *scores, hipStream_t st);
 
 hipError_t launch_coarse_select(const Shape &sh, const float *scores, int nq, int nprobe,

@@ -1,6 +1,6 @@
 // Stage 1 of IVF search (Section 2.2): coarse quantization.  Every query is
 // scored against every centroid as a dense contraction on the matrix cores
-// (split-bf16 MFMA at fp32 accuracy), then the nprobe best clusters per query
+// (split-fp16 MFMA at close to fp32 accuracy), then the nprobe best clusters per query
 // are selected exactly by a radix select over (score, cluster id).
 //
 // The paper keeps this stage on the CPU to avoid ping-pong between devices
@@ -38,50 +38,62 @@ hipError_t launch_cent_norms(const float *cent, int nlist, int d, float *out, hi
 }
 
 // ---------------------------------------------------------------------------
-// Three-way bf16 split of an fp32 matrix: x = h1 + h2 + h3 exactly (each part
-// is the bf16 rounding of what the previous parts left over; 3 x 8 significand
-// bits cover fp32's 24).  Output layout, chunk-major so that the K = 16 chunk
-// of a 128-row tile is one contiguous 12 KB block: for row r and group g of 8
-// consecutive k, three 16-byte units (parts 1, 2, 3) at unit index
-// ((g / 2) * rows + r) * 6 + (g % 2) * 3 + part.
+// Two-way fp16 split of an fp32 matrix.  Each row is first scaled by a power
+// of two 2^e (exact) that puts its largest magnitude in [2^8, 2^9); then
+// x * 2^e = h1 + h2 + rest with h1 = fp16(x * 2^e), h2 = fp16(x * 2^e - h1),
+// |rest| <= 2^-22 |x * 2^e| (2 x 11 significand bits of fp32's 24; entries 2^12
+// below the row maximum lose a little more to fp16's exponent range, far below
+// anything a dot product with that row can resolve).  Output layout, chunk-major
+// so that the K = 16 chunk of a row tile is one contiguous block: for row r and
+// group g of 8 consecutive k, two 16-byte units (h1, h2) at unit index
+// ((g / 2) * rows + r) * 4 + (g % 2) * 2 + part.  One wavefront per row.
 // ---------------------------------------------------------------------------
-__device__ __forceinline__ uint32_t bf16_rne_bits(float x) {
-  const uint32_t u = __float_as_uint(x);
-  return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
-}
+typedef _Float16 halfx8 __attribute__((ext_vector_type(8)));
 
-__global__ void k_split_bf16(const float *__restrict__ src, size_t rows, int groups_per_row,
-                             uint4 *__restrict__ dst) {
-  const size_t g = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (g >= rows * (size_t)groups_per_row) return;
-  const size_t row = g / groups_per_row;
-  const int gr = (int)(g % groups_per_row);
-  const size_t out = ((size_t)(gr >> 1) * rows + row) * 6 + (size_t)(gr & 1) * 3;
-  const float4 lo = reinterpret_cast<const float4 *>(src)[g * 2];
-  const float4 hi = reinterpret_cast<const float4 *>(src)[g * 2 + 1];
-  const float x[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
-  uint32_t part[3][8];
-#pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    float r = x[i];
-#pragma unroll
-    for (int p = 0; p < 3; ++p) {
-      const uint32_t h = bf16_rne_bits(r);
-      part[p][i] = h;
-      r -= __uint_as_float(h << 16);  // exact in fp32
-    }
+__global__ __launch_bounds__(256) void k_split_f16(const float *__restrict__ src, size_t rows,
+                                                   int groups_per_row, uint4 *__restrict__ dst,
+                                                   int32_t *__restrict__ row_exp) {
+  const size_t row = (size_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int lane = threadIdx.x & 63;
+  if (row >= rows) return;
+  const float4 *in = reinterpret_cast<const float4 *>(src + row * (size_t)groups_per_row * 8);
+  float mx = 0.0f;
+  for (int g = lane; g < groups_per_row; g += 64) {
+    const float4 lo = in[g * 2], hi = in[g * 2 + 1];
+    mx = fmaxf(mx, fmaxf(fmaxf(fabsf(lo.x), fabsf(lo.y)), fmaxf(fabsf(lo.z), fabsf(lo.w))));
+    mx = fmaxf(mx, fmaxf(fmaxf(fabsf(hi.x), fabsf(hi.y)), fmaxf(fabsf(hi.z), fabsf(hi.w))));
   }
 #pragma unroll
-  for (int p = 0; p < 3; ++p)
-    dst[out + p] = make_uint4(part[p][0] | (part[p][1] << 16), part[p][2] | (part[p][3] << 16),
-                                part[p][4] | (part[p][5] << 16), part[p][6] | (part[p][7] << 16));
+  for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 64));
+  int e = 0;
+  if (mx > 0.0f && mx < INFINITY) {
+    int ex;
+    (void)frexpf(mx, &ex);  // mx = f * 2^ex, f in [0.5, 1)
+    e = 9 - ex;             // mx * 2^e in [2^8, 2^9)
+  }
+  if (lane == 0) row_exp[row] = e;
+  for (int g = lane; g < groups_per_row; g += 64) {
+    const float4 lo = in[g * 2], hi = in[g * 2 + 1];
+    const float x[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+    halfx8 h1, h2;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const float v = ldexpf(x[i], e);
+      const _Float16 a = (_Float16)v;      // round to nearest even
+      h1[i] = a;
+      h2[i] = (_Float16)(v - (float)a);    // the difference is exact in fp32
+    }
+    const size_t out = ((size_t)(g >> 1) * rows + row) * 4 + (size_t)(g & 1) * 2;
+    dst[out] = __builtin_bit_cast(uint4, h1);
+    dst[out + 1] = __builtin_bit_cast(uint4, h2);
+  }
 }
 
-hipError_t launch_split_bf16(const float *src, size_t rows, int d, void *dst, hipStream_t st) {
-  const size_t n_groups = rows * (size_t)(d / 8);
-  if (n_groups == 0) return hipSuccess;
-  hipLaunchKernelGGL(k_split_bf16, dim3((unsigned)((n_groups + 255) / 256)), dim3(256), 0, st, src,
-                     rows, d / 8, (uint4 *)dst);
+hipError_t launch_split_f16(const float *src, size_t rows, int d, void *dst, int32_t *row_exp,
+                            hipStream_t st) {
+  if (rows == 0) return hipSuccess;
+  hipLaunchKernelGGL(k_split_f16, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, st, src, rows,
+                     d / 8, (uint4 *)dst, row_exp);
   return hipGetLastError();
 }
 
@@ -89,33 +101,34 @@ hipError_t launch_split_bf16(const float *src, size_t rows, int d, void *dst, hi
 // scores[q][c] = q . c            (IP, larger is better)
 //              = |c|^2 - 2 q . c  (L2, smaller is better)
 //
-// The contraction runs on the bf16 matrix cores at fp32 accuracy: with
-// q = q1+q2+q3 and c = c1+c2+c3 (three-way bf16 splits), q.c is accumulated in
-// fp32 from the six products q1c1, q1c2, q2c1, q1c3, q2c2, q3c1; the three
-// dropped products are below 2^-23 relative.  Six v_mfma_f32_32x32x16_bf16
-// cost 6/16 of the fp32 MFMA work for the same K.
+// The contraction runs on the fp16 matrix cores at close to fp32 accuracy:
+// with q 2^eq = q1 + q2 and c 2^ec = c1 + c2 (two-way fp16 splits of the scaled
+// rows), q.c 2^(eq+ec) is accumulated in fp32 from the three products q2c1,
+// q1c2, q1c1; the dropped product and the split remainders are below 2^-21
+// relative per term.  The power-of-two scales are taken out exactly in the
+// epilogue.  Three v_mfma_f32_32x32x16_f16 cost 3/16 of the fp32 MFMA work
+// for the same K.
 //
-// 128 x 128 block tile, 4 waves in a 2 x 2 arrangement, each wave 64 x 64 as
-// 2 x 2 MFMA tiles of 32 x 32; K is consumed 16 at a time through LDS (per
-// row: 2 groups x 3 parts x 16 B).  Blocks are numbered so that the row tiles
-// sharing a centroid tile run next to each other on one XCD (block id mod 8
-// picks the XCD), which keeps each centroid tile in that XCD's L2.
+// Block tile of WM x WN waves, each wave TM x TN MFMA tiles of 32 x 32; K is
+// consumed 16 at a time through LDS (per row: 2 groups x 2 parts x 16 B).
+// Blocks are numbered so that the row tiles sharing a centroid tile run next
+// to each other on one XCD (block id mod 8 picks the XCD), which keeps each
+// centroid tile in that XCD's L2.
 // ---------------------------------------------------------------------------
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-constexpr int kRowBytes = 112;  // 96 B of data per row and chunk, padded: conflict-free b128 reads
+constexpr int kRowBytes = 80;  // 64 B of data per row and chunk, padded: conflict-free b128 reads
 
-// WM x WN waves per block, each wave TM x TN MFMA tiles of 32 x 32.
 // <2,2,2,2>: 128 x 128 block, 4 waves (small batches: more blocks);
 // <4,2,2,4>: 256 x 256 block, 8 waves, 64 x 128 per wave (half the L2 traffic
-// and 25 % fewer LDS reads per MFMA, twice the MFMA work between barriers).
+// and fewer LDS reads per MFMA, twice the MFMA work between barriers).
 template <int WM, int WN, int TM, int TN>
 __global__ __launch_bounds__(WM *WN * 64) void k_coarse_gemm(
-    const uint4 *__restrict__ Qp, int nq, const uint4 *__restrict__ Cp, int nlist, int d,
+    const uint4 *__restrict__ Qp, const int32_t *__restrict__ q_exp, int nq,
+    const uint4 *__restrict__ Cp, const int32_t *__restrict__ c_exp, int nlist, int d,
     const float *__restrict__ cnorm, int metric_ip, int row_tiles, int col_tiles,
     float *__restrict__ scores) {
   constexpr int BM = WM * TM * 32, BN = WN * TN * 32, NT = WM * WN * 64;
-  constexpr int LA = BM * 6 / NT, LB = BN * 6 / NT;  // 16-byte units per thread and chunk
-  static_assert(BM * 6 % NT == 0 && BN * 6 % NT == 0, "tile loads divide evenly");
+  constexpr int LA = BM * 4 / NT, LB = BN * 4 / NT;  // 16-byte units per thread and chunk
+  static_assert(BM * 4 % NT == 0 && BN * 4 % NT == 0, "tile loads divide evenly");
   extern __shared__ __align__(16) unsigned char gsm[];
   auto a_tile = [&](int buf) { return gsm + buf * ((BM + BN) * kRowBytes); };
   auto b_tile = [&](int buf) { return gsm + buf * ((BM + BN) * kRowBytes) + BM * kRowBytes; };
@@ -130,35 +143,35 @@ __global__ __launch_bounds__(WM *WN * 64) void k_coarse_gemm(
   const int row0 = rt * BM;   // queries
   const int col0 = ct * BN;   // centroids
 
-  // global -> LDS: unit f = tid + NT * i, row = f / 6, u = f % 6; loads run one
-  // chunk ahead of the MFMAs in registers, LDS is double buffered.
-  uint4 ga[2][LA], gb[2][LB];  // two register stages: loads run two chunks ahead
+  // global -> LDS: unit f = tid + NT * i, row = f / 4, u = f % 4; loads run two
+  // chunks ahead of the MFMAs in registers, LDS is double buffered.
+  uint4 ga[2][LA], gb[2][LB];
   auto gload = [&](int kc, int slot) {
 #pragma unroll
     for (int i = 0; i < LA; ++i) {
       const int f = tid + NT * i;
-      const int r = f / 6, u = f % 6;
+      const int r = f >> 2, u = f & 3;
       const int qa = row0 + r;
-      ga[slot][i] = qa < nq ? Qp[((size_t)kc * nq + qa) * 6 + u] : make_uint4(0, 0, 0, 0);
+      ga[slot][i] = qa < nq ? Qp[((size_t)kc * nq + qa) * 4 + u] : make_uint4(0, 0, 0, 0);
     }
 #pragma unroll
     for (int i = 0; i < LB; ++i) {
       const int f = tid + NT * i;
-      const int r = f / 6, u = f % 6;
+      const int r = f >> 2, u = f & 3;
       const int cb = col0 + r;
-      gb[slot][i] = cb < nlist ? Cp[((size_t)kc * nlist + cb) * 6 + u] : make_uint4(0, 0, 0, 0);
+      gb[slot][i] = cb < nlist ? Cp[((size_t)kc * nlist + cb) * 4 + u] : make_uint4(0, 0, 0, 0);
     }
   };
   auto sstore = [&](int buf, int slot) {
 #pragma unroll
     for (int i = 0; i < LA; ++i) {
       const int f = tid + NT * i;
-      *reinterpret_cast<uint4 *>(a_tile(buf) + (f / 6) * kRowBytes + (f % 6) * 16) = ga[slot][i];
+      *reinterpret_cast<uint4 *>(a_tile(buf) + (f >> 2) * kRowBytes + (f & 3) * 16) = ga[slot][i];
     }
 #pragma unroll
     for (int i = 0; i < LB; ++i) {
       const int f = tid + NT * i;
-      *reinterpret_cast<uint4 *>(b_tile(buf) + (f / 6) * kRowBytes + (f % 6) * 16) = gb[slot][i];
+      *reinterpret_cast<uint4 *>(b_tile(buf) + (f >> 2) * kRowBytes + (f & 3) * 16) = gb[slot][i];
     }
   };
 
@@ -181,36 +194,39 @@ __global__ __launch_bounds__(WM *WN * 64) void k_coarse_gemm(
     const int buf = kc & 1;
     if (kc + 2 < nk) gload(kc + 2, slot_far);
     // lane (li, kk) holds k = 8*kk .. 8*kk+7 of the chunk for row li of a tile
-    bf16x8 a[TM][3];
+    halfx8 a[TM][2], b[TN][2];
 #pragma unroll
     for (int t = 0; t < TM; ++t)
 #pragma unroll
-      for (int p = 0; p < 3; ++p)
+      for (int p = 0; p < 2; ++p)
         a[t][p] = __builtin_bit_cast(
-            bf16x8,
+            halfx8,
             *reinterpret_cast<const uint4 *>(
-                a_tile(buf) + (wm * TM * 32 + t * 32 + li) * kRowBytes + (kk * 3 + p) * 16));
+                a_tile(buf) + (wm * TM * 32 + t * 32 + li) * kRowBytes + (kk * 2 + p) * 16));
 #pragma unroll
-    for (int nt = 0; nt < TN; ++nt) {
-      bf16x8 b[3];
+    for (int t = 0; t < TN; ++t)
 #pragma unroll
-      for (int p = 0; p < 3; ++p)
-        b[p] = __builtin_bit_cast(
-            bf16x8,
+      for (int p = 0; p < 2; ++p)
+        b[t][p] = __builtin_bit_cast(
+            halfx8,
             *reinterpret_cast<const uint4 *>(
-                b_tile(buf) + (wn * TN * 32 + nt * 32 + li) * kRowBytes + (kk * 3 + p) * 16));
+                b_tile(buf) + (wn * TN * 32 + t * 32 + li) * kRowBytes + (kk * 2 + p) * 16));
+    // small products first; consecutive MFMAs go to different accumulators
 #pragma unroll
-      for (int mt = 0; mt < TM; ++mt) {
-        floatx16 c = acc[mt][nt];
-        c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[mt][2], b[0], c, 0, 0, 0);
-        c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[mt][1], b[1], c, 0, 0, 0);
-        c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[mt][0], b[2], c, 0, 0, 0);
-        c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[mt][1], b[0], c, 0, 0, 0);
-        c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[mt][0], b[1], c, 0, 0, 0);
-        c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[mt][0], b[0], c, 0, 0, 0);
-        acc[mt][nt] = c;
-      }
-    }
+    for (int mt = 0; mt < TM; ++mt)
+#pragma unroll
+      for (int nt = 0; nt < TN; ++nt)
+        acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[mt][1], b[nt][0], acc[mt][nt], 0, 0, 0);
+#pragma unroll
+    for (int mt = 0; mt < TM; ++mt)
+#pragma unroll
+      for (int nt = 0; nt < TN; ++nt)
+        acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[mt][0], b[nt][1], acc[mt][nt], 0, 0, 0);
+#pragma unroll
+    for (int mt = 0; mt < TM; ++mt)
+#pragma unroll
+      for (int nt = 0; nt < TN; ++nt)
+        acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[mt][0], b[nt][0], acc[mt][nt], 0, 0, 0);
     if (kc + 1 < nk) sstore(buf ^ 1, slot_next);
     __syncthreads();
   };
@@ -226,11 +242,12 @@ __global__ __launch_bounds__(WM *WN * 64) void k_coarse_gemm(
     for (int nt = 0; nt < TN; ++nt) {
       const int c = col0 + wn * TN * 32 + nt * 32 + li;
       const float cn = (!metric_ip && c < nlist) ? cnorm[c] : 0.0f;
+      const int ce = c < nlist ? c_exp[c] : 0;
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int qi = row0 + wm * TM * 32 + mt * 32 + 8 * (r >> 2) + 4 * kk + (r & 3);
         if (qi < nq && c < nlist) {
-          const float dot = acc[mt][nt][r];
+          const float dot = ldexpf(acc[mt][nt][r], -(ce + q_exp[qi]));
           scores[(size_t)qi * nlist + c] = metric_ip ? dot : __builtin_fmaf(-2.0f, dot, cn);
         }
       }
@@ -238,9 +255,9 @@ __global__ __launch_bounds__(WM *WN * 64) void k_coarse_gemm(
 }
 
 template <int WM, int WN, int TM, int TN>
-static hipError_t launch_gemm_t(const Shape &sh, const void *q_parts, int nq,
-                                const void *cent_parts, const float *cent_norm, float *scores,
-                                hipStream_t st) {
+static hipError_t launch_gemm_t(const Shape &sh, const void *q_parts, const int32_t *q_exp, int nq,
+                                const void *cent_parts, const int32_t *cent_exp,
+                                const float *cent_norm, float *scores, hipStream_t st) {
   constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
   const size_t lds = (size_t)2 * (BM + BN) * kRowBytes;
   static bool attr_done = false;
@@ -255,18 +272,21 @@ static hipError_t launch_gemm_t(const Shape &sh, const void *q_parts, int nq,
   const int col_tiles = (sh.nlist + BN - 1) / BN;
   const int grid = 8 * ((col_tiles + 7) / 8) * row_tiles;
   hipLaunchKernelGGL((k_coarse_gemm<WM, WN, TM, TN>), dim3(grid), dim3(WM * WN * 64), lds, st,
-                     (const uint4 *)q_parts, nq, (const uint4 *)cent_parts, sh.nlist, sh.d,
-                     cent_norm, sh.metric_ip, row_tiles, col_tiles, scores);
+                     (const uint4 *)q_parts, q_exp, nq, (const uint4 *)cent_parts, cent_exp, sh.nlist,
+                     sh.d, cent_norm, sh.metric_ip, row_tiles, col_tiles, scores);
   return hipGetLastError();
 }
 
-hipError_t launch_coarse_gemm(const Shape &sh, const void *q_parts, int nq, const void *cent_parts,
+hipError_t launch_coarse_gemm(const Shape &sh, const void *q_parts, const int32_t *q_exp, int nq,
+                              const void *cent_parts, const int32_t *cent_exp,
                               const float *cent_norm, float *scores, hipStream_t st) {
   // big tiles once they still give every CU a block
   const long long big_blocks = (long long)((nq + 255) / 256) * ((sh.nlist + 255) / 256);
   if (big_blocks >= 192)
-    return launch_gemm_t<4, 2, 2, 4>(sh, q_parts, nq, cent_parts, cent_norm, scores, st);
-  return launch_gemm_t<2, 2, 2, 2>(sh, q_parts, nq, cent_parts, cent_norm, scores, st);
+    return launch_gemm_t<4, 2, 2, 4>(sh, q_parts, q_exp, nq, cent_parts, cent_exp, cent_norm,
+                                     scores, st);
+  return launch_gemm_t<2, 2, 2, 2>(sh, q_parts, q_exp, nq, cent_parts, cent_exp, cent_norm, scores,
+                                   st);
 }
 
 // ---------------------------------------------------------------------------
