@@ -309,20 +309,53 @@ __device__ __forceinline__ unsigned long long sel_key(float s, int metric_ip, in
   return ((unsigned long long)score_bits(s, metric_ip) << 32) | (unsigned)c;
 }
 
+// PER > 0: the query's row of scores is read once and held in registers (PER per
+// thread, nlist <= PER * kSelThreads); PER == 0: every pass re-reads the row.
+//
+// Fast path: one histogram over 2048 equal-width bins of the score range
+// [best, worst] of the row.  Binning is monotone in the score, so every cluster
+// in a bin before the one that contains rank `keep` beats every cluster after
+// it; all clusters up to and including that bin are collected (a few more than
+// `keep`) and sorted exactly by (score bits, id).  If that set does not fit the
+// `cap` LDS slots (heavy ties, a degenerate range, non-finite scores), the exact
+// MSB-first radix select over the 64-bit keys below does the work instead.
+template <int PER>
 __global__ __launch_bounds__(kSelThreads) void k_coarse_select(const float *__restrict__ scores,
                                                                int nlist, int metric_ip, int keep,
-                                                               int nprobe, int stride, int n2,
+                                                               int nprobe, int stride, int cap,
                                                                int32_t *__restrict__ probe) {
   __shared__ unsigned int hist[kSelBins];
   __shared__ unsigned int wsum[kSelThreads / 64];
+  __shared__ float wmin[kSelThreads / 64], wmax[kSelThreads / 64];
   __shared__ unsigned long long s_prefix, s_mask;
-  __shared__ unsigned int s_need, s_done, s_count;
-  extern __shared__ unsigned long long sel[];  // n2 entries
+  __shared__ unsigned int s_need, s_done, s_count, s_bin, s_total;
+  extern __shared__ unsigned long long sel[];  // cap entries
   const int q = blockIdx.x;
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
   const float *row = scores + (size_t)q * nlist;
   int32_t *out = probe + (size_t)q * stride;
+
+  float sc[PER > 0 ? PER : 1];
+  if (PER > 0) {
+#pragma unroll
+    for (int i = 0; i < PER; ++i) {
+      const int c = tid + i * kSelThreads;
+      sc[i] = c < nlist ? row[c] : 0.0f;
+    }
+  }
+  // body(score, cluster) for every cluster of the row this thread owns
+  auto visit = [&](auto body) {
+    if (PER > 0) {
+#pragma unroll
+      for (int i = 0; i < PER; ++i) {
+        const int c = tid + i * kSelThreads;
+        if (c < nlist) body(sc[i], c);
+      }
+    } else {
+      for (int c = tid; c < nlist; c += kSelThreads) body(row[c], c);
+    }
+  };
 
   if (tid == 0) {
     s_prefix = 0ull;
@@ -330,27 +363,47 @@ __global__ __launch_bounds__(kSelThreads) void k_coarse_select(const float *__re
     s_need = (unsigned)keep;
     s_done = 0u;
     s_count = 0u;
+    s_bin = 0xffffffffu;
+    s_total = 0u;
   }
-  unsigned long long thr = ~0ull;
-  if (keep < nlist) {
-    // digits of the 64-bit key, most significant first: (shift, bits)
-    const int shifts[6] = {53, 42, 32, 21, 10, 0};
-    const int widths[6] = {11, 11, 10, 11, 11, 10};
-    for (int pass = 0; pass < 6; ++pass) {
-      const int shift = shifts[pass];
-      const unsigned dmask = (1u << widths[pass]) - 1u;
 #pragma unroll
-      for (int b = 0; b < kSelBinsPerThread; ++b) hist[tid * kSelBinsPerThread + b] = 0u;
+  for (int b = 0; b < kSelBinsPerThread; ++b) hist[tid * kSelBinsPerThread + b] = 0u;
+
+  // ---- fast path ----
+  bool fast_ok = false;
+  if (keep < nlist) {
+    // v = score (L2) or -score (IP): smaller is better
+    float vmin = INFINITY, vmax = -INFINITY;
+    visit([&](float s0, int) {
+      const float v = metric_ip ? -s0 : s0;
+      vmin = fminf(vmin, v);
+      vmax = fmaxf(vmax, v);
+    });
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+      vmin = fminf(vmin, __shfl_xor(vmin, o, 64));
+      vmax = fmaxf(vmax, __shfl_xor(vmax, o, 64));
+    }
+    if (lane == 0) {
+      wmin[wave] = vmin;
+      wmax[wave] = vmax;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int w2 = 0; w2 < kSelThreads / 64; ++w2) {
+      vmin = fminf(vmin, wmin[w2]);
+      vmax = fmaxf(vmax, wmax[w2]);
+    }
+    const float scale = (float)(kSelBins - 1) / (vmax - vmin);
+    const bool usable = scale > 0.0f && scale < INFINITY;  // block-uniform
+    if (usable) {
+      auto bin_of = [&](float s0) -> unsigned {
+        const float v = metric_ip ? -s0 : s0;
+        const unsigned b = (unsigned)(int)((v - vmin) * scale);
+        return b < (unsigned)kSelBins ? b : (unsigned)(kSelBins - 1);
+      };
+      visit([&](float s0, int) { atomicAdd(&hist[bin_of(s0)], 1u); });
       __syncthreads();
-      const unsigned long long prefix = s_prefix, mask = s_mask;
-      const unsigned need = s_need;
-      if (s_done) break;
-      for (int c = tid; c < nlist; c += kSelThreads) {
-        const unsigned long long key = sel_key(row[c], metric_ip, c);
-        if ((key & mask) == prefix) atomicAdd(&hist[(unsigned)(key >> shift) & dmask], 1u);
-      }
-      __syncthreads();
-      // block-wide exclusive scan of per-thread bin sums
       unsigned loc[kSelBinsPerThread], tsum = 0;
 #pragma unroll
       for (int b = 0; b < kSelBinsPerThread; ++b) {
@@ -367,63 +420,141 @@ __global__ __launch_bounds__(kSelThreads) void k_coarse_select(const float *__re
       __syncthreads();
       unsigned before = incl - tsum;
       for (int w2 = 0; w2 < wave; ++w2) before += wsum[w2];
-      // the thread whose bins straddle rank `need` publishes the bucket
-      if (before < need && need <= before + tsum) {
+      if (before < (unsigned)keep && (unsigned)keep <= before + tsum) {
         unsigned cum = before;
         int b = 0;
         for (; b < kSelBinsPerThread - 1; ++b) {
-          if (cum + loc[b] >= need) break;
+          if (cum + loc[b] >= (unsigned)keep) break;
           cum += loc[b];
         }
-        const unsigned bucket = (unsigned)(tid * kSelBinsPerThread + b);
-        s_need = need - cum;
-        s_prefix = prefix | ((unsigned long long)bucket << shift);
-        s_mask = mask | ((unsigned long long)dmask << shift);
-        if (loc[b] == need - cum || pass == 5) s_done = 1u;  // whole bucket is selected
+        s_bin = (unsigned)(tid * kSelBinsPerThread + b);
+        s_total = cum + loc[b];  // clusters in bins up to and including this one
       }
       __syncthreads();
+      const unsigned tbin = s_bin, total = s_total;
+      if (total >= (unsigned)keep && total <= (unsigned)cap) {  // block-uniform
+        fast_ok = true;
+        for (int i = tid; i < cap; i += kSelThreads) sel[i] = ~0ull;
+        __syncthreads();
+        visit([&](float s0, int c) {
+          if (bin_of(s0) <= tbin) {
+            const unsigned slot = atomicAdd(&s_count, 1u);
+            if (slot < (unsigned)cap) sel[slot] = sel_key(s0, metric_ip, c);
+          }
+        });
+      }
     }
+  }
+
+  if (!fast_ok) {
+    unsigned long long thr = ~0ull;
+    if (keep < nlist) {
+      // digits of the 64-bit key, most significant first: (shift, bits)
+      const int shifts[6] = {53, 42, 32, 21, 10, 0};
+      const int widths[6] = {11, 11, 10, 11, 11, 10};
+      for (int pass = 0; pass < 6; ++pass) {
+        const int shift = shifts[pass];
+        const unsigned dmask = (1u << widths[pass]) - 1u;
+#pragma unroll
+        for (int b = 0; b < kSelBinsPerThread; ++b) hist[tid * kSelBinsPerThread + b] = 0u;
+        __syncthreads();
+        const unsigned long long prefix = s_prefix, mask = s_mask;
+        const unsigned need = s_need;
+        if (s_done) break;
+        visit([&](float s0, int c) {
+          const unsigned long long key = sel_key(s0, metric_ip, c);
+          if ((key & mask) == prefix) atomicAdd(&hist[(unsigned)(key >> shift) & dmask], 1u);
+        });
+        __syncthreads();
+        // block-wide exclusive scan of per-thread bin sums
+        unsigned loc[kSelBinsPerThread], tsum = 0;
+#pragma unroll
+        for (int b = 0; b < kSelBinsPerThread; ++b) {
+          loc[b] = hist[tid * kSelBinsPerThread + b];
+          tsum += loc[b];
+        }
+        unsigned incl = tsum;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+          const unsigned v = __shfl_up(incl, o, 64);
+          if (lane >= o) incl += v;
+        }
+        if (lane == 63) wsum[wave] = incl;
+        __syncthreads();
+        unsigned before = incl - tsum;
+        for (int w2 = 0; w2 < wave; ++w2) before += wsum[w2];
+        // the thread whose bins straddle rank `need` publishes the bucket
+        if (before < need && need <= before + tsum) {
+          unsigned cum = before;
+          int b = 0;
+          for (; b < kSelBinsPerThread - 1; ++b) {
+            if (cum + loc[b] >= need) break;
+            cum += loc[b];
+          }
+          const unsigned bucket = (unsigned)(tid * kSelBinsPerThread + b);
+          s_need = need - cum;
+          s_prefix = prefix | ((unsigned long long)bucket << shift);
+          s_mask = mask | ((unsigned long long)dmask << shift);
+          if (loc[b] == need - cum || pass == 5) s_done = 1u;  // whole bucket is selected
+        }
+        __syncthreads();
+      }
+      __syncthreads();
+      // threshold: prefix with all undecided low bits set
+      thr = s_prefix | ~s_mask;
+    }
+    for (int i = tid; i < cap; i += kSelThreads) sel[i] = ~0ull;
     __syncthreads();
-    // threshold: prefix with all undecided low bits set
-    thr = s_prefix | ~s_mask;
-  }
-  for (int i = tid; i < n2; i += kSelThreads) sel[i] = ~0ull;
-  __syncthreads();
-  for (int c = tid; c < nlist; c += kSelThreads) {
-    const unsigned long long key = sel_key(row[c], metric_ip, c);
-    if (key <= thr) {
-      const unsigned slot = atomicAdd(&s_count, 1u);
-      if (slot < (unsigned)n2) sel[slot] = key;
-    }
+    visit([&](float s0, int c) {
+      const unsigned long long key = sel_key(s0, metric_ip, c);
+      if (key <= thr) {
+        const unsigned slot = atomicAdd(&s_count, 1u);
+        if (slot < (unsigned)cap) sel[slot] = key;
+      }
+    });
+    __syncthreads();
   }
   __syncthreads();
-  for (int size = 2; size <= n2; size <<= 1) {
-    for (int st = size >> 1; st > 0; st >>= 1) {
-      for (int i = tid; i < n2; i += kSelThreads) {
-        const int j = i ^ st;
-        if (j > i) {
-          const bool asc = (i & size) == 0;
-          const unsigned long long a = sel[i], b = sel[j];
-          if ((b < a) == asc) {
-            sel[i] = b;
-            sel[j] = a;
+  // ---- exact order of the collected candidates: one wavefront, bitonic in LDS ----
+  if (wave == 0) {
+    int n2 = 2;
+    const int filled = (int)min(s_count, (unsigned)cap);
+    while (n2 < filled) n2 <<= 1;
+    for (int size = 2; size <= n2; size <<= 1) {
+      for (int st = size >> 1; st > 0; st >>= 1) {
+        for (int i = lane; i < n2; i += 64) {
+          const int j = i ^ st;
+          if (j > i) {
+            const bool asc = (i & size) == 0;
+            const unsigned long long a = sel[i], b = sel[j];
+            if ((b < a) == asc) {
+              sel[i] = b;
+              sel[j] = a;
+            }
           }
         }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
       }
-      __syncthreads();
     }
+    for (int p = lane; p < nprobe; p += 64)
+      out[p] = p < keep ? (int32_t)(sel[p] & 0xffffffffull) : -1;
   }
-  for (int p = tid; p < nprobe; p += kSelThreads)
-    out[p] = p < keep ? (int32_t)(sel[p] & 0xffffffffull) : -1;
 }
 
 hipError_t launch_coarse_select(const Shape &sh, const float *scores, int nq, int nprobe,
                                 int probe_stride, int32_t *probe, hipStream_t st) {
   const int keep = nprobe < sh.nlist ? nprobe : sh.nlist;
-  int n2 = 2;
-  while (n2 < keep) n2 <<= 1;
-  hipLaunchKernelGGL(k_coarse_select, dim3(nq), dim3(kSelThreads), (size_t)n2 * 8, st, scores,
-                     sh.nlist, sh.metric_ip, keep, nprobe, probe_stride, n2, probe);
+  int cap = 128;  // LDS slots for collected candidates: a power of two >= 2 * keep
+  while (cap < 2 * keep) cap <<= 1;
+#define IVF_SEL_LAUNCH(PER)                                                                  \
+  hipLaunchKernelGGL(k_coarse_select<PER>, dim3(nq), dim3(kSelThreads), (size_t)cap * 8, st, \
+                     scores, sh.nlist, sh.metric_ip, keep, nprobe, probe_stride, cap, probe)
+  if (sh.nlist <= 8 * kSelThreads) IVF_SEL_LAUNCH(8);
+  else if (sh.nlist <= 32 * kSelThreads) IVF_SEL_LAUNCH(32);
+  else IVF_SEL_LAUNCH(0);
+#undef IVF_SEL_LAUNCH
   return hipGetLastError();
 }
 
