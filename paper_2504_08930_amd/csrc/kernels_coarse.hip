@@ -301,7 +301,7 @@ __device__ __forceinline__ uint32_t score_bits(float s, int metric_ip) {
   return metric_ip ? ~u : u;                        // IP: larger score first
 }
 
-constexpr int kSelThreads = 512;
+constexpr int kSelThreads = 1024;
 constexpr int kSelBins = 2048;  // 11-bit digits
 constexpr int kSelBinsPerThread = kSelBins / kSelThreads;
 
@@ -551,8 +551,8 @@ hipError_t launch_coarse_select(const Shape &sh, const float *scores, int nq, in
 #define IVF_SEL_LAUNCH(PER)                                                                  \
   hipLaunchKernelGGL(k_coarse_select<PER>, dim3(nq), dim3(kSelThreads), (size_t)cap * 8, st, \
                      scores, sh.nlist, sh.metric_ip, keep, nprobe, probe_stride, cap, probe)
-  if (sh.nlist <= 8 * kSelThreads) IVF_SEL_LAUNCH(8);
-  else if (sh.nlist <= 32 * kSelThreads) IVF_SEL_LAUNCH(32);
+  if (sh.nlist <= 4 * kSelThreads) IVF_SEL_LAUNCH(4);
+  else if (sh.nlist <= 16 * kSelThreads) IVF_SEL_LAUNCH(16);
   else IVF_SEL_LAUNCH(0);
 #undef IVF_SEL_LAUNCH
   return hipGetLastError();
