@@ -1133,7 +1133,7 @@ static int enqueue_gpu(ivf_index *ix, const SearchArgs &a, const BatchCtx &c, bo
   G_TRY(mark(IVF_STAGE_ROUTE));
   if (sh.by_residual)
     G_TRY(launch_bias(sh, dq, nq, W.probe, np, np, L.centroids, W.bias, st));
-  G_TRY(launch_route(W.probe, nq, np, np, L.clus_tile[c.buf], L.clus_len, sh.M, W.g_base, W.g_len,
+  G_TRY(launch_route(W.probe, nq, np, np, sh.nlist, L.clus_tile[c.buf], L.clus_len, sh.M, W.g_base, W.g_len,
                      W.g_prefix, W.g_n, W.cold, W.n_cold, W.q_vecs,
                      sh.by_residual ? W.bias : nullptr, W.g_bias, W.qbmax, L.hits, L.qstats, 1,
                      st));

@@ -121,7 +121,7 @@ hipError_t launch_bias(const Shape &sh, const float *q, int nq, const int32_t *p
                        int probe_stride, const float *centroids, float *bias, hipStream_t st);
 
 // bias may be NULL (no residual encoding): g_bias is then untouched and qbmax set to 0.
-hipError_t launch_route(const int32_t *probe, int nq, int nprobe, int probe_stride,
+hipError_t launch_route(const int32_t *probe, int nq, int nprobe, int probe_stride, int nlist,
                         const int32_t *clus_tile, const int32_t *clus_len, int M, int32_t *g_base,
                         int32_t *g_len, int32_t *g_prefix, int32_t *g_n, int32_t *cold,
                         int32_t *n_cold, int32_t *q_vecs, const float *bias, float *g_bias,

@@ -180,13 +180,42 @@ __global__ __launch_bounds__(256) void k_route(
     const int32_t *__restrict__ clus_tile, const int32_t *__restrict__ clus_len, int M,
     int32_t *g_base, int32_t *g_len, int32_t *g_prefix, int32_t *g_n, int32_t *cold,
     int32_t *n_cold, int32_t *q_vecs, const float *__restrict__ bias, float *g_bias, float *qbmax,
-    unsigned long long *hits, int count_stats) {
-  // one wavefront per query, one lane per probe (64 probes per step); the GPU
-  // work list keeps probe order
+    unsigned long long *hits, int count_stats, int n2) {
+  // One wavefront per query, one lane per probe (64 probes per step).  The
+  // probes are first put in cluster-id order (n2 > 0: a bitonic sort of
+  // (id, rank) words in LDS), so that the work lists of queries that share
+  // lists name them in the same order: such queries, scheduled side by side,
+  // then stream the same tiles at about the same time and share them in L2.
+  // The result of a query does not depend on the order of its lists.
+  extern __shared__ int32_t route_sort[];
   const int q = blockIdx.x * 4 + (threadIdx.x >> 6);
   const int lane = threadIdx.x & 63;
   if (q >= nq) return;
   const int32_t *pr = probe + (size_t)q * stride;
+  int32_t *srt = route_sort + (threadIdx.x >> 6) * n2;
+  if (n2 > 0) {
+    for (int p = lane; p < n2; p += 64) {
+      const int c = p < nprobe ? pr[p] : -1;
+      srt[p] = c >= 0 ? ((c << 11) | p) : 0x7fffffff;
+    }
+    wave_sync();
+    for (int size = 2; size <= n2; size <<= 1) {
+      for (int st = size >> 1; st > 0; st >>= 1) {
+        for (int i = lane; i < n2; i += 64) {
+          const int j = i ^ st;
+          if (j > i) {
+            const bool asc = (i & size) == 0;
+            const int a = srt[i], b = srt[j];
+            if ((b < a) == asc) {
+              srt[i] = b;
+              srt[j] = a;
+            }
+          }
+        }
+        wave_sync();
+      }
+    }
+  }
   int32_t *gb = g_base + (size_t)q * stride;
   int32_t *gl = g_len + (size_t)q * stride;
   int32_t *gp = g_prefix + (size_t)q * (stride + 1);
@@ -196,8 +225,13 @@ __global__ __launch_bounds__(256) void k_route(
   unsigned long long vecs = 0;
   float bmax = 0.0f;
   for (int base = 0; base < nprobe; base += 64) {
-    const int p = base + lane;
-    const int c = p < nprobe ? pr[p] : -1;
+    int p = base + lane;
+    int c = p < nprobe ? pr[p] : -1;
+    if (n2 > 0) {  // take the probes in cluster-id order; p = rank of the probe
+      const int w = p < nprobe ? srt[p] : 0x7fffffff;
+      c = w != 0x7fffffff ? (w >> 11) : -1;
+      p = w & 2047;
+    }
     const bool valid = c >= 0;
     int t = -1, len = 0;
     float b = 0.0f;
@@ -352,15 +386,22 @@ hipError_t launch_order(const int32_t *probe, int nq, int probe_stride, int32_t 
   return hipGetLastError();
 }
 
-hipError_t launch_route(const int32_t *probe, int nq, int nprobe, int probe_stride,
+hipError_t launch_route(const int32_t *probe, int nq, int nprobe, int probe_stride, int nlist,
                         const int32_t *clus_tile, const int32_t *clus_len, int M, int32_t *g_base,
                         int32_t *g_len, int32_t *g_prefix, int32_t *g_n, int32_t *cold,
                         int32_t *n_cold, int32_t *q_vecs, const float *bias, float *g_bias,
                         float *qbmax, unsigned long long *hits, unsigned long long *qstats,
                         int count_stats, hipStream_t st) {
-  hipLaunchKernelGGL(k_route, dim3((nq + 3) / 4), dim3(256), 0, st, probe, nq, nprobe,
-                     probe_stride, clus_tile, clus_len, M, g_base, g_len, g_prefix, g_n, cold,
-                     n_cold, q_vecs, bias, g_bias, qbmax, hits, count_stats);
+  // (id << 11 | rank) must fit a positive int: nprobe <= 2048 holds, ids need < 2^20
+  int n2 = 0;
+  if (nlist < (1 << 20)) {
+    n2 = 64;
+    while (n2 < nprobe) n2 <<= 1;
+  }
+  hipLaunchKernelGGL(k_route, dim3((nq + 3) / 4), dim3(256), (size_t)4 * n2 * sizeof(int32_t), st,
+                     probe, nq, nprobe, probe_stride, clus_tile, clus_len, M, g_base, g_len,
+                     g_prefix, g_n, cold, n_cold, q_vecs, bias, g_bias, qbmax, hits, count_stats,
+                     n2);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(k_route_stats, dim3(1), dim3(1024), 0, st, g_n, n_cold, q_vecs, nq, M, qstats,
