@@ -246,7 +246,7 @@ static size_t plan_layout(const ivf_index_desc_t &d, int64_t resident_vectors, s
   DevLayout t;
   t.centroids = (float *)take(nl * D * 4);
   t.cent_norm = (float *)take(nl * 4);
-  t.cent_parts = take(nl * D * 4);
+  t.cent_parts = take(nl * D * 4 + kSplitPadBytes);
   t.cent_exp = (int32_t *)take(nl * 4);
   t.cbT = (float *)take(256 * D * 4);
   t.clus_len = (int32_t *)take(nl * 4);
@@ -255,7 +255,7 @@ static size_t plan_layout(const ivf_index_desc_t &d, int64_t resident_vectors, s
   t.qstats = (unsigned long long *)take(QS_COUNT * 8);
   for (int sl = 0; sl < kWsSlots; ++sl) {
     BatchWs &w = t.ws[sl];
-    w.q_parts = take(nq * D * 4);
+    w.q_parts = take(nq * D * 4 + kSplitPadBytes);
     w.q_exp = (int32_t *)take(nq * 4);
     w.queries = (float *)take(nq * D * 4);
     w.scores = (float *)take(nq * nl * 4);

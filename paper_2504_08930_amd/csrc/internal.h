@@ -12,6 +12,7 @@ constexpr int kMaxSlices = 8;      // scan blocks per query, upper bound
 constexpr int kMaxK = 128;
 constexpr int kMaxNprobe = 2048;
 constexpr int kLutMaxParts = 512;
+constexpr int kSplitPadBytes = 16384;  // tail padding of the split-fp16 operand arrays
 constexpr int kWsSlots = 2;        // batches that may be in flight on different streams  // per-query slots for partial table maxima
 
 // Counters kept on the device next to the per-cluster hit counters.

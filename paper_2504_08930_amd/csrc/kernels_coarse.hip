@@ -115,6 +115,7 @@ hipError_t launch_split_f16(const float *src, size_t rows, int d, void *dst, int
 // to each other on one XCD (block id mod 8 picks the XCD), which keeps each
 // centroid tile in that XCD's L2.
 // ---------------------------------------------------------------------------
+static_assert(kSplitPadBytes >= 256 * 64, "padding covers one row tile of the last chunk");
 constexpr int kRowBytes = 80;  // 64 B of data per row and chunk, padded: conflict-free b128 reads
 
 // <2,2,2,2>: 128 x 128 block, 4 waves (small batches: more blocks);
@@ -144,36 +145,40 @@ __global__ __launch_bounds__(WM *WN * 64) void k_coarse_gemm(
   const int col0 = ct * BN;   // centroids
 
   // global -> LDS: unit f = tid + NT * i, row = f / 4, u = f % 4; loads run two
-  // chunks ahead of the MFMAs in registers, LDS is double buffered.
-  uint4 ga[2][LA], gb[2][LB];
-  auto gload = [&](int kc, int slot) {
+  // chunks ahead of the MFMAs in registers, LDS is double buffered.  The loads
+  // carry no bounds check (straight-line code lets the compiler wait for exactly
+  // the older of the two stages): rows of a tile beyond the matrix read the
+  // following chunk or, for the last chunk, the kSplitPadBytes of padding that
+  // both operand arrays carry; whatever they hold only reaches rows and columns
+  // of the product that the epilogue never stores.
+  // Two register stages.  Each is named in the code that touches it (no stage
+  // index, no reference passed around), so both stay in registers.
+  typedef unsigned uintx4 __attribute__((ext_vector_type(4)));
+  uintx4 ga0[LA], gb0[LB], ga1[LA], gb1[LB];
+  // per-thread unit offsets inside a chunk (32-bit), added to a uniform chunk base
+  unsigned offa[LA], offb[LB];
 #pragma unroll
-    for (int i = 0; i < LA; ++i) {
-      const int f = tid + NT * i;
-      const int r = f >> 2, u = f & 3;
-      const int qa = row0 + r;
-      ga[slot][i] = qa < nq ? Qp[((size_t)kc * nq + qa) * 4 + u] : make_uint4(0, 0, 0, 0);
-    }
+  for (int i = 0; i < LA; ++i) offa[i] = (unsigned)(row0 * 4 + tid + NT * i);
 #pragma unroll
-    for (int i = 0; i < LB; ++i) {
-      const int f = tid + NT * i;
-      const int r = f >> 2, u = f & 3;
-      const int cb = col0 + r;
-      gb[slot][i] = cb < nlist ? Cp[((size_t)kc * nlist + cb) * 4 + u] : make_uint4(0, 0, 0, 0);
-    }
-  };
-  auto sstore = [&](int buf, int slot) {
-#pragma unroll
-    for (int i = 0; i < LA; ++i) {
-      const int f = tid + NT * i;
-      *reinterpret_cast<uint4 *>(a_tile(buf) + (f >> 2) * kRowBytes + (f & 3) * 16) = ga[slot][i];
-    }
-#pragma unroll
-    for (int i = 0; i < LB; ++i) {
-      const int f = tid + NT * i;
-      *reinterpret_cast<uint4 *>(b_tile(buf) + (f >> 2) * kRowBytes + (f & 3) * 16) = gb[slot][i];
-    }
-  };
+  for (int i = 0; i < LB; ++i) offb[i] = (unsigned)(col0 * 4 + tid + NT * i);
+#define IVF_GLOAD(kc, GA, GB)                                       \
+  do {                                                              \
+    const uintx4 *qb_ = reinterpret_cast<const uintx4 *>(Qp) + (size_t)(kc) * nq * 4;    \
+    const uintx4 *cb_ = reinterpret_cast<const uintx4 *>(Cp) + (size_t)(kc) * nlist * 4; \
+    _Pragma("unroll") for (int i = 0; i < LA; ++i) GA[i] = qb_[offa[i]]; \
+    _Pragma("unroll") for (int i = 0; i < LB; ++i) GB[i] = cb_[offb[i]]; \
+  } while (0)
+#define IVF_SSTORE(buf, GA, GB)                                                              \
+  do {                                                                                       \
+    _Pragma("unroll") for (int i = 0; i < LA; ++i) {                                         \
+      const int f = tid + NT * i;                                                            \
+      *reinterpret_cast<uintx4 *>(a_tile(buf) + (f >> 2) * kRowBytes + (f & 3) * 16) = GA[i]; \
+    }                                                                                        \
+    _Pragma("unroll") for (int i = 0; i < LB; ++i) {                                         \
+      const int f = tid + NT * i;                                                            \
+      *reinterpret_cast<uintx4 *>(b_tile(buf) + (f >> 2) * kRowBytes + (f & 3) * 16) = GB[i]; \
+    }                                                                                        \
+  } while (0)
 
   floatx16 acc[TM][TN];
 #pragma unroll
@@ -184,15 +189,13 @@ __global__ __launch_bounds__(WM *WN * 64) void k_coarse_gemm(
       for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.0f;
 
   const int nk = d / 16;  // d is a multiple of 16
-  gload(0, 0);
-  sstore(0, 0);
-  if (nk > 1) gload(1, 1);
+  IVF_GLOAD(0, ga0, gb0);
+  IVF_SSTORE(0, ga0, gb0);
+  if (nk > 1) IVF_GLOAD(1, ga1, gb1);
   __syncthreads();
   const int li = lane & 31, kk = lane >> 5;
-  // one K chunk; slot_next holds chunk kc+1 (already loaded), slot_far receives chunk kc+2
-  auto step = [&](int kc, int slot_next, int slot_far) {
-    const int buf = kc & 1;
-    if (kc + 2 < nk) gload(kc + 2, slot_far);
+  // the MFMA work of one K chunk held in LDS buffer `buf`
+  auto mma = [&](int buf) {
     // lane (li, kk) holds k = 8*kk .. 8*kk+7 of the chunk for row li of a tile
     halfx8 a[TM][2], b[TN][2];
 #pragma unroll
@@ -227,13 +230,35 @@ __global__ __launch_bounds__(WM *WN * 64) void k_coarse_gemm(
 #pragma unroll
       for (int nt = 0; nt < TN; ++nt)
         acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[mt][0], b[nt][0], acc[mt][nt], 0, 0, 0);
-    if (kc + 1 < nk) sstore(buf ^ 1, slot_next);
-    __syncthreads();
   };
-  for (int kc = 0; kc < nk; kc += 2) {  // unrolled by two: register stage indices are constants
-    step(kc, 1, 0);
-    if (kc + 1 < nk) step(kc + 1, 0, 1);
+  // chunk kc is computed from LDS while chunk kc+2 is loaded into the stage that
+  // chunk kc's own data left free, and chunk kc+1 (loaded one step earlier) moves
+  // from its stage to the other LDS buffer; unrolled by two, the stages alternate
+  int kc = 0;
+  for (; kc + 3 < nk; kc += 2) {  // steady state: straight-line, so waits can be exact
+    IVF_GLOAD(kc + 2, ga0, gb0);
+    mma(0);
+    IVF_SSTORE(1, ga1, gb1);
+    __syncthreads();
+    IVF_GLOAD(kc + 3, ga1, gb1);
+    mma(1);
+    IVF_SSTORE(0, ga0, gb0);
+    __syncthreads();
   }
+  for (; kc < nk; kc += 2) {  // the last one to three chunks
+    if (kc + 2 < nk) IVF_GLOAD(kc + 2, ga0, gb0);
+    mma(0);
+    if (kc + 1 < nk) IVF_SSTORE(1, ga1, gb1);
+    __syncthreads();
+    if (kc + 1 < nk) {
+      if (kc + 3 < nk) IVF_GLOAD(kc + 3, ga1, gb1);
+      mma(1);
+      if (kc + 2 < nk) IVF_SSTORE(0, ga0, gb0);
+      __syncthreads();
+    }
+  }
+#undef IVF_GLOAD
+#undef IVF_SSTORE
 
   // D[i][j]: register r of lane l holds i = 8*(r/4) + 4*(l/32) + r%4, j = l%32
 #pragma unroll
