@@ -263,8 +263,9 @@ int ivf_resident_info(ivf_index_t *index, int32_t *n_clusters, int64_t *n_vector
 
 /*
  * Tuning and instrumentation.  scan_slices: blocks per query in the ADC scan
- * (0 = automatic).  timing != 0 records HIP events around each kernel of
- * subsequent searches on their stream.
+ * (0 = automatic).  timing = 1 records HIP events around every stage of
+ * subsequent searches on their stream, timing = 2 only around the ADC scan
+ * (each recorded event costs a few microseconds of stream time), 0 none.
  */
 int ivf_set_tuning(ivf_index_t *index, int32_t scan_slices, int32_t timing);
 
@@ -276,10 +277,10 @@ int ivf_set_tuning(ivf_index_t *index, int32_t scan_slices, int32_t timing);
  * must stream.  Synchronizes with recorded events.  reset != 0 clears.
  */
 enum {
-  IVF_STAGE_COARSE_GEMM = 0,
-  IVF_STAGE_COARSE_SELECT = 1,
-  IVF_STAGE_ROUTE = 2,
-  IVF_STAGE_LUT = 3,
+  IVF_STAGE_LUT = 0,           /* lookup tables (built first: they need the queries only) */
+  IVF_STAGE_COARSE_GEMM = 1,
+  IVF_STAGE_COARSE_SELECT = 2,
+  IVF_STAGE_ROUTE = 3,
   IVF_STAGE_SCAN = 4,
   IVF_STAGE_MERGE = 5,
   IVF_N_STAGES = 6

@@ -15,7 +15,7 @@ LIB_PATH = os.path.join(_HERE, "libivfpq_hot.so")
 IVF_METRIC_L2, IVF_METRIC_IP = 0, 1
 IVF_OK, IVF_EINVAL, IVF_ENOMEM, IVF_EDEVICE, IVF_EBUSY, IVF_ESTATE = 0, -1, -2, -3, -4, -5
 IVF_N_STAGES = 6
-STAGE_NAMES = ("coarse_gemm", "coarse_select", "route", "lut", "scan", "merge")
+STAGE_NAMES = ("lut", "coarse_gemm", "coarse_select", "route", "scan", "merge")
 
 EXPORTS = (
     "ivf_index_arena_bytes", "ivf_index_create", "ivf_index_destroy",
@@ -304,8 +304,9 @@ class IvfIndex:
         return {"per_cluster_hits": hits, "mean_hit_rate": mean.value,
                 "min_hit_rate": mn.value, "n_queries": nq.value}
 
-    def set_tuning(self, scan_slices=0, timing=False):
-        _check(self._lib.ivf_set_tuning(self._h, int(scan_slices), int(bool(timing))))
+    def set_tuning(self, scan_slices=0, timing=0):
+        """timing: 0/False none, 1/True events around every stage, 2 around the scan only."""
+        _check(self._lib.ivf_set_tuning(self._h, int(scan_slices), int(timing)))
 
     def stage_times(self, reset=False):
         ms = np.zeros(IVF_N_STAGES, np.float64)

@@ -847,6 +847,7 @@ extern "C" int ivf_set_tuning(ivf_index_t *ix, int32_t scan_slices, int32_t timi
   if (!ix) return fail(IVF_EINVAL, "index is NULL");
   if (scan_slices < 0 || scan_slices > kMaxSlices)
     return fail(IVF_EINVAL, "scan_slices must be in [0, %d]", kMaxSlices);
+  if (timing < 0 || timing > 2) return fail(IVF_EINVAL, "timing must be 0, 1 or 2");
   std::lock_guard<std::mutex> lk(ix->mu);
   ix->tune_slices = scan_slices;
   ix->timing = timing;
@@ -1036,7 +1037,8 @@ struct SearchArgs {
 struct BatchCtx {
   int slot = 0;
   int buf = 0;
-  bool all_resident = false, any_resident = false, timing = false;
+  bool all_resident = false, any_resident = false;
+  int timing = 0;  // 0: no events; 1: around every stage; 2: around the scan only
   uint64_t ver_id = 0;
 };
 
@@ -1053,7 +1055,7 @@ static int begin_batch(ivf_index *ix, hipStream_t st, BatchCtx *c) {
   c->buf = ver.buf;
   c->all_resident = ix->resident_clusters == ix->sh.nlist;
   c->any_resident = ix->resident_clusters > 0;
-  c->timing = ix->timing != 0;
+  c->timing = ix->timing;
   return IVF_OK;
 }
 
@@ -1092,6 +1094,7 @@ static int enqueue_gpu(ivf_index *ix, const SearchArgs &a, const BatchCtx &c, bo
   memset(&trec, 0, sizeof(trec));
   auto mark = [&](int i) -> hipError_t {
     if (!c.timing) return hipSuccess;
+    if (c.timing == 2 && i != IVF_STAGE_SCAN && i != IVF_STAGE_MERGE) return hipSuccess;
     hipError_t e = hipEventCreate(&trec.ev[i]);
     if (e != hipSuccess) return e;
     trec.valid[i] = true;
@@ -1117,12 +1120,18 @@ static int enqueue_gpu(ivf_index *ix, const SearchArgs &a, const BatchCtx &c, bo
     G_TRY(hipMemcpyAsync(W.queries, a.q_host, (size_t)nq * sh.d * 4, hipMemcpyHostToDevice, st));
     dq = W.queries;
   }
+  // ---- stage 2 first: the lookup tables depend on the queries only ----
+  G_TRY(mark(IVF_STAGE_LUT));
+  int lut_parts = 0;
+  if (c.any_resident)
+    G_TRY(launch_lut(sh, dq, nq, L.cbT, W.lut, W.lutpart, &lut_parts, st));
   // ---- stage 1: coarse quantizer (or the caller's probe list) ----
+  G_TRY(mark(IVF_STAGE_COARSE_GEMM));
   if (a.probe_host) {
     memcpy(ix->h_probe, a.probe_host, (size_t)nq * np * 4);
     G_TRY(hipMemcpyAsync(W.probe, ix->h_probe, (size_t)nq * np * 4, hipMemcpyHostToDevice, st));
+    G_TRY(mark(IVF_STAGE_COARSE_SELECT));
   } else {
-    G_TRY(mark(IVF_STAGE_COARSE_GEMM));
     G_TRY(launch_split_f16(dq, (size_t)nq, sh.d, W.q_parts, W.q_exp, st));
     G_TRY(launch_coarse_gemm(sh, W.q_parts, W.q_exp, nq, L.cent_parts, L.cent_exp, L.cent_norm,
                              W.scores, st));
@@ -1135,8 +1144,9 @@ static int enqueue_gpu(ivf_index *ix, const SearchArgs &a, const BatchCtx &c, bo
     G_TRY(launch_bias(sh, dq, nq, W.probe, np, np, L.centroids, W.bias, st));
   G_TRY(launch_route(W.probe, nq, np, np, sh.nlist, L.clus_tile[c.buf], L.clus_len, sh.M, W.g_base, W.g_len,
                      W.g_prefix, W.g_n, W.cold, W.n_cold, W.q_vecs,
-                     sh.by_residual ? W.bias : nullptr, W.g_bias, W.qbmax, L.hits, L.qstats, 1,
-                     st));
+                     sh.by_residual ? W.bias : nullptr, W.g_bias, W.qbmax, L.hits, 1, W.lutpart,
+                     lut_parts, W.lutmax, st));
+  G_TRY(launch_order(W, nq, np, sh.M, L.qstats, 1, st));
   if (!final_on_gpu) {
     // cold probes go to the CPU (Section 4.3.1)
     G_TRY(hipMemcpyAsync(ix->h_ncold, W.n_cold, (size_t)nq * 4, hipMemcpyDeviceToHost, st));
@@ -1146,22 +1156,19 @@ static int enqueue_gpu(ivf_index *ix, const SearchArgs &a, const BatchCtx &c, bo
       G_TRY(hipMemcpyAsync(ix->h_queries, dq, (size_t)nq * sh.d * 4, hipMemcpyDeviceToHost, st));
     if (ev_route) G_TRY(hipEventRecord(ev_route, st));
   }
-  G_TRY(mark(IVF_STAGE_LUT));
   if (c.any_resident) {
-    // ---- stage 2: lookup tables; stage 3: scan + top-k ----
+    // ---- stage 3: scan + top-k ----
     const int slices = pick_slices(ix, nq);
-    G_TRY(launch_order(W.probe, nq, np, W.order, st));
-    G_TRY(launch_lut(sh, dq, nq, L.cbT, W.lut, W.lutpart, W.lutmax, st));
-    G_TRY(mark(IVF_STAGE_SCAN));
-    G_TRY(launch_scan(sh, L, W, nq, np, slices, k, st));
-    G_TRY(mark(IVF_STAGE_MERGE));
     int64_t *oid = nullptr;
     float *od = nullptr;
     if (final_on_gpu) {
       oid = a.out_device ? a.out_ids : W.out_ids;
       od = a.out_device ? a.out_dists : W.out_dists;
     }
-    G_TRY(launch_merge(sh, W, nq, slices, k, oid, od, st));
+    G_TRY(mark(IVF_STAGE_SCAN));
+    G_TRY(launch_scan(sh, L, W, nq, np, slices, k, oid, od, st));
+    G_TRY(mark(IVF_STAGE_MERGE));
+    if (slices > 1) G_TRY(launch_merge(sh, W, nq, slices, k, oid, od, st));
     G_TRY(mark(IVF_N_STAGES));
     if (!final_on_gpu) {
       G_TRY(hipMemcpyAsync(ix->h_reskey, W.res_key, (size_t)nq * k * 4, hipMemcpyDeviceToHost, st));

@@ -122,22 +122,28 @@ hipError_t launch_bias(const Shape &sh, const float *q, int nq, const int32_t *p
                        int probe_stride, const float *centroids, float *bias, hipStream_t st);
 
 // bias may be NULL (no residual encoding): g_bias is then untouched and qbmax set to 0.
+// lut_parts > 0: also reduce each query's lut_parts partial table maxima into lutmax.
 hipError_t launch_route(const int32_t *probe, int nq, int nprobe, int probe_stride, int nlist,
                         const int32_t *clus_tile, const int32_t *clus_len, int M, int32_t *g_base,
                         int32_t *g_len, int32_t *g_prefix, int32_t *g_n, int32_t *cold,
                         int32_t *n_cold, int32_t *q_vecs, const float *bias, float *g_bias,
-                        float *qbmax, unsigned long long *hits, unsigned long long *qstats,
-                        int count_stats, hipStream_t st);
+                        float *qbmax, unsigned long long *hits, int count_stats,
+                        const uint32_t *lutpart, int lut_parts, uint32_t *lutmax, hipStream_t st);
 
-hipError_t launch_order(const int32_t *probe, int nq, int probe_stride, int32_t *order,
-                        hipStream_t st);
-
+// Lookup tables of every query and, per query, *n_parts partial maxima in lutpart.
 hipError_t launch_lut(const Shape &sh, const float *q, int nq, const float *cbT, float *lut,
-                      uint32_t *lutpart, uint32_t *lutmax, hipStream_t st);
+                      uint32_t *lutpart, int *n_parts, hipStream_t st);
 
-// Returns hipErrorInvalidValue for an unsupported (M, k).
+// After the router: batch totals of the router counters, the scan's visiting order.
+hipError_t launch_order(const BatchWs &W, int nq, int probe_stride, int M,
+                        unsigned long long *qstats, int count_stats, hipStream_t st);
+
+// Returns hipErrorInvalidValue for an unsupported (M, k).  With slices == 1 the scan
+// writes the queries' results itself, as launch_merge would (same meaning of
+// out_ids / out_dists), and launch_merge is not needed.
 hipError_t launch_scan(const Shape &sh, const DevLayout &L, const BatchWs &W, int nq,
-                       int probe_stride, int slices, int k, hipStream_t st);
+                       int probe_stride, int slices, int k, int64_t *out_ids, float *out_dists,
+                       hipStream_t st);
 
 // final != 0: write (id, dist) to out_ids/out_dists; else (key, id) to res_key/res_id.
 hipError_t launch_merge(const Shape &sh, const BatchWs &W, int nq, int slices, int k,

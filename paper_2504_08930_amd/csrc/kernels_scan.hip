@@ -180,7 +180,8 @@ __global__ __launch_bounds__(256) void k_route(
     const int32_t *__restrict__ clus_tile, const int32_t *__restrict__ clus_len, int M,
     int32_t *g_base, int32_t *g_len, int32_t *g_prefix, int32_t *g_n, int32_t *cold,
     int32_t *n_cold, int32_t *q_vecs, const float *__restrict__ bias, float *g_bias, float *qbmax,
-    unsigned long long *hits, int count_stats, int n2) {
+    unsigned long long *hits, int count_stats, int n2, const uint32_t *__restrict__ lutpart,
+    int nparts, uint32_t *__restrict__ lutmax) {
   // One wavefront per query, one lane per probe (64 probes per step).  The
   // probes are first put in cluster-id order (n2 > 0: a bitonic sort of
   // (id, rank) words in LDS), so that the work lists of queries that share
@@ -192,6 +193,15 @@ __global__ __launch_bounds__(256) void k_route(
   const int lane = threadIdx.x & 63;
   if (q >= nq) return;
   const int32_t *pr = probe + (size_t)q * stride;
+  if (nparts > 0) {
+    // largest |entry| of the query's lookup table, from the partial maxima the
+    // table kernel left (the tables depend on the queries only and are built first)
+    uint32_t mx = 0;
+    for (int i = lane; i < nparts; i += 64) mx = max(mx, lutpart[(size_t)q * kLutMaxParts + i]);
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) mx = max(mx, (uint32_t)__shfl_xor((int)mx, o, 64));
+    if (lane == 0) lutmax[q] = mx;
+  }
   int32_t *srt = route_sort + (threadIdx.x >> 6) * n2;
   if (n2 > 0) {
     for (int p = lane; p < n2; p += 64) {
@@ -285,16 +295,29 @@ __global__ __launch_bounds__(256) void k_route(
   }
 }
 
-// Batch totals of the router counters: one block reduces the per-query values
-// (same-address atomics from every query would serialize).
-__global__ __launch_bounds__(1024) void k_route_stats(const int32_t *__restrict__ g_n,
-                                                      const int32_t *__restrict__ n_cold,
-                                                      const int32_t *__restrict__ q_vecs, int nq,
-                                                      int M, unsigned long long *qstats,
-                                                      int count_stats) {
+// One single-block kernel for the two small per-batch reductions between the
+// router and the scan:
+//  * batch totals of the router counters (same-address atomics from every
+//    query's wavefront would serialize);
+//  * the visiting order of the scan: queries grouped by their best cluster (a
+//    counting sort on the cluster id folded into kOrderBins bins; the order
+//    inside a group does not matter), histogram and offsets in LDS.
+constexpr int kOrderBins = 4096;
+
+__global__ __launch_bounds__(1024) void k_order(const int32_t *__restrict__ probe, int nq,
+                                                int stride, int32_t *__restrict__ order,
+                                                const int32_t *__restrict__ g_n,
+                                                const int32_t *__restrict__ n_cold,
+                                                const int32_t *__restrict__ q_vecs, int M,
+                                                unsigned long long *qstats, int count_stats) {
+  __shared__ unsigned int bins[kOrderBins];
+  __shared__ unsigned int wsum[16];
   __shared__ unsigned long long s_res[16], s_all[16], s_vec[16];
   __shared__ unsigned int s_min[16];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  for (int i = tid; i < kOrderBins; i += 1024) bins[i] = 0u;
+
+  // ---- router counters ----
   unsigned long long res = 0, all = 0, vec = 0;
   unsigned int mn = 0x3f800000u;  // 1.0f
   for (int q = tid; q < nq; q += 1024) {
@@ -318,7 +341,7 @@ __global__ __launch_bounds__(1024) void k_route_stats(const int32_t *__restrict_
     s_vec[wave] = vec;
     s_min[wave] = mn;
   }
-  __syncthreads();
+  __syncthreads();  // also: bins are zero
   if (tid == 0) {
     for (int w2 = 1; w2 < 16; ++w2) {
       res += s_res[w2];
@@ -334,20 +357,8 @@ __global__ __launch_bounds__(1024) void k_route_stats(const int32_t *__restrict_
       atomicMin(reinterpret_cast<unsigned int *>(&qstats[QS_MIN_RATE_BITS]), mn);
     }
   }
-}
 
-// Visiting order of the scan: queries grouped by their best cluster (a counting
-// sort on the cluster id folded into kOrderBins bins; the order inside a group
-// does not matter).  One block, histogram and offsets in LDS.
-constexpr int kOrderBins = 4096;
-
-__global__ __launch_bounds__(1024) void k_order(const int32_t *__restrict__ probe, int nq,
-                                                int stride, int32_t *__restrict__ order) {
-  __shared__ unsigned int bins[kOrderBins];
-  __shared__ unsigned int wsum[16];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  for (int i = tid; i < kOrderBins; i += 1024) bins[i] = 0u;
-  __syncthreads();
+  // ---- visiting order ----
   for (int q = tid; q < nq; q += 1024)
     atomicAdd(&bins[(unsigned)probe[(size_t)q * stride] % kOrderBins], 1u);
   __syncthreads();
@@ -380,9 +391,10 @@ __global__ __launch_bounds__(1024) void k_order(const int32_t *__restrict__ prob
   }
 }
 
-hipError_t launch_order(const int32_t *probe, int nq, int probe_stride, int32_t *order,
-                        hipStream_t st) {
-  hipLaunchKernelGGL(k_order, dim3(1), dim3(1024), 0, st, probe, nq, probe_stride, order);
+hipError_t launch_order(const BatchWs &W, int nq, int probe_stride, int M,
+                        unsigned long long *qstats, int count_stats, hipStream_t st) {
+  hipLaunchKernelGGL(k_order, dim3(1), dim3(1024), 0, st, W.probe, nq, probe_stride, W.order,
+                     W.g_n, W.n_cold, W.q_vecs, M, qstats, count_stats);
   return hipGetLastError();
 }
 
@@ -390,8 +402,8 @@ hipError_t launch_route(const int32_t *probe, int nq, int nprobe, int probe_stri
                         const int32_t *clus_tile, const int32_t *clus_len, int M, int32_t *g_base,
                         int32_t *g_len, int32_t *g_prefix, int32_t *g_n, int32_t *cold,
                         int32_t *n_cold, int32_t *q_vecs, const float *bias, float *g_bias,
-                        float *qbmax, unsigned long long *hits, unsigned long long *qstats,
-                        int count_stats, hipStream_t st) {
+                        float *qbmax, unsigned long long *hits, int count_stats,
+                        const uint32_t *lutpart, int lut_parts, uint32_t *lutmax, hipStream_t st) {
   // (id << 11 | rank) must fit a positive int: nprobe <= 2048 holds, ids need < 2^20
   int n2 = 0;
   if (nlist < (1 << 20)) {
@@ -401,11 +413,7 @@ hipError_t launch_route(const int32_t *probe, int nq, int nprobe, int probe_stri
   hipLaunchKernelGGL(k_route, dim3((nq + 3) / 4), dim3(256), (size_t)4 * n2 * sizeof(int32_t), st,
                      probe, nq, nprobe, probe_stride, clus_tile, clus_len, M, g_base, g_len,
                      g_prefix, g_n, cold, n_cold, q_vecs, bias, g_bias, qbmax, hits, count_stats,
-                     n2);
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(k_route_stats, dim3(1), dim3(1024), 0, st, g_n, n_cold, q_vecs, nq, M, qstats,
-                     count_stats);
+                     n2, lutpart, lut_parts, lutmax);
   return hipGetLastError();
 }
 
@@ -472,18 +480,6 @@ __global__ __launch_bounds__(256) void k_lut(const float *__restrict__ queries, 
   }
 }
 
-__global__ __launch_bounds__(256) void k_lut_max(const uint32_t *__restrict__ lutpart, int nq,
-                                                 int nparts, uint32_t *__restrict__ lutmax) {
-  const int q = blockIdx.x * 4 + (threadIdx.x >> 6);
-  const int lane = threadIdx.x & 63;
-  if (q >= nq) return;
-  uint32_t mx = 0;
-  for (int i = lane; i < nparts; i += 64) mx = max(mx, lutpart[(size_t)q * kLutMaxParts + i]);
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) mx = max(mx, (uint32_t)__shfl_xor((int)mx, o, 64));
-  if (lane == 0) lutmax[q] = mx;
-}
-
 // 4-bit codes: the table the scan reads has one column per code BYTE; entry j of
 // column m is the sum of the entries of the two sub-quantizers packed in the
 // byte (sub-quantizer 2m from the low half of j, 2m+1 from the high half).  A
@@ -539,7 +535,7 @@ __global__ __launch_bounds__(256) void k_lut4(const float *__restrict__ queries,
 }
 
 hipError_t launch_lut(const Shape &sh, const float *q, int nq, const float *cbT, float *lut,
-                      uint32_t *lutpart, uint32_t *lutmax, hipStream_t st) {
+                      uint32_t *lutpart, int *n_parts, hipStream_t st) {
   if (sh.nbits == 4) {
     if (sh.d > 2048 || sh.M > 128) return hipErrorInvalidValue;
     const int split = nq >= 512 ? 1 : (nq >= 128 ? 4 : 16);  // blocks per query
@@ -560,10 +556,7 @@ hipError_t launch_lut(const Shape &sh, const float *q, int nq, const float *cbT,
                            sh.lut_kind(), rows, lut, lutpart);
     }
 #undef IVF_LUT4_CASE
-    hipError_t e4 = hipGetLastError();
-    if (e4 != hipSuccess) return e4;
-    hipLaunchKernelGGL(k_lut_max, dim3((nq + 3) / 4), dim3(256), 0, st, lutpart, nq, split * 4,
-                       lutmax);
+    *n_parts = split * 4;
     return hipGetLastError();
   }
   const int MW = (sh.M % 32 == 0) ? 32 : 16;
@@ -585,10 +578,7 @@ hipError_t launch_lut(const Shape &sh, const float *q, int nq, const float *cbT,
                          sh.lut_kind(), lut, lutpart);
   }
 #undef IVF_LUT_CASE
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return e;
-  const int nparts = (int)(grid.x * grid.y * 4);
-  hipLaunchKernelGGL(k_lut_max, dim3((nq + 3) / 4), dim3(256), 0, st, lutpart, nq, nparts, lutmax);
+  *n_parts = (int)(grid.x * grid.y * 4);
   return hipGetLastError();
 }
 
@@ -678,6 +668,13 @@ struct ScanParams {
   const int32_t *order;
   int32_t *part_key;
   int64_t *part_id;
+  // slices == 1: the block's result is the query's result and is written here
+  // directly (ids and distances if out_ids != NULL, else keys and ids)
+  int32_t *res_key;
+  int64_t *res_id;
+  int64_t *out_ids;
+  float *out_dists;
+  int metric_ip;
   int nq;
   int probe_stride;
   int slices;
@@ -1007,21 +1004,34 @@ __global__ __launch_bounds__(NW * 64) void k_scan(ScanParams P) {
   }
   wave_sync();
   const size_t obase = ((size_t)q * P.slices + s) * k;
+  // rank-th best of this block: a partial result for k_merge, or, with one
+  // slice per query, the query's result itself
+  auto emit = [&](int rank, int key, long long id) {
+    if (P.slices > 1) {
+      P.part_key[obase + rank] = key;
+      P.part_id[obase + rank] = id;
+      return;
+    }
+    const bool ok = key != kKeyInvalid;
+    const size_t o = (size_t)q * k + rank;
+    if (P.out_ids) {
+      P.out_ids[o] = ok ? id : -1;
+      P.out_dists[o] =
+          ok ? key_to_dist(key, e, P.metric_ip) : (P.metric_ip ? -INFINITY : INFINITY);
+    } else {
+      P.res_key[o] = key;
+      P.res_id[o] = ok ? id : -1;
+    }
+  };
   if (nf <= 192) {
     for (int i = lane; i < nf; i += 64) {
       const int ki = fkey[i];
       const long long idi = fid[i];
       int rank = 0;
       for (int j = 0; j < nf; ++j) rank += cand_less(fkey[j], fid[j], ki, idi) ? 1 : 0;
-      if (rank < k) {
-        P.part_key[obase + rank] = ki;
-        P.part_id[obase + rank] = idi;
-      }
+      if (rank < k) emit(rank, ki, idi);
     }
-    for (int r = nf + lane; r < k; r += 64) {
-      P.part_key[obase + r] = kKeyInvalid;
-      P.part_id[obase + r] = 0x7fffffffffffffffll;
-    }
+    for (int r = nf + lane; r < k; r += 64) emit(r, kKeyInvalid, 0x7fffffffffffffffll);
   } else {  // a mass of equal keys: sort them all
     int n2 = 256;
     while (n2 < nf) n2 <<= 1;
@@ -1031,10 +1041,7 @@ __global__ __launch_bounds__(NW * 64) void k_scan(ScanParams P) {
     }
     wave_sync();
     bitonic_sort_lds<false>(fkey, fid, n2, lane, 64);
-    for (int r = lane; r < k; r += 64) {
-      P.part_key[obase + r] = fkey[r];
-      P.part_id[obase + r] = fid[r];
-    }
+    for (int r = lane; r < k; r += 64) emit(r, fkey[r], fid[r]);
   }
 }
 
@@ -1061,7 +1068,8 @@ bool scan_supports(int M, int k) {
 }
 
 hipError_t launch_scan(const Shape &sh, const DevLayout &L, const BatchWs &W, int nq,
-                       int probe_stride, int slices, int k, hipStream_t st) {
+                       int probe_stride, int slices, int k, int64_t *out_ids, float *out_dists,
+                       hipStream_t st) {
   if (!scan_supports(sh.M, k)) return hipErrorInvalidValue;
   ScanParams P;
   P.tile_codes = L.tile_codes;
@@ -1076,6 +1084,11 @@ hipError_t launch_scan(const Shape &sh, const DevLayout &L, const BatchWs &W, in
   P.nq = nq;
   P.part_key = W.part_key;
   P.part_id = W.part_id;
+  P.res_key = W.res_key;
+  P.res_id = W.res_id;
+  P.out_ids = out_ids;
+  P.out_dists = out_dists;
+  P.metric_ip = sh.metric_ip;
   P.probe_stride = probe_stride;
   P.slices = slices;
   P.k = k;
