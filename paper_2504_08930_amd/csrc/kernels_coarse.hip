@@ -326,9 +326,7 @@ __device__ __forceinline__ uint32_t score_bits(float s, int metric_ip) {
   return metric_ip ? ~u : u;                        // IP: larger score first
 }
 
-constexpr int kSelThreads = 1024;
 constexpr int kSelBins = 2048;  // 11-bit digits
-constexpr int kSelBinsPerThread = kSelBins / kSelThreads;
 
 __device__ __forceinline__ unsigned long long sel_key(float s, int metric_ip, int c) {
   return ((unsigned long long)score_bits(s, metric_ip) << 32) | (unsigned)c;
@@ -344,11 +342,12 @@ __device__ __forceinline__ unsigned long long sel_key(float s, int metric_ip, in
 // `keep`) and sorted exactly by (score bits, id).  If that set does not fit the
 // `cap` LDS slots (heavy ties, a degenerate range, non-finite scores), the exact
 // MSB-first radix select over the 64-bit keys below does the work instead.
-template <int PER>
+template <int PER, int kSelThreads>
 __global__ __launch_bounds__(kSelThreads) void k_coarse_select(const float *__restrict__ scores,
                                                                int nlist, int metric_ip, int keep,
                                                                int nprobe, int stride, int cap,
                                                                int32_t *__restrict__ probe) {
+  constexpr int kSelBinsPerThread = kSelBins / kSelThreads;
   __shared__ unsigned int hist[kSelBins];
   __shared__ unsigned int wsum[kSelThreads / 64];
   __shared__ float wmin[kSelThreads / 64], wmax[kSelThreads / 64];
@@ -380,6 +379,11 @@ __global__ __launch_bounds__(kSelThreads) void k_coarse_select(const float *__re
     } else {
       for (int c = tid; c < nlist; c += kSelThreads) body(row[c], c);
     }
+  };
+
+  // the same from memory (the rarely taken radix passes do not hold the row in registers)
+  auto visit_mem = [&](auto body) {
+    for (int c = tid; c < nlist; c += kSelThreads) body(row[c], c);
   };
 
   if (tid == 0) {
@@ -486,7 +490,7 @@ __global__ __launch_bounds__(kSelThreads) void k_coarse_select(const float *__re
         const unsigned long long prefix = s_prefix, mask = s_mask;
         const unsigned need = s_need;
         if (s_done) break;
-        visit([&](float s0, int c) {
+        visit_mem([&](float s0, int c) {
           const unsigned long long key = sel_key(s0, metric_ip, c);
           if ((key & mask) == prefix) atomicAdd(&hist[(unsigned)(key >> shift) & dmask], 1u);
         });
@@ -530,7 +534,7 @@ __global__ __launch_bounds__(kSelThreads) void k_coarse_select(const float *__re
     }
     for (int i = tid; i < cap; i += kSelThreads) sel[i] = ~0ull;
     __syncthreads();
-    visit([&](float s0, int c) {
+    visit_mem([&](float s0, int c) {
       const unsigned long long key = sel_key(s0, metric_ip, c);
       if (key <= thr) {
         const unsigned slot = atomicAdd(&s_count, 1u);
@@ -573,12 +577,13 @@ hipError_t launch_coarse_select(const Shape &sh, const float *scores, int nq, in
   const int keep = nprobe < sh.nlist ? nprobe : sh.nlist;
   int cap = 128;  // LDS slots for collected candidates: a power of two >= 2 * keep
   while (cap < 2 * keep) cap <<= 1;
-#define IVF_SEL_LAUNCH(PER)                                                                  \
-  hipLaunchKernelGGL(k_coarse_select<PER>, dim3(nq), dim3(kSelThreads), (size_t)cap * 8, st, \
-                     scores, sh.nlist, sh.metric_ip, keep, nprobe, probe_stride, cap, probe)
-  if (sh.nlist <= 4 * kSelThreads) IVF_SEL_LAUNCH(4);
-  else if (sh.nlist <= 16 * kSelThreads) IVF_SEL_LAUNCH(16);
-  else IVF_SEL_LAUNCH(0);
+#define IVF_SEL_LAUNCH(PER, THREADS)                                                          \
+  hipLaunchKernelGGL((k_coarse_select<PER, THREADS>), dim3(nq), dim3(THREADS), (size_t)cap * 8, \
+                     st, scores, sh.nlist, sh.metric_ip, keep, nprobe, probe_stride, cap, probe)
+  // the row of scores in registers (4 or 16 per thread) up to 16384 clusters, re-read above
+  if (sh.nlist <= 4 * 1024) IVF_SEL_LAUNCH(4, 1024);
+  else if (sh.nlist <= 16 * 1024) IVF_SEL_LAUNCH(16, 1024);
+  else IVF_SEL_LAUNCH(0, 1024);
 #undef IVF_SEL_LAUNCH
   return hipGetLastError();
 }
