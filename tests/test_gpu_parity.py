@@ -356,6 +356,54 @@ def test_k100_nprobe128(pkg, oracle):
     _CACHE.pop("C4S", None)
 
 
+@pytest.mark.skipif(os.environ.get("IVF_TEST_C4") != "1",
+                    reason="builds a 100M-vector index (about 3 minutes of GPU time, 25 GB of host "
+                           "memory): run with IVF_TEST_C4=1")
+@pytest.mark.timeout(900)
+def test_c4_config_full_size(pkg, oracle):
+    """The 100M x 768 configuration (nlist=65536, nq=4096, nprobe=128, k=100) at its real
+    size: oracle parity on a sample of queries for three access skews, with every cluster
+    resident and with a resident set taken from the hit-rate profile."""
+    import torch
+    spec, ix, q, calib = _case("C4")
+    index = pkg.IvfIndex(ix, max_nq=4096, max_nprobe=128, max_k=100)
+    full = np.arange(ix.nlist, dtype=np.int32)
+    index.load_partition(full)
+    centers = mixture_centers(spec, torch.device("cuda"))
+    for s_skew in (0.6, 1.0, 1.4):
+        qs, _ = make_queries(spec.with_(zipf_s=s_skew), centers)
+        qd = qs.contiguous()
+        qh = qd.cpu().numpy()
+        ids_d, dist_d = index.search_batch_dev(qd, spec.nprobe, spec.k)
+        torch.cuda.synchronize()
+        ids, dist = ids_d.cpu().numpy(), dist_d.cpu().numpy()
+        probe = index.coarse_probe_dev(qd, spec.nprobe).cpu().numpy()
+        sel = np.arange(0, qh.shape[0], 64)
+        n_coarse, n_amb = _check_search(oracle, ix, qh[sel], spec.nprobe, spec.k, ids[sel],
+                                        dist[sel], probe[sel])
+        _say(f"C4 zipf_s={s_skew}: coarse-ambiguous {n_coarse}, id-ambiguous {n_amb} of {len(sel)}")
+        assert n_coarse <= 1 and n_amb <= 2
+        assert (ids >= 0).all() and np.all(np.diff(dist, axis=1) <= 0)
+    # resident set from the hit-rate profile: the hottest clusters that cover 80 % of the accesses
+    index.load_partition(full)
+    index.hit_stats(reset=True)
+    for s0 in range(0, calib.shape[0], 4096):
+        index.search_batch_dev(torch.from_numpy(calib[s0:s0 + 4096]).cuda(), spec.nprobe, 1)
+    torch.cuda.synchronize()
+    hits = index.hit_stats(reset=True)["per_cluster_hits"].astype(np.int64)
+    order = np.lexsort((np.arange(ix.nlist), -hits))
+    cdf = np.cumsum(hits[order]) / max(1, hits.sum())
+    hot = np.sort(order[: int(np.searchsorted(cdf, 0.8)) + 1]).astype(np.int32)
+    index.load_partition(hot)
+    sub = np.arange(0, qh.shape[0], 8)            # the CPU tier scans the cold probes
+    hyb = index.search_batch(qh[sub], spec.nprobe, spec.k)
+    st = index.hit_stats()
+    _say(f"C4: {len(hot)} of {ix.nlist} clusters resident, mean hit rate {st['mean_hit_rate']:.3f}")
+    assert np.array_equal(hyb[0], ids[sub]) and np.array_equal(hyb[1], dist[sub])
+    index.close()
+    _CACHE.pop("C4", None)
+
+
 @pytest.mark.parametrize("name", ["T_L2", "T_IP", "T_IP96"])
 def test_residual_encoding(pkg, oracle, name):
     """Residual-encoded codes (x - centroid): bias per (query, list) and, for L2, a
