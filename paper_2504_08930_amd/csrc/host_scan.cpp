@@ -1,6 +1,7 @@
 #include "host_scan.h"
 
 #include <stdlib.h>
+#include <string.h>
 
 #include <algorithm>
 #include <atomic>
@@ -140,7 +141,19 @@ void cpu_scan_lists(const HostIndexView &ix, const int32_t *lut, int e, const fl
       const uint8_t *code = ix.codes + (size_t)v * M;
       int32_t sum = bias_key;
       if (ix.pv) sum += lut_quantize(ix.pv[v], e);
-      for (int m = 0; m < M; ++m) sum += lut[m * 256 + code[m]];
+      // eight code bytes per 64-bit load, two independent accumulators (integer sums:
+      // the order does not matter); M is a multiple of 16
+      int32_t s0 = 0, s1 = 0;
+      for (int m = 0; m < M; m += 8) {
+        uint64_t w;
+        memcpy(&w, code + m, 8);
+        const int32_t *t = lut + m * 256;
+        s0 += t[w & 255] + t[512 + ((w >> 16) & 255)] + t[1024 + ((w >> 32) & 255)] +
+              t[1536 + ((w >> 48) & 255)];
+        s1 += t[256 + ((w >> 8) & 255)] + t[768 + ((w >> 24) & 255)] +
+              t[1280 + ((w >> 40) & 255)] + t[1792 + (w >> 56)];
+      }
+      sum += s0 + s1;
       HostCand cand{sum, ix.ids[v]};
       if ((int)heap.size() < k) {
         heap.push_back(cand);
