@@ -46,6 +46,9 @@
 #ifdef __cplusplus
 extern "C" {
 #endif
+#if defined(__GNUC__)
+#pragma GCC visibility push(default) /* the library is built with hidden visibility */
+#endif
 
 typedef struct ivf_index ivf_index_t; /* opaque */
 
@@ -349,6 +352,9 @@ int ivf_calib_read(const void *src, void *sink, size_t bytes, void *stream);
 /* Message for the last error returned on this thread ("" if none). */
 const char *ivf_last_error(void);
 
+#if defined(__GNUC__)
+#pragma GCC visibility pop
+#endif
 #ifdef __cplusplus
 }
 #endif

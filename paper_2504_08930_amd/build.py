@@ -5,13 +5,13 @@ import subprocess
 _HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(_HERE, "csrc")
 LIB_PATH = os.path.join(_HERE, "libivfpq_hot.so")
-SOURCES = ["api.cpp", "host_scan.cpp", "partition_model.cpp", "kernels_scan.hip",
+SOURCES = ["index.cpp", "residency.cpp", "search.cpp", "dispatcher.cpp", "host_scan.cpp", "partition_model.cpp", "kernels_scan.hip",
            "kernels_coarse.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "-O3", "-std=c++17", "--offload-arch=gfx950",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-    "-fPIC", "-Xarch_host", "-march=x86-64-v3", "-Wno-unused-command-line-argument",
+    "-fPIC", "-fvisibility=hidden", "-Xarch_host", "-march=x86-64-v3", "-Wno-unused-command-line-argument",
 ]
 
 

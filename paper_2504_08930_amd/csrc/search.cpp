@@ -1,0 +1,457 @@
+// C ABI, part 3: the search driver.  Strings the kernels together on the
+// caller's stream, runs the CPU scan of cold probes and merges (bulk path).
+#include "index_state.h"
+
+// ---------------------------------------------------------------------------
+// search
+// ---------------------------------------------------------------------------
+static void emit_results(const ivf_index *ix, const HostCand *c, int k, int e, int64_t *ids,
+                         float *dists) {
+  for (int r = 0; r < k; ++r) {
+    if (c[r].key == kKeyInvalid) {
+      ids[r] = -1;
+      dists[r] = ix->sh.metric_ip ? -INFINITY : INFINITY;
+    } else {
+      ids[r] = c[r].id;
+      dists[r] = key_to_dist(c[r].key, e, ix->sh.metric_ip);
+    }
+  }
+}
+
+static int pick_slices(const ivf_index *ix, int64_t nq) {
+  if (ix->tune_slices > 0) return ix->tune_slices;
+  // one block per query fills the chip from 256 queries up; below that, split
+  int s = (int)((256 + nq - 1) / nq);
+  if (s < 1) s = 1;
+  if (s > kMaxSlices) s = kMaxSlices;
+  return s;
+}
+
+// Search on a device-less index: every probe is scanned on the CPU.
+static int search_host_only(ivf_index *ix, const float *queries, int64_t nq, const int32_t *probe,
+                            int nprobe, int k, int64_t *out_ids, float *out_dists) {
+  const HostIndexView view = host_view(ix);
+  std::vector<int64_t> ids((size_t)nq * k);
+  std::vector<float> dists((size_t)nq * k);
+  parallel_for(nq, [&](int64_t q) {
+    std::vector<int32_t> lut((size_t)view.M * 256);
+    std::vector<HostCand> cand(k);
+    const float *qv = queries + (size_t)q * view.d;
+    const int32_t *pr = probe + (size_t)q * nprobe;
+    const int e = cpu_build_lut(view, qv, cpu_max_bias(view, qv, pr, nprobe), lut.data());
+    cpu_scan_lists(view, lut.data(), e, qv, pr, nprobe, k, cand.data());
+    emit_results(ix, cand.data(), k, e, &ids[(size_t)q * k], &dists[(size_t)q * k]);
+  });
+  {
+    std::lock_guard<std::mutex> lk(ix->mu);
+    for (int64_t i = 0; i < nq * nprobe; ++i)
+      if (probe[i] >= 0) {
+        ix->hc_hits[probe[i]] += 1;
+        ix->hc_probes += 1;
+      }
+    ix->hc_queries += (uint64_t)nq;
+  }
+  memcpy(out_ids, ids.data(), ids.size() * 8);
+  memcpy(out_dists, dists.data(), dists.size() * 4);
+  return IVF_OK;
+}
+
+// Workspace slot for a batch on stream st (caller holds ix->mu).
+static int acquire_slot_locked(ivf_index *ix, hipStream_t st, int *slot) {
+  int pick = -1;
+  for (int i = 0; i < kWsSlots; ++i)
+    if (ix->slot_used[i] && ix->slot_stream[i] == st) pick = i;
+  if (pick < 0)
+    for (int i = 0; i < kWsSlots; ++i)
+      if (!ix->slot_used[i]) {
+        pick = i;
+        break;
+      }
+  if (pick < 0) {
+    pick = 0;
+    for (int i = 1; i < kWsSlots; ++i)
+      if (ix->slot_tick[i] < ix->slot_tick[pick]) pick = i;
+    HIP_TRY(hipStreamSynchronize(ix->slot_stream[pick]));
+  }
+  ix->slot_used[pick] = true;
+  ix->slot_stream[pick] = st;
+  ix->slot_tick[pick] = ++ix->tick;
+  *slot = pick;
+  return IVF_OK;
+}
+
+
+int begin_batch(ivf_index *ix, hipStream_t st, BatchCtx *c) {
+  std::lock_guard<std::mutex> lk(ix->mu);
+  int rc = acquire_slot_locked(ix, st, &c->slot);
+  if (rc < 0) return rc;
+  rc = publish_if_done_locked(ix, false);
+  if (rc < 0) return rc;
+  reclaim(ix);
+  Version &ver = ix->versions.back();
+  ver.refs += 1;
+  c->ver_id = ver.id;
+  c->buf = ver.buf;
+  c->all_resident = ix->resident_clusters == ix->sh.nlist;
+  c->any_resident = ix->resident_clusters > 0;
+  c->timing = ix->timing;
+  return IVF_OK;
+}
+
+// Drop the hold on the mapping-table version.  async_tail: device work that
+// reads the table may still be queued on st, so leave an event behind.
+void end_batch(ivf_index *ix, const BatchCtx &c, hipStream_t st, bool async_tail) {
+  std::lock_guard<std::mutex> lk(ix->mu);
+  for (auto &v : ix->versions) {
+    if (v.id != c.ver_id) continue;
+    if (async_tail) {
+      hipEvent_t e = get_event(ix);
+      if (e && hipEventRecord(e, st) == hipSuccess) v.events.push_back(e);
+      else (void)hipStreamSynchronize(st);
+    }
+    v.refs -= 1;
+    break;
+  }
+}
+
+// Enqueue the device side of one batch on a.st: coarse quantizer (or the
+// caller's probes), routing, lookup tables, scan of the resident probes and
+// merge of the slices.  final_on_gpu: every probe is resident and the merge
+// writes ids and distances; otherwise the per-query partial results, the cold
+// probe lists and the scale inputs are copied to the index's pinned buffers.
+// ev_route (optional) is recorded once the cold lists are on their way, so a
+// host thread can start on them while the device scans.
+int enqueue_gpu(ivf_index *ix, const SearchArgs &a, const BatchCtx &c, bool final_on_gpu,
+                       hipEvent_t ev_route) {
+  const DevLayout &L = ix->L;
+  const Shape &sh = ix->sh;
+  const int nq = (int)a.nq, k = a.k, np = a.nprobe;
+  hipStream_t st = a.st;
+  const BatchWs &W = L.ws[c.slot];
+
+  TimingRec trec;
+  memset(&trec, 0, sizeof(trec));
+  auto mark = [&](int i) -> hipError_t {
+    if (!c.timing) return hipSuccess;
+    if (c.timing == 2 && i != IVF_STAGE_SCAN && i != IVF_STAGE_MERGE) return hipSuccess;
+    hipError_t e = hipEventCreate(&trec.ev[i]);
+    if (e != hipSuccess) return e;
+    trec.valid[i] = true;
+    return hipEventRecord(trec.ev[i], st);
+  };
+  auto keep_timing = [&]() {
+    if (!c.timing) return;
+    std::lock_guard<std::mutex> lk(ix->mu);
+    ix->trecs.push_back(trec);
+  };
+#define G_TRY(expr)                                                                        \
+  do {                                                                                     \
+    hipError_t _e = (expr);                                                                \
+    if (_e != hipSuccess) {                                                                \
+      keep_timing();                                                                       \
+      return fail(IVF_EDEVICE, "%s failed: %s (%s:%d)", #expr, hipGetErrorString(_e),      \
+                  __FILE__, __LINE__);                                                     \
+    }                                                                                      \
+  } while (0)
+
+  const float *dq = a.q_dev;
+  if (!dq) {
+    G_TRY(hipMemcpyAsync(W.queries, a.q_host, (size_t)nq * sh.d * 4, hipMemcpyHostToDevice, st));
+    dq = W.queries;
+  }
+  // ---- stage 2 first: the lookup tables depend on the queries only ----
+  G_TRY(mark(IVF_STAGE_LUT));
+  int lut_parts = 0;
+  if (c.any_resident)
+    G_TRY(launch_lut(sh, dq, nq, L.cbT, W.lut, W.lutpart, &lut_parts, st));
+  // ---- stage 1: coarse quantizer (or the caller's probe list) ----
+  G_TRY(mark(IVF_STAGE_COARSE_GEMM));
+  if (a.probe_host) {
+    memcpy(ix->h_probe, a.probe_host, (size_t)nq * np * 4);
+    G_TRY(hipMemcpyAsync(W.probe, ix->h_probe, (size_t)nq * np * 4, hipMemcpyHostToDevice, st));
+    G_TRY(mark(IVF_STAGE_COARSE_SELECT));
+  } else {
+    G_TRY(launch_split_f16(dq, (size_t)nq, sh.d, W.q_parts, W.q_exp, st));
+    G_TRY(launch_coarse_gemm(sh, W.q_parts, W.q_exp, nq, L.cent_parts, L.cent_exp, L.cent_norm,
+                             W.scores, st));
+    G_TRY(mark(IVF_STAGE_COARSE_SELECT));
+    G_TRY(launch_coarse_select(sh, W.scores, nq, np, np, W.probe, st));
+  }
+  // ---- routing ----
+  G_TRY(mark(IVF_STAGE_ROUTE));
+  if (sh.by_residual)
+    G_TRY(launch_bias(sh, dq, nq, W.probe, np, np, L.centroids, W.bias, st));
+  G_TRY(launch_route(W.probe, nq, np, np, sh.nlist, L.clus_tile[c.buf], L.clus_len, sh.M, W.g_base, W.g_len,
+                     W.g_prefix, W.g_n, W.cold, W.n_cold, W.q_vecs,
+                     sh.by_residual ? W.bias : nullptr, W.g_bias, W.qbmax, L.hits, 1, W.lutpart,
+                     lut_parts, W.lutmax, st));
+  G_TRY(launch_order(W, nq, np, sh.M, L.qstats, 1, st));
+  if (!final_on_gpu) {
+    // cold probes go to the CPU (Section 4.3.1)
+    G_TRY(hipMemcpyAsync(ix->h_ncold, W.n_cold, (size_t)nq * 4, hipMemcpyDeviceToHost, st));
+    G_TRY(hipMemcpyAsync(ix->h_cold, W.cold, (size_t)nq * np * 4, hipMemcpyDeviceToHost, st));
+    G_TRY(hipMemcpyAsync(ix->h_qbmax, W.qbmax, (size_t)nq * 4, hipMemcpyDeviceToHost, st));
+    if (!a.q_host)
+      G_TRY(hipMemcpyAsync(ix->h_queries, dq, (size_t)nq * sh.d * 4, hipMemcpyDeviceToHost, st));
+    if (ev_route) G_TRY(hipEventRecord(ev_route, st));
+  }
+  if (c.any_resident) {
+    // ---- stage 3: scan + top-k ----
+    const int slices = pick_slices(ix, nq);
+    int64_t *oid = nullptr;
+    float *od = nullptr;
+    if (final_on_gpu) {
+      oid = a.out_device ? a.out_ids : W.out_ids;
+      od = a.out_device ? a.out_dists : W.out_dists;
+    }
+    G_TRY(mark(IVF_STAGE_SCAN));
+    G_TRY(launch_scan(sh, L, W, nq, np, slices, k, oid, od, st));
+    G_TRY(mark(IVF_STAGE_MERGE));
+    if (slices > 1) G_TRY(launch_merge(sh, W, nq, slices, k, oid, od, st));
+    G_TRY(mark(IVF_N_STAGES));
+    if (!final_on_gpu) {
+      G_TRY(hipMemcpyAsync(ix->h_reskey, W.res_key, (size_t)nq * k * 4, hipMemcpyDeviceToHost, st));
+      G_TRY(hipMemcpyAsync(ix->h_resid, W.res_id, (size_t)nq * k * 8, hipMemcpyDeviceToHost, st));
+      G_TRY(hipMemcpyAsync(ix->h_lutmax, W.lutmax, (size_t)nq * 4, hipMemcpyDeviceToHost, st));
+    }
+  }
+  keep_timing();
+  return IVF_OK;
+#undef G_TRY
+}
+
+// Final result of query q of a hybrid batch: the device's partial top-k (if any
+// cluster is resident) merged with the CPU scan of its cold probes.  cpu_e is the
+// table exponent the CPU scan used (only read when cpu is non-NULL).  Returns
+// false if the CPU and the device disagree on the exponent.
+bool finish_query(const ivf_index *ix, const HostIndexView &view, bool any_resident,
+                         int64_t q, int k, const HostCand *cpu, int cpu_e, int64_t *ids,
+                         float *dists) {
+  std::vector<HostCand> gpu((size_t)k), fin((size_t)k);
+  for (int r = 0; r < k; ++r) {
+    if (any_resident) gpu[r] = HostCand{ix->h_reskey[q * k + r], ix->h_resid[q * k + r]};
+    else gpu[r] = HostCand{kKeyInvalid, -1};
+  }
+  int e = 0;
+  if (any_resident) {
+    float mx;
+    memcpy(&mx, &ix->h_lutmax[q], 4);
+    e = lut_exponent(mx, view.M, ix->h_qbmax[q], view.pv ? view.pv_max : 0.0f);
+  }
+  const HostCand *res = gpu.data();
+  bool ok = true;
+  if (cpu) {
+    if (any_resident && cpu_e != e) ok = false;
+    e = cpu_e;
+    merge_topk(gpu.data(), cpu, k, fin.data());
+    res = fin.data();
+  }
+  emit_results(ix, res, k, e, ids, dists);
+  return ok;
+}
+
+static int search_device(ivf_index *ix, const SearchArgs &a) {
+  const int nq = (int)a.nq, k = a.k;
+  const int np = a.nprobe;
+  hipStream_t st = a.st;
+
+  {
+    std::lock_guard<std::mutex> lk(ix->mu);
+    if (ix->dispatch_active)
+      return fail(IVF_EBUSY, "an asynchronous batch is still in flight on this index");
+  }
+  BatchCtx ctx;
+  int rc = begin_batch(ix, st, &ctx);
+  if (rc < 0) return rc;
+  const BatchWs &W = ix->L.ws[ctx.slot];
+  const bool final_on_gpu = ctx.all_resident;
+  const bool any_resident = ctx.any_resident;
+  rc = enqueue_gpu(ix, a, ctx, final_on_gpu, nullptr);
+  if (rc < 0) {
+    (void)hipStreamSynchronize(st);
+    end_batch(ix, ctx, st, false);
+    return rc;
+  }
+#define S_TRY(expr)                                                                        \
+  do {                                                                                     \
+    hipError_t _e = (expr);                                                                \
+    if (_e != hipSuccess) {                                                                \
+      (void)hipStreamSynchronize(st);                                                      \
+      end_batch(ix, ctx, st, false);                                                       \
+      return fail(IVF_EDEVICE, "%s failed: %s (%s:%d)", #expr, hipGetErrorString(_e),      \
+                  __FILE__, __LINE__);                                                     \
+    }                                                                                      \
+  } while (0)
+
+  if (final_on_gpu) {
+    if (a.out_device) {
+      end_batch(ix, ctx, st, true);  // asynchronous: outputs valid when the stream gets here
+      return IVF_OK;
+    }
+    S_TRY(hipMemcpyAsync(ix->h_outids, W.out_ids, (size_t)nq * k * 8, hipMemcpyDeviceToHost, st));
+    S_TRY(hipMemcpyAsync(ix->h_outd, W.out_dists, (size_t)nq * k * 4, hipMemcpyDeviceToHost, st));
+    S_TRY(hipStreamSynchronize(st));
+    end_batch(ix, ctx, st, false);
+    memcpy(a.out_ids, ix->h_outids, (size_t)nq * k * 8);
+    memcpy(a.out_dists, ix->h_outd, (size_t)nq * k * 4);
+    return IVF_OK;
+  }
+
+  // ---- hybrid: cold probes on the CPU, then merge (Sections 4.3.1, 4.3.2) ----
+  S_TRY(hipStreamSynchronize(st));
+  end_batch(ix, ctx, st, false);
+  const float *hq = a.q_host ? a.q_host : ix->h_queries;
+
+  const HostIndexView view = host_view(ix);
+  std::vector<int> bad(1, 0);
+  parallel_for(nq, [&](int64_t q) {
+    const int nc = ix->h_ncold[q];
+    std::vector<HostCand> cpu;
+    int e_cpu = 0;
+    if (nc > 0 || !any_resident) {
+      std::vector<int32_t> lut((size_t)view.M * 256);
+      cpu.resize((size_t)k);
+      const float *qv = hq + (size_t)q * view.d;
+      e_cpu = cpu_build_lut(view, qv, ix->h_qbmax[q], lut.data());
+      cpu_scan_lists(view, lut.data(), e_cpu, qv, ix->h_cold + (size_t)q * np, nc, k, cpu.data());
+    }
+    if (!finish_query(ix, view, any_resident, q, k, cpu.empty() ? nullptr : cpu.data(), e_cpu,
+                      &ix->h_outids[(size_t)q * k], &ix->h_outd[(size_t)q * k]))
+      __atomic_store_n(&bad[0], 1, __ATOMIC_RELAXED);
+  });
+  if (bad[0])
+    return fail(IVF_EDEVICE, "internal: CPU and GPU lookup-table scales disagree");
+  if (a.out_device) {
+    HIP_TRY(hipMemcpyAsync(a.out_ids, ix->h_outids, (size_t)nq * k * 8, hipMemcpyHostToDevice, st));
+    HIP_TRY(hipMemcpyAsync(a.out_dists, ix->h_outd, (size_t)nq * k * 4, hipMemcpyHostToDevice, st));
+    HIP_TRY(hipStreamSynchronize(st));
+  } else {
+    memcpy(a.out_ids, ix->h_outids, (size_t)nq * k * 8);
+    memcpy(a.out_dists, ix->h_outd, (size_t)nq * k * 4);
+  }
+  return IVF_OK;
+#undef S_TRY
+}
+
+int check_search_args(const ivf_index *ix, const void *queries, int64_t nq, int32_t nprobe,
+                             int32_t k, const void *out_ids, const void *out_dists) {
+  if (!ix) return fail(IVF_EINVAL, "index is NULL");
+  if (nq < 0) return fail(IVF_EINVAL, "nq is negative");
+  if (nprobe < 1) return fail(IVF_EINVAL, "nprobe must be >= 1");
+  if (k < 1) return fail(IVF_EINVAL, "k must be >= 1");
+  if (nq == 0) return IVF_OK;
+  if (!queries || !out_ids || !out_dists) return fail(IVF_EINVAL, "NULL buffer");
+  if (ix->has_dev) {
+    if (nq > ix->desc.max_nq) return fail(IVF_EINVAL, "nq %lld exceeds max_nq %d", (long long)nq, ix->desc.max_nq);
+    if (k > ix->desc.max_k) return fail(IVF_EINVAL, "k %d exceeds max_k %d", k, ix->desc.max_k);
+  } else if (k > kMaxK) {
+    return fail(IVF_EINVAL, "k %d exceeds %d", k, kMaxK);
+  }
+  return IVF_OK;
+}
+
+// A caller's probe list: ids below nlist (negative = no probe), distinct within a query.
+int check_probe_list(const ivf_index *ix, const int32_t *probe, int64_t nq, int nprobe) {
+  std::vector<int32_t> row((size_t)nprobe);
+  for (int64_t q = 0; q < nq; ++q) {
+    int n = 0;
+    for (int p = 0; p < nprobe; ++p) {
+      const int32_t c = probe[q * nprobe + p];
+      if (c >= ix->sh.nlist) return fail(IVF_EINVAL, "probe id %d out of range", c);
+      if (c >= 0) row[n++] = c;
+    }
+    std::sort(row.begin(), row.begin() + n);
+    if (std::adjacent_find(row.begin(), row.begin() + n) != row.begin() + n)
+      return fail(IVF_EINVAL, "query %lld lists a cluster twice", (long long)q);
+  }
+  return IVF_OK;
+}
+
+extern "C" int ivf_search_batch(ivf_index_t *ix, const float *queries, int64_t nq, int32_t nprobe,
+                                int32_t k, int64_t *out_ids, float *out_dists) {
+  int rc = check_search_args(ix, queries, nq, nprobe, k, out_ids, out_dists);
+  if (rc != IVF_OK || nq == 0) return rc;
+  if (!ix->has_dev)
+    return fail(IVF_EDEVICE, "host-only index: the coarse quantizer needs the device "
+                             "(use ivf_search_batch_probes)");
+  SearchArgs a;
+  a.q_host = queries;
+  a.nq = nq;
+  a.nprobe = std::min<int32_t>(nprobe, ix->sh.nlist);
+  if (a.nprobe > ix->desc.max_nprobe)
+    return fail(IVF_EINVAL, "nprobe %d exceeds max_nprobe %d", a.nprobe, ix->desc.max_nprobe);
+  a.k = k;
+  a.out_ids = out_ids;
+  a.out_dists = out_dists;
+  a.st = ix->own_stream;
+  return search_device(ix, a);
+}
+
+extern "C" int ivf_search_batch_dev(ivf_index_t *ix, const float *queries, int64_t nq,
+                                    int32_t nprobe, int32_t k, int64_t *out_ids, float *out_dists,
+                                    void *stream) {
+  int rc = check_search_args(ix, queries, nq, nprobe, k, out_ids, out_dists);
+  if (rc != IVF_OK || nq == 0) return rc;
+  if (!ix->has_dev) return fail(IVF_EDEVICE, "host-only index: no device search");
+  SearchArgs a;
+  a.q_dev = queries;
+  a.nq = nq;
+  a.nprobe = std::min<int32_t>(nprobe, ix->sh.nlist);
+  if (a.nprobe > ix->desc.max_nprobe)
+    return fail(IVF_EINVAL, "nprobe %d exceeds max_nprobe %d", a.nprobe, ix->desc.max_nprobe);
+  a.k = k;
+  a.out_ids = out_ids;
+  a.out_dists = out_dists;
+  a.out_device = true;
+  a.st = (hipStream_t)stream;
+  return search_device(ix, a);
+}
+
+extern "C" int ivf_coarse_probe_dev(ivf_index_t *ix, const float *queries, int64_t nq,
+                                    int32_t nprobe, int32_t *out_probe, void *stream) {
+  if (!ix) return fail(IVF_EINVAL, "index is NULL");
+  if (!ix->has_dev) return fail(IVF_EDEVICE, "host-only index: no device coarse quantizer");
+  if (nq < 0 || nprobe < 1) return fail(IVF_EINVAL, "bad nq / nprobe");
+  if (nq == 0) return IVF_OK;
+  if (!queries || !out_probe) return fail(IVF_EINVAL, "NULL buffer");
+  if (nq > ix->desc.max_nq) return fail(IVF_EINVAL, "nq exceeds max_nq");
+  if (nprobe > kMaxNprobe) return fail(IVF_EINVAL, "nprobe exceeds %d", kMaxNprobe);
+  hipStream_t st = (hipStream_t)stream;
+  int slot = 0;
+  {
+    std::lock_guard<std::mutex> lk(ix->mu);
+    int rc = acquire_slot_locked(ix, st, &slot);
+    if (rc < 0) return rc;
+  }
+  const BatchWs &W = ix->L.ws[slot];
+  HIP_TRY(launch_split_f16(queries, (size_t)nq, ix->sh.d, W.q_parts, W.q_exp, st));
+  HIP_TRY(launch_coarse_gemm(ix->sh, W.q_parts, W.q_exp, (int)nq, ix->L.cent_parts, ix->L.cent_exp,
+                             ix->L.cent_norm,
+                             W.scores, st));
+  HIP_TRY(launch_coarse_select(ix->sh, W.scores, (int)nq, nprobe, nprobe, out_probe, st));
+  return IVF_OK;
+}
+
+extern "C" int ivf_search_batch_probes(ivf_index_t *ix, const float *queries, int64_t nq,
+                                       const int32_t *probe, int32_t nprobe, int32_t k,
+                                       int64_t *out_ids, float *out_dists) {
+  int rc = check_search_args(ix, queries, nq, nprobe, k, out_ids, out_dists);
+  if (rc != IVF_OK || nq == 0) return rc;
+  if (!probe) return fail(IVF_EINVAL, "probe is NULL");
+  if (ix->has_dev && nprobe > ix->desc.max_nprobe)
+    return fail(IVF_EINVAL, "nprobe %d exceeds max_nprobe %d", nprobe, ix->desc.max_nprobe);
+  rc = check_probe_list(ix, probe, nq, nprobe);
+  if (rc != IVF_OK) return rc;
+  if (!ix->has_dev) return search_host_only(ix, queries, nq, probe, nprobe, k, out_ids, out_dists);
+  SearchArgs a;
+  a.q_host = queries;
+  a.probe_host = probe;
+  a.nq = nq;
+  a.nprobe = nprobe;
+  a.k = k;
+  a.out_ids = out_ids;
+  a.out_dists = out_dists;
+  a.st = ix->own_stream;
+  return search_device(ix, a);
+}
+
