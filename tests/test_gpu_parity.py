@@ -515,3 +515,35 @@ def test_four_bit_codes(pkg, oracle, name, m, residual):
     ids, dist, _ = index.search_batch_async(q, spec.nprobe, spec.k).wait()
     assert np.array_equal(ids, base[0]) and np.array_equal(dist, base[1])
     index.close()
+
+
+def test_batches_in_flight_on_three_streams(pkg, oracle):
+    """The index keeps two per-batch workspaces, each tied to the stream that used it
+    last: batches issued back to back on different streams (a third stream makes the
+    least recently used workspace change hands) must all return what a single-stream
+    search returns, with different batch sizes and k per stream."""
+    import torch
+    spec, ix, q, calib = _case("T_IP96")
+    index = pkg.IvfIndex(ix, max_nq=256, max_nprobe=ix.nlist, max_k=128)
+    index.load_partition(np.arange(ix.nlist, dtype=np.int32))
+    qd = torch.from_numpy(q).cuda()
+    parts = [qd[:17].contiguous(), qd[17:].contiguous(), qd.contiguous()]
+    ks = [spec.k, 100, 1]
+    ref = []
+    for p, k in zip(parts, ks):
+        i, d = index.search_batch_dev(p, spec.nprobe, k)
+        torch.cuda.synchronize()
+        ref.append((i.cpu().numpy(), d.cpu().numpy()))
+    streams = [torch.cuda.Stream() for _ in range(3)]
+    outs = [(torch.empty((p.shape[0], k), dtype=torch.int64, device="cuda"),
+             torch.empty((p.shape[0], k), dtype=torch.float32, device="cuda"))
+            for p, k in zip(parts, ks)]
+    torch.cuda.synchronize()
+    for rep in range(6):
+        for j in (0, 1, 2, 1, 0, 2):
+            index.search_batch_dev(parts[j], spec.nprobe, ks[j], outs[j][0], outs[j][1], streams[j])
+    torch.cuda.synchronize()
+    for j in range(3):
+        assert np.array_equal(outs[j][0].cpu().numpy(), ref[j][0])
+        assert np.array_equal(outs[j][1].cpu().numpy(), ref[j][1])
+    index.close()
