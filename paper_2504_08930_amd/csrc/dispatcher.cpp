@@ -61,7 +61,8 @@ static void dispatcher_main(ivf_ticket *t) {
   const int32_t *cold = t->device ? ix->h_cold : t->own_probe.data();
   auto expected = [&](int q) { return t->device ? ix->h_ncold[q] : np; };
 
-  std::vector<std::thread> workers;
+  std::vector<std::thread> workers;  // only if the worker pool is taken
+  bool pooled = false;
   std::atomic<int64_t> next(0);
   std::vector<int32_t> order((size_t)nq);
   if (gpu_ok) {
@@ -97,7 +98,9 @@ static void dispatcher_main(ivf_ticket *t) {
       }
     };
     const int nt = (int)std::min<int64_t>(cpu_threads(), nq);
-    for (int i = 0; i < nt; ++i) workers.emplace_back(work);
+    pooled = WorkerPool::get().start(nt, work);
+    if (!pooled)
+      for (int i = 0; i < nt; ++i) workers.emplace_back(work);
   }
 
   // the GPU's completion flag: its partial results are on the host
@@ -138,6 +141,7 @@ static void dispatcher_main(ivf_ticket *t) {
       ++n_done;
     }
   }
+  if (pooled) WorkerPool::get().wait();
   for (auto &w : workers) w.join();
   {
     std::lock_guard<std::mutex> lk(t->mu);

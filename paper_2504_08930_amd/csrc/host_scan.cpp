@@ -5,6 +5,8 @@
 
 #include <algorithm>
 #include <atomic>
+#include <condition_variable>
+#include <mutex>
 #include <thread>
 
 #include "lut_quant.h"
@@ -25,6 +27,80 @@ int cpu_threads() {
   return n;
 }
 
+struct WorkerPool::Impl {
+  std::mutex mu;
+  std::condition_variable cv_work, cv_done;
+  std::vector<std::thread> threads;
+  std::function<void()> job;
+  uint64_t generation = 0;
+  int want = 0, started = 0, finished = 0;
+  bool busy = false, stop = false;
+};
+
+WorkerPool &WorkerPool::get() {
+  static WorkerPool pool;
+  return pool;
+}
+
+WorkerPool::WorkerPool() : impl_(new Impl()), n_threads_(cpu_threads()) {
+  impl_->threads.reserve((size_t)n_threads_);
+  for (int i = 0; i < n_threads_; ++i) impl_->threads.emplace_back([this] { worker(); });
+}
+
+WorkerPool::~WorkerPool() {
+  {
+    std::lock_guard<std::mutex> lk(impl_->mu);
+    impl_->stop = true;
+  }
+  impl_->cv_work.notify_all();
+  for (auto &t : impl_->threads) t.join();
+  delete impl_;
+}
+
+void WorkerPool::worker() {
+  Impl &p = *impl_;
+  uint64_t seen = 0;
+  std::unique_lock<std::mutex> lk(p.mu);
+  for (;;) {
+    p.cv_work.wait(lk, [&] { return p.stop || (p.generation != seen && p.started < p.want); });
+    if (p.stop) return;
+    seen = p.generation;
+    p.started += 1;
+    std::function<void()> job = p.job;
+    lk.unlock();
+    job();
+    lk.lock();
+    p.finished += 1;
+    if (p.finished == p.want) p.cv_done.notify_all();
+  }
+}
+
+bool WorkerPool::start(int n, std::function<void()> fn) {
+  Impl &p = *impl_;
+  n = std::min(n, n_threads_);
+  if (n <= 0) return false;
+  {
+    std::lock_guard<std::mutex> lk(p.mu);
+    if (p.busy) return false;
+    p.busy = true;
+    p.job = std::move(fn);
+    p.want = n;
+    p.started = 0;
+    p.finished = 0;
+    p.generation += 1;
+  }
+  p.cv_work.notify_all();
+  return true;
+}
+
+void WorkerPool::wait() {
+  Impl &p = *impl_;
+  std::unique_lock<std::mutex> lk(p.mu);
+  p.cv_done.wait(lk, [&] { return p.finished == p.want; });
+  p.job = nullptr;
+  p.busy = false;
+}
+
 void parallel_for(int64_t n, const std::function<void(int64_t)> &fn) {
   if (n <= 0) return;
   int nt = (int)std::min<int64_t>(cpu_threads(), n);
@@ -40,7 +116,14 @@ void parallel_for(int64_t n, const std::function<void(int64_t)> &fn) {
       fn(i);
     }
   };
-  std::vector<std::thread> th;
+  // the caller is one of the nt threads
+  WorkerPool &pool = WorkerPool::get();
+  if (pool.start(nt - 1, work)) {
+    work();
+    pool.wait();
+    return;
+  }
+  std::vector<std::thread> th;  // the pool is taken: threads of our own
   th.reserve(nt - 1);
   for (int t = 1; t < nt; ++t) th.emplace_back(work);
   work();

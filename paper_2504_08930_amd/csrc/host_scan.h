@@ -37,6 +37,29 @@ int cpu_threads();
 // Run fn(i) for i in [0, n) on up to cpu_threads() threads.
 void parallel_for(int64_t n, const std::function<void(int64_t)> &fn);
 
+// The library's worker threads: created once (cpu_threads() of them) and parked
+// between batches, so a small hybrid batch does not pay for thread creation.
+// One job at a time; a caller that finds the pool taken runs its job on threads
+// of its own.
+class WorkerPool {
+ public:
+  static WorkerPool &get();
+  // Start fn() on n pool threads (n is clamped to the pool size) and return at
+  // once; false (nothing started) if another job holds the pool.
+  bool start(int n, std::function<void()> fn);
+  // Block until the job given to start() has finished on every thread; frees the pool.
+  void wait();
+  int size() const { return n_threads_; }
+  ~WorkerPool();
+
+ private:
+  WorkerPool();
+  void worker();
+  struct Impl;
+  Impl *impl_;
+  int n_threads_;
+};
+
 // Per-vector term |r|^2 + 2 c.r of residual-encoded L2 for every stored vector
 // (r = decoded residual, c = centroid of its list); returns the largest |pv|.
 float cpu_residual_pv(const HostIndexView &ix, int64_t n_total, float *pv);
