@@ -82,8 +82,11 @@ IVF_HD inline int lut_exponent(float maxabs, int M, float max_bias = 0.0f, float
   return e;
 }
 
+// Total: a value that is not finite or does not fit (only possible for a query
+// that is itself not finite) quantizes to 0 on host and device alike.
 IVF_HD inline int lut_quantize(float v, int e) {
-  return (int)__builtin_rintf(__builtin_ldexpf(v, e));
+  const float r = __builtin_rintf(__builtin_ldexpf(v, e));
+  return __builtin_fabsf(r) < 2147483520.0f ? (int)r : 0;
 }
 
 // Residual encoding: partial sum over elements i = lane, lane + 64, ... of the

@@ -547,3 +547,25 @@ def test_batches_in_flight_on_three_streams(pkg, oracle):
         assert np.array_equal(outs[j][0].cpu().numpy(), ref[j][0])
         assert np.array_equal(outs[j][1].cpu().numpy(), ref[j][1])
     index.close()
+
+
+@pytest.mark.parametrize("name", ["T_L2", "T_IP96"])
+def test_non_finite_query_does_not_disturb_the_batch(pkg, oracle, name):
+    """A query of NaNs (or infinities) gets an unspecified answer, but every kernel must
+    finish and the other queries of the batch must be served exactly as without it."""
+    import torch
+    spec, ix, q, calib = _case(name)
+    index = pkg.IvfIndex(ix, max_nq=256, max_nprobe=ix.nlist, max_k=128)
+    index.load_partition(np.arange(ix.nlist, dtype=np.int32)[::2].copy())     # hybrid
+    ref_i, ref_d = index.search_batch(q, spec.nprobe, spec.k)
+    for bad_value in (np.nan, np.inf):
+        qb = q.copy()
+        qb[3, :] = bad_value
+        qb[7, 0] = -bad_value if np.isinf(bad_value) else bad_value
+        ids, dist = index.search_batch(qb, spec.nprobe, spec.k)
+        keep = np.ones(q.shape[0], bool)
+        keep[[3, 7]] = False
+        assert np.array_equal(ids[keep], ref_i[keep]) and np.array_equal(dist[keep], ref_d[keep])
+        ids2, dist2, _ = index.search_batch_async(qb, spec.nprobe, spec.k).wait()
+        assert np.array_equal(ids2[keep], ref_i[keep]) and np.array_equal(dist2[keep], ref_d[keep])
+    index.close()
