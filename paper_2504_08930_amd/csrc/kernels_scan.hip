@@ -710,6 +710,7 @@ __global__ __launch_bounds__(NW * 64) void k_scan(ScanParams P) {
                                              (size_t)NW * CAP * sizeof(long long));
   int *s_thr = buf_key_all + NW * CAP;
   int *s_total = s_thr + 1;
+  int *s_next = s_thr + 2;  // next tile (position in the block's range) nobody has taken yet
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -886,56 +887,89 @@ __global__ __launch_bounds__(NW * 64) void k_scan(ScanParams P) {
   };
 
   {
-    int t = t_begin + w;
+    // The first two tiles of every wave are fixed (positions w and w + NW of the
+    // block's range); after that a wave takes the next position nobody has taken
+    // from a counter in LDS, so all waves run out of work at about the same time
+    // whatever their tiles cost (waves of a SIMD do not get equal issue time, and
+    // a tile that feeds the candidate buffer costs more than one that does not).
+    const int span = t_end - t_begin;
+    const float4 *lut_src = reinterpret_cast<const float4 *>(P.lut + (size_t)q * 256 * M);
+    constexpr int kVec = 256 * M / 4;
+    constexpr int kIter = (kVec + NW * 64 - 1) / (NW * 64);
+    constexpr int kBatch = 4;  // table loads in flight per thread: one round trip per batch
+    // the first batch of table loads goes out before the (dependent) work-list loads
+    float4 lv[kBatch];
+#pragma unroll
+    for (int b = 0; b < kBatch; ++b) {
+      const int idx = tid + b * (NW * 64);
+      if (b < kIter && idx < kVec) lv[b] = lut_src[idx];
+    }
+    int t = w;  // position of the current tile in the block's range
     TileRef cur{0, 0, 0, 0};
     uint4 ca[M / 16];
     float pa = 0.0f;
-    if (t < t_end) {
-      cur = locate(t);
+    if (t < span) {
+      cur = locate(t_begin + t);
       load_tile(cur, ca, pa);
     }
     // ---- stage the query's table in LDS as fixed point, code-major (the first
     // tile's loads are already in flight) ----
     {
-      const float4 *src = reinterpret_cast<const float4 *>(P.lut + (size_t)q * 256 * M);
-      constexpr int kVec = 256 * M / 4;
-      for (int idx = tid; idx < kVec; idx += NW * 64) {
-        const float4 v = src[idx];
-        const int flat = idx * 4;
-        const int j = flat / M;
-        const int m0 = flat % M;  // 4 consecutive sub-quantizers of one code (M % 4 == 0)
-        const int4 keys = make_int4(lut_quantize(v.x, e), lut_quantize(v.y, e),
-                                    lut_quantize(v.z, e), lut_quantize(v.w, e));
-        const int gi = m0 / 32, r = m0 % 32;  // the four share a 32-wide group
-        int *row = tab + (gi >> 1) * (G::kTableBytes / 4) + j * 64 + (gi & 1) * 32;
-        *reinterpret_cast<int4 *>(row + r) = keys;
-        if (G::kRem && gi == G::kFull)  // 16-wide group: second replica
-          *reinterpret_cast<int4 *>(row + r + 16) = keys;
+#pragma unroll
+      for (int i0 = 0; i0 < kIter; i0 += kBatch) {
+        if (i0 > 0) {
+#pragma unroll
+          for (int b = 0; b < kBatch; ++b) {
+            const int idx = tid + (i0 + b) * (NW * 64);
+            if (i0 + b < kIter && idx < kVec) lv[b] = lut_src[idx];
+          }
+        }
+#pragma unroll
+        for (int b = 0; b < kBatch; ++b) {
+          const int idx = tid + (i0 + b) * (NW * 64);
+          if (i0 + b < kIter && idx < kVec) {
+            const int flat = idx * 4;
+            const int j = flat / M;
+            const int m0 = flat % M;  // 4 consecutive sub-quantizers of one code (M % 4 == 0)
+            const int4 keys = make_int4(lut_quantize(lv[b].x, e), lut_quantize(lv[b].y, e),
+                                        lut_quantize(lv[b].z, e), lut_quantize(lv[b].w, e));
+            const int gi = m0 / 32, r = m0 % 32;  // the four share a 32-wide group
+            int *row = tab + (gi >> 1) * (G::kTableBytes / 4) + j * 64 + (gi & 1) * 32;
+            *reinterpret_cast<int4 *>(row + r) = keys;
+            if (G::kRem && gi == G::kFull)  // 16-wide group: second replica
+              *reinterpret_cast<int4 *>(row + r + 16) = keys;
+          }
+        }
       }
       if (tid == 0) {
         *s_thr = kKeyInvalid;
         *s_total = 0;
+        *s_next = 2 * NW;
       }
     }
     __syncthreads();
-    while (t < t_end) {
-      const int tn = t + NW;
+    int tn = t + NW;  // the wave's second tile
+    while (t < span) {
       TileRef nxt{0, 0, 0, 0};
       uint4 cb[M / 16];
       float pb = 0.0f;
-      if (tn < t_end) {
-        nxt = locate(tn);
+      if (tn < span) {
+        nxt = locate(t_begin + tn);
         load_tile(nxt, cb, pb);
       } else {
 #pragma unroll
         for (int u = 0; u < M / 16; ++u) cb[u] = make_uint4(0, 0, 0, 0);
       }
+      // take the position after that; the answer is only needed after this tile's work
+      int taken = 0;
+      if (lane == 0) taken = atomicAdd(s_next, 1);
       process(cur, ca, pa);
 #pragma unroll
       for (int u = 0; u < M / 16; ++u) ca[u] = cb[u];
       pa = pb;
       cur = nxt;
       t = tn;
+      tn = __builtin_amdgcn_readfirstlane(taken);
     }
   }
 
@@ -954,12 +988,35 @@ __global__ __launch_bounds__(NW * 64) void k_scan(ScanParams P) {
   long long *fid = reinterpret_cast<long long *>(smem + (size_t)kMaxCand * 12);
   int *fkey = reinterpret_cast<int *>(smem + (size_t)kMaxCand * 12 + (size_t)kFin * 8);
   {
+    // Some wave holds k candidates at or below s_thr (the smallest k-th key any wave
+    // found), so nothing above it can be among the block's k best: only the
+    // candidates at or below it are gathered, a few more than k in all.
+    const int thr = *s_thr;
+    int kk[E];
+    long long ii[E];
+    bool keep[E];
+    int mine = 0;
+#pragma unroll
+    for (int e2 = 0; e2 < E; ++e2) {
+      const int idx = lane + 64 * e2;
+      const bool v = idx < cnt;
+      kk[e2] = v ? bkey[idx] : kKeyInvalid;
+      ii[e2] = v ? bid[idx] : 0;
+      keep[e2] = v && kk[e2] <= thr;
+      mine += __popcll(__ballot(keep[e2]));
+    }
     int base = 0;
-    if (lane == 0) base = atomicAdd(s_total, cnt);
+    if (lane == 0) base = atomicAdd(s_total, mine);
     base = __builtin_amdgcn_readfirstlane(base);
-    for (int i = lane; i < cnt; i += 64) {
-      mkey[base + i] = bkey[i];
-      mid[base + i] = bid[i];
+#pragma unroll
+    for (int e2 = 0; e2 < E; ++e2) {
+      const unsigned long long mask = __ballot(keep[e2]);
+      if (keep[e2]) {
+        const int o = base + __popcll(mask & lt_mask);
+        mkey[o] = kk[e2];
+        mid[o] = ii[e2];
+      }
+      base += __popcll(mask);
     }
   }
   __syncthreads();
