@@ -26,6 +26,8 @@
 //    does not change the sum.
 #include <hip/hip_runtime.h>
 
+#include <type_traits>
+
 #include "internal.h"
 #include "lut_quant.h"
 
@@ -289,6 +291,7 @@ __global__ __launch_bounds__(256) void k_route(
   if (lane == 0) {
     qbmax[q] = bmax;
     gp[ng] = tiles;
+    gp[stride] = tiles;  // also at a fixed place: readable without knowing ng
     g_n[q] = ng;
     n_cold[q] = nc;
     q_vecs[q] = (int32_t)vecs;
@@ -748,7 +751,7 @@ __global__ __launch_bounds__(NW * 64) void k_scan(ScanParams P) {
   const int32_t *gpre = P.g_prefix + (size_t)q * (P.probe_stride + 1);
   const int32_t *gbase = P.g_base + (size_t)q * P.probe_stride;
   const int32_t *glen = P.g_len + (size_t)q * P.probe_stride;
-  const int T = gpre[ng];
+  const int T = gpre[P.probe_stride];  // total tiles (the router keeps a copy in the last slot)
   const int t_begin = (int)((long long)T * s / P.slices);
   const int t_end = (int)((long long)T * (s + 1) / P.slices);
 
@@ -761,13 +764,18 @@ __global__ __launch_bounds__(NW * 64) void k_scan(ScanParams P) {
     while (t >= win_end) {  // wave-uniform
       win_base += 64;
       const int p = win_base + lane;
+      // the loads only need p inside the row, not the number of entries: they go
+      // out together with the load of ng, whose value then masks them
+      const bool can = p < P.probe_stride;
+      const int l_pre = can ? gpre[p] : 0, l_tile = can ? gbase[p] : 0, l_len = can ? glen[p] : 0;
+      const float l_bias = (RES && can) ? gbias[p] : 0.0f;
       const bool in = p < ng;
-      w_pre = in ? gpre[p] : 0x7fffffff;
-      w_tile = in ? gbase[p] : 0;
-      w_len = in ? glen[p] : 0;
-      if (RES) w_bias = in ? lut_quantize(gbias[p], e) : 0;
+      w_pre = in ? l_pre : 0x7fffffff;
+      w_tile = in ? l_tile : 0;
+      w_len = in ? l_len : 0;
+      if (RES) w_bias = in ? lut_quantize(l_bias, e) : 0;
       const int last = min(win_base + 64, ng);
-      win_end = gpre[last];
+      win_end = last == ng ? T : gpre[last];
     }
     const unsigned long long mask = __ballot(w_pre <= t);
     const int pl = max(__popcll(mask) - 1, 0);  // last probe of the window starting at or before t
@@ -896,7 +904,8 @@ __global__ __launch_bounds__(NW * 64) void k_scan(ScanParams P) {
     const float4 *lut_src = reinterpret_cast<const float4 *>(P.lut + (size_t)q * 256 * M);
     constexpr int kVec = 256 * M / 4;
     constexpr int kIter = (kVec + NW * 64 - 1) / (NW * 64);
-    constexpr int kBatch = 4;  // table loads in flight per thread: one round trip per batch
+    // table loads in flight per thread (one round trip per batch): all of them if few
+    constexpr int kBatch = kIter <= 6 ? kIter : 4;
     // the first batch of table loads goes out before the (dependent) work-list loads
     float4 lv[kBatch];
 #pragma unroll
@@ -1022,32 +1031,33 @@ __global__ __launch_bounds__(NW * 64) void k_scan(ScanParams P) {
   __syncthreads();
   if (w != 0) return;
   const int n = *s_total;
-  // keys of all gathered candidates in registers, order-preserving unsigned form
+  // Keys of the gathered candidates in registers (order-preserving unsigned form), RR
+  // per lane: bitwise search for the k-th smallest key, then everything at or below
+  // it moves to (fkey, fid).  Usually only a few more than k candidates arrive here.
   constexpr int R = kMaxCand / 64;
-  const int ne = (n + 63) >> 6;
-  uint32_t rk[R];
-#pragma unroll
-  for (int e2 = 0; e2 < R; ++e2) {
-    const int i = e2 * 64 + lane;
-    rk[e2] = (e2 < ne && i < n) ? ((uint32_t)mkey[i] ^ 0x80000000u) : 0xffffffffu;
-  }
-  uint32_t kth_u = 0xffffffffu;
-  if (n > k) {
-    uint32_t prefix = 0;
-    for (int bit = 31; bit >= 0; --bit) {
-      const uint32_t cand = prefix | (1u << bit);
-      int c = 0;
-#pragma unroll
-      for (int e2 = 0; e2 < R; ++e2)
-        if (e2 < ne) c += __popcll(__ballot(rk[e2] < cand));
-      if (c < k) prefix = cand;
-    }
-    kth_u = prefix;
-  }
   int nf = 0;
+  auto select_kth = [&](auto rr_tag) {
+    constexpr int RR = decltype(rr_tag)::value;
+    uint32_t rk[RR];
 #pragma unroll
-  for (int e2 = 0; e2 < R; ++e2) {
-    if (e2 < ne) {
+    for (int e2 = 0; e2 < RR; ++e2) {
+      const int i = e2 * 64 + lane;
+      rk[e2] = i < n ? ((uint32_t)mkey[i] ^ 0x80000000u) : 0xffffffffu;
+    }
+    uint32_t kth_u = 0xffffffffu;
+    if (n > k) {
+      uint32_t prefix = 0;
+      for (int bit = 31; bit >= 0; --bit) {
+        const uint32_t cand = prefix | (1u << bit);
+        int c = 0;
+#pragma unroll
+        for (int e2 = 0; e2 < RR; ++e2) c += __popcll(__ballot(rk[e2] < cand));
+        if (c < k) prefix = cand;
+      }
+      kth_u = prefix;
+    }
+#pragma unroll
+    for (int e2 = 0; e2 < RR; ++e2) {
       const int i = e2 * 64 + lane;
       const bool keep = i < n && rk[e2] <= kth_u;
       const unsigned long long mask = __ballot(keep);
@@ -1058,7 +1068,9 @@ __global__ __launch_bounds__(NW * 64) void k_scan(ScanParams P) {
       }
       nf += __popcll(mask);
     }
-  }
+  };
+  if (n <= 128) select_kth(std::integral_constant<int, 2>{});
+  else select_kth(std::integral_constant<int, R>{});
   wave_sync();
   const size_t obase = ((size_t)q * P.slices + s) * k;
   // rank-th best of this block: a partial result for k_merge, or, with one
