@@ -299,6 +299,30 @@ def test_c2_config_hybrid(pkg, oracle):
     index.close()
 
 
+def test_maximum_nprobe_and_k(pkg, oracle):
+    """The largest supported search parameters (nprobe = 2048 lists of 4096, k = 128) on
+    the 1M config: several 64-probe windows per work list, the 8-wave scan variant,
+    half of the database scanned per query."""
+    import torch
+    spec, ix, q, calib = _case("C2")
+    index = pkg.IvfIndex(ix, max_nq=32, max_nprobe=2048, max_k=128)
+    index.load_partition(np.arange(ix.nlist, dtype=np.int32))
+    qs = np.ascontiguousarray(q[:16])
+    qd = torch.from_numpy(qs).cuda()
+    ids_d, dist_d = index.search_batch_dev(qd, 2048, 128)
+    torch.cuda.synchronize()
+    ids, dist = ids_d.cpu().numpy(), dist_d.cpu().numpy()
+    probe = index.coarse_probe_dev(qd, 2048).cpu().numpy()
+    n_coarse, n_amb = _check_search(oracle, ix, qs, 2048, 128, ids, dist, probe)
+    _say(f"C2 nprobe=2048 k=128: coarse-ambiguous {n_coarse}, id-ambiguous {n_amb} of 16")
+    assert n_coarse <= 1 and n_amb <= 2
+    # hybrid with every other cluster resident: identical
+    index.load_partition(np.arange(ix.nlist, dtype=np.int32)[::2].copy())
+    hyb = index.search_batch(qs, 2048, 128)
+    assert np.array_equal(hyb[0], ids) and np.array_equal(hyb[1], dist)
+    index.close()
+
+
 def test_c3_config_full_size(pkg, oracle):
     """The 10M x 768 configuration the benchmark times (nq=1024, nprobe=64, k=10, one scan
     block per query): oracle parity on a sample of queries, and equality of the
