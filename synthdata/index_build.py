@@ -4,8 +4,10 @@ PQ codes with a trained code-book).
 
 This is input preparation for the search path, not part of it: the oracle
 and the HIP library both *consume* the arrays produced here.  torch matmuls
-are used freely (CPU or GPU).  Choices the paper leaves open (init, sample
-sizes, empty clusters) are fixed here and listed in the design doc.
+are used freely (CPU or GPU).  Choices the paper leaves open are fixed here:
+k-means is initialised from a seeded random sample, trained on the first
+64 * nlist vectors (rounded up to a generator chunk), PQ on at most 65536 of
+them; an empty cluster keeps its centroid.
 """
 from dataclasses import dataclass
 
