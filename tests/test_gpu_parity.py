@@ -214,6 +214,54 @@ def test_migration_keeps_results(pkg, oracle):
     index.close()
 
 
+def _shuffled_within_lists(ix, seed):
+    """The same index with the vectors of every list stored in another order."""
+    import dataclasses
+    rng = np.random.default_rng(seed)
+    order = np.arange(ix.n)
+    for c in range(ix.nlist):
+        a, b = int(ix.list_offsets[c]), int(ix.list_offsets[c + 1])
+        order[a:b] = a + rng.permutation(b - a)
+    return dataclasses.replace(ix, codes=np.ascontiguousarray(ix.codes[order]),
+                               ids=np.ascontiguousarray(ix.ids[order]))
+
+
+@pytest.mark.parametrize("name", ["T_L2", "T_IP96"])
+def test_layout_transforms_leave_results_unchanged(pkg, oracle, name):
+    """Where a cluster sits in the device arena and where a vector sits in its
+    list are storage choices (Section 4.2.3 places clusters freely): placing the
+    clusters in another order, and storing each list's vectors in another
+    order, both give the same ids and distances, ties included (they break by
+    id, never by position)."""
+    spec, ix, q, calib = _case(name)
+    index = pkg.IvfIndex(ix, max_nq=256, max_nprobe=ix.nlist, max_k=128)
+    index.load_partition(np.arange(ix.nlist, dtype=np.int32))
+    ref = index.search_batch(q, spec.nprobe, 100)
+    _check_search(oracle, ix, q, spec.nprobe, 100, ref[0], ref[1])
+    rng = np.random.default_rng(11)
+    for trial in range(2):
+        _say(f"{name} arena order {trial}")
+        # a random half placed first, the rest admitted behind it in two moves:
+        # no cluster keeps the tile position that loading all at once gave it
+        perm = rng.permutation(ix.nlist).astype(np.int32)
+        h = ix.nlist // 2
+        index.load_partition(perm[:h])
+        for part in (perm[h + h // 2:], perm[h: h + h // 2]):
+            index.migrate_clusters([], part)
+            index.migrate_poll(wait=True)
+        assert index.resident_info() == (ix.nlist, ix.n)
+        got = index.search_batch(q, spec.nprobe, 100)
+        assert np.array_equal(got[0], ref[0]) and np.array_equal(got[1], ref[1])
+    index.close()
+    _say(f"{name} vectors shuffled within lists")
+    ix2 = _shuffled_within_lists(ix, 12)
+    index = pkg.IvfIndex(ix2, max_nq=256, max_nprobe=ix.nlist, max_k=128)
+    index.load_partition(np.arange(ix.nlist - 1, -1, -1, dtype=np.int32))
+    got = index.search_batch(q, spec.nprobe, 100)
+    assert np.array_equal(got[0], ref[0]) and np.array_equal(got[1], ref[1])
+    index.close()
+
+
 def test_cluster_region_too_small(pkg):
     spec, ix, q, calib = _case("T_IP")
     index = pkg.IvfIndex(ix, max_nq=64, max_nprobe=16, max_k=16, resident_vectors=ix.n // 4)

@@ -133,6 +133,30 @@ def test_host_only_batch_invariance_and_negative_probes(case, oracle):
     assert np.array_equal(a_i, b_i) and np.array_equal(a_d, b_d)
 
 
+def test_host_only_vector_order_within_lists_is_irrelevant(case, lib, oracle):
+    """Storing each list's vectors in another order changes neither ids nor
+    distances (equal distances break by id, never by position), in the library
+    and in the oracle alike."""
+    import dataclasses
+    spec, ix, q, index = case
+    rng = np.random.default_rng(21)
+    order = np.arange(ix.n)
+    for c in range(ix.nlist):
+        a, b = int(ix.list_offsets[c]), int(ix.list_offsets[c + 1])
+        order[a:b] = a + rng.permutation(b - a)
+    ix2 = dataclasses.replace(ix, codes=np.ascontiguousarray(ix.codes[order]),
+                              ids=np.ascontiguousarray(ix.ids[order]))
+    probe, _, _ = oracle.coarse(ix.metric, ix.centroids, q, spec.nprobe)
+    ref = index.search_batch_probes(q, probe, 50)
+    other = lib.IvfIndex(ix2, spec.nq, spec.nprobe, 64, host_only=True)
+    got = other.search_batch_probes(q, probe, 50)
+    other.close()
+    assert np.array_equal(got[0], ref[0]) and np.array_equal(got[1], ref[1])
+    o1 = oracle.scan(ix.metric, ix.codebooks, ix.list_offsets, ix.codes, ix.ids, q, probe, 50)
+    o2 = oracle.scan(ix.metric, ix.codebooks, ix.list_offsets, ix2.codes, ix2.ids, q, probe, 50)
+    assert np.array_equal(o1[0], o2[0]) and np.array_equal(o1[1], o2[1])
+
+
 def test_host_only_counters(case, oracle):
     spec, ix, q, index = case
     index.hit_stats(reset=True)
