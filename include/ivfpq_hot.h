@@ -107,6 +107,11 @@ size_t ivf_index_arena_bytes(const ivf_index_desc_t *desc, int64_t resident_vect
  * centroids, codebooks, mapping tables, counters, batch workspace and the
  * cluster region inside it.  No cluster is resident after creation.
  *
+ * The codes, ids, centroids and codebooks of `desc` stay borrowed; the index
+ * adds host copies of its own only in derived layouts (codebooks element-major;
+ * codes column-major when the byte-plane CPU scan is used, see
+ * ivf_host_scan_form).
+ *
  * dev_arena == NULL creates a host-only index: every cluster is non-resident
  * and only ivf_search_batch_probes(), ivf_hit_stats() and destroy are valid
  * (anything that needs the device returns IVF_EDEVICE).
@@ -263,6 +268,17 @@ int ivf_migrate_stats(ivf_index_t *index, uint64_t *bytes_copied, double *copy_m
 
 /* Number of currently resident clusters and vectors (either may be NULL). */
 int ivf_resident_info(ivf_index_t *index, int32_t *n_clusters, int64_t *n_vectors);
+
+/*
+ * Which form of the CPU scan of non-resident clusters (Section 4.3.1) this
+ * index uses: 0 = the plain loop over each vector's code bytes, 1 = the
+ * byte-plane scan (CPUs with AVX-512 VBMI; the index then holds a column-major
+ * copy of the codes, N * code-bytes more host memory, made at creation).  Both
+ * add the same integers and return identical results.  The environment
+ * variable IVF_HOST_SCAN=scalar, read by ivf_index_create, selects form 0.
+ * Negative on error.
+ */
+int ivf_host_scan_form(const ivf_index_t *index);
 
 /*
  * Tuning and instrumentation.  scan_slices: blocks per query in the ADC scan

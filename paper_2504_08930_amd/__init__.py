@@ -59,3 +59,7 @@ def ivf_migrate_clusters(index, evict, admit, side_stream=None):
 
 def ivf_migrate_poll(index, wait=False):
     return index.migrate_poll(wait)
+
+
+def ivf_host_scan_form(index):
+    return index.host_scan_form()

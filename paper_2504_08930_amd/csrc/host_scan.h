@@ -27,9 +27,15 @@ struct HostIndexView {
   const float *pv;              // [N] per-vector term (residual-encoded L2 only), else NULL
   float pv_max;                 // largest |pv|
   const float *codebooks;       // [msub][2^nbits][dsub]
+  const float *codebooks_t;     // [msub][dsub][2^nbits]: the same, element-major (cpu_transpose_codebooks)
   const int64_t *list_offsets;  // [nlist+1]
   const uint8_t *codes;         // [N][M]
   const int64_t *ids;           // [N]
+  // column-major copy of the codes for the byte-plane scan, or NULL: list c starts at
+  // codes_t + list_toff[c]; row m (byte m of every vector of the list, zero-padded
+  // to a multiple of 64 vectors) follows row m - 1
+  const uint8_t *codes_t = nullptr;
+  const int64_t *list_toff = nullptr;  // [nlist+1], in bytes
 };
 
 int cpu_threads();
@@ -68,11 +74,22 @@ float cpu_residual_pv(const HostIndexView &ix, int64_t n_total, float *pv);
 // 0 without residual encoding.
 float cpu_max_bias(const HostIndexView &ix, const float *q, const int32_t *clusters, int n);
 
+// Element-major copy of the codebooks, [msub][dsub][2^nbits] floats, which lets
+// cpu_build_lut run its lanes along the codeword index.
+void cpu_transpose_codebooks(const HostIndexView &ix, float *out);
+
 // Fixed-point table of one query: lut[m*256 + j], one column per code byte (for
 // 4-bit codes entry j of column m is the float sum of the entries of the two
 // sub-quantizers packed in that byte, formed before quantization); max_bias: largest |bias| among
 // ALL of the query's probes (resident or not).  Returns the scale exponent.
 int cpu_build_lut(const HostIndexView &ix, const float *q, float max_bias, int32_t *lut);
+
+// True if this CPU runs the byte-plane scan (AVX-512 VBMI) and the environment
+// does not ask for the plain loop (IVF_HOST_SCAN=scalar, read at every call).
+bool cpu_has_plane_scan();
+// Size in bytes of the column-major code copy; fills list_toff[nlist+1] if given.
+int64_t cpu_transposed_bytes(const HostIndexView &ix, int64_t *list_toff);
+void cpu_transpose_codes(const HostIndexView &ix, const int64_t *list_toff, uint8_t *out);
 
 // Scan the listed clusters for one query with the table and exponent from
 // cpu_build_lut; writes k candidates, best first, padded with (kKeyInvalid, -1).

@@ -33,10 +33,18 @@ HostIndexView host_view(const ivf_index *ix) {
   v.pv = ix->pv.empty() ? nullptr : ix->pv.data();
   v.pv_max = ix->pv_max;
   v.codebooks = ix->desc.codebooks;
+  v.codebooks_t = ix->cb_t.data();
   v.list_offsets = ix->desc.list_offsets;
   v.codes = ix->desc.codes;
   v.ids = ix->desc.ids;
+  v.codes_t = ix->codes_t.empty() ? nullptr : ix->codes_t.data();
+  v.list_toff = ix->list_toff.empty() ? nullptr : ix->list_toff.data();
   return v;
+}
+
+extern "C" int ivf_host_scan_form(const ivf_index_t *ix) {
+  if (!ix) return fail(IVF_EINVAL, "index is NULL");
+  return ix->codes_t.empty() ? 0 : 1;
 }
 
 // Bytes of one stored code = columns of the scan's lookup table.
@@ -195,6 +203,18 @@ extern "C" int ivf_index_create(const ivf_index_desc_t *desc, void *dev_arena, s
     ix->h_len[c] = (int32_t)(desc->list_offsets[c + 1] - desc->list_offsets[c]);
   ix->hc_hits.assign(desc->nlist, 0);
   ix->versions.emplace_back();
+  ix->cb_t.resize((size_t)desc->d << desc->nbits);
+  {
+    HostIndexView v = host_view(ix);
+    cpu_transpose_codebooks(v, ix->cb_t.data());
+    if (cpu_has_plane_scan() && n_total > 0) {
+      // column-major copy of the codes for the CPU's byte-plane scan of cold clusters
+      ix->list_toff.resize((size_t)desc->nlist + 1);
+      const int64_t bytes = cpu_transposed_bytes(v, ix->list_toff.data());
+      ix->codes_t.resize((size_t)bytes);
+      cpu_transpose_codes(v, ix->list_toff.data(), ix->codes_t.data());
+    }
+  }
   if (desc->by_residual && desc->metric == IVF_METRIC_L2 && n_total > 0) {
     ix->pv.resize((size_t)n_total);
     HostIndexView v = host_view(ix);

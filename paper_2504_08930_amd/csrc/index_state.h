@@ -145,6 +145,10 @@ struct ivf_index {
   uint64_t n_migrations = 0;
   std::vector<hipEvent_t> event_pool;
 
+  std::vector<float> cb_t;  // codebooks, element-major (host table construction)
+  std::vector<uint8_t> codes_t;    // codes, column-major per list (byte-plane CPU scan), or empty
+  std::vector<int64_t> list_toff;  // start of each list in codes_t
+
   // residual encoding: per-vector term of L2 (host copy; also uploaded with the tiles)
   std::vector<float> pv;
   float pv_max = 0.0f;

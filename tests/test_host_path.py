@@ -157,6 +157,48 @@ def test_host_only_vector_order_within_lists_is_irrelevant(case, lib, oracle):
     assert np.array_equal(o1[0], o2[0]) and np.array_equal(o1[1], o2[1])
 
 
+@pytest.mark.parametrize("name,residual,nbits,m", [("T_L2", False, 8, None), ("T_L2", True, 8, None),
+                                                  ("T_IP96", True, 8, None), ("T_IP", False, 4, 64)])
+def test_host_scan_forms_agree_bit_for_bit(lib, oracle, monkeypatch, name, residual, nbits, m):
+    """The CPU scan has two forms: the plain loop over a vector's code bytes and,
+    on CPUs with AVX-512 VBMI, the byte-plane scan over column-major codes.  Both
+    add the same integers, so ids and distances are identical; two long lists
+    make the byte-plane scan cross its 2048-vector pass and end on a ragged
+    group."""
+    import dataclasses
+    spec = SPECS[name]
+    ix = build_index(spec, by_residual=residual, nbits=nbits, m=m)
+    if not residual:
+        # regroup the stored vectors into three lists, two of them longer than one pass
+        cut = [0, 2048 + 77, ix.n - 1, ix.n]
+        ix = dataclasses.replace(ix, nlist=3, centroids=np.ascontiguousarray(ix.centroids[:3]),
+                                 list_offsets=np.asarray(cut, np.int64))
+    q, _ = make_queries(spec, mixture_centers(spec))
+    q = q.numpy()
+    nprobe = min(spec.nprobe, ix.nlist)
+    rng = np.random.default_rng(3)
+    probe = np.stack([rng.permutation(ix.nlist)[:nprobe] for _ in range(q.shape[0])]).astype(np.int32)
+    got = {}
+    for form in ("scalar", "planes"):
+        if form == "scalar":
+            monkeypatch.setenv("IVF_HOST_SCAN", "scalar")
+        else:
+            monkeypatch.delenv("IVF_HOST_SCAN", raising=False)
+        index = lib.IvfIndex(ix, spec.nq, nprobe, 64, host_only=True)
+        if form == "scalar":
+            assert index.host_scan_form() == 0
+        elif "avx512_vbmi" in open("/proc/cpuinfo").read():
+            assert index.host_scan_form() == 1
+        got[form] = [index.search_batch_probes(q, probe, k) for k in (1, 10, 64)]
+        index.close()
+    for a, b in zip(got["scalar"], got["planes"]):
+        assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])
+    ref_i, ref_d = oracle.scan(ix.metric, ix.codebooks, ix.list_offsets, ix.codes, ix.ids, q, probe,
+                               64 + 16, residual_centroids=ix.centroids if residual else None)
+    ids, dist = got["planes"][2]
+    assert compare_topk(ids, dist, ref_i, ref_d, 64, scale_S(ix.metric, q)) <= max(1, q.shape[0] // 20)
+
+
 def test_host_only_counters(case, oracle):
     spec, ix, q, index = case
     index.hit_stats(reset=True)
