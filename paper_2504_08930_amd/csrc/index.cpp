@@ -169,6 +169,7 @@ extern "C" void ivf_index_destroy(ivf_index_t *ix) {
       for (int i = 0; i <= IVF_N_STAGES; ++i)
         if (r.valid[i]) (void)hipEventDestroy(r.ev[i]);
     free_host_buffers(ix);
+    if (ix->ev_routed) (void)hipEventDestroy(ix->ev_routed);
     if (ix->own_stream) (void)hipStreamDestroy(ix->own_stream);
   }
   delete ix;
@@ -263,6 +264,8 @@ extern "C" int ivf_index_create(const ivf_index_desc_t *desc, void *dev_arena, s
   hipError_t e;
   if ((e = hipStreamCreateWithFlags(&ix->own_stream, hipStreamNonBlocking)) != hipSuccess)
     return bail(e, "hipStreamCreateWithFlags");
+  if ((e = hipEventCreateWithFlags(&ix->ev_routed, hipEventDisableTiming)) != hipSuccess)
+    return bail(e, "hipEventCreateWithFlags");
   const size_t nq = desc->max_nq, np = desc->max_nprobe, k = desc->max_k;
   if ((e = pinned_alloc(&ix->h_ncold, nq)) != hipSuccess ||
       (e = pinned_alloc(&ix->h_cold, nq * np)) != hipSuccess ||

@@ -131,6 +131,7 @@ struct ivf_index {
   bool dispatch_active = false; // an asynchronous batch owns the pinned host buffers
   DevLayout L;
   hipStream_t own_stream = nullptr;
+  hipEvent_t ev_routed = nullptr;  // bulk hybrid search: the cold probe lists are on the host
   std::mutex mu;
 
   std::vector<int32_t> h_map;      // published mapping table (host mirror)

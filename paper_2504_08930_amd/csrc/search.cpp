@@ -266,7 +266,7 @@ static int search_device(ivf_index *ix, const SearchArgs &a) {
   const BatchWs &W = ix->L.ws[ctx.slot];
   const bool final_on_gpu = ctx.all_resident;
   const bool any_resident = ctx.any_resident;
-  rc = enqueue_gpu(ix, a, ctx, final_on_gpu, nullptr);
+  rc = enqueue_gpu(ix, a, ctx, final_on_gpu, final_on_gpu ? nullptr : ix->ev_routed);
   if (rc < 0) {
     (void)hipStreamSynchronize(st);
     end_batch(ix, ctx, st, false);
@@ -298,25 +298,31 @@ static int search_device(ivf_index *ix, const SearchArgs &a) {
   }
 
   // ---- hybrid: cold probes on the CPU, then merge (Sections 4.3.1, 4.3.2) ----
-  S_TRY(hipStreamSynchronize(st));
-  end_batch(ix, ctx, st, false);
+  // The cold probe lists reach the host right after routing; the CPU scans them
+  // while the device scans the resident ones.
+  S_TRY(hipEventSynchronize(ix->ev_routed));
   const float *hq = a.q_host ? a.q_host : ix->h_queries;
 
   const HostIndexView view = host_view(ix);
-  std::vector<int> bad(1, 0);
+  std::vector<HostCand> cpu_res((size_t)nq * k);
+  std::vector<int> cpu_e((size_t)nq, 0);
   parallel_for(nq, [&](int64_t q) {
     const int nc = ix->h_ncold[q];
-    std::vector<HostCand> cpu;
-    int e_cpu = 0;
-    if (nc > 0 || !any_resident) {
-      std::vector<int32_t> lut((size_t)view.M * 256);
-      cpu.resize((size_t)k);
-      const float *qv = hq + (size_t)q * view.d;
-      e_cpu = cpu_build_lut(view, qv, ix->h_qbmax[q], lut.data());
-      cpu_scan_lists(view, lut.data(), e_cpu, qv, ix->h_cold + (size_t)q * np, nc, k, cpu.data());
-    }
-    if (!finish_query(ix, view, any_resident, q, k, cpu.empty() ? nullptr : cpu.data(), e_cpu,
-                      &ix->h_outids[(size_t)q * k], &ix->h_outd[(size_t)q * k]))
+    if (nc == 0 && any_resident) return;
+    thread_local std::vector<int32_t> lut;
+    lut.resize((size_t)view.M * 256);
+    const float *qv = hq + (size_t)q * view.d;
+    cpu_e[(size_t)q] = cpu_build_lut(view, qv, ix->h_qbmax[q], lut.data());
+    cpu_scan_lists(view, lut.data(), cpu_e[(size_t)q], qv, ix->h_cold + (size_t)q * np, nc, k,
+                   &cpu_res[(size_t)q * k]);
+  });
+  S_TRY(hipStreamSynchronize(st));  // the device's partial results are on the host
+  end_batch(ix, ctx, st, false);
+  std::vector<int> bad(1, 0);
+  parallel_for(nq, [&](int64_t q) {
+    const bool has_cpu = ix->h_ncold[q] > 0 || !any_resident;
+    if (!finish_query(ix, view, any_resident, q, k, has_cpu ? &cpu_res[(size_t)q * k] : nullptr,
+                      cpu_e[(size_t)q], &ix->h_outids[(size_t)q * k], &ix->h_outd[(size_t)q * k]))
       __atomic_store_n(&bad[0], 1, __ATOMIC_RELAXED);
   });
   if (bad[0])
