@@ -465,6 +465,11 @@ def main():
             roofline["traffic"], roofline["traffic_source"] = MEASURED_TRAFFIC[key]
         if read_ceiling is not None:
             roofline["streaming_read_GBs"] = read_ceiling
+        if resident_frac == 1.0:
+            # bytes of the distinct lists the batch touches (what a perfect cache would fetch)
+            pr = index.coarse_probe_dev(q, spec.nprobe).cpu().numpy()
+            lens = np.diff(ix.list_offsets)
+            roofline["unique_bytes"] = int(lens[np.unique(pr)].sum()) * int(ix.codes.shape[1])
 
     cpu_baseline = None
     parity = None
@@ -486,6 +491,23 @@ def main():
                         "cores": orc.num_threads(), "kind": "oracle",
                         "sample": f"{ns} of the {nq} queries, same index, nprobe={spec.nprobe}, "
                                   f"k={spec.k}; brute-force coarse + decode-and-distance in fp64"}
+        # the same on one thread, over a sixteenth of the sample
+        n1 = max(1, ns // 16)
+        all_threads = orc.num_threads()
+        orc.set_num_threads(1)
+        t1 = time.perf_counter()
+        p1, _, _ = orc.coarse(ix.metric, ix.centroids, qs[:n1], spec.nprobe)
+        orc.scan(ix.metric, ix.codebooks, ix.list_offsets, ix.codes, ix.ids, qs[:n1],
+                 np.ascontiguousarray(p1), spec.k, residual_centroids=res_cen)
+        cpu_baseline["value_1_thread"] = round(n1 / (time.perf_counter() - t1), 2)
+        cpu_baseline["sample_1_thread"] = f"the first {n1} of those queries"
+        try:
+            with open("/proc/cpuinfo") as f:
+                model = [l.split(":", 1)[1].strip() for l in f if l.startswith("model name")]
+            cpu_baseline["host_cpu"] = f"{model[0]} x {len(model)}" if model else None
+        except OSError:
+            cpu_baseline["host_cpu"] = None
+        orc.set_num_threads(all_threads)
         # parity of the timed configuration on the same sample
         got_i = out_ids.cpu().numpy()[sel]
         got_d = out_d.cpu().numpy()[sel]

@@ -239,6 +239,15 @@ int oracle_hit_stats(int nlist, int64_t nq, int nprobe, const int32_t *probe,
     return 0;
 }
 
+/* Limit the query loops to n threads (n >= 1); the arithmetic is untouched. */
+void oracle_set_num_threads(int n) {
+#ifdef _OPENMP
+    if (n >= 1) omp_set_num_threads(n);
+#else
+    (void)n;
+#endif
+}
+
 /* Threads the query loops run on (OpenMP over queries only). */
 int oracle_num_threads(void) {
 #ifdef _OPENMP

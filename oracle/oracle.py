@@ -42,6 +42,8 @@ def _load():
         lib.oracle_scan.restype = ctypes.c_int
         lib.oracle_hit_stats.argtypes = [ctypes.c_int, ctypes.c_int64, ctypes.c_int, P, P, P, P]
         lib.oracle_hit_stats.restype = ctypes.c_int
+        lib.oracle_set_num_threads.argtypes = [ctypes.c_int]
+        lib.oracle_set_num_threads.restype = None
         lib.oracle_num_threads.argtypes = []
         lib.oracle_num_threads.restype = ctypes.c_int
         _lib = lib
@@ -134,3 +136,8 @@ def hit_stats(nlist, probe, resident_mask):
 
 def num_threads() -> int:
     return int(_load().oracle_num_threads())
+
+
+def set_num_threads(n: int) -> None:
+    """Threads for the loops over queries (timing only; results do not depend on it)."""
+    _load().oracle_set_num_threads(int(n))
