@@ -156,7 +156,16 @@ __global__ __launch_bounds__(256) void k_bias(const float *__restrict__ q, int n
   const int c = probe[(size_t)qi * stride + p];
   float t = 0.0f;
   if (c >= 0) {
-    t = residual_bias_part(metric_ip, q + (size_t)qi * d, cent + (size_t)c * d, d, lane);
+    // residual_bias_part with 16-byte loads: the same elements in the same order
+    const float4 *q4 = reinterpret_cast<const float4 *>(q + (size_t)qi * d);
+    const float4 *c4 = reinterpret_cast<const float4 *>(cent + (size_t)c * d);
+    for (int i = lane; i < (d >> 2); i += 64) {
+      const float4 a = q4[i], b = c4[i];
+      t = residual_bias_step(metric_ip, a.x, b.x, t);
+      t = residual_bias_step(metric_ip, a.y, b.y, t);
+      t = residual_bias_step(metric_ip, a.z, b.z, t);
+      t = residual_bias_step(metric_ip, a.w, b.w, t);
+    }
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) t += __shfl_xor(t, o, 64);
     if (metric_ip) t = -t;

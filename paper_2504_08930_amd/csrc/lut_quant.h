@@ -89,20 +89,23 @@ IVF_HD inline int lut_quantize(float v, int e) {
   return __builtin_fabsf(r) < 2147483520.0f ? (int)r : 0;
 }
 
-// Residual encoding: partial sum over elements i = lane, lane + 64, ... of the
-// (query, centroid) term; the 64 partial sums are then combined by a fixed
-// xor-butterfly (residual_bias_combine), the same on host and device.
+// Residual encoding: the (query, centroid) term is the sum of 64 partial sums,
+// combined by a fixed xor-butterfly (residual_bias_combine), the same on host
+// and device.  Partial sum `lane` runs over the groups of four consecutive
+// elements 4*lane + 256*j (j = 0, 1, ...), each group in index order, so that on
+// the device a lane reads 16 bytes at a time and a wavefront 1 KB; d is a
+// multiple of 16 (it is a multiple of M, and M of 16).
+IVF_HD inline float residual_bias_step(int metric_ip, float q, float c, float acc) {
+  if (metric_ip) return __builtin_fmaf(q, c, acc);
+  const float diff = q - c;
+  return __builtin_fmaf(diff, diff, acc);
+}
+
 IVF_HD inline float residual_bias_part(int metric_ip, const float *q, const float *c, int d,
                                        int lane) {
   float acc = 0.0f;
-  for (int i = lane; i < d; i += 64) {
-    if (metric_ip) {
-      acc = __builtin_fmaf(q[i], c[i], acc);
-    } else {
-      const float diff = q[i] - c[i];
-      acc = __builtin_fmaf(diff, diff, acc);
-    }
-  }
+  for (int i = 4 * lane; i < d; i += 256)
+    for (int t = 0; t < 4; ++t) acc = residual_bias_step(metric_ip, q[i + t], c[i + t], acc);
   return acc;
 }
 
