@@ -431,6 +431,21 @@ def main():
         stage_ms = timed_steps(index, q, spec.nprobe, spec.k, min(args.steps, 20), 2, args.slices,
                                timing=1, n_streams=1)["stage_ms"]
 
+    # the host-pointer entry point on the same batch (PCIe both ways, one call at a
+    # time): context for callers that hold their queries on the host, never `value`
+    host_ptr = None
+    if resident_frac == 1.0 and not args.no_timing:
+        q_host = q.cpu().numpy()
+        index.set_tuning(scan_slices=args.slices, timing=0)
+        for _ in range(3):
+            index.search_batch(q_host, spec.nprobe, spec.k)
+        n_h = min(args.steps, 30)
+        t0 = time.perf_counter()
+        for _ in range(n_h):
+            index.search_batch(q_host, spec.nprobe, spec.k)
+        host_ptr = {"queries_per_s": round(nq * n_h / (time.perf_counter() - t0), 1), "steps": n_h,
+                    "note": "ivf_search_batch with pageable host queries and results, synchronous"}
+
     read_ceiling = None
     if args.calib_copy:
         from paper_2504_08930_amd.binding import ivf_calib_copy, ivf_calib_read
@@ -545,6 +560,7 @@ def main():
         "stage_ms_source": "timed region" if args.stage_timing else
                            "separate pass with events around every stage (not in the timed region)",
         "parity": parity,
+        "host_pointer_call": host_ptr,
         "index_build_s": round(build_s, 2),
         "load_partition_s": round(load_s, 3),
     }
