@@ -281,6 +281,19 @@ int ivf_resident_info(ivf_index_t *index, int32_t *n_clusters, int64_t *n_vector
 int ivf_host_scan_form(const ivf_index_t *index);
 
 /*
+ * How cluster copies (ivf_index_load_partition, ivf_migrate_clusters; Section
+ * 4.3.3) reach the device: 1 = the copy kernel reads the caller's codes and ids
+ * itself, which needs both arrays in pinned host memory that the device can
+ * address (hipHostMalloc, or a pinned torch tensor; codes 16-byte aligned) and
+ * fewer than 2^31 vectors; 0 = runs of vectors are copied with hipMemcpyAsync
+ * into the staging area and rearranged from there (any host memory; one copy
+ * call per run of consecutive vectors, so scattered clusters copy slowly).
+ * Decided by ivf_index_create; IVF_COPY_PATH=staged in its environment selects
+ * 0.  The resulting tiles are identical.  Negative on error.
+ */
+int ivf_copy_form(const ivf_index_t *index);
+
+/*
  * Tuning and instrumentation.  scan_slices: blocks per query in the ADC scan
  * (0 = automatic).  timing = 1 records HIP events around every stage of
  * subsequent searches on their stream, timing = 2 only around the ADC scan

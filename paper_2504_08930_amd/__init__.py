@@ -63,3 +63,7 @@ def ivf_migrate_poll(index, wait=False):
 
 def ivf_host_scan_form(index):
     return index.host_scan_form()
+
+
+def ivf_copy_form(index):
+    return index.copy_form()

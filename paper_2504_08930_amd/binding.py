@@ -21,7 +21,7 @@ EXPORTS = (
     "ivf_index_arena_bytes", "ivf_index_create", "ivf_index_destroy",
     "ivf_index_load_partition", "ivf_search_batch", "ivf_search_batch_dev",
     "ivf_coarse_probe_dev", "ivf_search_batch_probes", "ivf_hit_stats",
-    "ivf_migrate_clusters", "ivf_migrate_poll", "ivf_migrate_stats", "ivf_resident_info", "ivf_host_scan_form",
+    "ivf_migrate_clusters", "ivf_migrate_poll", "ivf_migrate_stats", "ivf_resident_info", "ivf_host_scan_form", "ivf_copy_form",
     "ivf_set_tuning", "ivf_stage_times", "ivf_calib_copy", "ivf_calib_read", "ivf_last_error",
     "ivf_model_hybrid_latency", "ivf_model_min_hit_rate", "ivf_model_hitrate_to_coverage",
     "ivf_model_partition_point",
@@ -89,6 +89,8 @@ def load_library():
     lib.ivf_resident_info.argtypes = [P, P, P]
     lib.ivf_host_scan_form.argtypes = [P]
     lib.ivf_host_scan_form.restype = ctypes.c_int
+    lib.ivf_copy_form.argtypes = [P]
+    lib.ivf_copy_form.restype = ctypes.c_int
     lib.ivf_set_tuning.argtypes = [P, I32, I32]
     lib.ivf_stage_times.argtypes = [P, P, P, P, ctypes.c_int]
     lib.ivf_calib_copy.argtypes = [P, P, SZ, P]
@@ -247,6 +249,9 @@ class IvfIndex:
 
     def host_scan_form(self):
         return _check(self._lib.ivf_host_scan_form(self._h))
+
+    def copy_form(self):
+        return _check(self._lib.ivf_copy_form(self._h))
 
     # ---- search ----
     def search_batch(self, queries, nprobe, k):

@@ -30,7 +30,7 @@ HostIndexView host_view(const ivf_index *ix) {
   v.metric_ip = ix->sh.metric_ip;
   v.by_residual = ix->desc.by_residual;
   v.centroids = ix->desc.centroids;
-  v.pv = ix->pv.empty() ? nullptr : ix->pv.data();
+  v.pv = ix->pv_host();
   v.pv_max = ix->pv_max;
   v.codebooks = ix->desc.codebooks;
   v.codebooks_t = ix->cb_t.data();
@@ -45,6 +45,11 @@ HostIndexView host_view(const ivf_index *ix) {
 extern "C" int ivf_host_scan_form(const ivf_index_t *ix) {
   if (!ix) return fail(IVF_EINVAL, "index is NULL");
   return ix->codes_t.empty() ? 0 : 1;
+}
+
+extern "C" int ivf_copy_form(const ivf_index_t *ix) {
+  if (!ix) return fail(IVF_EINVAL, "index is NULL");
+  return ix->zc_codes ? 1 : 0;
 }
 
 // Bytes of one stored code = columns of the scan's lookup table.
@@ -169,6 +174,7 @@ extern "C" void ivf_index_destroy(ivf_index_t *ix) {
       for (int i = 0; i <= IVF_N_STAGES; ++i)
         if (r.valid[i]) (void)hipEventDestroy(r.ev[i]);
     free_host_buffers(ix);
+    if (ix->pv_pinned) (void)hipHostFree(ix->pv_pinned);
     if (ix->ev_routed) (void)hipEventDestroy(ix->ev_routed);
     if (ix->own_stream) (void)hipStreamDestroy(ix->own_stream);
   }
@@ -266,6 +272,31 @@ extern "C" int ivf_index_create(const ivf_index_desc_t *desc, void *dev_arena, s
     return bail(e, "hipStreamCreateWithFlags");
   if ((e = hipEventCreateWithFlags(&ix->ev_routed, hipEventDisableTiming)) != hipSuccess)
     return bail(e, "hipEventCreateWithFlags");
+  if (!ix->pv.empty()) {  // the per-vector term moves to pinned memory
+    if ((e = pinned_alloc(&ix->pv_pinned, ix->pv.size())) != hipSuccess)
+      return bail(e, "hipHostMalloc");
+    memcpy(ix->pv_pinned, ix->pv.data(), ix->pv.size() * sizeof(float));
+    std::vector<float>().swap(ix->pv);
+  }
+  // Pinned host arrays can be read by the copy kernel itself.  A pointer the
+  // runtime does not know (pageable memory) is no error: such an index copies
+  // through the staging area.  IVF_COPY_PATH=staged forces that path.
+  const char *copy_path = getenv("IVF_COPY_PATH");
+  if (n_total > 0 && n_total < 0x7fffffff && !(copy_path && !strcmp(copy_path, "staged"))) {
+    void *dc = nullptr, *di = nullptr, *dp = nullptr;
+    bool ok = hipHostGetDevicePointer(&dc, const_cast<uint8_t *>(desc->codes), 0) == hipSuccess &&
+              hipHostGetDevicePointer(&di, const_cast<int64_t *>(desc->ids), 0) == hipSuccess &&
+              dc && di && ((uintptr_t)dc & 15) == 0 && ((uintptr_t)di & 7) == 0;
+    if (ok && ix->pv_pinned)
+      ok = hipHostGetDevicePointer(&dp, ix->pv_pinned, 0) == hipSuccess && dp;
+    if (ok) {
+      ix->zc_codes = static_cast<const uint8_t *>(dc);
+      ix->zc_ids = static_cast<const int64_t *>(di);
+      ix->zc_pv = static_cast<const float *>(dp);
+    } else {
+      (void)hipGetLastError();
+    }
+  }
   const size_t nq = desc->max_nq, np = desc->max_nprobe, k = desc->max_k;
   if ((e = pinned_alloc(&ix->h_ncold, nq)) != hipSuccess ||
       (e = pinned_alloc(&ix->h_cold, nq * np)) != hipSuccess ||

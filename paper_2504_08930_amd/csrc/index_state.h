@@ -151,8 +151,17 @@ struct ivf_index {
   std::vector<int64_t> list_toff;  // start of each list in codes_t
 
   // residual encoding: per-vector term of L2 (host copy; also uploaded with the tiles)
-  std::vector<float> pv;
+  std::vector<float> pv;        // host-only index
+  float *pv_pinned = nullptr;   // index with a device: pinned, so the copy kernel can read it
   float pv_max = 0.0f;
+  const float *pv_host() const { return pv_pinned ? pv_pinned : (pv.empty() ? nullptr : pv.data()); }
+
+  // Device-visible addresses of the caller's codes and ids (and of pv) when they lie
+  // in pinned host memory: cluster copies then read them from a kernel.  NULL: the
+  // copies go through hipMemcpyAsync and the staging area.
+  const uint8_t *zc_codes = nullptr;
+  const int64_t *zc_ids = nullptr;
+  const float *zc_pv = nullptr;
 
   // host-only counters (device-less index)
   std::vector<uint64_t> hc_hits;

@@ -28,7 +28,7 @@ enum {
 // One 64-vector tile to fill from staged raw codes/ids.
 struct TileDesc {
   int32_t dst_tile;   // tile index in the cluster region
-  int32_t src_vec;    // first vector in the staging chunk
+  int32_t src_vec;    // first vector: in the staging chunk, or in the caller's arrays (direct copy)
   int32_t n_valid;    // 1..64 (0 never emitted)
   int32_t pad;
 };
@@ -154,6 +154,12 @@ hipError_t launch_interleave(const uint8_t *stage_codes, const int64_t *stage_id
                              const float *stage_pv, const TileDesc *descs, int n_tiles, int M,
                              uint8_t *tile_codes, int64_t *tile_ids, float *tile_pv,
                              hipStream_t st);
+// the same, reading the caller's pinned host arrays directly (descs[].src_vec =
+// index of the tile's first vector in those arrays)
+hipError_t launch_interleave_direct(const uint8_t *host_codes, const int64_t *host_ids,
+                                    const float *host_pv, const TileDesc *descs, int n_tiles, int M,
+                                    uint8_t *tile_codes, int64_t *tile_ids, float *tile_pv,
+                                    hipStream_t st);
 
 bool scan_supports(int M, int k);
 

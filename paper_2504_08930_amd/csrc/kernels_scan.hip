@@ -649,6 +649,66 @@ __global__ __launch_bounds__(512) void k_interleave(const uint8_t *__restrict__ 
   }
 }
 
+// The same from PINNED HOST memory that the device can address: a tile's source
+// (up to 64 vectors x M bytes, contiguous in the caller's array) crosses the bus
+// as 16-byte loads, 1 KB per wavefront instruction, into LDS; the bytes are then
+// gathered from LDS (rows padded by one word: lane l's row starts in bank
+// l * (M/4 + 1), so the 64 lanes of a gather spread over the banks).
+// td.src_vec is the vector's index in the caller's arrays.
+__global__ __launch_bounds__(512) void k_interleave_direct(
+    const uint8_t *__restrict__ host_codes, const int64_t *__restrict__ host_ids,
+    const float *__restrict__ host_pv, const TileDesc *__restrict__ descs, int M,
+    uint8_t *__restrict__ tile_codes, int64_t *__restrict__ tile_ids,
+    float *__restrict__ tile_pv) {
+  __shared__ uint32_t rows[64 * (128 / 4 + 1)];
+  const TileDesc td = descs[blockIdx.x];
+  const int units = M / 16;
+  const int lane = threadIdx.x & 63;
+  const int u = threadIdx.x >> 6;
+  const int pitch = M / 4 + 1;  // words per padded row
+  const uint4 *g = reinterpret_cast<const uint4 *>(host_codes + (size_t)td.src_vec * M);
+  for (int i = threadIdx.x; i < td.n_valid * units; i += 512) {
+    const uint4 v = g[i];
+    const int r = i / units, c = (i - r * units) * 4;
+    uint32_t *d = rows + r * pitch + c;
+    d[0] = v.x;
+    d[1] = v.y;
+    d[2] = v.z;
+    d[3] = v.w;
+  }
+  __syncthreads();
+  const bool valid = lane < td.n_valid;
+  if (u < units) {
+    uint32_t w[4] = {0u, 0u, 0u, 0u};
+    if (valid) {
+      const uint8_t *row = reinterpret_cast<const uint8_t *>(rows + lane * pitch);
+#pragma unroll
+      for (int b = 0; b < 16; ++b) {
+        int m = src_subq(lane, 16 * u + b, M);
+        w[b >> 2] |= (uint32_t)row[m] << (8 * (b & 3));
+      }
+    }
+    uint4 *dst = reinterpret_cast<uint4 *>(tile_codes + (size_t)td.dst_tile * kTileVecs * M);
+    dst[(size_t)u * 64 + lane] = make_uint4(w[0], w[1], w[2], w[3]);
+  }
+  if (u == 0) {
+    const size_t src = (size_t)td.src_vec + lane;
+    tile_ids[(size_t)td.dst_tile * kTileVecs + lane] = valid ? host_ids[src] : -1;
+    if (tile_pv) tile_pv[(size_t)td.dst_tile * kTileVecs + lane] = valid ? host_pv[src] : 0.0f;
+  }
+}
+
+hipError_t launch_interleave_direct(const uint8_t *host_codes, const int64_t *host_ids,
+                                    const float *host_pv, const TileDesc *descs, int n_tiles, int M,
+                                    uint8_t *tile_codes, int64_t *tile_ids, float *tile_pv,
+                                    hipStream_t st) {
+  if (n_tiles <= 0) return hipSuccess;
+  if (M > 128 || M % 16 != 0) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(k_interleave_direct, dim3(n_tiles), dim3(512), 0, st, host_codes, host_ids,
+                     host_pv, descs, M, tile_codes, tile_ids, tile_pv);
+  return hipGetLastError();
+}
+
 hipError_t launch_interleave(const uint8_t *stage_codes, const int64_t *stage_ids,
                              const float *stage_pv, const TileDesc *descs, int n_tiles, int M,
                              uint8_t *tile_codes, int64_t *tile_ids, float *tile_pv,

@@ -49,6 +49,41 @@ static int enqueue_cluster_copies(ivf_index *ix, const std::vector<int32_t> &clu
   const DevLayout &L = ix->L;
   const size_t M = ix->sh.M;
   const bool with_pv = L.tile_pv != nullptr;
+  if (ix->zc_codes && (!with_pv || ix->zc_pv)) {
+    // the caller's arrays are pinned: the kernel reads them itself, only the tile
+    // descriptors pass through the staging area
+    const size_t desc_cap = std::min<size_t>(L.staging_bytes / sizeof(TileDesc), (size_t)1 << 20);
+    if (desc_cap == 0) return fail(IVF_ENOMEM, "staging area too small");
+    size_t n = 0;       // descriptors written
+    size_t sent = 0;    // descriptors already handed to a launch
+    auto flush = [&]() -> int {
+      if (n == sent) return IVF_OK;
+      HIP_TRY(hipMemcpyAsync(L.staging, descs + sent, (n - sent) * sizeof(TileDesc),
+                             hipMemcpyHostToDevice, st));
+      HIP_TRY(launch_interleave_direct(ix->zc_codes, ix->zc_ids, ix->zc_pv,
+                                       (const TileDesc *)L.staging, (int)(n - sent), (int)M,
+                                       L.tile_codes, L.tile_ids, L.tile_pv, st));
+      sent = n;
+      return IVF_OK;
+    };
+    for (size_t ci = 0; ci < clusters.size(); ++ci) {
+      const int32_t c = clusters[ci];
+      const int32_t len = ix->h_len[c];
+      const int64_t nt = tiles_of(len);
+      for (int64_t t = 0; t < nt; ++t) {
+        TileDesc &d = descs[n++];
+        d.dst_tile = (int32_t)(bases[ci] + t);
+        d.src_vec = (int32_t)(ix->desc.list_offsets[c] + t * kTileVecs);
+        d.n_valid = (int32_t)std::min<int64_t>(kTileVecs, len - t * kTileVecs);
+        d.pad = 0;
+        if (n - sent == desc_cap) {
+          int rc = flush();
+          if (rc != IVF_OK) return rc;
+        }
+      }
+    }
+    return flush();
+  }
   const size_t per_tile = kTileVecs * (M + 8 + (with_pv ? 4 : 0)) + sizeof(TileDesc);
   if (L.staging_bytes < per_tile + 2048) return fail(IVF_ENOMEM, "staging area too small");
   const int64_t tile_cap = (int64_t)((L.staging_bytes - 1024) / per_tile);
@@ -74,7 +109,7 @@ static int enqueue_cluster_copies(ivf_index *ix, const std::vector<int32_t> &clu
       HIP_TRY(hipMemcpyAsync(st_ids + (size_t)run_dst * 8, ix->desc.ids + run_src,
                              (size_t)run_len * 8, hipMemcpyHostToDevice, st));
       if (with_pv)
-        HIP_TRY(hipMemcpyAsync(st_pv + (size_t)run_dst * 4, ix->pv.data() + run_src,
+        HIP_TRY(hipMemcpyAsync(st_pv + (size_t)run_dst * 4, ix->pv_host() + run_src,
                                (size_t)run_len * 4, hipMemcpyHostToDevice, st));
       run_len = 0;
       return IVF_OK;

@@ -163,12 +163,18 @@ def test_residency_invariance_and_counters(pkg, oracle, name):
     index.close()
 
 
-def test_migration_keeps_results(pkg, oracle):
+@pytest.mark.parametrize("copy_form", ["direct", "staged"])
+def test_migration_keeps_results(pkg, oracle, monkeypatch, copy_form):
     """Evict / admit while searching (Section 4.3.3): results identical before,
-    during and after; clusters in transit are served by the CPU path."""
+    during and after; clusters in transit are served by the CPU path.  Run with
+    both forms of the cluster copy (kernel reads of the pinned host arrays, and
+    copies through the staging area)."""
     import torch
     spec, ix, q, calib = _case("T_IP96")
+    if copy_form == "staged":
+        monkeypatch.setenv("IVF_COPY_PATH", "staged")
     index = pkg.IvfIndex(ix, max_nq=256, max_nprobe=ix.nlist, max_k=128)
+    assert index.copy_form() == (1 if copy_form == "direct" else 0)
     rng = np.random.default_rng(5)
     perm = rng.permutation(ix.nlist).astype(np.int32)
     a, b = np.sort(perm[: ix.nlist // 3]), np.sort(perm[ix.nlist // 3: 2 * ix.nlist // 3])
@@ -476,15 +482,20 @@ def test_c4_config_full_size(pkg, oracle):
     _CACHE.pop("C4", None)
 
 
-@pytest.mark.parametrize("name", ["T_L2", "T_IP", "T_IP96"])
-def test_residual_encoding(pkg, oracle, name):
+@pytest.mark.parametrize("name,copy_form", [("T_L2", "direct"), ("T_L2", "staged"),
+                                            ("T_IP", "direct"), ("T_IP96", "direct")])
+def test_residual_encoding(pkg, oracle, monkeypatch, name, copy_form):
     """Residual-encoded codes (x - centroid): bias per (query, list) and, for L2, a
     per-vector term, all added in the integer domain.  Oracle parity and exact
-    independence of the resident set."""
+    independence of the resident set.  For L2 the per-vector term travels with
+    the codes, in either form of the cluster copy."""
     import torch
     spec, ix, q, calib = _case(name, by_residual=True)
     assert ix.by_residual
+    if copy_form == "staged":
+        monkeypatch.setenv("IVF_COPY_PATH", "staged")
     index = pkg.IvfIndex(ix, max_nq=256, max_nprobe=ix.nlist, max_k=128)
+    assert index.copy_form() == (1 if copy_form == "direct" else 0)
     full = np.arange(ix.nlist, dtype=np.int32)
     index.load_partition(full)
     qd = torch.from_numpy(q).cuda()
