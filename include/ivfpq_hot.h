@@ -298,6 +298,8 @@ int ivf_copy_form(const ivf_index_t *index);
  * (0 = automatic).  timing = 1 records HIP events around every stage of
  * subsequent searches on their stream, timing = 2 only around the ADC scan
  * (each recorded event costs a few microseconds of stream time), 0 none.
+ * The events of a batch are held until ivf_stage_times() reads them; after
+ * 8192 unread batches further batches are not timed.
  */
 int ivf_set_tuning(ivf_index_t *index, int32_t scan_slices, int32_t timing);
 

@@ -94,7 +94,9 @@ int begin_batch(ivf_index *ix, hipStream_t st, BatchCtx *c) {
   c->buf = ver.buf;
   c->all_resident = ix->resident_clusters == ix->sh.nlist;
   c->any_resident = ix->resident_clusters > 0;
-  c->timing = ix->timing;
+  // events of timed batches are kept until ivf_stage_times() reads them; a caller
+  // that never does stops collecting after this many batches instead of growing
+  c->timing = ix->trecs.size() < 8192 ? ix->timing : 0;
   return IVF_OK;
 }
 
