@@ -2,6 +2,7 @@
 oracle on the same seeded inputs.  Ids bit-exact except ties within tolerance;
 distances within 1e-4 * max(|d|, S) (tests/parity.py)."""
 import os
+import time
 
 import numpy as np
 import pytest
@@ -265,6 +266,59 @@ def test_layout_transforms_leave_results_unchanged(pkg, oracle, name):
     index.load_partition(np.arange(ix.nlist - 1, -1, -1, dtype=np.int32))
     got = index.search_batch(q, spec.nprobe, 100)
     assert np.array_equal(got[0], ref[0]) and np.array_equal(got[1], ref[1])
+    index.close()
+
+
+def test_search_thread_and_migration_thread(pkg, oracle):
+    """One thread searches without pause while another evicts and admits clusters
+    (the concurrency the boundary allows: one searcher, one migrator).  Every
+    search returns the same ids and distances as before the migrations began."""
+    import threading
+    import torch
+    spec, ix, q, calib = _case("T_IP96")
+    index = pkg.IvfIndex(ix, max_nq=256, max_nprobe=ix.nlist, max_k=128)
+    rng = np.random.default_rng(17)
+    perm = rng.permutation(ix.nlist).astype(np.int32)
+    third = ix.nlist // 3
+    a, b = np.sort(perm[:third]), np.sort(perm[third: 2 * third])
+    index.load_partition(a)
+    ref = index.search_batch(q, spec.nprobe, spec.k)
+    stop = threading.Event()
+    state = {"searches": 0, "bad": 0, "error": None}
+
+    def searcher():
+        try:
+            while not stop.is_set():
+                got = index.search_batch(q, spec.nprobe, spec.k)
+                state["searches"] += 1
+                if not (np.array_equal(got[0], ref[0]) and np.array_equal(got[1], ref[1])):
+                    state["bad"] += 1
+        except Exception as e:          # noqa: BLE001 - reported by the assert below
+            state["error"] = repr(e)
+
+    t = threading.Thread(target=searcher)
+    t.start()
+    side = torch.cuda.Stream()
+    try:
+        for step in range(6):
+            evict, admit = (a[: third // 2], b[: third // 2]) if step % 2 == 0 else \
+                           (b[: third // 2], a[: third // 2])
+            _say(f"concurrent migration {step}")
+            before = state["searches"]
+            index.migrate_clusters(evict, admit, side_stream=side)
+            index.migrate_poll(wait=True)
+            # let the searcher see the new table at least twice before the next move
+            deadline = time.time() + 30
+            while state["searches"] < before + 2 and state["error"] is None and time.time() < deadline:
+                time.sleep(0.001)
+    finally:
+        stop.set()
+        t.join(timeout=60)
+    _say(f"searches {state['searches']} bad {state['bad']} error {state['error']}")
+    assert not t.is_alive()
+    assert state["error"] is None, state["error"]
+    assert state["searches"] >= 12 and state["bad"] == 0, state
+    assert index.migrate_stats()["migrations"] == 6
     index.close()
 
 
