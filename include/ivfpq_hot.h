@@ -30,6 +30,11 @@
  *  - Results are ordered best first; ties on distance go to the smaller id.
  *    Missing results are id = -1, dist = +INF (L2) / -INF (IP).
  *  - Threading: one searcher thread plus one migrator thread per index.
+ *    The CPU scan of non-resident clusters runs on worker threads of the
+ *    library's own, created once per process: as many as the environment
+ *    variable IVF_CPU_THREADS says, else OMP_NUM_THREADS, else the hardware
+ *    concurrency.
+ *  - PQ codes may also be 4 bits per sub-quantizer (nbits = 4, two per byte).
  *  - Streams are raw hipStream_t values passed as void*; NULL is HIP's null
  *    stream.  All streams must have default priority.  The host-pointer entry
  *    points run on a stream the index owns.  The index holds two per-batch
