@@ -322,6 +322,36 @@ def test_search_thread_and_migration_thread(pkg, oracle):
     index.close()
 
 
+@pytest.mark.parametrize("code_bytes,metric,residual", [
+    (16, "ip", False), (32, "l2", True), (48, "l2", False), (64, "ip", True),
+    (96, "l2", True), (128, "l2", False), (128, "ip", False), (128, "l2", True), (128, "ip", True)])
+def test_every_code_size(pkg, oracle, code_bytes, metric, residual):
+    """One small index per supported code size (16 ... 128 bytes per vector, 8-bit
+    codes) so that every instantiation of the scan is compared with the oracle:
+    odd batch size, nprobe and k, ragged lists, all clusters resident and half of
+    them (identical results)."""
+    import torch
+    from synthdata.workloads import METRIC_IP, METRIC_L2, WorkloadSpec
+    ip = metric == "ip"
+    spec = WorkloadSpec(f"S{code_bytes}{metric}", 5_000, 2 * code_bytes, 24, 24, code_bytes,
+                        METRIC_IP if ip else METRIC_L2, ip, 37, 7, 33, 1.0 if ip else None, 1.0,
+                        kmeans_iters=3)
+    _say(f"code size {code_bytes} {metric} residual={residual}")
+    ix = build_index(spec, device="cuda", by_residual=residual)
+    q, _ = make_queries(spec, mixture_centers(spec, torch.device("cuda")))
+    q = q.cpu().numpy()
+    index = pkg.IvfIndex(ix, max_nq=64, max_nprobe=ix.nlist, max_k=64)
+    index.load_partition(np.arange(ix.nlist, dtype=np.int32))
+    probe = index.coarse_probe_dev(torch.from_numpy(q).cuda(), spec.nprobe).cpu().numpy()
+    full = index.search_batch(q, spec.nprobe, spec.k)
+    n_coarse, n_amb = _check_search(oracle, ix, q, spec.nprobe, spec.k, full[0], full[1], probe)
+    assert n_coarse <= 1 and n_amb <= 2
+    index.load_partition(np.arange(0, ix.nlist, 2, dtype=np.int32))
+    half = index.search_batch(q, spec.nprobe, spec.k)
+    assert np.array_equal(half[0], full[0]) and np.array_equal(half[1], full[1])
+    index.close()
+
+
 def test_cluster_region_too_small(pkg):
     spec, ix, q, calib = _case("T_IP")
     index = pkg.IvfIndex(ix, max_nq=64, max_nprobe=16, max_k=16, resident_vectors=ix.n // 4)

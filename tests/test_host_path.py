@@ -199,6 +199,37 @@ def test_host_scan_forms_agree_bit_for_bit(lib, oracle, monkeypatch, name, resid
     assert compare_topk(ids, dist, ref_i, ref_d, 64, scale_S(ix.metric, q)) <= max(1, q.shape[0] // 20)
 
 
+@pytest.mark.parametrize("code_bytes,metric", [(48, "l2"), (64, "ip"), (128, "l2"), (128, "ip")])
+def test_host_only_other_code_sizes(lib, oracle, monkeypatch, code_bytes, metric):
+    """Code sizes the named small workloads do not have, up to the largest (128
+    bytes: 128 columns x 255 is the most the byte-plane scan's 16-bit partial
+    sums must hold).  Both forms of the CPU scan, against each other and the oracle."""
+    from synthdata.workloads import METRIC_IP, METRIC_L2, WorkloadSpec
+    ip = metric == "ip"
+    spec = WorkloadSpec(f"H{code_bytes}{metric}", 4_000, 2 * code_bytes, 16, 16, code_bytes,
+                        METRIC_IP if ip else METRIC_L2, ip, 21, 5, 20, 1.0 if ip else None, 1.0,
+                        kmeans_iters=3)
+    ix = build_index(spec)
+    q, _ = make_queries(spec, mixture_centers(spec))
+    q = q.numpy()
+    probe, _, _ = oracle.coarse(ix.metric, ix.centroids, q, spec.nprobe)
+    got = {}
+    for form in ("scalar", "planes"):
+        if form == "scalar":
+            monkeypatch.setenv("IVF_HOST_SCAN", "scalar")
+        else:
+            monkeypatch.delenv("IVF_HOST_SCAN", raising=False)
+        index = lib.IvfIndex(ix, spec.nq, spec.nprobe, 64, host_only=True)
+        got[form] = index.search_batch_probes(q, probe, spec.k)
+        index.close()
+    assert np.array_equal(got["scalar"][0], got["planes"][0])
+    assert np.array_equal(got["scalar"][1], got["planes"][1])
+    ref_i, ref_d = oracle.scan(ix.metric, ix.codebooks, ix.list_offsets, ix.codes, ix.ids, q, probe,
+                               spec.k + 16)
+    assert compare_topk(got["planes"][0], got["planes"][1], ref_i, ref_d, spec.k,
+                        scale_S(ix.metric, q)) <= 1
+
+
 def test_host_only_counters(case, oracle):
     spec, ix, q, index = case
     index.hit_stats(reset=True)
