@@ -352,6 +352,34 @@ def test_every_code_size(pkg, oracle, code_bytes, metric, residual):
     index.close()
 
 
+@pytest.mark.parametrize("nbits,dsub", [(8, 1), (8, 3), (8, 4), (8, 6), (8, 16), (8, 24),
+                                        (4, 1), (4, 3), (4, 4), (4, 8)])
+def test_every_subvector_length(pkg, oracle, nbits, dsub):
+    """Sub-vector lengths with a table kernel of their own (2, 4, 8, 12, 16 for
+    8-bit codes; 1, 2, 4, 8 for 4-bit codes) and lengths that take the generic
+    one, on 16-byte codes: table entries and results against the oracle, and the
+    CPU scan's table against the device's through a half-resident search."""
+    import torch
+    from synthdata.workloads import METRIC_L2, WorkloadSpec
+    m = 16 if nbits == 8 else 32
+    spec = WorkloadSpec(f"D{nbits}x{dsub}", 4_000, m * dsub, 20, 20, m, METRIC_L2, False,
+                        29, 6, 17, None, 1.0, kmeans_iters=3)
+    _say(f"nbits {nbits} dsub {dsub}")
+    ix = build_index(spec, device="cuda", nbits=nbits, m=m)
+    q, _ = make_queries(spec, mixture_centers(spec, torch.device("cuda")))
+    q = q.cpu().numpy()
+    index = pkg.IvfIndex(ix, max_nq=32, max_nprobe=ix.nlist, max_k=32)
+    index.load_partition(np.arange(ix.nlist, dtype=np.int32))
+    probe = index.coarse_probe_dev(torch.from_numpy(q).cuda(), spec.nprobe).cpu().numpy()
+    full = index.search_batch(q, spec.nprobe, spec.k)
+    n_coarse, n_amb = _check_search(oracle, ix, q, spec.nprobe, spec.k, full[0], full[1], probe)
+    assert n_coarse <= 1 and n_amb <= 2
+    index.load_partition(np.arange(1, ix.nlist, 2, dtype=np.int32))
+    half = index.search_batch(q, spec.nprobe, spec.k)
+    assert np.array_equal(half[0], full[0]) and np.array_equal(half[1], full[1])
+    index.close()
+
+
 def test_cluster_region_too_small(pkg):
     spec, ix, q, calib = _case("T_IP")
     index = pkg.IvfIndex(ix, max_nq=64, max_nprobe=16, max_k=16, resident_vectors=ix.n // 4)
