@@ -70,12 +70,15 @@ enum {
 
 /*
  * Index description.  All pointers are HOST memory, borrowed until
- * ivf_index_destroy().  `codes` should be pinned for asynchronous copies.
+ * ivf_index_destroy().  `codes` and `ids` should be pinned: cluster copies are
+ * then read from them by a kernel (ivf_copy_form).
  *
  * Supported shapes: nbits == 8 or 4; M * nbits / 8 (bytes per code) a multiple
  * of 16 and <= 128, i.e. M <= 128 for 8-bit and M <= 256 for 4-bit codes; d a multiple
- * of M; nlist >= 1.  max_nq / max_nprobe / max_k size the per-batch workspace
- * (max_k <= 128, max_nprobe <= 2048).
+ * of M; nlist >= 1; with a device and 4-bit codes d <= 2048; the device scan
+ * has kernels for 16, 32, 48, 64, 96 and 128 bytes per code.  max_nq /
+ * max_nprobe / max_k size the per-batch workspace (max_k <= 128,
+ * max_nprobe <= 2048).
  */
 typedef struct {
   int32_t d;      /* vector dimension */

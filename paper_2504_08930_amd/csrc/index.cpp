@@ -243,6 +243,10 @@ extern "C" int ivf_index_create(const ivf_index_desc_t *desc, void *dev_arena, s
     return fail(IVF_EINVAL, "no scan kernel for %d code bytes (supported: 16, 32, 48, 64, 96, 128)",
                 code_bytes(*desc));
   }
+  if (desc->nbits == 4 && desc->d > 2048) {
+    delete ix;
+    return fail(IVF_EINVAL, "4-bit codes on the device need d <= 2048 (got %d)", desc->d);
+  }
   // how many resident vectors does the arena leave room for?
   const size_t fixed = plan_layout(*desc, 0, staging_bytes, nullptr, nullptr);
   if (arena_bytes < fixed) {
