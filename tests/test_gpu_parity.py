@@ -380,6 +380,27 @@ def test_every_subvector_length(pkg, oracle, nbits, dsub):
     index.close()
 
 
+def test_more_lists_than_the_select_holds_in_registers(pkg, oracle):
+    """nlist above 16384: the coarse selection re-reads the query's row of scores
+    in every pass instead of keeping it in registers.  Many short and empty lists."""
+    import torch
+    from synthdata.workloads import METRIC_L2, WorkloadSpec
+    spec = WorkloadSpec("S20k", 60_000, 16, 512, 20_000, 16, METRIC_L2, False,
+                        24, 40, 10, None, 1.0, kmeans_iters=2)
+    ix = build_index(spec, device="cuda")
+    q, _ = make_queries(spec, mixture_centers(spec, torch.device("cuda")))
+    q = q.cpu().numpy()
+    index = pkg.IvfIndex(ix, max_nq=32, max_nprobe=64, max_k=16)
+    index.load_partition(np.arange(ix.nlist, dtype=np.int32))
+    probe = index.coarse_probe_dev(torch.from_numpy(q).cuda(), spec.nprobe).cpu().numpy()
+    got = index.search_batch(q, spec.nprobe, spec.k)
+    n_coarse, n_amb = _check_search(oracle, ix, q, spec.nprobe, spec.k, got[0], got[1], probe)
+    _say(f"nlist 20000: coarse-ambiguous {n_coarse}, id-ambiguous {n_amb}, "
+         f"empty lists {(np.diff(ix.list_offsets) == 0).sum()}")
+    assert n_coarse <= 2 and n_amb <= 2
+    index.close()
+
+
 def test_cluster_region_too_small(pkg):
     spec, ix, q, calib = _case("T_IP")
     index = pkg.IvfIndex(ix, max_nq=64, max_nprobe=16, max_k=16, resident_vectors=ix.n // 4)
