@@ -401,6 +401,59 @@ def test_more_lists_than_the_select_holds_in_registers(pkg, oracle):
     index.close()
 
 
+def test_coarse_ties_go_to_the_smaller_cluster_id(pkg, oracle):
+    """All centroids equal: every coarse score of a query is the same number, the
+    selection's histogram has no range to bin and its exact fall-back decides;
+    ties go to the smaller cluster id, as in the oracle.  Then half of the
+    centroids equal: the tie sits exactly on the nprobe boundary."""
+    import dataclasses
+    import torch
+    spec, ix, q, calib = _case("T_L2")
+    qd = torch.from_numpy(q).cuda()
+    for n_same in (ix.nlist, ix.nlist // 2):
+        cent = ix.centroids.copy()
+        cent[:n_same] = ix.centroids[0]
+        ix2 = dataclasses.replace(ix, centroids=cent)
+        index = pkg.IvfIndex(ix2, max_nq=256, max_nprobe=ix.nlist, max_k=16)
+        index.load_partition(np.arange(ix.nlist, dtype=np.int32))
+        for nprobe in (1, 5, ix.nlist // 2 + 3):
+            got = index.coarse_probe_dev(qd, nprobe).cpu().numpy()
+            ref, _, _ = oracle.coarse(ix2.metric, cent, q, nprobe)
+            assert np.array_equal(np.sort(got, axis=1), np.sort(ref, axis=1)), (n_same, nprobe)
+        index.close()
+
+
+def test_identical_codes_tie_by_id_on_the_device(pkg, oracle):
+    """Whole lists of identical codes (equal distances by construction): the
+    device scan, with its per-wave filters, block merge and slices, must order
+    them by id exactly as the oracle's full sort does, at k below, at and above
+    the number of tied vectors, and whichever side scans the list."""
+    import dataclasses
+    spec, ix, q, calib = _case("T_L2")
+    lens = np.diff(ix.list_offsets)
+    codes = ix.codes.copy()
+    big = np.argsort(-lens)[:6]
+    for c in big:
+        a, b = int(ix.list_offsets[c]), int(ix.list_offsets[c + 1])
+        codes[a:b] = codes[a]
+    rng = np.random.default_rng(9)
+    ids = ix.ids.copy()
+    ids[:] = rng.permutation(ix.n)            # ids in no relation to storage order
+    ix2 = dataclasses.replace(ix, codes=codes, ids=ids)
+    probe = np.tile(np.sort(big[:4]).astype(np.int32), (q.shape[0], 1))
+    index = pkg.IvfIndex(ix2, max_nq=256, max_nprobe=ix.nlist, max_k=128)
+    for resident in (np.arange(ix.nlist), big[:2], np.zeros(0)):
+        index.load_partition(np.sort(resident).astype(np.int32))
+        for slices in (0, 1, 4):
+            index.set_tuning(scan_slices=slices)
+            for k in (7, 64, 128):
+                got_i, got_d = index.search_batch_probes(q, probe, k)
+                ref_i, ref_d = oracle.scan(ix2.metric, ix2.codebooks, ix2.list_offsets, codes, ids,
+                                           q, probe, k)
+                assert np.array_equal(got_i, ref_i), (len(resident), slices, k)
+    index.close()
+
+
 def test_cluster_region_too_small(pkg):
     spec, ix, q, calib = _case("T_IP")
     index = pkg.IvfIndex(ix, max_nq=64, max_nprobe=16, max_k=16, resident_vectors=ix.n // 4)
