@@ -150,6 +150,14 @@ def test_residency_invariance_and_counters(pkg, oracle, name):
         assert np.array_equal(ids, base[0]), "ids depend on residency"
         assert np.array_equal(dist, base[1]), "distances depend on residency"
         st = index.hit_stats(reset=True)
+        # the device-pointer entry point on the same resident set (its hybrid form
+        # copies the merged result back to the device); counters are read before it
+        import torch
+        ids_d, dist_d = index.search_batch_dev(torch.from_numpy(q).cuda(), spec.nprobe, spec.k)
+        torch.cuda.synchronize()
+        assert np.array_equal(ids_d.cpu().numpy(), base[0])
+        assert np.array_equal(dist_d.cpu().numpy(), base[1])
+        index.hit_stats(reset=True)
         mask = np.zeros(ix.nlist, np.uint8)
         mask[rs] = 1
         import torch
