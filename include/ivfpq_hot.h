@@ -127,6 +127,11 @@ size_t ivf_index_arena_bytes(const ivf_index_desc_t *desc, int64_t resident_vect
 int ivf_index_create(const ivf_index_desc_t *desc, void *dev_arena, size_t arena_bytes,
                      size_t staging_bytes, ivf_index_t **out);
 
+/*
+ * Destroy the index (NULL is a no-op).  Waits for the device.  Must not run while
+ * another thread is inside a call on the index, nor before ivf_search_wait()
+ * has returned for an asynchronous batch started on it.
+ */
 void ivf_index_destroy(ivf_index_t *index);
 
 /*
