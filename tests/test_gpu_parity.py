@@ -462,6 +462,50 @@ def test_identical_codes_tie_by_id_on_the_device(pkg, oracle):
     index.close()
 
 
+def test_random_migrations_in_a_tight_cluster_region(pkg, oracle):
+    """Forty random evict/admit moves with a cluster region that holds about 60 %
+    of the index: space is found among the holes earlier evictions left, a move
+    that does not fit is refused with IVF_ENOMEM and changes nothing, and after
+    every move the results and the resident counts are what they must be."""
+    spec, ix, q, calib = _case("T_IP96")
+    lens = np.diff(ix.list_offsets)
+    tiles = (lens + 63) // 64
+    cap_vectors = int(0.6 * tiles.sum()) * 64
+    index = pkg.IvfIndex(ix, max_nq=256, max_nprobe=ix.nlist, max_k=32,
+                         resident_vectors=cap_vectors)
+    cap_tiles = cap_vectors // 64
+    ref = index.search_batch(q, spec.nprobe, spec.k)          # nothing resident: all on the CPU
+    rng = np.random.default_rng(23)
+    resident = set()
+    refused = moved = 0
+    for step in range(40):
+        res_list = sorted(resident)
+        cold_list = sorted(set(range(ix.nlist)) - resident)
+        n_e = int(rng.integers(0, min(len(res_list), 4) + 1))
+        n_a = int(rng.integers(0, min(len(cold_list), 12) + 1))
+        evict = rng.choice(res_list, n_e, replace=False).astype(np.int32) if n_e else np.zeros(0, np.int32)
+        admit = rng.choice(cold_list, n_a, replace=False).astype(np.int32) if n_a else np.zeros(0, np.int32)
+        # evicted space is not reusable within the same move
+        fits_for_sure = tiles[sorted(resident)].sum() + tiles[admit].sum() <= cap_tiles // 2
+        try:
+            index.migrate_clusters(evict, admit)
+        except pkg.IvfError as e:
+            assert e.code == -2 and not fits_for_sure, (step, e)
+            refused += 1
+        else:
+            index.migrate_poll(wait=True)
+            resident = (resident - set(evict.tolist())) | set(admit.tolist())
+            moved += 1
+        nc, nv = index.resident_info()
+        assert nc == len(resident) and nv == int(lens[sorted(resident)].sum()), step
+        assert tiles[sorted(resident)].sum() <= cap_tiles
+        got = index.search_batch(q, spec.nprobe, spec.k)
+        assert np.array_equal(got[0], ref[0]) and np.array_equal(got[1], ref[1]), step
+    _say(f"random migrations: {moved} done, {refused} refused, {len(resident)} clusters resident")
+    assert moved >= 15 and refused >= 3
+    index.close()
+
+
 def test_cluster_region_too_small(pkg):
     spec, ix, q, calib = _case("T_IP")
     index = pkg.IvfIndex(ix, max_nq=64, max_nprobe=16, max_k=16, resident_vectors=ix.n // 4)
