@@ -217,6 +217,7 @@ struct BatchCtx {
   int buf = 0;
   bool all_resident = false, any_resident = false;
   int timing = 0;  // 0: no events; 1: around every stage; 2: around the scan only
+  int list_tiles = 1;  // average tiles (64 vectors) of a resident list, at least 1
   uint64_t ver_id = 0;
 };
 

@@ -162,5 +162,7 @@ hipError_t launch_interleave_direct(const uint8_t *host_codes, const int64_t *ho
                                     hipStream_t st);
 
 bool scan_supports(int M, int k);
+// scan blocks that fit one compute unit at a time (its LDS decides)
+int scan_blocks_per_cu(int M, int k);
 
 }  // namespace ivf

@@ -1200,6 +1200,8 @@ static hipError_t launch_scan_t(const ScanParams &P, int nq, hipStream_t st) {
   return hipGetLastError();
 }
 
+int scan_blocks_per_cu(int M, int k) { return (M <= 64 && k <= 64) ? 2 : 1; }
+
 bool scan_supports(int M, int k) {
   if (k < 1 || k > kMaxK) return false;
   return M == 16 || M == 32 || M == 48 || M == 64 || M == 96 || M == 128;
@@ -1242,14 +1244,20 @@ hipError_t launch_scan(const Shape &sh, const DevLayout &L, const BatchWs &W, in
 #define IVF_SCAN_CASE(MM) \
   case MM:                \
     return k <= 64 ? IVF_SCAN_RES(MM, 16, 128) : IVF_SCAN_RES(MM, 8, 256);
+  // one table (up to 64 code bytes): blocks of eight wavefronts, so that two fit a
+  // CU's LDS and one stages its table while the other streams
+#define IVF_SCAN_CASE_SMALL(MM) \
+  case MM:                      \
+    return k <= 64 ? IVF_SCAN_RES(MM, 8, 128) : IVF_SCAN_RES(MM, 8, 256);
   switch (sh.M) {
-    IVF_SCAN_CASE(16)
-    IVF_SCAN_CASE(32)
-    IVF_SCAN_CASE(48)
-    IVF_SCAN_CASE(64)
+    IVF_SCAN_CASE_SMALL(16)
+    IVF_SCAN_CASE_SMALL(32)
+    IVF_SCAN_CASE_SMALL(48)
+    IVF_SCAN_CASE_SMALL(64)
     IVF_SCAN_CASE(96)
     IVF_SCAN_CASE(128)
   }
+#undef IVF_SCAN_CASE_SMALL
 #undef IVF_SCAN_CASE
 #undef IVF_SCAN_RES
   return hipErrorInvalidValue;

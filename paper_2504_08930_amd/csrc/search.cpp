@@ -18,10 +18,17 @@ static void emit_results(const ivf_index *ix, const HostCand *c, int k, int e, i
   }
 }
 
-static int pick_slices(const ivf_index *ix, int64_t nq) {
+static int pick_slices(const ivf_index *ix, const BatchCtx &c, int64_t nq, int nprobe, int k) {
   if (ix->tune_slices > 0) return ix->tune_slices;
-  // one block per query fills the chip from 256 queries up; below that, split
-  int s = (int)((256 + nq - 1) / nq);
+  // one block per query fills the chip's 256 compute units (each holding one or
+  // two scan blocks) from that many queries up; below that, split - but not so
+  // far that a block's wavefronts (8 or 16) are left with fewer than two tiles each
+  const int per_cu = scan_blocks_per_cu(ix->sh.M, k);
+  const int64_t fill = 256 * (int64_t)per_cu;
+  int s = (int)((fill + nq - 1) / nq);
+  const int waves = (per_cu == 2 || k > 64) ? 8 : 16;
+  const int64_t tiles = (int64_t)nprobe * c.list_tiles;  // estimate per query
+  s = (int)std::min<int64_t>(s, std::max<int64_t>(1, tiles / (2 * waves)));
   if (s < 1) s = 1;
   if (s > kMaxSlices) s = kMaxSlices;
   return s;
@@ -94,6 +101,9 @@ int begin_batch(ivf_index *ix, hipStream_t st, BatchCtx *c) {
   c->buf = ver.buf;
   c->all_resident = ix->resident_clusters == ix->sh.nlist;
   c->any_resident = ix->resident_clusters > 0;
+  c->list_tiles = ix->resident_clusters > 0
+                      ? (int)std::max<int64_t>(1, (ix->resident_vectors / ix->resident_clusters + kTileVecs - 1) / kTileVecs)
+                      : 1;
   // events of timed batches are kept until ivf_stage_times() reads them; a caller
   // that never does stops collecting after this many batches instead of growing
   c->timing = ix->trecs.size() < 8192 ? ix->timing : 0;
@@ -199,7 +209,7 @@ int enqueue_gpu(ivf_index *ix, const SearchArgs &a, const BatchCtx &c, bool fina
   }
   if (c.any_resident) {
     // ---- stage 3: scan + top-k ----
-    const int slices = pick_slices(ix, nq);
+    const int slices = pick_slices(ix, c, nq, np, k);
     int64_t *oid = nullptr;
     float *od = nullptr;
     if (final_on_gpu) {
