@@ -1241,14 +1241,17 @@ hipError_t launch_scan(const Shape &sh, const DevLayout &L, const BatchWs &W, in
   (res == 0 ? launch_scan_t<MM, NW_, CAP_, 0>(P, nq, st)                          \
             : res == 1 ? launch_scan_t<MM, NW_, CAP_, 1>(P, nq, st)               \
                        : launch_scan_t<MM, NW_, CAP_, 2>(P, nq, st))
+  // Wavefronts per block and candidate slots per wavefront (at least k + 64).
+  // Two tables (96 or 128 code bytes) leave 32 KB of LDS for the buffers: 16
+  // wavefronts of 128 slots up to k = 64, 12 of 192 above.  One table leaves room
+  // for two blocks of eight wavefronts per CU up to k = 64 (one stages its table
+  // while the other streams), one block of 16 above.
 #define IVF_SCAN_CASE(MM) \
   case MM:                \
-    return k <= 64 ? IVF_SCAN_RES(MM, 16, 128) : IVF_SCAN_RES(MM, 8, 256);
-  // one table (up to 64 code bytes): blocks of eight wavefronts, so that two fit a
-  // CU's LDS and one stages its table while the other streams
+    return k <= 64 ? IVF_SCAN_RES(MM, 16, 128) : IVF_SCAN_RES(MM, 12, 192);
 #define IVF_SCAN_CASE_SMALL(MM) \
   case MM:                      \
-    return k <= 64 ? IVF_SCAN_RES(MM, 8, 128) : IVF_SCAN_RES(MM, 8, 256);
+    return k <= 64 ? IVF_SCAN_RES(MM, 8, 128) : IVF_SCAN_RES(MM, 16, 192);
   switch (sh.M) {
     IVF_SCAN_CASE_SMALL(16)
     IVF_SCAN_CASE_SMALL(32)
