@@ -7,6 +7,9 @@
 // when several GPU shards are used (Section 4.2.1); with one GPU that concern
 // does not arise and the contraction runs on the device.
 #include <hip/hip_runtime.h>
+#include <math.h>
+
+#include <algorithm>
 
 #include "internal.h"
 
@@ -347,14 +350,23 @@ template <int PER, int kSelThreads>
 __global__ __launch_bounds__(kSelThreads) void k_coarse_select(const float *__restrict__ scores,
                                                                int nlist, int metric_ip, int keep,
                                                                int nprobe, int stride, int cap,
+                                                               float stash_z,
                                                                int32_t *__restrict__ probe) {
   constexpr int kSelBinsPerThread = kSelBins / kSelThreads;
   __shared__ unsigned int hist[kSelBins];
   __shared__ unsigned int wsum[kSelThreads / 64];
   __shared__ float wmin[kSelThreads / 64], wmax[kSelThreads / 64];
+  __shared__ float wmom[kSelThreads / 64][3];
   __shared__ unsigned long long s_prefix, s_mask;
   __shared__ unsigned int s_need, s_done, s_count, s_bin, s_total;
-  extern __shared__ unsigned long long sel[];  // cap entries
+  extern __shared__ unsigned long long sel[];  // cap entries (+ the stash when PER == 0)
+  // PER == 0: clusters met in the low bins during the histogram pass are kept
+  // aside (score and id), so that when the bin that holds rank `keep` turns out
+  // to lie among them the row need not be read again to collect them
+  constexpr int kStash = 1024;
+  float *stash_s = reinterpret_cast<float *>(sel + cap);
+  int *stash_c = reinterpret_cast<int *>(stash_s + kStash);
+  __shared__ unsigned int s_stash;
   const int q = blockIdx.x;
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
@@ -395,6 +407,7 @@ __global__ __launch_bounds__(kSelThreads) void k_coarse_select(const float *__re
     s_count = 0u;
     s_bin = 0xffffffffu;
     s_total = 0u;
+    s_stash = 0u;
   }
 #pragma unroll
   for (int b = 0; b < kSelBinsPerThread; ++b) hist[tid * kSelBinsPerThread + b] = 0u;
@@ -404,35 +417,95 @@ __global__ __launch_bounds__(kSelThreads) void k_coarse_select(const float *__re
   if (keep < nlist) {
     // v = score (L2) or -score (IP): smaller is better
     float vmin = INFINITY, vmax = -INFINITY;
-    visit([&](float s0, int) {
-      const float v = metric_ip ? -s0 : s0;
-      vmin = fminf(vmin, v);
-      vmax = fmaxf(vmax, v);
-    });
+    float ssum = 0.0f, ssq = 0.0f, scnt = 0.0f;  // PER == 0: moments of the sample
+    if (PER > 0) {
+      visit([&](float s0, int) {
+        const float v = metric_ip ? -s0 : s0;
+        vmin = fminf(vmin, v);
+        vmax = fmaxf(vmax, v);
+      });
+    } else {
+      // the row is not held in registers: take the range from every 16th stretch of
+      // it and leave room below (binning clamps, so it stays monotone whatever
+      // the range is; a range that turns out too narrow only sends the block to
+      // the exact fall-back)
+      for (int c = tid; c < nlist; c += kSelThreads * 16) {
+        const float v = metric_ip ? -row[c] : row[c];
+        vmin = fminf(vmin, v);
+        vmax = fmaxf(vmax, v);
+        ssum += v;
+        ssq += v * v;
+        scnt += 1.0f;
+      }
+    }
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) {
       vmin = fminf(vmin, __shfl_xor(vmin, o, 64));
       vmax = fmaxf(vmax, __shfl_xor(vmax, o, 64));
+      if (PER == 0) {
+        ssum += __shfl_xor(ssum, o, 64);
+        ssq += __shfl_xor(ssq, o, 64);
+        scnt += __shfl_xor(scnt, o, 64);
+      }
     }
     if (lane == 0) {
       wmin[wave] = vmin;
       wmax[wave] = vmax;
+      if (PER == 0) {
+        wmom[wave][0] = ssum;
+        wmom[wave][1] = ssq;
+        wmom[wave][2] = scnt;
+      }
     }
     __syncthreads();
+    ssum = ssq = scnt = 0.0f;
 #pragma unroll
     for (int w2 = 0; w2 < kSelThreads / 64; ++w2) {
       vmin = fminf(vmin, wmin[w2]);
       vmax = fmaxf(vmax, wmax[w2]);
+      if (PER == 0) {
+        ssum += wmom[w2][0];
+        ssq += wmom[w2][1];
+        scnt += wmom[w2][2];
+      }
     }
+    if (PER == 0) vmin -= 0.5f * (vmax - vmin);
     const float scale = (float)(kSelBins - 1) / (vmax - vmin);
     const bool usable = scale > 0.0f && scale < INFINITY;  // block-uniform
     if (usable) {
       auto bin_of = [&](float s0) -> unsigned {
         const float v = metric_ip ? -s0 : s0;
-        const unsigned b = (unsigned)(int)((v - vmin) * scale);
+        const unsigned b = (unsigned)(int)fmaxf((v - vmin) * scale, 0.0f);
         return b < (unsigned)kSelBins ? b : (unsigned)(kSelBins - 1);
       };
-      visit([&](float s0, int) { atomicAdd(&hist[bin_of(s0)], 1u); });
+      // bins up to this one are stashed: stash_z standard deviations of the sample
+      // on the good side of its mean (the launcher picks stash_z so that a
+      // bell-shaped row sends two to three times `keep` clusters there, whatever
+      // outliers the sample caught).  The stash holds 1024 clusters; if it
+      // overflows or ends before the bin of rank `keep`, the row is read again.
+      unsigned stash_bin = 0u;
+      if (PER == 0 && stash_z > 0.0f) {
+        const float mean = ssum / scnt;
+        const float sd = sqrtf(fmaxf(ssq / scnt - mean * mean, 0.0f));
+        const float lim =
+            fminf(fmaxf((mean - stash_z * sd - vmin) * scale, 0.0f), (float)(kSelBins - 1));
+        stash_bin = lim == lim ? (unsigned)(int)lim : 0u;
+      }
+      if (PER > 0) {
+        visit([&](float s0, int) { atomicAdd(&hist[bin_of(s0)], 1u); });
+      } else {
+        visit([&](float s0, int c) {
+          const unsigned b = bin_of(s0);
+          atomicAdd(&hist[b], 1u);
+          if (b <= stash_bin) {
+            const unsigned slot = atomicAdd(&s_stash, 1u);
+            if (slot < (unsigned)kStash) {
+              stash_s[slot] = s0;
+              stash_c[slot] = c;
+            }
+          }
+        });
+      }
       __syncthreads();
       unsigned loc[kSelBinsPerThread], tsum = 0;
 #pragma unroll
@@ -466,12 +539,18 @@ __global__ __launch_bounds__(kSelThreads) void k_coarse_select(const float *__re
         fast_ok = true;
         for (int i = tid; i < cap; i += kSelThreads) sel[i] = ~0ull;
         __syncthreads();
-        visit([&](float s0, int c) {
+        auto take = [&](float s0, int c) {
           if (bin_of(s0) <= tbin) {
             const unsigned slot = atomicAdd(&s_count, 1u);
             if (slot < (unsigned)cap) sel[slot] = sel_key(s0, metric_ip, c);
           }
-        });
+        };
+        const unsigned n_stash = PER == 0 ? s_stash : 0u;
+        if (PER == 0 && tbin <= stash_bin && n_stash <= (unsigned)kStash) {
+          for (unsigned i = tid; i < n_stash; i += kSelThreads) take(stash_s[i], stash_c[i]);
+        } else {
+          visit(take);
+        }
       }
     }
   }
@@ -578,9 +657,24 @@ hipError_t launch_coarse_select(const Shape &sh, const float *scores, int nq, in
   const int keep = nprobe < sh.nlist ? nprobe : sh.nlist;
   int cap = 128;  // LDS slots for collected candidates: a power of two >= 2 * keep
   while (cap < 2 * keep) cap <<= 1;
+  // PER == 0 only: how far from the mean the stash reaches.  For a bell-shaped row
+  // the stash should catch about 2.4 * keep clusters (never more than 800 of its
+  // 1024 slots); P(z < -stash_z) = that share of the row.  Solved by bisection
+  // on erfc; 0 (no stash) when even 1.5 * keep clusters would not fit.
+  float stash_z = 0.0f;
+  if (sh.nlist > 16 * 1024 && keep * 3 / 2 <= 800) {
+    const double want = std::min(800.0, 2.4 * keep) / (double)sh.nlist;
+    double lo = 0.0, hi = 8.0;
+    for (int it = 0; it < 60; ++it) {
+      const double mid = 0.5 * (lo + hi);
+      if (0.5 * erfc(mid / sqrt(2.0)) > want) lo = mid; else hi = mid;
+    }
+    stash_z = (float)lo;
+  }
 #define IVF_SEL_LAUNCH(PER, THREADS)                                                          \
-  hipLaunchKernelGGL((k_coarse_select<PER, THREADS>), dim3(nq), dim3(THREADS), (size_t)cap * 8, \
-                     st, scores, sh.nlist, sh.metric_ip, keep, nprobe, probe_stride, cap, probe)
+  hipLaunchKernelGGL((k_coarse_select<PER, THREADS>), dim3(nq), dim3(THREADS),                   \
+                     (size_t)cap * 8 + (PER == 0 ? 1024 * 8 : 0),                                \
+                     st, scores, sh.nlist, sh.metric_ip, keep, nprobe, probe_stride, cap, stash_z, probe)
   // the row of scores in registers (4 or 16 per thread) up to 16384 clusters, re-read above
   if (sh.nlist <= 4 * 1024) IVF_SEL_LAUNCH(4, 1024);
   else if (sh.nlist <= 16 * 1024) IVF_SEL_LAUNCH(16, 1024);
