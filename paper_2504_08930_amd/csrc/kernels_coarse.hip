@@ -390,7 +390,16 @@ __global__ __launch_bounds__(kSelThreads) void k_coarse_select(const float *__re
         if (c < nlist) body(sc[i], c);
       }
     } else {
-      for (int c = tid; c < nlist; c += kSelThreads) body(row[c], c);
+      // eight loads in flight per thread before their values are used
+      int c = tid;
+      for (; c + 7 * kSelThreads < nlist; c += 8 * kSelThreads) {
+        float v[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) v[i] = row[c + i * kSelThreads];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) body(v[i], c + i * kSelThreads);
+      }
+      for (; c < nlist; c += kSelThreads) body(row[c], c);
     }
   };
 
@@ -494,10 +503,16 @@ __global__ __launch_bounds__(kSelThreads) void k_coarse_select(const float *__re
       if (PER > 0) {
         visit([&](float s0, int) { atomicAdd(&hist[bin_of(s0)], 1u); });
       } else {
+        // with a stash only its bins are counted at first: rank `keep` lies among
+        // them whenever they hold at least `keep` clusters, and the bins above
+        // (nearly all of the row, and the crowded ones) then cost no atomics
+        const bool partial = stash_z > 0.0f;  // block-uniform
         visit([&](float s0, int c) {
           const unsigned b = bin_of(s0);
-          atomicAdd(&hist[b], 1u);
-          if (b <= stash_bin) {
+          if (!partial) {
+            atomicAdd(&hist[b], 1u);
+          } else if (b <= stash_bin) {
+            atomicAdd(&hist[b], 1u);
             const unsigned slot = atomicAdd(&s_stash, 1u);
             if (slot < (unsigned)kStash) {
               stash_s[slot] = s0;
@@ -505,6 +520,13 @@ __global__ __launch_bounds__(kSelThreads) void k_coarse_select(const float *__re
             }
           }
         });
+        __syncthreads();
+        if (partial && s_stash < (unsigned)keep) {  // too few below the limit: count the rest too
+          visit([&](float s0, int) {
+            const unsigned b = bin_of(s0);
+            if (b > stash_bin) atomicAdd(&hist[b], 1u);
+          });
+        }
       }
       __syncthreads();
       unsigned loc[kSelBinsPerThread], tsum = 0;
