@@ -407,6 +407,19 @@ def test_more_lists_than_the_select_holds_in_registers(pkg, oracle):
          f"empty lists {(np.diff(ix.list_offsets) == 0).sum()}")
     assert n_coarse <= 2 and n_amb <= 2
     index.close()
+    # the same with half of the centroids equal (a mass of tied scores in every row) and
+    # with more probes than the selection's side buffer of low-bin clusters can serve
+    import dataclasses
+    cent = ix.centroids.copy()
+    cent[: ix.nlist // 2] = ix.centroids[0]
+    ix2 = dataclasses.replace(ix, centroids=cent)
+    index = pkg.IvfIndex(ix2, max_nq=32, max_nprobe=1024, max_k=16)
+    qd = torch.from_numpy(q).cuda()
+    for nprobe in (40, 700):
+        got = index.coarse_probe_dev(qd, nprobe).cpu().numpy()
+        ref, _, _ = oracle.coarse(ix2.metric, cent, q, nprobe)
+        assert np.array_equal(np.sort(got, axis=1), np.sort(ref, axis=1)), nprobe
+    index.close()
 
 
 def test_coarse_ties_go_to_the_smaller_cluster_id(pkg, oracle):
