@@ -432,15 +432,17 @@ hipError_t launch_route(const int32_t *probe, int nq, int nprobe, int probe_stri
 // ---------------------------------------------------------------------------
 // Stage 2: per-query lookup table, fp32, layout [query][code j][sub-quantizer m],
 // plus the largest |entry| per query for the fixed-point scale.
-// Thread (ml, jl) owns eight codewords of sub-quantizer m in registers and
-// loops over the queries of its tile, so codebooks are read once per query
-// tile and each query sub-vector once per eight entries.  Lanes run along m:
-// table stores are contiguous in m.
+// Thread (ml, jl) owns JPT codewords of sub-quantizer m in registers (eight for
+// sub-vectors of up to 16 elements, fewer for longer ones so that they still
+// fit) and loops over the queries of its tile, so codebooks are read once per
+// query tile and each query sub-vector once per JPT entries.  Lanes run along
+// m: table stores are contiguous in m.  Sub-vector lengths without an
+// instantiation take DSUB = 0: nothing is held in registers and every entry
+// re-reads its codeword (correct, and an order of magnitude slower).
 // ---------------------------------------------------------------------------
 constexpr int kLutQTile = 8;   // queries per block
-constexpr int kLutJPT = 8;     // codewords (of one sub-quantizer) per thread
 
-template <int DSUB>
+template <int DSUB, int JPT>
 __global__ __launch_bounds__(256) void k_lut(const float *__restrict__ queries, int nq, int d,
                                              int M, int dsub_rt, int MW,
                                              const float *__restrict__ cbT, int kind,
@@ -451,14 +453,14 @@ __global__ __launch_bounds__(256) void k_lut(const float *__restrict__ queries, 
   const int JL = 256 / MW;  // j lanes per block
   const int ml = tid % MW, jl = tid / MW;
   const int m = blockIdx.y * MW + ml;
-  const int j0 = blockIdx.x * (JL * kLutJPT) + jl;  // this thread's codes: j0 + t * JL
+  const int j0 = blockIdx.x * (JL * JPT) + jl;  // this thread's codes: j0 + t * JL
   const int q0 = blockIdx.z * kLutQTile;
   const int q1 = min(nq, q0 + kLutQTile);
 
-  float creg[kLutJPT][DSUB > 0 ? DSUB : 1];
+  float creg[JPT][DSUB > 0 ? DSUB : 1];
   if (DSUB > 0) {
 #pragma unroll
-    for (int t = 0; t < kLutJPT; ++t) {
+    for (int t = 0; t < JPT; ++t) {
       const float *cw = cbT + ((size_t)(j0 + t * JL) * M + m) * DSUB;
 #pragma unroll
       for (int i = 0; i < DSUB; ++i) creg[t][i] = cw[i];
@@ -473,7 +475,7 @@ __global__ __launch_bounds__(256) void k_lut(const float *__restrict__ queries, 
     }
     float mxf = 0.0f;
 #pragma unroll
-    for (int t = 0; t < kLutJPT; ++t) {
+    for (int t = 0; t < JPT; ++t) {
       const int j = j0 + t * JL;
       const float v = DSUB > 0 ? lut_entry(kind, qreg, creg[t], DSUB)
                                : lut_entry(kind, qv, cbT + ((size_t)j * M + m) * dsub, dsub);
@@ -573,24 +575,34 @@ hipError_t launch_lut(const Shape &sh, const float *q, int nq, const float *cbT,
   }
   const int MW = (sh.M % 32 == 0) ? 32 : 16;
   const int JL = 256 / MW;
-  dim3 grid(256 / (JL * kLutJPT), sh.M / MW, (nq + kLutQTile - 1) / kLutQTile);
-#define IVF_LUT_CASE(DS)                                                                       \
+#define IVF_LUT_CASE(DS, JPT_)                                                                  \
   case DS:                                                                                     \
-    hipLaunchKernelGGL(k_lut<DS>, grid, dim3(256), 0, st, q, nq, sh.d, sh.M, sh.dsub, MW, cbT, \
-                       sh.lut_kind(), lut, lutpart);                                           \
+    grid = dim3(256 / (JL * JPT_), sh.M / MW, (nq + kLutQTile - 1) / kLutQTile);               \
+    hipLaunchKernelGGL((k_lut<DS, JPT_>), grid, dim3(256), 0, st, q, nq, sh.d, sh.M, sh.dsub,  \
+                       MW, cbT, sh.lut_kind(), lut, lutpart);                                  \
     break;
+  dim3 grid;
   switch (sh.dsub) {
-    IVF_LUT_CASE(2)
-    IVF_LUT_CASE(4)
-    IVF_LUT_CASE(8)
-    IVF_LUT_CASE(12)
-    IVF_LUT_CASE(16)
+    IVF_LUT_CASE(1, 8)
+    IVF_LUT_CASE(2, 8)
+    IVF_LUT_CASE(3, 8)
+    IVF_LUT_CASE(4, 8)
+    IVF_LUT_CASE(6, 8)
+    IVF_LUT_CASE(8, 8)
+    IVF_LUT_CASE(12, 8)
+    IVF_LUT_CASE(16, 8)
+    IVF_LUT_CASE(24, 2)
+    IVF_LUT_CASE(32, 2)
+    IVF_LUT_CASE(48, 1)
+    IVF_LUT_CASE(64, 1)
     default:
-      hipLaunchKernelGGL(k_lut<0>, grid, dim3(256), 0, st, q, nq, sh.d, sh.M, sh.dsub, MW, cbT,
-                         sh.lut_kind(), lut, lutpart);
+      grid = dim3(256 / (JL * 8), sh.M / MW, (nq + kLutQTile - 1) / kLutQTile);
+      hipLaunchKernelGGL((k_lut<0, 8>), grid, dim3(256), 0, st, q, nq, sh.d, sh.M, sh.dsub, MW,
+                         cbT, sh.lut_kind(), lut, lutpart);
   }
 #undef IVF_LUT_CASE
   *n_parts = (int)(grid.x * grid.y * 4);
+  if (*n_parts > kLutMaxParts) return hipErrorInvalidValue;  // cannot happen for M <= 128
   return hipGetLastError();
 }
 

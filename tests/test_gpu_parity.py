@@ -360,12 +360,12 @@ def test_every_code_size(pkg, oracle, code_bytes, metric, residual):
     index.close()
 
 
-@pytest.mark.parametrize("nbits,dsub", [(8, 1), (8, 3), (8, 4), (8, 6), (8, 16), (8, 24),
-                                        (4, 1), (4, 3), (4, 4), (4, 8)])
+@pytest.mark.parametrize("nbits,dsub", [(8, 1), (8, 3), (8, 4), (8, 5), (8, 6), (8, 16), (8, 24),
+                                        (8, 32), (8, 48), (8, 64), (4, 1), (4, 3), (4, 4), (4, 8)])
 def test_every_subvector_length(pkg, oracle, nbits, dsub):
-    """Sub-vector lengths with a table kernel of their own (2, 4, 8, 12, 16 for
-    8-bit codes; 1, 2, 4, 8 for 4-bit codes) and lengths that take the generic
-    one, on 16-byte codes: table entries and results against the oracle, and the
+    """Sub-vector lengths with a table kernel of their own (1 to 64 for 8-bit
+    codes, fewer codewords per thread as they grow; 1, 2, 4, 8 for 4-bit codes)
+    and lengths that take the generic one (5; 3 for 4-bit), on 16-byte codes: table entries and results against the oracle, and the
     CPU scan's table against the device's through a half-resident search."""
     import torch
     from synthdata.workloads import METRIC_L2, WorkloadSpec
