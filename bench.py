@@ -122,6 +122,8 @@ def main():
                     choices=["hotpath", "sweep", "drift", "partition", "dispatch"])
     ap.add_argument("--workload", default="C3", help="spec name in synthdata.SPECS")
     ap.add_argument("--nq", type=int, default=None)
+    ap.add_argument("--nprobe", type=int, default=0, help="override the workload's nprobe")
+    ap.add_argument("--k", type=int, default=0, help="override the workload's k")
     ap.add_argument("--slices", type=int, default=0, help="scan blocks per query (0 = auto)")
     ap.add_argument("--streams", type=int, default=1,
                     help="issue consecutive steps on this many alternating streams (1 or 2)")
@@ -167,6 +169,8 @@ def main():
         build()
     dev = torch.device("cuda:0")
     spec = SPECS[args.workload]
+    if args.nprobe or args.k:
+        spec = spec.with_(nprobe=args.nprobe or spec.nprobe, k=args.k or spec.k)
     nq = args.nq or spec.nq
 
     t0 = time.time()
