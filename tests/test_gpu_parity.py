@@ -519,6 +519,50 @@ def test_random_migrations_in_a_tight_cluster_region(pkg, oracle):
     index.close()
 
 
+def test_random_small_shapes(pkg, oracle):
+    """Sixty seeded random combinations of code size, sub-vector length, code bits,
+    metric, residual encoding, list count, batch size, nprobe, k and resident
+    fraction, each against the oracle and against itself with everything resident."""
+    import torch
+    from synthdata.workloads import METRIC_IP, METRIC_L2, WorkloadSpec
+    rng = np.random.default_rng(20240607)
+    for case in range(60):
+        nbits = int(rng.choice([8, 8, 4]))
+        cb = int(rng.choice([16, 32, 48, 64, 96, 128]))
+        m = cb if nbits == 8 else 2 * cb
+        dsub = int(rng.choice([1, 2, 3, 4, 5, 6, 8])) if m >= 96 else \
+            int(rng.choice([1, 2, 3, 4, 6, 8, 12, 16, 24]))
+        ip = bool(rng.integers(0, 2))
+        residual = bool(rng.integers(0, 2))
+        nlist = int(rng.choice([1, 3, 17, 64, 200]))
+        n = int(rng.integers(max(nlist, 600), 6000))
+        nq = int(rng.choice([1, 2, 7, 33, 100]))
+        nprobe = int(rng.integers(1, nlist + 3))
+        k = int(rng.choice([1, 5, 10, 64, 65, 100, 128]))
+        frac = float(rng.choice([0.0, 0.3, 0.7, 1.0]))
+        tag = (f"case {case}: nbits={nbits} bytes={cb} dsub={dsub} ip={ip} residual={residual} "
+               f"nlist={nlist} n={n} nq={nq} nprobe={nprobe} k={k} resident={frac}")
+        _say(tag)
+        spec = WorkloadSpec(f"R{case}", n, m * dsub, max(1, nlist // 2), nlist, m,
+                            METRIC_IP if ip else METRIC_L2, ip, nq, nprobe, k,
+                            1.0 if ip else None, 1.0, kmeans_iters=2)
+        ix = build_index(spec, device="cuda", by_residual=residual, nbits=nbits, m=m)
+        q, _ = make_queries(spec, mixture_centers(spec, torch.device("cuda")))
+        q = q.cpu().numpy()
+        index = pkg.IvfIndex(ix, max_nq=128, max_nprobe=nprobe, max_k=128)
+        res = np.sort(rng.choice(nlist, int(round(frac * nlist)), replace=False)).astype(np.int32)
+        index.load_partition(res)
+        npb = min(nprobe, nlist)
+        probe = index.coarse_probe_dev(torch.from_numpy(q).cuda(), npb).cpu().numpy()
+        ids, dist = index.search_batch(q, nprobe, k)
+        n_coarse, n_amb = _check_search(oracle, ix, q, nprobe, k, ids, dist, probe)
+        assert n_coarse <= max(1, nq // 10) and n_amb <= max(1, nq // 10), tag
+        index.load_partition(np.arange(nlist, dtype=np.int32))
+        ids2, dist2 = index.search_batch(q, nprobe, k)
+        assert np.array_equal(ids, ids2) and np.array_equal(dist, dist2), tag
+        index.close()
+
+
 def test_cluster_region_too_small(pkg):
     spec, ix, q, calib = _case("T_IP")
     index = pkg.IvfIndex(ix, max_nq=64, max_nprobe=16, max_k=16, resident_vectors=ix.n // 4)
