@@ -230,6 +230,41 @@ def test_host_only_other_code_sizes(lib, oracle, monkeypatch, code_bytes, metric
                         scale_S(ix.metric, q)) <= 1
 
 
+def test_host_only_random_small_shapes(lib, oracle):
+    """Thirty seeded random combinations of code size, sub-vector length, code
+    bits, metric, residual encoding, list count, batch, nprobe and k on a
+    device-less index (every probe scanned by the CPU path) against the oracle."""
+    from synthdata.workloads import METRIC_IP, METRIC_L2, WorkloadSpec
+    rng = np.random.default_rng(20240608)
+    for case in range(30):
+        nbits = int(rng.choice([8, 8, 4]))
+        cb = int(rng.choice([16, 32, 48, 64, 96, 128]))
+        m = cb if nbits == 8 else 2 * cb
+        dsub = int(rng.choice([1, 2, 3, 4, 5, 8]))
+        ip = bool(rng.integers(0, 2))
+        residual = bool(rng.integers(0, 2))
+        nlist = int(rng.choice([1, 3, 17, 64]))
+        n = int(rng.integers(max(nlist, 600), 4000))
+        nq = int(rng.choice([1, 2, 7, 33]))
+        nprobe = int(rng.integers(1, nlist + 1))
+        k = int(rng.choice([1, 5, 10, 64]))
+        tag = (f"case {case}: nbits={nbits} bytes={cb} dsub={dsub} ip={ip} residual={residual} "
+               f"nlist={nlist} n={n} nq={nq} nprobe={nprobe} k={k}")
+        spec = WorkloadSpec(f"HR{case}", n, m * dsub, max(1, nlist // 2), nlist, m,
+                            METRIC_IP if ip else METRIC_L2, ip, nq, nprobe, k,
+                            1.0 if ip else None, 1.0, kmeans_iters=2)
+        ix = build_index(spec, by_residual=residual, nbits=nbits, m=m)
+        q, _ = make_queries(spec, mixture_centers(spec))
+        q = q.numpy()
+        probe, _, _ = oracle.coarse(ix.metric, ix.centroids, q, nprobe)
+        index = lib.IvfIndex(ix, nq, nprobe, 64, host_only=True)
+        ids, dist = index.search_batch_probes(q, probe, k)
+        index.close()
+        ref_i, ref_d = oracle.scan(ix.metric, ix.codebooks, ix.list_offsets, ix.codes, ix.ids, q,
+                                   probe, k + 16, residual_centroids=ix.centroids if residual else None)
+        assert compare_topk(ids, dist, ref_i, ref_d, k, scale_S(ix.metric, q)) <= max(1, nq // 10), tag
+
+
 def test_host_only_counters(case, oracle):
     spec, ix, q, index = case
     index.hit_stats(reset=True)
