@@ -789,9 +789,11 @@ __global__ __launch_bounds__(NW * 64) void k_scan(ScanParams P) {
   using G = ScanGeom<M>;
   extern __shared__ __align__(16) unsigned char smem[];
   int *tab = reinterpret_cast<int *>(smem);
-  long long *buf_id_all = reinterpret_cast<long long *>(smem + G::kTables * G::kTableBytes);
+  // a candidate is (key, position): position = tile * 64 + lane in the cluster
+  // region; its 64-bit id is read only when ids decide (ties) and for the k winners
+  int *buf_pos_all = reinterpret_cast<int *>(smem + G::kTables * G::kTableBytes);
   int *buf_key_all = reinterpret_cast<int *>(smem + G::kTables * G::kTableBytes +
-                                             (size_t)NW * CAP * sizeof(long long));
+                                             (size_t)NW * CAP * sizeof(int));
   int *s_thr = buf_key_all + NW * CAP;
   int *s_total = s_thr + 1;
   int *s_next = s_thr + 2;  // next tile (position in the block's range) nobody has taken yet
@@ -820,7 +822,7 @@ __global__ __launch_bounds__(NW * 64) void k_scan(ScanParams P) {
   const int e = lut_exponent(__uint_as_float(P.lutmax[q]), M, RES ? P.qbmax[q] : 0.0f,
                              RES == 2 ? P.pv_max : 0.0f);
   int *bkey = buf_key_all + w * CAP;
-  long long *bid = buf_id_all + w * CAP;
+  int *bpos = buf_pos_all + w * CAP;
 
   // per-lane column offsets: x[ip] = ((lane ^ ip) & 31) * 4, with 1 in byte 2
   // (selected by the permute only for lookups in the second table).
@@ -889,7 +891,7 @@ __global__ __launch_bounds__(NW * 64) void k_scan(ScanParams P) {
   auto compact = [&]() {
     wave_sync();
     int kk[E];
-    long long ii[E];
+    int pp[E];
     uint32_t uk[E];
     bool vv[E];
 #pragma unroll
@@ -897,7 +899,7 @@ __global__ __launch_bounds__(NW * 64) void k_scan(ScanParams P) {
       const int idx = lane + 64 * e;
       vv[e] = idx < cnt;
       kk[e] = vv[e] ? bkey[idx] : kKeyInvalid;
-      ii[e] = vv[e] ? bid[idx] : 0;
+      pp[e] = vv[e] ? bpos[idx] : 0;
       uk[e] = (uint32_t)kk[e] ^ 0x80000000u;  // order-preserving unsigned form
     }
     uint32_t prefix = 0;
@@ -909,31 +911,54 @@ __global__ __launch_bounds__(NW * 64) void k_scan(ScanParams P) {
       if (c < k) prefix = cand;  // fewer than k keys below cand: the k-th smallest is >= cand
     }
     const int T = (int)(prefix ^ 0x80000000u);
+    int kept = 0, below = 0;
+#pragma unroll
+    for (int e = 0; e < E; ++e) {
+      kept += __popcll(__ballot(vv[e] && kk[e] <= T));
+      below += __popcll(__ballot(vv[e] && kk[e] < T));
+    }
+    // Usually all keys up to T stay.  Only with a mass of keys equal to T (more than
+    // the buffer can carry along) the ties are cut exactly: their ids are read and
+    // the (k - below) smallest ids stay, found by the same bitwise search on the
+    // order-preserving unsigned form of the id.
+    unsigned long long id_cut = ~0ull;
+    unsigned long long uid[E];
+    const bool cut_ties = kept > CAP - 64;  // wave-uniform
+    if (cut_ties) {
+      const int need = k - below;  // >= 1: fewer than k keys lie below the k-th smallest
+#pragma unroll
+      for (int e = 0; e < E; ++e) {
+        const bool tie = vv[e] && kk[e] == T;
+        uid[e] = tie ? ((unsigned long long)P.tile_ids[pp[e]] ^ 0x8000000000000000ull) : ~0ull;
+      }
+      unsigned long long pre = 0;
+      for (int bit = 63; bit >= 0; --bit) {
+        const unsigned long long cand = pre | (1ull << bit);
+        int c = 0;
+#pragma unroll
+        for (int e = 0; e < E; ++e)
+          c += __popcll(__ballot(vv[e] && kk[e] == T && uid[e] < cand));
+        if (c < need) pre = cand;
+      }
+      id_cut = pre;
+    }
     wave_sync();
     int base = 0;
 #pragma unroll
     for (int e = 0; e < E; ++e) {
-      const bool keep = vv[e] && kk[e] <= T;
+      bool keep = vv[e] && kk[e] <= T;
+      if (cut_ties && keep && kk[e] == T) keep = uid[e] <= id_cut;
       const unsigned long long mask = __ballot(keep);
       if (keep) {
         const int o = base + __popcll(mask & lt_mask);
         bkey[o] = kk[e];
-        bid[o] = ii[e];
+        bpos[o] = pp[e];
       }
       base += __popcll(mask);
     }
     cnt = base;
     tk = min(tk, T);
     if (lane == 0) atomicMin(s_thr, T);
-    if (cnt > CAP - 64) {  // only with a mass of equal keys: trim exactly by (key, id)
-      for (int i = cnt + lane; i < CAP; i += 64) {
-        bkey[i] = kKeyInvalid;
-        bid[i] = 0x7fffffffffffffffll;
-      }
-      wave_sync();
-      bitonic_sort_lds<false>(bkey, bid, CAP, lane, 64);
-      cnt = k;
-    }
   };
 
   auto process = [&](const TileRef &tr, const uint4 (&c)[M / 16], float pv) {
@@ -965,10 +990,9 @@ __global__ __launch_bounds__(NW * 64) void k_scan(ScanParams P) {
     const unsigned long long mask = __ballot(pass);
     if (mask) {  // rare after the first tiles
       if (pass) {
-        const long long id = P.tile_ids[(size_t)tr.gtile * kTileVecs + lane];
         const int off = cnt + __popcll(mask & lt_mask);
         bkey[off] = key;
-        bid[off] = id;
+        bpos[off] = tr.gtile * kTileVecs + lane;
       }
       cnt += __popcll(mask);
       if (cnt > CAP - 64) compact();
@@ -1072,18 +1096,18 @@ __global__ __launch_bounds__(NW * 64) void k_scan(ScanParams P) {
   __syncthreads();
   constexpr int kMaxCand = NW * (CAP - 64);        // every wave holds at most CAP - 64
   constexpr int kFin = kMaxCand <= 1024 ? 1024 : 2048;  // power of two >= kMaxCand
-  static_assert(kMaxCand <= kFin && kMaxCand * 12 + kFin * 12 <= 65536, "merge arrays fit");
-  long long *mid = reinterpret_cast<long long *>(smem);
-  int *mkey = reinterpret_cast<int *>(smem + (size_t)kMaxCand * 8);
-  long long *fid = reinterpret_cast<long long *>(smem + (size_t)kMaxCand * 12);
-  int *fkey = reinterpret_cast<int *>(smem + (size_t)kMaxCand * 12 + (size_t)kFin * 8);
+  static_assert(kMaxCand <= kFin && kMaxCand * 8 + kFin * 12 <= 65536, "merge arrays fit");
+  int *mpos = reinterpret_cast<int *>(smem);
+  int *mkey = reinterpret_cast<int *>(smem + (size_t)kMaxCand * 4);
+  long long *fid = reinterpret_cast<long long *>(smem + (size_t)kMaxCand * 8);
+  int *fkey = reinterpret_cast<int *>(smem + (size_t)kMaxCand * 8 + (size_t)kFin * 8);
   {
     // Some wave holds k candidates at or below s_thr (the smallest k-th key any wave
     // found), so nothing above it can be among the block's k best: only the
     // candidates at or below it are gathered, a few more than k in all.
     const int thr = *s_thr;
     int kk[E];
-    long long ii[E];
+    int pp[E];
     bool keep[E];
     int mine = 0;
 #pragma unroll
@@ -1091,7 +1115,7 @@ __global__ __launch_bounds__(NW * 64) void k_scan(ScanParams P) {
       const int idx = lane + 64 * e2;
       const bool v = idx < cnt;
       kk[e2] = v ? bkey[idx] : kKeyInvalid;
-      ii[e2] = v ? bid[idx] : 0;
+      pp[e2] = v ? bpos[idx] : 0;
       keep[e2] = v && kk[e2] <= thr;
       mine += __popcll(__ballot(keep[e2]));
     }
@@ -1104,7 +1128,7 @@ __global__ __launch_bounds__(NW * 64) void k_scan(ScanParams P) {
       if (keep[e2]) {
         const int o = base + __popcll(mask & lt_mask);
         mkey[o] = kk[e2];
-        mid[o] = ii[e2];
+        mpos[o] = pp[e2];
       }
       base += __popcll(mask);
     }
@@ -1114,7 +1138,8 @@ __global__ __launch_bounds__(NW * 64) void k_scan(ScanParams P) {
   const int n = *s_total;
   // Keys of the gathered candidates in registers (order-preserving unsigned form), RR
   // per lane: bitwise search for the k-th smallest key, then everything at or below
-  // it moves to (fkey, fid).  Usually only a few more than k candidates arrive here.
+  // it moves to (fkey, fid), its id read from the cluster region.  Usually only a few
+  // more than k candidates arrive here.
   constexpr int R = kMaxCand / 64;
   int nf = 0;
   auto select_kth = [&](auto rr_tag) {
@@ -1145,7 +1170,7 @@ __global__ __launch_bounds__(NW * 64) void k_scan(ScanParams P) {
       if (keep) {
         const int o = nf + __popcll(mask & lt_mask);
         fkey[o] = (int)(rk[e2] ^ 0x80000000u);
-        fid[o] = mid[i];
+        fid[o] = P.tile_ids[mpos[i]];  // the finalists' ids, for the exact (key, id) order
       }
       nf += __popcll(mask);
     }
@@ -1198,7 +1223,7 @@ __global__ __launch_bounds__(NW * 64) void k_scan(ScanParams P) {
 template <int M, int NW, int CAP, int RES>
 static hipError_t launch_scan_t(const ScanParams &P, int nq, hipStream_t st) {
   using G = ScanGeom<M>;
-  const size_t lds = (size_t)G::kTables * G::kTableBytes + (size_t)NW * CAP * 12 + 64;
+  const size_t lds = (size_t)G::kTables * G::kTableBytes + (size_t)NW * CAP * 8 + 64;
   static bool attr_done = false;
   if (!attr_done) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_scan<M, NW, CAP, RES>),
@@ -1253,14 +1278,14 @@ hipError_t launch_scan(const Shape &sh, const DevLayout &L, const BatchWs &W, in
   (res == 0 ? launch_scan_t<MM, NW_, CAP_, 0>(P, nq, st)                          \
             : res == 1 ? launch_scan_t<MM, NW_, CAP_, 1>(P, nq, st)               \
                        : launch_scan_t<MM, NW_, CAP_, 2>(P, nq, st))
-  // Wavefronts per block and candidate slots per wavefront (at least k + 64).
-  // Two tables (96 or 128 code bytes) leave 32 KB of LDS for the buffers: 16
-  // wavefronts of 128 slots up to k = 64, 12 of 192 above.  One table leaves room
-  // for two blocks of eight wavefronts per CU up to k = 64 (one stages its table
-  // while the other streams), one block of 16 above.
+  // Wavefronts per block and candidate slots (8 bytes each) per wavefront, at
+  // least k + 64.  Two tables (96 or 128 code bytes) leave 32 KB of LDS for the
+  // buffers: 16 wavefronts of 128 slots up to k = 64, of 192 above.  One table
+  // leaves room for two blocks of eight wavefronts per CU up to k = 64 (one
+  // stages its table while the other streams), one block of 16 above.
 #define IVF_SCAN_CASE(MM) \
   case MM:                \
-    return k <= 64 ? IVF_SCAN_RES(MM, 16, 128) : IVF_SCAN_RES(MM, 12, 192);
+    return k <= 64 ? IVF_SCAN_RES(MM, 16, 128) : IVF_SCAN_RES(MM, 16, 192);
 #define IVF_SCAN_CASE_SMALL(MM) \
   case MM:                      \
     return k <= 64 ? IVF_SCAN_RES(MM, 8, 128) : IVF_SCAN_RES(MM, 16, 192);

@@ -22,11 +22,11 @@ static int pick_slices(const ivf_index *ix, const BatchCtx &c, int64_t nq, int n
   if (ix->tune_slices > 0) return ix->tune_slices;
   // one block per query fills the chip's 256 compute units (each holding one or
   // two scan blocks) from that many queries up; below that, split - but not so
-  // far that a block's wavefronts (8, 12 or 16) are left with fewer than two tiles each
+  // far that a block's wavefronts (8 or 16) are left with fewer than two tiles each
   const int per_cu = scan_blocks_per_cu(ix->sh.M, k);
   const int64_t fill = 256 * (int64_t)per_cu;
   int s = (int)((fill + nq - 1) / nq);
-  const int waves = per_cu == 2 ? 8 : ((k > 64 && ix->sh.M > 64) ? 12 : 16);
+  const int waves = per_cu == 2 ? 8 : 16;
   const int64_t tiles = (int64_t)nprobe * c.list_tiles;  // estimate per query
   s = (int)std::min<int64_t>(s, std::max<int64_t>(1, tiles / (2 * waves)));
   if (s < 1) s = 1;
