@@ -1278,17 +1278,18 @@ hipError_t launch_scan(const Shape &sh, const DevLayout &L, const BatchWs &W, in
   (res == 0 ? launch_scan_t<MM, NW_, CAP_, 0>(P, nq, st)                          \
             : res == 1 ? launch_scan_t<MM, NW_, CAP_, 1>(P, nq, st)               \
                        : launch_scan_t<MM, NW_, CAP_, 2>(P, nq, st))
-  // Wavefronts per block and candidate slots (8 bytes each) per wavefront, at
-  // least k + 64.  Two tables (96 or 128 code bytes) leave 32 KB of LDS for the
-  // buffers: 16 wavefronts of 128 slots up to k = 64, of 192 above.  One table
-  // leaves room for two blocks of eight wavefronts per CU up to k = 64 (one
-  // stages its table while the other streams), one block of 16 above.
+  // Wavefronts per block and candidate slots (8 bytes each) per wavefront: at
+  // least k + 64 slots; 128 up to k = 48, 192 above (at k near 64 a buffer of 128
+  // would be trimmed after every 64 insertions).  Two tables (96 or 128 code
+  // bytes) leave 32 KB of LDS for the buffers of 16 wavefronts.  One table leaves
+  // room for two blocks of eight wavefronts per CU up to k = 64 (one stages its
+  // table while the other streams), one block of 16 above.
 #define IVF_SCAN_CASE(MM) \
   case MM:                \
-    return k <= 64 ? IVF_SCAN_RES(MM, 16, 128) : IVF_SCAN_RES(MM, 16, 192);
+    return k <= 48 ? IVF_SCAN_RES(MM, 16, 128) : IVF_SCAN_RES(MM, 16, 192);
 #define IVF_SCAN_CASE_SMALL(MM) \
   case MM:                      \
-    return k <= 64 ? IVF_SCAN_RES(MM, 8, 128) : IVF_SCAN_RES(MM, 16, 192);
+    return k <= 48 ? IVF_SCAN_RES(MM, 8, 128) : (k <= 64 ? IVF_SCAN_RES(MM, 8, 192) : IVF_SCAN_RES(MM, 16, 192));
   switch (sh.M) {
     IVF_SCAN_CASE_SMALL(16)
     IVF_SCAN_CASE_SMALL(32)
