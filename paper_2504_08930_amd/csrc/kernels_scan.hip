@@ -434,15 +434,13 @@ hipError_t launch_route(const int32_t *probe, int nq, int nprobe, int probe_stri
 // plus the largest |entry| per query for the fixed-point scale.
 // Thread (ml, jl) owns JPT codewords of sub-quantizer m in registers (eight for
 // sub-vectors of up to 16 elements, fewer for longer ones so that they still
-// fit) and loops over the queries of its tile, so codebooks are read once per
-// query tile and each query sub-vector once per JPT entries.  Lanes run along
+// fit) and strides over the queries, so a block reads its codewords once and each
+// query sub-vector once per JPT entries.  Lanes run along
 // m: table stores are contiguous in m.  Sub-vector lengths without an
 // instantiation take DSUB = 0: nothing is held in registers and every entry
 // re-reads its codeword (correct, and an order of magnitude slower).
 // ---------------------------------------------------------------------------
-constexpr int kLutQTile = 8;   // queries per block
-
-template <int DSUB, int JPT>
+template <int DSUB, int JPT, int NT>
 __global__ __launch_bounds__(256) void k_lut(const float *__restrict__ queries, int nq, int d,
                                              int M, int dsub_rt, int MW,
                                              const float *__restrict__ cbT, int kind,
@@ -454,9 +452,6 @@ __global__ __launch_bounds__(256) void k_lut(const float *__restrict__ queries, 
   const int ml = tid % MW, jl = tid / MW;
   const int m = blockIdx.y * MW + ml;
   const int j0 = blockIdx.x * (JL * JPT) + jl;  // this thread's codes: j0 + t * JL
-  const int q0 = blockIdx.z * kLutQTile;
-  const int q1 = min(nq, q0 + kLutQTile);
-
   float creg[JPT][DSUB > 0 ? DSUB : 1];
   if (DSUB > 0) {
 #pragma unroll
@@ -466,7 +461,7 @@ __global__ __launch_bounds__(256) void k_lut(const float *__restrict__ queries, 
       for (int i = 0; i < DSUB; ++i) creg[t][i] = cw[i];
     }
   }
-  for (int qi = q0; qi < q1; ++qi) {
+  for (int qi = blockIdx.z; qi < nq; qi += gridDim.z) {
     const float *qv = queries + (size_t)qi * d + (size_t)m * dsub;
     float qreg[DSUB > 0 ? DSUB : 1];
     if (DSUB > 0) {
@@ -479,7 +474,9 @@ __global__ __launch_bounds__(256) void k_lut(const float *__restrict__ queries, 
       const int j = j0 + t * JL;
       const float v = DSUB > 0 ? lut_entry(kind, qreg, creg[t], DSUB)
                                : lut_entry(kind, qv, cbT + ((size_t)j * M + m) * dsub, dsub);
-      lut[((size_t)qi * 256 + j) * M + m] = v;
+      float *dst = &lut[((size_t)qi * 256 + j) * M + m];
+      if (NT) __builtin_nontemporal_store(v, dst);
+      else *dst = v;
       mxf = fmaxf(mxf, fabsf(v));
     }
     // largest |entry| seen by this wave for the query: a plain store into the
@@ -492,6 +489,22 @@ __global__ __launch_bounds__(256) void k_lut(const float *__restrict__ queries, 
       lutpart[(size_t)qi * kLutMaxParts + part] = mx;
     }
   }
+}
+
+// Query strides of the table kernel: as many (x, y, z) blocks as the chip's 256
+// compute units hold at once, so the launch is one even round of blocks.
+template <int DSUB, int JPT>
+static int lut_zblocks(unsigned xy, int nq) {
+  static const int per_cu = [] {
+    int n = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, k_lut<DSUB, JPT, 0>, 256, 0) != hipSuccess || n < 1)
+      n = 1;
+    return n;
+  }();
+  int z = (int)(256u * (unsigned)per_cu / xy);
+  if (z < 1) z = 1;
+  if (z > nq) z = nq;
+  return z;
 }
 
 // 4-bit codes: the table the scan reads has one column per code BYTE; entry j of
@@ -575,11 +588,22 @@ hipError_t launch_lut(const Shape &sh, const float *q, int nq, const float *cbT,
   }
   const int MW = (sh.M % 32 == 0) ? 32 : 16;
   const int JL = 256 / MW;
+  // Tables of more than 32 MB per batch are stored past the caches: the scan reads
+  // them several kernels later, and what they leave dirty in the last-level cache
+  // is written back under the scan (measured: the scan of a batch of 512 or more
+  // queries at 96 code bytes runs 2 % faster this way; smaller tables, and the
+  // 4-bit kernel's at any size, gain nothing).
+  const bool stream_out = (size_t)nq * 256 * sh.M * sizeof(float) > ((size_t)32 << 20);
 #define IVF_LUT_CASE(DS, JPT_)                                                                  \
   case DS:                                                                                     \
-    grid = dim3(256 / (JL * JPT_), sh.M / MW, (nq + kLutQTile - 1) / kLutQTile);               \
-    hipLaunchKernelGGL((k_lut<DS, JPT_>), grid, dim3(256), 0, st, q, nq, sh.d, sh.M, sh.dsub,  \
-                       MW, cbT, sh.lut_kind(), lut, lutpart);                                  \
+    grid = dim3(256 / (JL * JPT_), sh.M / MW, 1);                                              \
+    grid.z = lut_zblocks<DS, JPT_>(grid.x * grid.y, nq);                                       \
+    if (stream_out)                                                                            \
+      hipLaunchKernelGGL((k_lut<DS, JPT_, 1>), grid, dim3(256), 0, st, q, nq, sh.d, sh.M,      \
+                         sh.dsub, MW, cbT, sh.lut_kind(), lut, lutpart);                       \
+    else                                                                                       \
+      hipLaunchKernelGGL((k_lut<DS, JPT_, 0>), grid, dim3(256), 0, st, q, nq, sh.d, sh.M,      \
+                         sh.dsub, MW, cbT, sh.lut_kind(), lut, lutpart);                       \
     break;
   dim3 grid;
   switch (sh.dsub) {
@@ -596,8 +620,9 @@ hipError_t launch_lut(const Shape &sh, const float *q, int nq, const float *cbT,
     IVF_LUT_CASE(48, 1)
     IVF_LUT_CASE(64, 1)
     default:
-      grid = dim3(256 / (JL * 8), sh.M / MW, (nq + kLutQTile - 1) / kLutQTile);
-      hipLaunchKernelGGL((k_lut<0, 8>), grid, dim3(256), 0, st, q, nq, sh.d, sh.M, sh.dsub, MW,
+      grid = dim3(256 / (JL * 8), sh.M / MW, 1);
+      grid.z = lut_zblocks<0, 8>(grid.x * grid.y, nq);
+      hipLaunchKernelGGL((k_lut<0, 8, 0>), grid, dim3(256), 0, st, q, nq, sh.d, sh.M, sh.dsub, MW,
                          cbT, sh.lut_kind(), lut, lutpart);
   }
 #undef IVF_LUT_CASE
