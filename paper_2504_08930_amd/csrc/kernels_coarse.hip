@@ -322,7 +322,7 @@ hipError_t launch_coarse_gemm(const Shape &sh, const void *q_parts, const int32_
 // Exact per-query selection of the `keep` best (score, id) pairs, best first,
 // ties to the smaller cluster id.  64-bit key = ordered score bits : id; an
 // MSB-first radix select finds the keep-th smallest key, a final pass collects
-// everything not larger and a bitonic sort orders it.
+// everything not larger and a counting pass ranks it.
 // ---------------------------------------------------------------------------
 __device__ __forceinline__ uint32_t score_bits(float s, int metric_ip) {
   uint32_t u = __float_as_uint(s);
@@ -646,32 +646,43 @@ __global__ __launch_bounds__(kSelThreads) void k_coarse_select(const float *__re
     __syncthreads();
   }
   __syncthreads();
-  // ---- exact order of the collected candidates: one wavefront, bitonic in LDS ----
-  if (wave == 0) {
-    int n2 = 2;
-    const int filled = (int)min(s_count, (unsigned)cap);
-    while (n2 < filled) n2 <<= 1;
-    for (int size = 2; size <= n2; size <<= 1) {
-      for (int st = size >> 1; st > 0; st >>= 1) {
-        for (int i = lane; i < n2; i += 64) {
-          const int j = i ^ st;
-          if (j > i) {
-            const bool asc = (i & size) == 0;
-            const unsigned long long a = sel[i], b = sel[j];
-            if ((b < a) == asc) {
-              sel[i] = b;
-              sel[j] = a;
-            }
-          }
-        }
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-      }
+  // ---- exact order of the collected candidates: rank by counting ----
+  // Keys are distinct (the id is part of them), so the number of keys that come
+  // before a candidate's is its rank.  Up to kSelThreads candidates: every
+  // thread counts, for one candidate, one stretch of the others, and the
+  // stretches' counts are added up in LDS; more: a thread counts all of them
+  // for each candidate it owns.  Lanes of a wavefront compare against the same
+  // key at a time (one LDS broadcast).
+  const int filled = (int)min(s_count, (unsigned)cap);
+  int n2 = 64;
+  while (n2 < filled) n2 <<= 1;
+  if (n2 <= kSelThreads) {
+    unsigned int *rank = hist;
+    if (tid < n2) rank[tid] = 0u;
+    __syncthreads();
+    const int i = tid & (n2 - 1), part = tid / n2, n_parts = kSelThreads / n2;
+    const int per = (filled + n_parts - 1) / n_parts;
+    if (i < filled) {
+      const unsigned long long mine = sel[i];
+      const int j1 = min(filled, (part + 1) * per);
+      unsigned cnt = 0;
+      for (int j = part * per; j < j1; ++j) cnt += sel[j] < mine ? 1u : 0u;
+      if (cnt) atomicAdd(&rank[i], cnt);
     }
-    for (int p = lane; p < nprobe; p += 64)
-      out[p] = p < keep ? (int32_t)(sel[p] & 0xffffffffull) : -1;
+    __syncthreads();
+    if (tid < filled) {
+      const unsigned r = rank[tid];
+      if (r < (unsigned)keep) out[r] = (int32_t)(sel[tid] & 0xffffffffull);
+    }
+  } else {
+    for (int i = tid; i < filled; i += kSelThreads) {
+      const unsigned long long mine = sel[i];
+      unsigned cnt = 0;
+      for (int j = 0; j < filled; ++j) cnt += sel[j] < mine ? 1u : 0u;
+      if (cnt < (unsigned)keep) out[cnt] = (int32_t)(mine & 0xffffffffull);
+    }
   }
+  for (int p = min(filled, keep) + tid; p < nprobe; p += kSelThreads) out[p] = -1;
 }
 
 hipError_t launch_coarse_select(const Shape &sh, const float *scores, int nq, int nprobe,
