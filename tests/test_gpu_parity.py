@@ -422,6 +422,39 @@ def test_more_lists_than_the_select_holds_in_registers(pkg, oracle):
     index.close()
 
 
+def test_coarse_probes_come_best_first(pkg, oracle):
+    """The probe list is ordered best cluster first, at every size of the
+    selection's candidate set (one stretch of candidates per thread, several
+    candidates per thread, more candidates than threads).  The oracle's fp64
+    scores of the returned clusters must be monotone up to the coarse tolerance,
+    and the set must be the oracle's up to ties at the boundary."""
+    import torch
+    from synthdata.workloads import METRIC_IP, METRIC_L2, WorkloadSpec
+    from tests.parity import COARSE_RTOL
+    for metric in (METRIC_L2, METRIC_IP):
+        spec = WorkloadSpec("S3k", 9_000, 16, 512, 3_000, 16, metric, metric == METRIC_IP,
+                            24, 40, 10, None, 1.0, kmeans_iters=1)
+        ix = build_index(spec, device="cuda")
+        q, _ = make_queries(spec, mixture_centers(spec, torch.device("cuda")))
+        q = q.cpu().numpy()[:48]
+        qd = torch.from_numpy(q).cuda()
+        index = pkg.IvfIndex(ix, max_nq=64, max_nprobe=2048, max_k=16)
+        all_probe, all_score, _ = oracle.coarse(ix.metric, ix.centroids, q, ix.nlist)
+        S = scale_S(ix.metric, q)
+        for nprobe in (1, 5, 64, 100, 300, 600, 1500):
+            _say(f"metric {metric} nprobe {nprobe}")
+            got = index.coarse_probe_dev(qd, nprobe).cpu().numpy()
+            compare_probes(got, all_probe, all_score, nprobe, S)
+            for r in range(q.shape[0]):
+                assert len(set(got[r].tolist())) == nprobe
+                score = np.empty(ix.nlist)
+                score[all_probe[r]] = all_score[r]
+                v = score[got[r]] if metric == METRIC_L2 else -score[got[r]]
+                band = COARSE_RTOL * np.maximum(np.abs(v[:-1]), S)
+                assert np.all(np.diff(v) >= -band), (metric, nprobe, r)
+        index.close()
+
+
 def test_coarse_ties_go_to_the_smaller_cluster_id(pkg, oracle):
     """All centroids equal: every coarse score of a query is the same number, the
     selection's histogram has no range to bin and its exact fall-back decides;
