@@ -16,10 +16,12 @@ def scale_S(metric, queries):
     return float((np.asarray(queries, np.float64) ** 2).sum(1).mean())
 
 
-def compare_topk(got_ids, got_d, ref_ids_ext, ref_d_ext, k, S, rtol=RTOL):
+def compare_topk(got_ids, got_d, ref_ids_ext, ref_d_ext, k, S, rtol=RTOL, details=None):
     """ref_*_ext: oracle results for k_ext >= k ranks.  Returns the number of
     queries whose id lists differ (all such differences verified to be ties
-    within tolerance); raises AssertionError on a real mismatch."""
+    within tolerance); raises AssertionError on a real mismatch.  details (a
+    list) receives (query, rank, |oracle distance of the id found - oracle
+    distance at that rank| / tolerance) for every rank that differs."""
     nq = got_ids.shape[0]
     ambiguous = 0
     for q in range(nq):
@@ -41,6 +43,8 @@ def compare_topk(got_ids, got_d, ref_ids_ext, ref_d_ext, k, S, rtol=RTOL):
                 continue
             assert int(gi[r]) in ext, f"query {q} rank {r}: id {gi[r]} not near the oracle's top"
             d_or = ext[int(gi[r])]
+            if details is not None:
+                details.append((q, r, abs(d_or - rd[r]) / tol[r]))
             assert abs(d_or - rd[r]) <= tol[r], \
                 f"query {q} rank {r}: id {gi[r]} (oracle d={d_or}) vs {ri[r]} (d={rd[r]})"
         assert len(set(gi[fin].tolist())) == int(fin.sum()), f"query {q}: duplicate ids"
