@@ -10,6 +10,7 @@
 #include <math.h>
 
 #include <algorithm>
+#include <atomic>
 
 #include "internal.h"
 
@@ -289,13 +290,13 @@ static hipError_t launch_gemm_t(const Shape &sh, const void *q_parts, const int3
                                 const float *cent_norm, float *scores, hipStream_t st) {
   constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
   const size_t lds = (size_t)2 * (BM + BN) * kRowBytes;
-  static bool attr_done = false;
-  if (!attr_done) {
+  static std::atomic<bool> attr_done{false};  // setting it twice is harmless
+  if (!attr_done.load(std::memory_order_acquire)) {
     hipError_t e =
         hipFuncSetAttribute(reinterpret_cast<const void *>(&k_coarse_gemm<WM, WN, TM, TN>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
-    attr_done = true;
+    attr_done.store(true, std::memory_order_release);
   }
   const int row_tiles = (nq + BM - 1) / BM;
   const int col_tiles = (sh.nlist + BN - 1) / BN;

@@ -26,6 +26,7 @@
 //    does not change the sum.
 #include <hip/hip_runtime.h>
 
+#include <atomic>
 #include <type_traits>
 
 #include "internal.h"
@@ -1249,12 +1250,12 @@ template <int M, int NW, int CAP, int RES>
 static hipError_t launch_scan_t(const ScanParams &P, int nq, hipStream_t st) {
   using G = ScanGeom<M>;
   const size_t lds = (size_t)G::kTables * G::kTableBytes + (size_t)NW * CAP * 8 + 64;
-  static bool attr_done = false;
-  if (!attr_done) {
+  static std::atomic<bool> attr_done{false};  // setting it twice is harmless
+  if (!attr_done.load(std::memory_order_acquire)) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_scan<M, NW, CAP, RES>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
-    attr_done = true;
+    attr_done.store(true, std::memory_order_release);
   }
   const int total = nq * P.slices;
   const int grid = (total + 8 * kScanChunk - 1) / (8 * kScanChunk) * (8 * kScanChunk);
