@@ -131,8 +131,10 @@ hipError_t launch_route(const int32_t *probe, int nq, int nprobe, int probe_stri
                         const uint32_t *lutpart, int lut_parts, uint32_t *lutmax, hipStream_t st);
 
 // Lookup tables of every query and, per query, *n_parts partial maxima in lutpart.
+// With q_parts != NULL the launch also does launch_split_f16(q, nq, d, q_parts, q_exp).
 hipError_t launch_lut(const Shape &sh, const float *q, int nq, const float *cbT, float *lut,
-                      uint32_t *lutpart, int *n_parts, hipStream_t st);
+                      uint32_t *lutpart, int *n_parts, void *q_parts, int32_t *q_exp,
+                      hipStream_t st);
 
 // After the router: batch totals of the router counters, the scan's visiting order.
 hipError_t launch_order(const BatchWs &W, int nq, int probe_stride, int M,

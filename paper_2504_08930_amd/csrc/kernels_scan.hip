@@ -31,6 +31,7 @@
 
 #include "internal.h"
 #include "lut_quant.h"
+#include "split_f16.h"
 
 namespace ivf {
 
@@ -446,7 +447,8 @@ __global__ __launch_bounds__(256) void k_lut(const float *__restrict__ queries, 
                                              int M, int dsub_rt, int MW,
                                              const float *__restrict__ cbT, int kind,
                                              float *__restrict__ lut,
-                                             uint32_t *__restrict__ lutpart) {
+                                             uint32_t *__restrict__ lutpart, SplitJob split) {
+  run_split_job(split);  // the queries' fp16 split for the coarse GEMM, if asked for
   const int dsub = DSUB > 0 ? DSUB : dsub_rt;
   const int tid = threadIdx.x;
   const int JL = 256 / MW;  // j lanes per block
@@ -518,7 +520,8 @@ template <int DSUB>
 __global__ __launch_bounds__(256) void k_lut4(const float *__restrict__ queries, int d, int M,
                                               int dsub_rt, const float *__restrict__ cbT, int kind,
                                               int rows_per_block, float *__restrict__ lut,
-                                              uint32_t *__restrict__ lutpart) {
+                                              uint32_t *__restrict__ lutpart, SplitJob split) {
+  run_split_job(split);
   __shared__ float t_even[16 * 128];  // [j][m]: sub-quantizer 2m
   __shared__ float t_odd[16 * 128];   //         sub-quantizer 2m + 1
   __shared__ float qs[2048];          // the query (d <= 2048 is checked by the launcher)
@@ -563,7 +566,11 @@ __global__ __launch_bounds__(256) void k_lut4(const float *__restrict__ queries,
 }
 
 hipError_t launch_lut(const Shape &sh, const float *q, int nq, const float *cbT, float *lut,
-                      uint32_t *lutpart, int *n_parts, hipStream_t st) {
+                      uint32_t *lutpart, int *n_parts, void *q_parts, int32_t *q_exp,
+                      hipStream_t st) {
+  // q_parts != NULL: the same launch also splits the queries into fp16 parts for
+  // the coarse GEMM (both depend on the queries only)
+  const SplitJob job{q, (uint4 *)q_parts, q_exp, q_parts ? nq : 0, sh.d / 8};
   if (sh.nbits == 4) {
     if (sh.d > 2048 || sh.M > 128) return hipErrorInvalidValue;
     const int split = nq >= 512 ? 1 : (nq >= 128 ? 4 : 16);  // blocks per query
@@ -572,7 +579,7 @@ hipError_t launch_lut(const Shape &sh, const float *q, int nq, const float *cbT,
 #define IVF_LUT4_CASE(DS)                                                                  \
   case DS:                                                                                 \
     hipLaunchKernelGGL(k_lut4<DS>, grid, dim3(256), 0, st, q, sh.d, sh.M, sh.dsub, cbT,    \
-                       sh.lut_kind(), rows, lut, lutpart);                                 \
+                       sh.lut_kind(), rows, lut, lutpart, job);                            \
     break;
     switch (sh.dsub) {
       IVF_LUT4_CASE(1)
@@ -581,7 +588,7 @@ hipError_t launch_lut(const Shape &sh, const float *q, int nq, const float *cbT,
       IVF_LUT4_CASE(8)
       default:
         hipLaunchKernelGGL(k_lut4<0>, grid, dim3(256), 0, st, q, sh.d, sh.M, sh.dsub, cbT,
-                           sh.lut_kind(), rows, lut, lutpart);
+                           sh.lut_kind(), rows, lut, lutpart, job);
     }
 #undef IVF_LUT4_CASE
     *n_parts = split * 4;
@@ -601,10 +608,10 @@ hipError_t launch_lut(const Shape &sh, const float *q, int nq, const float *cbT,
     grid.z = lut_zblocks<DS, JPT_>(grid.x * grid.y, nq);                                       \
     if (stream_out)                                                                            \
       hipLaunchKernelGGL((k_lut<DS, JPT_, 1>), grid, dim3(256), 0, st, q, nq, sh.d, sh.M,      \
-                         sh.dsub, MW, cbT, sh.lut_kind(), lut, lutpart);                       \
+                         sh.dsub, MW, cbT, sh.lut_kind(), lut, lutpart, job);                       \
     else                                                                                       \
       hipLaunchKernelGGL((k_lut<DS, JPT_, 0>), grid, dim3(256), 0, st, q, nq, sh.d, sh.M,      \
-                         sh.dsub, MW, cbT, sh.lut_kind(), lut, lutpart);                       \
+                         sh.dsub, MW, cbT, sh.lut_kind(), lut, lutpart, job);                       \
     break;
   dim3 grid;
   switch (sh.dsub) {
@@ -624,7 +631,7 @@ hipError_t launch_lut(const Shape &sh, const float *q, int nq, const float *cbT,
       grid = dim3(256 / (JL * 8), sh.M / MW, 1);
       grid.z = lut_zblocks<0, 8>(grid.x * grid.y, nq);
       hipLaunchKernelGGL((k_lut<0, 8, 0>), grid, dim3(256), 0, st, q, nq, sh.d, sh.M, sh.dsub, MW,
-                         cbT, sh.lut_kind(), lut, lutpart);
+                         cbT, sh.lut_kind(), lut, lutpart, job);
   }
 #undef IVF_LUT_CASE
   *n_parts = (int)(grid.x * grid.y * 4);

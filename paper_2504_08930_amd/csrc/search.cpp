@@ -174,8 +174,11 @@ int enqueue_gpu(ivf_index *ix, const SearchArgs &a, const BatchCtx &c, bool fina
   // ---- stage 2 first: the lookup tables depend on the queries only ----
   G_TRY(mark(IVF_STAGE_LUT));
   int lut_parts = 0;
+  // ... and so does the fp16 split of the queries for the coarse GEMM: one launch
+  const bool split_with_lut = c.any_resident && !a.probe_host;
   if (c.any_resident)
-    G_TRY(launch_lut(sh, dq, nq, L.cbT, W.lut, W.lutpart, &lut_parts, st));
+    G_TRY(launch_lut(sh, dq, nq, L.cbT, W.lut, W.lutpart, &lut_parts,
+                     split_with_lut ? W.q_parts : nullptr, W.q_exp, st));
   // ---- stage 1: coarse quantizer (or the caller's probe list) ----
   G_TRY(mark(IVF_STAGE_COARSE_GEMM));
   if (a.probe_host) {
@@ -183,7 +186,7 @@ int enqueue_gpu(ivf_index *ix, const SearchArgs &a, const BatchCtx &c, bool fina
     G_TRY(hipMemcpyAsync(W.probe, ix->h_probe, (size_t)nq * np * 4, hipMemcpyHostToDevice, st));
     G_TRY(mark(IVF_STAGE_COARSE_SELECT));
   } else {
-    G_TRY(launch_split_f16(dq, (size_t)nq, sh.d, W.q_parts, W.q_exp, st));
+    if (!split_with_lut) G_TRY(launch_split_f16(dq, (size_t)nq, sh.d, W.q_parts, W.q_exp, st));
     G_TRY(launch_coarse_gemm(sh, W.q_parts, W.q_exp, nq, L.cent_parts, L.cent_exp, L.cent_norm,
                              W.scores, st));
     G_TRY(mark(IVF_STAGE_COARSE_SELECT));

