@@ -62,10 +62,13 @@ def _kmeans(x, k, iters, spherical, seed, chunk):
     cent = x[perm].clone()
     for _ in range(iters):
         a = _best_centroid(x, cent, spherical, chunk)
-        sums = torch.zeros_like(cent)
-        sums.index_add_(0, a, x)
-        cnt = torch.bincount(a, minlength=k).to(x.dtype)
-        new = sums / cnt.clamp_min(1.0)[:, None]
+        # sums in fp64: on a GPU index_add_ adds with atomics in no fixed order, and
+        # in fp64 the order no longer shows in the fp32 result (same index every run)
+        sums = torch.zeros(cent.shape, dtype=torch.float64, device=x.device)
+        for s in range(0, x.shape[0], chunk):
+            sums.index_add_(0, a[s:s + chunk], x[s:s + chunk].double())
+        cnt = torch.bincount(a, minlength=k).double()
+        new = (sums / cnt.clamp_min(1.0)[:, None]).to(x.dtype)
         keep = cnt == 0
         new[keep] = cent[keep]          # an empty cluster keeps its centroid
         if spherical:
@@ -88,10 +91,10 @@ def _train_pq(x, m, iters, seed, ksub=256):
         dist = (cb * cb).sum(2)[:, None, :] - 2.0 * torch.bmm(xs, cb.transpose(1, 2))
         a = dist.argmin(2)                                      # [m, n]
         flat = (a + base).reshape(-1)
-        sums = torch.zeros(m * ksub, dsub, device=x.device, dtype=x.dtype)
-        sums.index_add_(0, flat, xs.reshape(-1, dsub))
-        cnt = torch.bincount(flat, minlength=m * ksub).to(x.dtype)
-        new = (sums / cnt.clamp_min(1.0)[:, None]).view(m, ksub, dsub)
+        sums = torch.zeros(m * ksub, dsub, device=x.device, dtype=torch.float64)  # see _kmeans
+        sums.index_add_(0, flat, xs.reshape(-1, dsub).double())
+        cnt = torch.bincount(flat, minlength=m * ksub).double()
+        new = (sums / cnt.clamp_min(1.0)[:, None]).to(x.dtype).view(m, ksub, dsub)
         keep = (cnt == 0).view(m, ksub)
         new[keep] = cb[keep]
         cb = new

@@ -791,9 +791,9 @@ def test_c4_config_full_size(pkg, oracle):
         _say(f"C4 zipf_s={s_skew}: coarse-ambiguous {n_coarse}, id-ambiguous {n_amb} of {len(sel)}; "
              f"ranks that differ (query, rank, gap / tolerance): "
              f"{[(a, b, round(c, 4)) for a, b, c in det]}")
-        # every difference has been checked to be a tie within the tolerance.  The
-        # index is built on the device with atomic sums, so it is not the same on
-        # every run: 0 to 3 such queries of the 64 have been seen at k = 100.
+        # every difference has been checked to be a tie within the tolerance; over
+        # different builds of the index 0 to 3 such queries of the 64 have been seen
+        # at k = 100
         assert n_coarse <= 1 and n_amb <= 5
         assert (ids >= 0).all() and np.all(np.diff(dist, axis=1) <= 0)
     # resident set from the hit-rate profile: the hottest clusters that cover 80 % of the accesses
@@ -840,9 +840,8 @@ def test_residual_encoding(pkg, oracle, monkeypatch, name, copy_form):
         ids, dist = index.search_batch(q, nprobe, k)
         n_coarse, n_amb = _check_search(oracle, ix, q, nprobe, k, ids, dist, probe)
         # (every id that differs has been checked to be a tie within the tolerance; with 16
-        # codewords per sub-quantizer and k = 100 near-equal distances are common, and the
-        # index, built on the device with atomic sums, is not the same on every run:
-        # 0 to 2 such queries of 32 have been seen)
+        # codewords per sub-quantizer and k = 100 near-equal distances are common: over
+        # different builds of the index 0 to 2 such queries of 32 have been seen)
         assert n_coarse <= 1 and n_amb <= max(3, q.shape[0] // 8)
         if base is None:
             base = (ids, dist)
