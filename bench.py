@@ -42,7 +42,7 @@ HBM_PEAK_GBS = 8000.0
 # HBM-side bytes per k_scan launch from the rocprofv3 --pmc runs (FETCH_SIZE + WRITE_SIZE, scaled
 # by the same counters on a plain copy kernel); valid for exactly this workload and launch shape.
 MEASURED_TRAFFIC = {
-    ("C3", 1024, 1.0): (3.036e9 + 0.164e6, "profiles/c3_nq1024_scan_hbm_traffic.md"),
+    ("C3", 1024, 1.0): (3.016e9 + 0.164e6, "profiles/c3_nq1024_scan_hbm_traffic.md"),
     ("C3", 256, 1.0): (738.5e6 + 0.04e6, "profiles/c3_nq256_scan_hbm_traffic.md"),
 }
 
