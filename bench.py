@@ -20,7 +20,7 @@ Other modes (each prints one JSON line of its own):
   --mode partition  profile the access skew and the CPU tier, pick the partitioning point
                  rho with the latency-bounded model (Eq. 1, Eq. 2, Algorithm 1; synthetic LLM
                  inputs), load it and compare predicted with measured batch latency
-  --mode dispatch  dynamic dispatcher on/off (Section 4.3.2): hybrid batches from host memory at
+  --mode dispatch  dynamic dispatcher on/off (Section 4.2.2): hybrid batches from host memory at
                  several resident fractions; batch latency and mean / p90 per-query hand-off
                  latency of ivf_search_batch_async against the bulk ivf_search_batch
   --mode drift   20 epochs x 10 000 queries, Zipf permutation re-drawn every 5
@@ -266,7 +266,7 @@ def main():
         from paper_2504_08930_amd import binding as B
         nlist = ix.nlist
         lens = np.diff(ix.list_offsets).astype(np.float64)
-        # --- access profile from calibration queries (Section 4.2.1) ---
+        # --- access profile from calibration queries (Section 4.1.1) ---
         index.hit_stats(reset=True)
         probes = []
         for s0 in range(0, calib.shape[0], index.max_nq):

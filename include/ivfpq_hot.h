@@ -6,10 +6,10 @@
  * The calls follow the tiered search structure of the paper: frequently hit
  * clusters are placed on the GPU and the rest stay on the CPU (Section 3.2,
  * Takeaway 2); a query is coarse-quantized, each probed cluster is looked up
- * in a mapping table and routed to the GPU or the CPU scan (Section 4.3.1
- * "Router"), partial results are merged and re-ranked (Section 4.3.2); the
+ * in a mapping table and routed to the GPU or the CPU scan (Section 4.2.1
+ * "Router"), partial results are merged and re-ranked (Section 4.2.2); the
  * router's counters and the refresh of the GPU-resident set follow Section
- * 4.3.3 "Adaptive Runtime Index Update".  Search itself is the three-stage
+ * 4.2.3 "Adaptive Runtime Index Update".  Search itself is the three-stage
  * IVF-PQ procedure of Section 2.2: coarse quantization, per-query lookup
  * table, table scan with top-k.
  *
@@ -135,7 +135,7 @@ int ivf_index_create(const ivf_index_desc_t *desc, void *dev_arena, size_t arena
 void ivf_index_destroy(ivf_index_t *index);
 
 /*
- * Make exactly the listed clusters GPU-resident (Section 4.2.3: the hot
+ * Make exactly the listed clusters GPU-resident (Section 4.1.4: the hot
  * clusters chosen from the access profile are placed on the GPU; the mapping
  * table records cluster id -> resident location).  Re-packs the cluster region
  * from scratch, i.e. a full refresh.  cluster_ids: HOST, n entries, distinct,
@@ -148,8 +148,8 @@ int ivf_index_load_partition(ivf_index_t *index, const int32_t *cluster_ids, int
                              void *stream);
 
 /*
- * Search a batch (Section 2.2 stages 1-3, routed per Section 4.3.1, merged per
- * Section 4.3.2).  queries: HOST fp32 [nq][d].  out_ids: HOST int64 [nq][k];
+ * Search a batch (Section 2.2 stages 1-3, routed per Section 4.2.1, merged per
+ * Section 4.2.2).  queries: HOST fp32 [nq][d].  out_ids: HOST int64 [nq][k];
  * out_dists: HOST fp32 [nq][k].  nprobe > nlist is clamped.  nq == 0 is a
  * no-op.  Requires 1 <= nq <= max_nq, 1 <= nprobe <= max_nprobe,
  * 1 <= k <= max_k.  Returns after the results are written.
@@ -189,7 +189,7 @@ int ivf_search_batch_probes(ivf_index_t *index, const float *queries, int64_t nq
                             float *out_dists);
 
 /*
- * Dynamic dispatcher (Section 4.3.2 "Dynamic Dispatcher"): the same search as
+ * Dynamic dispatcher (Section 4.2.2 "Dynamic Dispatcher"): the same search as
  * ivf_search_batch() (probe == NULL) or ivf_search_batch_probes() (probe given),
  * but every query is merged, re-ranked and handed on as soon as its own probes
  * are done instead of when the whole batch is.  The call enqueues the device
@@ -234,7 +234,7 @@ int ivf_search_poll(ivf_ticket_t *ticket, int64_t *queries_done, int64_t cap, in
 int ivf_search_wait(ivf_ticket_t *ticket, double *done_ms);
 
 /*
- * Router counters (Section 4.3.3; per-query hit rate as defined in Section
+ * Router counters (Section 4.2.3; per-query hit rate as defined in Section
  * 3.3: resident probes / probes).  per_cluster_hits: HOST uint64 [nlist] or
  * NULL, number of times each cluster was probed since the last reset.
  * mean_hit_rate = resident probes / all probes; min_hit_rate = smallest
@@ -246,7 +246,7 @@ int ivf_hit_stats(ivf_index_t *index, uint64_t *per_cluster_hits, double *mean_h
                   double *min_hit_rate, uint64_t *n_queries, int reset);
 
 /*
- * Change the resident set while searches continue (Section 4.3.3).  evict /
+ * Change the resident set while searches continue (Section 4.2.3).  evict /
  * admit: HOST cluster ids.  Evicted clusters stop being routed to the GPU at
  * the next publish; admitted clusters are copied host->device on side_stream
  * (pinned asynchronous copies when `codes` is pinned) and become resident when
@@ -283,7 +283,7 @@ int ivf_migrate_stats(ivf_index_t *index, uint64_t *bytes_copied, double *copy_m
 int ivf_resident_info(ivf_index_t *index, int32_t *n_clusters, int64_t *n_vectors);
 
 /*
- * Which form of the CPU scan of non-resident clusters (Section 4.3.1) this
+ * Which form of the CPU scan of non-resident clusters (Section 4.2.1) this
  * index uses: 0 = the plain loop over each vector's code bytes, 1 = the
  * byte-plane scan (CPUs with AVX-512 VBMI; the index then holds a column-major
  * copy of the codes, N * code-bytes more host memory, made at creation).  Both
@@ -295,7 +295,7 @@ int ivf_host_scan_form(const ivf_index_t *index);
 
 /*
  * How cluster copies (ivf_index_load_partition, ivf_migrate_clusters; Section
- * 4.3.3) reach the device: 1 = the copy kernel reads the caller's codes and ids
+ * 4.2.3) reach the device: 1 = the copy kernel reads the caller's codes and ids
  * itself, which needs both arrays in pinned host memory that the device can
  * address (hipHostMalloc, or a pinned torch tensor; codes 16-byte aligned) and
  * fewer than 2^31 vectors; 0 = runs of vectors are copied with hipMemcpyAsync
@@ -336,10 +336,10 @@ int ivf_stage_times(ivf_index_t *index, double *ms, uint64_t *launches, uint64_t
                     int reset);
 
 /*
- * ---- Partitioning point (Section 4.2): pure host functions ----
+ * ---- Partitioning point (Section 4.1): pure host functions ----
  *
  * ivf_latency_model_t: piecewise-linear CPU latency models of the two search
- * stages as functions of the batch size (Section 4.2.1), given by n_knots >= 1
+ * stages as functions of the batch size (Section 4.1.1), given by n_knots >= 1
  * profiled points with strictly increasing batch sizes; linear between knots
  * and beyond the outer ones.  All pointers HOST.
  */
@@ -356,7 +356,7 @@ double ivf_model_hybrid_latency(const ivf_latency_model_t *model, double batch, 
 
 /* Eq. (2): expected smallest per-query hit rate in a batch of `batch` queries,
  * hit rates ~ Beta with the given mean and variance 4 sigma_max2 mean (1 - mean)
- * (Section 4.2.2).  0 < sigma_max2 < 0.25, else NaN. */
+ * (Section 4.1.2).  0 < sigma_max2 < 0.25, else NaN. */
 double ivf_model_min_hit_rate(double mean_hit_rate, double sigma_max2, int32_t batch);
 
 /* Inverse of Eq. (2) over a measured profile ("HitRate2Coverage"): the smallest

@@ -218,7 +218,7 @@ int oracle_scan(int metric, int d, int M, int nbits, const float *codebooks,
  * Per-query hit rate as defined in Section 3.3 "Variance of Hit Rate across
  * Queries": the number of the query's probed clusters that fall inside the
  * cached (resident) set, over nprobe; plus per-cluster access counts
- * (Section 4.3.3, the router's counters).
+ * (Section 4.2.3, the router's counters).
  */
 int oracle_hit_stats(int nlist, int64_t nq, int nprobe, const int32_t *probe,
                      const uint8_t *resident, uint64_t *per_cluster,

@@ -1,10 +1,10 @@
 """Oracle for the latency-bounded partitioning model.  TEST INFRASTRUCTURE ONLY.
 
 Plain numpy/scipy, written from the definitions:
-  * piecewise-linear CPU latency models T_CQ(b), T_LUT(b) (Section 4.2.1);
+  * piecewise-linear CPU latency models T_CQ(b), T_LUT(b) (Section 4.1.1);
   * hybrid latency, Eq. (1): tau_s(b) = T_CQ(b) + (1 - eta) * T_LUT(b);
   * per-query hit rate ~ Beta with mean eta_bar and variance
-    4 * sigma_max^2 * eta_bar * (1 - eta_bar) (Section 4.2.2);
+    4 * sigma_max^2 * eta_bar * (1 - eta_bar) (Section 4.1.2);
   * expected minimum hit rate in a batch, Eq. (2):
     eta_min(B) = int_0^1 B x f(x) (1 - F(x))^(B-1) dx   (scipy quadrature, in u = F(x));
   * its numerical inverse over the measured hit-rate profile ("HitRate2Coverage");
@@ -14,11 +14,18 @@ Readings of the garbled listing of Algorithm 1: MEM_Index is evaluated at the
 midpoint rho_m; t_s is tau_s; the interval update is plain bisection on the sign
 of InferPartition(rho_m) - rho_m (rho_low <- rho_m when more coverage is needed);
 T_search = T_CQ + T_LUT; a required hit rate <= 0 needs no GPU coverage and a
-required hit rate that no coverage reaches maps to rho = 1.
+required hit rate that no coverage reaches maps to rho = 1.  InferPartition
+takes both roundings of B = tau_s * mu (Section 4.1.3): rounding up against the
+bound tau_s, rounding down against the bound B / mu, and returns the smaller
+coverage.
 
 Pins (tests/test_partition_model.py): closed forms (B = 1 gives the mean; the
 uniform case gives 1/(B+1)), Monte-Carlo minima of Beta samples, the variance
-model at eta_bar = 0.5, monotonicity, a hand-worked instance of Eq. (1).
+model at eta_bar = 0.5, monotonicity, a hand-worked instance of Eq. (1); for
+InferPartition two instances worked by hand (either rounding deciding the
+minimum); for Algorithm 1 a brute-force scan of every cluster count that
+evaluates Eq. (1) and Eq. (2) directly and locates the self-consistent
+crossing the bisection must find.
 """
 import math
 

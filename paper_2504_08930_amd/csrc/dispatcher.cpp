@@ -2,7 +2,7 @@
 #include "index_state.h"
 
 // ---------------------------------------------------------------------------
-// dynamic dispatcher (Section 4.3.2): per-query completion of a hybrid batch
+// dynamic dispatcher (Section 4.2.2): per-query completion of a hybrid batch
 // ---------------------------------------------------------------------------
 struct ivf_ticket {
   ivf_index *ix = nullptr;

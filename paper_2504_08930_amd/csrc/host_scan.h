@@ -1,7 +1,7 @@
 // CPU side of the hybrid search: the library's own scan of non-resident
-// ("cold") clusters (Section 4.3.1: the part of the search not held by the GPU
+// ("cold") clusters (Section 4.2.1: the part of the search not held by the GPU
 // is handled by the CPU) and the merge of CPU and GPU partial results
-// (Section 4.3.2).  Uses the same fixed-point table arithmetic as the kernels,
+// (Section 4.2.2).  Uses the same fixed-point table arithmetic as the kernels,
 // so a cluster yields bit-identical distances wherever it is scanned.
 #pragma once
 #include <stdint.h>
@@ -95,7 +95,7 @@ void cpu_transpose_codes(const HostIndexView &ix, const int64_t *list_toff, uint
 // cpu_build_lut; writes k candidates, best first, padded with (kKeyInvalid, -1).
 // Clusters are taken one by one; `scanned` (optional) holds the number of list
 // entries finished so far and reaches n_clusters once `out` is written, which is
-// what the dispatcher compares with the query's expected count (Section 4.3.2).
+// what the dispatcher compares with the query's expected count (Section 4.2.2).
 void cpu_scan_lists(const HostIndexView &ix, const int32_t *lut, int e, const float *q,
                     const int32_t *clusters, int n_clusters, int k, HostCand *out,
                     int32_t *scanned = nullptr);

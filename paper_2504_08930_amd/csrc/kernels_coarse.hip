@@ -4,7 +4,7 @@
 // are selected exactly by a radix select over (score, cluster id).
 //
 // The paper keeps this stage on the CPU to avoid ping-pong between devices
-// when several GPU shards are used (Section 4.2.1); with one GPU that concern
+// when several GPU shards are used (Section 4.1.1); with one GPU that concern
 // does not arise and the contraction runs on the device.
 #include <hip/hip_runtime.h>
 #include <math.h>

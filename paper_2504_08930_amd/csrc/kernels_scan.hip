@@ -4,7 +4,7 @@
 // Stage numbering follows Section 2.2 ("Search Operation in IVF Index"):
 // stage 2 builds the per-query table of partial distances, stage 3 scans the
 // codes of the probed clusters through it and keeps the k best.  Routing of
-// probes by the mapping table follows Section 4.3.1.
+// probes by the mapping table follows Section 4.2.1.
 //
 // ADC scan design (what differs from the one-thread-block-per-(query, cluster)
 // scheme the paper describes for its GPU tier in Section 3.1):
@@ -184,9 +184,9 @@ hipError_t launch_bias(const Shape &sh, const float *q, int nq, const int32_t *p
 }
 
 // ---------------------------------------------------------------------------
-// Routing (Section 4.3.1): each probe is looked up in the mapping table;
+// Routing (Section 4.2.1): each probe is looked up in the mapping table;
 // resident probes form the query's GPU work list, the others its cold list.
-// Also the router's counters (Section 4.3.3).
+// Also the router's counters (Section 4.2.3).
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void k_route(
     const int32_t *__restrict__ probe, int nq, int nprobe, int stride,

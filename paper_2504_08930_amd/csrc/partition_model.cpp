@@ -1,13 +1,13 @@
-// Latency-bounded choice of the partitioning point (Section 4.2): how much of
+// Latency-bounded choice of the partitioning point (Section 4.1): how much of
 // the index (which fraction rho of the clusters, hottest first) to keep on the
 // GPU so that the hybrid search meets its latency target.  Pure host
 // arithmetic; it feeds ivf_index_load_partition.
 //
 //   * T_CQ(b), T_LUT(b): piecewise-linear CPU latency models from profiled knots
-//     (Section 4.2.1), linear beyond the outer knots;
+//     (Section 4.1.1), linear beyond the outer knots;
 //   * Eq. (1): tau_s(b) = T_CQ(b) + (1 - eta) T_LUT(b), eta = smallest hit rate in the batch;
 //   * per-query hit rate ~ Beta(mean eta_bar, variance 4 sigma_max^2 eta_bar (1 - eta_bar))
-//     (Section 4.2.2);
+//     (Section 4.1.2);
 //   * Eq. (2), the expected smallest of B draws.  Integrating Eq. (2) by parts,
 //     int_0^1 B x f (1-F)^(B-1) dx = int_0^1 (1 - F(x))^B dx, which is the form
 //     evaluated here (composite Simpson after an end-flattening substitution; F by

@@ -202,7 +202,7 @@ int enqueue_gpu(ivf_index *ix, const SearchArgs &a, const BatchCtx &c, bool fina
                      lut_parts, W.lutmax, st));
   G_TRY(launch_order(W, nq, np, sh.M, L.qstats, 1, st));
   if (!final_on_gpu) {
-    // cold probes go to the CPU (Section 4.3.1)
+    // cold probes go to the CPU (Section 4.2.1)
     G_TRY(hipMemcpyAsync(ix->h_ncold, W.n_cold, (size_t)nq * 4, hipMemcpyDeviceToHost, st));
     G_TRY(hipMemcpyAsync(ix->h_cold, W.cold, (size_t)nq * np * 4, hipMemcpyDeviceToHost, st));
     G_TRY(hipMemcpyAsync(ix->h_qbmax, W.qbmax, (size_t)nq * 4, hipMemcpyDeviceToHost, st));
@@ -312,7 +312,7 @@ static int search_device(ivf_index *ix, const SearchArgs &a) {
     return IVF_OK;
   }
 
-  // ---- hybrid: cold probes on the CPU, then merge (Sections 4.3.1, 4.3.2) ----
+  // ---- hybrid: cold probes on the CPU, then merge (Sections 4.2.1, 4.2.2) ----
   // The cold probe lists reach the host right after routing; the CPU scans them
   // while the device scans the resident ones.
   S_TRY(hipEventSynchronize(ix->ev_routed));

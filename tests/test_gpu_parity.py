@@ -126,7 +126,7 @@ def test_forced_probes_and_scan_slices(pkg, oracle, name):
 
 @pytest.mark.parametrize("name", ["T_L2", "T_IP", "T_IP96"])
 def test_residency_invariance_and_counters(pkg, oracle, name):
-    """Results must not depend on which clusters are GPU-resident (Section 4.3.2:
+    """Results must not depend on which clusters are GPU-resident (Section 4.2.2:
     the hybrid result is the merge of the CPU and GPU partial results); with the
     fixed-point table both sides produce identical sums, so equality is exact."""
     spec, ix, q, calib = _case(name)
@@ -174,7 +174,7 @@ def test_residency_invariance_and_counters(pkg, oracle, name):
 
 @pytest.mark.parametrize("copy_form", ["direct", "staged"])
 def test_migration_keeps_results(pkg, oracle, monkeypatch, copy_form):
-    """Evict / admit while searching (Section 4.3.3): results identical before,
+    """Evict / admit while searching (Section 4.2.3): results identical before,
     during and after; clusters in transit are served by the CPU path.  Run with
     both forms of the cluster copy (kernel reads of the pinned host arrays, and
     copies through the staging area)."""
@@ -244,7 +244,7 @@ def _shuffled_within_lists(ix, seed):
 @pytest.mark.parametrize("name", ["T_L2", "T_IP96"])
 def test_layout_transforms_leave_results_unchanged(pkg, oracle, name):
     """Where a cluster sits in the device arena and where a vector sits in its
-    list are storage choices (Section 4.2.3 places clusters freely): placing the
+    list are storage choices (Section 4.1.4 places clusters freely): placing the
     clusters in another order, and storing each list's vectors in another
     order, both give the same ids and distances, ties included (they break by
     id, never by position)."""
@@ -863,7 +863,7 @@ def test_residual_encoding(pkg, oracle, monkeypatch, name, copy_form):
 
 @pytest.mark.parametrize("name,residual", [("T_L2", False), ("T_IP96", False), ("T_L2", True)])
 def test_dispatcher_hybrid(pkg, oracle, name, residual):
-    """Dynamic dispatcher (Section 4.3.2): per-query hand-off of a hybrid batch.  What is
+    """Dynamic dispatcher (Section 4.2.2): per-query hand-off of a hybrid batch.  What is
     unique (each query's ids and distances) must equal the bulk path bit for bit and the
     oracle within tolerance; the order of hand-off is not unique and is checked for
     validity (each query once, its row final at that moment, times non-decreasing)."""

@@ -320,7 +320,7 @@ def test_desc_validation_and_arena_size(lib):
 
 
 def test_dispatcher_host_only_matches_synchronous_search(case, oracle):
-    """Per-query completion (Section 4.3.2): every query is handed on exactly once, its
+    """Per-query completion (Section 4.2.2): every query is handed on exactly once, its
     row is final when the callback runs, and the results are those of the bulk path."""
     spec, ix, q, index = case
     probe, _, _ = oracle.coarse(ix.metric, ix.centroids, q, spec.nprobe)

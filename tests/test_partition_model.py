@@ -1,4 +1,4 @@
-"""Partitioning model (Section 4.2): pins of the numpy/scipy oracle against closed
+"""Partitioning model (Section 4.1): pins of the numpy/scipy oracle against closed
 forms and Monte-Carlo, then the library's C implementation against the oracle.
 CPU only."""
 import numpy as np
@@ -123,3 +123,108 @@ def test_library_partition_point_matches_oracle(lib):
     assert r2 <= r1 + 1.0 / 64
     with pytest.raises(lib.IvfError):
         lib.ivf_model_partition_point(model, hit_cdf, mem, 0.3, 15e-3, 1.0, 1.0, 1.0, 0.01)
+
+
+# ---------------- Algorithm 1: pins that do not go through its own listing ----------------
+def test_infer_partition_hand_worked_instances(lib):
+    """InferPartition of Algorithm 1 worked by hand (Section 4.1.3, "Rounding up" /
+    "Rounding down"): four clusters whose hottest 0..4 cover 0, 1/2, 3/4, 9/10, 1 of the
+    accesses; sigma_max^2 = 1/12, for which the hit-rate model at mean 1/2 is the uniform
+    distribution (expected minimum of B draws = 1/(B+1)); tau_s = 10 ms, mu = 150 /s, so
+    tau_s * mu = 1.5: B = 2 rounding up, B = 1 rounding down with the bound B/mu = 6.67 ms.
+
+    (a) flat latency models T_CQ = 1 ms, T_LUT = 12 ms:
+        eta_1 = (13 - 10) / 12 = 0.25; with B = 2 no coverage gives 0 and one cluster gives
+        1/3 >= 0.25, so rho_1 = 1/4.
+        eta_2 = (13 - 6.67) / 12 = 0.528; with B = 1 the expected minimum is the mean, and the
+        first prefix that covers 0.528 is two clusters (0.75), so rho_2 = 1/2.  min = 1/4.
+    (b) models through the origin, T_CQ = 1 ms * b, T_LUT = 16/3 ms * b:
+        eta_1 = (2 + 10.67 - 10) / 10.67 = 0.25 -> rho_1 = 1/4;
+        eta_2 = (1 + 5.33 - 6.67) / 5.33 < 0 -> no coverage needed, rho_2 = 0.  min = 0.
+    The library's InferPartition is reached through Algorithm 1 with an index that takes no
+    memory (mu stays mu_LLM0, so every iteration returns the same value)."""
+    hit_cdf = np.array([0.0, 0.5, 0.75, 0.9, 1.0])
+    s2, tau, mu = 1.0 / 12.0, 10e-3, 150.0
+    cases = [(([1.0, 2.0], [1e-3, 1e-3], [12e-3, 12e-3]), 0.25),
+             (([1.0, 2.0], [1e-3, 2e-3], [16e-3 / 3, 32e-3 / 3]), 0.0)]
+    for (kb, cq, lut), want in cases:
+        assert po.infer_partition(kb, cq, lut, hit_cdf, s2, tau, mu) == want
+        model = lib.LatencyModel(kb, cq, lut)
+        got = lib.ivf_model_partition_point(model, hit_cdf, np.zeros(5), s2, 2 * tau, 1.0, 1.0, mu,
+                                            1.0 / 8)
+        assert got == want
+    # the two roundings apart, from the closed forms used above
+    assert abs(po.expected_min_hit_rate(0.5, s2, 2) - 1.0 / 3.0) < 1e-9
+    assert po.hitrate_to_coverage(hit_cdf, s2, 2, 0.25) == 0.25
+    assert po.hitrate_to_coverage(hit_cdf, s2, 1, (13e-3 - 1 / 150.0) / 12e-3) == 0.5
+
+
+_ETA_MEMO = {}
+
+
+def _eta_min(mean, s2, B):
+    """expected_min_hit_rate with a memo: the brute force asks for the same few batch sizes
+    at every prefix of the profile."""
+    key = (round(mean, 15), s2, B)
+    if key not in _ETA_MEMO:
+        _ETA_MEMO[key] = po.expected_min_hit_rate(mean, s2, B)
+    return _ETA_MEMO[key]
+
+
+def _coverage_needed_brute(kb, cq, lut, hit_cdf, s2, tau_s, mu):
+    """What InferPartition must return, from the definitions and not from its algebra:
+    for either rounding of B = tau_s * mu, the smallest prefix of clusters at which the
+    latency of Eq. (1), with the expected smallest hit rate of Eq. (2), meets the bound
+    (tau_s rounding up; B / mu rounding down), 1 if none does; then the smaller."""
+    nlist = len(hit_cdf) - 1
+    out = []
+    for B, bound in ((max(1, int(np.ceil(tau_s * mu))), tau_s),
+                     (max(1, int(np.floor(tau_s * mu))), None)):
+        if bound is None:
+            bound = B / mu
+        need = 1.0
+        for i in range(nlist + 1):
+            eta = _eta_min(float(hit_cdf[i]), s2, B)
+            if po.hybrid_latency(kb, cq, lut, B, eta) <= bound * (1 + 1e-12):
+                need = i / nlist
+                break
+        out.append(need)
+    return min(out)
+
+
+@pytest.mark.parametrize("zipf_s,slo,kv_mult,mu0", [(1.0, 20e-3, 4.0, 900.0),
+                                                    (0.7, 24e-3, 2.0, 1500.0),
+                                                    (1.3, 16e-3, 3.0, 1500.0),
+                                                    (1.0, 30e-3, 1.5, 1500.0)])
+def test_partition_point_is_the_self_consistent_crossing(lib, zipf_s, slo, kv_mult, mu0):
+    """Algorithm 1 searches for the coverage rho at which the coverage that the latency bound
+    asks for, at the batch size the remaining LLM throughput implies, equals the coverage
+    spent.  Brute force over every cluster count i: evaluate the needed coverage need(i) from
+    Eq. (1) and Eq. (2) directly (no inversion formula, no bisection) with mu taken at i
+    clusters; below the crossing need(i) > i / nlist, from it on need(i) <= i / nlist.  Both
+    the oracle's and the library's answers must lie at that crossing, within the search's
+    stopping width delta plus the size of the steps need() takes there."""
+    nlist = 48
+    kb, cq, lut = [1, 4, 16, 64], [1e-3, 1.5e-3, 3e-3, 9e-3], [4e-3, 6e-3, 14e-3, 50e-3]
+    hit_cdf, mem = _profile(nlist, zipf_s)
+    s2, eps, delta = 0.02, 1.0, 1.0 / 256
+    kv = kv_mult * mem[-1]
+    tau_s = slo / (1 + eps)
+    need = np.empty(nlist + 1)
+    for i in range(nlist + 1):
+        mu = max(0.0, (kv - mem[i]) / kv) * mu0
+        need[i] = _coverage_needed_brute(kb, cq, lut, hit_cdf, s2, tau_s, mu)
+    frac = np.arange(nlist + 1) / nlist
+    ok = need <= frac
+    assert ok.any() and not ok.all(), "scenario has no interior crossing"
+    i_star = int(np.argmax(ok))
+    assert not ok[:i_star].any() and ok[i_star:].all(), "need(i) - i/nlist changes sign once"
+    # the answer is need() at the last midpoint, which lies within delta of the crossing
+    near = need[max(0, i_star - 2): i_star + 2]
+    lo, hi = near.min() - 1e-12, near.max() + 1e-12
+    ref = po.partition_point(kb, cq, lut, hit_cdf, mem, s2, slo, eps, kv, mu0, delta)
+    got = lib.ivf_model_partition_point(lib.LatencyModel(kb, cq, lut), hit_cdf, mem, s2, slo, eps,
+                                        kv, mu0, delta)
+    for name, val in (("oracle", ref), ("library", got)):
+        assert lo <= val <= hi, (name, val, i_star / nlist, near)
+        assert abs(val - i_star / nlist) <= delta + 2.0 / nlist + (hi - lo), (name, val, i_star)
