@@ -17,3 +17,10 @@ def oracle():
     from oracle import oracle as orc
     orc.build()
     return orc
+
+
+def pytest_terminal_summary(terminalreporter):
+    """What the oracle comparisons of this run saw, beside their pass/fail."""
+    from tests.parity import TOTAL
+    if TOTAL.queries:
+        terminalreporter.write_line(f"oracle comparisons: {TOTAL.summary()}")

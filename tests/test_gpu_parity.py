@@ -8,7 +8,7 @@ import numpy as np
 import pytest
 
 from synthdata import SPECS, build_index, mixture_centers, make_queries
-from tests.parity import compare_probes, compare_topk, scale_S
+from tests.parity import ParityStats, compare_probes, compare_topk, scale_S
 
 pytestmark = pytest.mark.gpu
 
@@ -63,10 +63,14 @@ def _oracle_ref(oracle, ix, q, nprobe, k):
     return probe, pscore
 
 
-def _check_search(oracle, ix, q, nprobe, k, got_ids, got_d, got_probe=None, details=None):
+def _check_search(oracle, ix, q, nprobe, k, got_ids, got_d, got_probe=None, details=None,
+                  stats=None):
     """End-to-end check with the coarse near-tie rule: if the GPU's probe set
     differs from the oracle's only by boundary ties, ids are compared against
-    the oracle run on the GPU's own probe list."""
+    the oracle run on the GPU's own probe list.  Beside the contract (1e-4) the
+    comparison asserts the regression bounds of tests/parity.py: distances within
+    1e-5, ids trade ranks only when the oracle's distances tie within 1e-6, and at
+    most 1 % of the compared ranks (two for tiny cases) hold another id at all."""
     S = scale_S(ix.metric, q)
     npb = min(nprobe, ix.nlist)
     ext = min(npb + 8, ix.nlist)
@@ -79,7 +83,11 @@ def _check_search(oracle, ix, q, nprobe, k, got_ids, got_d, got_probe=None, deta
     ref_i, ref_d = oracle.scan(ix.metric, ix.codebooks, ix.list_offsets, ix.codes, ix.ids, q,
                                use_probe, k + 16,
                                residual_centroids=oracle.residual_centroids_of(ix))
-    n_amb = compare_topk(got_ids, got_d, ref_i, ref_d, k, S, details=details)
+    st = ParityStats()
+    n_amb = compare_topk(got_ids, got_d, ref_i, ref_d, k, S, details=details, stats=st)
+    assert st.ranks_differ <= max(2, 0.01 * st.ranks), st.summary()
+    if stats is not None:
+        stats.merge(st)
     return n_coarse, n_amb
 
 
@@ -706,32 +714,127 @@ def test_maximum_nprobe_and_k(pkg, oracle):
 
 
 def test_c3_config_full_size(pkg, oracle):
-    """The 10M x 768 configuration the benchmark times (nq=1024, nprobe=64, k=10, one scan
-    block per query): oracle parity on a sample of queries, and equality of the
-    all-resident and 30 %-resident (hybrid) results on every query."""
+    """The 10M x 768 configuration the benchmark times (nprobe=64, k=10), at every point of
+    its sweep: batches of 256 (a query split over no more than one block), 1024 (the
+    benchmark's launch: one scan block per query) and 4096 queries, each with every cluster
+    resident and with the hottest 10 %, 30 % and 50 % resident (the rest scanned on the CPU).
+    Per batch size: oracle parity on a sample of the all-resident result and properties that
+    hold at any size; per resident fraction: the hybrid result equals the all-resident one
+    bit for bit on every query, and the oracle sample again."""
     import torch
     spec, ix, q, calib = _case("C3")
-    index = pkg.IvfIndex(ix, max_nq=1024, max_nprobe=64, max_k=16)
-    index.load_partition(np.arange(ix.nlist, dtype=np.int32))
-    qd = torch.from_numpy(q).cuda()
-    ids_d, dist_d = index.search_batch_dev(qd, spec.nprobe, spec.k)
-    torch.cuda.synchronize()
-    ids, dist = ids_d.cpu().numpy(), dist_d.cpu().numpy()
-    probe = index.coarse_probe_dev(qd, spec.nprobe).cpu().numpy()
-    sel = np.arange(0, q.shape[0], 16)
-    n_coarse, n_amb = _check_search(oracle, ix, q[sel], spec.nprobe, spec.k, ids[sel], dist[sel],
-                                    probe[sel])
-    _say(f"C3: coarse-ambiguous {n_coarse}, id-ambiguous {n_amb} of {len(sel)}")
-    assert n_coarse <= 1 and n_amb <= 2
-    # properties that hold at any size
-    assert (ids >= 0).all() and np.all(np.diff(dist, axis=1) <= 0)          # IP: best first
-    assert all(len(set(r.tolist())) == spec.k for r in ids)
+    centers = mixture_centers(spec, torch.device("cuda"))
+    index = pkg.IvfIndex(ix, max_nq=4096, max_nprobe=64, max_k=16)
+    full = np.arange(ix.nlist, dtype=np.int32)
+    index.load_partition(full)
+    hot = {frac: hottest(index, calib, spec.nprobe, frac, ix.nlist) for frac in (0.1, 0.3, 0.5)}
+    stats = ParityStats()
+    for nq in (256, 1024, 4096):
+        if nq == q.shape[0]:
+            qh = q
+        else:
+            qh = make_queries(spec, centers, nq=nq, seed=spec.seed_queries + nq)[0].cpu().numpy()
+        qd = torch.from_numpy(qh).cuda()
+        index.load_partition(full)
+        ids_d, dist_d = index.search_batch_dev(qd, spec.nprobe, spec.k)
+        torch.cuda.synchronize()
+        ids, dist = ids_d.cpu().numpy(), dist_d.cpu().numpy()
+        probe = index.coarse_probe_dev(qd, spec.nprobe).cpu().numpy()
+        sel = np.arange(0, nq, nq // 64)
+        n_coarse, n_amb = _check_search(oracle, ix, qh[sel], spec.nprobe, spec.k, ids[sel],
+                                        dist[sel], probe[sel], stats=stats)
+        _say(f"C3 nq={nq} all resident: coarse-ambiguous {n_coarse}, id-ambiguous {n_amb} "
+             f"of {len(sel)}")
+        assert n_coarse <= 1 and n_amb <= 1
+        # properties that hold at any size
+        assert (ids >= 0).all() and np.all(np.diff(dist, axis=1) <= 0)          # IP: best first
+        assert all(len(set(r.tolist())) == spec.k for r in ids)
+        for frac in (0.1, 0.3, 0.5):
+            index.load_partition(hot[frac])
+            index.hit_stats(reset=True)
+            hyb = index.search_batch(qh, spec.nprobe, spec.k)
+            st = index.hit_stats()
+            _say(f"C3 nq={nq} resident {frac:.0%}: mean hit rate {st['mean_hit_rate']:.3f}, "
+                 f"min {st['min_hit_rate']:.3f}")
+            assert np.array_equal(hyb[0], ids) and np.array_equal(hyb[1], dist), (nq, frac)
+            assert 0.0 < st["mean_hit_rate"] < 1.0 and st["n_queries"] == nq
+    _say(f"C3: {stats.summary()}")
+    index.close()
+
+
+def test_c5_drift_epochs(pkg, oracle):
+    """The drift configuration on the 10M index (Section 4.2.3 "Adaptive Runtime Index
+    Update"): 8 epochs of 3 batches of 1024 queries, 30 % of the clusters resident, the
+    query-to-cluster permutation re-drawn once (epoch 4).  After every epoch the router's
+    counters are read and reset, the new hot set is the hottest 30 % by those counters, and
+    the difference is migrated on a side stream while the next epoch's first batch is already
+    being searched (clusters in transit are served by the CPU).  Checked: every batch equals
+    the all-resident result of the same queries bit for bit; an oracle sample per epoch;
+    bytes copied = sum over admitted clusters of L_c * (M + 8); the hit rate falls at the
+    re-draw and is back one epoch later."""
+    import torch
+    spec, ix, q, calib = _case("C3")
+    centers = mixture_centers(spec, torch.device("cuda"))
+    n_epochs, n_batches, nq, redraw = 8, 3, 1024, 4
+    index = pkg.IvfIndex(ix, max_nq=nq, max_nprobe=64, max_k=16)
+    full = np.arange(ix.nlist, dtype=np.int32)
+    index.load_partition(full)
+    # reference: every batch with every cluster resident (device only)
+    batches, ref = {}, {}
+    for ep in range(n_epochs):
+        perm_seed = spec.seed_perm + (redraw if ep >= redraw else 0)
+        for b in range(n_batches):
+            qb = make_queries(spec, centers, nq=nq, seed=spec.seed_queries + 1000 + 10 * ep + b,
+                              perm_seed=perm_seed)[0].contiguous()
+            i_d, d_d = index.search_batch_dev(qb, spec.nprobe, spec.k)
+            torch.cuda.synchronize()
+            batches[ep, b] = qb.cpu().numpy()
+            ref[ep, b] = (i_d.cpu().numpy(), d_d.cpu().numpy())
     hot = hottest(index, calib, spec.nprobe, 0.3, ix.nlist)
     index.load_partition(hot)
-    hyb = index.search_batch(q, spec.nprobe, spec.k)
-    st = index.hit_stats()
-    _say(f"C3: 30 % resident, mean hit rate {st['mean_hit_rate']:.3f}")
-    assert np.array_equal(hyb[0], ids) and np.array_equal(hyb[1], dist)
+    resident = set(hot.tolist())
+    lens = np.diff(ix.list_offsets)
+    side = torch.cuda.Stream()
+    expect_bytes, overlapped = 0, 0
+    rates = []
+    stats = ParityStats()
+    for ep in range(n_epochs):
+        index.hit_stats(reset=True)
+        for b in range(n_batches):
+            got = index.search_batch(batches[ep, b], spec.nprobe, spec.k)
+            if b == 0 and index.migrate_poll()[0]:
+                overlapped += 1          # the batch ran while the copies were in flight
+            assert np.array_equal(got[0], ref[ep, b][0]), (ep, b)
+            assert np.array_equal(got[1], ref[ep, b][1]), (ep, b)
+        sel = np.arange(0, nq, nq // 16)
+        _check_search(oracle, ix, batches[ep, 0][sel], spec.nprobe, spec.k,
+                      ref[ep, 0][0][sel], ref[ep, 0][1][sel], stats=stats)
+        in_flight, nbytes = index.migrate_poll(wait=True)
+        assert not in_flight and nbytes == expect_bytes, (ep, nbytes, expect_bytes)
+        nc, nv = index.resident_info()
+        assert nc == len(resident) and nv == int(lens[sorted(resident)].sum())
+        st = index.hit_stats(reset=True)
+        assert st["n_queries"] == n_batches * nq
+        rates.append(st["mean_hit_rate"])
+        hits = st["per_cluster_hits"].astype(np.int64)
+        order = np.lexsort((np.arange(ix.nlist), -hits))
+        want = set(order[: len(hot)].tolist())
+        evict, admit = sorted(resident - want), sorted(want - resident)
+        _say(f"drift epoch {ep}: mean hit rate {rates[-1]:.3f}, evict {len(evict)} admit {len(admit)}")
+        if evict or admit:
+            index.migrate_clusters(evict, admit, side_stream=side)
+            expect_bytes += int(lens[admit].sum()) * (ix.m + 8)
+            resident = want
+    in_flight, nbytes = index.migrate_poll(wait=True)
+    assert not in_flight and nbytes == expect_bytes
+    ms = index.migrate_stats()
+    _say(f"drift: hit rate per epoch {[round(r, 3) for r in rates]}, {ms['migrations']} migrations, "
+         f"{ms['bytes'] / 1e6:.1f} MB, {overlapped} first batches ran during a copy; {stats.summary()}")
+    assert ms["bytes"] == expect_bytes and ms["migrations"] >= n_epochs - 2
+    steady = np.mean(rates[1:redraw])
+    assert rates[redraw] < steady - 0.1, rates            # the re-drawn permutation misses the hot set
+    assert rates[redraw + 1] > rates[redraw] + 0.1, rates  # ... and the next epoch has it back
+    assert abs(np.mean(rates[redraw + 1:]) - steady) < 0.1, rates
     index.close()
     _CACHE.pop("C3", None)
 
@@ -762,9 +865,9 @@ def test_k100_nprobe128(pkg, oracle):
     _CACHE.pop("C4S", None)
 
 
-@pytest.mark.skipif(os.environ.get("IVF_TEST_C4") != "1",
-                    reason="builds a 100M-vector index (about 3 minutes of GPU time, 25 GB of host "
-                           "memory): run with IVF_TEST_C4=1")
+@pytest.mark.skipif(os.environ.get("IVF_SKIP_C4") == "1",
+                    reason="IVF_SKIP_C4=1: the 100M-vector index takes about 2.5 minutes of GPU "
+                           "time and 25 GB of host memory to build")
 @pytest.mark.timeout(900)
 def test_c4_config_full_size(pkg, oracle):
     """The 100M x 768 configuration (nlist=65536, nq=4096, nprobe=128, k=100) at its real
@@ -786,15 +889,16 @@ def test_c4_config_full_size(pkg, oracle):
         probe = index.coarse_probe_dev(qd, spec.nprobe).cpu().numpy()
         sel = np.arange(0, qh.shape[0], 64)
         det = []
+        st = ParityStats()
         n_coarse, n_amb = _check_search(oracle, ix, qh[sel], spec.nprobe, spec.k, ids[sel],
-                                        dist[sel], probe[sel], details=det)
+                                        dist[sel], probe[sel], details=det, stats=st)
         _say(f"C4 zipf_s={s_skew}: coarse-ambiguous {n_coarse}, id-ambiguous {n_amb} of {len(sel)}; "
              f"ranks that differ (query, rank, gap / tolerance): "
-             f"{[(a, b, round(c, 4)) for a, b, c in det]}")
-        # every difference has been checked to be a tie within the tolerance; over
-        # different builds of the index 0 to 3 such queries of the 64 have been seen
-        # at k = 100
-        assert n_coarse <= 1 and n_amb <= 5
+             f"{[(a, b, round(c, 4)) for a, b, c in det]}; {st.summary()}")
+        # at k = 100 a query has a hundred chances of two neighbours that tie to six
+        # digits: what is bounded is the share of ranks that differ (1 %) and how close
+        # every such pair is (both asserted by _check_search), not the count of queries
+        assert n_coarse <= 1
         assert (ids >= 0).all() and np.all(np.diff(dist, axis=1) <= 0)
     # resident set from the hit-rate profile: the hottest clusters that cover 80 % of the accesses
     index.load_partition(full)
@@ -838,11 +942,12 @@ def test_residual_encoding(pkg, oracle, monkeypatch, name, copy_form):
         _say(f"{name}/res nprobe={nprobe} k={k}")
         probe = index.coarse_probe_dev(qd, nprobe).cpu().numpy()
         ids, dist = index.search_batch(q, nprobe, k)
-        n_coarse, n_amb = _check_search(oracle, ix, q, nprobe, k, ids, dist, probe)
-        # (every id that differs has been checked to be a tie within the tolerance; with 16
-        # codewords per sub-quantizer and k = 100 near-equal distances are common: over
-        # different builds of the index 0 to 2 such queries of 32 have been seen)
-        assert n_coarse <= 1 and n_amb <= max(3, q.shape[0] // 8)
+        st = ParityStats()
+        n_coarse, n_amb = _check_search(oracle, ix, q, nprobe, k, ids, dist, probe, stats=st)
+        _say(f"{name}/res nprobe={nprobe} k={k}: {st.summary()}")
+        # at k = 100 what is bounded is the share of ranks that differ and how close each
+        # traded pair is (asserted by _check_search); at k = 10 also the count of queries
+        assert n_coarse <= 1 and (k > 10 or n_amb <= 1)
         if base is None:
             base = (ids, dist)
     rng = np.random.default_rng(7)
