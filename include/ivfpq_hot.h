@@ -178,6 +178,32 @@ int ivf_coarse_probe_dev(ivf_index_t *index, const float *queries, int64_t nq, i
                          int32_t *out_probe, void *stream);
 
 /*
+ * ivf_coarse_probe_dev for callers that cannot allocate device memory or hand
+ * over a workspace, and must not be made to wait for one: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, same result (the same kernels run).  What differs is where the
+ * kernels' intermediates live (the queries' fp16 split, their scales, the
+ * nq x nlist score matrix): not in one of the index's two per-batch workspaces
+ * but in a file-scope device array of IVF_STATIC_SCRATCH_BYTES that is part of
+ * the library's code object; every GPU the library runs on holds its own copy
+ * until the process ends.  Its device address is looked up once per device by
+ * ivf_index_create.  The call takes no workspace slot, no lock and no event,
+ * never waits for another stream, and calls no hipMalloc / hipFree or any other
+ * allocating routine; the caller still passes queries and out_probe (DEVICE).
+ *
+ * Limit: 256-byte-rounded nq * d * 4 + 16384, nq * 4 and nq * nlist * 4 bytes
+ * together must fit the array (e.g. nq <= 126 at nlist = 65536, d = 768;
+ * nq <= 488 at nlist = 16384); a larger batch returns IVF_EINVAL and launches
+ * nothing.  Nothing in the array needs clearing between calls.  All calls on
+ * one GPU, from any index, share that GPU's array: calls that overlap on one GPU
+ * (different streams or threads) race on it and return garbage; calls on one
+ * stream are ordered by the stream.
+ */
+#define IVF_STATIC_SCRATCH_BYTES ((size_t)32 << 20)
+int ivf_coarse_probe_dev_noalloc(ivf_index_t *index, const float *queries, int64_t nq,
+                                 int32_t nprobe, int32_t *out_probe, void *stream);
+
+/*
  * Stages 2-3 with a caller-given probe list instead of the coarse quantizer
  * (routing, GPU scan of resident probes, CPU scan of the rest, merge).  All
  * pointers HOST.  probe: int32 [nq][nprobe]; negative entries are skipped;

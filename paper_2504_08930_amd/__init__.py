@@ -33,6 +33,10 @@ def ivf_coarse_probe_dev(index, queries, nprobe, stream=None):
     return index.coarse_probe_dev(queries, nprobe, stream)
 
 
+def ivf_coarse_probe_dev_noalloc(index, queries, nprobe, out, stream=None):
+    return index.coarse_probe_dev_noalloc(queries, nprobe, out, stream)
+
+
 def ivf_search_batch_probes(index, queries, probe, k):
     return index.search_batch_probes(queries, probe, k)
 

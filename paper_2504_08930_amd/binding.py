@@ -20,7 +20,8 @@ STAGE_NAMES = ("lut", "coarse_gemm", "coarse_select", "route", "scan", "merge")
 EXPORTS = (
     "ivf_index_arena_bytes", "ivf_index_create", "ivf_index_destroy",
     "ivf_index_load_partition", "ivf_search_batch", "ivf_search_batch_dev",
-    "ivf_coarse_probe_dev", "ivf_search_batch_probes", "ivf_hit_stats",
+    "ivf_coarse_probe_dev", "ivf_coarse_probe_dev_noalloc", "ivf_search_batch_probes",
+    "ivf_hit_stats",
     "ivf_migrate_clusters", "ivf_migrate_poll", "ivf_migrate_stats", "ivf_resident_info", "ivf_host_scan_form", "ivf_copy_form",
     "ivf_set_tuning", "ivf_stage_times", "ivf_calib_copy", "ivf_calib_read", "ivf_last_error",
     "ivf_model_hybrid_latency", "ivf_model_min_hit_rate", "ivf_model_hitrate_to_coverage",
@@ -77,6 +78,7 @@ def load_library():
     lib.ivf_search_batch.argtypes = [P, P, I64, I32, I32, P, P]
     lib.ivf_search_batch_dev.argtypes = [P, P, I64, I32, I32, P, P, P]
     lib.ivf_coarse_probe_dev.argtypes = [P, P, I64, I32, P, P]
+    lib.ivf_coarse_probe_dev_noalloc.argtypes = [P, P, I64, I32, P, P]
     lib.ivf_search_batch_probes.argtypes = [P, P, I64, P, I32, I32, P, P]
     lib.ivf_search_batch_async.argtypes = [P, P, I64, P, I32, I32, P, P, QUERY_DONE_FN, P,
                                            ctypes.POINTER(P)]
@@ -287,6 +289,19 @@ class IvfIndex:
         _check(self._lib.ivf_coarse_probe_dev(self._h, ctypes.c_void_p(queries.data_ptr()), nq,
                                               nprobe, ctypes.c_void_p(out.data_ptr()),
                                               self._stream_ptr(st)))
+        return out
+
+    def coarse_probe_dev_noalloc(self, queries, nprobe, out, stream=None):
+        """ivf_coarse_probe_dev_noalloc: `out` (int32 [nq, nprobe], device) is the caller's."""
+        torch = self._torch
+        assert queries.is_cuda and queries.dtype == torch.float32 and queries.is_contiguous()
+        assert out.is_cuda and out.dtype == torch.int32 and out.is_contiguous()
+        nq = queries.shape[0]
+        assert tuple(out.shape) == (nq, nprobe)
+        st = stream if stream is not None else torch.cuda.current_stream(queries.device)
+        _check(self._lib.ivf_coarse_probe_dev_noalloc(self._h, ctypes.c_void_p(queries.data_ptr()),
+                                                      nq, nprobe, ctypes.c_void_p(out.data_ptr()),
+                                                      self._stream_ptr(st)))
         return out
 
     def search_batch_probes(self, queries, probe, k):

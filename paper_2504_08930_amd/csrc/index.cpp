@@ -272,6 +272,8 @@ extern "C" int ivf_index_create(const ivf_index_desc_t *desc, void *dev_arena, s
     return fail(IVF_EDEVICE, "%s", msg.c_str());
   };
   hipError_t e;
+  if ((e = static_scratch_for_device(ix->device, &ix->static_scratch)) != hipSuccess)
+    return bail(e, "hipGetSymbolAddress(scratch)");
   if ((e = hipStreamCreateWithFlags(&ix->own_stream, hipStreamNonBlocking)) != hipSuccess)
     return bail(e, "hipStreamCreateWithFlags");
   if ((e = hipEventCreateWithFlags(&ix->ev_routed, hipEventDisableTiming)) != hipSuccess)

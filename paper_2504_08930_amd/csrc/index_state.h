@@ -128,6 +128,7 @@ struct ivf_index {
   int64_t n_total = 0;
   bool has_dev = false;
   int device = 0;               // HIP device the arena lives on
+  void *static_scratch = nullptr;  // that device's copy of the library's file-scope scratch array
   bool dispatch_active = false; // an asynchronous batch owns the pinned host buffers
   DevLayout L;
   hipStream_t own_stream = nullptr;

@@ -11,9 +11,11 @@ constexpr int kTileVecs = 64;      // vectors per code tile (one wavefront)
 constexpr int kMaxSlices = 8;      // scan blocks per query, upper bound
 constexpr int kMaxK = 128;
 constexpr int kMaxNprobe = 2048;
-constexpr int kLutMaxParts = 512;
+constexpr int kLutMaxParts = 512;   // per-query slots for partial table maxima
 constexpr int kSplitPadBytes = 16384;  // tail padding of the split-fp16 operand arrays
-constexpr int kWsSlots = 2;        // batches that may be in flight on different streams  // per-query slots for partial table maxima
+constexpr int kWsSlots = 2;        // batches that may be in flight on different streams
+// size of the file-scope device array behind ivf_coarse_probe_dev_noalloc
+constexpr size_t kStaticScratchBytes = IVF_STATIC_SCRATCH_BYTES;
 
 // Counters kept on the device next to the per-cluster hit counters.
 enum {
@@ -116,6 +118,17 @@ hipError_t launch_coarse_gemm(const Shape &sh, const void *q_parts, const int32_
 
 hipError_t launch_coarse_select(const Shape &sh, const float *scores, int nq, int nprobe,
                                 int probe_stride, int32_t *probe, hipStream_t st);
+
+// The coarse quantizer with its intermediates in the library's file-scope device array
+// (kStaticScratchBytes per device) instead of a workspace.  static_scratch_for_device
+// returns that array's address on `device`, which must be the current device the first
+// time it is asked for; coarse_static_bytes is what a batch of nq queries needs of it.
+hipError_t static_scratch_for_device(int device, void **ptr);
+size_t coarse_static_bytes(const Shape &sh, int64_t nq);
+hipError_t launch_coarse_probe_static(const Shape &sh, const float *queries, int nq, int nprobe,
+                                      const void *cent_parts, const int32_t *cent_exp,
+                                      const float *cent_norm, void *scratch_ptr, int32_t *out_probe,
+                                      hipStream_t st);
 
 // bias(q, probe) for every probe of every query (residual encoding)
 hipError_t launch_bias(const Shape &sh, const float *q, int nq, const int32_t *probe, int nprobe,

@@ -677,4 +677,64 @@ hipError_t launch_coarse_select(const Shape &sh, const float *scores, int nq, in
   return hipGetLastError();
 }
 
+// ---------------------------------------------------------------------------
+// Coarse quantizer for callers that cannot allocate or bring a workspace: the
+// split queries, their scales and the score matrix live in a file-scope device
+// array instead of the index's per-batch workspace.  The array's name is only a
+// host-side handle; its device address is looked up once per device
+// (static_scratch_for_device) and that pointer is what the kernels get.
+// ---------------------------------------------------------------------------
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+static std::atomic<void *> g_scratch_ptr[kMaxDevices];
+
+hipError_t static_scratch_for_device(int device, void **ptr) {
+  *ptr = nullptr;
+  if (device < 0 || device >= kMaxDevices) return hipErrorInvalidDevice;
+  void *p = g_scratch_ptr[device].load(std::memory_order_acquire);
+  if (!p) {
+    // every device holds its own copy of the array at its own address: ask with that
+    // device current (two threads asking at once get the same answer)
+    int cur = -1;
+    hipError_t e = hipGetDevice(&cur);
+    if (e != hipSuccess) return e;
+    if (cur != device) return hipErrorInvalidDevice;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!p) return hipErrorInvalidSymbol;
+    g_scratch_ptr[device].store(p, std::memory_order_release);
+  }
+  *ptr = p;
+  return hipSuccess;
+}
+
+static size_t round256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+size_t coarse_static_bytes(const Shape &sh, int64_t nq) {
+  return round256((size_t)nq * sh.d * 4 + kSplitPadBytes) + round256((size_t)nq * 4) +
+         round256((size_t)nq * sh.nlist * 4);
+}
+
+hipError_t launch_coarse_probe_static(const Shape &sh, const float *queries, int nq, int nprobe,
+                                      const void *cent_parts, const int32_t *cent_exp,
+                                      const float *cent_norm, void *scratch_ptr, int32_t *out_probe,
+                                      hipStream_t st) {
+  if (!scratch_ptr || coarse_static_bytes(sh, nq) > (size_t)kStaticScratchBytes)
+    return hipErrorInvalidValue;
+  unsigned char *base = static_cast<unsigned char *>(scratch_ptr);
+  void *q_parts = base;
+  int32_t *q_exp = reinterpret_cast<int32_t *>(base + round256((size_t)nq * sh.d * 4 + kSplitPadBytes));
+  float *scores = reinterpret_cast<float *>(reinterpret_cast<unsigned char *>(q_exp) +
+                                            round256((size_t)nq * 4));
+  // Nothing in the array has to start at zero: every word the kernels read for a row
+  // or column they store was written earlier in this call; the operand padding the
+  // GEMM reads unchecked only feeds rows of the product that are never stored.
+  hipError_t e = launch_split_f16(queries, (size_t)nq, sh.d, q_parts, q_exp, st);
+  if (e != hipSuccess) return e;
+  e = launch_coarse_gemm(sh, q_parts, q_exp, nq, cent_parts, cent_exp, cent_norm, scores, st);
+  if (e != hipSuccess) return e;
+  return launch_coarse_select(sh, scores, nq, nprobe, nprobe, out_probe, st);
+}
+
 }  // namespace ivf

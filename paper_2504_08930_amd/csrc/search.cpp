@@ -453,6 +453,29 @@ extern "C" int ivf_coarse_probe_dev(ivf_index_t *ix, const float *queries, int64
   return IVF_OK;
 }
 
+extern "C" int ivf_coarse_probe_dev_noalloc(ivf_index_t *ix, const float *queries, int64_t nq,
+                                            int32_t nprobe, int32_t *out_probe, void *stream) {
+  if (!ix) return fail(IVF_EINVAL, "index is NULL");
+  if (!ix->has_dev) return fail(IVF_EDEVICE, "host-only index: no device coarse quantizer");
+  if (nq < 0 || nprobe < 1) return fail(IVF_EINVAL, "bad nq / nprobe");
+  if (nq == 0) return IVF_OK;
+  if (!queries || !out_probe) return fail(IVF_EINVAL, "NULL buffer");
+  if (nprobe > kMaxNprobe) return fail(IVF_EINVAL, "nprobe exceeds %d", kMaxNprobe);
+  if (nq > 0x7fffffff || coarse_static_bytes(ix->sh, nq) > kStaticScratchBytes)
+    return fail(IVF_EINVAL,
+                "nq = %lld needs %zu bytes of the library's static scratch array, which holds "
+                "%zu (nq * (nlist + d) * 4 bytes, about): use a smaller batch or "
+                "ivf_coarse_probe_dev",
+                (long long)nq, nq > 0x7fffffff ? (size_t)0 : coarse_static_bytes(ix->sh, nq),
+                kStaticScratchBytes);
+  // no workspace slot, no lock, no event: the kernels' intermediates go to the
+  // file-scope device array whose address ivf_index_create looked up
+  HIP_TRY(launch_coarse_probe_static(ix->sh, queries, (int)nq, nprobe, ix->L.cent_parts,
+                                     ix->L.cent_exp, ix->L.cent_norm, ix->static_scratch,
+                                     out_probe, (hipStream_t)stream));
+  return IVF_OK;
+}
+
 extern "C" int ivf_search_batch_probes(ivf_index_t *ix, const float *queries, int64_t nq,
                                        const int32_t *probe, int32_t nprobe, int32_t k,
                                        int64_t *out_ids, float *out_dists) {
