@@ -2,7 +2,7 @@
 """Benchmark of the IVF-PQ hot path on one MI355X.
 
 Default mode ("hotpath"): a step is one pass of the whole hot path over one
-query batch that is already resident in HBM: coarse quantizer (split-bf16 MFMA
+query batch that is already resident in HBM: coarse quantizer (split-fp16 MFMA
 contraction + per-query top-nprobe), routing through the mapping table,
 per-query lookup tables, ADC scan of the resident inverted lists with in-block
 top-k, per-query merge.  The workload is the 10M-vector configuration (N = 10M,
@@ -40,11 +40,27 @@ if ROOT not in sys.path:
 METRIC = "search queries/sec at fixed nprobe,k; ADC-scan HBM GB/s as % of peak"
 HBM_PEAK_GBS = 8000.0
 # HBM-side bytes per k_scan launch from the rocprofv3 --pmc runs (FETCH_SIZE + WRITE_SIZE, scaled
-# by the same counters on a plain copy kernel); valid for exactly this workload and launch shape.
+# by the same counters on a plain copy kernel); valid for exactly this workload and launch shape,
+# and for the scan kernel's sources as they were when the counters were read: each entry carries
+# the hash of those sources (scan_source_hash), and a line measured on other sources reports
+# no traffic figure rather than a stale one.
+SCAN_SOURCES = ("kernels_scan.hip", "lut_quant.h", "internal.h")
 MEASURED_TRAFFIC = {
-    ("C3", 1024, 1.0): (3.016e9 + 0.164e6, "profiles/c3_nq1024_scan_hbm_traffic.md"),
-    ("C3", 256, 1.0): (738.5e6 + 0.04e6, "profiles/c3_nq256_scan_hbm_traffic.md"),
+    ("C3", 1024, 1.0): (3.016e9 + 0.164e6, "profiles/c3_nq1024_scan_hbm_traffic.md",
+                        "0000000000000000"),
+    ("C3", 256, 1.0): (738.5e6 + 0.04e6, "profiles/c3_nq256_scan_hbm_traffic.md",
+                       "0000000000000000"),
 }
+
+
+def scan_source_hash():
+    """First 16 hex digits of the SHA-256 of the sources the scan kernel is built from."""
+    import hashlib
+    h = hashlib.sha256()
+    for name in SCAN_SOURCES:
+        with open(os.path.join(ROOT, "paper_2504_08930_amd", "csrc", name), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()[:16]
 
 
 def log(msg):
@@ -111,6 +127,32 @@ def timed_steps(index, q, nprobe, k, steps, warmup, slices, timing=2, n_streams=
     res["stage_ms"] = {s: round(v / max(1, st["launches"][s]), 4) for s, v in st["ms"].items()
                        if st["launches"][s] > 0}
     return res
+
+
+def measure_read_ceiling(dev, with_copy=False, launches=10):
+    """GB/s of the library's plain streaming-read kernel over a 1 GiB buffer (HIP events on
+    the launch stream).  with_copy: also launch the 1 GiB copy kernel once (the launch the
+    byte counters are calibrated on when this script runs under rocprofv3 --pmc)."""
+    import torch
+    from paper_2504_08930_amd.binding import ivf_calib_copy, ivf_calib_read
+    src = torch.ones(1 << 28, dtype=torch.float32, device=dev)      # 1 GiB
+    sink = torch.empty(1 << 20, dtype=torch.int32, device=dev)
+    stream = torch.cuda.current_stream(dev)
+    torch.cuda.synchronize()
+    if with_copy:
+        dst = torch.empty_like(src)
+        ivf_calib_copy(src, dst, stream)
+        torch.cuda.synchronize()
+        del dst
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    for _ in range(2):
+        ivf_calib_read(src, sink, stream)
+    e0.record(stream)
+    for _ in range(launches):
+        ivf_calib_read(src, sink, stream)
+    e1.record(stream)
+    torch.cuda.synchronize()
+    return round(launches * (1 << 30) / (e0.elapsed_time(e1) * 1e-3) / 1e9, 1)
 
 
 def main():
@@ -425,11 +467,16 @@ def main():
         index.load_partition(hot)
         resident_frac = len(hot) / ix.nlist
 
+    # the machine's achievable streaming-read rate, the second denominator of the scan's
+    # roofline: the plain read kernel over 1 GiB, ten launches timed after two untimed ones
+    read_ceiling = measure_read_ceiling(dev, with_copy=args.calib_copy)
+
     # timed region: HIP events around the scan kernel only (they feed the roofline figure)
     r = timed_steps(index, q, spec.nprobe, spec.k, args.steps, args.warmup, args.slices,
                     timing=0 if args.no_timing else (1 if args.stage_timing else 2),
                     n_streams=args.streams)
     out_ids, out_d = r["out_ids"], r["out_d"]
+    out_d_dev = out_d
     stage_ms = r["stage_ms"]
     if not args.stage_timing:
         # per-stage times from a short pass of its own, events around every stage
@@ -440,37 +487,28 @@ def main():
     # time): context for callers that hold their queries on the host, never `value`
     host_ptr = None
     if resident_frac == 1.0 and not args.no_timing:
-        q_host = q.cpu().numpy()
         index.set_tuning(scan_slices=args.slices, timing=0)
-        for _ in range(3):
-            index.search_batch(q_host, spec.nprobe, spec.k)
         n_h = min(args.steps, 30)
-        t0 = time.perf_counter()
-        for _ in range(n_h):
-            index.search_batch(q_host, spec.nprobe, spec.k)
-        host_ptr = {"queries_per_s": round(nq * n_h / (time.perf_counter() - t0), 1), "steps": n_h,
-                    "note": "ivf_search_batch with pageable host queries and results, synchronous"}
-
-    read_ceiling = None
-    if args.calib_copy:
-        from paper_2504_08930_amd.binding import ivf_calib_copy, ivf_calib_read
-        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)      # 1 GiB
-        dst = torch.empty_like(src)
-        sink = torch.empty(1 << 20, dtype=torch.int32, device=dev)
-        stream = torch.cuda.current_stream(dev)
-        torch.cuda.synchronize()
-        ivf_calib_copy(src, dst, stream)
-        torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        ivf_calib_read(src, sink, stream)
-        torch.cuda.synchronize()
-        e0.record()
-        for _ in range(5):
-            ivf_calib_read(src, sink, stream)
-        e1.record()
-        torch.cuda.synchronize()
-        read_ceiling = round(5 * (1 << 30) / (e0.elapsed_time(e1) * 1e-3) / 1e9, 1)
-        del src, dst, sink
+        host_ptr = {"steps": n_h,
+                    "note": "ivf_search_batch: host queries in, host results out, one synchronous "
+                            "call at a time (PCIe both ways inside the timed call)"}
+        q_pinned = q.cpu().pin_memory()
+        for kind, q_host in (("pinned", q_pinned.numpy()), ("pageable", q.cpu().numpy().copy())):
+            out_i = torch.empty((nq, spec.k), dtype=torch.int64)
+            out_d = torch.empty((nq, spec.k), dtype=torch.float32)
+            if kind == "pinned":
+                out_i, out_d = out_i.pin_memory(), out_d.pin_memory()
+            for _ in range(3):
+                index.search_batch(q_host, spec.nprobe, spec.k, out_i.numpy(), out_d.numpy())
+            t0 = time.perf_counter()
+            for _ in range(n_h):
+                index.search_batch(q_host, spec.nprobe, spec.k, out_i.numpy(), out_d.numpy())
+            dt = time.perf_counter() - t0
+            host_ptr[f"queries_per_s_{kind}"] = round(nq * n_h / dt, 1)
+            host_ptr[f"ms_per_call_{kind}"] = round(1e3 * dt / n_h, 4)
+            assert torch.equal(out_i, out_ids.cpu()) and torch.equal(out_d, out_d_dev.cpu())
+        host_ptr["pinned_over_device_resident"] = round(
+            host_ptr["queries_per_s_pinned"] / r["qps"], 4)
 
     roofline = None
     if "scan_gbs" in r:
@@ -480,11 +518,24 @@ def main():
                     "bytes_per_launch": int(r["scan_bytes_per_launch"]),
                     "avg_launch_ms": round(r["scan_ms"], 4)}
         key = (spec.name, nq, round(resident_frac, 4))
+        roofline["scan_source_hash"] = scan_source_hash()
         if (key in MEASURED_TRAFFIC and args.slices == 0 and not args.residual
-                and args.nbits == 8 and not args.m):
-            roofline["traffic"], roofline["traffic_source"] = MEASURED_TRAFFIC[key]
-        if read_ceiling is not None:
-            roofline["streaming_read_GBs"] = read_ceiling
+                and args.nbits == 8 and not args.m and not args.nprobe and not args.k):
+            traffic, source, src_hash = MEASURED_TRAFFIC[key]
+            if src_hash == roofline["scan_source_hash"]:
+                # bytes that crossed the L2 boundary per launch (rocprofv3 counters, measured
+                # once on these sources) over this run's launch time: the counter-based rate
+                roofline["traffic"], roofline["traffic_source"] = traffic, source
+                roofline["frac_traffic"] = round(
+                    traffic / (r["scan_ms"] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
+            else:
+                roofline["traffic_note"] = (f"{source} was measured on other scan sources "
+                                            f"({src_hash}); no traffic figure for this build")
+        roofline["frac_note"] = ("achieved = algorithmic bytes / time: lists that queries share "
+                                 "are counted once per query but can be served from L2, so frac "
+                                 "may pass 1; frac_traffic counts the bytes that crossed L2")
+        roofline["streaming_read_GBs"] = read_ceiling
+        roofline["frac_of_streaming_read"] = round(r["scan_gbs"] / read_ceiling, 4)
         if resident_frac == 1.0:
             # bytes of the distinct lists the batch touches (what a perfect cache would fetch)
             pr = index.coarse_probe_dev(q, spec.nprobe).cpu().numpy()
@@ -558,7 +609,9 @@ def main():
                    "resident_fraction": round(resident_frac, 4),
                    "mean_hit_rate": round(r["hit_rate"], 4),
                    "scan_slices": args.slices, "streams": args.streams,
-                   "inputs": "device-resident queries"},
+                   "inputs": "queries already in HBM when the timed region starts "
+                             "(ivf_search_batch_dev); the host-pointer call is in "
+                             "host_pointer_call"},
         "roofline": roofline,
         "cpu_baseline": cpu_baseline,
         "stage_ms": stage_ms,

@@ -16,7 +16,8 @@
  * Conventions
  *  - Plain C ABI.  Every pointer is documented as HOST or DEVICE memory.
  *  - A negative return value is an error; ivf_last_error() then holds a
- *    message (thread-local).  On error no output buffer is partially written.
+ *    message (thread-local).  On an argument, state or memory error no output
+ *    buffer is written; after a HIP failure (IVF_EDEVICE) outputs are undefined.
  *  - The library never frees or reallocates caller memory.  Arrays named in
  *    ivf_index_desc_t are BORROWED for the lifetime of the index: they are the
  *    source of the CPU scan and of host-to-device cluster copies.
@@ -152,7 +153,10 @@ int ivf_index_load_partition(ivf_index_t *index, const int32_t *cluster_ids, int
  * Section 4.2.2).  queries: HOST fp32 [nq][d].  out_ids: HOST int64 [nq][k];
  * out_dists: HOST fp32 [nq][k].  nprobe > nlist is clamped.  nq == 0 is a
  * no-op.  Requires 1 <= nq <= max_nq, 1 <= nprobe <= max_nprobe,
- * 1 <= k <= max_k.  Returns after the results are written.
+ * 1 <= k <= max_k.  Returns after the results are written.  Buffers in pinned
+ * host memory (hipHostMalloc) are copied from and to by DMA as they are;
+ * pageable queries are first gathered in a pinned buffer of the index by the
+ * library's worker threads, pageable results pass through one.
  */
 int ivf_search_batch(ivf_index_t *index, const float *queries, int64_t nq, int32_t nprobe,
                      int32_t k, int64_t *out_ids, float *out_dists);
@@ -338,7 +342,8 @@ int ivf_copy_form(const ivf_index_t *index);
  * subsequent searches on their stream, timing = 2 only around the ADC scan
  * (each recorded event costs a few microseconds of stream time), 0 none.
  * The events of a batch are held until ivf_stage_times() reads them; after
- * 8192 unread batches further batches are not timed.
+ * 8192 unread batches further batches are not timed.  Events are pooled:
+ * turning timing on stocks the pool, ivf_stage_times() returns events to it.
  */
 int ivf_set_tuning(ivf_index_t *index, int32_t scan_slices, int32_t timing);
 

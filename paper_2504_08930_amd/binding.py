@@ -256,11 +256,16 @@ class IvfIndex:
         return _check(self._lib.ivf_copy_form(self._h))
 
     # ---- search ----
-    def search_batch(self, queries, nprobe, k):
+    def search_batch(self, queries, nprobe, k, out_ids=None, out_dists=None):
+        """out_ids / out_dists: optional caller arrays (int64 / float32, [nq, k], contiguous;
+        pinned memory is written by the device directly)."""
         q = np.ascontiguousarray(queries, dtype=np.float32)
         nq = q.shape[0]
-        ids = np.empty((nq, k), np.int64)
-        dists = np.empty((nq, k), np.float32)
+        ids = np.empty((nq, k), np.int64) if out_ids is None else out_ids
+        dists = np.empty((nq, k), np.float32) if out_dists is None else out_dists
+        assert ids.dtype == np.int64 and dists.dtype == np.float32
+        assert ids.shape == (nq, k) and dists.shape == (nq, k)
+        assert ids.flags.c_contiguous and dists.flags.c_contiguous
         _check(self._lib.ivf_search_batch(self._h, _np_ptr(q), nq, nprobe, k, _np_ptr(ids),
                                           _np_ptr(dists)))
         return ids, dists

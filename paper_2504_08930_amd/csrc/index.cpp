@@ -170,6 +170,7 @@ extern "C" void ivf_index_destroy(ivf_index_t *ix) {
     for (auto &v : ix->versions)
       for (auto e : v.events) (void)hipEventDestroy(e);
     for (auto e : ix->event_pool) (void)hipEventDestroy(e);
+    for (auto e : ix->timing_pool) (void)hipEventDestroy(e);
     for (auto &r : ix->trecs)
       for (int i = 0; i <= IVF_N_STAGES; ++i)
         if (r.valid[i]) (void)hipEventDestroy(r.ev[i]);
@@ -361,6 +362,12 @@ extern "C" int ivf_set_tuning(ivf_index_t *ix, int32_t scan_slices, int32_t timi
   std::lock_guard<std::mutex> lk(ix->mu);
   ix->tune_slices = scan_slices;
   ix->timing = timing;
+  // timed batches take their events from a pool; stock it here, outside any timed region
+  while (timing && ix->has_dev && ix->timing_pool.size() < 1024) {
+    hipEvent_t e = nullptr;
+    HIP_TRY(hipEventCreate(&e));
+    ix->timing_pool.push_back(e);
+  }
   return IVF_OK;
 }
 
@@ -379,7 +386,10 @@ static int drain_timing(ivf_index *ix) {
       }
     }
     for (int i = 0; i <= IVF_N_STAGES; ++i)
-      if (r.valid[i]) (void)hipEventDestroy(r.ev[i]);
+      if (r.valid[i]) {
+        if (ix->timing_pool.size() < 4096) ix->timing_pool.push_back(r.ev[i]);
+        else (void)hipEventDestroy(r.ev[i]);
+      }
   }
   ix->trecs.clear();
   return IVF_OK;

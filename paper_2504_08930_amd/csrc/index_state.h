@@ -146,6 +146,7 @@ struct ivf_index {
   double migrate_ms = 0.0;      // device time of completed migrations' copies
   uint64_t n_migrations = 0;
   std::vector<hipEvent_t> event_pool;
+  std::vector<hipEvent_t> timing_pool;  // events with timing enabled, reused by timed batches
 
   std::vector<float> cb_t;  // codebooks, element-major (host table construction)
   std::vector<uint8_t> codes_t;    // codes, column-major per list (byte-plane CPU scan), or empty

@@ -63,6 +63,35 @@ static int search_host_only(ivf_index *ix, const float *queries, int64_t nq, con
   return IVF_OK;
 }
 
+// True if p lies in pinned host memory that the runtime knows: a copy from or to it
+// is a DMA transfer that runs asynchronously at the bus rate.  Anything else
+// (pageable memory) the runtime would stage by itself, synchronously and slowly.
+static bool host_ptr_pinned(const void *p) {
+  hipPointerAttribute_t at;
+  memset(&at, 0, sizeof(at));
+  if (hipPointerGetAttributes(&at, p) != hipSuccess) {
+    (void)hipGetLastError();  // an unknown pointer is no error here
+    return false;
+  }
+  return at.type == hipMemoryTypeHost;
+}
+
+// Copy n bytes of pageable host memory into one of the index's pinned buffers on
+// the library's worker threads (one thread moves about 10 GB/s; a batch of 1024
+// queries is 3 MB).
+static void staged_copy(void *dst, const void *src, size_t n) {
+  constexpr size_t kChunk = (size_t)256 << 10;
+  if (n <= 2 * kChunk) {
+    memcpy(dst, src, n);
+    return;
+  }
+  const int64_t chunks = (int64_t)((n + kChunk - 1) / kChunk);
+  parallel_for(chunks, [&](int64_t i) {
+    const size_t off = (size_t)i * kChunk;
+    memcpy((char *)dst + off, (const char *)src + off, std::min(kChunk, n - off));
+  });
+}
+
 // Workspace slot for a batch on stream st (caller holds ix->mu).
 static int acquire_slot_locked(ivf_index *ix, hipStream_t st, int *slot) {
   int pick = -1;
@@ -146,9 +175,21 @@ int enqueue_gpu(ivf_index *ix, const SearchArgs &a, const BatchCtx &c, bool fina
   auto mark = [&](int i) -> hipError_t {
     if (!c.timing) return hipSuccess;
     if (c.timing == 2 && i != IVF_STAGE_SCAN && i != IVF_STAGE_MERGE) return hipSuccess;
-    hipError_t e = hipEventCreate(&trec.ev[i]);
-    if (e != hipSuccess) return e;
-    trec.valid[i] = true;
+    // events come from a pool that ivf_stage_times() refills: in steady state a timed
+    // batch creates none
+    {
+      std::lock_guard<std::mutex> lk(ix->mu);
+      if (!ix->timing_pool.empty()) {
+        trec.ev[i] = ix->timing_pool.back();
+        ix->timing_pool.pop_back();
+        trec.valid[i] = true;
+      }
+    }
+    if (!trec.valid[i]) {
+      hipError_t e = hipEventCreate(&trec.ev[i]);
+      if (e != hipSuccess) return e;
+      trec.valid[i] = true;
+    }
     return hipEventRecord(trec.ev[i], st);
   };
   auto keep_timing = [&]() {
@@ -168,7 +209,15 @@ int enqueue_gpu(ivf_index *ix, const SearchArgs &a, const BatchCtx &c, bool fina
 
   const float *dq = a.q_dev;
   if (!dq) {
-    G_TRY(hipMemcpyAsync(W.queries, a.q_host, (size_t)nq * sh.d * 4, hipMemcpyHostToDevice, st));
+    // pinned caller memory goes over the bus as it is; pageable memory is first
+    // gathered in the index's pinned buffer (the host-pointer calls are synchronous
+    // and the asynchronous one holds the index, so that buffer is free)
+    const float *src = a.q_host;
+    if (!host_ptr_pinned(src)) {
+      staged_copy(ix->h_queries, src, (size_t)nq * sh.d * 4);
+      src = ix->h_queries;
+    }
+    G_TRY(hipMemcpyAsync(W.queries, src, (size_t)nq * sh.d * 4, hipMemcpyHostToDevice, st));
     dq = W.queries;
   }
   // ---- stage 2 first: the lookup tables depend on the queries only ----
@@ -281,7 +330,25 @@ static int search_device(ivf_index *ix, const SearchArgs &a) {
   const BatchWs &W = ix->L.ws[ctx.slot];
   const bool final_on_gpu = ctx.all_resident;
   const bool any_resident = ctx.any_resident;
-  rc = enqueue_gpu(ix, a, ctx, final_on_gpu, final_on_gpu ? nullptr : ix->ev_routed);
+  // Host results of a fully resident batch: when the caller's buffers are pinned host
+  // memory that the device can address, the last kernel writes ids and distances into
+  // them itself (120 KB at nq = 1024, k = 10) and no copy follows; the stream
+  // synchronization below makes them visible to the host.
+  SearchArgs dev_args = a;
+  bool zero_copy_out = false;
+  if (final_on_gpu && !a.out_device && host_ptr_pinned(a.out_ids) && host_ptr_pinned(a.out_dists)) {
+    void *di = nullptr, *dd = nullptr;
+    if (hipHostGetDevicePointer(&di, a.out_ids, 0) == hipSuccess &&
+        hipHostGetDevicePointer(&dd, a.out_dists, 0) == hipSuccess && di && dd) {
+      dev_args.out_ids = static_cast<int64_t *>(di);
+      dev_args.out_dists = static_cast<float *>(dd);
+      dev_args.out_device = true;
+      zero_copy_out = true;
+    } else {
+      (void)hipGetLastError();
+    }
+  }
+  rc = enqueue_gpu(ix, dev_args, ctx, final_on_gpu, final_on_gpu ? nullptr : ix->ev_routed);
   if (rc < 0) {
     (void)hipStreamSynchronize(st);
     end_batch(ix, ctx, st, false);
@@ -303,6 +370,12 @@ static int search_device(ivf_index *ix, const SearchArgs &a) {
       end_batch(ix, ctx, st, true);  // asynchronous: outputs valid when the stream gets here
       return IVF_OK;
     }
+    if (zero_copy_out) {
+      S_TRY(hipStreamSynchronize(st));
+      end_batch(ix, ctx, st, false);
+      return IVF_OK;
+    }
+    // pageable results: one pair of copies into the index's pinned buffers, then out
     S_TRY(hipMemcpyAsync(ix->h_outids, W.out_ids, (size_t)nq * k * 8, hipMemcpyDeviceToHost, st));
     S_TRY(hipMemcpyAsync(ix->h_outd, W.out_dists, (size_t)nq * k * 4, hipMemcpyDeviceToHost, st));
     S_TRY(hipStreamSynchronize(st));

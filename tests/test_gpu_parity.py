@@ -1042,6 +1042,38 @@ def test_four_bit_codes(pkg, oracle, name, m, residual):
     index.close()
 
 
+def test_host_pointer_call_with_pinned_and_pageable_buffers(pkg, oracle):
+    """ivf_search_batch takes any host memory.  Pinned queries are copied by DMA as they
+    are and pinned result buffers are written by the last kernel itself; pageable ones go
+    through the index's pinned buffers.  All four combinations, with every cluster resident
+    and with half of them (where the merged result is copied out), must return the same
+    bytes, and large batches take the multi-threaded staging copy."""
+    import torch
+    spec, ix, q, calib = _case("T_IP96")
+    centers = mixture_centers(spec, torch.device("cuda"))
+    big = make_queries(spec, centers, nq=2048, seed=spec.seed_queries + 9)[0].cpu()
+    index = pkg.IvfIndex(ix, max_nq=2048, max_nprobe=ix.nlist, max_k=128)
+    full = np.arange(ix.nlist, dtype=np.int32)
+    for resident in (full, full[::2].copy()):
+        index.load_partition(resident)
+        for nq, k in ((2048, 10), (40, 100), (1, 1)):
+            qp = big[:nq].contiguous()
+            ref = index.search_batch(qp.numpy().copy(), spec.nprobe, k)
+            for pin_q in (False, True):
+                for pin_out in (False, True):
+                    _say(f"host call: resident {len(resident)} nq={nq} k={k} "
+                         f"pinned queries={pin_q} outputs={pin_out}")
+                    qh = qp.pin_memory() if pin_q else qp.clone()
+                    oi = torch.full((nq, k), -5, dtype=torch.int64)
+                    od = torch.full((nq, k), float("nan"), dtype=torch.float32)
+                    if pin_out:
+                        oi, od = oi.pin_memory(), od.pin_memory()
+                    index.search_batch(qh.numpy(), spec.nprobe, k, oi.numpy(), od.numpy())
+                    assert np.array_equal(oi.numpy(), ref[0]), (nq, k, pin_q, pin_out)
+                    assert np.array_equal(od.numpy(), ref[1]), (nq, k, pin_q, pin_out)
+    index.close()
+
+
 def test_batches_in_flight_on_three_streams(pkg, oracle):
     """The index keeps two per-batch workspaces, each tied to the stream that used it
     last: batches issued back to back on different streams (a third stream makes the
