@@ -188,6 +188,9 @@ def main():
     ap.add_argument("--stage-timing", action="store_true",
                     help="record HIP events around every stage in the timed region instead of "
                          "around the scan only (each event costs a few microseconds per step)")
+    ap.add_argument("--nq-list", default="256,1024,4096", help="sweep mode: batch sizes")
+    ap.add_argument("--resident-list", default="1.0,0.5,0.3,0.1",
+                    help="sweep mode: resident fractions")
     ap.add_argument("--slo-ms", type=float, default=60.0,
                     help="partition mode: search latency target SLO_search in ms")
     ap.add_argument("--epochs", type=int, default=20, help="drift mode: epochs")
@@ -222,7 +225,8 @@ def main():
     torch.cuda.synchronize()
     build_s = time.time() - t0
     log(f"index built in {build_s:.1f}s: N={ix.n} nlist={ix.nlist} M={ix.m}")
-    max_nq = max(nq, 4096 if args.mode == "sweep" else 1024)
+    nq_list = [int(x) for x in args.nq_list.split(",")]
+    max_nq = max(nq, max(nq_list) if args.mode == "sweep" else 1024)
     index = pkg.IvfIndex(ix, max_nq=max_nq, max_nprobe=spec.nprobe, max_k=spec.k)
     t0 = time.time()
     all_clusters = np.arange(ix.nlist, dtype=np.int32)
@@ -238,11 +242,11 @@ def main():
 
     if args.mode == "sweep":
         rows = []
-        for frac in (1.0, 0.5, 0.3, 0.1):
+        for frac in [float(x) for x in args.resident_list.split(",")]:
             if frac < 1.0:
                 index.load_partition(all_clusters)
                 index.load_partition(hottest_clusters(index, calib, spec.nprobe, frac, ix.nlist))
-            for n in (256, 1024, 4096):
+            for n in nq_list:
                 q, _ = make_queries(spec, centers, nq=n)
                 steps = min(args.steps, 50) if frac == 1.0 else 3
                 r = timed_steps(index, q.contiguous(), spec.nprobe, spec.k, steps,
@@ -252,7 +256,9 @@ def main():
                        "mean_hit_rate": round(r["hit_rate"], 4),
                        "min_hit_rate": round(r["min_hit_rate"], 4),
                        "scan_ms": round(r.get("scan_ms", 0.0), 4),
-                       "scan_GBs": round(r.get("scan_gbs", 0.0), 1), "stage_ms": r["stage_ms"]}
+                       "scan_GBs": round(r.get("scan_gbs", 0.0), 1),
+                       "scan_frac_of_peak": round(r.get("scan_gbs", 0.0) / HBM_PEAK_GBS, 4),
+                       "stage_ms": r["stage_ms"]}
                 log(json.dumps(row))
                 rows.append(row)
         index.close()

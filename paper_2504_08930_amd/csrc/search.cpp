@@ -559,7 +559,14 @@ extern "C" int ivf_search_batch_probes(ivf_index_t *ix, const float *queries, in
     return fail(IVF_EINVAL, "nprobe %d exceeds max_nprobe %d", nprobe, ix->desc.max_nprobe);
   rc = check_probe_list(ix, probe, nq, nprobe);
   if (rc != IVF_OK) return rc;
-  if (!ix->has_dev) return search_host_only(ix, queries, nq, probe, nprobe, k, out_ids, out_dists);
+  if (!ix->has_dev) {
+    {
+      std::lock_guard<std::mutex> lk(ix->mu);
+      if (ix->dispatch_active)
+        return fail(IVF_EBUSY, "an asynchronous batch is still in flight on this index");
+    }
+    return search_host_only(ix, queries, nq, probe, nprobe, k, out_ids, out_dists);
+  }
   SearchArgs a;
   a.q_host = queries;
   a.probe_host = probe;

@@ -862,6 +862,29 @@ def test_k100_nprobe128(pkg, oracle):
     assert np.array_equal(ids10.cpu().numpy(), ids[:, :10])
     assert np.array_equal(dist10.cpu().numpy(), dist[:, :10])
     index.close()
+    # The paper's own operating point (Section 5.1 "Experiment Setup": nprobe = 2048, the 25
+    # best documents, small on-demand batches): half of this index's lists per query, thirty-two
+    # 64-probe windows per work list, batches of 8 and 64 queries split over several blocks.
+    index = pkg.IvfIndex(ix, max_nq=64, max_nprobe=2048, max_k=32)
+    index.load_partition(np.arange(ix.nlist, dtype=np.int32))
+    for nq in (8, 64):
+        qs = np.ascontiguousarray(q[100:100 + nq])
+        qd = torch.from_numpy(qs).cuda()
+        ids_d, dist_d = index.search_batch_dev(qd, 2048, 25)
+        torch.cuda.synchronize()
+        ids, dist = ids_d.cpu().numpy(), dist_d.cpu().numpy()
+        probe = index.coarse_probe_dev(qd, 2048).cpu().numpy()
+        sel = np.arange(0, nq, max(1, nq // 8))
+        st = ParityStats()
+        n_coarse, n_amb = _check_search(oracle, ix, qs[sel], 2048, 25, ids[sel], dist[sel],
+                                        probe[sel], stats=st)
+        _say(f"C4S nprobe=2048 k=25 nq={nq}: coarse-ambiguous {n_coarse}; {st.summary()}")
+        assert n_coarse <= 1 and n_amb <= 1
+        hyb_ref = (ids, dist)
+    index.load_partition(np.arange(0, ix.nlist, 3, dtype=np.int32))           # a third resident
+    hyb = index.search_batch(qs, 2048, 25)
+    assert np.array_equal(hyb[0], hyb_ref[0]) and np.array_equal(hyb[1], hyb_ref[1])
+    index.close()
     _CACHE.pop("C4S", None)
 
 
