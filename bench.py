@@ -250,7 +250,8 @@ def main():
                 q, _ = make_queries(spec, centers, nq=n)
                 steps = min(args.steps, 50) if frac == 1.0 else 3
                 r = timed_steps(index, q.contiguous(), spec.nprobe, spec.k, steps,
-                                min(args.warmup, 20) if frac == 1.0 else 1, args.slices)
+                                min(args.warmup, 20) if frac == 1.0 else 1, args.slices,
+                                timing=1 if args.stage_timing else 2)
                 row = {"nq": n, "resident_fraction": frac, "queries_per_s": round(r["qps"], 1),
                        "ms_per_step": round(r["ms_per_step"], 3),
                        "mean_hit_rate": round(r["hit_rate"], 4),

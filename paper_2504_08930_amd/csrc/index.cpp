@@ -121,8 +121,8 @@ static size_t plan_layout(const ivf_index_desc_t &d, int64_t resident_vectors, s
     w.bias = (float *)take(nq * np * 4);
     w.g_bias = (float *)take(nq * np * 4);
     w.qbmax = (float *)take(nq * 4);
-    w.part_key = (int32_t *)take(nq * kMaxSlices * k * 4);
-    w.part_id = (int64_t *)take(nq * kMaxSlices * k * 8);
+    w.part_key = (int32_t *)take((size_t)part_rows((int64_t)nq) * k * 4);
+    w.part_id = (int64_t *)take((size_t)part_rows((int64_t)nq) * k * 8);
     w.res_key = (int32_t *)take(nq * k * 4);
     w.res_id = (int64_t *)take(nq * k * 8);
     w.out_ids = (int64_t *)take(nq * k * 8);

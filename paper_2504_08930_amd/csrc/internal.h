@@ -8,7 +8,13 @@
 namespace ivf {
 
 constexpr int kTileVecs = 64;      // vectors per code tile (one wavefront)
-constexpr int kMaxSlices = 8;      // scan blocks per query, upper bound
+constexpr int kMaxSlices = 32;     // scan blocks per query, upper bound
+// Partial-result rows (one per scan block of a sliced query) the workspace holds:
+// room for eight slices of every query of a full batch, and for kMaxSlices slices of
+// the small batches that need them to fill the chip.
+constexpr int64_t part_rows(int64_t max_nq) {
+  return max_nq * 8 > 64 * (int64_t)kMaxSlices ? max_nq * 8 : 64 * (int64_t)kMaxSlices;
+}
 constexpr int kMaxK = 128;
 constexpr int kMaxNprobe = 2048;
 constexpr int kLutMaxParts = 512;   // per-query slots for partial table maxima
@@ -58,7 +64,7 @@ struct BatchWs {
   float *bias;             // [max_nq][max_nprobe] residual encoding: bias(q, probe), probe order
   float *g_bias;           // [max_nq][max_nprobe] the same for resident probes, work-list order
   float *qbmax;            // [max_nq] largest |bias| among the query's probes (0 if unused)
-  int32_t *part_key;       // [max_nq][kMaxSlices][max_k]
+  int32_t *part_key;       // [part_rows(max_nq)][max_k]: row (q * slices + s) of a launch
   int64_t *part_id;
   int32_t *res_key;        // [max_nq][max_k] merged GPU partial (hybrid path)
   int64_t *res_id;

@@ -351,14 +351,14 @@ __global__ __launch_bounds__(kSelThreads) void k_coarse_select(const float *__re
         if (c < nlist) body(sc[i], c);
       }
     } else {
-      // eight loads in flight per thread before their values are used
+      // sixteen loads in flight per thread before their values are used
       int c = tid;
-      for (; c + 7 * kSelThreads < nlist; c += 8 * kSelThreads) {
-        float v[8];
+      for (; c + 15 * kSelThreads < nlist; c += 16 * kSelThreads) {
+        float v[16];
 #pragma unroll
-        for (int i = 0; i < 8; ++i) v[i] = row[c + i * kSelThreads];
+        for (int i = 0; i < 16; ++i) v[i] = row[c + i * kSelThreads];
 #pragma unroll
-        for (int i = 0; i < 8; ++i) body(v[i], c + i * kSelThreads);
+        for (int i = 0; i < 16; ++i) body(v[i], c + i * kSelThreads);
       }
       for (; c < nlist; c += kSelThreads) body(row[c], c);
     }
@@ -611,9 +611,8 @@ __global__ __launch_bounds__(kSelThreads) void k_coarse_select(const float *__re
   // Keys are distinct (the id is part of them), so the number of keys that come
   // before a candidate's is its rank.  Up to kSelThreads candidates: every
   // thread counts, for one candidate, one stretch of the others, and the
-  // stretches' counts are added up in LDS; more: a thread counts all of them
-  // for each candidate it owns.  Lanes of a wavefront compare against the same
-  // key at a time (one LDS broadcast).
+  // stretches' counts are added up in LDS (lanes of a wavefront compare against
+  // the same key at a time, one LDS broadcast); more: the block sorts them.
   const int filled = (int)min(s_count, (unsigned)cap);
   int n2 = 64;
   while (n2 < filled) n2 <<= 1;
@@ -636,12 +635,27 @@ __global__ __launch_bounds__(kSelThreads) void k_coarse_select(const float *__re
       if (r < (unsigned)keep) out[r] = (int32_t)(sel[tid] & 0xffffffffull);
     }
   } else {
-    for (int i = tid; i < filled; i += kSelThreads) {
-      const unsigned long long mine = sel[i];
-      unsigned cnt = 0;
-      for (int j = 0; j < filled; ++j) cnt += sel[j] < mine ? 1u : 0u;
-      if (cnt < (unsigned)keep) out[cnt] = (int32_t)(mine & 0xffffffffull);
+    // more candidates than threads (nprobe in the thousands): counting would cost
+    // filled^2 / threads comparisons per thread, so sort instead.  Slots beyond
+    // `filled` hold ~0, the largest key; cap is a power of two.
+    for (int size = 2; size <= cap; size <<= 1) {
+      for (int st = size >> 1; st > 0; st >>= 1) {
+        for (int i = tid; i < cap; i += kSelThreads) {
+          const int j = i ^ st;
+          if (j > i) {
+            const bool asc = (i & size) == 0;
+            const unsigned long long a = sel[i], b = sel[j];
+            if ((b < a) == asc) {
+              sel[i] = b;
+              sel[j] = a;
+            }
+          }
+        }
+        __syncthreads();
+      }
     }
+    for (int r = tid; r < min(filled, keep); r += kSelThreads)
+      out[r] = (int32_t)(sel[r] & 0xffffffffull);
   }
   for (int p = min(filled, keep) + tid; p < nprobe; p += kSelThreads) out[p] = -1;
 }

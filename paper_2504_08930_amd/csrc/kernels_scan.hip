@@ -309,6 +309,203 @@ __global__ __launch_bounds__(256) void k_route(
   }
 }
 
+// The same routing for long probe lists (more than 256 probes, as at the paper's
+// own operating point of 2048 probes per query, Section 5.1): one block per query,
+// every step spread over all of its threads.
+//  A. cluster-id order: without residual encoding a probe needs no memory of its
+//     rank, so the probed clusters are marked in a bitmap over the lists and read
+//     back in order (a prefix sum over the words' bit counts); otherwise (or when
+//     the bitmap would not fit) a block-wide bitonic sort of (id, rank) words;
+//  B. mapping table, list length, bias and counters for every probe, all loads in
+//     flight together;
+//  C. block-wide prefix sums place every probe in the GPU work list or the cold list.
+// Outputs are exactly those of k_route.
+constexpr int kRouteBigThreads = 512;
+constexpr int kRouteBigPer = kMaxNprobe / kRouteBigThreads;  // probes per thread, at most
+constexpr int kRouteBitmapLists = 1 << 17;                   // 16 KB of LDS
+
+// exclusive prefix of v over the block's threads (total in *total); s_w: one slot per wavefront
+__device__ __forceinline__ int block_excl_scan(int v, int *s_w, int *total) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  int incl = v;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const int u = __shfl_up(incl, o, 64);
+    if (lane >= o) incl += u;
+  }
+  if (lane == 63) s_w[wave] = incl;
+  __syncthreads();
+  int before = 0, all = 0;
+  for (int w2 = 0; w2 < kRouteBigThreads / 64; ++w2) {
+    const int x = s_w[w2];
+    if (w2 < wave) before += x;
+    all += x;
+  }
+  __syncthreads();  // s_w may be reused
+  *total = all;
+  return before + incl - v;
+}
+
+__global__ __launch_bounds__(kRouteBigThreads) void k_route_big(
+    const int32_t *__restrict__ probe, int nq, int nprobe, int stride, int nlist,
+    const int32_t *__restrict__ clus_tile, const int32_t *__restrict__ clus_len, int32_t *g_base,
+    int32_t *g_len, int32_t *g_prefix, int32_t *g_n, int32_t *cold, int32_t *n_cold,
+    int32_t *q_vecs, const float *__restrict__ bias, float *g_bias, float *qbmax,
+    unsigned long long *hits, int count_stats, int use_bitmap,
+    const uint32_t *__restrict__ lutpart, int nparts, uint32_t *__restrict__ lutmax) {
+  constexpr int NT = kRouteBigThreads, E = kRouteBigPer, N = NT * E;
+  __shared__ int32_t s_c[N];      // cluster of the i-th probe in cluster-id order, or -1
+  __shared__ int32_t s_p[N];      // its rank in the query's probe list (bias index)
+  __shared__ uint32_t s_bm[kRouteBitmapLists / 32];
+  __shared__ int s_w[NT / 64];
+  __shared__ unsigned long long s_vecs;
+  __shared__ unsigned int s_bmax;
+  const int q = blockIdx.x;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int32_t *pr = probe + (size_t)q * stride;
+  if (nparts > 0 && tid < 64) {
+    uint32_t mx = 0;
+    for (int i = lane; i < nparts; i += 64) mx = max(mx, lutpart[(size_t)q * kLutMaxParts + i]);
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) mx = max(mx, (uint32_t)__shfl_xor((int)mx, o, 64));
+    if (lane == 0) lutmax[q] = mx;
+  }
+  if (tid == 0) {
+    s_vecs = 0ull;
+    s_bmax = 0u;
+  }
+  // ---- A. probes in cluster-id order ----
+  int nv = 0;  // valid probes
+  if (use_bitmap) {
+    const int nwords = (nlist + 31) >> 5;
+    for (int w = tid; w < nwords; w += NT) s_bm[w] = 0u;
+    __syncthreads();
+    for (int p = tid; p < nprobe; p += NT) {
+      const int c = pr[p];
+      if (c >= 0) atomicOr(&s_bm[c >> 5], 1u << (c & 31));
+    }
+    __syncthreads();
+    const int per = (nwords + NT - 1) / NT;
+    const int w0 = min(tid * per, nwords), w1 = min(w0 + per, nwords);
+    int cnt = 0;
+    for (int w = w0; w < w1; ++w) cnt += __popc(s_bm[w]);
+    int pos = block_excl_scan(cnt, s_w, &nv);
+    for (int w = w0; w < w1; ++w) {
+      uint32_t bits = s_bm[w];
+      while (bits) {
+        const int b = __ffs((int)bits) - 1;
+        bits &= bits - 1;
+        s_c[pos] = (w << 5) | b;
+        s_p[pos] = 0;
+        ++pos;
+      }
+    }
+    for (int i = nv + tid; i < N; i += NT) s_c[i] = -1;
+  } else {
+    int n2 = 512;
+    while (n2 < nprobe) n2 <<= 1;
+    for (int p = tid; p < N; p += NT) {
+      const int c = p < nprobe ? pr[p] : -1;
+      s_c[p] = c >= 0 ? ((c << 11) | p) : 0x7fffffff;
+    }
+    __syncthreads();
+    for (int size = 2; size <= n2; size <<= 1) {
+      for (int st = size >> 1; st > 0; st >>= 1) {
+        for (int i = tid; i < n2; i += NT) {
+          const int j = i ^ st;
+          if (j > i) {
+            const bool asc = (i & size) == 0;
+            const int a = s_c[i], b = s_c[j];
+            if ((b < a) == asc) {
+              s_c[i] = b;
+              s_c[j] = a;
+            }
+          }
+        }
+        __syncthreads();
+      }
+    }
+    for (int i = tid; i < N; i += NT) {
+      const int w = s_c[i];
+      s_c[i] = w != 0x7fffffff ? (w >> 11) : -1;
+      s_p[i] = w & 2047;
+    }
+  }
+  __syncthreads();
+  // ---- B. look every probe up (thread t owns probes t*E .. t*E+E-1 of the order) ----
+  int c[E], t[E], len[E];
+  float b[E];
+#pragma unroll
+  for (int e = 0; e < E; ++e) {
+    const int i = tid * E + e;
+    c[e] = s_c[i];
+    t[e] = -1;
+    len[e] = 0;
+    b[e] = 0.0f;
+  }
+#pragma unroll
+  for (int e = 0; e < E; ++e) {
+    if (c[e] >= 0) {
+      if (count_stats) atomicAdd(&hits[c[e]], 1ull);
+      t[e] = clus_tile[c[e]];
+      len[e] = clus_len[c[e]];
+      if (bias) b[e] = bias[(size_t)q * stride + s_p[tid * E + e]];
+    }
+  }
+  // ---- C. place them ----
+  int n_res = 0, n_cld = 0, n_tiles = 0;
+  unsigned long long vec = 0;
+  float bm = 0.0f;
+#pragma unroll
+  for (int e = 0; e < E; ++e) {
+    if (c[e] < 0) continue;
+    bm = fmaxf(bm, fabsf(b[e]));
+    if (t[e] >= 0) {
+      n_res += 1;
+      n_tiles += (len[e] + kTileVecs - 1) / kTileVecs;
+      vec += (unsigned long long)len[e];
+    } else {
+      n_cld += 1;
+    }
+  }
+  int ng = 0, nc = 0, tiles = 0, both = 0;
+  const int packed = block_excl_scan((n_res << 16) | n_cld, s_w, &both);  // each at most 2048
+  int o_res = packed >> 16, o_cld = packed & 0xffff;
+  ng = both >> 16;
+  nc = both & 0xffff;
+  int o_tile = block_excl_scan(n_tiles, s_w, &tiles);
+  int32_t *gb = g_base + (size_t)q * stride;
+  int32_t *gl = g_len + (size_t)q * stride;
+  int32_t *gp = g_prefix + (size_t)q * (stride + 1);
+  int32_t *cd = cold + (size_t)q * stride;
+#pragma unroll
+  for (int e = 0; e < E; ++e) {
+    if (c[e] < 0) continue;
+    if (t[e] >= 0) {
+      gb[o_res] = t[e];
+      gl[o_res] = len[e];
+      gp[o_res] = o_tile;
+      if (bias) g_bias[(size_t)q * stride + o_res] = b[e];
+      o_res += 1;
+      o_tile += (len[e] + kTileVecs - 1) / kTileVecs;
+    } else {
+      cd[o_cld++] = c[e];
+    }
+  }
+  for (int p = nc + tid; p < nprobe; p += NT) cd[p] = -1;
+  if (vec) atomicAdd(&s_vecs, vec);
+  if (bm > 0.0f) atomicMax(&s_bmax, __float_as_uint(bm));  // non-negative floats order like their bits
+  __syncthreads();
+  if (tid == 0) {
+    qbmax[q] = __uint_as_float(s_bmax);
+    gp[ng] = tiles;
+    gp[stride] = tiles;
+    g_n[q] = ng;
+    n_cold[q] = nc;
+    q_vecs[q] = (int32_t)s_vecs;
+  }
+}
+
 // One single-block kernel for the two small per-batch reductions between the
 // router and the scan:
 //  * batch totals of the router counters (same-address atomics from every
@@ -423,6 +620,14 @@ hipError_t launch_route(const int32_t *probe, int nq, int nprobe, int probe_stri
   if (nlist < (1 << 20)) {
     n2 = 64;
     while (n2 < nprobe) n2 <<= 1;
+  }
+  if (nprobe > 256 && nlist < (1 << 20)) {  // long lists: a block per query
+    const int use_bitmap = (!bias && nlist <= kRouteBitmapLists) ? 1 : 0;
+    hipLaunchKernelGGL(k_route_big, dim3(nq), dim3(kRouteBigThreads), 0, st, probe, nq, nprobe,
+                       probe_stride, nlist, clus_tile, clus_len, g_base, g_len, g_prefix, g_n, cold,
+                       n_cold, q_vecs, bias, g_bias, qbmax, hits, count_stats, use_bitmap, lutpart,
+                       lut_parts, lutmax);
+    return hipGetLastError();
   }
   hipLaunchKernelGGL(k_route, dim3((nq + 3) / 4), dim3(256), (size_t)4 * n2 * sizeof(int32_t), st,
                      probe, nq, nprobe, probe_stride, clus_tile, clus_len, M, g_base, g_len,
@@ -1339,47 +1544,84 @@ hipError_t launch_scan(const Shape &sh, const DevLayout &L, const BatchWs &W, in
 
 // ---------------------------------------------------------------------------
 // Per-query merge of the scan blocks' partial lists; emits the GPU result.
-// One wavefront per query.
+// One block per query: a wavefront for up to 256 candidates (slices * k), sixteen
+// wavefronts above (a query of a small batch may be split over kMaxSlices blocks).
 // ---------------------------------------------------------------------------
-__global__ __launch_bounds__(64) void k_merge(const int32_t *__restrict__ part_key,
+template <int NT>
+__global__ __launch_bounds__(NT) void k_merge(const int32_t *__restrict__ part_key,
                                               const int64_t *__restrict__ part_id, int slices,
-                                              int k, int n2, const uint32_t *__restrict__ lutmax,
+                                              int k, const uint32_t *__restrict__ lutmax,
                                               const float *__restrict__ qbmax, float pv_max,
                                               int M, int metric_ip, int32_t *res_key, int64_t *res_id,
                                               int64_t *out_ids, float *out_dists) {
-  __shared__ int mkey[kMaxSlices * kMaxK];
-  __shared__ long long mid[kMaxSlices * kMaxK];
-  const int q = blockIdx.x;
-  const int lane = threadIdx.x;
+  // Every partial list arrives in (key, id) order, padded with invalid entries.  The
+  // rank of a candidate in the merged order is its rank in its own list plus, for every
+  // other list, the number of entries that come before it there (a binary search);
+  // valid candidates are distinct, so their ranks are too.  Invalid entries of
+  // different lists get equal ranks and write the same padding.
+  extern __shared__ __align__(16) unsigned char merge_smem[];
   const int n_in = slices * k;
-  for (int i = lane; i < n2; i += 64) {
-    const bool ok = i < n_in;
-    mkey[i] = ok ? part_key[(size_t)q * n_in + i] : kKeyInvalid;
-    mid[i] = ok ? (long long)part_id[(size_t)q * n_in + i] : 0x7fffffffffffffffll;
+  long long *mid = reinterpret_cast<long long *>(merge_smem);          // [n_in]
+  int *mkey = reinterpret_cast<int *>(merge_smem + (size_t)n_in * 8);  // [n_in]
+  const int q = blockIdx.x;
+  const int tid = threadIdx.x;
+  for (int i = tid; i < n_in; i += NT) {
+    mkey[i] = part_key[(size_t)q * n_in + i];
+    mid[i] = (long long)part_id[(size_t)q * n_in + i];
   }
-  wave_sync();
-  if (slices > 1) bitonic_sort_lds<false>(mkey, mid, n2, lane, 64);
+  if (NT > 64) __syncthreads(); else wave_sync();
   const int e = lut_exponent(__uint_as_float(lutmax[q]), M, qbmax[q], pv_max);
-  for (int r = lane; r < k; r += 64) {
-    const int key = mkey[r];
+  const int step0 = 1 << (31 - __clz(k));  // largest power of two not above k
+  for (int i = tid; i < n_in; i += NT) {
+    const int key = mkey[i];
+    const long long id = mid[i];
+    const int own = i / k;
+    // One branch-free binary search per other list, four lists advanced together step
+    // by step so that their (independent) LDS reads overlap: pos[u] ends as the number
+    // of entries of that list that come before this candidate.
+    int rank = i - own * k;
+    for (int b0 = 0; b0 < slices; b0 += 4) {
+      int pos[4] = {0, 0, 0, 0};
+      for (int step = step0; step >= 1; step >>= 1) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const int b = b0 + u, j = pos[u] + step;
+          if (b < slices && b != own && j <= k) {
+            const int kb = mkey[b * k + j - 1];
+            bool less = kb < key;
+            if (kb == key) less = mid[b * k + j - 1] < id;
+            if (less) pos[u] = j;
+          }
+        }
+      }
+      rank += pos[0] + pos[1] + pos[2] + pos[3];
+    }
+    if (rank >= k) continue;
     const bool ok = key != kKeyInvalid;
     if (out_ids) {
-      out_ids[(size_t)q * k + r] = ok ? (int64_t)mid[r] : -1;
-      out_dists[(size_t)q * k + r] =
+      out_ids[(size_t)q * k + rank] = ok ? (int64_t)id : -1;
+      out_dists[(size_t)q * k + rank] =
           ok ? key_to_dist(key, e, metric_ip) : (metric_ip ? -INFINITY : INFINITY);
     } else {
-      res_key[(size_t)q * k + r] = key;
-      res_id[(size_t)q * k + r] = ok ? (int64_t)mid[r] : -1;
+      res_key[(size_t)q * k + rank] = key;
+      res_id[(size_t)q * k + rank] = ok ? (int64_t)id : -1;
     }
   }
 }
 
 hipError_t launch_merge(const Shape &sh, const BatchWs &W, int nq, int slices, int k,
                         int64_t *out_ids, float *out_dists, hipStream_t st) {
-  int n2 = 1;
-  while (n2 < slices * k) n2 <<= 1;
-  hipLaunchKernelGGL(k_merge, dim3(nq), dim3(64), 0, st, W.part_key, W.part_id, slices, k, n2,
-                     W.lutmax, W.qbmax, sh.scan_res() == 2 ? sh.pv_max : 0.0f, sh.M, sh.metric_ip, W.res_key, W.res_id, out_ids, out_dists);
+  if (slices < 1 || slices > kMaxSlices || k > kMaxK) return hipErrorInvalidValue;
+  const size_t lds = (size_t)slices * k * 12;  // at most 48 KB
+  const float pvm = sh.scan_res() == 2 ? sh.pv_max : 0.0f;
+  if (slices * k <= 256)
+    hipLaunchKernelGGL(k_merge<64>, dim3(nq), dim3(64), lds, st, W.part_key, W.part_id, slices, k,
+                       W.lutmax, W.qbmax, pvm, sh.M, sh.metric_ip, W.res_key, W.res_id, out_ids,
+                       out_dists);
+  else
+    hipLaunchKernelGGL(k_merge<1024>, dim3(nq), dim3(1024), lds, st, W.part_key, W.part_id, slices,
+                       k, W.lutmax, W.qbmax, pvm, sh.M, sh.metric_ip, W.res_key, W.res_id, out_ids,
+                       out_dists);
   return hipGetLastError();
 }
 

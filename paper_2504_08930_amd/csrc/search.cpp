@@ -19,7 +19,9 @@ static void emit_results(const ivf_index *ix, const HostCand *c, int k, int e, i
 }
 
 static int pick_slices(const ivf_index *ix, const BatchCtx &c, int64_t nq, int nprobe, int k) {
-  if (ix->tune_slices > 0) return ix->tune_slices;
+  // the workspace holds part_rows(max_nq) partial results of a launch
+  const int room = (int)std::min<int64_t>(kMaxSlices, part_rows(ix->desc.max_nq) / nq);
+  if (ix->tune_slices > 0) return std::min(ix->tune_slices, std::max(room, 1));
   // one block per query fills the chip's 256 compute units (each holding one or
   // two scan blocks) from that many queries up; below that, split - but not so
   // far that a block's wavefronts (8 or 16) are left with fewer than two tiles each
@@ -30,7 +32,7 @@ static int pick_slices(const ivf_index *ix, const BatchCtx &c, int64_t nq, int n
   const int64_t tiles = (int64_t)nprobe * c.list_tiles;  // estimate per query
   s = (int)std::min<int64_t>(s, std::max<int64_t>(1, tiles / (2 * waves)));
   if (s < 1) s = 1;
-  if (s > kMaxSlices) s = kMaxSlices;
+  if (s > room) s = room;
   return s;
 }
 

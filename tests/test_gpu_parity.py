@@ -121,7 +121,7 @@ def test_forced_probes_and_scan_slices(pkg, oracle, name):
     ref_i, ref_d = oracle.scan(ix.metric, ix.codebooks, ix.list_offsets, ix.codes, ix.ids, q,
                                probe, spec.k + 16)
     base = None
-    for slices in (0, 1, 3, 8):
+    for slices in (0, 1, 3, 8, 17, 32):
         _say(f"{name} slices={slices}")
         index.set_tuning(scan_slices=slices)
         ids, dist = index.search_batch_probes(q, probe, spec.k)
@@ -430,6 +430,56 @@ def test_more_lists_than_the_select_holds_in_registers(pkg, oracle):
     index.close()
 
 
+@pytest.mark.parametrize("residual", [False, True])
+def test_long_probe_lists(pkg, oracle, residual):
+    """More than 256 probes per query (the paper's own operating point is 2048, Section
+    5.1): the router then takes a block per query (cluster order from a bitmap over the
+    lists, or from a block-wide sort when residual codes need each probe's rank for its
+    bias), small batches are split over up to 32 scan blocks per query, and the merge
+    ranks their partial lists.  Oracle parity, independence of the resident set, and the
+    router's counters."""
+    import torch
+    from synthdata.workloads import METRIC_IP, WorkloadSpec
+    spec = WorkloadSpec("S3kL", 40_000, 32, 512, 3_000, 16, METRIC_IP, True,
+                        12, 600, 25, 1.0, 1.0, kmeans_iters=2)
+    ix = build_index(spec, device="cuda", by_residual=residual)
+    q, _ = make_queries(spec, mixture_centers(spec, torch.device("cuda")))
+    q = q.cpu().numpy()
+    qd = torch.from_numpy(q).cuda()
+    index = pkg.IvfIndex(ix, max_nq=16, max_nprobe=2048, max_k=128)
+    full = np.arange(ix.nlist, dtype=np.int32)
+    rng = np.random.default_rng(3)
+    half = np.sort(rng.choice(ix.nlist, ix.nlist // 2, replace=False)).astype(np.int32)
+    for nprobe, k in ((257, 10), (600, 25), (2048, 128)):
+        index.load_partition(full)
+        probe = index.coarse_probe_dev(qd, nprobe).cpu().numpy()
+        base = None
+        for slices in (0, 1, 32):
+            index.set_tuning(scan_slices=slices)
+            ids, dist = index.search_batch(q, nprobe, k)
+            if base is None:
+                base = (ids, dist)
+                st = ParityStats()
+                n_coarse, n_amb = _check_search(oracle, ix, q, nprobe, k, ids, dist, probe, stats=st)
+                _say(f"long lists residual={residual} nprobe={nprobe} k={k}: "
+                     f"coarse-ambiguous {n_coarse}; {st.summary()}")
+                assert n_coarse <= 1
+            assert np.array_equal(ids, base[0]) and np.array_equal(dist, base[1]), (nprobe, slices)
+        index.set_tuning(scan_slices=0)
+        index.load_partition(half)
+        index.hit_stats(reset=True)
+        ids, dist = index.search_batch(q, nprobe, k)
+        assert np.array_equal(ids, base[0]) and np.array_equal(dist, base[1]), nprobe
+        st = index.hit_stats(reset=True)
+        mask = np.zeros(ix.nlist, np.uint8)
+        mask[half] = 1
+        ref_hits, ref_rate = oracle.hit_stats(ix.nlist, probe, mask)
+        assert np.array_equal(st["per_cluster_hits"], ref_hits)
+        assert abs(st["mean_hit_rate"] - ref_rate.mean()) < 1e-9
+        assert abs(st["min_hit_rate"] - ref_rate.min()) < 1e-6
+    index.close()
+
+
 def test_coarse_probes_come_best_first(pkg, oracle):
     """The probe list is ordered best cluster first, at every size of the
     selection's candidate set (one stretch of candidates per thread, several
@@ -506,7 +556,7 @@ def test_identical_codes_tie_by_id_on_the_device(pkg, oracle):
     index = pkg.IvfIndex(ix2, max_nq=256, max_nprobe=ix.nlist, max_k=128)
     for resident in (np.arange(ix.nlist), big[:2], np.zeros(0)):
         index.load_partition(np.sort(resident).astype(np.int32))
-        for slices in (0, 1, 4):
+        for slices in (0, 1, 4, 32):
             index.set_tuning(scan_slices=slices)
             for k in (7, 64, 128):
                 got_i, got_d = index.search_batch_probes(q, probe, k)
