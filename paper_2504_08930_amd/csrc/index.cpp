@@ -106,6 +106,7 @@ static size_t plan_layout(const ivf_index_desc_t &d, int64_t resident_vectors, s
     w.q_exp = (int32_t *)take(nq * 4);
     w.queries = (float *)take(nq * D * 4);
     w.scores = (float *)take(nq * nl * 4);
+    w.sel_split = take(coarse_select_split_bytes());
     w.probe = (int32_t *)take(nq * np * 4);
     w.g_base = (int32_t *)take(nq * np * 4);
     w.g_len = (int32_t *)take(nq * np * 4);

@@ -17,6 +17,7 @@ constexpr int64_t part_rows(int64_t max_nq) {
 }
 constexpr int kMaxK = 128;
 constexpr int kMaxNprobe = 2048;
+constexpr int kSelSplitMaxNq = 128;  // largest batch the split coarse selection serves
 constexpr int kLutMaxParts = 512;   // per-query slots for partial table maxima
 constexpr int kSplitPadBytes = 16384;  // tail padding of the split-fp16 operand arrays
 constexpr int kWsSlots = 2;        // batches that may be in flight on different streams
@@ -49,6 +50,7 @@ struct BatchWs {
   int32_t *q_exp;          // [max_nq] power-of-two scale of each split row
   float *queries;          // [max_nq][d]
   float *scores;           // [max_nq][nlist]
+  void *sel_split;         // workspace of the split coarse selection
   int32_t *probe;          // [max_nq][max_nprobe]
   int32_t *g_base;         // [max_nq][max_nprobe] first tile of each resident probe
   int32_t *g_len;          // [max_nq][max_nprobe] list length
@@ -122,8 +124,15 @@ hipError_t launch_coarse_gemm(const Shape &sh, const void *q_parts, const int32_
                               const void *cent_parts, const int32_t *cent_exp,
                               const float *cent_norm, float *scores, hipStream_t st);
 
+// split_ws: coarse_select_split_bytes() of workspace (256-byte aligned), or NULL.  With it,
+// batches of up to kSelSplitMaxNq queries over more than 16384 lists are selected by
+// several blocks per query; the result is the same exact selection.  ordered != 0: best
+// first throughout; ordered == 0: the best cluster first, the others in any order
+// (selections of more than a thousand candidates are then not sorted).
 hipError_t launch_coarse_select(const Shape &sh, const float *scores, int nq, int nprobe,
-                                int probe_stride, int32_t *probe, hipStream_t st);
+                                int probe_stride, int32_t *probe, void *split_ws, int ordered,
+                                hipStream_t st);
+size_t coarse_select_split_bytes();
 
 // The coarse quantizer with its intermediates in the library's file-scope device array
 // (kStaticScratchBytes per device) instead of a workspace.  static_scratch_for_device

@@ -80,8 +80,20 @@ hipError_t launch_split_f16(const float *src, size_t rows, int d, void *dst, int
 // centroid tile in that XCD's L2.
 // ---------------------------------------------------------------------------
 static_assert(kSplitPadBytes >= 256 * 64, "padding covers one row tile of the last chunk");
-constexpr int kRowBytes = 80;  // 64 B of data per row and chunk, padded: conflict-free b128 reads
+// LDS image of a K = 16 chunk: 64 B per row (two groups x two parts x 16 B), unpadded.
+// The 16-byte unit u of row r sits at unit position u ^ swz(r), swz a 2-bit function of
+// the row chosen so that both access patterns are conflict-free whether the LDS serves
+// 8 lanes x 16 B per cycle over 32 banks or 16 lanes over 64: the fragment reads (32
+// consecutive rows, one unit each) and the stores of the staged chunk (four
+// consecutive units of consecutive rows).  A padded layout (80 B per row) makes the
+// reads conflict-free too, but every group of 8 or 16 storing lanes then hits one
+// 16-byte bank group twice.
+constexpr int kRowBytes = 64;
+__device__ __forceinline__ int lds_swz(int row) {
+  return (((row >> 1) ^ (row >> 3)) & 1) | (((row >> 2) & 1) << 1);
+}
 
+// <1,4,1,2> / <1,2,1,2>: 32 x 256 / 32 x 128 block, 4 / 2 waves of 32 x 64 (up to 64 queries);
 // <2,2,2,2>: 128 x 128 block, 4 waves (small batches: more blocks);
 // <4,4,2,2>: 256 x 256 block, 16 waves of 64 x 64 (half the L2 traffic per MFMA of the
 // small tile; 120 registers, so four waves per SIMD hide one another's LDS and
@@ -93,11 +105,16 @@ __global__ __launch_bounds__(WM *WN * 64) void k_coarse_gemm(
     const float *__restrict__ cnorm, int metric_ip, int row_tiles, int col_tiles,
     float *__restrict__ scores) {
   constexpr int BM = WM * TM * 32, BN = WN * TN * 32, NT = WM * WN * 64;
-  constexpr int LA = BM * 4 / NT, LB = BN * 4 / NT;  // 16-byte units per thread and chunk
-  static_assert(BM * 4 % NT == 0 && BN * 4 % NT == 0, "tile loads divide evenly");
+  // rows of the query operand staged per chunk: the tile's, or (a tile of 32 queries
+  // under 128 or 256 threads) as many as give every thread one unit to load; the
+  // extra rows are read like any rows beyond the matrix and never used
+  constexpr int BMA = BM * 4 >= NT ? BM : NT / 4;
+  constexpr int LA = BMA * 4 / NT, LB = BN * 4 / NT;  // 16-byte units per thread and chunk
+  static_assert(BMA * 4 % NT == 0 && BN * 4 % NT == 0, "tile loads divide evenly");
+  static_assert(BMA * 64 <= kSplitPadBytes, "staged rows beyond the matrix stay inside the padding");
   extern __shared__ __align__(16) unsigned char gsm[];
-  auto a_tile = [&](int buf) { return gsm + buf * ((BM + BN) * kRowBytes); };
-  auto b_tile = [&](int buf) { return gsm + buf * ((BM + BN) * kRowBytes) + BM * kRowBytes; };
+  auto a_tile = [&](int buf) { return gsm + buf * ((BMA + BN) * kRowBytes); };
+  auto b_tile = [&](int buf) { return gsm + buf * ((BMA + BN) * kRowBytes) + BMA * kRowBytes; };
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = tid >> 6;
@@ -137,14 +154,16 @@ __global__ __launch_bounds__(WM *WN * 64) void k_coarse_gemm(
   do {                                                                                       \
     _Pragma("unroll") for (int i = 0; i < LA; ++i) {                                         \
       const int f = tid + NT * i;                                                            \
-      *reinterpret_cast<uintx4 *>(a_tile(buf) + (f >> 2) * kRowBytes + (f & 3) * 16) = GA[i]; \
+      *reinterpret_cast<uintx4 *>(a_tile(buf) + (f >> 2) * kRowBytes + (((f & 3) ^ swz_st) << 4)) = GA[i]; \
     }                                                                                        \
     _Pragma("unroll") for (int i = 0; i < LB; ++i) {                                         \
       const int f = tid + NT * i;                                                            \
-      *reinterpret_cast<uintx4 *>(b_tile(buf) + (f >> 2) * kRowBytes + (f & 3) * 16) = GB[i]; \
+      *reinterpret_cast<uintx4 *>(b_tile(buf) + (f >> 2) * kRowBytes + (((f & 3) ^ swz_st) << 4)) = GB[i]; \
     }                                                                                        \
   } while (0)
 
+  // a thread's stored rows are (tid >> 2) + a multiple of 64: one swizzle for all of them
+  const int swz_st = lds_swz(tid >> 2);
   floatx16 acc[TM][TN];
 #pragma unroll
   for (int a = 0; a < TM; ++a)
@@ -159,6 +178,7 @@ __global__ __launch_bounds__(WM *WN * 64) void k_coarse_gemm(
   if (nk > 1) IVF_GLOAD(1, ga1, gb1);
   __syncthreads();
   const int li = lane & 31, kk = lane >> 5;
+  const int swz_ld = lds_swz(li);  // fragment rows are li + a multiple of 32
   // the MFMA work of one K chunk held in LDS buffer `buf`
   auto mma = [&](int buf) {
     // lane (li, kk) holds k = 8*kk .. 8*kk+7 of the chunk for row li of a tile
@@ -170,7 +190,7 @@ __global__ __launch_bounds__(WM *WN * 64) void k_coarse_gemm(
         a[t][p] = __builtin_bit_cast(
             halfx8,
             *reinterpret_cast<const uint4 *>(
-                a_tile(buf) + (wm * TM * 32 + t * 32 + li) * kRowBytes + (kk * 2 + p) * 16));
+                a_tile(buf) + (wm * TM * 32 + t * 32 + li) * kRowBytes + (((kk * 2 + p) ^ swz_ld) << 4)));
 #pragma unroll
     for (int t = 0; t < TN; ++t)
 #pragma unroll
@@ -178,7 +198,7 @@ __global__ __launch_bounds__(WM *WN * 64) void k_coarse_gemm(
         b[t][p] = __builtin_bit_cast(
             halfx8,
             *reinterpret_cast<const uint4 *>(
-                b_tile(buf) + (wn * TN * 32 + t * 32 + li) * kRowBytes + (kk * 2 + p) * 16));
+                b_tile(buf) + (wn * TN * 32 + t * 32 + li) * kRowBytes + (((kk * 2 + p) ^ swz_ld) << 4)));
     // small products first; consecutive MFMAs go to different accumulators
 #pragma unroll
     for (int mt = 0; mt < TM; ++mt)
@@ -248,8 +268,9 @@ template <int WM, int WN, int TM, int TN>
 static hipError_t launch_gemm_t(const Shape &sh, const void *q_parts, const int32_t *q_exp, int nq,
                                 const void *cent_parts, const int32_t *cent_exp,
                                 const float *cent_norm, float *scores, hipStream_t st) {
-  constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
-  const size_t lds = (size_t)2 * (BM + BN) * kRowBytes;
+  constexpr int BM = WM * TM * 32, BN = WN * TN * 32, NT = WM * WN * 64;
+  constexpr int BMA = BM * 4 >= NT ? BM : NT / 4;
+  const size_t lds = (size_t)2 * (BMA + BN) * kRowBytes;
   static std::atomic<bool> attr_done{false};  // setting it twice is harmless
   if (!attr_done.load(std::memory_order_acquire)) {
     hipError_t e =
@@ -270,6 +291,18 @@ static hipError_t launch_gemm_t(const Shape &sh, const void *q_parts, const int3
 hipError_t launch_coarse_gemm(const Shape &sh, const void *q_parts, const int32_t *q_exp, int nq,
                               const void *cent_parts, const int32_t *cent_exp,
                               const float *cent_norm, float *scores, hipStream_t st) {
+  // A handful of queries (the paper's batches run from a few to a few dozen): tiles
+  // of 32 queries, so that the matrix cores are not fed 256 rows of which 8 are real
+  // and the kernel is bound by reading the centroids once; 256 centroids wide when
+  // that still gives the chip enough blocks.
+  if (nq <= 64) {
+    const long long wide_blocks = (long long)((nq + 31) / 32) * ((sh.nlist + 255) / 256);
+    if (wide_blocks >= 192)
+      return launch_gemm_t<1, 4, 1, 2>(sh, q_parts, q_exp, nq, cent_parts, cent_exp, cent_norm,
+                                       scores, st);
+    return launch_gemm_t<1, 2, 1, 2>(sh, q_parts, q_exp, nq, cent_parts, cent_exp, cent_norm, scores,
+                                     st);
+  }
   // big tiles once they still give every CU a block
   const long long big_blocks = (long long)((nq + 255) / 256) * ((sh.nlist + 255) / 256);
   if (big_blocks >= 192)
@@ -297,6 +330,132 @@ __device__ __forceinline__ unsigned long long sel_key(float s, int metric_ip, in
   return ((unsigned long long)score_bits(s, metric_ip) << 32) | (unsigned)c;
 }
 
+// Exact order of `filled` collected candidates (64-bit keys in sel[0..cap), slots
+// beyond `filled` hold ~0; cap a power of two): the `keep` best go to out[], best
+// first, entries from there up to nprobe become -1.  Keys are distinct (the id is part
+// of them), so the number of keys that come before a candidate's is its rank.  Up to
+// NT candidates: every thread counts, for one candidate, one stretch of the others,
+// and the stretches' counts are added up in LDS (lanes of a wavefront compare against
+// the same key at a time, one LDS broadcast); more (nprobe in the thousands): counting
+// would cost filled^2 / NT comparisons per thread, so the block sorts them.
+// rank: NT words of LDS.  Called by every thread of the block.
+// ordered == 0 (the search path, which routes probes in cluster-id order anyway): a
+// large candidate set is not sorted; the keep-th smallest key is found by a radix
+// search over the keys' bytes and the keys up to it are written in no particular
+// order, except that the best cluster still comes first (the scan's visiting order
+// groups queries by it).
+template <int NT>
+__device__ __forceinline__ void sel_rank_emit(unsigned long long *sel, int filled, int cap, int keep,
+                                              int nprobe, int32_t *out, unsigned int *rank,
+                                              int ordered) {
+  const int tid = threadIdx.x;
+  int n2 = 64;
+  while (n2 < filled) n2 <<= 1;
+  __syncthreads();
+  if (n2 > NT && !ordered && filled > keep) {
+    __shared__ unsigned long long s_prefix2, s_mask2, s_best;
+    __shared__ unsigned int s_need2, s_slot;
+    unsigned int *hist = rank;  // 256 bins
+    if (tid == 0) {
+      s_prefix2 = 0ull;
+      s_mask2 = 0ull;
+      s_need2 = (unsigned)keep;
+      s_slot = 1u;
+      s_best = ~0ull;
+    }
+    for (int pass = 0; pass < 8; ++pass) {
+      const int shift = 56 - 8 * pass;
+      if (tid < 256) hist[tid] = 0u;
+      __syncthreads();
+      const unsigned long long prefix = s_prefix2, mask = s_mask2;
+      const unsigned need = s_need2;
+      for (int i = tid; i < filled; i += NT) {
+        const unsigned long long key = sel[i];
+        if ((key & mask) == prefix) atomicAdd(&hist[(unsigned)(key >> shift) & 255u], 1u);
+      }
+      __syncthreads();
+      if (tid < 64) {  // one wavefront finds the byte value that holds rank `need`
+        unsigned loc[4], tsum = 0;
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+          loc[b] = hist[tid * 4 + b];
+          tsum += loc[b];
+        }
+        unsigned incl = tsum;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+          const unsigned u = __shfl_up(incl, o, 64);
+          if (tid >= o) incl += u;
+        }
+        const unsigned before = incl - tsum;
+        if (before < need && need <= before + tsum) {
+          unsigned cum = before;
+          int b = 0;
+          for (; b < 3; ++b) {
+            if (cum + loc[b] >= need) break;
+            cum += loc[b];
+          }
+          s_need2 = need - cum;
+          s_prefix2 = prefix | ((unsigned long long)(tid * 4 + b) << shift);
+          s_mask2 = mask | (0xffull << shift);
+        }
+      }
+      __syncthreads();
+    }
+    const unsigned long long thr = s_prefix2;  // the keep-th smallest key itself
+    unsigned long long mine_best = ~0ull;
+    for (int i = tid; i < filled; i += NT) mine_best = min(mine_best, sel[i]);
+    atomicMin(&s_best, mine_best);
+    __syncthreads();
+    const unsigned long long best = s_best;
+    for (int i = tid; i < filled; i += NT) {
+      const unsigned long long key = sel[i];
+      if (key > thr) continue;
+      const unsigned slot = key == best ? 0u : atomicAdd(&s_slot, 1u);
+      out[slot] = (int32_t)(key & 0xffffffffull);
+    }
+    for (int p = keep + tid; p < nprobe; p += NT) out[p] = -1;
+    return;
+  }
+  if (n2 <= NT) {
+    if (tid < n2) rank[tid] = 0u;
+    __syncthreads();
+    const int i = tid & (n2 - 1), part = tid / n2, n_parts = NT / n2;
+    const int per = (filled + n_parts - 1) / n_parts;
+    if (i < filled) {
+      const unsigned long long mine = sel[i];
+      const int j1 = min(filled, (part + 1) * per);
+      unsigned cnt = 0;
+      for (int j = part * per; j < j1; ++j) cnt += sel[j] < mine ? 1u : 0u;
+      if (cnt) atomicAdd(&rank[i], cnt);
+    }
+    __syncthreads();
+    if (tid < filled) {
+      const unsigned r = rank[tid];
+      if (r < (unsigned)keep) out[r] = (int32_t)(sel[tid] & 0xffffffffull);
+    }
+  } else {
+    for (int size = 2; size <= cap; size <<= 1) {
+      for (int st = size >> 1; st > 0; st >>= 1) {
+        for (int i = tid; i < cap; i += NT) {
+          const int j = i ^ st;
+          if (j > i) {
+            const bool asc = (i & size) == 0;
+            const unsigned long long a = sel[i], b = sel[j];
+            if ((b < a) == asc) {
+              sel[i] = b;
+              sel[j] = a;
+            }
+          }
+        }
+        __syncthreads();
+      }
+    }
+    for (int r = tid; r < min(filled, keep); r += NT) out[r] = (int32_t)(sel[r] & 0xffffffffull);
+  }
+  for (int p = min(filled, keep) + tid; p < nprobe; p += NT) out[p] = -1;
+}
+
 // PER > 0: the query's row of scores is read once and held in registers (PER per
 // thread, nlist <= PER * kSelThreads); PER == 0: every pass re-reads the row.
 //
@@ -312,7 +471,11 @@ __global__ __launch_bounds__(kSelThreads) void k_coarse_select(const float *__re
                                                                int nlist, int metric_ip, int keep,
                                                                int nprobe, int stride, int cap,
                                                                float stash_z,
-                                                               int32_t *__restrict__ probe) {
+                                                               int32_t *__restrict__ probe,
+                                                               const int32_t *__restrict__ only_flagged,
+                                                               int ordered) {
+  // only_flagged: the split selection below has served every query but those it flagged
+  if (only_flagged && !only_flagged[blockIdx.x]) return;
   constexpr int kSelBinsPerThread = kSelBins / kSelThreads;
   __shared__ unsigned int hist[kSelBins];
   __shared__ unsigned int wsum[kSelThreads / 64];
@@ -607,64 +770,264 @@ __global__ __launch_bounds__(kSelThreads) void k_coarse_select(const float *__re
     __syncthreads();
   }
   __syncthreads();
-  // ---- exact order of the collected candidates: rank by counting ----
-  // Keys are distinct (the id is part of them), so the number of keys that come
-  // before a candidate's is its rank.  Up to kSelThreads candidates: every
-  // thread counts, for one candidate, one stretch of the others, and the
-  // stretches' counts are added up in LDS (lanes of a wavefront compare against
-  // the same key at a time, one LDS broadcast); more: the block sorts them.
-  const int filled = (int)min(s_count, (unsigned)cap);
-  int n2 = 64;
-  while (n2 < filled) n2 <<= 1;
-  if (n2 <= kSelThreads) {
-    unsigned int *rank = hist;
-    if (tid < n2) rank[tid] = 0u;
-    __syncthreads();
-    const int i = tid & (n2 - 1), part = tid / n2, n_parts = kSelThreads / n2;
-    const int per = (filled + n_parts - 1) / n_parts;
-    if (i < filled) {
-      const unsigned long long mine = sel[i];
-      const int j1 = min(filled, (part + 1) * per);
-      unsigned cnt = 0;
-      for (int j = part * per; j < j1; ++j) cnt += sel[j] < mine ? 1u : 0u;
-      if (cnt) atomicAdd(&rank[i], cnt);
-    }
-    __syncthreads();
-    if (tid < filled) {
-      const unsigned r = rank[tid];
-      if (r < (unsigned)keep) out[r] = (int32_t)(sel[tid] & 0xffffffffull);
-    }
-  } else {
-    // more candidates than threads (nprobe in the thousands): counting would cost
-    // filled^2 / threads comparisons per thread, so sort instead.  Slots beyond
-    // `filled` hold ~0, the largest key; cap is a power of two.
-    for (int size = 2; size <= cap; size <<= 1) {
-      for (int st = size >> 1; st > 0; st >>= 1) {
-        for (int i = tid; i < cap; i += kSelThreads) {
-          const int j = i ^ st;
-          if (j > i) {
-            const bool asc = (i & size) == 0;
-            const unsigned long long a = sel[i], b = sel[j];
-            if ((b < a) == asc) {
-              sel[i] = b;
-              sel[j] = a;
-            }
-          }
-        }
-        __syncthreads();
-      }
-    }
-    for (int r = tid; r < min(filled, keep); r += kSelThreads)
-      out[r] = (int32_t)(sel[r] & 0xffffffffull);
+  sel_rank_emit<kSelThreads>(sel, (int)min(s_count, (unsigned)cap), cap, keep, nprobe, out, hist,
+                             ordered);
+}
+
+// ---------------------------------------------------------------------------
+// The same selection for a handful of queries over many clusters (the paper's
+// batches of a few to a few dozen queries against tens of thousands of lists): one
+// block per query would leave the chip idle and spend its time on the latency of
+// three passes over a long row, so the row is cut into kSelParts parts with a block
+// each, and the passes become small kernels: range of each part; histogram of each
+// part over the query's common range, added into one histogram per query; the
+// clusters up to the bin that holds rank `keep` appended to one candidate list per
+// query; exact ranking of the candidates.  Everything that made the one-block fast
+// path give up (candidates that do not fit, a degenerate range) flags the query,
+// and the one-block kernel then runs for the flagged queries only.  The result is
+// the exact selection either way.
+// Workspace per query: SelSplitWs below.
+// ---------------------------------------------------------------------------
+constexpr int kSelParts = 32;
+constexpr int kSelPartThreads = 256;
+constexpr int kSelPartPer = 8;  // scores per thread: parts of up to 2048 clusters
+constexpr int kSelSplitCap = 4096;
+
+struct SelSplitWs {
+  float minmax[kSelParts][2];
+  unsigned int hist[kSelBins];
+  unsigned int count;   // candidates appended
+  int flag;             // 1: leave the query to the one-block kernel
+  unsigned int pad[62];
+  unsigned long long cand[kSelSplitCap];
+};
+static_assert(sizeof(SelSplitWs) % 256 == 0, "workspace entries stay aligned");
+
+// one entry per query, then one flag word per query
+static size_t coarse_select_split_entries_bytes() { return sizeof(SelSplitWs) * (size_t)kSelSplitMaxNq; }
+size_t coarse_select_split_bytes() {
+  return coarse_select_split_entries_bytes() + (size_t)kSelSplitMaxNq * sizeof(int32_t);
+}
+
+__device__ __forceinline__ void sel_part_load(const float *__restrict__ row, int nlist, int part_len,
+                                              int metric_ip, float (&v)[kSelPartPer],
+                                              int (&c)[kSelPartPer]) {
+  const int base = blockIdx.x * part_len;
+#pragma unroll
+  for (int i = 0; i < kSelPartPer; ++i) {
+    const int o = threadIdx.x + i * kSelPartThreads;
+    c[i] = (o < part_len && base + o < nlist) ? base + o : -1;
+    const float s0 = c[i] >= 0 ? row[c[i]] : 0.0f;
+    v[i] = metric_ip ? -s0 : s0;  // smaller is better
   }
-  for (int p = min(filled, keep) + tid; p < nprobe; p += kSelThreads) out[p] = -1;
+}
+
+__global__ __launch_bounds__(kSelPartThreads) void k_sel_part_range(
+    const float *__restrict__ scores, int nlist, int part_len, int metric_ip, SelSplitWs *ws) {
+  __shared__ float wmin[kSelPartThreads / 64], wmax[kSelPartThreads / 64];
+  const int q = blockIdx.y, tid = threadIdx.x;
+  SelSplitWs &W = ws[q];
+  float v[kSelPartPer];
+  int c[kSelPartPer];
+  sel_part_load(scores + (size_t)q * nlist, nlist, part_len, metric_ip, v, c);
+  float vmin = INFINITY, vmax = -INFINITY;
+#pragma unroll
+  for (int i = 0; i < kSelPartPer; ++i)
+    if (c[i] >= 0) {
+      vmin = fminf(vmin, v[i]);
+      vmax = fmaxf(vmax, v[i]);
+    }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    vmin = fminf(vmin, __shfl_xor(vmin, o, 64));
+    vmax = fmaxf(vmax, __shfl_xor(vmax, o, 64));
+  }
+  if ((tid & 63) == 0) {
+    wmin[tid >> 6] = vmin;
+    wmax[tid >> 6] = vmax;
+  }
+  __syncthreads();
+  if (tid == 0) {
+    for (int w = 1; w < kSelPartThreads / 64; ++w) {
+      vmin = fminf(vmin, wmin[w]);
+      vmax = fmaxf(vmax, wmax[w]);
+    }
+    W.minmax[blockIdx.x][0] = vmin;
+    W.minmax[blockIdx.x][1] = vmax;
+  }
+  // the query's histogram and counters start from zero (this kernel precedes their use)
+  if (blockIdx.x == 0) {
+    for (int b = tid; b < kSelBins; b += kSelPartThreads) W.hist[b] = 0u;
+    if (tid == 0) {
+      W.count = 0u;
+      W.flag = 0;
+    }
+  }
+}
+
+// common range of a query's parts -> (vmin, scale); false if the range cannot be binned
+__device__ __forceinline__ bool sel_part_scale(const SelSplitWs &W, int parts, float *vmin_out,
+                                               float *scale_out) {
+  float vmin = INFINITY, vmax = -INFINITY;
+  for (int p = 0; p < parts; ++p) {
+    vmin = fminf(vmin, W.minmax[p][0]);
+    vmax = fmaxf(vmax, W.minmax[p][1]);
+  }
+  const float scale = (float)(kSelBins - 1) / (vmax - vmin);
+  *vmin_out = vmin;
+  *scale_out = scale;
+  return scale > 0.0f && scale < INFINITY;
+}
+
+__device__ __forceinline__ unsigned sel_part_bin(float v, float vmin, float scale) {
+  const unsigned b = (unsigned)(int)fmaxf((v - vmin) * scale, 0.0f);
+  return b < (unsigned)kSelBins ? b : (unsigned)(kSelBins - 1);
+}
+
+__global__ __launch_bounds__(kSelPartThreads) void k_sel_part_hist(
+    const float *__restrict__ scores, int nlist, int part_len, int metric_ip, SelSplitWs *ws) {
+  __shared__ unsigned int hist[kSelBins];
+  const int q = blockIdx.y, tid = threadIdx.x;
+  SelSplitWs &W = ws[q];
+  float vmin, scale;
+  if (!sel_part_scale(W, gridDim.x, &vmin, &scale)) return;  // uniform over the query's blocks
+  for (int b = tid; b < kSelBins; b += kSelPartThreads) hist[b] = 0u;
+  float v[kSelPartPer];
+  int c[kSelPartPer];
+  sel_part_load(scores + (size_t)q * nlist, nlist, part_len, metric_ip, v, c);
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < kSelPartPer; ++i)
+    if (c[i] >= 0) atomicAdd(&hist[sel_part_bin(v[i], vmin, scale)], 1u);
+  __syncthreads();
+  for (int b = tid; b < kSelBins; b += kSelPartThreads) {
+    const unsigned n = hist[b];
+    if (n) atomicAdd(&W.hist[b], n);
+  }
+}
+
+__global__ __launch_bounds__(kSelPartThreads) void k_sel_part_collect(
+    const float *__restrict__ scores, int nlist, int part_len, int metric_ip, int keep, int cap,
+    SelSplitWs *ws) {
+  constexpr int kPerThread = kSelBins / kSelPartThreads;
+  __shared__ unsigned int wsum[kSelPartThreads / 64];
+  __shared__ unsigned int s_bin, s_total, s_n, s_base;
+  const int q = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  SelSplitWs &W = ws[q];
+  float vmin, scale;
+  if (!sel_part_scale(W, gridDim.x, &vmin, &scale)) {
+    if (blockIdx.x == 0 && tid == 0) W.flag = 1;
+    return;
+  }
+  if (tid == 0) {
+    s_bin = 0xffffffffu;
+    s_total = 0u;
+    s_n = 0u;
+  }
+  // the bin that holds rank `keep` (every block of the query finds the same one)
+  unsigned loc[kPerThread], tsum = 0;
+#pragma unroll
+  for (int b = 0; b < kPerThread; ++b) {
+    loc[b] = W.hist[tid * kPerThread + b];
+    tsum += loc[b];
+  }
+  unsigned incl = tsum;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const unsigned u = __shfl_up(incl, o, 64);
+    if (lane >= o) incl += u;
+  }
+  if (lane == 63) wsum[wave] = incl;
+  __syncthreads();
+  unsigned before = incl - tsum;
+  for (int w2 = 0; w2 < wave; ++w2) before += wsum[w2];
+  if (before < (unsigned)keep && (unsigned)keep <= before + tsum) {
+    unsigned cum = before;
+    int b = 0;
+    for (; b < kPerThread - 1; ++b) {
+      if (cum + loc[b] >= (unsigned)keep) break;
+      cum += loc[b];
+    }
+    s_bin = (unsigned)(tid * kPerThread + b);
+    s_total = cum + loc[b];
+  }
+  __syncthreads();
+  const unsigned tbin = s_bin, total = s_total;
+  if (total < (unsigned)keep || total > (unsigned)cap) {  // uniform over the query's blocks
+    if (blockIdx.x == 0 && tid == 0) W.flag = 1;
+    return;
+  }
+  float v[kSelPartPer];
+  int c[kSelPartPer];
+  sel_part_load(scores + (size_t)q * nlist, nlist, part_len, metric_ip, v, c);
+  bool take[kSelPartPer];
+  unsigned slot[kSelPartPer];
+#pragma unroll
+  for (int i = 0; i < kSelPartPer; ++i) {
+    take[i] = c[i] >= 0 && sel_part_bin(v[i], vmin, scale) <= tbin;
+    slot[i] = take[i] ? atomicAdd(&s_n, 1u) : 0u;
+  }
+  __syncthreads();
+  if (tid == 0) s_base = s_n ? atomicAdd(&W.count, s_n) : 0u;
+  __syncthreads();
+  const unsigned base = s_base;
+#pragma unroll
+  for (int i = 0; i < kSelPartPer; ++i)
+    if (take[i]) {
+      const float s0 = metric_ip ? -v[i] : v[i];
+      W.cand[base + slot[i]] = sel_key(s0, metric_ip, c[i]);  // base + slot < total <= cap
+    }
+}
+
+__global__ __launch_bounds__(1024) void k_sel_part_rank(SelSplitWs *ws, int keep, int nprobe,
+                                                        int stride, int cap, int ordered,
+                                                        int32_t *__restrict__ probe,
+                                                        int32_t *__restrict__ flags) {
+  extern __shared__ unsigned long long sel[];  // cap entries
+  __shared__ unsigned int rank[1024];
+  const int q = blockIdx.x, tid = threadIdx.x;
+  SelSplitWs &W = ws[q];
+  const int flag = W.flag;  // uniform
+  if (tid == 0) flags[q] = flag;
+  if (flag) return;
+  const int filled = (int)min(W.count, (unsigned)cap);
+  for (int i = tid; i < cap; i += 1024) sel[i] = i < filled ? W.cand[i] : ~0ull;
+  sel_rank_emit<1024>(sel, filled, cap, keep, nprobe, probe + (size_t)q * stride, rank, ordered);
 }
 
 hipError_t launch_coarse_select(const Shape &sh, const float *scores, int nq, int nprobe,
-                                int probe_stride, int32_t *probe, hipStream_t st) {
+                                int probe_stride, int32_t *probe, void *split_ws, int ordered,
+                                hipStream_t st) {
   const int keep = nprobe < sh.nlist ? nprobe : sh.nlist;
   int cap = 128;  // LDS slots for collected candidates: a power of two >= 2 * keep
   while (cap < 2 * keep) cap <<= 1;
+  const int32_t *only_flagged = nullptr;
+  // few queries, long rows, more probes than the one-block kernel's side buffer of low-bin
+  // clusters serves (it then reads the row three times): the split selection first, the
+  // one-block kernel for what it flags
+  if (split_ws && nq <= kSelSplitMaxNq && sh.nlist > 16 * 1024 && keep < sh.nlist && keep > 533 &&
+      cap <= kSelSplitCap) {
+    int parts = kSelParts;
+    int part_len = (sh.nlist + parts - 1) / parts;
+    if (part_len > kSelPartThreads * kSelPartPer) {  // more than 65536 lists: more parts would be
+      part_len = 0;                                  // needed than the workspace holds
+    }
+    if (part_len > 0) {
+      SelSplitWs *ws = static_cast<SelSplitWs *>(split_ws);
+      const dim3 grid(parts, nq);
+      hipLaunchKernelGGL(k_sel_part_range, grid, dim3(kSelPartThreads), 0, st, scores, sh.nlist,
+                         part_len, sh.metric_ip, ws);
+      hipLaunchKernelGGL(k_sel_part_hist, grid, dim3(kSelPartThreads), 0, st, scores, sh.nlist,
+                         part_len, sh.metric_ip, ws);
+      hipLaunchKernelGGL(k_sel_part_collect, grid, dim3(kSelPartThreads), 0, st, scores, sh.nlist,
+                         part_len, sh.metric_ip, keep, cap, ws);
+      int32_t *flag_arr = reinterpret_cast<int32_t *>(reinterpret_cast<unsigned char *>(split_ws) +
+                                                      coarse_select_split_entries_bytes());
+      hipLaunchKernelGGL(k_sel_part_rank, dim3(nq), dim3(1024), (size_t)cap * 8, st, ws, keep,
+                         nprobe, probe_stride, cap, ordered, probe, flag_arr);
+      only_flagged = flag_arr;
+    }
+  }
   // PER == 0 only: how far from the mean the stash reaches.  For a bell-shaped row
   // the stash should catch about 2.4 * keep clusters (never more than 800 of its
   // 1024 slots); P(z < -stash_z) = that share of the row.  Solved by bisection
@@ -682,7 +1045,8 @@ hipError_t launch_coarse_select(const Shape &sh, const float *scores, int nq, in
 #define IVF_SEL_LAUNCH(PER, THREADS)                                                          \
   hipLaunchKernelGGL((k_coarse_select<PER, THREADS>), dim3(nq), dim3(THREADS),                   \
                      (size_t)cap * 8 + (PER == 0 ? 1024 * 8 : 0),                                \
-                     st, scores, sh.nlist, sh.metric_ip, keep, nprobe, probe_stride, cap, stash_z, probe)
+                     st, scores, sh.nlist, sh.metric_ip, keep, nprobe, probe_stride, cap, stash_z, probe, \
+                     only_flagged, ordered)
   // the row of scores in registers (4 or 16 per thread) up to 16384 clusters, re-read above
   if (sh.nlist <= 4 * 1024) IVF_SEL_LAUNCH(4, 1024);
   else if (sh.nlist <= 16 * 1024) IVF_SEL_LAUNCH(16, 1024);
@@ -748,7 +1112,7 @@ hipError_t launch_coarse_probe_static(const Shape &sh, const float *queries, int
   if (e != hipSuccess) return e;
   e = launch_coarse_gemm(sh, q_parts, q_exp, nq, cent_parts, cent_exp, cent_norm, scores, st);
   if (e != hipSuccess) return e;
-  return launch_coarse_select(sh, scores, nq, nprobe, nprobe, out_probe, st);
+  return launch_coarse_select(sh, scores, nq, nprobe, nprobe, out_probe, nullptr, 1, st);
 }
 
 }  // namespace ivf

@@ -22,18 +22,34 @@ static int pick_slices(const ivf_index *ix, const BatchCtx &c, int64_t nq, int n
   // the workspace holds part_rows(max_nq) partial results of a launch
   const int room = (int)std::min<int64_t>(kMaxSlices, part_rows(ix->desc.max_nq) / nq);
   if (ix->tune_slices > 0) return std::min(ix->tune_slices, std::max(room, 1));
-  // one block per query fills the chip's 256 compute units (each holding one or
-  // two scan blocks) from that many queries up; below that, split - but not so
-  // far that a block's wavefronts (8 or 16) are left with fewer than two tiles each
+  // One block per query fills the chip's 256 compute units (each holding one or two
+  // scan blocks) from that many queries up.  Smaller batches are split; the number of
+  // blocks per query is the one a small cost model likes best (in units of one tile's
+  // streaming time): a launch of N blocks takes about r rounds of the chip, r between
+  // N / fill and its ceiling (blocks are handed out as units come free, and a part-full
+  // last round runs faster than a full one), each round streams a block's tiles, and
+  // every block costs a fixed overhead on top (it stages the query's table again and
+  // ends with its own selection: about 8 us, forty tiles' worth; twice that for long
+  // result lists).  Never so many that a block's wavefronts get fewer than two tiles each.
   const int per_cu = scan_blocks_per_cu(ix->sh.M, k);
-  const int64_t fill = 256 * (int64_t)per_cu;
-  int s = (int)((fill + nq - 1) / nq);
+  const double fill = 256.0 * per_cu;
+  if ((double)nq > 1.25 * fill) return 1;
   const int waves = per_cu == 2 ? 8 : 16;
-  const int64_t tiles = (int64_t)nprobe * c.list_tiles;  // estimate per query
-  s = (int)std::min<int64_t>(s, std::max<int64_t>(1, tiles / (2 * waves)));
-  if (s < 1) s = 1;
-  if (s > room) s = room;
-  return s;
+  const double tiles = (double)nprobe * c.list_tiles;  // estimate per query
+  const double overhead = k <= 48 ? 40.0 : 80.0;
+  const int s_max = (int)std::min<double>(room, std::max(1.0, tiles / (2 * waves)));
+  int best = 1;
+  double best_cost = 0.0;
+  for (int s = 1; s <= s_max; ++s) {
+    const double r = (double)nq * s / fill;
+    const double rounds = r <= 1.0 ? 1.0 : 0.5 * (r + ceil(r));
+    const double cost = rounds * (tiles / s) + ceil(r) * overhead;
+    if (s == 1 || cost < best_cost) {
+      best = s;
+      best_cost = cost;
+    }
+  }
+  return best;
 }
 
 // Search on a device-less index: every probe is scanned on the CPU.
@@ -241,7 +257,7 @@ int enqueue_gpu(ivf_index *ix, const SearchArgs &a, const BatchCtx &c, bool fina
     G_TRY(launch_coarse_gemm(sh, W.q_parts, W.q_exp, nq, L.cent_parts, L.cent_exp, L.cent_norm,
                              W.scores, st));
     G_TRY(mark(IVF_STAGE_COARSE_SELECT));
-    G_TRY(launch_coarse_select(sh, W.scores, nq, np, np, W.probe, st));
+    G_TRY(launch_coarse_select(sh, W.scores, nq, np, np, W.probe, W.sel_split, /*ordered=*/0, st));
   }
   // ---- routing ----
   G_TRY(mark(IVF_STAGE_ROUTE));
@@ -524,7 +540,8 @@ extern "C" int ivf_coarse_probe_dev(ivf_index_t *ix, const float *queries, int64
   HIP_TRY(launch_coarse_gemm(ix->sh, W.q_parts, W.q_exp, (int)nq, ix->L.cent_parts, ix->L.cent_exp,
                              ix->L.cent_norm,
                              W.scores, st));
-  HIP_TRY(launch_coarse_select(ix->sh, W.scores, (int)nq, nprobe, nprobe, out_probe, st));
+  HIP_TRY(launch_coarse_select(ix->sh, W.scores, (int)nq, nprobe, nprobe, out_probe, W.sel_split,
+                               /*ordered=*/1, st));
   return IVF_OK;
 }
 
