@@ -8,12 +8,13 @@
 namespace ivf {
 
 constexpr int kTileVecs = 64;      // vectors per code tile (one wavefront)
-constexpr int kMaxSlices = 32;     // scan blocks per query, upper bound
+constexpr int kMaxSlices = 128;    // scan blocks per query, upper bound (slices * k <= kMaxMergeCand)
+constexpr int kMaxMergeCand = 4096;  // candidates the per-query merge holds in LDS
 // Partial-result rows (one per scan block of a sliced query) the workspace holds:
 // room for eight slices of every query of a full batch, and for kMaxSlices slices of
 // the small batches that need them to fill the chip.
 constexpr int64_t part_rows(int64_t max_nq) {
-  return max_nq * 8 > 64 * (int64_t)kMaxSlices ? max_nq * 8 : 64 * (int64_t)kMaxSlices;
+  return max_nq * 8 > 16 * (int64_t)kMaxSlices ? max_nq * 8 : 16 * (int64_t)kMaxSlices;
 }
 constexpr int kMaxK = 128;
 constexpr int kMaxNprobe = 2048;

@@ -1544,8 +1544,11 @@ hipError_t launch_scan(const Shape &sh, const DevLayout &L, const BatchWs &W, in
 
 // ---------------------------------------------------------------------------
 // Per-query merge of the scan blocks' partial lists; emits the GPU result.
-// One block per query: a wavefront for up to 256 candidates (slices * k), sixteen
-// wavefronts above (a query of a small batch may be split over kMaxSlices blocks).
+// One block per query.  The k-th smallest key of the slices * k candidates is found
+// by a radix search over the keys' bytes (four passes of a 256-bin histogram in LDS),
+// the few candidates at or below it are ranked exactly by (key, id) by counting, and
+// ranks below k are written: the cost does not grow with the number of slices a
+// small batch was split into.
 // ---------------------------------------------------------------------------
 template <int NT>
 __global__ __launch_bounds__(NT) void k_merge(const int32_t *__restrict__ part_key,
@@ -1554,49 +1557,72 @@ __global__ __launch_bounds__(NT) void k_merge(const int32_t *__restrict__ part_k
                                               const float *__restrict__ qbmax, float pv_max,
                                               int M, int metric_ip, int32_t *res_key, int64_t *res_id,
                                               int64_t *out_ids, float *out_dists) {
-  // Every partial list arrives in (key, id) order, padded with invalid entries.  The
-  // rank of a candidate in the merged order is its rank in its own list plus, for every
-  // other list, the number of entries that come before it there (a binary search);
-  // valid candidates are distinct, so their ranks are too.  Invalid entries of
-  // different lists get equal ranks and write the same padding.
   extern __shared__ __align__(16) unsigned char merge_smem[];
   const int n_in = slices * k;
   long long *mid = reinterpret_cast<long long *>(merge_smem);          // [n_in]
   int *mkey = reinterpret_cast<int *>(merge_smem + (size_t)n_in * 8);  // [n_in]
+  int *fin = mkey + n_in;                                              // [n_in] finalists' indices
+  __shared__ unsigned int hist[256];
+  __shared__ unsigned int s_prefix, s_mask, s_need, s_nf;
   const int q = blockIdx.x;
   const int tid = threadIdx.x;
   for (int i = tid; i < n_in; i += NT) {
     mkey[i] = part_key[(size_t)q * n_in + i];
     mid[i] = (long long)part_id[(size_t)q * n_in + i];
   }
-  if (NT > 64) __syncthreads(); else wave_sync();
-  const int e = lut_exponent(__uint_as_float(lutmax[q]), M, qbmax[q], pv_max);
-  const int step0 = 1 << (31 - __clz(k));  // largest power of two not above k
+  if (tid == 0) {
+    s_prefix = 0u;
+    s_mask = 0u;
+    s_need = (unsigned)k;  // n_in >= k
+    s_nf = 0u;
+  }
+  for (int pass = 0; pass < 4; ++pass) {
+    const int shift = 24 - 8 * pass;
+    for (int b = tid; b < 256; b += NT) hist[b] = 0u;
+    __syncthreads();
+    const unsigned prefix = s_prefix, mask = s_mask, need = s_need;
+    for (int i = tid; i < n_in; i += NT) {
+      const unsigned u = (unsigned)mkey[i] ^ 0x80000000u;  // order-preserving unsigned form
+      if ((u & mask) == prefix) atomicAdd(&hist[(u >> shift) & 255u], 1u);
+    }
+    __syncthreads();
+    if (tid < 64) {  // one wavefront finds the byte value that holds rank `need`
+      unsigned loc[4], tsum = 0;
+#pragma unroll
+      for (int b = 0; b < 4; ++b) {
+        loc[b] = hist[tid * 4 + b];
+        tsum += loc[b];
+      }
+      unsigned incl = tsum;
+#pragma unroll
+      for (int o = 1; o < 64; o <<= 1) {
+        const unsigned u = __shfl_up(incl, o, 64);
+        if (tid >= o) incl += u;
+      }
+      const unsigned before = incl - tsum;
+      if (before < need && need <= before + tsum) {
+        unsigned cum = before;
+        int b = 0;
+        for (; b < 3; ++b) {
+          if (cum + loc[b] >= need) break;
+          cum += loc[b];
+        }
+        s_need = need - cum;
+        s_prefix = prefix | ((unsigned)(tid * 4 + b) << shift);
+        s_mask = mask | (0xffu << shift);
+      }
+    }
+    __syncthreads();
+  }
+  const int kth = (int)(s_prefix ^ 0x80000000u);  // the k-th smallest key
   for (int i = tid; i < n_in; i += NT) {
     const int key = mkey[i];
-    const long long id = mid[i];
-    const int own = i / k;
-    // One branch-free binary search per other list, four lists advanced together step
-    // by step so that their (independent) LDS reads overlap: pos[u] ends as the number
-    // of entries of that list that come before this candidate.
-    int rank = i - own * k;
-    for (int b0 = 0; b0 < slices; b0 += 4) {
-      int pos[4] = {0, 0, 0, 0};
-      for (int step = step0; step >= 1; step >>= 1) {
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-          const int b = b0 + u, j = pos[u] + step;
-          if (b < slices && b != own && j <= k) {
-            const int kb = mkey[b * k + j - 1];
-            bool less = kb < key;
-            if (kb == key) less = mid[b * k + j - 1] < id;
-            if (less) pos[u] = j;
-          }
-        }
-      }
-      rank += pos[0] + pos[1] + pos[2] + pos[3];
-    }
-    if (rank >= k) continue;
+    if (key <= kth && key != kKeyInvalid) fin[atomicAdd(&s_nf, 1u)] = i;
+  }
+  __syncthreads();
+  const int nf = (int)s_nf;  // k or a few more (ties on the k-th key), fewer if fewer candidates exist
+  const int e = lut_exponent(__uint_as_float(lutmax[q]), M, qbmax[q], pv_max);
+  auto emit = [&](int rank, int key, long long id) {
     const bool ok = key != kKeyInvalid;
     if (out_ids) {
       out_ids[(size_t)q * k + rank] = ok ? (int64_t)id : -1;
@@ -1606,22 +1632,43 @@ __global__ __launch_bounds__(NT) void k_merge(const int32_t *__restrict__ part_k
       res_key[(size_t)q * k + rank] = key;
       res_id[(size_t)q * k + rank] = ok ? (int64_t)id : -1;
     }
+  };
+  for (int f = tid; f < nf; f += NT) {
+    const int i = fin[f];
+    const int key = mkey[i];
+    const long long id = mid[i];
+    int rank = 0;
+    for (int g = 0; g < nf; ++g) {
+      const int j = fin[g];
+      rank += cand_less(mkey[j], mid[j], key, id) ? 1 : 0;
+    }
+    if (rank < k) emit(rank, key, id);
   }
+  for (int r = nf + tid; r < k; r += NT) emit(r, kKeyInvalid, -1);
 }
 
 hipError_t launch_merge(const Shape &sh, const BatchWs &W, int nq, int slices, int k,
                         int64_t *out_ids, float *out_dists, hipStream_t st) {
-  if (slices < 1 || slices > kMaxSlices || k > kMaxK) return hipErrorInvalidValue;
-  const size_t lds = (size_t)slices * k * 12;  // at most 48 KB
+  if (slices < 1 || slices > kMaxSlices || k > kMaxK || slices * k > kMaxMergeCand)
+    return hipErrorInvalidValue;
+  const size_t lds = (size_t)slices * k * 16;  // at most 64 KB
   const float pvm = sh.scan_res() == 2 ? sh.pv_max : 0.0f;
-  if (slices * k <= 256)
-    hipLaunchKernelGGL(k_merge<64>, dim3(nq), dim3(64), lds, st, W.part_key, W.part_id, slices, k,
+  if (slices * k <= 1024) {
+    hipLaunchKernelGGL(k_merge<256>, dim3(nq), dim3(256), lds, st, W.part_key, W.part_id, slices, k,
                        W.lutmax, W.qbmax, pvm, sh.M, sh.metric_ip, W.res_key, W.res_id, out_ids,
                        out_dists);
-  else
+  } else {
+    static std::atomic<bool> attr_done{false};  // setting it twice is harmless
+    if (!attr_done.load(std::memory_order_acquire)) {
+      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_merge<1024>),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, 65536);
+      if (e != hipSuccess) return e;
+      attr_done.store(true, std::memory_order_release);
+    }
     hipLaunchKernelGGL(k_merge<1024>, dim3(nq), dim3(1024), lds, st, W.part_key, W.part_id, slices,
                        k, W.lutmax, W.qbmax, pvm, sh.M, sh.metric_ip, W.res_key, W.res_id, out_ids,
                        out_dists);
+  }
   return hipGetLastError();
 }
 

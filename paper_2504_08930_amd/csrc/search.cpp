@@ -20,7 +20,8 @@ static void emit_results(const ivf_index *ix, const HostCand *c, int k, int e, i
 
 static int pick_slices(const ivf_index *ix, const BatchCtx &c, int64_t nq, int nprobe, int k) {
   // the workspace holds part_rows(max_nq) partial results of a launch
-  const int room = (int)std::min<int64_t>(kMaxSlices, part_rows(ix->desc.max_nq) / nq);
+  const int room = (int)std::min<int64_t>(std::min<int64_t>(kMaxSlices, kMaxMergeCand / k),
+                                          part_rows(ix->desc.max_nq) / nq);
   if (ix->tune_slices > 0) return std::min(ix->tune_slices, std::max(room, 1));
   // One block per query fills the chip's 256 compute units (each holding one or two
   // scan blocks) from that many queries up.  Smaller batches are split; the number of
