@@ -466,8 +466,11 @@ __device__ __forceinline__ void sel_rank_emit(unsigned long long *sel, int fille
 // `keep`) and sorted exactly by (score bits, id).  If that set does not fit the
 // `cap` LDS slots (heavy ties, a degenerate range, non-finite scores), the exact
 // MSB-first radix select over the 64-bit keys below does the work instead.
+// Two blocks of sixteen wavefronts per CU (eight wavefronts per SIMD) need the kernel
+// within 64 vector registers; at 66 the compiler leaves one block per CU and a batch of
+// thousands of queries takes a third longer.
 template <int PER, int kSelThreads>
-__global__ __launch_bounds__(kSelThreads) void k_coarse_select(const float *__restrict__ scores,
+__global__ __launch_bounds__(kSelThreads) __attribute__((amdgpu_waves_per_eu(8, 8))) void k_coarse_select(const float *__restrict__ scores,
                                                                int nlist, int metric_ip, int keep,
                                                                int nprobe, int stride, int cap,
                                                                float stash_z,
@@ -514,14 +517,14 @@ __global__ __launch_bounds__(kSelThreads) void k_coarse_select(const float *__re
         if (c < nlist) body(sc[i], c);
       }
     } else {
-      // sixteen loads in flight per thread before their values are used
+      // eight loads in flight per thread before their values are used
       int c = tid;
-      for (; c + 15 * kSelThreads < nlist; c += 16 * kSelThreads) {
-        float v[16];
+      for (; c + 7 * kSelThreads < nlist; c += 8 * kSelThreads) {
+        float v[8];
 #pragma unroll
-        for (int i = 0; i < 16; ++i) v[i] = row[c + i * kSelThreads];
+        for (int i = 0; i < 8; ++i) v[i] = row[c + i * kSelThreads];
 #pragma unroll
-        for (int i = 0; i < 16; ++i) body(v[i], c + i * kSelThreads);
+        for (int i = 0; i < 8; ++i) body(v[i], c + i * kSelThreads);
       }
       for (; c < nlist; c += kSelThreads) body(row[c], c);
     }
