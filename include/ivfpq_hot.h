@@ -418,11 +418,13 @@ int ivf_calib_copy(const void *src, void *dst, size_t bytes, void *stream);
 
 /*
  * Instrumentation aid: a plain streaming read of `bytes` from src (DEVICE,
- * 16-byte aligned, bytes a multiple of 16); sink is DEVICE scratch of at least
- * 2 MiB that receives one word per thread.  Its rate is the achievable read
+ * 16-byte aligned, bytes a multiple of 16); sink is DEVICE scratch of
+ * sink_bytes >= IVF_CALIB_SINK_BYTES that receives one word per launched thread
+ * (a smaller sink returns IVF_EINVAL).  Its rate is the achievable read
  * bandwidth, the practical ceiling of the ADC scan.  Asynchronous on `stream`.
  */
-int ivf_calib_read(const void *src, void *sink, size_t bytes, void *stream);
+#define IVF_CALIB_SINK_BYTES ((size_t)2 << 20)
+int ivf_calib_read(const void *src, void *sink, size_t sink_bytes, size_t bytes, void *stream);
 
 /* Message for the last error returned on this thread ("" if none). */
 const char *ivf_last_error(void);

@@ -96,7 +96,7 @@ def load_library():
     lib.ivf_set_tuning.argtypes = [P, I32, I32]
     lib.ivf_stage_times.argtypes = [P, P, P, P, ctypes.c_int]
     lib.ivf_calib_copy.argtypes = [P, P, SZ, P]
-    lib.ivf_calib_read.argtypes = [P, P, SZ, P]
+    lib.ivf_calib_read.argtypes = [P, P, SZ, SZ, P]
     lib.ivf_last_error.argtypes = []
     lib.ivf_last_error.restype = ctypes.c_char_p
     D = ctypes.c_double
@@ -134,10 +134,10 @@ def ivf_calib_copy(src, dst, stream=None):
 def ivf_calib_read(src, sink, stream=None):
     """Streaming read of torch tensor src; sink: device tensor of >= 2 MiB."""
     nbytes = src.numel() * src.element_size()
-    assert sink.numel() * sink.element_size() >= (2 << 20)
     st = None if stream is None else ctypes.c_void_p(stream.cuda_stream)
     _check(load_library().ivf_calib_read(ctypes.c_void_p(src.data_ptr()),
-                                         ctypes.c_void_p(sink.data_ptr()), nbytes, st))
+                                         ctypes.c_void_p(sink.data_ptr()),
+                                         sink.numel() * sink.element_size(), nbytes, st))
 
 
 def _np_ptr(a):

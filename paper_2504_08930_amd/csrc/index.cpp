@@ -469,8 +469,12 @@ extern "C" int ivf_calib_copy(const void *src, void *dst, size_t bytes, void *st
   return IVF_OK;
 }
 
-extern "C" int ivf_calib_read(const void *src, void *sink, size_t bytes, void *stream) {
+extern "C" int ivf_calib_read(const void *src, void *sink, size_t sink_bytes, size_t bytes,
+                              void *stream) {
   if (!src || !sink || bytes % 16 != 0) return fail(IVF_EINVAL, "calib read: bad arguments");
+  if (sink_bytes < IVF_CALIB_SINK_BYTES)
+    return fail(IVF_EINVAL, "calib read: the sink holds %zu bytes, %zu are written", sink_bytes,
+                IVF_CALIB_SINK_BYTES);
   HIP_TRY(launch_calib_read(src, sink, bytes, (hipStream_t)stream));
   return IVF_OK;
 }

@@ -124,6 +124,8 @@ __global__ void k_calib_read(const uint4 *__restrict__ src, size_t n, uint32_t *
 }
 
 constexpr int kCalibBlocks = 256 * 8, kCalibThreads = 256;
+static_assert((size_t)kCalibBlocks * kCalibThreads * 4 == IVF_CALIB_SINK_BYTES,
+              "the read kernel's sink: one word per launched thread");
 
 hipError_t launch_calib_copy(const void *src, void *dst, size_t bytes, hipStream_t st) {
   const size_t n = bytes / 16;

@@ -34,6 +34,16 @@ def test_library_exports_every_declared_symbol(lib):
     assert declared == set(lib.EXPORTS)
 
 
+def test_calib_read_refuses_a_small_sink(lib):
+    """The streaming-read aid writes one word per launched thread (2 MiB): a smaller sink is
+    an argument error, reported before anything is launched (no device needed)."""
+    import ctypes
+    cdll = lib.load_library()
+    buf = (ctypes.c_char * 64)()
+    rc = cdll.ivf_calib_read(ctypes.addressof(buf), ctypes.addressof(buf), (2 << 20) - 4, 64, None)
+    assert rc == -1 and b"sink" in cdll.ivf_last_error()
+
+
 @pytest.fixture(scope="module", params=["T_L2", "T_IP", "T_IP96"])
 def case(request, lib, oracle):
     spec = SPECS[request.param]
