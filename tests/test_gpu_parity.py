@@ -654,6 +654,54 @@ def test_random_small_shapes(pkg, oracle):
         index.close()
 
 
+def test_random_long_probe_lists(pkg, oracle):
+    """Twenty-four seeded random combinations around the kernels that serve long probe lists
+    and small batches: 257 to 2048 probes over 300 to 20 000 lists (above 16 384 the coarse
+    selection of a small batch is spread over several blocks per query), raw and residual
+    codes, both metrics, 1 to 40 queries, k up to 128, a forced number of scan blocks per query
+    up to the maximum, any resident share; each against the oracle and against itself with
+    everything resident."""
+    import torch
+    from synthdata.workloads import METRIC_IP, METRIC_L2, WorkloadSpec
+    rng = np.random.default_rng(20250311)
+    for case in range(24):
+        nlist = int(rng.choice([300, 1000, 3000, 20000]))
+        cb = int(rng.choice([16, 32, 96]))
+        dsub = int(rng.choice([1, 2, 4]))
+        ip = bool(rng.integers(0, 2))
+        residual = bool(rng.integers(0, 2))
+        n = int(rng.integers(2 * nlist, 3 * nlist + 20000))
+        nq = int(rng.choice([1, 3, 9, 40]))
+        nprobe = int(rng.integers(257, min(2048, nlist) + 1))
+        k = int(rng.choice([1, 10, 25, 100, 128]))
+        slices = int(rng.choice([0, 0, 1, 5, 32, 128]))
+        frac = float(rng.choice([0.0, 0.4, 1.0]))
+        tag = (f"case {case}: bytes={cb} dsub={dsub} ip={ip} residual={residual} nlist={nlist} "
+               f"n={n} nq={nq} nprobe={nprobe} k={k} slices={slices} resident={frac}")
+        _say(tag)
+        spec = WorkloadSpec(f"L{case}", n, cb * dsub, max(1, nlist // 4), nlist, cb,
+                            METRIC_IP if ip else METRIC_L2, ip, nq, nprobe, k,
+                            1.0 if ip else None, 1.0, kmeans_iters=1)
+        ix = build_index(spec, device="cuda", by_residual=residual)
+        q, _ = make_queries(spec, mixture_centers(spec, torch.device("cuda")))
+        q = q.cpu().numpy()
+        index = pkg.IvfIndex(ix, max_nq=64, max_nprobe=2048, max_k=128)
+        index.set_tuning(scan_slices=slices)
+        res = np.sort(rng.choice(nlist, int(round(frac * nlist)), replace=False)).astype(np.int32)
+        index.load_partition(res)
+        probe = index.coarse_probe_dev(torch.from_numpy(q).cuda(), nprobe).cpu().numpy()
+        ids, dist = index.search_batch(q, nprobe, k)
+        n_coarse, n_amb = _check_search(oracle, ix, q, nprobe, k, ids, dist, probe)
+        assert n_coarse <= max(1, nq // 10), tag
+        index.load_partition(np.arange(nlist, dtype=np.int32))
+        ids2, dist2 = index.search_batch(q, nprobe, k)
+        assert np.array_equal(ids, ids2) and np.array_equal(dist, dist2), tag
+        ids3, dist3 = index.search_batch_dev(torch.from_numpy(q).cuda(), nprobe, k)
+        torch.cuda.synchronize()
+        assert np.array_equal(ids3.cpu().numpy(), ids) and np.array_equal(dist3.cpu().numpy(), dist), tag
+        index.close()
+
+
 def test_cluster_region_too_small(pkg):
     spec, ix, q, calib = _case("T_IP")
     index = pkg.IvfIndex(ix, max_nq=64, max_nprobe=16, max_k=16, resident_vectors=ix.n // 4)
