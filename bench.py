@@ -129,9 +129,11 @@ def timed_steps(index, q, nprobe, k, steps, warmup, slices, timing=2, n_streams=
     return res
 
 
-def measure_read_ceiling(dev, with_copy=False, launches=10):
+def measure_read_ceiling(dev, with_copy=False, launches=100):
     """GB/s of the library's plain streaming-read kernel over a 1 GiB buffer (HIP events on
-    the launch stream).  with_copy: also launch the 1 GiB copy kernel once (the launch the
+    the launch stream): `launches` timed launches (about 20 ms of sustained reading, so the
+    figure is the rate at the GPU's sustained clock, not at the clock of an idle one) after
+    ten untimed ones.  with_copy: also launch the 1 GiB copy kernel once (the launch the
     byte counters are calibrated on when this script runs under rocprofv3 --pmc)."""
     import torch
     from paper_2504_08930_amd.binding import ivf_calib_copy, ivf_calib_read
@@ -145,7 +147,7 @@ def measure_read_ceiling(dev, with_copy=False, launches=10):
         torch.cuda.synchronize()
         del dst
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    for _ in range(2):
+    for _ in range(10):
         ivf_calib_read(src, sink, stream)
     e0.record(stream)
     for _ in range(launches):
@@ -475,7 +477,8 @@ def main():
         resident_frac = len(hot) / ix.nlist
 
     # the machine's achievable streaming-read rate, the second denominator of the scan's
-    # roofline: the plain read kernel over 1 GiB, ten launches timed after two untimed ones
+    # roofline: the plain read kernel over 1 GiB (it runs right before the warm-up, so the
+    # search steps start on a GPU that is already at its sustained clock)
     read_ceiling = measure_read_ceiling(dev, with_copy=args.calib_copy)
 
     # timed region: HIP events around the scan kernel only (they feed the roofline figure)
