@@ -185,7 +185,8 @@ int ivf_coarse_probe_dev(ivf_index_t *index, const float *queries, int64_t nq, i
  * ivf_coarse_probe_dev for callers that cannot allocate device memory or hand
  * over a workspace, and must not be made to wait for one: code under HIP graph
  * capture, tight serving loops, harnesses that forbid hipMalloc.  Same
- * arguments, same result (the same kernels run).  What differs is where the
+ * arguments, same result (the selection is exact on either path; this one always
+ * uses the one-block-per-query selection kernel).  What differs is where the
  * kernels' intermediates live (the queries' fp16 split, their scales, the
  * nq x nlist score matrix): not in one of the index's two per-batch workspaces
  * but in a file-scope device array of IVF_STATIC_SCRATCH_BYTES that is part of
