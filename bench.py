@@ -493,6 +493,19 @@ def main():
         stage_ms = timed_steps(index, q, spec.nprobe, spec.k, min(args.steps, 20), 2, args.slices,
                                timing=1, n_streams=1)["stage_ms"]
 
+    # the same steps issued on two alternating streams (the index keeps a workspace per
+    # stream, so one batch's coarse stage overlaps the previous batch's scan): what a
+    # caller that pipelines its batches gets; per-kernel times mean nothing then, so it
+    # is a figure of its own beside `value`, from a short pass of its own
+    two_streams = None
+    if args.streams == 1 and resident_frac == 1.0 and not args.no_timing:
+        r2s = timed_steps(index, q, spec.nprobe, spec.k, min(args.steps, 100), min(args.warmup, 10),
+                          args.slices, timing=0, n_streams=2)
+        assert torch.equal(r2s["out_ids"], out_ids) and torch.equal(r2s["out_d"], out_d)
+        two_streams = {"queries_per_s": round(r2s["qps"], 1),
+                       "ms_per_step": round(r2s["ms_per_step"], 4),
+                       "steps": min(args.steps, 100)}
+
     # the host-pointer entry point on the same batch (PCIe both ways, one call at a
     # time): context for callers that hold their queries on the host, never `value`
     host_ptr = None
@@ -629,6 +642,7 @@ def main():
                            "separate pass with events around every stage (not in the timed region)",
         "parity": parity,
         "host_pointer_call": host_ptr,
+        "two_streams": two_streams,
         "index_build_s": round(build_s, 2),
         "load_partition_s": round(load_s, 3),
     }
