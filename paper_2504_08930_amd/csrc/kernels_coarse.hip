@@ -94,7 +94,9 @@ __device__ __forceinline__ int lds_swz(int row) {
 }
 
 // <1,4,1,2> / <1,2,1,2>: 32 x 256 / 32 x 128 block, 4 / 2 waves of 32 x 64 (up to 64 queries);
-// <2,2,2,2>: 128 x 128 block, 4 waves (small batches: more blocks);
+// <4,2,1,2>: 128 x 128 block, 8 waves of 32 x 64 (batches that leave big tiles too few
+// blocks; twice the waves of a 4-wave block of 64 x 64 tiles hide more of the K loop's
+// latency: 29 instead of 36 us at 256 queries x 16384 centroids);
 // <4,4,2,2>: 256 x 256 block, 16 waves of 64 x 64 (half the L2 traffic per MFMA of the
 // small tile; 120 registers, so four waves per SIMD hide one another's LDS and
 // barrier waits - measured 10 % faster than 8 waves of 64 x 128 at two per SIMD).
@@ -303,12 +305,22 @@ hipError_t launch_coarse_gemm(const Shape &sh, const void *q_parts, const int32_
     return launch_gemm_t<1, 2, 1, 2>(sh, q_parts, q_exp, nq, cent_parts, cent_exp, cent_norm, scores,
                                      st);
   }
-  // big tiles once they still give every CU a block
+  // 256 x 256 tiles of 16 waves or 128 x 128 tiles of 8 waves (two blocks per CU): the
+  // one that a fit to measured launches expects to finish first (us).  A launch of
+  // small tiles lasts 25 us however little it does (its K loop of d / 16 chunks),
+  // then grows with its blocks, 0.1 us each beyond two per CU; a round of big tiles on
+  // all 256 CUs lasts 85 us, a part-full last round 55 us plus 0.11 us per block.
   const long long big_blocks = (long long)((nq + 255) / 256) * ((sh.nlist + 255) / 256);
-  if (big_blocks >= 192)
+  const long long mid_blocks = (long long)((nq + 127) / 128) * ((sh.nlist + 127) / 128);
+  const double t_mid = mid_blocks <= 512
+                           ? 25.0 + 0.0625 * (double)std::max<long long>(0, mid_blocks - 128)
+                           : 0.1 * (double)mid_blocks;
+  const long long rem = big_blocks % 256;
+  const double t_big = 85.0 * (double)(big_blocks / 256) + (rem ? 55.0 + 0.11 * (double)rem : 0.0);
+  if (t_big <= t_mid)
     return launch_gemm_t<4, 4, 2, 2>(sh, q_parts, q_exp, nq, cent_parts, cent_exp, cent_norm,
                                      scores, st);
-  return launch_gemm_t<2, 2, 2, 2>(sh, q_parts, q_exp, nq, cent_parts, cent_exp, cent_norm, scores,
+  return launch_gemm_t<4, 2, 1, 2>(sh, q_parts, q_exp, nq, cent_parts, cent_exp, cent_norm, scores,
                                    st);
 }
 
