@@ -64,6 +64,9 @@ static void dispatcher_main(ivf_ticket *t) {
   std::vector<std::thread> workers;  // only if the worker pool is taken
   bool pooled = false;
   std::atomic<int64_t> next(0);
+  // set once the device's partial results are on the host: queries the CPU loop starts
+  // after that scan with the device's k-th best key as their bound
+  std::atomic<int> gpu_ready(0);
   std::vector<int32_t> order((size_t)nq);
   if (gpu_ok) {
     // CPU search loop.  Queries are taken fewest cold probes first, so that the
@@ -84,8 +87,11 @@ static void dispatcher_main(ivf_ticket *t) {
           const float mb = t->device ? ix->h_qbmax[q] : cpu_max_bias(view, qv, pr, nc);
           const int e = cpu_build_lut(view, qv, mb, lut.data());
           t->cpu_e[q] = e;
+          int32_t cap = kKeyInvalid;
+          if (t->device && t->any_resident && gpu_ready.load(std::memory_order_acquire))
+            cap = device_key_cap(ix, view, q, k, e);
           cpu_scan_lists(view, lut.data(), e, qv, pr, nc, k, &t->cpu_res[(size_t)q * k],
-                         &t->scanned[q]);
+                         &t->scanned[q], cap);
         }
         // scan count == expected count: the query goes to the completed queue
         if (__atomic_load_n(&t->scanned[q], __ATOMIC_ACQUIRE) == nc) {
@@ -109,6 +115,8 @@ static void dispatcher_main(ivf_ticket *t) {
     if (e != hipSuccess) {
       ticket_fail(t, IVF_EDEVICE, std::string("device scan failed: ") + hipGetErrorString(e));
       gpu_ok = false;
+    } else {
+      gpu_ready.store(1, std::memory_order_release);
     }
   }
   if (t->device) end_batch(ix, t->ctx, t->st, false);

@@ -102,10 +102,15 @@ void WorkerPool::wait() {
   p.busy = false;
 }
 
-void parallel_for(int64_t n, const std::function<void(int64_t)> &fn) {
-  if (n <= 0) return;
+void parallel_for(int64_t n, const std::function<void(int64_t)> &fn,
+                  const std::function<void()> *caller_first) {
+  if (n <= 0) {
+    if (caller_first) (*caller_first)();
+    return;
+  }
   int nt = (int)std::min<int64_t>(cpu_threads(), n);
   if (nt <= 1) {
+    if (caller_first) (*caller_first)();
     for (int64_t i = 0; i < n; ++i) fn(i);
     return;
   }
@@ -120,6 +125,7 @@ void parallel_for(int64_t n, const std::function<void(int64_t)> &fn) {
   // the caller is one of the nt threads
   WorkerPool &pool = WorkerPool::get();
   if (pool.start(nt - 1, work)) {
+    if (caller_first) (*caller_first)();
     work();
     pool.wait();
     return;
@@ -127,6 +133,7 @@ void parallel_for(int64_t n, const std::function<void(int64_t)> &fn) {
   std::vector<std::thread> th;  // the pool is taken: threads of our own
   th.reserve(nt - 1);
   for (int t = 1; t < nt; ++t) th.emplace_back(work);
+  if (caller_first) (*caller_first)();
   work();
   for (auto &t : th) t.join();
 }
@@ -258,6 +265,23 @@ int cpu_build_lut(const HostIndexView &ix, const float *q, float max_bias, int32
   return e;
 }
 
+// Sum of a vector's M table entries by plain lookups: eight code bytes per 64-bit
+// load, two independent accumulators (integer sums: the order does not matter); M is
+// a multiple of 8.
+static inline int32_t code_sum(const int32_t *lut, const uint8_t *code, int M) {
+  int32_t s0 = 0, s1 = 0;
+  for (int m = 0; m < M; m += 8) {
+    uint64_t w;
+    memcpy(&w, code + m, 8);
+    const int32_t *t = lut + m * 256;
+    s0 += t[w & 255] + t[512 + ((w >> 16) & 255)] + t[1024 + ((w >> 32) & 255)] +
+          t[1536 + ((w >> 48) & 255)];
+    s1 += t[256 + ((w >> 8) & 255)] + t[768 + ((w >> 24) & 255)] +
+          t[1280 + ((w >> 40) & 255)] + t[1792 + (w >> 56)];
+  }
+  return (int32_t)((uint32_t)s0 + (uint32_t)s1);
+}
+
 static inline bool cand_less(const HostCand &a, const HostCand &b) {
   return a.key < b.key || (a.key == b.key && a.id < b.id);
 }
@@ -376,6 +400,159 @@ __attribute__((target("avx512f,avx512bw,avx512vbmi"))) static void plane_accumul
   }
 }
 
+// ---------------------------------------------------------------------------
+// Filter pass.  Once the query's result list is full, nearly every vector of a
+// list is rejected, and a lower bound of its sum is enough to reject it.  With
+// mn_m the smallest entry of column m, the entry less mn_m is non-negative, and
+// h = min((entry - mn_m) >> 8, 65535) satisfies 256 * h <= entry - mn_m.  So
+//   sum_m mn_m + 256 * sum_m h_m(code_m)  <=  the vector's true sum,
+// short of it by less than 256 per column unless an entry saturates (only the
+// largest entries of a column whose range passes 2^24 do, and they belong to
+// vectors far from the query).  h has two bytes, so the bound costs two byte
+// planes per column instead of four; a group of 64 vectors in which no bound
+// reaches the worst kept key is done, the few others get the exact four-plane
+// sums.  Every key that is compared with the result list's is therefore exact,
+// and results are the same with or without the filter.
+// ---------------------------------------------------------------------------
+// filt[(m * 2 + p) * 256 + j] = byte p of h_m(j); returns sum_m mn_m (mod 2^32)
+static int32_t build_filter(const int32_t *lut, int M, uint8_t *filt) {
+  uint32_t base = 0;
+  for (int m = 0; m < M; ++m) {
+    const int32_t *col = lut + (size_t)m * 256;
+    int32_t mn = col[0];
+    for (int j = 1; j < 256; ++j) mn = std::min(mn, col[j]);
+    base += (uint32_t)mn;
+    uint8_t *f = filt + (size_t)m * 512;
+    for (int j = 0; j < 256; ++j) {
+      const uint32_t h = std::min<uint32_t>(((uint32_t)col[j] - (uint32_t)mn) >> 8, 65535u);
+      f[j] = (uint8_t)h;
+      f[256 + j] = (uint8_t)(h >> 8);
+    }
+  }
+  return (int32_t)base;
+}
+
+// acc[g][p][h]: for byte plane p of the filter values, the sums of the group's even
+// (h = 0) and odd (h = 1) vectors as 32 uint16 lanes (at most 128 columns x 255).
+// GB groups at a time keep their sixteen partial sums in registers while the
+// columns go by (a column's two byte tables are reloaded per block of groups instead:
+// eight loads from the cache per column against sixteen loads and sixteen stores of
+// partial sums).
+template <int VARIANT, int GB>
+__attribute__((target("avx512f,avx512bw,avx512vbmi"))) static inline void filter_block(
+    const uint8_t *rows, size_t stride, int M, const uint8_t *filt, uint16_t *acc) {
+  const __m512i lo8 = _mm512_set1_epi16(0x00ff);
+  const __m512i bit6 = _mm512_set1_epi8(0x40);
+  __m512i s[GB][4];
+#pragma unroll
+  for (int g = 0; g < GB; ++g)
+#pragma unroll
+    for (int r = 0; r < 4; ++r) s[g][r] = _mm512_setzero_si512();
+  for (int m = 0; m < M; ++m) {
+    __m512i T[8];
+#pragma unroll
+    for (int r = 0; r < 8; ++r)
+      T[r] = _mm512_loadu_si512((const void *)(filt + (size_t)m * 512 + r * 64));
+    const uint8_t *row = rows + (size_t)m * stride;
+#pragma unroll
+    for (int g = 0; g < GB; ++g) {
+      const __m512i c = _mm512_loadu_si512((const void *)(row + (size_t)g * 64));
+      const __mmask64 b7 = _mm512_movepi8_mask(c);  // codes 128..255
+      __mmask64 k1 = 0, k2 = 0, k3 = 0;
+      if (VARIANT == 1) {
+        const __mmask64 b6 = _mm512_test_epi8_mask(c, bit6);
+        k1 = b6 & ~b7;
+        k2 = ~b6 & b7;
+        k3 = b6 & b7;
+      }
+#pragma unroll
+      for (int p = 0; p < 2; ++p) {
+        __m512i v;
+        if (VARIANT == 0) {
+          const __m512i lo = _mm512_permutex2var_epi8(T[4 * p + 0], c, T[4 * p + 1]);
+          const __m512i hi = _mm512_permutex2var_epi8(T[4 * p + 2], c, T[4 * p + 3]);
+          v = _mm512_mask_blend_epi8(b7, lo, hi);
+        } else {
+          v = _mm512_permutexvar_epi8(c, T[4 * p + 0]);
+          v = _mm512_mask_permutexvar_epi8(v, k1, c, T[4 * p + 1]);
+          v = _mm512_mask_permutexvar_epi8(v, k2, c, T[4 * p + 2]);
+          v = _mm512_mask_permutexvar_epi8(v, k3, c, T[4 * p + 3]);
+        }
+        s[g][2 * p] = _mm512_add_epi16(s[g][2 * p], _mm512_and_si512(v, lo8));
+        s[g][2 * p + 1] = _mm512_add_epi16(s[g][2 * p + 1], _mm512_srli_epi16(v, 8));
+      }
+    }
+  }
+#pragma unroll
+  for (int g = 0; g < GB; ++g)
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+      _mm512_storeu_si512((void *)(acc + (size_t)g * 128 + r * 32), s[g][r]);
+}
+
+template <int VARIANT>
+__attribute__((target("avx512f,avx512bw,avx512vbmi"))) static void filter_accumulate(
+    const uint8_t *rows, size_t stride, int M, int ng, const uint8_t *filt, uint16_t *acc) {
+  int g = 0;
+  for (; g + 4 <= ng; g += 4)
+    filter_block<VARIANT, 4>(rows + (size_t)g * 64, stride, M, filt, acc + (size_t)g * 128);
+  switch (ng - g) {
+    case 3: filter_block<VARIANT, 3>(rows + (size_t)g * 64, stride, M, filt, acc + (size_t)g * 128); break;
+    case 2: filter_block<VARIANT, 2>(rows + (size_t)g * 64, stride, M, filt, acc + (size_t)g * 128); break;
+    case 1: filter_block<VARIANT, 1>(rows + (size_t)g * 64, stride, M, filt, acc + (size_t)g * 128); break;
+    default: break;
+  }
+}
+
+// The groups (of the ng in acc) in which some vector's lower bound, plus add (the
+// table's base and the list's bias) and the vector's own term pvq (or NULL), does
+// not exceed bound; nv = vectors in the ng groups (the last group may be ragged).
+// Returns how many, their numbers in gidx and, per such group, the vectors in
+// question as a bit mask (bit i = vector i of the group) in gmask.
+__attribute__((target("avx512f,avx512bw,avx512vbmi,bmi2"))) static int filter_survivors(
+    const uint16_t *acc, int ng, int64_t nv, uint32_t add, const int32_t *pvq, int32_t bound,
+    int *gidx, uint64_t *gmask) {
+  const __m512i vadd = _mm512_set1_epi32((int)add);
+  const __m512i vbound = _mm512_set1_epi32(bound);
+  const __m512i lane = _mm512_set_epi32(15, 14, 13, 12, 11, 10, 9, 8, 7, 6, 5, 4, 3, 2, 1, 0);
+  const __m512i idx_even = _mm512_slli_epi32(lane, 1);                       // 0, 2, ..., 30
+  const __m512i idx_odd = _mm512_add_epi32(idx_even, _mm512_set1_epi32(1));  // 1, 3, ..., 31
+  int n = 0;
+  for (int g = 0; g < ng; ++g) {
+    const uint16_t *a = acc + (size_t)g * 128;
+    const int left = (int)std::min<int64_t>(64, nv - (int64_t)g * 64);  // vectors of this group
+    uint64_t any = 0;
+    for (int h2 = 0; h2 < 2; ++h2) {  // words 16 * h2 .. + 15 of the even and of the odd vectors
+      const __m512i e0 = _mm512_cvtepu16_epi32(_mm256_loadu_si256((const __m256i *)(a + 16 * h2)));
+      const __m512i o0 = _mm512_cvtepu16_epi32(_mm256_loadu_si256((const __m256i *)(a + 32 + 16 * h2)));
+      const __m512i e1 = _mm512_cvtepu16_epi32(_mm256_loadu_si256((const __m256i *)(a + 64 + 16 * h2)));
+      const __m512i o1 = _mm512_cvtepu16_epi32(_mm256_loadu_si256((const __m256i *)(a + 96 + 16 * h2)));
+      // 256 * (plane 0 + 256 * plane 1) + add, modulo 2^32 (the true value fits an int32)
+      __m512i ke = _mm512_add_epi32(_mm512_slli_epi32(_mm512_add_epi32(e0, _mm512_slli_epi32(e1, 8)), 8), vadd);
+      __m512i ko = _mm512_add_epi32(_mm512_slli_epi32(_mm512_add_epi32(o0, _mm512_slli_epi32(o1, 8)), 8), vadd);
+      if (pvq) {
+        const int32_t *pq = pvq + (size_t)g * 64 + 32 * h2;  // vectors 32 * h2 .. + 31 of the group
+        const __m512i p_lo = _mm512_loadu_si512((const void *)pq);
+        const __m512i p_hi = _mm512_loadu_si512((const void *)(pq + 16));
+        ke = _mm512_add_epi32(ke, _mm512_permutex2var_epi32(p_lo, idx_even, p_hi));
+        ko = _mm512_add_epi32(ko, _mm512_permutex2var_epi32(p_lo, idx_odd, p_hi));
+      }
+      // word w of this half is vector 32 * h2 + 2 * w (even) or + 1 (odd)
+      const int rem = left - 32 * h2;  // vectors of the group from this half on
+      const __mmask16 ve = rem >= 32 ? (__mmask16)0xffff : rem <= 0 ? (__mmask16)0 : (__mmask16)((1u << ((rem + 1) / 2)) - 1u);
+      const __mmask16 vo = rem >= 32 ? (__mmask16)0xffff : rem <= 0 ? (__mmask16)0 : (__mmask16)((1u << (rem / 2)) - 1u);
+      const uint64_t me = _mm512_mask_cmple_epi32_mask(ve, ke, vbound);
+      const uint64_t mo = _mm512_mask_cmple_epi32_mask(vo, ko, vbound);
+      any |= (_pdep_u64(me, 0x55555555ull) | _pdep_u64(mo, 0xaaaaaaaaull)) << (32 * h2);
+    }
+    if (any) {
+      gidx[n] = g;
+      gmask[n++] = any;
+    }
+  }
+  return n;
+}
+
 // int32 sums in vector order from the partial sums of plane_accumulate
 static void plane_combine(const uint16_t *acc, int ng, int32_t *sums) {
   for (int g = 0; g < ng; ++g) {
@@ -398,10 +575,12 @@ namespace {
 struct TopK {
   std::vector<HostCand> heap;
   int k;
-  explicit TopK(int k_) : k(k_) { heap.reserve((size_t)k_); }
+  int32_t cap;  // keys above it are not wanted at all
+  TopK(int k_, int32_t cap_) : k(k_), cap(cap_) { heap.reserve((size_t)k_); }
   // every candidate with key above this is certainly rejected
-  int32_t bound() const { return (int)heap.size() < k ? 0x7fffffff : heap.front().key; }
+  int32_t bound() const { return (int)heap.size() < k ? cap : std::min(cap, heap.front().key); }
   void offer(const HostCand &cand) {
+    if (cand.key > cap) return;
     if ((int)heap.size() < k) {
       heap.push_back(cand);
       std::push_heap(heap.begin(), heap.end(), cand_less);
@@ -421,31 +600,88 @@ struct TopK {
 
 static const int g_plane_variant = __builtin_cpu_is("intel") ? 1 : 0;
 
-static void plane_scan_list(const HostIndexView &ix, const uint8_t *planes, int e, int cl,
+// The filter pass runs unless the environment says IVF_HOST_FILTER=0 (read per
+// query, so a test can compare the two in one process).
+static bool host_filter_on() {
+  const char *e = getenv("IVF_HOST_FILTER");
+  return !(e && !strcmp(e, "0"));
+}
+
+struct PlaneTables {
+  const int32_t *lut;     // the query's table
+  const uint8_t *planes;  // build_planes (filter pass off), else NULL
+  const uint8_t *filt;    // build_filter (filter pass on), else NULL
+  int32_t filt_base;
+};
+
+static void plane_scan_list(const HostIndexView &ix, const PlaneTables &tb, int e, int cl,
                             int32_t bias_key, TopK &top) {
   const int64_t v0 = ix.list_offsets[cl], len = ix.list_offsets[cl + 1] - v0;
   const int64_t lpad = (len + 63) / 64 * 64;
   const uint8_t *base = ix.codes_t + ix.list_toff[cl];
   alignas(64) uint16_t acc[kPlaneSegGroups * 256];
   alignas(64) int32_t sums[kPlaneSegGroups * 64];
+  alignas(64) int32_t pvq[kPlaneSegGroups * 64];
+  int gidx[kPlaneSegGroups];
+  uint64_t gmask[kPlaneSegGroups];
   const float scale = ldexpf(1.0f, e);
+  // exact key of vector i of the segment at s0, by plain lookups in the row-major codes
+  auto exact_offer = [&](int64_t s0, int64_t i, int32_t &bound) {
+    const int64_t v = v0 + s0 + i;
+    uint32_t sum = (uint32_t)code_sum(tb.lut, ix.codes + (size_t)v * ix.M, ix.M) + (uint32_t)bias_key;
+    if (ix.pv) sum += (uint32_t)pvq[i];
+    const int32_t key = (int32_t)sum;
+    if (key > bound) return;
+    top.offer(HostCand{key, ix.ids[v]});
+    bound = top.bound();
+  };
   for (int64_t s0 = 0; s0 < len; s0 += kPlaneSegGroups * 64) {
     const int64_t nv = std::min<int64_t>(kPlaneSegGroups * 64, len - s0);
     const int ng = (int)((nv + 63) / 64);
-    if (g_plane_variant == 0) plane_accumulate<0>(base + s0, (size_t)lpad, ix.M, ng, planes, acc);
-    else plane_accumulate<1>(base + s0, (size_t)lpad, ix.M, ng, planes, acc);
-    plane_combine(acc, ng, sums);
     if (ix.pv) {
-      // + lut_quantize(pv, e), the scaling written as an exact product
+      // lut_quantize(pv, e), the scaling written as an exact product
       const float *pv = ix.pv + v0 + s0;
       for (int64_t i = 0; i < nv; ++i) {
         const float r = __builtin_rintf(pv[i] * scale);
-        sums[i] += __builtin_fabsf(r) < 2147483520.0f ? (int)r : 0;
+        pvq[i] = __builtin_fabsf(r) < 2147483520.0f ? (int)r : 0;
       }
     }
     int32_t bound = top.bound();
+    if (tb.filt) {
+      // With nothing to compare against yet (no bound from the device and the result
+      // list not full) whole groups are summed exactly until there is; then the two-
+      // plane lower bounds of the remaining groups, and exact sums for the few
+      // vectors whose bound does not rule them out.
+      int g0 = 0;
+      for (; g0 < ng && bound == kKeyInvalid; ++g0) {
+        const int64_t i1 = std::min<int64_t>(nv, (int64_t)(g0 + 1) * 64);
+        for (int64_t i = (int64_t)g0 * 64; i < i1; ++i) exact_offer(s0, i, bound);
+      }
+      if (g0 == ng) continue;
+      const int64_t off = (int64_t)g0 * 64;
+      if (g_plane_variant == 0)
+        filter_accumulate<0>(base + s0 + off, (size_t)lpad, ix.M, ng - g0, tb.filt, acc);
+      else
+        filter_accumulate<1>(base + s0 + off, (size_t)lpad, ix.M, ng - g0, tb.filt, acc);
+      const int n_hit = filter_survivors(acc, ng - g0, nv - off,
+                                         (uint32_t)tb.filt_base + (uint32_t)bias_key,
+                                         ix.pv ? pvq + off : nullptr, bound, gidx, gmask);
+      for (int j = 0; j < n_hit; ++j) {
+        const int64_t i0 = off + (int64_t)gidx[j] * 64;
+        for (uint64_t mk = gmask[j]; mk; mk &= mk - 1)
+          exact_offer(s0, i0 + __builtin_ctzll(mk), bound);
+      }
+      continue;
+    }
+    if (g_plane_variant == 0)
+      plane_accumulate<0>(base + s0, (size_t)lpad, ix.M, ng, tb.planes, acc);
+    else
+      plane_accumulate<1>(base + s0, (size_t)lpad, ix.M, ng, tb.planes, acc);
+    plane_combine(acc, ng, sums);
     for (int64_t i = 0; i < nv; ++i) {
-      const int32_t key = (int32_t)((uint32_t)sums[i] + (uint32_t)bias_key);
+      uint32_t sum = (uint32_t)sums[i] + (uint32_t)bias_key;
+      if (ix.pv) sum += (uint32_t)pvq[i];
+      const int32_t key = (int32_t)sum;
       if (key > bound) continue;
       top.offer(HostCand{key, ix.ids[v0 + s0 + i]});
       bound = top.bound();
@@ -455,14 +691,22 @@ static void plane_scan_list(const HostIndexView &ix, const uint8_t *planes, int 
 
 void cpu_scan_lists(const HostIndexView &ix, const int32_t *lut, int e, const float *q,
                     const int32_t *clusters, int n_clusters, int k, HostCand *out,
-                    int32_t *scanned) {
-  TopK top(k);
+                    int32_t *scanned, int32_t key_cap) {
+  TopK top(k, key_cap);
   const int M = ix.M;
   const bool planes_on = ix.codes_t != nullptr;
   thread_local std::vector<uint8_t> planes;
+  PlaneTables tb{lut, nullptr, nullptr, 0};
   if (planes_on && n_clusters > 0) {
-    planes.resize((size_t)M * 1024);
-    build_planes(lut, M, planes.data());
+    if (host_filter_on()) {
+      planes.resize((size_t)M * 512);
+      tb.filt = planes.data();
+      tb.filt_base = build_filter(lut, M, planes.data());
+    } else {
+      planes.resize((size_t)M * 1024);
+      build_planes(lut, M, planes.data());
+      tb.planes = planes.data();
+    }
   }
   for (int c = 0; c < n_clusters; ++c) {
     const int cl = clusters[c];
@@ -473,26 +717,22 @@ void cpu_scan_lists(const HostIndexView &ix, const int32_t *lut, int e, const fl
       bias_key = lut_quantize(
           residual_bias_host(ix.metric_ip, q, ix.centroids + (size_t)cl * ix.d, ix.d), e);
     if (planes_on) {
-      plane_scan_list(ix, planes.data(), e, cl, bias_key, top);
+      // the next list lies somewhere else in memory: ask for its first 64 KB now, so
+      // that the lines are on their way while this list is scanned
+      if (c + 1 < n_clusters && clusters[c + 1] >= 0) {
+        const int nx = clusters[c + 1];
+        const uint8_t *p0 = ix.codes_t + ix.list_toff[nx];
+        const int64_t nb = std::min<int64_t>(ix.list_toff[nx + 1] - ix.list_toff[nx], 64 << 10);
+        for (int64_t o = 0; o < nb; o += 64) __builtin_prefetch(p0 + o, 0, 2);
+      }
+      plane_scan_list(ix, tb, e, cl, bias_key, top);
       continue;
     }
     for (int64_t v = ix.list_offsets[cl]; v < ix.list_offsets[cl + 1]; ++v) {
       const uint8_t *code = ix.codes + (size_t)v * M;
       int32_t sum = bias_key;
       if (ix.pv) sum += lut_quantize(ix.pv[v], e);
-      // eight code bytes per 64-bit load, two independent accumulators (integer sums:
-      // the order does not matter); M is a multiple of 16
-      int32_t s0 = 0, s1 = 0;
-      for (int m = 0; m < M; m += 8) {
-        uint64_t w;
-        memcpy(&w, code + m, 8);
-        const int32_t *t = lut + m * 256;
-        s0 += t[w & 255] + t[512 + ((w >> 16) & 255)] + t[1024 + ((w >> 32) & 255)] +
-              t[1536 + ((w >> 48) & 255)];
-        s1 += t[256 + ((w >> 8) & 255)] + t[768 + ((w >> 24) & 255)] +
-              t[1280 + ((w >> 40) & 255)] + t[1792 + (w >> 56)];
-      }
-      sum += s0 + s1;
+      sum += code_sum(lut, code, M);
       top.offer(HostCand{sum, ix.ids[v]});
     }
   }

@@ -9,6 +9,8 @@
 #include <functional>
 #include <vector>
 
+#include "lut_quant.h"
+
 namespace ivf {
 
 struct HostCand {
@@ -41,7 +43,9 @@ struct HostIndexView {
 int cpu_threads();
 
 // Run fn(i) for i in [0, n) on up to cpu_threads() threads.
-void parallel_for(int64_t n, const std::function<void(int64_t)> &fn);
+// caller_first (optional) runs on the calling thread before it joins the others.
+void parallel_for(int64_t n, const std::function<void(int64_t)> &fn,
+                  const std::function<void()> *caller_first = nullptr);
 
 // The library's worker threads: created once (cpu_threads() of them) and parked
 // between batches, so a small hybrid batch does not pay for thread creation.
@@ -96,9 +100,14 @@ void cpu_transpose_codes(const HostIndexView &ix, const int64_t *list_toff, uint
 // Clusters are taken one by one; `scanned` (optional) holds the number of list
 // entries finished so far and reaches n_clusters once `out` is written, which is
 // what the dispatcher compares with the query's expected count (Section 4.2.2).
+// key_cap: only candidates with key <= key_cap are wanted (kKeyInvalid: all of them).
+// A hybrid batch passes the k-th best key of the device's partial result once that
+// is on the host: vectors of the cold lists that cannot displace it are then
+// rejected by the filter pass from the first list on, and `out` may hold fewer than
+// k candidates.
 void cpu_scan_lists(const HostIndexView &ix, const int32_t *lut, int e, const float *q,
                     const int32_t *clusters, int n_clusters, int k, HostCand *out,
-                    int32_t *scanned = nullptr);
+                    int32_t *scanned = nullptr, int32_t key_cap = kKeyInvalid);
 
 // Merge two best-first lists of k candidates into the k best.
 void merge_topk(const HostCand *a, const HostCand *b, int k, HostCand *out);

@@ -237,6 +237,8 @@ IVF_INTERNAL int enqueue_gpu(ivf_index *ix, const SearchArgs &a, const BatchCtx 
 IVF_INTERNAL bool finish_query(const ivf_index *ix, const HostIndexView &view,
                                bool any_resident, int64_t q, int k, const HostCand *cpu,
                                int cpu_e, int64_t *ids, float *dists);
+IVF_INTERNAL int32_t device_key_cap(const ivf_index *ix, const HostIndexView &view, int64_t q,
+                                    int k, int e);
 IVF_INTERNAL int check_search_args(const ivf_index *ix, const void *queries, int64_t nq,
                                    int32_t nprobe, int32_t k, const void *out_ids,
                                    const void *out_dists);

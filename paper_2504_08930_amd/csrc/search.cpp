@@ -333,6 +333,20 @@ bool finish_query(const ivf_index *ix, const HostIndexView &view, bool any_resid
   return ok;
 }
 
+// The k-th best key of the device's partial result for query q (on the host once
+// the batch's stream has drained), if the device found k candidates and quantized
+// with the exponent e the CPU scan uses; kKeyInvalid otherwise.  The resident and the
+// cold lists are disjoint, so a vector of a cold list with a larger key cannot be
+// among the k best of both.
+int32_t device_key_cap(const ivf_index *ix, const HostIndexView &view, int64_t q, int k, int e) {
+  const int32_t kth = ix->h_reskey[q * k + (k - 1)];
+  if (kth == kKeyInvalid) return kKeyInvalid;
+  float mx;
+  memcpy(&mx, &ix->h_lutmax[q], 4);
+  const int e_dev = lut_exponent(mx, view.M, ix->h_qbmax[q], view.pv ? view.pv_max : 0.0f);
+  return e_dev == e ? kth : kKeyInvalid;
+}
+
 static int search_device(ivf_index *ix, const SearchArgs &a) {
   const int nq = (int)a.nq, k = a.k;
   const int np = a.nprobe;
@@ -413,17 +427,32 @@ static int search_device(ivf_index *ix, const SearchArgs &a) {
   const HostIndexView view = host_view(ix);
   std::vector<HostCand> cpu_res((size_t)nq * k);
   std::vector<int> cpu_e((size_t)nq, 0);
+  // The calling thread first waits for the device (a fraction of a millisecond; the
+  // other threads are already scanning) and then joins them.  From then on a query's
+  // CPU scan starts with the k-th best key of the device's partial result as its
+  // bound: the resident lists are the query's nearest, so hardly any vector of a
+  // cold list gets past the filter pass.
+  std::atomic<int> gpu_ready(0);
+  hipError_t sync_err = hipSuccess;
+  const std::function<void()> wait_gpu = [&]() {
+    sync_err = hipStreamSynchronize(st);  // the device's partial results are on the host
+    if (sync_err == hipSuccess) gpu_ready.store(1, std::memory_order_release);
+  };
   parallel_for(nq, [&](int64_t q) {
     const int nc = ix->h_ncold[q];
     if (nc == 0 && any_resident) return;
     thread_local std::vector<int32_t> lut;
     lut.resize((size_t)view.M * 256);
     const float *qv = hq + (size_t)q * view.d;
-    cpu_e[(size_t)q] = cpu_build_lut(view, qv, ix->h_qbmax[q], lut.data());
-    cpu_scan_lists(view, lut.data(), cpu_e[(size_t)q], qv, ix->h_cold + (size_t)q * np, nc, k,
-                   &cpu_res[(size_t)q * k]);
-  });
-  S_TRY(hipStreamSynchronize(st));  // the device's partial results are on the host
+    const int e = cpu_build_lut(view, qv, ix->h_qbmax[q], lut.data());
+    cpu_e[(size_t)q] = e;
+    int32_t cap = kKeyInvalid;
+    if (any_resident && gpu_ready.load(std::memory_order_acquire))
+      cap = device_key_cap(ix, view, q, k, e);
+    cpu_scan_lists(view, lut.data(), e, qv, ix->h_cold + (size_t)q * np, nc, k,
+                   &cpu_res[(size_t)q * k], nullptr, cap);
+  }, &wait_gpu);
+  S_TRY(sync_err);
   end_batch(ix, ctx, st, false);
   std::vector<int> bad(1, 0);
   parallel_for(nq, [&](int64_t q) {

@@ -171,8 +171,10 @@ def test_host_only_vector_order_within_lists_is_irrelevant(case, lib, oracle):
                                                   ("T_IP96", True, 8, None), ("T_IP", False, 4, 64)])
 def test_host_scan_forms_agree_bit_for_bit(lib, oracle, monkeypatch, name, residual, nbits, m):
     """The CPU scan has two forms: the plain loop over a vector's code bytes and,
-    on CPUs with AVX-512 VBMI, the byte-plane scan over column-major codes.  Both
-    add the same integers, so ids and distances are identical; two long lists
+    on CPUs with AVX-512 VBMI, the byte-plane scan over column-major codes, with
+    or without its filter pass (a two-plane lower bound that rejects most groups
+    of 64 vectors once the result list is full).  All add the same integers for
+    every key they compare, so ids and distances are identical; two long lists
     make the byte-plane scan cross its 2048-vector pass and end on a ragged
     group."""
     import dataclasses
@@ -189,11 +191,15 @@ def test_host_scan_forms_agree_bit_for_bit(lib, oracle, monkeypatch, name, resid
     rng = np.random.default_rng(3)
     probe = np.stack([rng.permutation(ix.nlist)[:nprobe] for _ in range(q.shape[0])]).astype(np.int32)
     got = {}
-    for form in ("scalar", "planes"):
+    for form in ("scalar", "planes", "planes_nofilter"):
         if form == "scalar":
             monkeypatch.setenv("IVF_HOST_SCAN", "scalar")
         else:
             monkeypatch.delenv("IVF_HOST_SCAN", raising=False)
+        if form == "planes_nofilter":
+            monkeypatch.setenv("IVF_HOST_FILTER", "0")
+        else:
+            monkeypatch.delenv("IVF_HOST_FILTER", raising=False)
         index = lib.IvfIndex(ix, spec.nq, nprobe, 64, host_only=True)
         if form == "scalar":
             assert index.host_scan_form() == 0
@@ -201,8 +207,9 @@ def test_host_scan_forms_agree_bit_for_bit(lib, oracle, monkeypatch, name, resid
             assert index.host_scan_form() == 1
         got[form] = [index.search_batch_probes(q, probe, k) for k in (1, 10, 64)]
         index.close()
-    for a, b in zip(got["scalar"], got["planes"]):
+    for a, b, c in zip(got["scalar"], got["planes"], got["planes_nofilter"]):
         assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])
+        assert np.array_equal(a[0], c[0]) and np.array_equal(a[1], c[1])
     ref_i, ref_d = oracle.scan(ix.metric, ix.codebooks, ix.list_offsets, ix.codes, ix.ids, q, probe,
                                64 + 16, residual_centroids=ix.centroids if residual else None)
     ids, dist = got["planes"][2]
@@ -224,11 +231,15 @@ def test_host_only_other_code_sizes(lib, oracle, monkeypatch, code_bytes, metric
     q = q.numpy()
     probe, _, _ = oracle.coarse(ix.metric, ix.centroids, q, spec.nprobe)
     got = {}
-    for form in ("scalar", "planes"):
+    for form in ("scalar", "planes", "planes_nofilter"):
         if form == "scalar":
             monkeypatch.setenv("IVF_HOST_SCAN", "scalar")
         else:
             monkeypatch.delenv("IVF_HOST_SCAN", raising=False)
+        if form == "planes_nofilter":
+            monkeypatch.setenv("IVF_HOST_FILTER", "0")
+        else:
+            monkeypatch.delenv("IVF_HOST_FILTER", raising=False)
         index = lib.IvfIndex(ix, spec.nq, spec.nprobe, 64, host_only=True)
         got[form] = index.search_batch_probes(q, probe, spec.k)
         index.close()
