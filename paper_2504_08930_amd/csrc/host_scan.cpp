@@ -438,9 +438,17 @@ static int32_t build_filter(const int32_t *lut, int M, uint8_t *filt) {
 // columns go by (a column's two byte tables are reloaded per block of groups instead:
 // eight loads from the cache per column against sixteen loads and sixteen stores of
 // partial sums).
+// pf (optional): a cursor through memory that will be read next (the rest of the
+// next list); one line of it is requested per line of codes read here, so the
+// requests are spread over the scan instead of arriving in one burst.
+struct PrefetchCursor {
+  const uint8_t *at = nullptr, *end = nullptr;
+};
+
 template <int VARIANT, int GB>
 __attribute__((target("avx512f,avx512bw,avx512vbmi"))) static inline void filter_block(
-    const uint8_t *rows, size_t stride, int M, const uint8_t *filt, uint16_t *acc) {
+    const uint8_t *rows, size_t stride, int M, const uint8_t *filt, uint16_t *acc,
+    PrefetchCursor *pf) {
   const __m512i lo8 = _mm512_set1_epi16(0x00ff);
   const __m512i bit6 = _mm512_set1_epi8(0x40);
   __m512i s[GB][4];
@@ -454,6 +462,11 @@ __attribute__((target("avx512f,avx512bw,avx512vbmi"))) static inline void filter
     for (int r = 0; r < 8; ++r)
       T[r] = _mm512_loadu_si512((const void *)(filt + (size_t)m * 512 + r * 64));
     const uint8_t *row = rows + (size_t)m * stride;
+    if (pf->at < pf->end) {
+#pragma unroll
+      for (int g = 0; g < GB; ++g) __builtin_prefetch(pf->at + 64 * g, 0, 2);
+      pf->at += 64 * GB;
+    }
 #pragma unroll
     for (int g = 0; g < GB; ++g) {
       const __m512i c = _mm512_loadu_si512((const void *)(row + (size_t)g * 64));
@@ -492,14 +505,15 @@ __attribute__((target("avx512f,avx512bw,avx512vbmi"))) static inline void filter
 
 template <int VARIANT>
 __attribute__((target("avx512f,avx512bw,avx512vbmi"))) static void filter_accumulate(
-    const uint8_t *rows, size_t stride, int M, int ng, const uint8_t *filt, uint16_t *acc) {
+    const uint8_t *rows, size_t stride, int M, int ng, const uint8_t *filt, uint16_t *acc,
+    PrefetchCursor *pf) {
   int g = 0;
   for (; g + 4 <= ng; g += 4)
-    filter_block<VARIANT, 4>(rows + (size_t)g * 64, stride, M, filt, acc + (size_t)g * 128);
+    filter_block<VARIANT, 4>(rows + (size_t)g * 64, stride, M, filt, acc + (size_t)g * 128, pf);
   switch (ng - g) {
-    case 3: filter_block<VARIANT, 3>(rows + (size_t)g * 64, stride, M, filt, acc + (size_t)g * 128); break;
-    case 2: filter_block<VARIANT, 2>(rows + (size_t)g * 64, stride, M, filt, acc + (size_t)g * 128); break;
-    case 1: filter_block<VARIANT, 1>(rows + (size_t)g * 64, stride, M, filt, acc + (size_t)g * 128); break;
+    case 3: filter_block<VARIANT, 3>(rows + (size_t)g * 64, stride, M, filt, acc + (size_t)g * 128, pf); break;
+    case 2: filter_block<VARIANT, 2>(rows + (size_t)g * 64, stride, M, filt, acc + (size_t)g * 128, pf); break;
+    case 1: filter_block<VARIANT, 1>(rows + (size_t)g * 64, stride, M, filt, acc + (size_t)g * 128, pf); break;
     default: break;
   }
 }
@@ -615,7 +629,7 @@ struct PlaneTables {
 };
 
 static void plane_scan_list(const HostIndexView &ix, const PlaneTables &tb, int e, int cl,
-                            int32_t bias_key, TopK &top) {
+                            int32_t bias_key, TopK &top, PrefetchCursor *pf) {
   const int64_t v0 = ix.list_offsets[cl], len = ix.list_offsets[cl + 1] - v0;
   const int64_t lpad = (len + 63) / 64 * 64;
   const uint8_t *base = ix.codes_t + ix.list_toff[cl];
@@ -660,9 +674,9 @@ static void plane_scan_list(const HostIndexView &ix, const PlaneTables &tb, int 
       if (g0 == ng) continue;
       const int64_t off = (int64_t)g0 * 64;
       if (g_plane_variant == 0)
-        filter_accumulate<0>(base + s0 + off, (size_t)lpad, ix.M, ng - g0, tb.filt, acc);
+        filter_accumulate<0>(base + s0 + off, (size_t)lpad, ix.M, ng - g0, tb.filt, acc, pf);
       else
-        filter_accumulate<1>(base + s0 + off, (size_t)lpad, ix.M, ng - g0, tb.filt, acc);
+        filter_accumulate<1>(base + s0 + off, (size_t)lpad, ix.M, ng - g0, tb.filt, acc, pf);
       const int n_hit = filter_survivors(acc, ng - g0, nv - off,
                                          (uint32_t)tb.filt_base + (uint32_t)bias_key,
                                          ix.pv ? pvq + off : nullptr, bound, gidx, gmask);
@@ -717,15 +731,15 @@ void cpu_scan_lists(const HostIndexView &ix, const int32_t *lut, int e, const fl
       bias_key = lut_quantize(
           residual_bias_host(ix.metric_ip, q, ix.centroids + (size_t)cl * ix.d, ix.d), e);
     if (planes_on) {
-      // the next list lies somewhere else in memory: ask for its first 64 KB now, so
-      // that the lines are on their way while this list is scanned
+      // the next list lies somewhere else in memory: its lines are requested one by
+      // one while this list is scanned
+      PrefetchCursor pf;
       if (c + 1 < n_clusters && clusters[c + 1] >= 0) {
         const int nx = clusters[c + 1];
-        const uint8_t *p0 = ix.codes_t + ix.list_toff[nx];
-        const int64_t nb = std::min<int64_t>(ix.list_toff[nx + 1] - ix.list_toff[nx], 64 << 10);
-        for (int64_t o = 0; o < nb; o += 64) __builtin_prefetch(p0 + o, 0, 2);
+        pf.at = ix.codes_t + ix.list_toff[nx];
+        pf.end = ix.codes_t + ix.list_toff[nx + 1];
       }
-      plane_scan_list(ix, tb, e, cl, bias_key, top);
+      plane_scan_list(ix, tb, e, cl, bias_key, top, &pf);
       continue;
     }
     for (int64_t v = ix.list_offsets[cl]; v < ix.list_offsets[cl + 1]; ++v) {

@@ -220,7 +220,11 @@ extern "C" int ivf_index_create(const ivf_index_desc_t *desc, void *dev_arena, s
       // column-major copy of the codes for the CPU's byte-plane scan of cold clusters
       ix->list_toff.resize((size_t)desc->nlist + 1);
       const int64_t bytes = cpu_transposed_bytes(v, ix->list_toff.data());
-      ix->codes_t.resize((size_t)bytes);
+      if (!ix->codes_t.alloc((size_t)bytes)) {
+        delete ix;
+        return fail(IVF_ENOMEM, "no host memory for the column-major code copy (%lld bytes)",
+                    (long long)bytes);
+      }
       cpu_transpose_codes(v, ix->list_toff.data(), ix->codes_t.data());
     }
   }

@@ -7,7 +7,9 @@
 #include <math.h>
 #include <stdarg.h>
 #include <stdio.h>
+#include <stdlib.h>
 #include <string.h>
+#include <sys/mman.h>
 
 #include <algorithm>
 #include <atomic>
@@ -27,6 +29,33 @@
 using namespace ivf;  // the C ABI files are the only users of this header
 
 #define IVF_INTERNAL __attribute__((visibility("hidden")))
+
+// A large host array that asks for 2 MB pages: the CPU scan reads lists of tens of
+// kilobytes at random places of a gigabyte, and with 4 KB pages nearly every list
+// starts with a run of TLB misses (which also make the hardware drop prefetches).
+struct HugeBytes {
+  uint8_t *p = nullptr;
+  size_t n = 0;
+  HugeBytes() = default;
+  HugeBytes(const HugeBytes &) = delete;
+  HugeBytes &operator=(const HugeBytes &) = delete;
+  ~HugeBytes() { ::free(p); }
+  bool alloc(size_t bytes) {
+    ::free(p);
+    p = nullptr;
+    n = 0;
+    if (bytes == 0) return true;
+    constexpr size_t kAlign = (size_t)2 << 20;
+    void *q = nullptr;
+    if (posix_memalign(&q, kAlign, (bytes + kAlign - 1) & ~(kAlign - 1)) != 0) return false;
+    (void)madvise(q, (bytes + kAlign - 1) & ~(kAlign - 1), MADV_HUGEPAGE);  // advice only
+    p = static_cast<uint8_t *>(q);
+    n = bytes;
+    return true;
+  }
+  bool empty() const { return n == 0; }
+  uint8_t *data() const { return p; }
+};
 
 // Sets the calling thread's error message (ivf_last_error) and returns code.
 IVF_INTERNAL int fail(int code, const char *fmt, ...) __attribute__((format(printf, 2, 3)));
@@ -149,7 +178,7 @@ struct ivf_index {
   std::vector<hipEvent_t> timing_pool;  // events with timing enabled, reused by timed batches
 
   std::vector<float> cb_t;  // codebooks, element-major (host table construction)
-  std::vector<uint8_t> codes_t;    // codes, column-major per list (byte-plane CPU scan), or empty
+  HugeBytes codes_t;               // codes, column-major per list (byte-plane CPU scan), or empty
   std::vector<int64_t> list_toff;  // start of each list in codes_t
 
   // residual encoding: per-vector term of L2 (host copy; also uploaded with the tiles)
