@@ -414,19 +414,30 @@ __attribute__((target("avx512f,avx512bw,avx512vbmi"))) static void plane_accumul
 // sums.  Every key that is compared with the result list's is therefore exact,
 // and results are the same with or without the filter.
 // ---------------------------------------------------------------------------
-// filt[(m * 2 + p) * 256 + j] = byte p of h_m(j); returns sum_m mn_m (mod 2^32)
-static int32_t build_filter(const int32_t *lut, int M, uint8_t *filt) {
+// filt[(m * 2 + p) * 256 + j] = byte p of h_m(j); returns sum_m mn_m (mod 2^32).
+// Only called on CPUs that run the byte-plane scan.
+__attribute__((target("avx512f,avx512bw"))) static int32_t build_filter(const int32_t *lut, int M,
+                                                                        uint8_t *filt) {
   uint32_t base = 0;
+  const __m512i cap = _mm512_set1_epi32(65535);
   for (int m = 0; m < M; ++m) {
     const int32_t *col = lut + (size_t)m * 256;
-    int32_t mn = col[0];
-    for (int j = 1; j < 256; ++j) mn = std::min(mn, col[j]);
+    __m512i x[16];
+    __m512i vmn = _mm512_loadu_si512((const void *)col);
+    x[0] = vmn;
+    for (int r = 1; r < 16; ++r) {
+      x[r] = _mm512_loadu_si512((const void *)(col + 16 * r));
+      vmn = _mm512_min_epi32(vmn, x[r]);
+    }
+    const int32_t mn = _mm512_reduce_min_epi32(vmn);
     base += (uint32_t)mn;
+    const __m512i bmn = _mm512_set1_epi32(mn);
     uint8_t *f = filt + (size_t)m * 512;
-    for (int j = 0; j < 256; ++j) {
-      const uint32_t h = std::min<uint32_t>(((uint32_t)col[j] - (uint32_t)mn) >> 8, 65535u);
-      f[j] = (uint8_t)h;
-      f[256 + j] = (uint8_t)(h >> 8);
+    for (int r = 0; r < 16; ++r) {
+      // (entry - mn) as an unsigned 32-bit value, its bits 8..23 saturated to 16 bits
+      const __m512i h = _mm512_min_epu32(_mm512_srli_epi32(_mm512_sub_epi32(x[r], bmn), 8), cap);
+      _mm_storeu_si128((__m128i *)(f + 16 * r), _mm512_cvtepi32_epi8(h));
+      _mm_storeu_si128((__m128i *)(f + 256 + 16 * r), _mm512_cvtepi32_epi8(_mm512_srli_epi32(h, 8)));
     }
   }
   return (int32_t)base;
