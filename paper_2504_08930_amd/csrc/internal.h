@@ -8,8 +8,8 @@
 namespace ivf {
 
 constexpr int kTileVecs = 64;      // vectors per code tile (one wavefront)
-constexpr int kMaxSlices = 128;    // scan blocks per query, upper bound (slices * k <= kMaxMergeCand)
-constexpr int kMaxMergeCand = 4096;  // candidates the per-query merge holds in LDS
+constexpr int kMaxSlices = 256;    // scan blocks per query, upper bound (slices * k <= kMaxMergeCand)
+constexpr int kMaxMergeCand = 8192;  // candidates the per-query merge holds in LDS (16 B each)
 // Partial-result rows (one per scan block of a sliced query) the workspace holds:
 // room for eight slices of every query of a full batch, and for kMaxSlices slices of
 // the small batches that need them to fill the chip.

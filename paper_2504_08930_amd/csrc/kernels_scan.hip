@@ -1653,7 +1653,7 @@ hipError_t launch_merge(const Shape &sh, const BatchWs &W, int nq, int slices, i
                         int64_t *out_ids, float *out_dists, hipStream_t st) {
   if (slices < 1 || slices > kMaxSlices || k > kMaxK || slices * k > kMaxMergeCand)
     return hipErrorInvalidValue;
-  const size_t lds = (size_t)slices * k * 16;  // at most 64 KB
+  const size_t lds = (size_t)slices * k * 16;  // at most 128 KB
   const float pvm = sh.scan_res() == 2 ? sh.pv_max : 0.0f;
   if (slices * k <= 1024) {
     hipLaunchKernelGGL(k_merge<256>, dim3(nq), dim3(256), lds, st, W.part_key, W.part_id, slices, k,
@@ -1663,7 +1663,7 @@ hipError_t launch_merge(const Shape &sh, const BatchWs &W, int nq, int slices, i
     static std::atomic<bool> attr_done{false};  // setting it twice is harmless
     if (!attr_done.load(std::memory_order_acquire)) {
       hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_merge<1024>),
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, 65536);
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, kMaxMergeCand * 16);
       if (e != hipSuccess) return e;
       attr_done.store(true, std::memory_order_release);
     }

@@ -454,7 +454,7 @@ def test_long_probe_lists(pkg, oracle, residual):
         index.load_partition(full)
         probe = index.coarse_probe_dev(qd, nprobe).cpu().numpy()
         base = None
-        for slices in (0, 1, 32):
+        for slices in (0, 1, 32, 256):
             index.set_tuning(scan_slices=slices)
             ids, dist = index.search_batch(q, nprobe, k)
             if base is None:
@@ -674,7 +674,7 @@ def test_random_long_probe_lists(pkg, oracle):
         nq = int(rng.choice([1, 3, 9, 40]))
         nprobe = int(rng.integers(257, min(2048, nlist) + 1))
         k = int(rng.choice([1, 10, 25, 100, 128]))
-        slices = int(rng.choice([0, 0, 1, 5, 32, 128]))
+        slices = int(rng.choice([0, 0, 1, 5, 32, 128, 256]))
         frac = float(rng.choice([0.0, 0.4, 1.0]))
         tag = (f"case {case}: bytes={cb} dsub={dsub} ip={ip} residual={residual} nlist={nlist} "
                f"n={n} nq={nq} nprobe={nprobe} k={k} slices={slices} resident={frac}")
