@@ -409,9 +409,9 @@ __attribute__((target("avx512f,avx512bw,avx512vbmi"))) static void plane_accumul
 // short of it by less than 256 per column unless an entry saturates (only the
 // largest entries of a column whose range passes 2^24 do, and they belong to
 // vectors far from the query).  h has two bytes, so the bound costs two byte
-// planes per column instead of four; a group of 64 vectors in which no bound
-// reaches the worst kept key is done, the few others get the exact four-plane
-// sums.  Every key that is compared with the result list's is therefore exact,
+// planes per column instead of four; a vector whose bound exceeds the worst kept
+// key is done, the few others get their exact sum by plain lookups in the row-major
+// codes.  Every key that is compared with the result list's is therefore exact,
 // and results are the same with or without the filter.
 // ---------------------------------------------------------------------------
 // filt[(m * 2 + p) * 256 + j] = byte p of h_m(j); returns sum_m mn_m (mod 2^32).
