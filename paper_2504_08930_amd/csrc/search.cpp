@@ -60,8 +60,10 @@ static int search_host_only(ivf_index *ix, const float *queries, int64_t nq, con
   std::vector<int64_t> ids((size_t)nq * k);
   std::vector<float> dists((size_t)nq * k);
   parallel_for(nq, [&](int64_t q) {
-    std::vector<int32_t> lut((size_t)view.M * 256);
-    std::vector<HostCand> cand(k);
+    thread_local std::vector<int32_t> lut;  // every entry is written before it is read
+    thread_local std::vector<HostCand> cand;
+    lut.resize((size_t)view.M * 256);
+    cand.resize((size_t)k);
     const float *qv = queries + (size_t)q * view.d;
     const int32_t *pr = probe + (size_t)q * nprobe;
     const int e = cpu_build_lut(view, qv, cpu_max_bias(view, qv, pr, nprobe), lut.data());
