@@ -119,6 +119,8 @@ static size_t plan_layout(const ivf_index_desc_t &d, int64_t resident_vectors, s
     w.lutmax = (uint32_t *)take(nq * 4);
     w.q_vecs = (int32_t *)take(nq * 4);
     w.order = (int32_t *)take(nq * 4);
+    w.heavy = (int32_t *)take(nq * 4);
+    w.hslot = (int32_t *)take(nq * 4);
     w.bias = (float *)take(nq * np * 4);
     w.g_bias = (float *)take(nq * np * 4);
     w.qbmax = (float *)take(nq * 4);

@@ -64,6 +64,8 @@ struct BatchWs {
   uint32_t *lutmax;        // [max_nq] bits of the largest |entry| of the query's table
   int32_t *q_vecs;         // [max_nq] vectors in the query's resident probes
   int32_t *order;          // [max_nq] scan visiting order of the queries
+  int32_t *heavy;          // [max_nq] the queries that get one more scan block than the others
+  int32_t *hslot;          // [max_nq] position of a query in heavy[], or -1
   float *bias;             // [max_nq][max_nprobe] residual encoding: bias(q, probe), probe order
   float *g_bias;           // [max_nq][max_nprobe] the same for resident probes, work-list order
   float *qbmax;            // [max_nq] largest |bias| among the query's probes (0 if unused)
@@ -165,19 +167,21 @@ hipError_t launch_lut(const Shape &sh, const float *q, int nq, const float *cbT,
                       uint32_t *lutpart, int *n_parts, void *q_parts, int32_t *q_exp,
                       hipStream_t st);
 
-// After the router: batch totals of the router counters, the scan's visiting order.
+// After the router: batch totals of the router counters, the scan's visiting order and,
+// with extra > 0, the `extra` queries with the most resident vectors (W.heavy, W.hslot).
 hipError_t launch_order(const BatchWs &W, int nq, int probe_stride, int M,
-                        unsigned long long *qstats, int count_stats, hipStream_t st);
+                        unsigned long long *qstats, int count_stats, int extra, hipStream_t st);
 
-// Returns hipErrorInvalidValue for an unsupported (M, k).  With slices == 1 the scan
-// writes the queries' results itself, as launch_merge would (same meaning of
-// out_ids / out_dists), and launch_merge is not needed.
+// Every query is scanned by `slices` blocks, the `extra` heaviest ones (launch_order) by
+// slices + 1.  Returns hipErrorInvalidValue for an unsupported (M, k).  A query scanned
+// by a single block gets its result written by that block, as launch_merge would (same
+// meaning of out_ids / out_dists); with slices == 1 and extra == 0 launch_merge is not needed.
 hipError_t launch_scan(const Shape &sh, const DevLayout &L, const BatchWs &W, int nq,
-                       int probe_stride, int slices, int k, int64_t *out_ids, float *out_dists,
-                       hipStream_t st);
+                       int probe_stride, int slices, int extra, int k, int64_t *out_ids,
+                       float *out_dists, hipStream_t st);
 
-// final != 0: write (id, dist) to out_ids/out_dists; else (key, id) to res_key/res_id.
-hipError_t launch_merge(const Shape &sh, const BatchWs &W, int nq, int slices, int k,
+// out_ids != NULL: write (id, dist) to out_ids/out_dists; else (key, id) to res_key/res_id.
+hipError_t launch_merge(const Shape &sh, const BatchWs &W, int nq, int slices, int extra, int k,
                         int64_t *out_ids, float *out_dists, hipStream_t st);
 
 // stage_pv / tile_pv may be NULL

@@ -522,7 +522,9 @@ __global__ __launch_bounds__(1024) void k_order(const int32_t *__restrict__ prob
                                                 const int32_t *__restrict__ g_n,
                                                 const int32_t *__restrict__ n_cold,
                                                 const int32_t *__restrict__ q_vecs, int M,
-                                                unsigned long long *qstats, int count_stats) {
+                                                unsigned long long *qstats, int count_stats,
+                                                int extra, int32_t *__restrict__ heavy,
+                                                int32_t *__restrict__ hslot) {
   __shared__ unsigned int bins[kOrderBins];
   __shared__ unsigned int wsum[16];
   __shared__ unsigned long long s_res[16], s_all[16], s_vec[16];
@@ -602,12 +604,28 @@ __global__ __launch_bounds__(1024) void k_order(const int32_t *__restrict__ prob
     const unsigned pos = atomicAdd(&bins[(unsigned)probe[(size_t)q * stride] % kOrderBins], 1u);
     order[pos] = q;
   }
+  // ---- the `extra` queries with the most resident vectors get one more scan block ----
+  // (small batches only: every thread ranks its queries by counting those that come
+  // before them, larger first and the smaller query number first among equals)
+  if (extra > 0) {
+    for (int q = tid; q < nq; q += 1024) {
+      const int mine = q_vecs[q];
+      int rank = 0;
+      for (int o = 0; o < nq; ++o) {
+        const int v = q_vecs[o];
+        rank += (v > mine || (v == mine && o < q)) ? 1 : 0;
+      }
+      hslot[q] = rank < extra ? rank : -1;
+      if (rank < extra) heavy[rank] = q;
+    }
+  }
 }
 
 hipError_t launch_order(const BatchWs &W, int nq, int probe_stride, int M,
-                        unsigned long long *qstats, int count_stats, hipStream_t st) {
+                        unsigned long long *qstats, int count_stats, int extra, hipStream_t st) {
+  if (extra < 0 || extra > nq) return hipErrorInvalidValue;
   hipLaunchKernelGGL(k_order, dim3(1), dim3(1024), 0, st, W.probe, nq, probe_stride, W.order,
-                     W.g_n, W.n_cold, W.q_vecs, M, qstats, count_stats);
+                     W.g_n, W.n_cold, W.q_vecs, M, qstats, count_stats, extra, W.heavy, W.hslot);
   return hipGetLastError();
 }
 
@@ -1002,6 +1020,11 @@ struct ScanParams {
   int nq;
   int probe_stride;
   int slices;
+  // `extra` queries (heavy[0 .. extra), hslot[q] = position there or -1) are cut into
+  // slices + 1 blocks instead of slices: their last block is unit nq * slices + hslot
+  int extra;
+  const int32_t *heavy;
+  const int32_t *hslot;
   int k;
 };
 
@@ -1053,9 +1076,12 @@ __global__ __launch_bounds__(NW * 64) void k_scan(ScanParams P) {
     const int within = jj % kScanChunk, cc = jj / kScanChunk;
     u = (cc * 8 + x) * kScanChunk + within;
   }
-  if (u >= P.nq * P.slices) return;
-  const int q = P.order[u / P.slices];
-  const int s = u % P.slices;
+  const int base_units = P.nq * P.slices;
+  if (u >= base_units + P.extra) return;
+  const int q = u < base_units ? P.order[u / P.slices] : P.heavy[u - base_units];
+  const int s = u < base_units ? u % P.slices : P.slices;
+  const int hs = P.extra ? P.hslot[q] : -1;
+  const int n_slices = P.slices + (hs >= 0 ? 1 : 0);  // blocks this query is cut into
   const int k = P.k;
 
   // scale of the query's fixed-point table
@@ -1075,8 +1101,8 @@ __global__ __launch_bounds__(NW * 64) void k_scan(ScanParams P) {
   const int32_t *gbase = P.g_base + (size_t)q * P.probe_stride;
   const int32_t *glen = P.g_len + (size_t)q * P.probe_stride;
   const int T = gpre[P.probe_stride];  // total tiles (the router keeps a copy in the last slot)
-  const int t_begin = (int)((long long)T * s / P.slices);
-  const int t_end = (int)((long long)T * (s + 1) / P.slices);
+  const int t_begin = (int)((long long)T * s / n_slices);
+  const int t_end = (int)((long long)T * (s + 1) / n_slices);
 
   // window of 64 probes held one per lane
   int win_base = -64, win_end = 0;  // win_end: first tile index beyond the window
@@ -1418,11 +1444,11 @@ __global__ __launch_bounds__(NW * 64) void k_scan(ScanParams P) {
   if (n <= 128) select_kth(std::integral_constant<int, 2>{});
   else select_kth(std::integral_constant<int, R>{});
   wave_sync();
-  const size_t obase = ((size_t)q * P.slices + s) * k;
+  const size_t obase = (s < P.slices ? (size_t)q * P.slices + s : (size_t)base_units + hs) * k;
   // rank-th best of this block: a partial result for k_merge, or, with one
   // slice per query, the query's result itself
   auto emit = [&](int rank, int key, long long id) {
-    if (P.slices > 1) {
+    if (n_slices > 1) {
       P.part_key[obase + rank] = key;
       P.part_id[obase + rank] = id;
       return;
@@ -1471,7 +1497,7 @@ static hipError_t launch_scan_t(const ScanParams &P, int nq, hipStream_t st) {
     if (e != hipSuccess) return e;
     attr_done.store(true, std::memory_order_release);
   }
-  const int total = nq * P.slices;
+  const int total = nq * P.slices + P.extra;
   const int grid = (total + 8 * kScanChunk - 1) / (8 * kScanChunk) * (8 * kScanChunk);
   hipLaunchKernelGGL((k_scan<M, NW, CAP, RES>), dim3(grid), dim3(NW * 64), lds, st, P);
   return hipGetLastError();
@@ -1485,9 +1511,10 @@ bool scan_supports(int M, int k) {
 }
 
 hipError_t launch_scan(const Shape &sh, const DevLayout &L, const BatchWs &W, int nq,
-                       int probe_stride, int slices, int k, int64_t *out_ids, float *out_dists,
-                       hipStream_t st) {
+                       int probe_stride, int slices, int extra, int k, int64_t *out_ids,
+                       float *out_dists, hipStream_t st) {
   if (!scan_supports(sh.M, k)) return hipErrorInvalidValue;
+  if (slices < 1 || extra < 0 || extra > nq) return hipErrorInvalidValue;
   ScanParams P;
   P.tile_codes = L.tile_codes;
   P.tile_ids = L.tile_ids;
@@ -1508,6 +1535,9 @@ hipError_t launch_scan(const Shape &sh, const DevLayout &L, const BatchWs &W, in
   P.metric_ip = sh.metric_ip;
   P.probe_stride = probe_stride;
   P.slices = slices;
+  P.extra = extra;
+  P.heavy = W.heavy;
+  P.hslot = W.hslot;
   P.k = k;
   P.qbmax = W.qbmax;
   P.g_bias = W.g_bias;
@@ -1555,22 +1585,30 @@ hipError_t launch_scan(const Shape &sh, const DevLayout &L, const BatchWs &W, in
 template <int NT>
 __global__ __launch_bounds__(NT) void k_merge(const int32_t *__restrict__ part_key,
                                               const int64_t *__restrict__ part_id, int slices,
-                                              int k, const uint32_t *__restrict__ lutmax,
+                                              int nq, const int32_t *__restrict__ hslot, int k,
+                                              const uint32_t *__restrict__ lutmax,
                                               const float *__restrict__ qbmax, float pv_max,
                                               int M, int metric_ip, int32_t *res_key, int64_t *res_id,
                                               int64_t *out_ids, float *out_dists) {
   extern __shared__ __align__(16) unsigned char merge_smem[];
-  const int n_in = slices * k;
+  const int q = blockIdx.x;
+  const int tid = threadIdx.x;
+  // the query's `slices` partial lists, plus one more (stored after those of all the
+  // queries) if it is one of the batch's heavy queries (hslot, optional)
+  const int hs = hslot ? hslot[q] : -1;
+  const int n_base = slices * k;
+  const int n_in = n_base + (hs >= 0 ? k : 0);
+  if (n_in == k) return;  // a single block scanned this query and wrote its result itself
   long long *mid = reinterpret_cast<long long *>(merge_smem);          // [n_in]
   int *mkey = reinterpret_cast<int *>(merge_smem + (size_t)n_in * 8);  // [n_in]
   int *fin = mkey + n_in;                                              // [n_in] finalists' indices
   __shared__ unsigned int hist[256];
   __shared__ unsigned int s_prefix, s_mask, s_need, s_nf;
-  const int q = blockIdx.x;
-  const int tid = threadIdx.x;
   for (int i = tid; i < n_in; i += NT) {
-    mkey[i] = part_key[(size_t)q * n_in + i];
-    mid[i] = (long long)part_id[(size_t)q * n_in + i];
+    const size_t src = i < n_base ? (size_t)q * n_base + i
+                                  : ((size_t)nq * slices + hs) * k + (i - n_base);
+    mkey[i] = part_key[src];
+    mid[i] = (long long)part_id[src];
   }
   if (tid == 0) {
     s_prefix = 0u;
@@ -1649,27 +1687,30 @@ __global__ __launch_bounds__(NT) void k_merge(const int32_t *__restrict__ part_k
   for (int r = nf + tid; r < k; r += NT) emit(r, kKeyInvalid, -1);
 }
 
-hipError_t launch_merge(const Shape &sh, const BatchWs &W, int nq, int slices, int k,
+hipError_t launch_merge(const Shape &sh, const BatchWs &W, int nq, int slices, int extra, int k,
                         int64_t *out_ids, float *out_dists, hipStream_t st) {
-  if (slices < 1 || slices > kMaxSlices || k > kMaxK || slices * k > kMaxMergeCand)
+  const int most = slices + (extra > 0 ? 1 : 0);  // partial lists of one query, at most
+  if (slices < 1 || most > kMaxSlices + 1 || k > kMaxK || most * k > kMaxMergeCand + kMaxK)
     return hipErrorInvalidValue;
-  const size_t lds = (size_t)slices * k * 16;  // at most 128 KB
+  const size_t lds = (size_t)most * k * 16;  // at most 130 KB
   const float pvm = sh.scan_res() == 2 ? sh.pv_max : 0.0f;
-  if (slices * k <= 1024) {
-    hipLaunchKernelGGL(k_merge<256>, dim3(nq), dim3(256), lds, st, W.part_key, W.part_id, slices, k,
-                       W.lutmax, W.qbmax, pvm, sh.M, sh.metric_ip, W.res_key, W.res_id, out_ids,
-                       out_dists);
+  const int32_t *hslot = extra > 0 ? W.hslot : nullptr;
+  if (most * k <= 1024) {
+    hipLaunchKernelGGL(k_merge<256>, dim3(nq), dim3(256), lds, st, W.part_key, W.part_id, slices, nq,
+                       hslot, k, W.lutmax, W.qbmax, pvm, sh.M, sh.metric_ip, W.res_key, W.res_id,
+                       out_ids, out_dists);
   } else {
     static std::atomic<bool> attr_done{false};  // setting it twice is harmless
     if (!attr_done.load(std::memory_order_acquire)) {
       hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_merge<1024>),
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, kMaxMergeCand * 16);
+                                         hipFuncAttributeMaxDynamicSharedMemorySize,
+                                         (kMaxMergeCand + kMaxK) * 16);
       if (e != hipSuccess) return e;
       attr_done.store(true, std::memory_order_release);
     }
     hipLaunchKernelGGL(k_merge<1024>, dim3(nq), dim3(1024), lds, st, W.part_key, W.part_id, slices,
-                       k, W.lutmax, W.qbmax, pvm, sh.M, sh.metric_ip, W.res_key, W.res_id, out_ids,
-                       out_dists);
+                       nq, hslot, k, W.lutmax, W.qbmax, pvm, sh.M, sh.metric_ip, W.res_key, W.res_id,
+                       out_ids, out_dists);
   }
   return hipGetLastError();
 }

@@ -18,11 +18,18 @@ static void emit_results(const ivf_index *ix, const HostCand *c, int k, int e, i
   }
 }
 
-static int pick_slices(const ivf_index *ix, const BatchCtx &c, int64_t nq, int nprobe, int k) {
+// How a batch's scan is cut into blocks: every query into `slices` blocks, the `extra`
+// queries with the most resident vectors into one more.
+struct ScanCut {
+  int slices;
+  int extra;
+};
+
+static ScanCut pick_slices(const ivf_index *ix, const BatchCtx &c, int64_t nq, int nprobe, int k) {
   // the workspace holds part_rows(max_nq) partial results of a launch
   const int room = (int)std::min<int64_t>(std::min<int64_t>(kMaxSlices, kMaxMergeCand / k),
                                           part_rows(ix->desc.max_nq) / nq);
-  if (ix->tune_slices > 0) return std::min(ix->tune_slices, std::max(room, 1));
+  if (ix->tune_slices > 0) return ScanCut{std::min(ix->tune_slices, std::max(room, 1)), 0};
   // One block per query fills the chip's 256 compute units (each holding one or two
   // scan blocks) from that many queries up.  Smaller batches are split; the number of
   // blocks per query is the one a small cost model likes best (in units of one tile's
@@ -32,22 +39,39 @@ static int pick_slices(const ivf_index *ix, const BatchCtx &c, int64_t nq, int n
   // every block costs a fixed overhead on top (it stages the query's table again and
   // ends with its own selection: about 8 us, forty tiles' worth; twice that for long
   // result lists).  Never so many that a block's wavefronts get fewer than two tiles each.
+  // A cut that leaves the last round part-full can be topped up: the queries with the
+  // most vectors get one block more, as many of them as it takes to fill the round,
+  // which also evens out the blocks' lengths (the model then takes a block's tiles as
+  // the batch's tiles over its blocks).
   const int per_cu = scan_blocks_per_cu(ix->sh.M, k);
-  const double fill = 256.0 * per_cu;
-  if ((double)nq > 1.25 * fill) return 1;
+  const int fill_i = 256 * per_cu;
+  const double fill = (double)fill_i;
+  if ((double)nq > 1.25 * fill) return ScanCut{1, 0};
   const int waves = per_cu == 2 ? 8 : 16;
   const double tiles = (double)nprobe * c.list_tiles;  // estimate per query
   const double overhead = k <= 48 ? 40.0 : 80.0;
   const int s_max = (int)std::min<double>(room, std::max(1.0, tiles / (2 * waves)));
-  int best = 1;
+  ScanCut best{1, 0};
   double best_cost = 0.0;
   for (int s = 1; s <= s_max; ++s) {
     const double r = (double)nq * s / fill;
     const double rounds = r <= 1.0 ? 1.0 : 0.5 * (r + ceil(r));
     const double cost = rounds * (tiles / s) + ceil(r) * overhead;
     if (s == 1 || cost < best_cost) {
-      best = s;
+      best = ScanCut{s, 0};
       best_cost = cost;
+    }
+    const int64_t units = nq * s;
+    const int extra = (int)((fill_i - units % fill_i) % fill_i);
+    if (extra > 0 && extra <= nq && (int64_t)(s + 1) * k <= kMaxMergeCand &&
+        s + 1 <= kMaxSlices && units + extra <= part_rows(ix->desc.max_nq)) {
+      const double full_rounds = (double)(units + extra) / fill;  // whole rounds, even blocks
+      const double cost_x = full_rounds * (tiles * (double)nq / (double)(units + extra)) +
+                            full_rounds * overhead;
+      if (cost_x < best_cost) {
+        best = ScanCut{s, extra};
+        best_cost = cost_x;
+      }
     }
   }
   return best;
@@ -270,7 +294,8 @@ int enqueue_gpu(ivf_index *ix, const SearchArgs &a, const BatchCtx &c, bool fina
                      W.g_prefix, W.g_n, W.cold, W.n_cold, W.q_vecs,
                      sh.by_residual ? W.bias : nullptr, W.g_bias, W.qbmax, L.hits, 1, W.lutpart,
                      lut_parts, W.lutmax, st));
-  G_TRY(launch_order(W, nq, np, sh.M, L.qstats, 1, st));
+  const ScanCut cut = c.any_resident ? pick_slices(ix, c, nq, np, k) : ScanCut{1, 0};
+  G_TRY(launch_order(W, nq, np, sh.M, L.qstats, 1, cut.extra, st));
   if (!final_on_gpu) {
     // cold probes go to the CPU (Section 4.2.1)
     G_TRY(hipMemcpyAsync(ix->h_ncold, W.n_cold, (size_t)nq * 4, hipMemcpyDeviceToHost, st));
@@ -282,7 +307,6 @@ int enqueue_gpu(ivf_index *ix, const SearchArgs &a, const BatchCtx &c, bool fina
   }
   if (c.any_resident) {
     // ---- stage 3: scan + top-k ----
-    const int slices = pick_slices(ix, c, nq, np, k);
     int64_t *oid = nullptr;
     float *od = nullptr;
     if (final_on_gpu) {
@@ -290,9 +314,10 @@ int enqueue_gpu(ivf_index *ix, const SearchArgs &a, const BatchCtx &c, bool fina
       od = a.out_device ? a.out_dists : W.out_dists;
     }
     G_TRY(mark(IVF_STAGE_SCAN));
-    G_TRY(launch_scan(sh, L, W, nq, np, slices, k, oid, od, st));
+    G_TRY(launch_scan(sh, L, W, nq, np, cut.slices, cut.extra, k, oid, od, st));
     G_TRY(mark(IVF_STAGE_MERGE));
-    if (slices > 1) G_TRY(launch_merge(sh, W, nq, slices, k, oid, od, st));
+    if (cut.slices > 1 || cut.extra > 0)
+      G_TRY(launch_merge(sh, W, nq, cut.slices, cut.extra, k, oid, od, st));
     G_TRY(mark(IVF_N_STAGES));
     if (!final_on_gpu) {
       G_TRY(hipMemcpyAsync(ix->h_reskey, W.res_key, (size_t)nq * k * 4, hipMemcpyDeviceToHost, st));

@@ -856,6 +856,25 @@ def test_c3_config_full_size(pkg, oracle):
                  f"min {st['min_hit_rate']:.3f}")
             assert np.array_equal(hyb[0], ids) and np.array_equal(hyb[1], dist), (nq, frac)
             assert 0.0 < st["mean_hit_rate"] < 1.0 and st["n_queries"] == nq
+    # Batches between the named sizes, which leave the chip's last round of scan blocks
+    # part-full: there the queries with the most resident vectors are cut into one more
+    # block than the others.  The result must be the one of one block per query, bit for
+    # bit, and match the oracle on a sample.
+    index.load_partition(full)
+    for nq in (100, 160, 200, 300):
+        qh = make_queries(spec, centers, nq=nq, seed=spec.seed_queries + nq)[0].cpu().numpy()
+        index.set_tuning(scan_slices=0)
+        ids, dist = index.search_batch(qh, spec.nprobe, spec.k)
+        index.set_tuning(scan_slices=1)
+        one = index.search_batch(qh, spec.nprobe, spec.k)
+        index.set_tuning(scan_slices=0)
+        assert np.array_equal(one[0], ids) and np.array_equal(one[1], dist), nq
+        probe = index.coarse_probe_dev(torch.from_numpy(qh).cuda(), spec.nprobe).cpu().numpy()
+        sel = np.arange(0, nq, max(1, nq // 24))
+        n_coarse, n_amb = _check_search(oracle, ix, qh[sel], spec.nprobe, spec.k, ids[sel],
+                                        dist[sel], probe[sel], stats=stats)
+        _say(f"C3 nq={nq}: coarse-ambiguous {n_coarse}, id-ambiguous {n_amb} of {len(sel)}")
+        assert n_coarse <= 1 and n_amb <= 1
     _say(f"C3: {stats.summary()}")
     index.close()
 
