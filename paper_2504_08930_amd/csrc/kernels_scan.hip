@@ -508,13 +508,16 @@ __global__ __launch_bounds__(kRouteBigThreads) void k_route_big(
   }
 }
 
-// One single-block kernel for the two small per-batch reductions between the
-// router and the scan:
+// One single-block kernel for the small per-batch steps between the router and
+// the scan:
 //  * batch totals of the router counters (same-address atomics from every
 //    query's wavefront would serialize);
 //  * the visiting order of the scan: queries grouped by their best cluster (a
 //    counting sort on the cluster id folded into kOrderBins bins; the order
-//    inside a group does not matter), histogram and offsets in LDS.
+//    inside a group does not matter), histogram and offsets in LDS;
+//  * for small batches whose scan blocks would leave the last round of the chip
+//    part-full: the `extra` queries with the most resident vectors, which the
+//    scan cuts into one block more than the others.
 constexpr int kOrderBins = 4096;
 
 __global__ __launch_bounds__(1024) void k_order(const int32_t *__restrict__ probe, int nq,
