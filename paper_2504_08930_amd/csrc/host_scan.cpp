@@ -443,31 +443,34 @@ __attribute__((target("avx512f,avx512bw"))) static int32_t build_filter(const in
   return (int32_t)base;
 }
 
-// acc[g][p][h]: for byte plane p of the filter values, the sums of the group's even
-// (h = 0) and odd (h = 1) vectors as 32 uint16 lanes (at most 128 columns x 255).
-// GB groups at a time keep their sixteen partial sums in registers while the
-// columns go by (a column's two byte tables are reloaded per block of groups instead:
-// eight loads from the cache per column against sixteen loads and sixteen stores of
-// partial sums).
-// pf (optional): a cursor through memory that will be read next (the rest of the
-// next list); one line of it is requested per line of codes read here, so the
-// requests are spread over the scan instead of arriving in one burst.
+// acc[group][p][h]: for byte plane p of the filter values, the sums over the columns
+// seen so far of the group's even (h = 0) and odd (h = 1) vectors as 32 uint16 lanes
+// (at most 128 columns x 255).  A block of up to four groups (numbers in gsel, groups
+// of 64 vectors counted from `rows`) keeps its sixteen partial sums in registers while
+// the columns m0 .. m1 - 1 go by (a column's two byte tables are reloaded per block of
+// groups instead: eight loads from the cache per column against sixteen loads and
+// sixteen stores of partial sums); with m0 > 0 the sums continue from what acc holds.
+// pf (optional): a cursor through memory that will be read next (the head of the next
+// list); one line of it is requested per line of codes read here, so the requests are
+// spread over the scan instead of arriving in one burst.
 struct PrefetchCursor {
   const uint8_t *at = nullptr, *end = nullptr;
 };
 
 template <int VARIANT, int GB>
 __attribute__((target("avx512f,avx512bw,avx512vbmi"))) static inline void filter_block(
-    const uint8_t *rows, size_t stride, int M, const uint8_t *filt, uint16_t *acc,
-    PrefetchCursor *pf) {
+    const uint8_t *rows, size_t stride, int m0, int m1, const int *gsel, const uint8_t *filt,
+    uint16_t *acc, PrefetchCursor *pf) {
   const __m512i lo8 = _mm512_set1_epi16(0x00ff);
   const __m512i bit6 = _mm512_set1_epi8(0x40);
   __m512i s[GB][4];
 #pragma unroll
   for (int g = 0; g < GB; ++g)
 #pragma unroll
-    for (int r = 0; r < 4; ++r) s[g][r] = _mm512_setzero_si512();
-  for (int m = 0; m < M; ++m) {
+    for (int r = 0; r < 4; ++r)
+      s[g][r] = m0 > 0 ? _mm512_loadu_si512((const void *)(acc + (size_t)gsel[g] * 128 + r * 32))
+                       : _mm512_setzero_si512();
+  for (int m = m0; m < m1; ++m) {
     __m512i T[8];
 #pragma unroll
     for (int r = 0; r < 8; ++r)
@@ -480,7 +483,7 @@ __attribute__((target("avx512f,avx512bw,avx512vbmi"))) static inline void filter
     }
 #pragma unroll
     for (int g = 0; g < GB; ++g) {
-      const __m512i c = _mm512_loadu_si512((const void *)(row + (size_t)g * 64));
+      const __m512i c = _mm512_loadu_si512((const void *)(row + (size_t)gsel[g] * 64));
       const __mmask64 b7 = _mm512_movepi8_mask(c);  // codes 128..255
       __mmask64 k1 = 0, k2 = 0, k3 = 0;
       if (VARIANT == 1) {
@@ -511,39 +514,44 @@ __attribute__((target("avx512f,avx512bw,avx512vbmi"))) static inline void filter
   for (int g = 0; g < GB; ++g)
 #pragma unroll
     for (int r = 0; r < 4; ++r)
-      _mm512_storeu_si512((void *)(acc + (size_t)g * 128 + r * 32), s[g][r]);
+      _mm512_storeu_si512((void *)(acc + (size_t)gsel[g] * 128 + r * 32), s[g][r]);
 }
 
+// Columns m0 .. m1 - 1 for the n listed groups.
 template <int VARIANT>
 __attribute__((target("avx512f,avx512bw,avx512vbmi"))) static void filter_accumulate(
-    const uint8_t *rows, size_t stride, int M, int ng, const uint8_t *filt, uint16_t *acc,
-    PrefetchCursor *pf) {
+    const uint8_t *rows, size_t stride, int m0, int m1, const int *gsel, int n,
+    const uint8_t *filt, uint16_t *acc, PrefetchCursor *pf) {
   int g = 0;
-  for (; g + 4 <= ng; g += 4)
-    filter_block<VARIANT, 4>(rows + (size_t)g * 64, stride, M, filt, acc + (size_t)g * 128, pf);
-  switch (ng - g) {
-    case 3: filter_block<VARIANT, 3>(rows + (size_t)g * 64, stride, M, filt, acc + (size_t)g * 128, pf); break;
-    case 2: filter_block<VARIANT, 2>(rows + (size_t)g * 64, stride, M, filt, acc + (size_t)g * 128, pf); break;
-    case 1: filter_block<VARIANT, 1>(rows + (size_t)g * 64, stride, M, filt, acc + (size_t)g * 128, pf); break;
+  for (; g + 4 <= n; g += 4)
+    filter_block<VARIANT, 4>(rows, stride, m0, m1, gsel + g, filt, acc, pf);
+  switch (n - g) {
+    case 3: filter_block<VARIANT, 3>(rows, stride, m0, m1, gsel + g, filt, acc, pf); break;
+    case 2: filter_block<VARIANT, 2>(rows, stride, m0, m1, gsel + g, filt, acc, pf); break;
+    case 1: filter_block<VARIANT, 1>(rows, stride, m0, m1, gsel + g, filt, acc, pf); break;
     default: break;
   }
 }
 
-// The groups (of the ng in acc) in which some vector's lower bound, plus add (the
-// table's base and the list's bias) and the vector's own term pvq (or NULL), does
-// not exceed bound; nv = vectors in the ng groups (the last group may be ragged).
-// Returns how many, their numbers in gidx and, per such group, the vectors in
-// question as a bit mask (bit i = vector i of the group) in gmask.
+// Of the n groups listed in gsel, those in which some vector's lower bound (256 x the
+// partial sums in acc, plus add: the table's base and the list's bias, plus the
+// vector's own term pvq, or NULL) does not exceed bound; nv = vectors from `rows` on
+// (the last group may be ragged).  The list is compacted in place; per remaining group
+// the vectors in question come back as a bit mask (bit i = vector i of the group) in
+// gmask.  Returns how many remain.  The bound is valid whichever columns acc covers so
+// far: the base counts every column's smallest entry, and a column not yet seen adds
+// nothing below that.
 __attribute__((target("avx512f,avx512bw,avx512vbmi,bmi2"))) static int filter_survivors(
-    const uint16_t *acc, int ng, int64_t nv, uint32_t add, const int32_t *pvq, int32_t bound,
-    int *gidx, uint64_t *gmask) {
+    const uint16_t *acc, int *gsel, int n, int64_t nv, uint32_t add, const int32_t *pvq,
+    int32_t bound, uint64_t *gmask) {
   const __m512i vadd = _mm512_set1_epi32((int)add);
   const __m512i vbound = _mm512_set1_epi32(bound);
   const __m512i lane = _mm512_set_epi32(15, 14, 13, 12, 11, 10, 9, 8, 7, 6, 5, 4, 3, 2, 1, 0);
   const __m512i idx_even = _mm512_slli_epi32(lane, 1);                       // 0, 2, ..., 30
   const __m512i idx_odd = _mm512_add_epi32(idx_even, _mm512_set1_epi32(1));  // 1, 3, ..., 31
-  int n = 0;
-  for (int g = 0; g < ng; ++g) {
+  int kept = 0;
+  for (int j = 0; j < n; ++j) {
+    const int g = gsel[j];
     const uint16_t *a = acc + (size_t)g * 128;
     const int left = (int)std::min<int64_t>(64, nv - (int64_t)g * 64);  // vectors of this group
     uint64_t any = 0;
@@ -571,11 +579,11 @@ __attribute__((target("avx512f,avx512bw,avx512vbmi,bmi2"))) static int filter_su
       any |= (_pdep_u64(me, 0x55555555ull) | _pdep_u64(mo, 0xaaaaaaaaull)) << (32 * h2);
     }
     if (any) {
-      gidx[n] = g;
-      gmask[n++] = any;
+      gsel[kept] = g;
+      gmask[kept++] = any;
     }
   }
-  return n;
+  return kept;
 }
 
 // int32 sums in vector order from the partial sums of plane_accumulate
@@ -683,15 +691,29 @@ static void plane_scan_list(const HostIndexView &ix, const PlaneTables &tb, int 
         for (int64_t i = (int64_t)g0 * 64; i < i1; ++i) exact_offer(s0, i, bound);
       }
       if (g0 == ng) continue;
+      // The columns are taken in four stretches (an eighth, a quarter, a half, all of
+      // them); after each, the groups in which every vector's bound already exceeds
+      // the worst kept key are dropped, and the rows of the remaining columns are
+      // never read for them.
       const int64_t off = (int64_t)g0 * 64;
-      if (g_plane_variant == 0)
-        filter_accumulate<0>(base + s0 + off, (size_t)lpad, ix.M, ng - g0, tb.filt, acc, pf);
-      else
-        filter_accumulate<1>(base + s0 + off, (size_t)lpad, ix.M, ng - g0, tb.filt, acc, pf);
-      const int n_hit = filter_survivors(acc, ng - g0, nv - off,
-                                         (uint32_t)tb.filt_base + (uint32_t)bias_key,
-                                         ix.pv ? pvq + off : nullptr, bound, gidx, gmask);
-      for (int j = 0; j < n_hit; ++j) {
+      int n_alive = ng - g0;
+      for (int g = 0; g < n_alive; ++g) gidx[g] = g;
+      const int M = ix.M;
+      const int stops[4] = {std::max(4, M / 8), M / 4, M / 2, M};
+      int m0 = 0;
+      for (int p = 0; p < 4 && n_alive > 0; ++p) {
+        const int m1 = stops[p];
+        if (m1 <= m0) continue;
+        if (g_plane_variant == 0)
+          filter_accumulate<0>(base + s0 + off, (size_t)lpad, m0, m1, gidx, n_alive, tb.filt, acc, pf);
+        else
+          filter_accumulate<1>(base + s0 + off, (size_t)lpad, m0, m1, gidx, n_alive, tb.filt, acc, pf);
+        n_alive = filter_survivors(acc, gidx, n_alive, nv - off,
+                                   (uint32_t)tb.filt_base + (uint32_t)bias_key,
+                                   ix.pv ? pvq + off : nullptr, bound, gmask);
+        m0 = m1;
+      }
+      for (int j = 0; j < n_alive; ++j) {
         const int64_t i0 = off + (int64_t)gidx[j] * 64;
         for (uint64_t mk = gmask[j]; mk; mk &= mk - 1)
           exact_offer(s0, i0 + __builtin_ctzll(mk), bound);
@@ -747,8 +769,10 @@ void cpu_scan_lists(const HostIndexView &ix, const int32_t *lut, int e, const fl
       PrefetchCursor pf;
       if (c + 1 < n_clusters && clusters[c + 1] >= 0) {
         const int nx = clusters[c + 1];
+        // its first stretch of columns: the rest is rarely read
+        const int64_t rows_bytes = (ix.list_toff[nx + 1] - ix.list_toff[nx]) / ix.M;
         pf.at = ix.codes_t + ix.list_toff[nx];
-        pf.end = ix.codes_t + ix.list_toff[nx + 1];
+        pf.end = pf.at + rows_bytes * std::max(4, ix.M / 8);
       }
       plane_scan_list(ix, tb, e, cl, bias_key, top, &pf);
       continue;
