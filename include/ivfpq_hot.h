@@ -321,8 +321,9 @@ int ivf_resident_info(ivf_index_t *index, int32_t *n_clusters, int64_t *n_vector
  * add the same integers and return identical results.  The environment
  * variable IVF_HOST_SCAN=scalar, read by ivf_index_create, selects form 0.
  * Form 1 first bounds every vector's sum from below with two of the four byte
- * planes and forms exact sums only for vectors the bound does not rule out
- * (same results; IVF_HOST_FILTER=0, read at every search, turns the bound off).
+ * planes of a growing share of the columns and forms exact sums only for
+ * vectors the bound does not rule out (same results; IVF_HOST_FILTER=0, read
+ * at every search, turns the bound off).
  * Negative on error.
  */
 int ivf_host_scan_form(const ivf_index_t *index);

@@ -413,6 +413,12 @@ __attribute__((target("avx512f,avx512bw,avx512vbmi"))) static void plane_accumul
 // key is done, the few others get their exact sum by plain lookups in the row-major
 // codes.  Every key that is compared with the result list's is therefore exact,
 // and results are the same with or without the filter.
+// The inequality also holds with the sum over any subset of the columns (a column
+// left out adds nothing below its mn_m, which the base already counts), so the pass
+// adds the columns in stretches and drops a group of 64 vectors as soon as all of
+// its bounds exceed the worst kept key: for the cold lists of a hybrid batch, which
+// mostly lie far from the query, the first eighth of the columns settles nearly
+// every group, and the rows of the other columns are never read.
 // ---------------------------------------------------------------------------
 // filt[(m * 2 + p) * 256 + j] = byte p of h_m(j); returns sum_m mn_m (mod 2^32).
 // Only called on CPUs that run the byte-plane scan.
