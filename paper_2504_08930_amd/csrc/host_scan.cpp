@@ -770,16 +770,26 @@ void cpu_scan_lists(const HostIndexView &ix, const int32_t *lut, int e, const fl
       bias_key = lut_quantize(
           residual_bias_host(ix.metric_ip, q, ix.centroids + (size_t)cl * ix.d, ix.d), e);
     if (planes_on) {
-      // the next list lies somewhere else in memory: its lines are requested one by
-      // one while this list is scanned
-      PrefetchCursor pf;
-      if (c + 1 < n_clusters && clusters[c + 1] >= 0) {
-        const int nx = clusters[c + 1];
-        // its first stretch of columns: the rest is rarely read
-        const int64_t rows_bytes = (ix.list_toff[nx + 1] - ix.list_toff[nx]) / ix.M;
-        pf.at = ix.codes_t + ix.list_toff[nx];
-        pf.end = pf.at + rows_bytes * std::max(4, ix.M / 8);
+      // The lists lie at unrelated places in memory.  The head of a list (its first
+      // stretch of columns: the rest is rarely read) is requested two lists ahead, one
+      // line per line of codes read meanwhile; the first two are requested at once.
+      constexpr int kAhead = 2;
+      auto head_of = [&](int list, const uint8_t **at, const uint8_t **end) {
+        const int64_t row_bytes = (ix.list_toff[list + 1] - ix.list_toff[list]) / ix.M;
+        *at = ix.codes_t + ix.list_toff[list];
+        *end = *at + row_bytes * std::max(4, ix.M / 8);
+      };
+      if (c == 0) {
+        for (int a = 0; a < kAhead && a < n_clusters; ++a) {
+          if (clusters[a] < 0) continue;
+          const uint8_t *at, *end;
+          head_of(clusters[a], &at, &end);
+          for (; at < end; at += 64) __builtin_prefetch(at, 0, 2);
+        }
       }
+      PrefetchCursor pf;
+      if (c + kAhead < n_clusters && clusters[c + kAhead] >= 0)
+        head_of(clusters[c + kAhead], &pf.at, &pf.end);
       plane_scan_list(ix, tb, e, cl, bias_key, top, &pf);
       continue;
     }
