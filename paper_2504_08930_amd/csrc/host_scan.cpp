@@ -220,31 +220,73 @@ static void lut_column(int kind, const float *q, const float *ct, int dsub, int 
   for (int j0 = 0; j0 < n; j0 += 64) lut_column_block<64>(kind, q, ct + j0, dsub, n, out + j0);
 }
 
-int cpu_build_lut(const HostIndexView &ix, const float *q, float max_bias, int32_t *lut) {
-  const int M = ix.M, dsub = ix.dsub;
-  const int kind = ix.metric_ip ? kLutIP : (ix.by_residual ? kLutL2Res : kLutL2);
-  const size_t n = (size_t)M * 256;
-  thread_local std::vector<float> f, t;
-  f.resize(n);
-  if (ix.nbits == 8) {
-    for (int m = 0; m < M; ++m)
-      lut_column(kind, q + (size_t)m * dsub, ix.codebooks_t + (size_t)m * dsub * 256, dsub, 256,
-                 &f[(size_t)m * 256]);
-  } else {
-    // 16 entries per sub-quantizer, then one 256-entry column per code byte
-    t.resize((size_t)ix.msub * 16);
-    for (int s = 0; s < ix.msub; ++s)
-      lut_column(kind, q + (size_t)s * dsub, ix.codebooks_t + (size_t)s * dsub * 16, dsub, 16,
-                 &t[(size_t)s * 16]);
-    for (int m = 0; m < M; ++m) {
-      const float *lo = &t[(size_t)(2 * m) * 16], *hi = &t[(size_t)(2 * m + 1) * 16];
-      float *col = &f[(size_t)m * 256];
-      for (int jh = 0; jh < 16; ++jh)
-        for (int jl = 0; jl < 16; ++jl) col[jh * 16 + jl] = lut_pair_entry(lo[jl], hi[jh]);
+// The 256 entries of one column for NQ queries at once, with 512-bit vectors: the
+// codewords (the larger operand: 256 x dsub floats per column, 786 KB per table at
+// 768 dimensions) are read once for all of them.  Every lane does lut_entry's
+// operations in lut_entry's order, hence the same bits.
+// mx[b]: sixteen running maxima of |entry| per query (a NaN entry is skipped, as fmaxf
+// skips it on the device).
+template <int NQ>
+__attribute__((target("avx512f"))) static void lut_column_wide(int kind, const float *const *q,
+                                                               const float *ct, int dsub,
+                                                               float *const *out, __m512 *mx) {
+  const __m512 sc = _mm512_set1_ps(kind == kLutIP ? -1.0f : -2.0f);  // exact either way
+  for (int j0 = 0; j0 < 256; j0 += 64) {
+    __m512 acc[NQ][4];
+#pragma unroll
+    for (int b = 0; b < NQ; ++b)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) acc[b][i] = _mm512_setzero_ps();
+    for (int t = 0; t < dsub; ++t) {
+      __m512 c[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) c[i] = _mm512_loadu_ps(ct + (size_t)t * 256 + j0 + 16 * i);
+#pragma unroll
+      for (int b = 0; b < NQ; ++b) {
+        const __m512 qt = _mm512_set1_ps(q[b][t]);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          if (kind != kLutL2) {
+            acc[b][i] = _mm512_fmadd_ps(qt, c[i], acc[b][i]);
+          } else {
+            const __m512 diff = _mm512_sub_ps(qt, c[i]);
+            acc[b][i] = _mm512_fmadd_ps(diff, diff, acc[b][i]);
+          }
+        }
+      }
     }
+#pragma unroll
+    for (int b = 0; b < NQ; ++b)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const __m512 v = kind != kLutL2 ? _mm512_mul_ps(sc, acc[b][i]) : acc[b][i];
+        _mm512_storeu_ps(out[b] + j0 + 16 * i, v);
+        mx[b] = _mm512_max_ps(_mm512_abs_ps(v), mx[b]);  // (a > mx) ? a : mx, lane by lane
+      }
   }
-  // largest |entry|: sixteen running maxima so that the loop vectorizes (a
-  // NaN entry is skipped, as fmaxf skips it on the device)
+}
+
+// The float table in fixed point with exponent e, 512 bits at a time (lut_quantize
+// lane by lane: the scaling as an exact product, round to nearest even, 0 for what
+// does not fit).
+__attribute__((target("avx512f"))) static void lut_quantize_wide(const float *f, size_t n, int e,
+                                                                 int32_t *lut) {
+  const __m512 scale = _mm512_set1_ps(ldexpf(1.0f, e));
+  const __m512 lim = _mm512_set1_ps(2147483520.0f);
+  for (size_t i = 0; i < n; i += 16) {
+    const __m512 r = _mm512_roundscale_ps(_mm512_mul_ps(_mm512_loadu_ps(f + i), scale),
+                                          _MM_FROUND_TO_NEAREST_INT | _MM_FROUND_NO_EXC);
+    const __mmask16 ok = _mm512_cmp_ps_mask(_mm512_abs_ps(r), lim, _CMP_LT_OQ);
+    _mm512_storeu_si512((void *)(lut + i), _mm512_maskz_cvttps_epi32(ok, r));
+  }
+}
+
+// Largest |entry| of the float table f, the scale exponent it gives, and the table in
+// fixed point.
+static int lut_finish(const HostIndexView &ix, const float *f, float max_bias, int32_t *lut) {
+  const size_t n = (size_t)ix.M * 256;
+  // sixteen running maxima so that the loop vectorizes (a NaN entry is skipped, as
+  // fmaxf skips it on the device)
   float lane_mx[16];
   for (int l = 0; l < 16; ++l) lane_mx[l] = 0.0f;
   for (size_t i = 0; i < n; i += 16)
@@ -254,7 +296,7 @@ int cpu_build_lut(const HostIndexView &ix, const float *q, float max_bias, int32
     }
   float mx = 0.0f;
   for (int l = 0; l < 16; ++l) mx = std::max(mx, lane_mx[l]);
-  const int e = lut_exponent(mx, M, max_bias, ix.pv ? ix.pv_max : 0.0f);
+  const int e = lut_exponent(mx, ix.M, max_bias, ix.pv ? ix.pv_max : 0.0f);
   // lut_quantize with the scaling written as a product: |e| <= 60, so 2^e is a
   // normal float and v * 2^e rounds exactly as ldexpf(v, e) does
   const float scale = ldexpf(1.0f, e);
@@ -262,6 +304,76 @@ int cpu_build_lut(const HostIndexView &ix, const float *q, float max_bias, int32
     const float r = __builtin_rintf(f[i] * scale);
     lut[i] = __builtin_fabsf(r) < 2147483520.0f ? (int)r : 0;
   }
+  return e;
+}
+
+// 8-bit codes on a CPU with AVX-512: columns, largest |entry| and fixed point, for one
+// query (q1 == NULL) or two.  f: 2 * M * 256 floats of scratch.
+__attribute__((target("avx512f"))) static void lut_pair_wide(
+    const HostIndexView &ix, int kind, const float *q0, const float *q1, float max_bias0,
+    float max_bias1, float *f, int32_t *lut0, int32_t *lut1, int *e0, int *e1) {
+  const int M = ix.M, dsub = ix.dsub;
+  const size_t n = (size_t)M * 256;
+  __m512 mx[2] = {_mm512_setzero_ps(), _mm512_setzero_ps()};
+  for (int m = 0; m < M; ++m) {
+    const float *qm[2] = {q0 + (size_t)m * dsub, q1 ? q1 + (size_t)m * dsub : nullptr};
+    float *om[2] = {f + (size_t)m * 256, f + n + (size_t)m * 256};
+    const float *ct = ix.codebooks_t + (size_t)m * dsub * 256;
+    if (q1) lut_column_wide<2>(kind, qm, ct, dsub, om, mx);
+    else lut_column_wide<1>(kind, qm, ct, dsub, om, mx);
+  }
+  const float pvm = ix.pv ? ix.pv_max : 0.0f;
+  *e0 = lut_exponent(_mm512_reduce_max_ps(mx[0]), M, max_bias0, pvm);
+  lut_quantize_wide(f, n, *e0, lut0);
+  if (q1) {
+    *e1 = lut_exponent(_mm512_reduce_max_ps(mx[1]), M, max_bias1, pvm);
+    lut_quantize_wide(f + n, n, *e1, lut1);
+  }
+}
+
+void cpu_build_lut_pair(const HostIndexView &ix, const float *q0, const float *q1, float max_bias0,
+                        float max_bias1, int32_t *lut0, int32_t *lut1, int *e0, int *e1) {
+  const int M = ix.M, dsub = ix.dsub;
+  const int kind = ix.metric_ip ? kLutIP : (ix.by_residual ? kLutL2Res : kLutL2);
+  const size_t n = (size_t)M * 256;
+  static const bool wide = __builtin_cpu_supports("avx512f");
+  thread_local std::vector<float> f, t;
+  f.resize(2 * n);
+  const float *qs[2] = {q0, q1};
+  const int nb = q1 ? 2 : 1;
+  if (ix.nbits == 8 && wide) {
+    lut_pair_wide(ix, kind, q0, q1, max_bias0, max_bias1, f.data(), lut0, lut1, e0, e1);
+    return;
+  } else {
+    for (int b = 0; b < nb; ++b) {
+      const float *q = qs[b];
+      float *fb = &f[(size_t)b * n];
+      if (ix.nbits == 8) {
+        for (int m = 0; m < M; ++m)
+          lut_column(kind, q + (size_t)m * dsub, ix.codebooks_t + (size_t)m * dsub * 256, dsub, 256,
+                     fb + (size_t)m * 256);
+      } else {
+        // 16 entries per sub-quantizer, then one 256-entry column per code byte
+        t.resize((size_t)ix.msub * 16);
+        for (int s2 = 0; s2 < ix.msub; ++s2)
+          lut_column(kind, q + (size_t)s2 * dsub, ix.codebooks_t + (size_t)s2 * dsub * 16, dsub, 16,
+                     &t[(size_t)s2 * 16]);
+        for (int m = 0; m < M; ++m) {
+          const float *lo = &t[(size_t)(2 * m) * 16], *hi = &t[(size_t)(2 * m + 1) * 16];
+          float *col = fb + (size_t)m * 256;
+          for (int jh = 0; jh < 16; ++jh)
+            for (int jl = 0; jl < 16; ++jl) col[jh * 16 + jl] = lut_pair_entry(lo[jl], hi[jh]);
+        }
+      }
+    }
+  }
+  *e0 = lut_finish(ix, &f[0], max_bias0, lut0);
+  if (q1) *e1 = lut_finish(ix, &f[n], max_bias1, lut1);
+}
+
+int cpu_build_lut(const HostIndexView &ix, const float *q, float max_bias, int32_t *lut) {
+  int e = 0;
+  cpu_build_lut_pair(ix, q, nullptr, max_bias, 0.0f, lut, nullptr, &e, nullptr);
   return e;
 }
 

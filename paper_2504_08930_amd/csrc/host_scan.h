@@ -87,6 +87,10 @@ void cpu_transpose_codebooks(const HostIndexView &ix, float *out);
 // sub-quantizers packed in that byte, formed before quantization); max_bias: largest |bias| among
 // ALL of the query's probes (resident or not).  Returns the scale exponent.
 int cpu_build_lut(const HostIndexView &ix, const float *q, float max_bias, int32_t *lut);
+// The same for two queries at once (q1 may be NULL: one query): the codebooks, the
+// larger operand, are read once for both.  Same tables, bit for bit.
+void cpu_build_lut_pair(const HostIndexView &ix, const float *q0, const float *q1, float max_bias0,
+                        float max_bias1, int32_t *lut0, int32_t *lut1, int *e0, int *e1);
 
 // True if this CPU runs the byte-plane scan (AVX-512 VBMI) and the environment
 // does not ask for the plain loop (IVF_HOST_SCAN=scalar, read at every call).

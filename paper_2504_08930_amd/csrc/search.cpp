@@ -465,19 +465,31 @@ static int search_device(ivf_index *ix, const SearchArgs &a) {
     sync_err = hipStreamSynchronize(st);  // the device's partial results are on the host
     if (sync_err == hipSuccess) gpu_ready.store(1, std::memory_order_release);
   };
-  parallel_for(nq, [&](int64_t q) {
-    const int nc = ix->h_ncold[q];
-    if (nc == 0 && any_resident) return;
+  // two queries per work item: their tables are built together (the codebooks are read
+  // once for both), then each is scanned
+  parallel_for((nq + 1) / 2, [&](int64_t item) {
     thread_local std::vector<int32_t> lut;
-    lut.resize((size_t)view.M * 256);
-    const float *qv = hq + (size_t)q * view.d;
-    const int e = cpu_build_lut(view, qv, ix->h_qbmax[q], lut.data());
-    cpu_e[(size_t)q] = e;
-    int32_t cap = kKeyInvalid;
-    if (any_resident && gpu_ready.load(std::memory_order_acquire))
-      cap = device_key_cap(ix, view, q, k, e);
-    cpu_scan_lists(view, lut.data(), e, qv, ix->h_cold + (size_t)q * np, nc, k,
-                   &cpu_res[(size_t)q * k], nullptr, cap);
+    lut.resize((size_t)view.M * 512);
+    int64_t qs[2];
+    int n_act = 0;
+    for (int64_t q = 2 * item; q < std::min<int64_t>(nq, 2 * item + 2); ++q)
+      if (ix->h_ncold[q] > 0 || !any_resident) qs[n_act++] = q;
+    if (n_act == 0) return;
+    int32_t *luts[2] = {lut.data(), lut.data() + (size_t)view.M * 256};
+    int es[2] = {0, 0};
+    cpu_build_lut_pair(view, hq + (size_t)qs[0] * view.d,
+                       n_act == 2 ? hq + (size_t)qs[1] * view.d : nullptr, ix->h_qbmax[qs[0]],
+                       n_act == 2 ? ix->h_qbmax[qs[1]] : 0.0f, luts[0], luts[1], &es[0], &es[1]);
+    for (int a = 0; a < n_act; ++a) {
+      const int64_t q = qs[a];
+      const int e = es[a];
+      cpu_e[(size_t)q] = e;
+      int32_t cap = kKeyInvalid;
+      if (any_resident && gpu_ready.load(std::memory_order_acquire))
+        cap = device_key_cap(ix, view, q, k, e);
+      cpu_scan_lists(view, luts[a], e, hq + (size_t)q * view.d, ix->h_cold + (size_t)q * np,
+                     ix->h_ncold[q], k, &cpu_res[(size_t)q * k], nullptr, cap);
+    }
   }, &wait_gpu);
   S_TRY(sync_err);
   end_batch(ix, ctx, st, false);
