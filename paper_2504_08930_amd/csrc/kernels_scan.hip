@@ -287,7 +287,7 @@ __global__ __launch_bounds__(256) void k_route(
       gp[o] = tiles + incl - nt;
       if (bias) g_bias[(size_t)q * stride + o] = b;
     }
-    if (cld) cd[nc + __popcll(mcold & lt)] = c;
+    if (cld && n2 == 0) cd[nc + __popcll(mcold & lt)] = c;  // n2 > 0: written below
     // wave totals
     long long lv = res ? len : 0;
 #pragma unroll
@@ -297,6 +297,21 @@ __global__ __launch_bounds__(256) void k_route(
     ng += __popcll(mres);
     nc += __popcll(mcold);
     valid_n += __popcll(__ballot(valid));
+  }
+  if (n2 > 0) {
+    // The cold list goes to the CPU in the order of the probe list, best cluster
+    // first (the cluster-id order above only serves the device's lists): the CPU scan
+    // then meets the query's nearest cold lists first and rejects most of the others
+    // against what it found there.
+    int at = 0;
+    for (int base = 0; base < nprobe; base += 64) {
+      const int p = base + lane;
+      const int c = p < nprobe ? pr[p] : -1;
+      const bool cld = c >= 0 && clus_tile[c] < 0;
+      const unsigned long long mcold = __ballot(cld);
+      if (cld) cd[at + __popcll(mcold & lt)] = c;
+      at += __popcll(mcold);
+    }
   }
   for (int p = nc + lane; p < nprobe; p += 64) cd[p] = -1;
 #pragma unroll
@@ -472,7 +487,7 @@ __global__ __launch_bounds__(kRouteBigThreads) void k_route_big(
   }
   int ng = 0, nc = 0, tiles = 0, both = 0;
   const int packed = block_excl_scan((n_res << 16) | n_cld, s_w, &both);  // each at most 2048
-  int o_res = packed >> 16, o_cld = packed & 0xffff;
+  int o_res = packed >> 16;
   ng = both >> 16;
   nc = both & 0xffff;
   int o_tile = block_excl_scan(n_tiles, s_w, &tiles);
@@ -490,9 +505,24 @@ __global__ __launch_bounds__(kRouteBigThreads) void k_route_big(
       if (bias) g_bias[(size_t)q * stride + o_res] = b[e];
       o_res += 1;
       o_tile += (len[e] + kTileVecs - 1) / kTileVecs;
-    } else {
-      cd[o_cld++] = c[e];
     }
+  }
+  // the cold list in the order of the probe list (see k_route): thread t takes probes
+  // t*E .. t*E+E-1 of that list
+  {
+    int cc[E], n_mine = 0;
+#pragma unroll
+    for (int e = 0; e < E; ++e) {
+      const int p = tid * E + e;
+      const int c0 = p < nprobe ? pr[p] : -1;
+      cc[e] = (c0 >= 0 && clus_tile[c0] < 0) ? c0 : -1;
+      n_mine += cc[e] >= 0 ? 1 : 0;
+    }
+    int total_cold = 0;
+    int o = block_excl_scan(n_mine, s_w, &total_cold);
+#pragma unroll
+    for (int e = 0; e < E; ++e)
+      if (cc[e] >= 0) cd[o++] = cc[e];
   }
   for (int p = nc + tid; p < nprobe; p += NT) cd[p] = -1;
   if (vec) atomicAdd(&s_vecs, vec);
