@@ -409,7 +409,6 @@ def main():
         side = torch.cuda.Stream(device=dev)
         hot = hottest_clusters(index, calib, spec.nprobe, frac, ix.nlist)
         index.load_partition(hot)
-        resident = set(hot.tolist())
         per_epoch = []
         mig_time = 0.0
         total_q = 0
@@ -431,25 +430,21 @@ def main():
                     pending_t0 = None
             ep_s = time.perf_counter() - t_ep
             total_q += args.epoch_queries
-            st = index.hit_stats(reset=True)
-            # recompute the hot set from this epoch's counters and migrate the difference
-            hits = st["per_cluster_hits"].astype(np.int64)
-            order = np.lexsort((np.arange(ix.nlist), -hits))
-            want = set(order[: len(hot)].tolist())
+            st = index.hit_stats()
             if pending_t0 is not None:
                 index.migrate_poll(wait=True)
                 mig_time += time.perf_counter() - pending_t0
                 pending_t0 = None
-            evict = sorted(resident - want)
-            admit = sorted(want - resident)
-            if evict or admit:
-                pending_t0 = time.perf_counter()
-                index.migrate_clusters(evict, admit, side_stream=side)
-                resident = want
+            # the library ranks this epoch's counters, migrates the difference to the
+            # new hot set on the side stream and clears the counters
+            t_refresh = time.perf_counter()
+            moved = index.refresh_hot_set(len(hot), reset=True, side_stream=side)
+            if moved["evicted"] or moved["admitted"]:
+                pending_t0 = t_refresh
             row = {"epoch": ep, "queries_per_s": round(args.epoch_queries / ep_s, 1),
                    "mean_hit_rate": round(st["mean_hit_rate"], 4),
                    "min_hit_rate": round(st["min_hit_rate"], 4),
-                   "migrated_clusters": len(admit)}
+                   "migrated_clusters": moved["admitted"], "deferred_clusters": moved["deferred"]}
             log(json.dumps(row))
             per_epoch.append(row)
         if pending_t0 is not None:

@@ -302,6 +302,32 @@ int ivf_migrate_clusters(ivf_index_t *index, const int32_t *evict, int32_t n_evi
 int ivf_migrate_poll(ivf_index_t *index, int wait, uint64_t *bytes_copied);
 
 /*
+ * One step of the runtime index update (Section 4.2.3 "Adaptive Runtime Index
+ * Update": the access counters name a new hot set and the device's copy is
+ * refreshed while the CPU serves what is not there yet).  Reads the router's
+ * per-cluster counters, takes the n_hot most accessed clusters as the hot set
+ * (Section 4.1.4 "Index Splitter": clusters ranked by access frequency; equal
+ * counts go to the smaller cluster id), and starts the migration from the
+ * current resident set to it on side_stream exactly as ivf_migrate_clusters
+ * would: resident clusters outside the hot set are evicted, hot clusters that
+ * are not resident are admitted, hottest first.  A cluster that finds no free
+ * space (space of evicted clusters is reusable only once the searches that
+ * might read it have drained) is left cold and counted in *n_deferred; the next
+ * refresh admits it.  reset != 0 clears the counters after reading, also when
+ * there was nothing to move.  Outputs (HOST, any may be NULL): clusters
+ * evicted, admitted and deferred; mean_hit_rate of the searches counted since
+ * the last reset.  Nothing to move: IVF_OK and no migration is started.
+ * IVF_EBUSY if a migration is in flight or an old mapping table is still being
+ * read; IVF_ESTATE if no search has been counted since the last reset (the
+ * counters then say nothing and the resident set is kept); IVF_EINVAL for
+ * n_hot outside [0, nlist].  Synchronizes with searches already enqueued, like
+ * ivf_hit_stats.
+ */
+int ivf_refresh_hot_set(ivf_index_t *index, int32_t n_hot, int reset, void *side_stream,
+                        int32_t *n_evicted, int32_t *n_admitted, int32_t *n_deferred,
+                        double *mean_hit_rate);
+
+/*
  * Totals over migrations completed since creation (any output may be NULL):
  * bytes_copied as in ivf_migrate_poll; copy_ms = time between the first copy
  * and the last kernel of each migration on its side stream, from HIP events;
@@ -312,6 +338,15 @@ int ivf_migrate_stats(ivf_index_t *index, uint64_t *bytes_copied, double *copy_m
 
 /* Number of currently resident clusters and vectors (either may be NULL). */
 int ivf_resident_info(ivf_index_t *index, int32_t *n_clusters, int64_t *n_vectors);
+
+/*
+ * The published resident set (the mapping table of Section 4.1.4 read back):
+ * ids of the resident clusters in ascending order into cluster_ids (HOST int32
+ * [cap], may be NULL when cap = 0), their number into *n (HOST).  Clusters of a
+ * migration still in flight are not in it.  IVF_EINVAL if cap is smaller than
+ * the number of resident clusters (*n is still written, nothing else is).
+ */
+int ivf_resident_list(ivf_index_t *index, int32_t *cluster_ids, int32_t cap, int32_t *n);
 
 /*
  * Which form of the CPU scan of non-resident clusters (Section 4.2.1) this

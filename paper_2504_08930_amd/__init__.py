@@ -61,8 +61,16 @@ def ivf_migrate_clusters(index, evict, admit, side_stream=None):
     return index.migrate_clusters(evict, admit, side_stream)
 
 
+def ivf_refresh_hot_set(index, n_hot, reset=True, side_stream=None):
+    return index.refresh_hot_set(n_hot, reset, side_stream)
+
+
 def ivf_migrate_poll(index, wait=False):
     return index.migrate_poll(wait)
+
+
+def ivf_resident_list(index):
+    return index.resident_list()
 
 
 def ivf_host_scan_form(index):

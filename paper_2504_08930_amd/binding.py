@@ -22,7 +22,8 @@ EXPORTS = (
     "ivf_index_load_partition", "ivf_search_batch", "ivf_search_batch_dev",
     "ivf_coarse_probe_dev", "ivf_coarse_probe_dev_noalloc", "ivf_search_batch_probes",
     "ivf_hit_stats",
-    "ivf_migrate_clusters", "ivf_migrate_poll", "ivf_migrate_stats", "ivf_resident_info", "ivf_host_scan_form", "ivf_copy_form",
+    "ivf_migrate_clusters", "ivf_migrate_poll", "ivf_migrate_stats", "ivf_refresh_hot_set",
+    "ivf_resident_info", "ivf_resident_list", "ivf_host_scan_form", "ivf_copy_form",
     "ivf_set_tuning", "ivf_stage_times", "ivf_calib_copy", "ivf_calib_read", "ivf_last_error",
     "ivf_model_hybrid_latency", "ivf_model_min_hit_rate", "ivf_model_hitrate_to_coverage",
     "ivf_model_partition_point",
@@ -87,8 +88,10 @@ def load_library():
     lib.ivf_hit_stats.argtypes = [P, P, P, P, P, ctypes.c_int]
     lib.ivf_migrate_clusters.argtypes = [P, P, I32, P, I32, P]
     lib.ivf_migrate_poll.argtypes = [P, ctypes.c_int, P]
+    lib.ivf_refresh_hot_set.argtypes = [P, I32, ctypes.c_int, P, P, P, P, P]
     lib.ivf_migrate_stats.argtypes = [P, P, P, P]
     lib.ivf_resident_info.argtypes = [P, P, P]
+    lib.ivf_resident_list.argtypes = [P, P, I32, P]
     lib.ivf_host_scan_form.argtypes = [P]
     lib.ivf_host_scan_form.restype = ctypes.c_int
     lib.ivf_copy_form.argtypes = [P]
@@ -233,6 +236,16 @@ class IvfIndex:
         _check(self._lib.ivf_migrate_clusters(self._h, _np_ptr(ev), ev.size, _np_ptr(ad), ad.size,
                                               self._stream_ptr(side_stream)))
 
+    def refresh_hot_set(self, n_hot, reset=True, side_stream=None):
+        """ivf_refresh_hot_set: the n_hot most accessed clusters become the resident set."""
+        ev, ad, de = ctypes.c_int32(0), ctypes.c_int32(0), ctypes.c_int32(0)
+        rate = ctypes.c_double(0)
+        _check(self._lib.ivf_refresh_hot_set(self._h, int(n_hot), int(bool(reset)),
+                                             self._stream_ptr(side_stream), ctypes.byref(ev),
+                                             ctypes.byref(ad), ctypes.byref(de), ctypes.byref(rate)))
+        return {"evicted": ev.value, "admitted": ad.value, "deferred": de.value,
+                "mean_hit_rate": rate.value}
+
     def migrate_poll(self, wait=False):
         nbytes = ctypes.c_uint64(0)
         rc = _check(self._lib.ivf_migrate_poll(self._h, int(bool(wait)), ctypes.byref(nbytes)))
@@ -248,6 +261,13 @@ class IvfIndex:
         nc, nv = ctypes.c_int32(0), ctypes.c_int64(0)
         _check(self._lib.ivf_resident_info(self._h, ctypes.byref(nc), ctypes.byref(nv)))
         return nc.value, nv.value
+
+    def resident_list(self):
+        """ivf_resident_list: ids of the resident clusters, ascending."""
+        out = np.empty(self.resident_info()[0], dtype=np.int32)
+        n = ctypes.c_int32(0)
+        _check(self._lib.ivf_resident_list(self._h, _np_ptr(out), out.size, ctypes.byref(n)))
+        return out[: n.value]
 
     def host_scan_form(self):
         return _check(self._lib.ivf_host_scan_form(self._h))

@@ -429,10 +429,19 @@ extern "C" int ivf_stage_times(ivf_index_t *ix, double *ms, uint64_t *launches,
 // ---------------------------------------------------------------------------
 // router counters
 // ---------------------------------------------------------------------------
-extern "C" int ivf_hit_stats(ivf_index_t *ix, uint64_t *per_cluster_hits, double *mean_hit_rate,
-                             double *min_hit_rate, uint64_t *n_queries, int reset) {
-  if (!ix) return fail(IVF_EINVAL, "index is NULL");
-  std::lock_guard<std::mutex> lk(ix->mu);
+// Clears the device's counters on the index's own stream and waits for that
+// stream only (not for copies running on a migration's side stream).
+int reset_counters_locked(ivf_index *ix) {
+  hipStream_t st = ix->own_stream;
+  HIP_TRY(launch_fill_u32((uint32_t *)ix->L.hits, (size_t)ix->sh.nlist * 2, 0u, st));
+  HIP_TRY(launch_fill_u32((uint32_t *)ix->L.qstats, 4 * 2, 0u, st));
+  HIP_TRY(launch_fill_u32((uint32_t *)&ix->L.qstats[QS_MIN_RATE_BITS], 1, 0x3f800000u, st));
+  HIP_TRY(hipStreamSynchronize(st));
+  return IVF_OK;
+}
+
+int read_counters_locked(ivf_index *ix, uint64_t *per_cluster_hits, double *mean_hit_rate,
+                         double *min_hit_rate, uint64_t *n_queries, int reset) {
   if (!ix->has_dev) {
     if (per_cluster_hits)
       memcpy(per_cluster_hits, ix->hc_hits.data(), (size_t)ix->sh.nlist * 8);
@@ -459,14 +468,15 @@ extern "C" int ivf_hit_stats(ivf_index_t *ix, uint64_t *per_cluster_hits, double
     *min_hit_rate = (double)f;
   }
   if (n_queries) *n_queries = ix->h_stats[QS_QUERIES];
-  if (reset) {
-    hipStream_t st = ix->own_stream;
-    HIP_TRY(launch_fill_u32((uint32_t *)ix->L.hits, (size_t)ix->sh.nlist * 2, 0u, st));
-    HIP_TRY(launch_fill_u32((uint32_t *)ix->L.qstats, 4 * 2, 0u, st));
-    HIP_TRY(launch_fill_u32((uint32_t *)&ix->L.qstats[QS_MIN_RATE_BITS], 1, 0x3f800000u, st));
-    HIP_TRY(hipStreamSynchronize(st));
-  }
+  if (reset) return reset_counters_locked(ix);
   return IVF_OK;
+}
+
+extern "C" int ivf_hit_stats(ivf_index_t *ix, uint64_t *per_cluster_hits, double *mean_hit_rate,
+                             double *min_hit_rate, uint64_t *n_queries, int reset) {
+  if (!ix) return fail(IVF_EINVAL, "index is NULL");
+  std::lock_guard<std::mutex> lk(ix->mu);
+  return read_counters_locked(ix, per_cluster_hits, mean_hit_rate, min_hit_rate, n_queries, reset);
 }
 
 extern "C" int ivf_calib_copy(const void *src, void *dst, size_t bytes, void *stream) {

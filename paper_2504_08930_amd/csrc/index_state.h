@@ -254,6 +254,11 @@ struct BatchCtx {
 
 // index.cpp
 IVF_INTERNAL HostIndexView host_view(const ivf_index *ix);
+// the router's counters, as ivf_hit_stats returns them (caller holds ix->mu)
+IVF_INTERNAL int read_counters_locked(ivf_index *ix, uint64_t *per_cluster_hits,
+                                      double *mean_hit_rate, double *min_hit_rate,
+                                      uint64_t *n_queries, int reset);
+IVF_INTERNAL int reset_counters_locked(ivf_index *ix);
 // residency.cpp (callers hold ix->mu)
 IVF_INTERNAL hipEvent_t get_event(ivf_index *ix);
 IVF_INTERNAL void reclaim(ivf_index *ix);

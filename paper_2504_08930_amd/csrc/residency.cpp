@@ -251,6 +251,20 @@ extern "C" int ivf_resident_info(ivf_index_t *ix, int32_t *n_clusters, int64_t *
   return IVF_OK;
 }
 
+extern "C" int ivf_resident_list(ivf_index_t *ix, int32_t *cluster_ids, int32_t cap, int32_t *n) {
+  if (!ix) return fail(IVF_EINVAL, "index is NULL");
+  if (!n || cap < 0 || (cap > 0 && !cluster_ids)) return fail(IVF_EINVAL, "resident_list: bad arguments");
+  std::lock_guard<std::mutex> lk(ix->mu);
+  *n = ix->resident_clusters;
+  if (cap < ix->resident_clusters)
+    return fail(IVF_EINVAL, "resident_list: %d clusters are resident, the array holds %d",
+                ix->resident_clusters, cap);
+  int32_t w = 0;
+  for (int32_t c = 0; c < ix->sh.nlist && ix->has_dev; ++c)
+    if (ix->h_map[c] >= 0) cluster_ids[w++] = c;
+  return IVF_OK;
+}
+
 // ---------------------------------------------------------------------------
 // migration (caller holds ix->mu for the *_locked helpers)
 // ---------------------------------------------------------------------------
@@ -289,14 +303,14 @@ int publish_if_done_locked(ivf_index *ix, bool wait) {
   return 0;
 }
 
-extern "C" int ivf_migrate_clusters(ivf_index_t *ix, const int32_t *evict, int32_t n_evict,
-                                    const int32_t *admit, int32_t n_admit, void *side_stream) {
-  if (!ix) return fail(IVF_EINVAL, "index is NULL");
-  if (!ix->has_dev) return fail(IVF_EDEVICE, "host-only index: nothing to migrate");
-  std::lock_guard<std::mutex> lk(ix->mu);
-  int rc = publish_if_done_locked(ix, false);
-  if (rc < 0) return rc;
-  if (ix->mig.active) return fail(IVF_EBUSY, "a migration is already in flight");
+// Starts the migration evict -> admit on side stream st (caller holds ix->mu, no
+// migration is in flight).  partial: admitted clusters are placed in the order
+// given and one that finds no free space is left out instead of failing the call;
+// *n_placed (may be NULL) receives how many were placed.
+static int migrate_locked(ivf_index *ix, const int32_t *evict, int32_t n_evict,
+                          const int32_t *admit, int32_t n_admit, hipStream_t st, bool partial,
+                          int32_t *n_placed) {
+  int rc;
   std::vector<char> seen(ix->sh.nlist, 0);
   if ((rc = check_cluster_list(ix, evict, n_evict, "evict", seen)) != IVF_OK) return rc;
   if ((rc = check_cluster_list(ix, admit, n_admit, "admit", seen)) != IVF_OK) return rc;
@@ -306,7 +320,6 @@ extern "C" int ivf_migrate_clusters(ivf_index_t *ix, const int32_t *evict, int32
   for (int32_t i = 0; i < n_admit; ++i)
     if (ix->h_map[admit[i]] >= 0)
       return fail(IVF_EINVAL, "admit: cluster %d is already resident", admit[i]);
-  hipStream_t st = (hipStream_t)side_stream;
 
   reclaim(ix);
   const int target = (ix->versions.back().buf + 1) % 3;
@@ -316,20 +329,23 @@ extern "C" int ivf_migrate_clusters(ivf_index_t *ix, const int32_t *evict, int32
 
   // place admitted clusters in free space only
   std::vector<int32_t> clusters(admit, admit + n_admit);
-  std::sort(clusters.begin(), clusters.end());
+  if (!partial) std::sort(clusters.begin(), clusters.end());
   std::vector<int64_t> bases(clusters.size());
   size_t placed = 0;
   int64_t need_tiles = 0;
   bool ok = true;
-  for (; placed < clusters.size(); ++placed) {
-    const int64_t nt = tiles_of(ix->h_len[clusters[placed]]);
+  for (size_t i = 0; i < clusters.size(); ++i) {
+    const int64_t nt = tiles_of(ix->h_len[clusters[i]]);
     const int64_t s = ix->alloc.alloc(nt);
     if (s < 0) {
+      if (partial) continue;  // stays cold; a later refresh finds the evicted space free
       ok = false;
       break;
     }
+    clusters[placed] = clusters[i];
     bases[placed] = s;
     need_tiles += nt;
+    ++placed;
   }
   auto undo = [&]() {
     for (size_t i = 0; i < placed; ++i)
@@ -339,6 +355,22 @@ extern "C" int ivf_migrate_clusters(ivf_index_t *ix, const int32_t *evict, int32
     undo();
     return fail(IVF_ENOMEM, "cluster region cannot hold the admitted clusters (%lld tiles free)",
                 (long long)ix->alloc.free_tiles());
+  }
+  clusters.resize(placed);
+  bases.resize(placed);
+  if (partial) {  // the copies take the clusters in id order, like the caller's list above
+    std::vector<size_t> by_id(placed);
+    for (size_t i = 0; i < placed; ++i) by_id[i] = i;
+    std::sort(by_id.begin(), by_id.end(),
+              [&](size_t a, size_t b) { return clusters[a] < clusters[b]; });
+    std::vector<int32_t> c2(placed);
+    std::vector<int64_t> b2(placed);
+    for (size_t i = 0; i < placed; ++i) {
+      c2[i] = clusters[by_id[i]];
+      b2[i] = bases[by_id[i]];
+    }
+    clusters.swap(c2);
+    bases.swap(b2);
   }
 
   Migration m;
@@ -393,6 +425,75 @@ extern "C" int ivf_migrate_clusters(ivf_index_t *ix, const int32_t *evict, int32
   }
   m.active = true;
   ix->mig = std::move(m);
+  if (n_placed) *n_placed = (int32_t)placed;
+  return IVF_OK;
+}
+
+extern "C" int ivf_migrate_clusters(ivf_index_t *ix, const int32_t *evict, int32_t n_evict,
+                                    const int32_t *admit, int32_t n_admit, void *side_stream) {
+  if (!ix) return fail(IVF_EINVAL, "index is NULL");
+  if (!ix->has_dev) return fail(IVF_EDEVICE, "host-only index: nothing to migrate");
+  std::lock_guard<std::mutex> lk(ix->mu);
+  int rc = publish_if_done_locked(ix, false);
+  if (rc < 0) return rc;
+  if (ix->mig.active) return fail(IVF_EBUSY, "a migration is already in flight");
+  return migrate_locked(ix, evict, n_evict, admit, n_admit, (hipStream_t)side_stream,
+                        /*partial=*/false, nullptr);
+}
+
+extern "C" int ivf_refresh_hot_set(ivf_index_t *ix, int32_t n_hot, int reset, void *side_stream,
+                                   int32_t *n_evicted, int32_t *n_admitted, int32_t *n_deferred,
+                                   double *mean_hit_rate) {
+  if (!ix) return fail(IVF_EINVAL, "index is NULL");
+  if (!ix->has_dev) return fail(IVF_EDEVICE, "host-only index: nothing to migrate");
+  const int32_t nlist = ix->sh.nlist;
+  if (n_hot < 0 || n_hot > nlist)
+    return fail(IVF_EINVAL, "refresh: n_hot = %d, the index has %d clusters", n_hot, nlist);
+  std::lock_guard<std::mutex> lk(ix->mu);
+  int rc = publish_if_done_locked(ix, false);
+  if (rc < 0) return rc;
+  if (ix->mig.active) return fail(IVF_EBUSY, "a migration is already in flight");
+  reclaim(ix);
+  {
+    const int target = (ix->versions.back().buf + 1) % 3;
+    for (auto &v : ix->versions)
+      if (v.buf == target)
+        return fail(IVF_EBUSY, "searches on an old mapping table have not drained yet");
+  }
+  std::vector<uint64_t> hits((size_t)nlist);
+  uint64_t counted = 0;
+  {
+    // without any search since the last reset the ranking below would be by id alone
+    // and would throw the hot set away: look before the counters are cleared
+    rc = read_counters_locked(ix, hits.data(), mean_hit_rate, nullptr, &counted, 0);
+    if (rc != IVF_OK) return rc;
+    if (counted == 0) return fail(IVF_ESTATE, "refresh: no search has been counted since the reset");
+  }
+  // the n_hot most accessed clusters, ties to the smaller id
+  std::vector<int32_t> order((size_t)nlist);
+  for (int32_t c = 0; c < nlist; ++c) order[c] = c;
+  auto hotter = [&](int32_t a, int32_t b) {
+    return hits[a] != hits[b] ? hits[a] > hits[b] : a < b;
+  };
+  std::partial_sort(order.begin(), order.begin() + n_hot, order.end(), hotter);
+  std::vector<char> want((size_t)nlist, 0);
+  for (int32_t i = 0; i < n_hot; ++i) want[order[i]] = 1;
+  std::vector<int32_t> evict, admit;
+  for (int32_t c = 0; c < nlist; ++c)
+    if (ix->h_map[c] >= 0 && !want[c]) evict.push_back(c);
+  for (int32_t i = 0; i < n_hot; ++i)  // hottest first: they are placed first
+    if (ix->h_map[order[i]] < 0) admit.push_back(order[i]);
+  int32_t placed = 0;
+  if (!evict.empty() || !admit.empty()) {
+    rc = migrate_locked(ix, evict.data(), (int32_t)evict.size(), admit.data(),
+                        (int32_t)admit.size(), (hipStream_t)side_stream, /*partial=*/true, &placed);
+    if (rc != IVF_OK) return rc;
+  }
+  // (clears on the index's own stream: a device-wide wait would wait for the copies just started)
+  if (reset && (rc = reset_counters_locked(ix)) != IVF_OK) return rc;
+  if (n_evicted) *n_evicted = (int32_t)evict.size();
+  if (n_admitted) *n_admitted = placed;
+  if (n_deferred) *n_deferred = (int32_t)admit.size() - placed;
   return IVF_OK;
 }
 

@@ -956,6 +956,99 @@ def test_c5_drift_epochs(pkg, oracle):
     _CACHE.pop("C3", None)
 
 
+def test_refresh_hot_set(pkg, oracle):
+    """ivf_refresh_hot_set (Section 4.2.3 "Adaptive Runtime Index Update" in one call): the
+    resident set it reaches is the one ranked here from ivf_hit_stats' counters (most
+    accessed first, ties to the smaller id), the clusters it reports moved are the two set
+    differences, results stay bit-identical to the all-resident ones before, during and after,
+    and the counters are cleared.  Then with a cluster region that only just holds the hot
+    set: clusters that find no free space are deferred and a later refresh admits them."""
+    import torch
+    spec, ix, q, calib = _case("C2")
+    centers = mixture_centers(spec, torch.device("cuda"))
+    lens = np.diff(ix.list_offsets)
+    n_hot = int(round(0.3 * ix.nlist))
+    nq = 500
+
+    def batch(i, perm_seed):
+        return make_queries(spec, centers, nq=nq, seed=spec.seed_queries + 500 + i,
+                            perm_seed=perm_seed)[0].cpu().numpy()
+
+    def ranked(hits):
+        order = np.lexsort((np.arange(ix.nlist), -hits.astype(np.int64)))
+        return np.sort(order[:n_hot]).astype(np.int32)
+
+    index = pkg.IvfIndex(ix, max_nq=nq, max_nprobe=spec.nprobe, max_k=16)
+    index.load_partition(np.arange(ix.nlist, dtype=np.int32))
+    qs = {(e, b): batch(10 * e + b, spec.seed_perm + e) for e in range(3) for b in range(2)}
+    ref = {key: index.search_batch(v, spec.nprobe, spec.k) for key, v in qs.items()}
+    # no search counted: the resident set is kept
+    index.hit_stats(reset=True)
+    with pytest.raises(pkg.IvfError) as e:
+        index.refresh_hot_set(n_hot)
+    assert e.value.code == -5 and index.resident_info()[0] == ix.nlist
+    with pytest.raises(pkg.IvfError) as e:
+        index.refresh_hot_set(ix.nlist + 1)
+    assert e.value.code == -1
+    index.load_partition(hottest(index, calib, spec.nprobe, 0.3, ix.nlist))
+    side = torch.cuda.Stream()
+    expect_bytes = 0
+    for ep in range(3):                      # every epoch draws another permutation of the centres
+        for b in range(2):
+            got = index.search_batch(qs[ep, b], spec.nprobe, spec.k)
+            assert np.array_equal(got[0], ref[ep, b][0]) and np.array_equal(got[1], ref[ep, b][1])
+        st = index.hit_stats()
+        before = set(index.resident_list().tolist())
+        want = ranked(st["per_cluster_hits"])
+        r = index.refresh_hot_set(n_hot, reset=True, side_stream=side)
+        evict, admit = before - set(want.tolist()), set(want.tolist()) - before
+        _say(f"refresh {ep}: hit rate {r['mean_hit_rate']:.3f}, evicted {r['evicted']}, "
+             f"admitted {r['admitted']}, deferred {r['deferred']}")
+        assert r["evicted"] == len(evict) and r["admitted"] == len(admit) and r["deferred"] == 0
+        assert abs(r["mean_hit_rate"] - st["mean_hit_rate"]) < 1e-12
+        expect_bytes += int(lens[sorted(admit)].sum()) * (ix.m + 8)
+        during = index.search_batch(qs[ep, 0], spec.nprobe, spec.k)   # copies may be in flight
+        assert np.array_equal(during[0], ref[ep, 0][0]) and np.array_equal(during[1], ref[ep, 0][1])
+        in_flight, nbytes = index.migrate_poll(wait=True)
+        assert not in_flight and nbytes == expect_bytes
+        assert np.array_equal(index.resident_list(), want)
+        after = index.hit_stats(reset=True)
+        assert after["n_queries"] == nq      # only the batch searched since the refresh cleared them
+        if ep:
+            assert len(admit) > n_hot // 4    # a re-drawn permutation moves the hot set
+    sel = np.arange(0, nq, 25)
+    _check_search(oracle, ix, qs[2, 1][sel], spec.nprobe, spec.k, ref[2, 1][0][sel], ref[2, 1][1][sel])
+    index.close()
+
+    # a cluster region with room for the hot set and little else
+    index = pkg.IvfIndex(ix, max_nq=nq, max_nprobe=spec.nprobe, max_k=16,
+                         resident_vectors=int(lens.sum() * 0.45))
+    index.hit_stats(reset=True)
+    index.search_batch(qs[0, 0], spec.nprobe, spec.k)
+    want0 = ranked(index.hit_stats()["per_cluster_hits"])
+    r = index.refresh_hot_set(n_hot, side_stream=side)     # from nothing resident
+    assert r["evicted"] == 0 and r["admitted"] + r["deferred"] == n_hot
+    index.migrate_poll(wait=True)
+    deferred_seen = r["deferred"]
+    for rounds in range(1, 7):
+        for b in range(2):
+            got = index.search_batch(qs[1, b], spec.nprobe, spec.k)
+            assert np.array_equal(got[0], ref[1, b][0]) and np.array_equal(got[1], ref[1, b][1])
+        want = ranked(index.hit_stats()["per_cluster_hits"])
+        r = index.refresh_hot_set(n_hot, side_stream=side)
+        index.migrate_poll(wait=True)
+        deferred_seen += r["deferred"]
+        _say(f"tight region, refresh {rounds}: evicted {r['evicted']}, admitted {r['admitted']}, "
+             f"deferred {r['deferred']}")
+        have = set(index.resident_list().tolist())
+        assert have <= set(want.tolist()) and len(have) == len(want) - r["deferred"]
+        if r["deferred"] == 0 and r["admitted"] == 0 and r["evicted"] == 0:
+            break
+    assert deferred_seen > 0, "the region was meant to be too small for a swap in one step"
+    assert np.array_equal(index.resident_list(), want)
+    index.close()
+
+
 def test_k100_nprobe128(pkg, oracle):
     """Search parameters of the 100M config (nprobe=128, k=100) on a 4M-vector
     index: exercises the k > 64 scan variant and lists of ~1000 vectors."""

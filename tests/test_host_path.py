@@ -319,6 +319,10 @@ def test_argument_errors(case, lib):
         index.load_partition([0])
     with pytest.raises(lib.IvfError):
         index.migrate_clusters([], [0])
+    with pytest.raises(lib.IvfError) as e:
+        index.refresh_hot_set(1)                             # nothing lives on a device
+    assert e.value.code == -3
+    assert index.resident_info() == (0, 0) and index.resident_list().size == 0
 
 
 def test_desc_validation_and_arena_size(lib):
