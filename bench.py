@@ -320,7 +320,6 @@ def main():
     if args.mode == "partition":
         from paper_2504_08930_amd import binding as B
         nlist = ix.nlist
-        lens = np.diff(ix.list_offsets).astype(np.float64)
         # --- access profile from calibration queries (Section 4.1.1) ---
         index.hit_stats(reset=True)
         probes = []
@@ -330,12 +329,9 @@ def main():
             probes.append(index.coarse_probe_dev(cq, spec.nprobe).cpu().numpy())
         torch.cuda.synchronize()
         probes = np.concatenate(probes)
-        hits = index.hit_stats(reset=True)["per_cluster_hits"].astype(np.int64)
-        order = np.lexsort((np.arange(nlist), -hits))                 # hottest first
-        hit_cdf = np.concatenate([[0.0], np.cumsum(hits[order]) / hits.sum()])
-        hit_cdf[-1] = 1.0
-        per_vec = ix.m * ix.nbits // 8 + 8 + (4 if (ix.by_residual and ix.metric == 0) else 0)
-        mem_index = np.concatenate([[0.0], np.cumsum(lens[order] * per_vec)])
+        # ranking (hottest first), cumulative hit share and cumulative device bytes
+        order, hit_cdf, mem_index = index.profile_curves()
+        index.hit_stats(reset=True)
         # sigma_max^2: variance of the per-query hit rate at the coverage where the mean is 0.5
         i_half = int(np.searchsorted(hit_cdf, 0.5))
         hot_mask = np.zeros(nlist, bool)

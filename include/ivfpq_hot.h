@@ -407,6 +407,24 @@ int ivf_stage_times(ivf_index_t *index, double *ms, uint64_t *launches, uint64_t
                     int reset);
 
 /*
+ * The access profile the partitioning model works on (Section 4.1.1: cluster
+ * access frequencies collected over calibration queries; Section 3.2: their
+ * cumulative distribution), taken from the router's per-cluster counters as
+ * they stand (searches since the last reset; nothing is cleared).  Clusters are
+ * ranked from the most to the least probed, equal counts by id.  All outputs
+ * HOST, any may be NULL: ranked int32 [nlist], the cluster ids in that order;
+ * hit_cdf double [nlist+1], hit_cdf[i] = share of all counted probes that fall
+ * into the i hottest clusters (hit_cdf[0] = 0, hit_cdf[nlist] = 1); mem_index
+ * double [nlist+1], device bytes of the i hottest clusters (code bytes + 8 id
+ * bytes per vector, + 4 for residual codes under L2).  The two curves are the
+ * hit_cdf / mem_index arguments of ivf_model_hitrate_to_coverage and
+ * ivf_model_partition_point, whose rho, times nlist, is ivf_refresh_hot_set's
+ * n_hot.  IVF_ESTATE if no probe has been counted.  Synchronizes with searches
+ * already enqueued.
+ */
+int ivf_profile_curves(ivf_index_t *index, int32_t *ranked, double *hit_cdf, double *mem_index);
+
+/*
  * ---- Partitioning point (Section 4.1): pure host functions ----
  *
  * ivf_latency_model_t: piecewise-linear CPU latency models of the two search

@@ -61,6 +61,10 @@ def ivf_migrate_clusters(index, evict, admit, side_stream=None):
     return index.migrate_clusters(evict, admit, side_stream)
 
 
+def ivf_profile_curves(index):
+    return index.profile_curves()
+
+
 def ivf_refresh_hot_set(index, n_hot, reset=True, side_stream=None):
     return index.refresh_hot_set(n_hot, reset, side_stream)
 

@@ -21,7 +21,7 @@ EXPORTS = (
     "ivf_index_arena_bytes", "ivf_index_create", "ivf_index_destroy",
     "ivf_index_load_partition", "ivf_search_batch", "ivf_search_batch_dev",
     "ivf_coarse_probe_dev", "ivf_coarse_probe_dev_noalloc", "ivf_search_batch_probes",
-    "ivf_hit_stats",
+    "ivf_hit_stats", "ivf_profile_curves",
     "ivf_migrate_clusters", "ivf_migrate_poll", "ivf_migrate_stats", "ivf_refresh_hot_set",
     "ivf_resident_info", "ivf_resident_list", "ivf_host_scan_form", "ivf_copy_form",
     "ivf_set_tuning", "ivf_stage_times", "ivf_calib_copy", "ivf_calib_read", "ivf_last_error",
@@ -86,6 +86,7 @@ def load_library():
     lib.ivf_search_poll.argtypes = [P, P, I64, P, P]
     lib.ivf_search_wait.argtypes = [P, P]
     lib.ivf_hit_stats.argtypes = [P, P, P, P, P, ctypes.c_int]
+    lib.ivf_profile_curves.argtypes = [P, P, P, P]
     lib.ivf_migrate_clusters.argtypes = [P, P, I32, P, I32, P]
     lib.ivf_migrate_poll.argtypes = [P, ctypes.c_int, P]
     lib.ivf_refresh_hot_set.argtypes = [P, I32, ctypes.c_int, P, P, P, P, P]
@@ -235,6 +236,15 @@ class IvfIndex:
         ev, ad = _i32(evict), _i32(admit)
         _check(self._lib.ivf_migrate_clusters(self._h, _np_ptr(ev), ev.size, _np_ptr(ad), ad.size,
                                               self._stream_ptr(side_stream)))
+
+    def profile_curves(self):
+        """ivf_profile_curves: (ranked cluster ids, hit_cdf, mem_index) from the counters."""
+        ranked = np.empty(self.nlist, dtype=np.int32)
+        hit_cdf = np.empty(self.nlist + 1, dtype=np.float64)
+        mem_index = np.empty(self.nlist + 1, dtype=np.float64)
+        _check(self._lib.ivf_profile_curves(self._h, _np_ptr(ranked), _np_ptr(hit_cdf),
+                                            _np_ptr(mem_index)))
+        return ranked, hit_cdf, mem_index
 
     def refresh_hot_set(self, n_hot, reset=True, side_stream=None):
         """ivf_refresh_hot_set: the n_hot most accessed clusters become the resident set."""

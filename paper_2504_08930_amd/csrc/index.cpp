@@ -479,6 +479,48 @@ extern "C" int ivf_hit_stats(ivf_index_t *ix, uint64_t *per_cluster_hits, double
   return read_counters_locked(ix, per_cluster_hits, mean_hit_rate, min_hit_rate, n_queries, reset);
 }
 
+// Clusters from the most to the least accessed, equal counts by id.
+void rank_clusters(const std::vector<uint64_t> &hits, std::vector<int32_t> &order) {
+  order.resize(hits.size());
+  for (size_t c = 0; c < hits.size(); ++c) order[c] = (int32_t)c;
+  std::sort(order.begin(), order.end(), [&](int32_t a, int32_t b) {
+    return hits[a] != hits[b] ? hits[a] > hits[b] : a < b;
+  });
+}
+
+extern "C" int ivf_profile_curves(ivf_index_t *ix, int32_t *ranked, double *hit_cdf,
+                                  double *mem_index) {
+  if (!ix) return fail(IVF_EINVAL, "index is NULL");
+  const int32_t nlist = ix->sh.nlist;
+  std::vector<uint64_t> hits((size_t)nlist);
+  {
+    std::lock_guard<std::mutex> lk(ix->mu);
+    int rc = read_counters_locked(ix, hits.data(), nullptr, nullptr, nullptr, 0);
+    if (rc != IVF_OK) return rc;
+  }
+  uint64_t total = 0;
+  for (uint64_t h : hits) total += h;
+  if (total == 0) return fail(IVF_ESTATE, "profile: no probe has been counted since the reset");
+  std::vector<int32_t> order;
+  rank_clusters(hits, order);
+  // what a resident vector costs on the device: its code, its id, and for residual
+  // codes under L2 its per-vector term
+  const double per_vec = (double)ix->sh.M + 8.0 + (ix->sh.by_residual && !ix->sh.metric_ip ? 4.0 : 0.0);
+  uint64_t acc = 0;
+  double bytes = 0.0;
+  if (hit_cdf) hit_cdf[0] = 0.0;
+  if (mem_index) mem_index[0] = 0.0;
+  for (int32_t i = 0; i < nlist; ++i) {
+    const int32_t c = order[i];
+    acc += hits[c];
+    bytes += per_vec * (double)ix->h_len[c];
+    if (ranked) ranked[i] = c;
+    if (hit_cdf) hit_cdf[i + 1] = i + 1 == nlist ? 1.0 : (double)acc / (double)total;
+    if (mem_index) mem_index[i + 1] = bytes;
+  }
+  return IVF_OK;
+}
+
 extern "C" int ivf_calib_copy(const void *src, void *dst, size_t bytes, void *stream) {
   if (!src || !dst || bytes % 16 != 0) return fail(IVF_EINVAL, "calib copy: bad arguments");
   HIP_TRY(launch_calib_copy(src, dst, bytes, (hipStream_t)stream));

@@ -259,6 +259,8 @@ IVF_INTERNAL int read_counters_locked(ivf_index *ix, uint64_t *per_cluster_hits,
                                       double *mean_hit_rate, double *min_hit_rate,
                                       uint64_t *n_queries, int reset);
 IVF_INTERNAL int reset_counters_locked(ivf_index *ix);
+// cluster ids from the most to the least accessed, equal counts by id
+IVF_INTERNAL void rank_clusters(const std::vector<uint64_t> &hits, std::vector<int32_t> &order);
 // residency.cpp (callers hold ix->mu)
 IVF_INTERNAL hipEvent_t get_event(ivf_index *ix);
 IVF_INTERNAL void reclaim(ivf_index *ix);

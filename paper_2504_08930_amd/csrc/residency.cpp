@@ -470,12 +470,8 @@ extern "C" int ivf_refresh_hot_set(ivf_index_t *ix, int32_t n_hot, int reset, vo
     if (counted == 0) return fail(IVF_ESTATE, "refresh: no search has been counted since the reset");
   }
   // the n_hot most accessed clusters, ties to the smaller id
-  std::vector<int32_t> order((size_t)nlist);
-  for (int32_t c = 0; c < nlist; ++c) order[c] = c;
-  auto hotter = [&](int32_t a, int32_t b) {
-    return hits[a] != hits[b] ? hits[a] > hits[b] : a < b;
-  };
-  std::partial_sort(order.begin(), order.begin() + n_hot, order.end(), hotter);
+  std::vector<int32_t> order;
+  rank_clusters(hits, order);
   std::vector<char> want((size_t)nlist, 0);
   for (int32_t i = 0; i < n_hot; ++i) want[order[i]] = 1;
   std::vector<int32_t> evict, admit;

@@ -162,8 +162,26 @@ static void run_case(int M, int nbits, int dsub, int metric, int residual, unsig
   std::vector<uint64_t> hits((size_t)ix.nlist);
   uint64_t nqs = 0;
   double mean = -1, mn = -1;
+  {
+    // the access profile from those counters: a permutation of the ids, curves that rise to
+    // the whole (read before the counters are cleared below)
+    std::vector<int32_t> ranked((size_t)ix.nlist);
+    std::vector<double> cdf((size_t)ix.nlist + 1), mem((size_t)ix.nlist + 1);
+    CHECK(ivf_profile_curves(ix.h, ranked.data(), cdf.data(), mem.data()) == IVF_OK);
+    std::vector<char> seen_id((size_t)ix.nlist, 0);
+    for (int32_t c : ranked) {
+      CHECK(c >= 0 && c < ix.nlist && !seen_id[(size_t)c]);
+      seen_id[(size_t)c] = 1;
+    }
+    CHECK(cdf[0] == 0.0 && cdf[(size_t)ix.nlist] == 1.0 && mem[0] == 0.0);
+    for (int i = 0; i < ix.nlist; ++i) CHECK(cdf[(size_t)i + 1] >= cdf[(size_t)i] && mem[(size_t)i + 1] >= mem[(size_t)i]);
+    int32_t nres = -1;
+    CHECK(ivf_resident_list(ix.h, nullptr, 0, &nres) == IVF_OK && nres == 0);
+    CHECK(ivf_refresh_hot_set(ix.h, 1, 0, nullptr, nullptr, nullptr, nullptr, nullptr) == IVF_EDEVICE);
+  }
   CHECK(ivf_hit_stats(ix.h, hits.data(), &mean, &mn, &nqs, 1) == IVF_OK);
   CHECK(nqs > 0 && mean == 0.0);
+  CHECK(ivf_profile_curves(ix.h, nullptr, nullptr, nullptr) == IVF_ESTATE);
   CHECK(ivf_hit_stats(ix.h, hits.data(), nullptr, nullptr, &nqs, 0) == IVF_OK && nqs == 0);
   // what needs the device says so
   std::vector<int64_t> oi(10);

@@ -1000,6 +1000,9 @@ def test_refresh_hot_set(pkg, oracle):
         st = index.hit_stats()
         before = set(index.resident_list().tolist())
         want = ranked(st["per_cluster_hits"])
+        prof_rank, prof_cdf, _ = index.profile_curves()      # the device's counters, same ranking
+        assert np.array_equal(np.sort(prof_rank[:n_hot]), want)
+        assert abs(prof_cdf[n_hot] - st["per_cluster_hits"][want].sum() / st["per_cluster_hits"].sum()) < 1e-12
         r = index.refresh_hot_set(n_hot, reset=True, side_stream=side)
         evict, admit = before - set(want.tolist()), set(want.tolist()) - before
         _say(f"refresh {ep}: hit rate {r['mean_hit_rate']:.3f}, evicted {r['evicted']}, "

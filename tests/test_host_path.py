@@ -298,6 +298,33 @@ def test_host_only_counters(case, oracle):
     assert index.hit_stats()["per_cluster_hits"].sum() == 0
 
 
+def test_profile_curves_from_the_counters(case, oracle, lib):
+    """ivf_profile_curves (the access profile of Section 4.1.1): ranking, cumulative hit share and
+    cumulative device bytes against the same curves written out here from the oracle's counts."""
+    spec, ix, q, index = case
+    index.hit_stats(reset=True)
+    with pytest.raises(lib.IvfError) as e:
+        index.profile_curves()                               # nothing counted
+    assert e.value.code == -5
+    probe, _, _ = oracle.coarse(ix.metric, ix.centroids, q, spec.nprobe)
+    index.search_batch_probes(q, probe, spec.k)
+    hits, _ = oracle.hit_stats(ix.nlist, probe, np.zeros(ix.nlist, np.uint8))
+    hits = hits.astype(np.int64)
+    ranked, hit_cdf, mem_index = index.profile_curves()
+    # hottest first, equal counts by id: a stable sort of the ids by falling count
+    want = np.argsort(-hits, kind="stable")
+    assert np.array_equal(ranked, want)
+    assert hit_cdf[0] == 0.0 and hit_cdf[-1] == 1.0 and np.all(np.diff(hit_cdf) >= 0)
+    for i in (1, 2, ix.nlist // 3, ix.nlist - 1):
+        assert abs(hit_cdf[i] - hits[want[:i]].sum() / hits.sum()) < 1e-12
+    lens = np.diff(ix.list_offsets)
+    per_vec = ix.m + 8                                        # code bytes + the 64-bit id
+    assert mem_index[0] == 0.0 and mem_index[-1] == per_vec * ix.n
+    for i in (1, 5, ix.nlist // 2):
+        assert mem_index[i] == per_vec * lens[want[:i]].sum()
+    assert index.hit_stats(reset=True)["per_cluster_hits"].sum() == hits.sum()   # nothing was cleared
+
+
 def test_argument_errors(case, lib):
     spec, ix, q, index = case
     good = np.zeros((q.shape[0], 2), np.int32)
