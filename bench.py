@@ -13,7 +13,8 @@ kernel: algorithmic bytes (sum over (query, resident probe) pairs of M * list
 length) per launch over that kernel's average duration, taken from HIP events
 recorded on the search stream inside the timed region.  `cpu_baseline` is the
 oracle (oracle/) timed on this machine's host cores on a bounded sample of the same
-queries.
+queries.  `other_points` holds short passes over the configuration's other batch
+sizes and resident fractions, run after the timed region.
 
 Other modes (each prints one JSON line of its own):
   --mode sweep   nq in {256, 1024, 4096} x resident fraction in {0.1, 0.3, 0.5, 1.0}
@@ -24,8 +25,8 @@ Other modes (each prints one JSON line of its own):
                  several resident fractions; batch latency and mean / p90 per-query hand-off
                  latency of ivf_search_batch_async against the bulk ivf_search_batch
   --mode drift   20 epochs x 10 000 queries, Zipf permutation re-drawn every 5
-                 epochs, hot set recomputed from ivf_hit_stats after every epoch
-                 and migrated with ivf_migrate_clusters while searches continue
+                 epochs, after every epoch ivf_refresh_hot_set re-ranks the clusters by the
+                 router's counters and migrates to the new hot set while searches continue
 """
 import argparse
 import json
@@ -186,6 +187,9 @@ def main():
                     help="fraction of clusters (hottest first) kept on the GPU")
     ap.add_argument("--oracle-sample", type=int, default=512)
     ap.add_argument("--no-oracle", action="store_true")
+    ap.add_argument("--no-other-points", action="store_true",
+                    help="default mode: leave out the short passes over the configuration's other "
+                         "batch sizes and resident fractions (other_points in the line)")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also launch one 1 GiB streaming copy and a few 1 GiB streaming read "
                          "kernels (counter calibration / read ceiling)")
@@ -610,6 +614,37 @@ def main():
         parity = {"queries_checked": int(ns), "coarse_ambiguous": int(n_coarse),
                   "id_ambiguous": int(n_amb), "pass": True}
 
+    # The configuration's other named points (batch sizes 256 and 4096, hottest 50 / 30 / 10 %
+    # of the clusters resident with the rest scanned by the library's CPU tier), each from a
+    # short pass of its own after everything above: context beside `value`, never part of it.
+    # Runs under a profiler leave them out (they pass --no-oracle) so that a kernel's
+    # statistics cover one launch shape.
+    other_points = None
+    if (args.workload == "C3" and not args.no_other_points and not args.no_oracle
+            and resident_frac == 1.0 and not args.no_timing and args.streams == 1
+            and not (args.nq or args.nprobe or args.k or args.residual or args.m)
+            and args.nbits == 8):
+        index.close()
+        index = pkg.IvfIndex(ix, max_nq=4096, max_nprobe=spec.nprobe, max_k=spec.k)
+        other_points = []
+        for frac in (1.0, 0.5, 0.3, 0.1):
+            index.load_partition(all_clusters)
+            if frac < 1.0:
+                index.load_partition(hottest_clusters(index, calib, spec.nprobe, frac, ix.nlist))
+            for n in ((256, 4096) if frac == 1.0 else (1024,)):
+                qn = make_queries(spec, centers, nq=n)[0].contiguous()
+                rp = timed_steps(index, qn, spec.nprobe, spec.k, 20 if frac == 1.0 else 5,
+                                 5 if frac == 1.0 else 2, 0, timing=2)
+                row = {"nq": n, "resident_fraction": frac, "queries_per_s": round(rp["qps"], 1),
+                       "ms_per_step": round(rp["ms_per_step"], 4),
+                       "mean_hit_rate": round(rp["hit_rate"], 4),
+                       "min_hit_rate": round(rp["min_hit_rate"], 4)}
+                if "scan_gbs" in rp:
+                    row["scan_ms"] = round(rp["scan_ms"], 4)
+                    row["scan_frac_of_peak"] = round(rp["scan_gbs"] / HBM_PEAK_GBS, 4)
+                log(json.dumps(row))
+                other_points.append(row)
+
     out = {
         "metric": METRIC,
         "value": round(r["qps"], 1),
@@ -640,6 +675,11 @@ def main():
         "parity": parity,
         "host_pointer_call": host_ptr,
         "two_streams": two_streams,
+        "other_points": other_points,
+        "other_points_note": "same index, short passes after the timed region: all clusters "
+                             "resident at nq = 256 and 4096 (device-resident queries); hottest "
+                             "50 / 30 / 10 % resident at nq = 1024, the cold probes scanned by the "
+                             "library's CPU tier on the host's threads inside the same call",
         "index_build_s": round(build_s, 2),
         "load_partition_s": round(load_s, 3),
     }
