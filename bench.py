@@ -325,23 +325,22 @@ def main():
         from paper_2504_08930_amd import binding as B
         nlist = ix.nlist
         # --- access profile from calibration queries (Section 4.1.1) ---
-        index.hit_stats(reset=True)
-        probes = []
-        for s0 in range(0, calib.shape[0], index.max_nq):
-            cq = calib[s0:s0 + index.max_nq].contiguous()
-            index.search_batch_dev(cq, spec.nprobe, 1)
-            probes.append(index.coarse_probe_dev(cq, spec.nprobe).cpu().numpy())
-        torch.cuda.synchronize()
-        probes = np.concatenate(probes)
+        def run_calibration():
+            index.hit_stats(reset=True)
+            for s0 in range(0, calib.shape[0], index.max_nq):
+                index.search_batch_dev(calib[s0:s0 + index.max_nq].contiguous(), spec.nprobe, 1)
+            torch.cuda.synchronize()
+        run_calibration()
         # ranking (hottest first), cumulative hit share and cumulative device bytes
         order, hit_cdf, mem_index = index.profile_curves()
-        index.hit_stats(reset=True)
-        # sigma_max^2: variance of the per-query hit rate at the coverage where the mean is 0.5
+        # sigma_max^2, the constant of the variance model (Section 4.1.2), profiled where the mean
+        # hit rate is one half: that share of the clusters resident, the same queries again,
+        # and the spread of the per-query hit rate the router counted
         i_half = int(np.searchsorted(hit_cdf, 0.5))
-        hot_mask = np.zeros(nlist, bool)
-        hot_mask[order[:i_half]] = True
-        per_q = hot_mask[probes].mean(1)
-        sigma_max2 = float(per_q.var())
+        index.load_partition(np.sort(order[:i_half]).astype(np.int32))
+        run_calibration()
+        sigma_max2 = float(index.hit_rate_moments()["sigma_max2"])
+        index.hit_stats(reset=True)
         # --- CPU-tier latency model: knots measured with nothing resident ---
         index.load_partition(np.zeros(0, np.int32))
         knots_b, t_cq, t_lut = [], [], []

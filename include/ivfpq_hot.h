@@ -407,6 +407,23 @@ int ivf_stage_times(ivf_index_t *index, double *ms, uint64_t *launches, uint64_t
                     int reset);
 
 /*
+ * Spread of the per-query hit rate over the searches counted since the last
+ * reset (Section 3.3: the hit rate varies from query to query; Section 4.1.2
+ * models its variance as 4 sigma_max^2 mean (1 - mean) with one profiled
+ * constant).  mean = average over queries of (resident probes / probes) (equal
+ * to ivf_hit_stats' mean_hit_rate when every query has the same number of
+ * probes), variance = their population variance, sigma_max2 = variance /
+ * (4 mean (1 - mean)), the constant that ivf_model_min_hit_rate and its
+ * relatives take (NaN when the mean is 0 or 1: the model says nothing there;
+ * the paper profiles it where the mean is near one half).  All outputs HOST,
+ * any may be NULL.  Rates are accumulated in units of 2^-32.  Synchronizes with
+ * searches already enqueued; cleared by ivf_hit_stats' / ivf_refresh_hot_set's
+ * reset.
+ */
+int ivf_hit_rate_moments(ivf_index_t *index, double *mean, double *variance, double *sigma_max2,
+                         uint64_t *n_queries);
+
+/*
  * The access profile the partitioning model works on (Section 4.1.1: cluster
  * access frequencies collected over calibration queries; Section 3.2: their
  * cumulative distribution), taken from the router's per-cluster counters as

@@ -61,6 +61,10 @@ def ivf_migrate_clusters(index, evict, admit, side_stream=None):
     return index.migrate_clusters(evict, admit, side_stream)
 
 
+def ivf_hit_rate_moments(index):
+    return index.hit_rate_moments()
+
+
 def ivf_profile_curves(index):
     return index.profile_curves()
 

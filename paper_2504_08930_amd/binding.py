@@ -21,7 +21,7 @@ EXPORTS = (
     "ivf_index_arena_bytes", "ivf_index_create", "ivf_index_destroy",
     "ivf_index_load_partition", "ivf_search_batch", "ivf_search_batch_dev",
     "ivf_coarse_probe_dev", "ivf_coarse_probe_dev_noalloc", "ivf_search_batch_probes",
-    "ivf_hit_stats", "ivf_profile_curves",
+    "ivf_hit_stats", "ivf_hit_rate_moments", "ivf_profile_curves",
     "ivf_migrate_clusters", "ivf_migrate_poll", "ivf_migrate_stats", "ivf_refresh_hot_set",
     "ivf_resident_info", "ivf_resident_list", "ivf_host_scan_form", "ivf_copy_form",
     "ivf_set_tuning", "ivf_stage_times", "ivf_calib_copy", "ivf_calib_read", "ivf_last_error",
@@ -87,6 +87,7 @@ def load_library():
     lib.ivf_search_wait.argtypes = [P, P]
     lib.ivf_hit_stats.argtypes = [P, P, P, P, P, ctypes.c_int]
     lib.ivf_profile_curves.argtypes = [P, P, P, P]
+    lib.ivf_hit_rate_moments.argtypes = [P, P, P, P, P]
     lib.ivf_migrate_clusters.argtypes = [P, P, I32, P, I32, P]
     lib.ivf_migrate_poll.argtypes = [P, ctypes.c_int, P]
     lib.ivf_refresh_hot_set.argtypes = [P, I32, ctypes.c_int, P, P, P, P, P]
@@ -236,6 +237,15 @@ class IvfIndex:
         ev, ad = _i32(evict), _i32(admit)
         _check(self._lib.ivf_migrate_clusters(self._h, _np_ptr(ev), ev.size, _np_ptr(ad), ad.size,
                                               self._stream_ptr(side_stream)))
+
+    def hit_rate_moments(self):
+        """ivf_hit_rate_moments: mean, variance and sigma_max^2 of the per-query hit rate."""
+        m, v, s2 = ctypes.c_double(0), ctypes.c_double(0), ctypes.c_double(0)
+        n = ctypes.c_uint64(0)
+        _check(self._lib.ivf_hit_rate_moments(self._h, ctypes.byref(m), ctypes.byref(v),
+                                              ctypes.byref(s2), ctypes.byref(n)))
+        return {"mean": m.value, "variance": v.value, "sigma_max2": s2.value,
+                "n_queries": n.value}
 
     def profile_curves(self):
         """ivf_profile_curves: (ranked cluster ids, hit_cdf, mem_index) from the counters."""

@@ -436,6 +436,7 @@ int reset_counters_locked(ivf_index *ix) {
   HIP_TRY(launch_fill_u32((uint32_t *)ix->L.hits, (size_t)ix->sh.nlist * 2, 0u, st));
   HIP_TRY(launch_fill_u32((uint32_t *)ix->L.qstats, 4 * 2, 0u, st));
   HIP_TRY(launch_fill_u32((uint32_t *)&ix->L.qstats[QS_MIN_RATE_BITS], 1, 0x3f800000u, st));
+  HIP_TRY(launch_fill_u32((uint32_t *)&ix->L.qstats[QS_RATE_SUM], 2 * 2, 0u, st));
   HIP_TRY(hipStreamSynchronize(st));
   return IVF_OK;
 }
@@ -477,6 +478,31 @@ extern "C" int ivf_hit_stats(ivf_index_t *ix, uint64_t *per_cluster_hits, double
   if (!ix) return fail(IVF_EINVAL, "index is NULL");
   std::lock_guard<std::mutex> lk(ix->mu);
   return read_counters_locked(ix, per_cluster_hits, mean_hit_rate, min_hit_rate, n_queries, reset);
+}
+
+extern "C" int ivf_hit_rate_moments(ivf_index_t *ix, double *mean, double *variance,
+                                    double *sigma_max2, uint64_t *n_queries) {
+  if (!ix) return fail(IVF_EINVAL, "index is NULL");
+  std::lock_guard<std::mutex> lk(ix->mu);
+  double m = 0.0, var = 0.0;
+  uint64_t n = 0;
+  if (ix->has_dev) {
+    HIP_TRY(hipDeviceSynchronize());
+    HIP_TRY(hipMemcpy(ix->h_stats, ix->L.qstats, QS_COUNT * 8, hipMemcpyDeviceToHost));
+    n = ix->h_stats[QS_QUERIES];
+    if (n) {
+      // the two sums are integers in units of 2^-32
+      m = ldexp((double)ix->h_stats[QS_RATE_SUM], -32) / (double)n;
+      var = std::max(0.0, ldexp((double)ix->h_stats[QS_RATE_SQ], -32) / (double)n - m * m);
+    }
+  } else {
+    n = ix->hc_queries;  // nothing is resident: every hit rate is 0
+  }
+  if (mean) *mean = m;
+  if (variance) *variance = var;
+  if (sigma_max2) *sigma_max2 = (m > 0.0 && m < 1.0) ? var / (4.0 * m * (1.0 - m)) : NAN;
+  if (n_queries) *n_queries = n;
+  return IVF_OK;
 }
 
 // Clusters from the most to the least accessed, equal counts by id.

@@ -32,6 +32,8 @@ enum {
   QS_QUERIES = 2,
   QS_MIN_RATE_BITS = 3,  // float bits of the smallest per-query hit rate
   QS_SCAN_BYTES = 4,     // instrumentation, reset separately
+  QS_RATE_SUM = 5,       // sum over queries of the hit rate, in units of 2^-32
+  QS_RATE_SQ = 6,        // sum over queries of its square, in units of 2^-32
   QS_COUNT = 8
 };
 

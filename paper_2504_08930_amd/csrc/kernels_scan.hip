@@ -560,13 +560,15 @@ __global__ __launch_bounds__(1024) void k_order(const int32_t *__restrict__ prob
                                                 int32_t *__restrict__ hslot) {
   __shared__ unsigned int bins[kOrderBins];
   __shared__ unsigned int wsum[16];
-  __shared__ unsigned long long s_res[16], s_all[16], s_vec[16];
+  __shared__ unsigned long long s_res[16], s_all[16], s_vec[16], s_r1[16], s_r2[16];
   __shared__ unsigned int s_min[16];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   for (int i = tid; i < kOrderBins; i += 1024) bins[i] = 0u;
 
   // ---- router counters ----
-  unsigned long long res = 0, all = 0, vec = 0;
+  // (first and second moment of the per-query hit rate as integers in units of 2^-32:
+  // the sums do not depend on the order in which they are formed)
+  unsigned long long res = 0, all = 0, vec = 0, r1 = 0, r2 = 0;
   unsigned int mn = 0x3f800000u;  // 1.0f
   for (int q = tid; q < nq; q += 1024) {
     const int ng = g_n[q], valid = ng + n_cold[q];
@@ -575,18 +577,27 @@ __global__ __launch_bounds__(1024) void k_order(const int32_t *__restrict__ prob
     vec += (unsigned long long)q_vecs[q];
     const float rate = valid ? (float)ng / (float)valid : 0.0f;
     mn = min(mn, __float_as_uint(rate));
+    if (valid) {  // ng <= valid <= 2048
+      r1 += ((unsigned long long)ng << 32) / (unsigned long long)valid;
+      r2 += (((unsigned long long)ng * (unsigned long long)ng) << 32) /
+            ((unsigned long long)valid * (unsigned long long)valid);
+    }
   }
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) {
     res += __shfl_xor((long long)res, o, 64);
     all += __shfl_xor((long long)all, o, 64);
     vec += __shfl_xor((long long)vec, o, 64);
+    r1 += __shfl_xor((long long)r1, o, 64);
+    r2 += __shfl_xor((long long)r2, o, 64);
     mn = min(mn, (unsigned int)__shfl_xor((int)mn, o, 64));
   }
   if (lane == 0) {
     s_res[wave] = res;
     s_all[wave] = all;
     s_vec[wave] = vec;
+    s_r1[wave] = r1;
+    s_r2[wave] = r2;
     s_min[wave] = mn;
   }
   __syncthreads();  // also: bins are zero
@@ -595,6 +606,8 @@ __global__ __launch_bounds__(1024) void k_order(const int32_t *__restrict__ prob
       res += s_res[w2];
       all += s_all[w2];
       vec += s_vec[w2];
+      r1 += s_r1[w2];
+      r2 += s_r2[w2];
       mn = min(mn, s_min[w2]);
     }
     atomicAdd(&qstats[QS_SCAN_BYTES], vec * (unsigned long long)M);
@@ -602,6 +615,8 @@ __global__ __launch_bounds__(1024) void k_order(const int32_t *__restrict__ prob
       atomicAdd(&qstats[QS_RESIDENT_PROBES], res);
       atomicAdd(&qstats[QS_PROBES], all);
       atomicAdd(&qstats[QS_QUERIES], (unsigned long long)nq);
+      atomicAdd(&qstats[QS_RATE_SUM], r1);
+      atomicAdd(&qstats[QS_RATE_SQ], r2);
       atomicMin(reinterpret_cast<unsigned int *>(&qstats[QS_MIN_RATE_BITS]), mn);
     }
   }

@@ -175,6 +175,10 @@ static void run_case(int M, int nbits, int dsub, int metric, int residual, unsig
     }
     CHECK(cdf[0] == 0.0 && cdf[(size_t)ix.nlist] == 1.0 && mem[0] == 0.0);
     for (int i = 0; i < ix.nlist; ++i) CHECK(cdf[(size_t)i + 1] >= cdf[(size_t)i] && mem[(size_t)i + 1] >= mem[(size_t)i]);
+    double rm = -1, rv = -1, rs2 = 0;
+    uint64_t rn = 0;
+    CHECK(ivf_hit_rate_moments(ix.h, &rm, &rv, &rs2, &rn) == IVF_OK);
+    CHECK(rn > 0 && rm == 0.0 && rv == 0.0 && rs2 != rs2);  // nothing resident: no spread, no model
     int32_t nres = -1;
     CHECK(ivf_resident_list(ix.h, nullptr, 0, &nres) == IVF_OK && nres == 0);
     CHECK(ivf_refresh_hot_set(ix.h, 1, 0, nullptr, nullptr, nullptr, nullptr, nullptr) == IVF_EDEVICE);

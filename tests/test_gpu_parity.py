@@ -157,6 +157,7 @@ def test_residency_invariance_and_counters(pkg, oracle, name):
             _check_search(oracle, ix, q, spec.nprobe, spec.k, ids, dist)
         assert np.array_equal(ids, base[0]), "ids depend on residency"
         assert np.array_equal(dist, base[1]), "distances depend on residency"
+        mom = index.hit_rate_moments()            # read before the reset below clears them
         st = index.hit_stats(reset=True)
         # the device-pointer entry point on the same resident set (its hybrid form
         # copies the merged result back to the device); counters are read before it
@@ -176,7 +177,16 @@ def test_residency_invariance_and_counters(pkg, oracle, name):
         assert st["n_queries"] == q.shape[0]
         assert abs(st["mean_hit_rate"] - ref_rate.mean()) < 1e-9
         assert abs(st["min_hit_rate"] - ref_rate.min()) < 1e-6
+        # first and second moment of the per-query hit rate (Section 4.1.2's variance model)
+        rr = ref_rate.astype(np.float64)
+        assert mom["n_queries"] == q.shape[0]
+        assert abs(mom["mean"] - rr.mean()) < 1e-8 and abs(mom["variance"] - rr.var()) < 1e-8
+        if 0.0 < rr.mean() < 1.0:
+            assert abs(mom["sigma_max2"] - rr.var() / (4 * rr.mean() * (1 - rr.mean()))) < 1e-7
+        else:
+            assert np.isnan(mom["sigma_max2"])
     assert index.hit_stats()["per_cluster_hits"].sum() == 0
+    assert index.hit_rate_moments()["n_queries"] == 0 and index.hit_rate_moments()["variance"] == 0.0
     index.close()
 
 

@@ -295,6 +295,8 @@ def test_host_only_counters(case, oracle):
     ref, _ = oracle.hit_stats(ix.nlist, probe, np.zeros(ix.nlist, np.uint8))
     assert np.array_equal(st["per_cluster_hits"], ref)
     assert st["n_queries"] == q.shape[0] and st["mean_hit_rate"] == 0.0
+    mom = index.hit_rate_moments()                          # nothing can be resident here
+    assert mom["mean"] == 0.0 and mom["variance"] == 0.0 and np.isnan(mom["sigma_max2"])
     assert index.hit_stats()["per_cluster_hits"].sum() == 0
 
 
