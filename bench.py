@@ -47,10 +47,10 @@ HBM_PEAK_GBS = 8000.0
 # no traffic figure rather than a stale one.
 SCAN_SOURCES = ("kernels_scan.hip", "lut_quant.h", "internal.h")
 MEASURED_TRAFFIC = {
-    ("C3", 1024, 1.0): (3.0355e9 + 0.164e6, "profiles/c3_nq1024_scan_hbm_traffic.md",
-                        "68d3c7596d059b75"),
-    ("C3", 256, 1.0): (739.0e6 + 0.04e6, "profiles/c3_nq256_scan_hbm_traffic.md",
-                       "68d3c7596d059b75"),
+    ("C3", 1024, 1.0): (3.0220e9 + 0.164e6, "profiles/c3_nq1024_scan_hbm_traffic.md",
+                        "6c770ad915d5d1c5"),
+    ("C3", 256, 1.0): (739.3e6 + 0.04e6, "profiles/c3_nq256_scan_hbm_traffic.md",
+                       "6c770ad915d5d1c5"),
 }
 
 
