@@ -421,3 +421,12 @@ def test_dispatcher_blocks_other_searches_until_waited(case, lib, oracle):
     got, fin = empty.poll()
     assert got.size == 0 and fin
     empty.wait()
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py measures one GPU; asked for more it says so and exits before touching a device."""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"],
+                       capture_output=True, text=True, timeout=120)
+    assert r.returncode == 2 and "one GPU" in r.stderr and r.stdout.strip() == ""
