@@ -201,7 +201,7 @@ def main():
     ap.add_argument("--nq-list", default="256,1024,4096", help="sweep mode: batch sizes")
     ap.add_argument("--resident-list", default="1.0,0.5,0.3,0.1",
                     help="sweep mode: resident fractions")
-    ap.add_argument("--slo-ms", type=float, default=60.0,
+    ap.add_argument("--slo-ms", type=float, default=10.0,
                     help="partition mode: search latency target SLO_search in ms")
     ap.add_argument("--epochs", type=int, default=20, help="drift mode: epochs")
     ap.add_argument("--epoch-queries", type=int, default=10000, help="drift mode: queries/epoch")
