@@ -28,25 +28,31 @@ def build(force: bool = False) -> str:
 _lib = None
 
 
+def bind(path: str):
+    """Load an oracle library from `path` and declare its entry points (the tests that
+    plant mistakes in a copy of the source load the copy through this)."""
+    lib = ctypes.CDLL(path)
+    P = ctypes.c_void_p
+    lib.oracle_coarse.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, P,
+                                  ctypes.c_int64, P, ctypes.c_int, P, P, P]
+    lib.oracle_coarse.restype = ctypes.c_int
+    lib.oracle_scan.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, P, P, P, P, P,
+                                ctypes.c_int, P, ctypes.c_int64, P, ctypes.c_int, P,
+                                ctypes.c_int, P, P]
+    lib.oracle_scan.restype = ctypes.c_int
+    lib.oracle_hit_stats.argtypes = [ctypes.c_int, ctypes.c_int64, ctypes.c_int, P, P, P, P]
+    lib.oracle_hit_stats.restype = ctypes.c_int
+    lib.oracle_set_num_threads.argtypes = [ctypes.c_int]
+    lib.oracle_set_num_threads.restype = None
+    lib.oracle_num_threads.argtypes = []
+    lib.oracle_num_threads.restype = ctypes.c_int
+    return lib
+
+
 def _load():
     global _lib
     if _lib is None:
-        lib = ctypes.CDLL(build())
-        P = ctypes.c_void_p
-        lib.oracle_coarse.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, P,
-                                      ctypes.c_int64, P, ctypes.c_int, P, P, P]
-        lib.oracle_coarse.restype = ctypes.c_int
-        lib.oracle_scan.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, P, P, P, P, P,
-                                    ctypes.c_int, P, ctypes.c_int64, P, ctypes.c_int, P,
-                                    ctypes.c_int, P, P]
-        lib.oracle_scan.restype = ctypes.c_int
-        lib.oracle_hit_stats.argtypes = [ctypes.c_int, ctypes.c_int64, ctypes.c_int, P, P, P, P]
-        lib.oracle_hit_stats.restype = ctypes.c_int
-        lib.oracle_set_num_threads.argtypes = [ctypes.c_int]
-        lib.oracle_set_num_threads.restype = None
-        lib.oracle_num_threads.argtypes = []
-        lib.oracle_num_threads.restype = ctypes.c_int
-        _lib = lib
+        _lib = bind(build())
     return _lib
 
 

@@ -22,10 +22,12 @@ coverage.
 Pins (tests/test_partition_model.py): closed forms (B = 1 gives the mean; the
 uniform case gives 1/(B+1)), Monte-Carlo minima of Beta samples, the variance
 model at eta_bar = 0.5, monotonicity, a hand-worked instance of Eq. (1); for
-InferPartition two instances worked by hand (either rounding deciding the
-minimum); for Algorithm 1 a brute-force scan of every cluster count that
+InferPartition three instances worked by hand (either rounding deciding the
+minimum, and one in which the rounding-down bound B / mu, not tau_s, decides);
+for Algorithm 1 a brute-force scan of every cluster count that
 evaluates Eq. (1) and Eq. (2) directly and locates the self-consistent
-crossing the bisection must find.
+crossing the bisection must find; ten mistakes planted in a copy of this file
+each fail the pins named for them.
 """
 import math
 

@@ -350,3 +350,114 @@ def test_nibble_encoder_picks_nearest_codeword(tiny_nibble):
         xs = x[i].reshape(ix.m, 1, dsub)
         best = ((xs - ix.codebooks) ** 2).sum(-1).argmin(1)
         assert np.array_equal(best, codes[pos[i]])
+
+
+# ---------------------------------------------------------------------------
+# The pins above are only worth something if a plausible mistake in the oracle
+# fails one of them.  Each case below plants one mistake in a copy of the
+# oracle's source (an exact textual edit), builds the copy, runs the named pins
+# on it and expects every one of them to fail.  CPU only; the shipped oracle is
+# not touched.
+# ---------------------------------------------------------------------------
+def _pins_pq(o, t, tr, tn):
+    for name in ("T_L2", "T_IP"):
+        test_pq_all_lists_equals_exhaustive_decoded_scan(o, t, name)
+
+
+def _pins_flat_and_coarse(o, t, tr, tn):
+    for name in ("T_L2", "T_IP"):
+        test_flat_all_lists_equals_exact_knn(o, t, name)
+        test_coarse_matches_numpy_full_sort(o, t, name)
+
+
+def _pins_probed(o, t, tr, tn):
+    for name in ("T_L2", "T_IP"):
+        test_probed_search_equals_brute_force_restricted_to_probed_lists(o, t, name)
+
+
+def _pins_hand(o, t, tr, tn):
+    test_hand_computed_adc_example(o, L2, "l2")
+    test_hand_computed_adc_example(o, IP, "ip")
+
+
+def _pins_ties(o, t, tr, tn):
+    test_ties_go_to_smaller_id_and_padding(o)
+
+
+def _pins_residual(o, t, tr, tn):
+    for name in ("T_L2", "T_IP"):
+        test_residual_pq_all_lists_equals_exhaustive_decoded_scan(o, tr, name)
+    test_hand_computed_residual_example(o, L2, "residual_l2")
+    test_hand_computed_residual_example(o, IP, "residual_ip")
+
+
+def _pins_nibble(o, t, tr, tn):
+    test_hand_computed_nibble_example(o, L2, "nibble_l2")
+    test_hand_computed_nibble_example(o, IP, "nibble_ip")
+    test_nibble_pq_all_lists_equals_exhaustive_decoded_scan(o, tn, ("T_L2", False))
+
+
+def _pins_hits(o, t, tr, tn):
+    test_hit_stats_conservation(o, t)
+
+
+# name -> (edits [(text, replacement, occurrences)], pins expected to notice)
+PLANTED = {
+    "codebook indexed [code][sub-quantizer] instead of [sub-quantizer][code]": (
+        [("codebooks + ((size_t)m * ksub + j) * dsub", "codebooks + ((size_t)j * M + m) * dsub", 1)],
+        [_pins_pq, _pins_hand]),
+    "inner product sorted like a distance": (
+        [("metric == ORACLE_L2 ? cmp_asc : cmp_desc", "cmp_asc", 2)],
+        [_pins_flat_and_coarse]),
+    "last sub-quantizer of every code left out": (
+        [("for (int m = 0; m < M; ++m) {", "for (int m = 0; m < M - 1; ++m) {", 1),
+         ("float *xhat = (float *)malloc(sizeof(float) * (size_t)d);",
+          "float *xhat = (float *)calloc((size_t)d, sizeof(float));", 1)],
+        [_pins_pq, _pins_hand]),
+    "difference of the L2 distance taken as a sum": (
+        [("double t = (double)q[i] - (double)x[i];", "double t = (double)q[i] + (double)x[i];", 1)],
+        [_pins_flat_and_coarse, _pins_hand]),
+    "equal scores resolved to the larger id": (
+        [("return (x->id > y->id) - (x->id < y->id);", "return (x->id < y->id) - (x->id > y->id);", 2)],
+        [_pins_ties]),
+    "last vector of every list skipped": (
+        [("v < list_offsets[c + 1]; ++v)", "v < list_offsets[c + 1] - 1; ++v)", 1)],
+        [_pins_probed, _pins_pq]),
+    "halves of a 4-bit code byte swapped": (
+        [("(4 * (m & 1))", "(4 * ((m & 1) ^ 1))", 1)],
+        [_pins_nibble]),
+    "residual codes decoded without their centroid": (
+        [("((double)a[i] + (double)b[i])", "((double)b[i])", 2)],
+        [_pins_residual]),
+    "hit rate counts the probes that miss": (
+        [("if (resident[c]) ++hit;", "if (!resident[c]) ++hit;", 1)],
+        [_pins_hits]),
+    "one probe too few kept by the coarse stage": (
+        [("int keep = nprobe < nlist ? nprobe : nlist;", "int keep = (nprobe < nlist ? nprobe : nlist) - 1;", 1)],
+        [_pins_flat_and_coarse, _pins_ties]),
+}
+
+
+@pytest.mark.parametrize("mistake", sorted(PLANTED))
+def test_a_planted_mistake_fails_a_pin(oracle, tiny, tiny_residual, tiny_nibble, tmp_path,
+                                       monkeypatch, mistake):
+    import subprocess
+    edits, pins = PLANTED[mistake]
+    src = open(os.path.join(os.path.dirname(oracle.__file__), "ivfpq_oracle.c")).read()
+    for text, replacement, occurrences in edits:
+        assert src.count(text) == occurrences, (mistake, text)
+        src = src.replace(text, replacement)
+    c_path, so_path = tmp_path / "mutant.c", tmp_path / "mutant.so"
+    c_path.write_text(src)
+    subprocess.check_call(["gcc", "-O2", "-fopenmp", "-shared", "-fPIC", "-std=c11", "-o",
+                           str(so_path), str(c_path), "-lm"])
+    oracle.build()
+    oracle.coarse(L2, np.zeros((2, 4), np.float32), np.zeros((1, 4), np.float32), 1)  # loads the real one
+    monkeypatch.setattr(oracle, "_lib", oracle.bind(str(so_path)))
+    noticed = []
+    for pin in pins:
+        try:
+            pin(oracle, tiny, tiny_residual, tiny_nibble)
+        except AssertionError:
+            noticed.append(pin.__name__)
+    assert noticed == [p.__name__ for p in pins], f"{mistake}: noticed only by {noticed}"

@@ -141,12 +141,17 @@ def test_infer_partition_hand_worked_instances(lib):
     (b) models through the origin, T_CQ = 1 ms * b, T_LUT = 16/3 ms * b:
         eta_1 = (2 + 10.67 - 10) / 10.67 = 0.25 -> rho_1 = 1/4;
         eta_2 = (1 + 5.33 - 6.67) / 5.33 < 0 -> no coverage needed, rho_2 = 0.  min = 0.
+    (c) T_CQ = 1 ms, T_LUT = 8 ms at b = 1 and 12 ms at b = 2, where it matters that rounding down
+        is held to B/mu and not to tau_s: eta_1 = 0.25 -> rho_1 = 1/4 as in (a);
+        eta_2 = (9 - 6.67) / 8 = 0.29 -> one cluster (0.5), rho_2 = 1/4; min = 1/4.  (Held to
+        tau_s, eta_2 = (9 - 10) / 8 < 0 would ask for no coverage and the minimum would be 0.)
     The library's InferPartition is reached through Algorithm 1 with an index that takes no
     memory (mu stays mu_LLM0, so every iteration returns the same value)."""
     hit_cdf = np.array([0.0, 0.5, 0.75, 0.9, 1.0])
     s2, tau, mu = 1.0 / 12.0, 10e-3, 150.0
     cases = [(([1.0, 2.0], [1e-3, 1e-3], [12e-3, 12e-3]), 0.25),
-             (([1.0, 2.0], [1e-3, 2e-3], [16e-3 / 3, 32e-3 / 3]), 0.0)]
+             (([1.0, 2.0], [1e-3, 2e-3], [16e-3 / 3, 32e-3 / 3]), 0.0),
+             (([1.0, 2.0], [1e-3, 1e-3], [8e-3, 12e-3]), 0.25)]
     for (kb, cq, lut), want in cases:
         assert po.infer_partition(kb, cq, lut, hit_cdf, s2, tau, mu) == want
         model = lib.LatencyModel(kb, cq, lut)
@@ -228,3 +233,77 @@ def test_partition_point_is_the_self_consistent_crossing(lib, zipf_s, slo, kv_mu
     for name, val in (("oracle", ref), ("library", got)):
         assert lo <= val <= hi, (name, val, i_star / nlist, near)
         assert abs(val - i_star / nlist) <= delta + 2.0 / nlist + (hi - lo), (name, val, i_star)
+
+
+# ---------------------------------------------------------------------------
+# Planted mistakes: each is an exact textual edit of a copy of the oracle's source,
+# run as a module of its own under the pins named for it; every named pin must fail.
+# ---------------------------------------------------------------------------
+def _pin_closed(lib):
+    test_oracle_min_hit_rate_closed_forms()
+
+
+def _pin_monte_carlo(lib):
+    test_oracle_min_hit_rate_monte_carlo_and_monotone()
+
+
+def _pin_latency(lib):
+    test_oracle_hybrid_latency_hand_instance()
+
+
+def _pin_infer(lib):
+    test_infer_partition_hand_worked_instances(lib)
+
+
+def _pin_crossing(lib):
+    for args in ((1.0, 20e-3, 4.0, 900.0), (0.7, 24e-3, 2.0, 1500.0), (1.3, 16e-3, 3.0, 1500.0),
+                 (1.0, 30e-3, 1.5, 1500.0)):
+        test_partition_point_is_the_self_consistent_crossing(lib, *args)
+
+
+PLANTED = {
+    "Eq. (1) adds the hit share of the table time": (
+        [("(1.0 - eta) * piecewise_linear", "(1.0 + eta) * piecewise_linear", 1)], [_pin_latency]),
+    "variance model with half its factor": (
+        [("var = 4.0 * sigma_max2", "var = 2.0 * sigma_max2", 1)], [_pin_closed]),
+    "Eq. (2) with the exponent B": (
+        [("(1.0 - u) ** (B - 1)", "(1.0 - u) ** B", 1)], [_pin_closed, _pin_monte_carlo]),
+    "no extrapolation beyond the last knot": (
+        [("0, len(kb) - 2))", "0, len(kb) - 2))\n    b = min(b, kb[-1])", 1)], [_pin_latency]),
+    "coverage one cluster too many": (
+        [("            return i / nlist\n", "            return (i + 1) / nlist\n", 1)], [_pin_infer]),
+    "the larger of the two roundings' coverages": (
+        [("return min(out)", "return max(out)", 1)], [_pin_infer]),
+    "rounding down held to tau_s instead of B / mu": (
+        [("target = tau_s if bound is None else B / mu", "target = tau_s", 1)], [_pin_infer]),
+    "bisection moves the wrong end": (
+        [("        if rho > mid:\n            lo = mid\n        else:\n            hi = mid",
+          "        if rho > mid:\n            hi = mid\n        else:\n            lo = mid", 1)],
+        [_pin_crossing]),
+    "throughput from the index's share of memory": (
+        [("(mem_kvcache - mem) / mem_kvcache", "mem / mem_kvcache", 1)], [_pin_crossing]),
+    "latency budget not split with the queue": (
+        [("tau_s = slo_search / (1.0 + eps)", "tau_s = slo_search", 1)], [_pin_crossing]),
+}
+
+
+@pytest.mark.parametrize("mistake", sorted(PLANTED))
+def test_a_planted_mistake_fails_a_pin(lib, monkeypatch, mistake):
+    import sys
+    import types
+    edits, pins = PLANTED[mistake]
+    src = open(po.__file__).read()
+    for text, replacement, occurrences in edits:
+        assert src.count(text) == occurrences, (mistake, text)
+        src = src.replace(text, replacement)
+    mutant = types.ModuleType("partition_oracle_mutant")
+    exec(compile(src, "partition_oracle_mutant.py", "exec"), mutant.__dict__)
+    monkeypatch.setattr(sys.modules[__name__], "po", mutant)
+    monkeypatch.setattr(sys.modules[__name__], "_ETA_MEMO", {})
+    noticed = []
+    for pin in pins:
+        try:
+            pin(lib)
+        except (AssertionError, ArithmeticError):   # a mutant may also divide by zero
+            noticed.append(pin.__name__)
+    assert noticed == [p.__name__ for p in pins], f"{mistake}: noticed only by {noticed}"
