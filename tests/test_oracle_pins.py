@@ -432,6 +432,17 @@ PLANTED = {
     "hit rate counts the probes that miss": (
         [("if (resident[c]) ++hit;", "if (!resident[c]) ++hit;", 1)],
         [_pins_hits]),
+    "stored position returned instead of the caller's id": (
+        [("cand[n].id = ids[v];", "cand[n].id = v;", 1)], [_pins_pq, _pins_probed]),
+    "padding of short results with the wrong infinity": (
+        [("metric == ORACLE_L2 ? INFINITY : -INFINITY", "metric == ORACLE_L2 ? -INFINITY : INFINITY", 1)],
+        [_pins_ties]),
+    "gap to the next centroid taken one rank early": (
+        [("fabs(c[keep - 1].score - c[keep].score)", "fabs(c[keep - 2].score - c[keep - 1].score)", 1)],
+        [_pins_flat_and_coarse]),
+    "probe scores reported from the wrong rank": (
+        [("p < keep ? c[p].score : NAN", "p < keep ? c[keep - 1 - p].score : NAN", 1)],
+        [_pins_flat_and_coarse]),
     "one probe too few kept by the coarse stage": (
         [("int keep = nprobe < nlist ? nprobe : nlist;", "int keep = (nprobe < nlist ? nprobe : nlist) - 1;", 1)],
         [_pins_flat_and_coarse, _pins_ties]),
