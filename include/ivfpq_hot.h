@@ -424,6 +424,18 @@ int ivf_hit_rate_moments(ivf_index_t *index, double *mean, double *variance, dou
                          uint64_t *n_queries);
 
 /*
+ * The hit rate weighted by size (Section 3.2's access-skew figure counts distance
+ * computations, not clusters): of the code bytes that the probes counted since
+ * the last reset scan (each probe of list c scans M * L_c bytes), the share
+ * that falls into clusters of the resident set as it stands now.  rate and
+ * probed_bytes (that total) are HOST, either may be NULL; rate is 0 when nothing
+ * has been counted.  Equals what the device scanned over what was scanned in
+ * all if the resident set has not changed since the reset.  Synchronizes with
+ * searches already enqueued.
+ */
+int ivf_weighted_hit_rate(ivf_index_t *index, double *rate, double *probed_bytes);
+
+/*
  * The access profile the partitioning model works on (Section 4.1.1: cluster
  * access frequencies collected over calibration queries; Section 3.2: their
  * cumulative distribution), taken from the router's per-cluster counters as

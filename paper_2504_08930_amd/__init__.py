@@ -65,6 +65,10 @@ def ivf_hit_rate_moments(index):
     return index.hit_rate_moments()
 
 
+def ivf_weighted_hit_rate(index):
+    return index.weighted_hit_rate()
+
+
 def ivf_profile_curves(index):
     return index.profile_curves()
 

@@ -21,7 +21,7 @@ EXPORTS = (
     "ivf_index_arena_bytes", "ivf_index_create", "ivf_index_destroy",
     "ivf_index_load_partition", "ivf_search_batch", "ivf_search_batch_dev",
     "ivf_coarse_probe_dev", "ivf_coarse_probe_dev_noalloc", "ivf_search_batch_probes",
-    "ivf_hit_stats", "ivf_hit_rate_moments", "ivf_profile_curves",
+    "ivf_hit_stats", "ivf_hit_rate_moments", "ivf_weighted_hit_rate", "ivf_profile_curves",
     "ivf_migrate_clusters", "ivf_migrate_poll", "ivf_migrate_stats", "ivf_refresh_hot_set",
     "ivf_resident_info", "ivf_resident_list", "ivf_host_scan_form", "ivf_copy_form",
     "ivf_set_tuning", "ivf_stage_times", "ivf_calib_copy", "ivf_calib_read", "ivf_last_error",
@@ -88,6 +88,7 @@ def load_library():
     lib.ivf_hit_stats.argtypes = [P, P, P, P, P, ctypes.c_int]
     lib.ivf_profile_curves.argtypes = [P, P, P, P]
     lib.ivf_hit_rate_moments.argtypes = [P, P, P, P, P]
+    lib.ivf_weighted_hit_rate.argtypes = [P, P, P]
     lib.ivf_migrate_clusters.argtypes = [P, P, I32, P, I32, P]
     lib.ivf_migrate_poll.argtypes = [P, ctypes.c_int, P]
     lib.ivf_refresh_hot_set.argtypes = [P, I32, ctypes.c_int, P, P, P, P, P]
@@ -246,6 +247,12 @@ class IvfIndex:
                                               ctypes.byref(s2), ctypes.byref(n)))
         return {"mean": m.value, "variance": v.value, "sigma_max2": s2.value,
                 "n_queries": n.value}
+
+    def weighted_hit_rate(self):
+        """ivf_weighted_hit_rate: (share of the probed code bytes that are resident, those bytes)."""
+        r, b = ctypes.c_double(0), ctypes.c_double(0)
+        _check(self._lib.ivf_weighted_hit_rate(self._h, ctypes.byref(r), ctypes.byref(b)))
+        return r.value, b.value
 
     def profile_curves(self):
         """ivf_profile_curves: (ranked cluster ids, hit_cdf, mem_index) from the counters."""

@@ -505,6 +505,25 @@ extern "C" int ivf_hit_rate_moments(ivf_index_t *ix, double *mean, double *varia
   return IVF_OK;
 }
 
+extern "C" int ivf_weighted_hit_rate(ivf_index_t *ix, double *rate, double *probed_bytes) {
+  if (!ix) return fail(IVF_EINVAL, "index is NULL");
+  std::lock_guard<std::mutex> lk(ix->mu);
+  const int32_t nlist = ix->sh.nlist;
+  std::vector<uint64_t> hits((size_t)nlist);
+  int rc = read_counters_locked(ix, hits.data(), nullptr, nullptr, nullptr, 0);
+  if (rc != IVF_OK) return rc;
+  // every probe of list c scans M * L_c bytes of codes, on the device if c is resident
+  double all = 0.0, res = 0.0;
+  for (int32_t c = 0; c < nlist; ++c) {
+    const double b = (double)hits[c] * (double)ix->h_len[c] * (double)ix->sh.M;
+    all += b;
+    if (ix->h_map[c] >= 0) res += b;
+  }
+  if (rate) *rate = all > 0.0 ? res / all : 0.0;
+  if (probed_bytes) *probed_bytes = all;
+  return IVF_OK;
+}
+
 // Clusters from the most to the least accessed, equal counts by id.
 void rank_clusters(const std::vector<uint64_t> &hits, std::vector<int32_t> &order) {
   order.resize(hits.size());

@@ -179,6 +179,8 @@ static void run_case(int M, int nbits, int dsub, int metric, int residual, unsig
     uint64_t rn = 0;
     CHECK(ivf_hit_rate_moments(ix.h, &rm, &rv, &rs2, &rn) == IVF_OK);
     CHECK(rn > 0 && rm == 0.0 && rv == 0.0 && rs2 != rs2);  // nothing resident: no spread, no model
+    double wr = -1, wb = -1;
+    CHECK(ivf_weighted_hit_rate(ix.h, &wr, &wb) == IVF_OK && wr == 0.0 && wb > 0.0);
     int32_t nres = -1;
     CHECK(ivf_resident_list(ix.h, nullptr, 0, &nres) == IVF_OK && nres == 0);
     CHECK(ivf_refresh_hot_set(ix.h, 1, 0, nullptr, nullptr, nullptr, nullptr, nullptr) == IVF_EDEVICE);

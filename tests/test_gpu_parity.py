@@ -158,6 +158,7 @@ def test_residency_invariance_and_counters(pkg, oracle, name):
         assert np.array_equal(ids, base[0]), "ids depend on residency"
         assert np.array_equal(dist, base[1]), "distances depend on residency"
         mom = index.hit_rate_moments()            # read before the reset below clears them
+        wrate, wbytes = index.weighted_hit_rate()
         st = index.hit_stats(reset=True)
         # the device-pointer entry point on the same resident set (its hybrid form
         # copies the merged result back to the device); counters are read before it
@@ -177,6 +178,11 @@ def test_residency_invariance_and_counters(pkg, oracle, name):
         assert st["n_queries"] == q.shape[0]
         assert abs(st["mean_hit_rate"] - ref_rate.mean()) < 1e-9
         assert abs(st["min_hit_rate"] - ref_rate.min()) < 1e-6
+        # size-weighted hit rate: resident share of the code bytes the probes scan
+        lens_b = np.diff(ix.list_offsets).astype(np.float64) * ix.codes.shape[1]
+        per_c = ref_hits.astype(np.float64) * lens_b
+        assert wbytes == per_c.sum()
+        assert abs(wrate - (per_c[mask.astype(bool)].sum() / per_c.sum())) < 1e-12
         # first and second moment of the per-query hit rate (Section 4.1.2's variance model)
         rr = ref_rate.astype(np.float64)
         assert mom["n_queries"] == q.shape[0]

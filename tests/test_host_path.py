@@ -295,6 +295,7 @@ def test_host_only_counters(case, oracle):
     ref, _ = oracle.hit_stats(ix.nlist, probe, np.zeros(ix.nlist, np.uint8))
     assert np.array_equal(st["per_cluster_hits"], ref)
     assert st["n_queries"] == q.shape[0] and st["mean_hit_rate"] == 0.0
+    assert index.weighted_hit_rate() == (0.0, 0.0)          # counters just cleared
     mom = index.hit_rate_moments()                          # nothing can be resident here
     assert mom["mean"] == 0.0 and mom["variance"] == 0.0 and np.isnan(mom["sigma_max2"])
     assert index.hit_stats()["per_cluster_hits"].sum() == 0
@@ -324,6 +325,9 @@ def test_profile_curves_from_the_counters(case, oracle, lib):
     assert mem_index[0] == 0.0 and mem_index[-1] == per_vec * ix.n
     for i in (1, 5, ix.nlist // 2):
         assert mem_index[i] == per_vec * lens[want[:i]].sum()
+    # size-weighted: nothing is resident on a device-less index, the bytes are still counted
+    wrate, wbytes = index.weighted_hit_rate()
+    assert wrate == 0.0 and wbytes == float((hits * lens).sum() * ix.m)
     assert index.hit_stats(reset=True)["per_cluster_hits"].sum() == hits.sum()   # nothing was cleared
 
 
