@@ -115,10 +115,12 @@ def timed_steps(index, q, nprobe, k, steps, warmup, slices, timing=2, n_streams=
     elapsed = time.perf_counter() - t0
     st = index.stage_times(reset=True)
     hs = index.hit_stats()
+    weighted = index.weighted_hit_rate()[0]
     index.set_tuning(scan_slices=slices, timing=0)
     res = {"elapsed": elapsed, "ms_per_step": 1e3 * elapsed / steps,
            "qps": nq * steps / elapsed, "hit_rate": hs["mean_hit_rate"],
-           "min_hit_rate": hs["min_hit_rate"], "stage": st, "out_ids": out_ids, "out_d": out_d}
+           "min_hit_rate": hs["min_hit_rate"], "bytes_hit_rate": weighted, "stage": st,
+           "out_ids": out_ids, "out_d": out_d}
     n_scan = st["launches"]["scan"]
     if timing and n_scan > 0:
         scan_ms = st["ms"]["scan"] / n_scan
@@ -266,6 +268,7 @@ def main():
                        "ms_per_step": round(r["ms_per_step"], 3),
                        "mean_hit_rate": round(r["hit_rate"], 4),
                        "min_hit_rate": round(r["min_hit_rate"], 4),
+                       "bytes_hit_rate": round(r["bytes_hit_rate"], 4),
                        "scan_ms": round(r.get("scan_ms", 0.0), 4),
                        "scan_GBs": round(r.get("scan_gbs", 0.0), 1),
                        "scan_frac_of_peak": round(r.get("scan_gbs", 0.0) / HBM_PEAK_GBS, 4),
@@ -637,7 +640,8 @@ def main():
                 row = {"nq": n, "resident_fraction": frac, "queries_per_s": round(rp["qps"], 1),
                        "ms_per_step": round(rp["ms_per_step"], 4),
                        "mean_hit_rate": round(rp["hit_rate"], 4),
-                       "min_hit_rate": round(rp["min_hit_rate"], 4)}
+                       "min_hit_rate": round(rp["min_hit_rate"], 4),
+                       "bytes_hit_rate": round(rp["bytes_hit_rate"], 4)}
                 if "scan_gbs" in rp:
                     row["scan_ms"] = round(rp["scan_ms"], 4)
                     row["scan_frac_of_peak"] = round(rp["scan_gbs"] / HBM_PEAK_GBS, 4)
@@ -662,6 +666,7 @@ def main():
         "config": {"workload": f"{workload} nq={nq}",
                    "resident_fraction": round(resident_frac, 4),
                    "mean_hit_rate": round(r["hit_rate"], 4),
+                   "bytes_hit_rate": round(r["bytes_hit_rate"], 4),
                    "scan_slices": args.slices, "streams": args.streams,
                    "inputs": "queries already in HBM when the timed region starts "
                              "(ivf_search_batch_dev); the host-pointer call is in "
