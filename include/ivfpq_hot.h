@@ -24,10 +24,11 @@
  *  - The library performs no device allocation of its own: all device state
  *    lives in the caller-supplied arena.
  *  - "L2" is squared Euclidean distance (smaller is better); "IP" is the inner
- *    product (larger is better).  PQ codes are 8 bits per sub-quantizer and
- *    encode either the raw vector or (by_residual) its residual to the centroid
- *    of its list; a stored code then stands for centroid + representative
- *    values.  Either way one lookup table per query serves every probed list.
+ *    product (larger is better).  PQ codes are 8 bits per sub-quantizer, or 4
+ *    (nbits = 4, two per byte), and encode either the raw vector or
+ *    (by_residual) its residual to the centroid of its list; a stored code then
+ *    stands for centroid + representative values.  Either way one lookup table
+ *    per query serves every probed list.
  *  - Results are ordered best first; ties on distance go to the smaller id.
  *    Missing results are id = -1, dist = +INF (L2) / -INF (IP).
  *  - Threading: one searcher thread plus one migrator thread per index.
@@ -35,7 +36,6 @@
  *    library's own, created once per process: as many as the environment
  *    variable IVF_CPU_THREADS says, else OMP_NUM_THREADS, else the hardware
  *    concurrency.
- *  - PQ codes may also be 4 bits per sub-quantizer (nbits = 4, two per byte).
  *  - Streams are raw hipStream_t values passed as void*; NULL is HIP's null
  *    stream.  All streams must have default priority.  The host-pointer entry
  *    points run on a stream the index owns.  The index holds two per-batch
@@ -65,7 +65,7 @@ enum {
   IVF_EINVAL = -1,  /* bad argument / unsupported shape */
   IVF_ENOMEM = -2,  /* arena (or its cluster region) too small */
   IVF_EDEVICE = -3, /* HIP error, or a device call on an index without arena */
-  IVF_EBUSY = -4,   /* a migration is already in flight */
+  IVF_EBUSY = -4,   /* a migration or an asynchronous batch is still in flight */
   IVF_ESTATE = -5   /* call not valid in the current state */
 };
 
